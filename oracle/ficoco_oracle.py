@@ -1,0 +1,417 @@
+"""FiCoCo filter / correlate / compress step -- plain CPU oracle (TEST INFRASTRUCTURE).
+
+This module is the checker, not the product.  It states, in slow and obvious float64
+numpy, what one FiCoCo token-reduction step computes, following the paper
+"Filter, Correlate, Compress" (arxiv 2411.17686): Algorithm 1 (FiCoCo-V),
+Algorithm 2 (FiCoCo-L), Eq. 1 (integrated redundancy score), Eq. 2 (self-preserving
+compression), Eq. 3 (FiCoCo-L score), Eq. 4 (FiCoCo-L correlation) and the appendix
+section "Implementation of the Equivalent Token".
+
+Only tests, the smoke check and the benchmark's CPU-baseline leg may import it.  It shares
+no code with the HIP library and never calls it.  There is no blocking, fusion or
+reordering here beyond what the definitions state.
+
+Index convention (the paper's own is not self-consistent, see "readings" below).
+`P[q, k]` is the usual row-stochastic attention map, row = query, column = key.  The
+paper's A_{i,j} for visual token i is read as "attention token i RECEIVES from token j",
+i.e. P[j, i]: Sec. "Redundancy-based Token Discard" calls the first score term the token's
+"received attention" and the appendix section on the sign of vision-aware redundancy calls
+it the "attention-in" score; a literal row sum of a softmax is the constant 1 and could
+not rank anything.
+
+Readings (where the paper is silent, ambiguous or garbled):
+  R1  multi-head maps are reduced to one map by the head mean, heads added in order.
+  R2  first score term = column mean over the N visual query rows (diagonal included).
+  R3  second score term = the [CLS] query row (V) / mean over the M text query rows (L);
+      Eq. 3 keeps the 1/M that Algorithm 2 drops.
+  R4  local penalty: 2-D grid of cells, -inf padding for absent cells, non-overlapping
+      W x W windows anchored at (0,0) of each sub-grid; the maximum of a window (ties: the
+      lowest cell index) is multiplied by the coefficient, whatever its sign.
+  R5  filter: discard the N^S largest by (score descending, index ascending).
+  R6  V correlation C[i, j] = head-mean attention P[j, i] (preserved query j on discarded
+      key i), read from the map materialised in single precision.
+  R7  L indirect term = (1/M) sum_k P[k, i] P[k, j] over text queries k (co-attention of
+      the two visual tokens by the text); Eq. 4 keeps the 1/M that Algorithm 2 drops.
+  R8  the epsilon-quantile is the linear-interpolation order statistic
+      v[f] + g (v[f+1] - v[f]),  p = eps (n-1), f = floor(p), g = p - f.
+  R9  a row whose selected correlations sum to <= 0 recycles nothing (pure pruning).
+  R10 extension (not in the paper): cosine correlation max(0, xh_i . xh_j) with the
+      normalised rows xh rounded to bfloat16, and the mean-cosine first score term.
+
+All decisions (window maxima, the top-K filter, the threshold test) are taken on float64
+values; scalar hyper-parameters cross the library boundary as float32 and are widened
+from that value here too.
+"""
+import math
+
+import numpy as np
+
+F64 = np.float64
+
+
+# --------------------------------------------------------------------------- input decoding
+def widen(buf):
+    """Exact float64 view of an input buffer: float32 array, or bfloat16 bits as uint16."""
+    buf = np.asarray(buf)
+    if buf.dtype == np.uint16:
+        return (buf.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(F64)
+    if buf.dtype in (np.float32, np.float64):
+        return buf.astype(F64)
+    raise TypeError("expected float32 values or bfloat16 bit patterns (uint16)")
+
+
+def f32(x):
+    """The float64 value of a scalar that crossed the boundary as float32."""
+    return float(np.float32(x))
+
+
+def round_to_bf16(x):
+    """Round float64 values to the nearest bfloat16 (ties to even); result kept as float64.
+
+    bfloat16 has 8 significant bits and float32's exponent range, so the spacing at a value
+    with binary exponent e is 2^(max(e, -126) - 7).
+    """
+    x = np.asarray(x, dtype=F64)
+    _, e = np.frexp(x)                     # x = m * 2^e with 0.5 <= |m| < 1  ->  exponent e-1
+    q = np.ldexp(1.0, np.maximum(e - 1, -126) - 7)
+    return np.where(x == 0.0, 0.0, np.rint(x / q) * q)
+
+
+def round_to_dtype(x, dtype):
+    """Round a float64 array to the storage type of the tokens ('f32' or 'bf16')."""
+    if dtype == "f32":
+        return np.asarray(x, dtype=F64).astype(np.float32).astype(F64)
+    if dtype == "bf16":
+        return round_to_bf16(x)
+    raise ValueError(dtype)
+
+
+# --------------------------------------------------------------------------- filter: score
+def head_mean(A):
+    """Reading R1: (1/H) sum_h A[h], heads added in order.  A: [H, Nq, Nk] float64."""
+    A = np.asarray(A, dtype=F64)
+    acc = np.zeros(A.shape[1:], dtype=F64)
+    for h in range(A.shape[0]):
+        acc = acc + A[h]
+    return acc * (1.0 / A.shape[0])
+
+
+def received_attention(P, query_rows, key_cols):
+    """First term of Eq. 1 / Eq. 3 (reading R2): for each visual token (a key column) the
+    mean over the visual query rows of the attention it receives; rows added in order,
+    divided by the number of visual tokens N = len(key_cols)."""
+    acc = np.zeros(len(key_cols), dtype=F64)
+    for q in query_rows:
+        acc = acc + P[q, key_cols]
+    return acc / float(len(key_cols))
+
+
+def cls_attention(P, cls_row, key_cols):
+    """Semantic term of Eq. 1: the [CLS] query's attention weight on each patch."""
+    return P[cls_row, key_cols].astype(F64)
+
+
+def text_attention(P, text_rows, key_cols):
+    """Task term of Eq. 3 (reading R3): mean over the M text queries of the attention each
+    visual token receives from them."""
+    acc = np.zeros(len(key_cols), dtype=F64)
+    for k in text_rows:
+        acc = acc + P[k, key_cols]
+    return acc / float(len(text_rows))
+
+
+def head_mean_vector(V):
+    """Pre-reduced per-head score vectors [H, N] -> head mean [N], heads added in order."""
+    V = np.asarray(V, dtype=F64)
+    acc = np.zeros(V.shape[1], dtype=F64)
+    for h in range(V.shape[0]):
+        acc = acc + V[h]
+    return acc * (1.0 / V.shape[0])
+
+
+def l2_norms(F):
+    """Euclidean norm of each row, squares added in order along the feature axis."""
+    F = np.asarray(F, dtype=F64)
+    acc = np.zeros(F.shape[0], dtype=F64)
+    for d in range(F.shape[1]):
+        acc = acc + F[:, d] * F[:, d]
+    return np.sqrt(acc)
+
+
+def unit_rows(F):
+    """Rows divided by their Euclidean norm; a zero row stays zero (its cosines are 0)."""
+    F = np.asarray(F, dtype=F64)
+    nrm = l2_norms(F)
+    safe = np.where(nrm > 0.0, nrm, 1.0)
+    return np.where(nrm[:, None] > 0.0, F / safe[:, None], 0.0)
+
+
+def equivalent_token_term(F):
+    """Appendix "Implementation of the Equivalent Token": mu = mean of the patch features
+    (the caller supplies head-mean keys), a_i^Eq = -cos(mu, F_i).  Replaces a^CLS in Eq. 1."""
+    F = np.asarray(F, dtype=F64)
+    mu = np.zeros(F.shape[1], dtype=F64)
+    for i in range(F.shape[0]):
+        mu = mu + F[i]
+    mu = mu / float(F.shape[0])
+    mu_n = math.sqrt(float(np.sum(mu * mu)))
+    nrm = l2_norms(F)
+    out = np.zeros(F.shape[0], dtype=F64)
+    for i in range(F.shape[0]):
+        if mu_n > 0.0 and nrm[i] > 0.0:
+            out[i] = -(float(np.dot(mu, F[i])) / (mu_n * nrm[i]))
+    return out
+
+
+def mean_cosine_term(F):
+    """Reading R10 (extension): (1/N) sum_j cos(F_i, F_j), j = i included -- the plain
+    definition through the full cosine matrix."""
+    U = unit_rows(F)
+    G = U @ U.T
+    return G.sum(axis=1) / float(F.shape[0])
+
+
+def combine_score(R, G, w):
+    """Eq. 1 (w = lambda) and Eq. 3 (w = beta):  s = w R - (1 - w) G."""
+    w = f32(w)
+    return w * np.asarray(R, F64) - (1.0 - w) * np.asarray(G, F64)
+
+
+def local_penalty(s, pos, grid_g, grid_h, grid_w, window, coef):
+    """Local penalty of Sec. "Redundancy-based Token Discard" (reading R4).
+
+    s[t] is the score of visual token t, pos[t] its cell in `grid_g` stacked grid_h x grid_w
+    grids (row-major).  Cells of tokens discarded by earlier steps are padding.  In every
+    non-overlapping window that holds at least one token the largest score (first in cell
+    order on ties) is multiplied by `coef`.  window <= 0 switches the penalty off."""
+    s = np.asarray(s, dtype=F64)
+    out = s.copy()
+    if window <= 0:
+        return out
+    coef = f32(coef)
+    cells = grid_g * grid_h * grid_w
+    owner = np.full(cells, -1, dtype=np.int64)
+    for t in range(len(s)):
+        assert 0 <= pos[t] < cells and owner[pos[t]] < 0, "pos must be distinct grid cells"
+        owner[pos[t]] = t
+    for sub in range(grid_g):
+        for r0 in range(0, grid_h, window):
+            for c0 in range(0, grid_w, window):
+                best = -1
+                for r in range(r0, min(r0 + window, grid_h)):
+                    for c in range(c0, min(c0 + window, grid_w)):
+                        t = owner[(sub * grid_h + r) * grid_w + c]
+                        if t >= 0 and (best < 0 or s[t] > s[best]):
+                            best = t
+                if best >= 0:
+                    out[best] = coef * s[best]
+    return out
+
+
+# --------------------------------------------------------------------------- filter: top-K
+def filter_tokens(s, n_keep):
+    """Stage 1 of Algorithms 1 and 2 (reading R5): the N^S = N - n_keep tokens with the
+    highest redundancy form the source set S, the rest the target set T.  Both are returned
+    in ascending index order."""
+    s = np.asarray(s, dtype=F64)
+    assert np.all(np.isfinite(s)), "scores must be finite"
+    n = len(s)
+    n_s = n - n_keep
+    assert 0 <= n_s <= n
+    order = sorted(range(n), key=lambda i: (-s[i], i))
+    S = np.array(sorted(order[:n_s]), dtype=np.int64)
+    T = np.array(sorted(order[n_s:]), dtype=np.int64)
+    return S, T
+
+
+# --------------------------------------------------------------------------- correlate
+def materialise_f32(P):
+    """The head-mean map as the step stores it between its two passes: single precision."""
+    return np.asarray(P, dtype=F64).astype(np.float32).astype(F64)
+
+
+def correlation_attention(P32, S, T, key_cols, query_rows):
+    """Stage 2 of Algorithm 1 (reading R6): C[i, j] = P[query j in T, key i in S].
+    key_cols / query_rows map a visual token index to its column / row of P32."""
+    S = np.asarray(S, dtype=np.int64)
+    T = np.asarray(T, dtype=np.int64)
+    rows = np.asarray(query_rows)[T]
+    cols = np.asarray(key_cols)[S]
+    return P32[np.ix_(rows, cols)].T.astype(F64)       # a pure gather: C[a, b] = P32[rows[b], cols[a]]
+
+
+def text_bridge(Ptext, S, T):
+    """Indirect term of Eq. 4 (reading R7).  Ptext: [M, N] head-mean attention of the M text
+    queries on the N visual tokens.  B[i, j] = (1/M) sum_k Ptext[k, i] Ptext[k, j], text
+    tokens added in order."""
+    M = Ptext.shape[0]
+    Bm = np.zeros((len(S), len(T)), dtype=F64)
+    for k in range(M):
+        Bm = Bm + np.outer(Ptext[k, S], Ptext[k, T])
+    return Bm / float(M)
+
+
+def correlation_cosine(F, S, T):
+    """Reading R10 (extension): unit rows rounded to bfloat16, C[i, j] = max(0, xh_i . xh_j)
+    (a float64 matrix product of the rounded rows)."""
+    Uh = round_to_bf16(unit_rows(F))
+    C = Uh[np.asarray(S, dtype=np.int64)] @ Uh[np.asarray(T, dtype=np.int64)].T
+    return np.maximum(C, 0.0)
+
+
+def correlation_l(direct, bridge, gamma):
+    """Eq. 4:  C = gamma * direct + (1 - gamma) * indirect."""
+    g = f32(gamma)
+    return g * direct + (1.0 - g) * bridge
+
+
+# --------------------------------------------------------------------------- compress
+def quantile_threshold(row, eps):
+    """tau = epsilon-quantile of one row of C (Algorithm 1, stage 3; reading R8)."""
+    v = np.sort(np.asarray(row, dtype=F64))
+    n = len(v)
+    p = f32(eps) * float(n - 1)
+    f = int(math.floor(p))
+    g = p - float(f)
+    f1 = min(f + 1, n - 1)
+    return v[f] + g * (v[f1] - v[f])
+
+
+def correlated_targets(C, eps):
+    """Token-adaptive K (Sec. "Correlation-based Information Recycling") and the weights of
+    Eq. 2.  Returns, per discarded row i: J_i (positions in T, ascending) and alpha_i."""
+    J, alpha, tau = [], [], []
+    for i in range(C.shape[0]):
+        if C.shape[1] == 0:
+            J.append(np.zeros(0, np.int64)); alpha.append(np.zeros(0, F64)); tau.append(0.0)
+            continue
+        t = quantile_threshold(C[i], eps)
+        sel = np.nonzero(C[i] >= t)[0]
+        d = 0.0
+        for j in sel:
+            d = d + C[i, j]
+        if d > 0.0:
+            J.append(sel.astype(np.int64))
+            alpha.append(np.array([C[i, j] / d for j in sel], dtype=F64))
+        else:                                       # reading R9
+            J.append(np.zeros(0, np.int64))
+            alpha.append(np.zeros(0, F64))
+        tau.append(t)
+    return J, alpha, np.array(tau, dtype=F64)
+
+
+def compress(X, vis_begin, S, T, J, alpha):
+    """Eq. 2 and the last stage of Algorithms 1 and 2.
+
+    X: [n_tot, D] float64 tokens of the whole sequence; S, T index the visual span that
+    starts at vis_begin.  Every preserved visual token j becomes
+        (X_j + sum_{i in I_j} alpha_ij X_i) / (1 + sum_{i in I_j} alpha_ij),
+    sources added in ascending order of i; the discarded tokens are then removed and all
+    other tokens of the sequence keep their order."""
+    X = np.asarray(X, dtype=F64)
+    num = {int(j): X[vis_begin + int(j)].copy() for j in T}
+    den = {int(j): 1.0 for j in T}
+    for a, i in enumerate(S):                       # S ascending -> ascending i per target
+        for jj, w in zip(J[a], alpha[a]):
+            j = int(T[jj])
+            num[j] = num[j] + w * X[vis_begin + int(i)]
+            den[j] = den[j] + w
+    gone = set(vis_begin + int(i) for i in S)
+    rows = []
+    for t in range(X.shape[0]):
+        if t in gone:
+            continue
+        j = t - vis_begin
+        if j in num:
+            rows.append(num[j] / den[j])
+        else:
+            rows.append(X[t].copy())
+    return np.array(rows, dtype=F64).reshape(len(rows), X.shape[1])
+
+
+# --------------------------------------------------------------------------- whole steps
+def _finish(X, vis_begin, s, n_keep, C_of, eps, pos):
+    S, T = filter_tokens(s, n_keep)
+    C = C_of(S, T)
+    J, alpha, tau = correlated_targets(C, eps)
+    X_out = compress(X, vis_begin, S, T, J, alpha)
+    pos_out = None if pos is None else np.asarray(pos)[T]
+    return dict(X_out=X_out, S=S, T=T, J=J, alpha=alpha, tau=tau, scores=s, C=C,
+                pos_out=pos_out)
+
+
+def v_step(X, A, *, cls_index, vis_begin, N, n_keep, lam=0.35, eps=0.998,
+           pos=None, grid=(1, 0, 0), window=2, coef=2.0,
+           recv_vec=None, sem_vec=None, F=None,
+           red_src="attn", sem_src="cls", corr_src="attn"):
+    """Algorithm 1 for one image.
+
+    X [n_tot, D]; A [H, n_tot, n_tot] or None; visual span [vis_begin, vis_begin+N).
+    red_src: 'attn' | 'vector' | 'sim_mean';  sem_src: 'cls' | 'vector' | 'eq_token';
+    corr_src: 'attn' | 'cosine'.  F: features for the cosine-based terms (default: the
+    visual rows of X)."""
+    X = np.asarray(X, dtype=F64)
+    vis = np.arange(vis_begin, vis_begin + N)
+    Fv = X[vis] if F is None else np.asarray(F, dtype=F64)
+    P = head_mean(A) if A is not None else None
+    if red_src == "attn":
+        R = received_attention(P, vis, vis)
+    elif red_src == "vector":
+        R = head_mean_vector(recv_vec)
+    elif red_src == "sim_mean":
+        R = mean_cosine_term(Fv)
+    else:
+        raise ValueError(red_src)
+    if sem_src == "cls":
+        G = cls_attention(P, cls_index, vis)
+    elif sem_src == "vector":
+        G = head_mean_vector(sem_vec)
+    elif sem_src == "eq_token":
+        G = equivalent_token_term(Fv)
+    else:
+        raise ValueError(sem_src)
+    s = combine_score(R, G, lam)
+    if pos is None:
+        pos = np.arange(N)
+    s = local_penalty(s, pos, grid[0], grid[1], grid[2], window, coef)
+    if corr_src == "attn":
+        P32 = materialise_f32(P)
+        C_of = lambda S, T: correlation_attention(P32, S, T, vis, vis)
+    elif corr_src == "cosine":
+        C_of = lambda S, T: correlation_cosine(Fv, S, T)
+    else:
+        raise ValueError(corr_src)
+    return _finish(X, vis_begin, s, n_keep, C_of, eps, pos)
+
+
+def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.998,
+           F=None, red_src="attn", corr_src="attn"):
+    """Algorithm 2 for one sequence.
+
+    X [n_tot, D] (system + visual + text tokens); A_tv [H, M, N]: attention of the M text
+    queries on the N visual keys; A_vv [H, N, N]: attention among the visual tokens (None
+    when the caller has no such map -- then red_src='sim_mean' and corr_src='cosine', the
+    extension of reading R10, stand in for it).  No local penalty in FiCoCo-L."""
+    X = np.asarray(X, dtype=F64)
+    vis = np.arange(vis_begin, vis_begin + N)
+    loc = np.arange(N)
+    Fv = X[vis] if F is None else np.asarray(F, dtype=F64)
+    Pt = head_mean(A_tv)
+    Pv = head_mean(A_vv) if A_vv is not None else None
+    if red_src == "attn":
+        R = received_attention(Pv, loc, loc)
+    elif red_src == "sim_mean":
+        R = mean_cosine_term(Fv)
+    else:
+        raise ValueError(red_src)
+    G = text_attention(Pt, np.arange(Pt.shape[0]), loc)
+    s = combine_score(R, G, beta)
+    if corr_src == "attn":
+        P32 = materialise_f32(Pv)
+        direct = lambda S, T: correlation_attention(P32, S, T, loc, loc)
+    elif corr_src == "cosine":
+        direct = lambda S, T: correlation_cosine(Fv, S, T)
+    else:
+        raise ValueError(corr_src)
+    C_of = lambda S, T: correlation_l(direct(S, T), text_bridge(Pt, S, T), gamma)
+    return _finish(X, vis_begin, s, n_keep, C_of, eps, None)

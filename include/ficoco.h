@@ -1,0 +1,208 @@
+/*
+ * ficoco.h -- C ABI of the MI355X (gfx950) FiCoCo token-reduction library.
+ *
+ * One call of a *_step function runs one per-layer "filter, correlate, compress" step of
+ * the paper "Filter, Correlate, Compress" (arxiv 2411.17686): Algorithm 1 (FiCoCo-V, vision
+ * encoder) or Algorithm 2 (FiCoCo-L, LLM decoder, text guided).  The stage functions expose
+ * the same path in four pieces: score -> filter -> correlate -> compress.
+ *
+ * Conventions that hold for every entry point
+ *   - Plain C: no C++ types, no exceptions cross this boundary.
+ *   - Every data pointer is a DEVICE pointer owned by the caller (tokens, maps, outputs and
+ *     the workspace).  The library allocates no device memory and frees nothing of the
+ *     caller's.  Outputs must not alias inputs.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
+ *     enqueued on it asynchronously; no call synchronises the device or copies to the host.
+ *   - Return value: a ficoco_status.  Argument errors are found on the host before anything
+ *     is launched (FICOCO_EINVAL), a workspace that is too small gives FICOCO_ENOMEM, a
+ *     failed launch FICOCO_EHIP, a legal but unimplemented combination
+ *     FICOCO_EUNSUPPORTED.  ficoco_last_error(ctx) describes the last failure on that ctx.
+ *   - Inputs are assumed finite (no NaN / Inf); behaviour is undefined otherwise.
+ *   - Attention maps P[b][h][q][k] are row-stochastic over k (query q attends key k), the
+ *     key axis contiguous.  Following the paper's wording ("received attention",
+ *     "attention-in"), the paper's A_{i,j} for a visual token i is P[j][i].
+ *   - Scores, thresholds and merge weights are computed and compared in double precision;
+ *     tokens are read and written in `dtype`.  Ties in the top-K filter go to the lower
+ *     token index.
+ */
+#ifndef FICOCO_H
+#define FICOCO_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ficoco_ctx ficoco_ctx; /* opaque: device id + last error text */
+
+typedef enum {
+  FICOCO_OK = 0,
+  FICOCO_EINVAL = 1,
+  FICOCO_ENOMEM = 2,
+  FICOCO_EHIP = 3,
+  FICOCO_EUNSUPPORTED = 4
+} ficoco_status;
+
+typedef enum { FICOCO_F32 = 0, FICOCO_BF16 = 1 } ficoco_dtype;
+
+/* Which algorithm of the paper the problem describes. */
+typedef enum { FICOCO_VARIANT_V = 0, FICOCO_VARIANT_L = 1 } ficoco_variant;
+
+/* First score term R_i of Eq. 1 / Eq. 3 (the token's received attention). */
+typedef enum {
+  FICOCO_R_ATTN_RECV = 0, /* (1/N) sum over visual queries q of headmean P[q][i]              */
+  FICOCO_R_VECTOR = 1,    /* headmean of the caller's pre-reduced recv_vec[b][h][i]          */
+  FICOCO_R_SIM_MEAN = 2   /* extension: (1/N) sum_j cos(F_i, F_j), when no map is available  */
+} ficoco_red_src;
+
+/* Second score term G_i (entered with a minus sign). */
+typedef enum {
+  FICOCO_G_CLS_ATTN = 0,  /* Eq. 1: headmean P[CLS][i]                                        */
+  FICOCO_G_TEXT_ATTN = 1, /* Eq. 3: (1/M) sum over text queries k of headmean P[k][i]         */
+  FICOCO_G_VECTOR = 2,    /* headmean of sem_vec[b][h][i]                                     */
+  FICOCO_G_EQ_TOKEN = 3   /* appendix "Implementation of the Equivalent Token": -cos(mu,F_i) */
+} ficoco_sem_src;
+
+/* Direct correlation C_ij between discarded i and preserved j. */
+typedef enum {
+  FICOCO_C_ATTN = 0,  /* Algorithm 1 stage 2: headmean P[j][i], held in single precision      */
+  FICOCO_C_COSINE = 1 /* extension: max(0, xh_i . xh_j), xh = bfloat16(F / |F|)                */
+} ficoco_corr_src;
+
+/*
+ * Problem description (host struct, passed by pointer, read during the call only).
+ * Token indices are positions in the sequence of n_tot tokens; the reducible visual tokens
+ * are the span [vis_begin, vis_begin + N).  "Visual token i" below means sequence position
+ * vis_begin + i.  Strides are in ELEMENTS of `dtype`.
+ */
+typedef struct {
+  int32_t variant; /* ficoco_variant */
+  int32_t dtype;   /* ficoco_dtype of X, A, A_text, recv_vec, sem_vec, F and X_out */
+  int32_t B, H, D;
+  int32_t n_tot;     /* tokens per sequence in X (V: [CLS]+N or N;  L: system+N+text)  */
+  int32_t vis_begin; /* first reducible visual token                                     */
+  int32_t N;         /* number of reducible visual tokens                                */
+  int32_t n_keep;    /* N^T = tokens preserved;  N^S = N - n_keep are discarded          */
+  int32_t cls_index; /* sequence position of [CLS] (FICOCO_G_CLS_ATTN), else -1         */
+
+  const void *X; /* [B][n_tot][D], D contiguous */
+  int64_t x_stride_b, x_stride_n;
+
+  /* Attention block that holds the visual queries x visual keys (and the [CLS] query row
+   * when used): row r is the query at sequence position a_q_begin + r, column c the key at
+   * a_k_begin + c.  NULL when neither FICOCO_R_ATTN_RECV, FICOCO_G_CLS_ATTN nor
+   * FICOCO_C_ATTN is selected. */
+  const void *A; /* [B][H][a_nq][a_nk], a_nk contiguous */
+  int64_t a_stride_b, a_stride_h, a_stride_q;
+  int32_t a_q_begin, a_nq, a_k_begin, a_nk;
+
+  /* FiCoCo-L: attention of the M text queries, columns covering the visual keys: column c
+   * is the key at sequence position at_k_begin + c.  May point into the same map as A. */
+  const void *A_text; /* [B][H][M][at_nk] */
+  int64_t at_stride_b, at_stride_h, at_stride_q;
+  int32_t M, at_k_begin, at_nk;
+
+  const void *recv_vec; /* [B][H][N] contiguous, FICOCO_R_VECTOR */
+  const void *sem_vec;  /* [B][H][N] contiguous, FICOCO_G_VECTOR */
+
+  /* Features of the visual tokens for the cosine-based terms (EQ_TOKEN: head-mean keys).
+   * NULL = use the visual rows of X (then Df is ignored and D is used). */
+  const void *F; /* [B][N][Df] */
+  int64_t f_stride_b, f_stride_n;
+  int32_t Df;
+
+  /* Local penalty (FiCoCo-V): pos[b][i] = grid cell of visual token i in grid_g stacked
+   * grid_h x grid_w grids, row-major; NULL = cell i.  window = 0 switches it off. */
+  const int32_t *pos;
+  int32_t grid_g, grid_h, grid_w, window;
+  float penalty_coef;
+
+  float w_score; /* lambda (Eq. 1) or beta (Eq. 3) */
+  float gamma;   /* Eq. 4; ignored by FiCoCo-V      */
+  float eps;     /* quantile of the token-wise threshold, in [0, 1] */
+
+  int32_t red_src, sem_src, corr_src;
+  int32_t k_max; /* capacity of targets per discarded token in the edge lists (>= 1) */
+} ficoco_problem;
+
+/* ctx: create once per device; not thread safe (one ctx per calling thread). */
+int ficoco_create(ficoco_ctx **out, int device);
+int ficoco_destroy(ficoco_ctx *ctx);
+const char *ficoco_last_error(const ficoco_ctx *ctx);
+const char *ficoco_version(void);
+
+/* Bytes of device workspace the calls below need for this problem (256-byte aligned
+ * pointer expected).  The workspace carries state from one stage to the next: the stage
+ * functions must be called in order, on one stream, with the same problem and workspace. */
+int ficoco_workspace_bytes(const ficoco_problem *p, size_t *out_bytes);
+
+/*
+ * Filter, part 1 (Eq. 1 / Eq. 3 and the local penalty, Sec. "Redundancy-based Token
+ * Discard"; Sec. "Task-Aware Improvements for FiCoCo-L"): reduces the attention maps /
+ * features once and writes the redundancy score of every visual token.  Also leaves the
+ * head-mean maps needed by ficoco_correlate in the workspace.
+ *   scores  [B][N] double, out: penalised scores (what the filter ranks).
+ */
+int ficoco_score(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                 double *scores, void *stream);
+
+/*
+ * Filter, part 2 (Algorithm 1/2, stage 1): the N^S visual tokens with the highest score
+ * (ties: lower index first) are discarded.
+ *   scores       [B][N] double, in.
+ *   discard_idx  [B][N^S] int32, out: visual token indices of the source set, ascending.
+ *   keep_idx     [B][N^T] int32, out: visual token indices of the target set, ascending.
+ */
+int ficoco_filter(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                  const double *scores, int32_t *discard_idx, int32_t *keep_idx, void *stream);
+
+/*
+ * Correlate (Sec. "Correlation-based Information Recycling", Eq. 4, and the threshold /
+ * weight lines of Algorithm 1/2 stage 3): for every discarded token the correlation row
+ * over the preserved tokens, its eps-quantile tau_i (linear interpolation between order
+ * statistics), the targets J_i = { j : C_ij >= tau_i } and the weights
+ * alpha_ij = C_ij / sum_{J_i} C_ij.  Needs the workspace left by ficoco_score.
+ *   edge_cnt   [B][N^S] int32, out: |J_i| stored for discarded row i (0 = pruned).
+ *   edge_tgt   [B][N^S][k_max] int32, out: slots into keep_idx, ascending.
+ *   edge_alpha [B][N^S][k_max] double, out.
+ *   overflow   [B] int32, out: set to 1 when some row had more than k_max targets (that
+ *              image's result is then incomplete: rerun with a larger k_max), else 0.
+ */
+int ficoco_correlate(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                     const int32_t *discard_idx, const int32_t *keep_idx, int32_t *edge_cnt,
+                     int32_t *edge_tgt, double *edge_alpha, int32_t *overflow, void *stream);
+
+/*
+ * Compress (Eq. 2, self-preserving compression; last lines of Algorithm 1/2): every
+ * preserved visual token becomes (X_j + sum_i alpha_ij X_i) / (1 + sum_i alpha_ij), sources
+ * added in ascending order; discarded tokens are dropped and every other token of the
+ * sequence is copied unchanged, order preserved.
+ *   X_out   [B][n_tot - N^S][D] dtype, out (dense).
+ *   pos_out [B][N^T] int32, out: grid cells of the preserved tokens (may be NULL).
+ */
+int ficoco_compress(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                    const int32_t *discard_idx, const int32_t *keep_idx, const int32_t *edge_cnt,
+                    const int32_t *edge_tgt, const double *edge_alpha, void *X_out,
+                    int32_t *pos_out, void *stream);
+
+/*
+ * Algorithm 1 (FiCoCo-V) / Algorithm 2 (FiCoCo-L) as one call: the four stages above on
+ * one stream and one workspace without host synchronisation.  Every output of the stage
+ * functions is produced (scores, index sets, edge lists, overflow flags, X_out, pos_out);
+ * pos_out may be NULL.  n_keep == N is legal: X_out is then a bit-exact copy of X.
+ */
+int ficoco_v_step(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                  void *X_out, int32_t *pos_out, int32_t *keep_idx, int32_t *discard_idx,
+                  int32_t *edge_cnt, int32_t *edge_tgt, double *edge_alpha, double *scores,
+                  int32_t *overflow, void *stream);
+int ficoco_l_step(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                  void *X_out, int32_t *pos_out, int32_t *keep_idx, int32_t *discard_idx,
+                  int32_t *edge_cnt, int32_t *edge_tgt, double *edge_alpha, double *scores,
+                  int32_t *overflow, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FICOCO_H */

@@ -1,0 +1,305 @@
+// C-ABI layer: argument checks, workspace plan and the stage / fused-step entry points
+// declared in include/ficoco.h.  Host code only; every launch goes to the caller's stream.
+#include <cmath>
+#include <cstdio>
+#include <cstring>
+#include <new>
+
+#include "common.hpp"
+
+struct ficoco_ctx {
+  int device;
+  char err[512];
+};
+
+namespace ficoco {
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
+  static const char* kNone = "";
+  *why = kNone;
+  std::memset(&pl, 0, sizeof(pl));
+#define REQUIRE(c, msg) do { if (!(c)) { *why = msg; return FICOCO_EINVAL; } } while (0)
+  REQUIRE(p.variant == FICOCO_VARIANT_V || p.variant == FICOCO_VARIANT_L, "variant must be V or L");
+  REQUIRE(p.dtype == FICOCO_F32 || p.dtype == FICOCO_BF16, "dtype must be F32 or BF16");
+  REQUIRE(p.B >= 1 && p.D >= 1 && p.n_tot >= 1, "B, D, n_tot must be positive");
+  REQUIRE(p.N >= 1 && p.vis_begin >= 0 && p.vis_begin + (int64_t)p.N <= p.n_tot,
+          "visual span [vis_begin, vis_begin+N) must lie inside the sequence");
+  REQUIRE(p.n_keep >= 0 && p.n_keep <= p.N, "n_keep must be in [0, N]");
+  REQUIRE(p.n_keep >= 1 || p.N == 0, "n_keep must be >= 1 (nothing to recycle into)");
+  REQUIRE(p.N <= kMaxSelectN, "N exceeds the per-image limit of the filter kernel (12288)");
+  REQUIRE(p.X != nullptr, "X is NULL");
+  REQUIRE(p.x_stride_n >= p.D && p.x_stride_b >= 0, "bad X strides");
+  REQUIRE(p.eps >= 0.0f && p.eps <= 1.0f, "eps must be in [0, 1]");
+  REQUIRE(p.k_max >= 1, "k_max must be >= 1");
+  REQUIRE(p.red_src >= 0 && p.red_src <= 2 && p.sem_src >= 0 && p.sem_src <= 3 &&
+              p.corr_src >= 0 && p.corr_src <= 1, "unknown source selector");
+  const bool L = p.variant == FICOCO_VARIANT_L;
+  const bool need_A = p.red_src == FICOCO_R_ATTN_RECV || p.sem_src == FICOCO_G_CLS_ATTN ||
+                      p.corr_src == FICOCO_C_ATTN;
+  if (need_A) {
+    REQUIRE(p.A != nullptr, "A is NULL but an attention-derived term is selected");
+    REQUIRE(p.H >= 1, "H must be positive");
+    REQUIRE(p.a_nq >= 1 && p.a_nk >= 1 && p.a_stride_q >= p.a_nk, "bad A shape / strides");
+    REQUIRE(p.a_k_begin <= p.vis_begin && p.vis_begin + p.N <= p.a_k_begin + p.a_nk,
+            "A does not cover the visual keys");
+    if (p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN)
+      REQUIRE(p.a_q_begin <= p.vis_begin && p.vis_begin + p.N <= p.a_q_begin + p.a_nq,
+              "A does not cover the visual queries");
+    if (p.sem_src == FICOCO_G_CLS_ATTN)
+      REQUIRE(p.cls_index >= p.a_q_begin && p.cls_index < p.a_q_begin + p.a_nq &&
+                  (p.cls_index < p.vis_begin || p.cls_index >= p.vis_begin + p.N),
+              "cls_index must be a query row of A outside the visual span");
+  }
+  if (L) {
+    REQUIRE(p.sem_src == FICOCO_G_TEXT_ATTN, "FiCoCo-L uses the text-attention term (Eq. 3)");
+    REQUIRE(p.A_text != nullptr && p.M >= 1 && p.H >= 1, "A_text / M missing for FiCoCo-L");
+    REQUIRE(p.at_stride_q >= p.at_nk && p.at_k_begin <= p.vis_begin &&
+                p.vis_begin + p.N <= p.at_k_begin + p.at_nk, "A_text does not cover the visual keys");
+  } else {
+    REQUIRE(p.sem_src != FICOCO_G_TEXT_ATTN, "the text-attention term belongs to FiCoCo-L");
+  }
+  if (p.red_src == FICOCO_R_VECTOR) REQUIRE(p.recv_vec != nullptr && p.H >= 1, "recv_vec is NULL");
+  if (p.sem_src == FICOCO_G_VECTOR) REQUIRE(p.sem_vec != nullptr && p.H >= 1, "sem_vec is NULL");
+  const bool penalty = !L && p.window > 0;
+  if (penalty) {
+    REQUIRE(p.grid_g >= 1 && p.grid_h >= 1 && p.grid_w >= 1, "grid dimensions must be positive");
+    const int64_t cells = (int64_t)p.grid_g * p.grid_h * p.grid_w;
+    REQUIRE(cells >= p.N && cells <= kMaxSelectN, "grid must have between N and 12288 cells");
+    REQUIRE(p.pos != nullptr || cells == p.N, "pos is NULL but the grid has more cells than tokens");
+  }
+  pl.need_features = p.red_src == FICOCO_R_SIM_MEAN || p.sem_src == FICOCO_G_EQ_TOKEN ||
+                     p.corr_src == FICOCO_C_COSINE;
+  pl.Df = p.F ? p.Df : p.D;
+  if (pl.need_features && p.F)
+    REQUIRE(p.Df >= 1 && p.f_stride_n >= p.Df, "bad F shape / strides");
+#undef REQUIRE
+
+  pl.n_disc = p.N - p.n_keep;
+  pl.n_out = p.n_tot - pl.n_disc;
+
+  // attention reduction geometry
+  const int groups = (p.N + kVec - 1) / kVec;
+  pl.col_strips = (groups + kReduceThreads - 1) / kReduceThreads;
+  pl.strip_groups = (groups + pl.col_strips - 1) / pl.col_strips;
+  pl.row_lanes = kReduceThreads / pl.strip_groups;
+  if (pl.row_lanes < 1) pl.row_lanes = 1;
+  auto rows_per_wg = [&](int rows) {
+    int64_t want = ((int64_t)p.B * pl.col_strips * rows + 1023) / 1024;  // aim at ~1024 workgroups
+    if (want < 1) want = 1;
+    int r = (int)((want + pl.row_lanes - 1) / pl.row_lanes) * pl.row_lanes;
+    return r;
+  };
+  if (need_A) {
+    int lo = p.vis_begin - p.a_q_begin, hi = lo + p.N;  // visual query rows
+    const bool vis_rows = p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN;
+    if (!vis_rows) { lo = hi = p.cls_index - p.a_q_begin; ++hi; }
+    if (p.sem_src == FICOCO_G_CLS_ATTN) {
+      const int c = p.cls_index - p.a_q_begin;
+      if (c < lo) lo = c;
+      if (c + 1 > hi) hi = c + 1;
+    }
+    pl.a_row0 = lo;
+    pl.a_rows = hi - lo;
+    pl.rows_per_wg = rows_per_wg(pl.a_rows);
+    pl.n_chunks = (pl.a_rows + pl.rows_per_wg - 1) / pl.rows_per_wg;
+  } else {
+    pl.n_chunks = 0;
+  }
+  if (L) {
+    pl.t_rows_per_wg = rows_per_wg(p.M);
+    pl.t_chunks = (p.M + pl.t_rows_per_wg - 1) / pl.t_rows_per_wg;
+  }
+
+  // threshold selection: p = eps (n-1) evaluated in double from the float eps
+  if (p.n_keep >= 1) {
+    const double q = (double)p.eps * (double)(p.n_keep - 1);
+    const double f = std::floor(q);
+    pl.sel_f = (int)f;
+    pl.sel_g = q - f;
+    pl.sel_m = p.n_keep - pl.sel_f;
+    pl.dense_rows = pl.sel_m > kSelMax;
+  }
+
+  // feature pass geometry (column sums over the tokens)
+  if (pl.need_features) {
+    pl.f_rows_per_wg = 16;
+    pl.f_chunks = (p.N + pl.f_rows_per_wg - 1) / pl.f_rows_per_wg;
+  }
+
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1); return o; };
+  const size_t B = p.B, N = p.N;
+  pl.abar = take(p.corr_src == FICOCO_C_ATTN ? B * N * N * sizeof(float) : 0);
+  pl.recv_part = take(B * (size_t)pl.n_chunks * N * sizeof(double));
+  pl.cls = take(B * N * sizeof(double));
+  pl.ttext = take(L ? B * N * (size_t)p.M * sizeof(double) : 0);
+  pl.inv_norm = take(pl.need_features ? B * N * sizeof(double) : 0);
+  pl.xhat = take(p.corr_src == FICOCO_C_COSINE ? B * N * (size_t)pl.Df * sizeof(bf16_t) : 0);
+  pl.colsum_part = take(pl.need_features ? 2 * B * (size_t)pl.f_chunks * pl.Df * sizeof(double) : 0);
+  pl.colmean = take(pl.need_features ? 2 * B * (size_t)pl.Df * sizeof(double) : 0);
+  pl.fterm = take(B * N * sizeof(double));
+  pl.fterm2 = take(B * N * sizeof(double));
+  pl.slot_of = take(B * N * sizeof(int32_t));
+  pl.tgt_ptr = take(B * (size_t)(p.n_keep + 1) * sizeof(int32_t));
+  pl.tgt_src = take(B * (size_t)pl.n_disc * p.k_max * sizeof(int32_t));
+  pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
+  pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
+  pl.total = off;
+  return FICOCO_OK;
+}
+
+static int fail(ficoco_ctx* ctx, int code, const char* what, const char* detail) {
+  if (ctx) std::snprintf(ctx->err, sizeof(ctx->err), "%s: %s", what, detail ? detail : "");
+  return code;
+}
+
+static int prepare(ficoco_ctx* ctx, const ficoco_problem* p, const void* ws, size_t ws_bytes,
+                   Plan& pl, const char* fn) {
+  if (!ctx) return FICOCO_EINVAL;
+  if (!p) return fail(ctx, FICOCO_EINVAL, fn, "problem is NULL");
+  const char* why;
+  const int rc = make_plan(*p, pl, &why);
+  if (rc != FICOCO_OK) return fail(ctx, rc, fn, why);
+  if (!ws || ((uintptr_t)ws & 255)) return fail(ctx, FICOCO_EINVAL, fn, "workspace is NULL or not 256-byte aligned");
+  if (ws_bytes < pl.total) return fail(ctx, FICOCO_ENOMEM, fn, "workspace smaller than ficoco_workspace_bytes()");
+  return FICOCO_OK;
+}
+
+static int finish(ficoco_ctx* ctx, const char* fn) {
+  const hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return fail(ctx, FICOCO_EHIP, fn, hipGetErrorString(e));
+  return FICOCO_OK;
+}
+
+static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void* ws, size_t ws_bytes,
+                    void* X_out, int32_t* pos_out, int32_t* keep_idx, int32_t* discard_idx,
+                    int32_t* edge_cnt, int32_t* edge_tgt, double* edge_alpha, double* scores,
+                    int32_t* overflow, void* stream, const char* fn) {
+  if (!ctx) return FICOCO_EINVAL;
+  if (!p0) return fail(ctx, FICOCO_EINVAL, fn, "problem is NULL");
+  if (p0->variant != variant) return fail(ctx, FICOCO_EINVAL, fn, "problem.variant does not match the entry point");
+  Plan pl;
+  const int rc = prepare(ctx, p0, ws, ws_bytes, pl, fn);
+  if (rc != FICOCO_OK) return rc;
+  if (!X_out || !keep_idx || !scores || !overflow ||
+      (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
+    return fail(ctx, FICOCO_EINVAL, fn, "an output pointer is NULL");
+  const ficoco_problem& p = *p0;
+  hipStream_t s = (hipStream_t)stream;
+  char* w = (char*)ws;
+  launch_attn_reduce(p, pl, w, s);
+  if (pl.need_features) launch_features(p, pl, w, s);
+  launch_score(p, pl, w, scores, s);
+  launch_filter(p, pl, w, scores, discard_idx, keep_idx, s);
+  launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, s);
+  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
+  return finish(ctx, fn);
+}
+
+}  // namespace ficoco
+
+using namespace ficoco;
+
+extern "C" {
+
+int ficoco_create(ficoco_ctx** out, int device) {
+  if (!out) return FICOCO_EINVAL;
+  *out = nullptr;
+  int count = 0;
+  if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return FICOCO_EHIP;
+  ficoco_ctx* c = new (std::nothrow) ficoco_ctx;
+  if (!c) return FICOCO_ENOMEM;
+  c->device = device;
+  c->err[0] = 0;
+  *out = c;
+  return FICOCO_OK;
+}
+
+int ficoco_destroy(ficoco_ctx* ctx) {
+  delete ctx;
+  return FICOCO_OK;
+}
+
+const char* ficoco_last_error(const ficoco_ctx* ctx) { return ctx ? ctx->err : "ctx is NULL"; }
+
+const char* ficoco_version(void) { return "ficoco-gfx950 0.1"; }
+
+int ficoco_workspace_bytes(const ficoco_problem* p, size_t* out_bytes) {
+  if (!p || !out_bytes) return FICOCO_EINVAL;
+  Plan pl;
+  const char* why;
+  const int rc = make_plan(*p, pl, &why);
+  if (rc != FICOCO_OK) return rc;
+  *out_bytes = pl.total;
+  return FICOCO_OK;
+}
+
+int ficoco_score(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, double* scores,
+                 void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_score");
+  if (rc != FICOCO_OK) return rc;
+  if (!scores) return fail(ctx, FICOCO_EINVAL, "ficoco_score", "scores is NULL");
+  launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
+  if (pl.need_features) launch_features(*p, pl, (char*)ws, (hipStream_t)stream);
+  launch_score(*p, pl, (char*)ws, scores, (hipStream_t)stream);
+  return finish(ctx, "ficoco_score");
+}
+
+int ficoco_filter(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,
+                  const double* scores, int32_t* discard_idx, int32_t* keep_idx, void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_filter");
+  if (rc != FICOCO_OK) return rc;
+  if (!scores || !keep_idx || (pl.n_disc > 0 && !discard_idx))
+    return fail(ctx, FICOCO_EINVAL, "ficoco_filter", "a pointer is NULL");
+  launch_filter(*p, pl, (char*)ws, scores, discard_idx, keep_idx, (hipStream_t)stream);
+  return finish(ctx, "ficoco_filter");
+}
+
+int ficoco_correlate(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,
+                     const int32_t* discard_idx, const int32_t* keep_idx, int32_t* edge_cnt,
+                     int32_t* edge_tgt, double* edge_alpha, int32_t* overflow, void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_correlate");
+  if (rc != FICOCO_OK) return rc;
+  if (!keep_idx || !overflow || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
+    return fail(ctx, FICOCO_EINVAL, "ficoco_correlate", "a pointer is NULL");
+  launch_correlate(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow,
+                   (hipStream_t)stream);
+  return finish(ctx, "ficoco_correlate");
+}
+
+int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,
+                    const int32_t* discard_idx, const int32_t* keep_idx, const int32_t* edge_cnt,
+                    const int32_t* edge_tgt, const double* edge_alpha, void* X_out, int32_t* pos_out,
+                    void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_compress");
+  if (rc != FICOCO_OK) return rc;
+  if (!X_out || !keep_idx || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
+    return fail(ctx, FICOCO_EINVAL, "ficoco_compress", "a pointer is NULL");
+  launch_compress(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out,
+                  pos_out, (hipStream_t)stream);
+  return finish(ctx, "ficoco_compress");
+}
+
+int ficoco_v_step(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, void* X_out,
+                  int32_t* pos_out, int32_t* keep_idx, int32_t* discard_idx, int32_t* edge_cnt,
+                  int32_t* edge_tgt, double* edge_alpha, double* scores, int32_t* overflow,
+                  void* stream) {
+  return run_step(ctx, p, FICOCO_VARIANT_V, ws, ws_bytes, X_out, pos_out, keep_idx, discard_idx,
+                  edge_cnt, edge_tgt, edge_alpha, scores, overflow, stream, "ficoco_v_step");
+}
+
+int ficoco_l_step(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, void* X_out,
+                  int32_t* pos_out, int32_t* keep_idx, int32_t* discard_idx, int32_t* edge_cnt,
+                  int32_t* edge_tgt, double* edge_alpha, double* scores, int32_t* overflow,
+                  void* stream) {
+  return run_step(ctx, p, FICOCO_VARIANT_L, ws, ws_bytes, X_out, pos_out, keep_idx, discard_idx,
+                  edge_cnt, edge_tgt, edge_alpha, scores, overflow, stream, "ficoco_l_step");
+}
+
+}  // extern "C"

@@ -1,0 +1,175 @@
+// Attention-map reduction: the one pass over the [B,H,Nq,Nk] maps.
+//
+// For every query row that carries a role (visual query, [CLS] query, text query) the
+// head mean  Pbar[q][k] = (1/H) sum_h P[h][q][k]  is formed in double precision, heads added
+// in order (so the value does not depend on the launch shape), and consumed three ways:
+//   visual query : added into the per-column "received attention" partial of this row chunk
+//                  (first term of Eq. 1 / Eq. 3) and stored in single precision as the map
+//                  the correlate stage gathers from (Algorithm 1, stage 2);
+//   [CLS] query  : stored as the semantic term of Eq. 1;
+//   text query   : stored transposed as the token's text-attention profile (task term of
+//                  Eq. 3 and indirect term of Eq. 4).
+// HBM-bound: each lane streams 8 consecutive key columns of one row for all heads with
+// 16-byte loads; rows of a dense map with an odd length are only element aligned, the
+// hardware's unaligned dwordx4 access is relied on for those.
+#include "common.hpp"
+
+namespace ficoco {
+
+struct AttnArgs {
+  const void* A;
+  int64_t sb, sh, sq;
+  int H;
+  int row0, nrows;  // rows [row0, row0+nrows) of the block are visited
+  int col0;         // column of visual key 0
+  int N;
+  int vis_r0, n_vis;  // rows of the visual queries (n_vis = 0: none)
+  int cls_r;          // row of the [CLS] query or -1
+  int txt_r0, M;      // rows of the text queries (M = 0: none)
+  float* abar;
+  double* recv_part;
+  double* cls;
+  double* ttext;
+  int rows_per_wg, n_chunks, row_lanes, strip_groups;
+  double invH;
+};
+
+template <typename T>
+__global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a) {
+  extern __shared__ double lds[];
+  const int chunk = blockIdx.x, strip = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int cg = tid % a.strip_groups, rl = tid / a.strip_groups;
+  const int col = (strip * a.strip_groups + cg) * kVec;
+  const int ncol = min(kVec, a.N - col);
+  const bool active = rl < a.row_lanes && ncol > 0;
+
+  double acc[kVec];
+#pragma unroll
+  for (int k = 0; k < kVec; ++k) acc[k] = 0.0;
+
+  if (active) {
+    const int r_begin = a.row0 + chunk * a.rows_per_wg;
+    const int r_end = min(r_begin + a.rows_per_wg, a.row0 + a.nrows);
+    const T* Ab = (const T*)a.A + (int64_t)b * a.sb + a.col0 + col;
+    for (int r = r_begin + rl; r < r_end; r += a.row_lanes) {
+      const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
+      const bool is_cls = r == a.cls_r;
+      const bool is_txt = r >= a.txt_r0 && r < a.txt_r0 + a.M;
+      if (!(is_vis || is_cls || is_txt)) continue;
+      const T* base = Ab + (int64_t)r * a.sq;
+      double p[kVec];
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) p[k] = 0.0;
+      if (ncol == kVec) {
+#pragma unroll 8
+        for (int h = 0; h < a.H; ++h) {
+          double v[kVec];
+          load8<T>(base + (int64_t)h * a.sh, v);
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) p[k] += v[k];
+        }
+      } else {
+        for (int h = 0; h < a.H; ++h)
+          for (int k = 0; k < ncol; ++k) p[k] += widen(base[(int64_t)h * a.sh + k]);
+      }
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) p[k] *= a.invH;
+
+      if (is_vis) {
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) acc[k] += p[k];
+        if (a.abar) {
+          float* dst = a.abar + ((int64_t)b * a.N + (r - a.vis_r0)) * a.N + col;
+          if (ncol == kVec) {
+            float4 lo = make_float4((float)p[0], (float)p[1], (float)p[2], (float)p[3]);
+            float4 hi = make_float4((float)p[4], (float)p[5], (float)p[6], (float)p[7]);
+            __builtin_memcpy(dst, &lo, 16);
+            __builtin_memcpy(dst + 4, &hi, 16);
+          } else {
+            for (int k = 0; k < ncol; ++k) dst[k] = (float)p[k];
+          }
+        }
+      }
+      if (is_cls) {
+        double* dst = a.cls + (int64_t)b * a.N + col;
+        for (int k = 0; k < ncol; ++k) dst[k] = p[k];
+      }
+      if (is_txt) {
+        double* dst = a.ttext + ((int64_t)b * a.N + col) * a.M + (r - a.txt_r0);
+        for (int k = 0; k < ncol; ++k) dst[(int64_t)k * a.M] = p[k];
+      }
+    }
+  }
+
+  if (a.recv_part == nullptr) return;  // uniform for the whole grid
+  // Combine the row lanes in a fixed order, then one partial per (image, chunk, column).
+  const int width = a.strip_groups * kVec;
+  if (rl < a.row_lanes) {
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) lds[rl * width + cg * kVec + k] = acc[k];
+  }
+  __syncthreads();
+  if (rl == 0 && ncol > 0) {
+    double* dst = a.recv_part + ((int64_t)b * a.n_chunks + chunk) * a.N + col;
+    for (int k = 0; k < ncol; ++k) {
+      double s = 0.0;
+      for (int l = 0; l < a.row_lanes; ++l) s += lds[l * width + cg * kVec + k];
+      dst[k] = s;
+    }
+  }
+}
+
+static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hipStream_t s) {
+  dim3 grid(a.n_chunks, col_strips, B), block(kReduceThreads);
+  const size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
+  if (bf16)
+    hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, a);
+  else
+    hipLaunchKernelGGL(attn_reduce_kernel<float>, grid, block, lds, s, a);
+}
+
+void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+  const bool bf16 = p.dtype == FICOCO_BF16;
+  const bool want_recv = p.red_src == FICOCO_R_ATTN_RECV;
+  const bool want_cls = p.sem_src == FICOCO_G_CLS_ATTN;
+  const bool want_abar = p.corr_src == FICOCO_C_ATTN && pl.n_disc > 0;
+  if (p.A && (want_recv || want_cls || want_abar)) {
+    AttnArgs a{};
+    a.A = p.A; a.sb = p.a_stride_b; a.sh = p.a_stride_h; a.sq = p.a_stride_q;
+    a.H = p.H;
+    a.row0 = pl.a_row0; a.nrows = pl.a_rows;
+    a.col0 = p.vis_begin - p.a_k_begin;
+    a.N = p.N;
+    a.vis_r0 = p.vis_begin - p.a_q_begin;
+    a.n_vis = (want_recv || want_abar) ? p.N : 0;
+    a.cls_r = want_cls ? p.cls_index - p.a_q_begin : -1;
+    a.txt_r0 = 0; a.M = 0;
+    a.abar = want_abar ? (float*)(ws + pl.abar) : nullptr;
+    a.recv_part = (double*)(ws + pl.recv_part);
+    a.cls = (double*)(ws + pl.cls);
+    a.ttext = nullptr;
+    a.rows_per_wg = pl.rows_per_wg; a.n_chunks = pl.n_chunks;
+    a.row_lanes = pl.row_lanes; a.strip_groups = pl.strip_groups;
+    a.invH = 1.0 / (double)p.H;
+    launch_block(a, p.B, pl.col_strips, bf16, s);
+  }
+  if (p.A_text && p.variant == FICOCO_VARIANT_L) {
+    AttnArgs a{};
+    a.A = p.A_text; a.sb = p.at_stride_b; a.sh = p.at_stride_h; a.sq = p.at_stride_q;
+    a.H = p.H;
+    a.row0 = 0; a.nrows = p.M;
+    a.col0 = p.vis_begin - p.at_k_begin;
+    a.N = p.N;
+    a.vis_r0 = 0; a.n_vis = 0; a.cls_r = -1;
+    a.txt_r0 = 0; a.M = p.M;
+    a.abar = nullptr; a.recv_part = nullptr; a.cls = nullptr;
+    a.ttext = (double*)(ws + pl.ttext);
+    a.rows_per_wg = pl.t_rows_per_wg; a.n_chunks = pl.t_chunks;
+    a.row_lanes = pl.row_lanes; a.strip_groups = pl.strip_groups;
+    a.invH = 1.0 / (double)p.H;
+    launch_block(a, p.B, pl.col_strips, bf16, s);
+  }
+}
+
+}  // namespace ficoco

@@ -1,0 +1,117 @@
+// Internal declarations shared by the kernels and the C-ABI layer of the FiCoCo library.
+// gfx950 only (64-wide wavefronts).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+
+#include "../../include/ficoco.h"
+
+namespace ficoco {
+
+constexpr int kWave = 64;
+constexpr int kVec = 8;            // elements per lane per load in the streaming kernels
+constexpr int kSelMax = 8;         // order statistics kept in registers by the fast threshold path
+constexpr int kReduceThreads = 256;
+constexpr int kSelectThreads = 1024;
+constexpr int kMaxSelectN = 12288; // visual tokens / grid cells the per-image select kernel holds in LDS
+
+// Workspace layout: byte offsets from a 256-byte aligned base, 0 = absent.
+struct Plan {
+  int n_disc;            // N^S
+  int n_out;             // n_tot - N^S
+  // attention reduction
+  int col_strips;        // column strips of the visual keys
+  int strip_groups;      // 8-column groups per strip
+  int row_lanes;         // rows processed concurrently by one workgroup
+  int rows_per_wg;       // visual-block rows per workgroup
+  int n_chunks;          // row chunks of the A block (partials of the received attention)
+  int a_row0, a_rows;    // rows of A that carry a role (first, count)
+  int t_rows_per_wg, t_chunks;
+  // threshold selection
+  int sel_m;             // order statistics needed: n_keep - floor(eps (n_keep-1))
+  int sel_f;             // floor(p)
+  double sel_g;          // fractional part of p
+  bool dense_rows;       // sel_m > kSelMax: rows are materialised and selected bit by bit
+  bool need_features;    // unit rows / norms
+  size_t abar;           // float  [B][N][N]      head-mean visual x visual map
+  size_t recv_part;      // double [B][n_chunks][N]
+  size_t cls;            // double [B][N]
+  size_t ttext;          // double [B][N][M]      head-mean text->visual map, transposed
+  size_t inv_norm;       // double [B][N]         1/|F_i| (0 for a zero row)
+  size_t xhat;           // bf16   [B][N][Df]     unit rows rounded to bfloat16
+  size_t colsum_part;    // double [B][f_chunks][Df]
+  size_t colmean;        // double [B][Df]
+  size_t fterm;          // double [B][N]         feature-derived score term
+  size_t fterm2;         // double [B][N]
+  size_t slot_of;        // int32  [B][N]         keep slot of a preserved token, -1 if discarded
+  size_t tgt_ptr;        // int32  [B][n_keep+1]
+  size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
+  size_t tgt_alpha;      // double [B][N^S*k_max]
+  size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
+  int f_chunks, f_rows_per_wg, Df;
+  size_t total;
+};
+
+int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
+
+// ---- launchers (all asynchronous on `s`) -----------------------------------------------
+void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s);
+void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
+                   int32_t* discard_idx, int32_t* keep_idx, hipStream_t s);
+void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
+                      const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
+                      double* edge_alpha, int32_t* overflow, hipStream_t s);
+void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
+                     const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
+                     const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s);
+
+// ---- device helpers ----------------------------------------------------------------------
+typedef uint16_t bf16_t;
+
+template <typename T> struct __attribute__((packed, aligned(2))) Pack8 { T v[kVec]; };
+
+__device__ __forceinline__ double widen(bf16_t x) {
+  return (double)__uint_as_float(((uint32_t)x) << 16);
+}
+__device__ __forceinline__ double widen(float x) { return (double)x; }
+
+// 8 consecutive elements from an address that is only element aligned.
+template <typename T>
+__device__ __forceinline__ void load8(const T* __restrict__ p, double (&out)[kVec]);
+
+template <>
+__device__ __forceinline__ void load8<bf16_t>(const bf16_t* __restrict__ p, double (&out)[kVec]) {
+  uint4 r;
+  __builtin_memcpy(&r, p, 16);
+  const uint32_t w[4] = {r.x, r.y, r.z, r.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    out[2 * j] = (double)__uint_as_float(w[j] << 16);
+    out[2 * j + 1] = (double)__uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+template <>
+__device__ __forceinline__ void load8<float>(const float* __restrict__ p, double (&out)[kVec]) {
+  float4 a, b;
+  __builtin_memcpy(&a, p, 16);
+  __builtin_memcpy(&b, p + 4, 16);
+  out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
+  out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
+}
+
+// Round a double to the nearest bfloat16, ties to even, straight from double (no
+// intermediate float rounding).  The spacing at binary exponent e is 2^(max(e,-126)-7).
+__device__ __forceinline__ bf16_t to_bf16(double x) {
+  const uint64_t u = (uint64_t)__double_as_longlong(x);
+  int e = (int)((u >> 52) & 0x7ff) - 1023;
+  e = e < -126 ? -126 : e;
+  const double r = ldexp(rint(ldexp(x, 7 - e)), e - 7);
+  return (bf16_t)(__float_as_uint((float)r) >> 16);
+}
+__device__ __forceinline__ void store_token(bf16_t* p, double x) { *p = to_bf16(x); }
+__device__ __forceinline__ void store_token(float* p, double x) { *p = (float)x; }
+
+}  // namespace ficoco

@@ -1,0 +1,212 @@
+// Compress stage: self-preserving compression (Eq. 2) and the removal of the discarded
+// tokens (last lines of Algorithm 1/2).
+//
+// Two kernels.  `invert_edges` turns the per-source edge lists into per-target lists
+// (target j -> its sources in ascending order) with an integer counting sort in LDS; the
+// final order of every list is fixed by a sort on the source index, so the result does not
+// depend on scheduling.  `merge_rows` is then a pure pull: one wavefront per OUTPUT row
+// reads its own token plus its sources and writes
+//     (X_j + sum_i alpha_ij X_i) / (1 + sum_i alpha_ij)
+// accumulated in double precision in ascending i; rows without sources, and every token
+// outside the visual span, are copied bit for bit.  No floating-point atomics anywhere.
+#include "common.hpp"
+
+namespace ficoco {
+
+struct InvertArgs {
+  int n_keep, n_disc, k_max;
+  const int32_t* edge_cnt;
+  const int32_t* edge_tgt;
+  const double* edge_alpha;
+  int32_t* tgt_ptr;    // [B][n_keep+1]
+  int32_t* tgt_src;    // [B][n_disc*k_max]  discarded row index (position in S)
+  double* tgt_alpha;
+};
+
+__global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs a) {
+  extern __shared__ int lds_i[];
+  int* cnt = lds_i;                       // [n_keep+1] counts, then exclusive offsets
+  int* cursor = lds_i + (a.n_keep + 1);   // [n_keep]
+  int* part = cursor + a.n_keep;          // [2][nt] scan scratch
+  const int64_t b = blockIdx.x;
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int n = a.n_keep;
+  for (int j = tid; j <= n; j += nt) cnt[j] = 0;
+  __syncthreads();
+  for (int r = tid; r < a.n_disc; r += nt) {
+    const int c = a.edge_cnt[b * a.n_disc + r];
+    for (int e = 0; e < c; ++e) {
+      const int j = a.edge_tgt[(b * a.n_disc + r) * a.k_max + e];
+      if (j >= 0 && j < n) atomicAdd(&cnt[j], 1);
+    }
+  }
+  __syncthreads();
+  // exclusive scan of cnt[0..n): thread t owns a contiguous slice
+  const int per = (n + nt - 1) / nt;
+  const int lo = min(tid * per, n), hi = min(lo + per, n);
+  int local = 0;
+  for (int j = lo; j < hi; ++j) local += cnt[j];
+  int* cur = part;
+  int* nxt = part + nt;
+  cur[tid] = local;
+  __syncthreads();
+  for (int off = 1; off < nt; off <<= 1) {
+    nxt[tid] = cur[tid] + (tid >= off ? cur[tid - off] : 0);
+    __syncthreads();
+    int* t = cur; cur = nxt; nxt = t;
+  }
+  int run = cur[tid] - local;
+  const int total = cur[nt - 1];
+  for (int j = lo; j < hi; ++j) {
+    const int c = cnt[j];
+    cnt[j] = run;
+    cursor[j] = run;
+    run += c;
+  }
+  if (tid == 0) cnt[n] = total;
+  __syncthreads();
+  for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
+  const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+  for (int r = tid; r < a.n_disc; r += nt) {
+    const int c = a.edge_cnt[b * a.n_disc + r];
+    for (int e = 0; e < c; ++e) {
+      const int64_t src = (b * a.n_disc + r) * a.k_max + e;
+      const int j = a.edge_tgt[src];
+      if (j >= 0 && j < n) {
+        const int slot = atomicAdd(&cursor[j], 1);
+        a.tgt_src[ebase + slot] = r;
+        a.tgt_alpha[ebase + slot] = a.edge_alpha[src];
+      }
+    }
+  }
+  __syncthreads();
+  // fix the order inside every target's list: ascending source row (insertion sort)
+  for (int j = tid; j < n; j += nt) {
+    const int s0 = cnt[j], s1 = cnt[j + 1];
+    for (int x = s0 + 1; x < s1; ++x) {
+      const int r = a.tgt_src[ebase + x];
+      const double w = a.tgt_alpha[ebase + x];
+      int y = x - 1;
+      while (y >= s0 && a.tgt_src[ebase + y] > r) {
+        a.tgt_src[ebase + y + 1] = a.tgt_src[ebase + y];
+        a.tgt_alpha[ebase + y + 1] = a.tgt_alpha[ebase + y];
+        --y;
+      }
+      a.tgt_src[ebase + y + 1] = r;
+      a.tgt_alpha[ebase + y + 1] = w;
+    }
+  }
+}
+
+struct MergeArgs {
+  const void* X;
+  int64_t xsb, xsn;
+  void* X_out;
+  int D, n_tot, n_out, vis_begin, N, n_keep, n_disc, k_max;
+  const int32_t* S;
+  const int32_t* T;
+  const int32_t* tgt_ptr;
+  const int32_t* tgt_src;
+  const double* tgt_alpha;
+  const int32_t* pos;
+  int32_t* pos_out;
+};
+
+template <typename T>
+__device__ __forceinline__ void copy8(const T* src, T* dst) {
+  Pack8<T> v;
+  __builtin_memcpy(&v, src, sizeof(v));
+  __builtin_memcpy(dst, &v, sizeof(v));
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int r = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (r >= a.n_out) return;
+  const T* Xb = (const T*)a.X + b * a.xsb;
+  T* out = (T*)a.X_out + (b * a.n_out + r) * (int64_t)a.D;
+  int t, e0 = 0, e1 = 0;
+  if (r < a.vis_begin) {
+    t = r;
+  } else if (r < a.vis_begin + a.n_keep) {
+    const int j = r - a.vis_begin;
+    const int tok = a.T[b * a.n_keep + j];
+    t = a.vis_begin + tok;
+    if (a.n_disc > 0) {
+      e0 = a.tgt_ptr[b * (a.n_keep + 1) + j];
+      e1 = a.tgt_ptr[b * (a.n_keep + 1) + j + 1];
+    }
+    if (lane == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
+  } else {
+    t = r + a.n_disc;
+  }
+  const T* x = Xb + (int64_t)t * a.xsn;
+  const int Dv = a.D - a.D % kVec;
+  if (e0 == e1) {  // nothing merged into this row: exact copy
+    for (int d = lane * kVec; d < Dv; d += kWave * kVec) copy8<T>(x + d, out + d);
+    for (int d = Dv + lane; d < a.D; d += kWave) out[d] = x[d];
+    return;
+  }
+  const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+  double den = 1.0;
+  for (int e = e0; e < e1; ++e) den += a.tgt_alpha[ebase + e];
+  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+    double num[kVec];
+    load8<T>(x + d, num);
+    for (int e = e0; e < e1; ++e) {
+      const int i = a.S[b * a.n_disc + a.tgt_src[ebase + e]];
+      const double w = a.tgt_alpha[ebase + e];
+      double v[kVec];
+      load8<T>(Xb + (int64_t)(a.vis_begin + i) * a.xsn + d, v);
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) num[k] += w * v[k];
+    }
+    Pack8<T> o;
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[k] / den);
+    __builtin_memcpy(out + d, &o, sizeof(o));
+  }
+  for (int d = Dv + lane; d < a.D; d += kWave) {
+    double num = widen(x[d]);
+    for (int e = e0; e < e1; ++e) {
+      const int i = a.S[b * a.n_disc + a.tgt_src[ebase + e]];
+      num += a.tgt_alpha[ebase + e] * widen(Xb[(int64_t)(a.vis_begin + i) * a.xsn + d]);
+    }
+    store_token(out + d, num / den);
+  }
+}
+
+void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
+                     const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
+                     const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s) {
+  if (pl.n_disc > 0) {
+    InvertArgs a{};
+    a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.k_max = p.k_max;
+    a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha;
+    a.tgt_ptr = (int32_t*)(ws + pl.tgt_ptr);
+    a.tgt_src = (int32_t*)(ws + pl.tgt_src);
+    a.tgt_alpha = (double*)(ws + pl.tgt_alpha);
+    const size_t lds = ((size_t)2 * p.n_keep + 1 + 2 * kSelectThreads) * sizeof(int);
+    if (lds > 32768)
+      (void)hipFuncSetAttribute((const void*)invert_edges_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(invert_edges_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+  }
+  MergeArgs m{};
+  m.X = p.X; m.xsb = p.x_stride_b; m.xsn = p.x_stride_n; m.X_out = X_out;
+  m.D = p.D; m.n_tot = p.n_tot; m.n_out = pl.n_out; m.vis_begin = p.vis_begin; m.N = p.N;
+  m.n_keep = p.n_keep; m.n_disc = pl.n_disc; m.k_max = p.k_max;
+  m.S = discard_idx; m.T = keep_idx;
+  m.tgt_ptr = (const int32_t*)(ws + pl.tgt_ptr);
+  m.tgt_src = (const int32_t*)(ws + pl.tgt_src);
+  m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
+  m.pos = p.pos; m.pos_out = pos_out;
+  dim3 grid((pl.n_out + 3) / 4, p.B), block(256);
+  if (p.dtype == FICOCO_BF16)
+    hipLaunchKernelGGL(merge_rows_kernel<bf16_t>, grid, block, 0, s, m);
+  else
+    hipLaunchKernelGGL(merge_rows_kernel<float>, grid, block, 0, s, m);
+}
+
+}  // namespace ficoco

@@ -1,0 +1,155 @@
+// Feature-derived terms: row norms and bfloat16 unit rows (cosine correlation), the
+// equivalent-token term -cos(mu, F_i) of the appendix "Implementation of the Equivalent
+// Token", and the mean-cosine redundancy term (1/N) sum_j cos(F_i, F_j), evaluated as
+// u_i . mean_j u_j with u = F / |F|.  Double precision throughout; column sums use a fixed
+// two-level order (row chunks, then chunks) so results do not depend on scheduling.
+#include "common.hpp"
+
+namespace ficoco {
+
+struct FeatArgs {
+  const void* F;
+  int64_t sb, sn;
+  int N, Df, f_chunks, f_rows_per_wg;
+  double* norm;         // [B][N]
+  bf16_t* xhat;         // [B][N][Df] or null
+  double* colsum_part;  // [2][B][f_chunks][Df]  (0: unit rows, 1: raw rows)
+  double* colmean;      // [2][B][Df]
+  double* fterm_r;      // [B][N]
+  double* fterm_g;      // [B][N]
+  int want_sim, want_eq;
+  int B;
+};
+
+__device__ __forceinline__ double wave_sum_d(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (i >= a.N) return;
+  const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
+  const int Dv = a.Df - a.Df % kVec;
+  double ss = 0.0;
+  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+    double v[kVec];
+    load8<T>(x + d, v);
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) ss += v[k] * v[k];
+  }
+  for (int d = Dv + lane; d < a.Df; d += kWave) { const double v = widen(x[d]); ss += v * v; }
+  ss = wave_sum_d(ss);
+  const double nrm = sqrt(ss);
+  if (lane == 0) a.norm[b * a.N + i] = nrm;
+  if (a.xhat) {
+    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+    bf16_t* o = a.xhat + (b * a.N + i) * (int64_t)a.Df;
+    for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+      double v[kVec];
+      load8<T>(x + d, v);
+      Pack8<bf16_t> r;
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) r.v[k] = to_bf16(v[k] * inv);
+      __builtin_memcpy(o + d, &r, sizeof(r));
+    }
+    for (int d = Dv + lane; d < a.Df; d += kWave) o[d] = to_bf16(widen(x[d]) * inv);
+  }
+}
+
+// Partial column sums over a chunk of rows: slot 0 adds unit rows, slot 1 raw rows.
+template <typename T>
+__global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
+  const int chunk = blockIdx.x;
+  const int d = blockIdx.y * blockDim.x + threadIdx.x;
+  const int64_t b = blockIdx.z;
+  if (d >= a.Df) return;
+  const int r0 = chunk * a.f_rows_per_wg, r1 = min(r0 + a.f_rows_per_wg, a.N);
+  double su = 0.0, sr = 0.0;
+  for (int i = r0; i < r1; ++i) {
+    const double v = widen(((const T*)a.F)[b * a.sb + (int64_t)i * a.sn + d]);
+    const double nrm = a.norm[b * a.N + i];
+    su += nrm > 0.0 ? v / nrm : 0.0;
+    sr += v;
+  }
+  const int64_t slot = (int64_t)a.B * a.f_chunks * a.Df;
+  a.colsum_part[(b * a.f_chunks + chunk) * a.Df + d] = su;
+  a.colsum_part[slot + (b * a.f_chunks + chunk) * a.Df + d] = sr;
+}
+
+__global__ __launch_bounds__(256) void col_mean_kernel(FeatArgs a) {
+  const int d = blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = blockIdx.y;
+  if (d >= a.Df) return;
+  const int64_t slot = (int64_t)a.B * a.f_chunks * a.Df;
+  double su = 0.0, sr = 0.0;
+  for (int c = 0; c < a.f_chunks; ++c) {
+    su += a.colsum_part[(b * a.f_chunks + c) * a.Df + d];
+    sr += a.colsum_part[slot + (b * a.f_chunks + c) * a.Df + d];
+  }
+  a.colmean[b * a.Df + d] = su / (double)a.N;
+  a.colmean[(int64_t)a.B * a.Df + b * a.Df + d] = sr / (double)a.N;
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void feature_terms_kernel(FeatArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (i >= a.N) return;
+  const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
+  const double* ubar = a.colmean + b * a.Df;
+  const double* mu = a.colmean + (int64_t)a.B * a.Df + b * a.Df;
+  double du = 0.0, dm = 0.0, mm = 0.0;
+  for (int d = lane; d < a.Df; d += kWave) {
+    const double v = widen(x[d]);
+    du += v * ubar[d];
+    dm += v * mu[d];
+    mm += mu[d] * mu[d];
+  }
+  du = wave_sum_d(du); dm = wave_sum_d(dm); mm = wave_sum_d(mm);
+  if (lane == 0) {
+    const double nrm = a.norm[b * a.N + i];
+    if (a.want_sim) a.fterm_r[b * a.N + i] = nrm > 0.0 ? du / nrm : 0.0;
+    if (a.want_eq) {
+      const double mn = sqrt(mm);
+      a.fterm_g[b * a.N + i] = (nrm > 0.0 && mn > 0.0) ? -(dm / (mn * nrm)) : 0.0;
+    }
+  }
+}
+
+void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+  FeatArgs a{};
+  if (p.F) { a.F = p.F; a.sb = p.f_stride_b; a.sn = p.f_stride_n; }
+  else {
+    const size_t es = p.dtype == FICOCO_BF16 ? 2 : 4;
+    a.F = (const char*)p.X + (size_t)p.vis_begin * p.x_stride_n * es;
+    a.sb = p.x_stride_b; a.sn = p.x_stride_n;
+  }
+  a.N = p.N; a.Df = pl.Df; a.f_chunks = pl.f_chunks; a.f_rows_per_wg = pl.f_rows_per_wg; a.B = p.B;
+  a.norm = (double*)(ws + pl.inv_norm);
+  a.xhat = p.corr_src == FICOCO_C_COSINE ? (bf16_t*)(ws + pl.xhat) : nullptr;
+  a.colsum_part = (double*)(ws + pl.colsum_part);
+  a.colmean = (double*)(ws + pl.colmean);
+  a.fterm_r = (double*)(ws + pl.fterm);
+  a.fterm_g = (double*)(ws + pl.fterm2);
+  a.want_sim = p.red_src == FICOCO_R_SIM_MEAN;
+  a.want_eq = p.sem_src == FICOCO_G_EQ_TOKEN;
+  const bool bf16 = p.dtype == FICOCO_BF16;
+  dim3 rows((p.N + 3) / 4, p.B), block(256);
+  if (bf16) hipLaunchKernelGGL(row_norm_kernel<bf16_t>, rows, block, 0, s, a);
+  else hipLaunchKernelGGL(row_norm_kernel<float>, rows, block, 0, s, a);
+  if (!a.want_sim && !a.want_eq) return;
+  dim3 cgrid(pl.f_chunks, (pl.Df + 255) / 256, p.B);
+  if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);
+  else hipLaunchKernelGGL(col_sum_kernel<float>, cgrid, block, 0, s, a);
+  hipLaunchKernelGGL(col_mean_kernel, dim3((pl.Df + 255) / 256, p.B), block, 0, s, a);
+  if (bf16) hipLaunchKernelGGL(feature_terms_kernel<bf16_t>, rows, block, 0, s, a);
+  else hipLaunchKernelGGL(feature_terms_kernel<float>, rows, block, 0, s, a);
+}
+
+}  // namespace ficoco

@@ -3,7 +3,7 @@
 These generators serve the tests, the smoke check and the benchmark.  They hold none of
 the method's arithmetic: only random draws, a softmax to make row-stochastic attention
 maps, and the cast to the storage type.  Everything is generated on the CPU with a seeded
-torch generator (so the CPU oracle and the GPU library read the same bits) and returned
+torch generator (so the CPU checker and the GPU library read the same bits) and returned
 as CPU tensors; the caller moves them to the device.
 
 Workloads (stand-ins for the paper's models, Sec. "Implementation Details" / "Backbone
@@ -28,7 +28,7 @@ def _cast(t, dtype):
 
 
 def to_numpy(t):
-    """CPU/GPU tensor -> numpy array the oracle can widen: float32 as is, bfloat16 as its
+    """CPU/GPU tensor -> numpy array a CPU checker can widen: float32 as is, bfloat16 as its
     uint16 bit patterns."""
     t = t.detach().cpu().contiguous()
     if t.dtype == torch.bfloat16:

@@ -139,6 +139,15 @@ const char *ficoco_version(void);
 int ficoco_workspace_bytes(const ficoco_problem *p, size_t *out_bytes);
 
 /*
+ * Attention reduction alone (the first term of Eq. 1 / Eq. 3, the [CLS] / text terms and
+ * the head-mean maps of Algorithm 1/2 stage 2): the one pass over the [B][H][q][k] maps,
+ * leaving per-column partial sums and the head-mean maps in the workspace.  ficoco_score
+ * runs this itself; the separate entry point exists so the dominant, bandwidth-bound pass
+ * can be timed and profiled on its own.
+ */
+int ficoco_reduce(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes, void *stream);
+
+/*
  * Filter, part 1 (Eq. 1 / Eq. 3 and the local penalty, Sec. "Redundancy-based Token
  * Discard"; Sec. "Task-Aware Improvements for FiCoCo-L"): reduces the attention maps /
  * features once and writes the redundancy score of every visual token.  Also leaves the

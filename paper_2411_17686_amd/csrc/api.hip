@@ -236,6 +236,14 @@ int ficoco_workspace_bytes(const ficoco_problem* p, size_t* out_bytes) {
   return FICOCO_OK;
 }
 
+int ficoco_reduce(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_reduce");
+  if (rc != FICOCO_OK) return rc;
+  launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
+  return finish(ctx, "ficoco_reduce");
+}
+
 int ficoco_score(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, double* scores,
                  void* stream) {
   Plan pl;

@@ -34,7 +34,7 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   for (int j = tid; j <= n; j += nt) cnt[j] = 0;
   __syncthreads();
   for (int r = tid; r < a.n_disc; r += nt) {
-    const int c = a.edge_cnt[b * a.n_disc + r];
+    const int c = min(a.edge_cnt[b * a.n_disc + r], a.k_max);
     for (int e = 0; e < c; ++e) {
       const int j = a.edge_tgt[(b * a.n_disc + r) * a.k_max + e];
       if (j >= 0 && j < n) atomicAdd(&cnt[j], 1);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
   for (int r = tid; r < a.n_disc; r += nt) {
-    const int c = a.edge_cnt[b * a.n_disc + r];
+    const int c = min(a.edge_cnt[b * a.n_disc + r], a.k_max);
     for (int e = 0; e < c; ++e) {
       const int64_t src = (b * a.n_disc + r) * a.k_max + e;
       const int j = a.edge_tgt[src];
@@ -132,7 +132,8 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
     t = r;
   } else if (r < a.vis_begin + a.n_keep) {
     const int j = r - a.vis_begin;
-    const int tok = a.T[b * a.n_keep + j];
+    int tok = a.T[b * a.n_keep + j];
+    tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
     t = a.vis_begin + tok;
     if (a.n_disc > 0) {
       e0 = a.tgt_ptr[b * (a.n_keep + 1) + j];
@@ -156,7 +157,7 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
     double num[kVec];
     load8<T>(x + d, num);
     for (int e = e0; e < e1; ++e) {
-      const int i = a.S[b * a.n_disc + a.tgt_src[ebase + e]];
+      const int i = min(max(a.S[b * a.n_disc + a.tgt_src[ebase + e]], 0), a.N - 1);
       const double w = a.tgt_alpha[ebase + e];
       double v[kVec];
       load8<T>(Xb + (int64_t)(a.vis_begin + i) * a.xsn + d, v);
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   for (int d = Dv + lane; d < a.D; d += kWave) {
     double num = widen(x[d]);
     for (int e = e0; e < e1; ++e) {
-      const int i = a.S[b * a.n_disc + a.tgt_src[ebase + e]];
+      const int i = min(max(a.S[b * a.n_disc + a.tgt_src[ebase + e]], 0), a.N - 1);
       num += a.tgt_alpha[ebase + e] * widen(Xb[(int64_t)(a.vis_begin + i) * a.xsn + d]);
     }
     store_token(out + d, num / den);

@@ -120,7 +120,11 @@ __global__ __launch_bounds__(256) void corr_fill_rows_kernel(CorrArgs a) {
   if (row >= a.n_disc) return;
   const int i = a.S[b * a.n_disc + row];
   double* dst = a.rowbuf + (b * a.n_disc + row) * a.n_keep;
-  for (int jj = lane; jj < a.n_keep; jj += kWave) dst[jj] = corr_value(a, b, i, a.T[b * a.n_keep + jj]);
+  for (int jj = lane; jj < a.n_keep; jj += kWave) {
+    const int j = a.T[b * a.n_keep + jj];
+    const bool ok = (unsigned)i < (unsigned)a.N && (unsigned)j < (unsigned)a.N;  // index sets are device data
+    dst[jj] = ok ? corr_value(a, b, i, j) : -__builtin_huge_val();
+  }
 }
 
 __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
@@ -131,6 +135,10 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
   const int n = a.n_keep;
   const int i = a.S[b * a.n_disc + row];
   const int32_t* T = a.T + b * n;
+  if ((unsigned)i >= (unsigned)a.N) {  // index sets are device data: never index with a bad one
+    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    return;
+  }
   const double* rowv = a.dense ? a.rowbuf + (b * a.n_disc + row) * n : nullptr;
   const double NEG = -__builtin_huge_val();
 
@@ -144,7 +152,8 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
 #pragma unroll
     for (int k = 0; k < kSelMax; ++k) top[k] = NEG;
     for (int jj = lane; jj < n; jj += kWave) {
-      double c = corr_value(a, b, i, T[jj]);
+      const int j = T[jj];
+      double c = (unsigned)j < (unsigned)a.N ? corr_value(a, b, i, j) : NEG;
       if (c > top[kSelMax - 1]) {
 #pragma unroll
         for (int k = 0; k < kSelMax; ++k) {
@@ -180,7 +189,11 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
   const int64_t ebase = (b * a.n_disc + row) * a.k_max;
   for (int base = 0; base < n; base += kWave) {
     const int jj = base + lane;
-    const double c = jj < n ? (a.dense ? rowv[jj] : corr_value(a, b, i, T[jj])) : NEG;
+    double c = NEG;
+    if (jj < n) {
+      if (a.dense) c = rowv[jj];
+      else { const int j = T[jj]; if ((unsigned)j < (unsigned)a.N) c = corr_value(a, b, i, j); }
+    }
     unsigned long long hit = __ballot(jj < n && c >= tau);
     while (hit) {
       const int l = __ffsll(hit) - 1;

@@ -107,25 +107,31 @@ struct FilterArgs {
 
 __global__ __launch_bounds__(kSelectThreads) void filter_kernel(FilterArgs a) {
   extern __shared__ double lds_d[];
-  double* s = lds_d;                        // [N]
+  uint64_t* keys = (uint64_t*)lds_d;        // [N]
   int* scan = (int*)(lds_d + a.N);          // [2][nt]
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = a.N;
-  for (int i = tid; i < N; i += nt) s[i] = a.scores[(int64_t)b * N + i];
+  for (int i = tid; i < N; i += nt) {
+    const uint64_t u = (uint64_t)__double_as_longlong(a.scores[(int64_t)b * N + i] + 0.0);
+    keys[i] = (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
+  }
   __syncthreads();
 
   // Thread t owns the contiguous tokens [t*per, (t+1)*per).  rank_i = number of tokens
-  // that come before i in (score descending, index ascending) order.
+  // that come before i in (score descending, index ascending) order.  The comparison runs
+  // on order-preserving integer keys of the doubles (-0 folded into +0), which is the same
+  // order for finite scores and stays a strict total order whatever the bits are, so
+  // exactly n_disc tokens are flagged even for non-finite input.
   const int per = (N + nt - 1) / nt;
   const int lo = min(tid * per, N), hi = min(lo + per, N);
   int n_dis = 0;
   uint32_t dis_mask = 0;  // per <= 12 tokens per thread (N <= kMaxSelectN)
   for (int i = lo; i < hi; ++i) {
-    const double si = s[i];
+    const uint64_t ki = keys[i];
     int rank = 0;
     for (int j = 0; j < N; ++j) {
-      const double sj = s[j];
-      rank += (sj > si || (sj == si && j < i)) ? 1 : 0;
+      const uint64_t kj = keys[j];
+      rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
     }
     if (rank < a.n_disc) { dis_mask |= 1u << (i - lo); ++n_dis; }
   }

@@ -20,7 +20,7 @@ G_CLS_ATTN, G_TEXT_ATTN, G_VECTOR, G_EQ_TOKEN = 0, 1, 2, 3
 C_ATTN, C_COSINE = 0, 1
 
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
-           "ficoco_workspace_bytes", "ficoco_score", "ficoco_filter", "ficoco_correlate",
+           "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
            "ficoco_compress", "ficoco_v_step", "ficoco_l_step"]
 
 
@@ -68,6 +68,7 @@ def lib():
         L.ficoco_last_error.restype = C.c_char_p
         L.ficoco_version.restype = C.c_char_p
         L.ficoco_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
+        L.ficoco_reduce.argtypes = [vp, pp, vp, C.c_size_t, vp]
         L.ficoco_score.argtypes = [vp, pp, vp, C.c_size_t, f64p, vp]
         L.ficoco_filter.argtypes = [vp, pp, vp, C.c_size_t, f64p, i32p, i32p, vp]
         L.ficoco_correlate.argtypes = [vp, pp, vp, C.c_size_t, i32p, i32p, i32p, i32p, f64p, i32p, vp]
@@ -207,6 +208,11 @@ class Buffers:
 
 def _ws(buf):
     return C.c_void_p(buf.ws_ptr), C.c_size_t(buf.ws_bytes)
+
+
+def ficoco_reduce(ctx, p, buf):
+    ws, n = _ws(buf)
+    ctx.check(lib().ficoco_reduce(ctx._h, C.byref(p), ws, n, ctx.stream()))
 
 
 def ficoco_score(ctx, p, buf):

@@ -74,15 +74,16 @@ def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src
     X = cfg["X"] if X is None else X
     Xd, Ad = dev(X), dev(A)
     posd = dev(pos)
+    rv = dev(cfg.get("recv_vec")) if red_src == fc.R_VECTOR else None
+    sv = dev(cfg.get("sem_vec")) if sem_src == fc.G_VECTOR else None
+    Fd = dev(F)
     p = fc.make_problem(
         Xd, variant=fc.VARIANT_V, vis_begin=cfg["vis_begin"], N=Xd.shape[1] - cfg["vis_begin"],
         n_keep=cfg["n_keep"] if n_keep is None else n_keep, A=Ad, cls_index=cfg["cls_index"],
-        recv_vec=dev(cfg.get("recv_vec")) if red_src == fc.R_VECTOR else None,
-        sem_vec=dev(cfg.get("sem_vec")) if sem_src == fc.G_VECTOR else None,
-        F=dev(F), pos=posd, grid=cfg["grid"], window=cfg["window"] if window is None else window,
+        recv_vec=rv, sem_vec=sv, F=Fd, pos=posd, grid=cfg["grid"], window=cfg["window"] if window is None else window,
         penalty_coef=cfg["coef"], w_score=cfg["lam"], eps=cfg["eps"] if eps is None else eps,
         red_src=red_src, sem_src=sem_src, corr_src=corr_src, k_max=k_max, H=cfg["H"])
-    keep_alive = (Xd, Ad, posd)
+    keep_alive = (Xd, Ad, posd, rv, sv, Fd)   # the problem holds raw pointers only
     buf = fc.Buffers(p, "cuda", Xd.dtype)
     if staged:
         fc.ficoco_score(ctx, p, buf)

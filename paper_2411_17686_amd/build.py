@@ -18,32 +18,35 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]
 
 
-def build(verbose=True):
+def build(verbose=True, out=LIB, defines=(), tag=""):
+    """Compile every source and link `out`.  `defines` / `tag` build a tuning variant
+    elsewhere without touching the product library."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     objs = []
     procs = []
     os.makedirs(os.path.join(HERE, "_build"), exist_ok=True)
     for src in SOURCES:
-        obj = os.path.join(HERE, "_build", src.replace(".hip", ".o"))
-        cmd = [hipcc, "-c"] + [f for f in FLAGS if f != "-shared"] + ["-o", obj, os.path.join(CSRC, src)]
+        obj = os.path.join(HERE, "_build", src.replace(".hip", tag + ".o"))
+        cmd = [hipcc, "-c"] + [f for f in FLAGS if f != "-shared"] + ["-D" + d for d in defines] \
+            + ["-o", obj, os.path.join(CSRC, src)]
         procs.append((src, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
         objs.append(obj)
     failed = False
     for src, pr in procs:
-        out, _ = pr.communicate()
-        out = "\n".join(l for l in out.splitlines() if "packed-fp32-ops" not in l and l.strip())
+        log, _ = pr.communicate()
+        log = "\n".join(l for l in log.splitlines() if "packed-fp32-ops" not in l and l.strip())
         if pr.returncode != 0:
             failed = True
-            sys.stderr.write("hipcc failed on %s:\n%s\n" % (src, out))
-        elif verbose and out:
-            sys.stderr.write(out + "\n")
+            sys.stderr.write("hipcc failed on %s:\n%s\n" % (src, log))
+        elif verbose and log:
+            sys.stderr.write(log + "\n")
     if failed:
         raise RuntimeError("hipcc failed")
-    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", LIB] + objs
+    cmd = [hipcc, "-shared", "-fPIC", "--offload-arch=gfx950", "-o", out] + objs
     subprocess.check_call(cmd)
     if verbose:
-        print("built", LIB)
-    return LIB
+        print("built", out)
+    return out
 
 
 if __name__ == "__main__":

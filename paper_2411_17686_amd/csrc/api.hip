@@ -14,6 +14,11 @@ struct ficoco_ctx {
 
 namespace ficoco {
 
+#ifndef FICOCO_WG_TARGET
+#define FICOCO_WG_TARGET 1024
+#endif
+constexpr int64_t kWgTarget = FICOCO_WG_TARGET;
+
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
 int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
@@ -86,7 +91,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.row_lanes = kReduceThreads / pl.strip_groups;
   if (pl.row_lanes < 1) pl.row_lanes = 1;
   auto rows_per_wg = [&](int rows) {
-    int64_t want = ((int64_t)p.B * pl.col_strips * rows + 1023) / 1024;  // aim at ~1024 workgroups
+    int64_t want = ((int64_t)p.B * pl.col_strips * rows + kWgTarget - 1) / kWgTarget;  // aim at ~kWgTarget workgroups
     if (want < 1) want = 1;
     int r = (int)((want + pl.row_lanes - 1) / pl.row_lanes) * pl.row_lanes;
     return r;
@@ -191,9 +196,8 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   char* w = (char*)ws;
   launch_attn_reduce(p, pl, w, s);
   if (pl.need_features) launch_features(p, pl, w, s);
-  launch_score(p, pl, w, scores, s);
-  launch_filter(p, pl, w, scores, discard_idx, keep_idx, s);
-  launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, s);
+  launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
+  launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true, s);
   launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
   return finish(ctx, fn);
 }
@@ -276,7 +280,7 @@ int ficoco_correlate(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t 
   if (!keep_idx || !overflow || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_correlate", "a pointer is NULL");
   launch_correlate(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow,
-                   (hipStream_t)stream);
+                   false, (hipStream_t)stream);
   return finish(ctx, "ficoco_correlate");
 }
 

@@ -16,6 +16,11 @@
 
 namespace ficoco {
 
+#ifndef FICOCO_HEAD_BATCH
+#define FICOCO_HEAD_BATCH 8
+#endif
+constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
+
 struct AttnArgs {
   const void* A;
   int64_t sb, sh, sq;
@@ -62,12 +67,16 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
 #pragma unroll
       for (int k = 0; k < kVec; ++k) p[k] = 0.0;
       if (ncol == kVec) {
-#pragma unroll 8
-        for (int h = 0; h < a.H; ++h) {
-          double v[kVec];
-          load8<T>(base + (int64_t)h * a.sh, v);
+        // kHeadBatch independent 16-byte loads are issued before the first add; the adds
+        // then run in head order.
+        for (int h0 = 0; h0 < a.H; h0 += kHeadBatch) {
+          Raw8<T> raw[kHeadBatch];
 #pragma unroll
-          for (int k = 0; k < kVec; ++k) p[k] += v[k];
+          for (int u = 0; u < kHeadBatch; ++u)
+            if (h0 + u < a.H) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
+#pragma unroll
+          for (int u = 0; u < kHeadBatch; ++u)
+            if (h0 + u < a.H) add_raw(raw[u], p);
         }
       } else {
         for (int h = 0; h < a.H; ++h)

@@ -61,9 +61,12 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s);
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s);
+void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
+                   bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
+                   hipStream_t s);
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, hipStream_t s);
+                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero, hipStream_t s);
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s);
@@ -77,6 +80,32 @@ __device__ __forceinline__ double widen(bf16_t x) {
   return (double)__uint_as_float(((uint32_t)x) << 16);
 }
 __device__ __forceinline__ double widen(float x) { return (double)x; }
+
+// Raw bits of 8 consecutive elements, loaded from an address that is only element aligned
+// (kept unconverted so that many loads can be in flight before the first use).
+template <typename T> struct Raw8;
+template <> struct Raw8<bf16_t> { uint4 a; };
+template <> struct Raw8<float> { float4 a, b; };
+
+__device__ __forceinline__ void load_raw(const bf16_t* __restrict__ p, Raw8<bf16_t>& r) {
+  __builtin_memcpy(&r.a, p, 16);
+}
+__device__ __forceinline__ void load_raw(const float* __restrict__ p, Raw8<float>& r) {
+  __builtin_memcpy(&r.a, p, 16);
+  __builtin_memcpy(&r.b, p + 4, 16);
+}
+__device__ __forceinline__ void add_raw(const Raw8<bf16_t>& r, double (&acc)[kVec]) {
+  const uint32_t w[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    acc[2 * j] += (double)__uint_as_float(w[j] << 16);
+    acc[2 * j + 1] += (double)__uint_as_float(w[j] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void add_raw(const Raw8<float>& r, double (&acc)[kVec]) {
+  acc[0] += r.a.x; acc[1] += r.a.y; acc[2] += r.a.z; acc[3] += r.a.w;
+  acc[4] += r.b.x; acc[5] += r.b.y; acc[6] += r.b.z; acc[7] += r.b.w;
+}
 
 // 8 consecutive elements from an address that is only element aligned.
 template <typename T>

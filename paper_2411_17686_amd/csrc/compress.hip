@@ -108,6 +108,9 @@ struct MergeArgs {
   const int32_t* tgt_ptr;
   const int32_t* tgt_src;
   const double* tgt_alpha;
+  const int32_t* edge_cnt;
+  const int32_t* edge_tgt;
+  const double* edge_alpha;
   const int32_t* pos;
   int32_t* pos_out;
 };
@@ -119,7 +122,13 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-template <typename T>
+constexpr int kMergeSlice = 2;   // 8-element vectors per lane per pass over the feature axis
+
+// One wavefront per output row.  MATCH = false: the sources of a preserved token come from
+// the inverted edge lists.  MATCH = true (few discarded tokens): no inversion kernel; the
+// wavefront scans the per-source edge lists itself, 64 discarded rows at a time, and takes
+// the rows that name its target -- in ascending row order, so the sum order is the same.
+template <typename T, bool MATCH>
 __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   const int lane = threadIdx.x % kWave;
   const int r = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -127,15 +136,15 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   if (r >= a.n_out) return;
   const T* Xb = (const T*)a.X + b * a.xsb;
   T* out = (T*)a.X_out + (b * a.n_out + r) * (int64_t)a.D;
-  int t, e0 = 0, e1 = 0;
+  int t, j = -1, e0 = 0, e1 = 0;
   if (r < a.vis_begin) {
     t = r;
   } else if (r < a.vis_begin + a.n_keep) {
-    const int j = r - a.vis_begin;
+    j = r - a.vis_begin;
     int tok = a.T[b * a.n_keep + j];
     tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
     t = a.vis_begin + tok;
-    if (a.n_disc > 0) {
+    if (!MATCH && a.n_disc > 0) {
       e0 = a.tgt_ptr[b * (a.n_keep + 1) + j];
       e1 = a.tgt_ptr[b * (a.n_keep + 1) + j + 1];
     }
@@ -145,44 +154,100 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   }
   const T* x = Xb + (int64_t)t * a.xsn;
   const int Dv = a.D - a.D % kVec;
-  if (e0 == e1) {  // nothing merged into this row: exact copy
+  const bool merged_row = j >= 0 && a.n_disc > 0;
+  if (!merged_row || (!MATCH && e0 == e1)) {  // nothing merged into this row: exact copy
     for (int d = lane * kVec; d < Dv; d += kWave * kVec) copy8<T>(x + d, out + d);
     for (int d = Dv + lane; d < a.D; d += kWave) out[d] = x[d];
     return;
   }
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
-  double den = 1.0;
-  for (int e = e0; e < e1; ++e) den += a.tgt_alpha[ebase + e];
-  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-    double num[kVec];
-    load8<T>(x + d, num);
-    for (int e = e0; e < e1; ++e) {
-      const int i = min(max(a.S[b * a.n_disc + a.tgt_src[ebase + e]], 0), a.N - 1);
-      const double w = a.tgt_alpha[ebase + e];
-      double v[kVec];
-      load8<T>(Xb + (int64_t)(a.vis_begin + i) * a.xsn + d, v);
+  constexpr int kSpan = kWave * kVec * kMergeSlice;           // features per pass
+  for (int d0 = 0; d0 < a.D; d0 += kSpan) {
+    double num[kMergeSlice][kVec];
+    bool full[kMergeSlice];
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) num[k] += w * v[k];
+    for (int u = 0; u < kMergeSlice; ++u) {
+      const int d = d0 + (u * kWave + lane) * kVec;
+      full[u] = d + kVec <= a.D;
+      if (full[u]) load8<T>(x + d, num[u]);
+      else
+        for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
     }
-    Pack8<T> o;
+    double den = 1.0;
+    bool any = false;
+    auto add_source = [&](int i, double w) {
+      i = min(max(i, 0), a.N - 1);
+      const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+      den += w;
+      any = true;
 #pragma unroll
-    for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[k] / den);
-    __builtin_memcpy(out + d, &o, sizeof(o));
-  }
-  for (int d = Dv + lane; d < a.D; d += kWave) {
-    double num = widen(x[d]);
-    for (int e = e0; e < e1; ++e) {
-      const int i = min(max(a.S[b * a.n_disc + a.tgt_src[ebase + e]], 0), a.N - 1);
-      num += a.tgt_alpha[ebase + e] * widen(Xb[(int64_t)(a.vis_begin + i) * a.xsn + d]);
+      for (int u = 0; u < kMergeSlice; ++u) {
+        const int d = d0 + (u * kWave + lane) * kVec;
+        if (full[u]) {
+          double v[kVec];
+          load8<T>(xs + d, v);
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) num[u][k] += w * v[k];
+        } else {
+          for (int k = 0; k < kVec; ++k)
+            if (d + k < a.D) num[u][k] += w * widen(xs[d + k]);
+        }
+      }
+    };
+    if (MATCH) {
+      for (int base = 0; base < a.n_disc; base += kWave) {
+        const int row = base + lane;
+        double w = 0.0;
+        int src = 0;
+        bool hit = false;
+        if (row < a.n_disc) {
+          const int cnt = min(a.edge_cnt[b * a.n_disc + row], a.k_max);
+          src = a.S[b * a.n_disc + row];
+          for (int e = 0; e < cnt; ++e)
+            if (a.edge_tgt[(b * a.n_disc + row) * a.k_max + e] == j) {
+              hit = true;
+              w = a.edge_alpha[(b * a.n_disc + row) * a.k_max + e];
+            }
+        }
+        unsigned long long m = __ballot(hit);
+        while (m) {
+          const int l = __ffsll(m) - 1;
+          m &= m - 1;
+          add_source(__shfl(src, l, kWave), __shfl(w, l, kWave));
+        }
+      }
+    } else {
+      for (int e = e0; e < e1; ++e)
+        add_source(a.S[b * a.n_disc + a.tgt_src[ebase + e]], a.tgt_alpha[ebase + e]);
     }
-    store_token(out + d, num / den);
+#pragma unroll
+    for (int u = 0; u < kMergeSlice; ++u) {
+      const int d = d0 + (u * kWave + lane) * kVec;
+      if (!any) {   // no source names this target: exact copy
+        if (full[u]) copy8<T>(x + d, out + d);
+        else
+          for (int k = 0; k < kVec; ++k)
+            if (d + k < a.D) out[d + k] = x[d + k];
+      } else if (full[u]) {
+        Pack8<T> o;
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[u][k] / den);
+        __builtin_memcpy(out + d, &o, sizeof(o));
+      } else {
+        for (int k = 0; k < kVec; ++k)
+          if (d + k < a.D) store_token(out + d + k, num[u][k] / den);
+      }
+    }
   }
 }
+
+constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s) {
-  if (pl.n_disc > 0) {
+  const bool match = pl.n_disc <= kMatchMaxRows;
+  if (pl.n_disc > 0 && !match) {
     InvertArgs a{};
     a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.k_max = p.k_max;
     a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha;
@@ -202,12 +267,17 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.tgt_ptr = (const int32_t*)(ws + pl.tgt_ptr);
   m.tgt_src = (const int32_t*)(ws + pl.tgt_src);
   m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
+  m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
   m.pos = p.pos; m.pos_out = pos_out;
   dim3 grid((pl.n_out + 3) / 4, p.B), block(256);
-  if (p.dtype == FICOCO_BF16)
-    hipLaunchKernelGGL(merge_rows_kernel<bf16_t>, grid, block, 0, s, m);
-  else
-    hipLaunchKernelGGL(merge_rows_kernel<float>, grid, block, 0, s, m);
+  const bool bf16 = p.dtype == FICOCO_BF16;
+  if (match) {
+    if (bf16) hipLaunchKernelGGL((merge_rows_kernel<bf16_t, true>), grid, block, 0, s, m);
+    else hipLaunchKernelGGL((merge_rows_kernel<float, true>), grid, block, 0, s, m);
+  } else {
+    if (bf16) hipLaunchKernelGGL((merge_rows_kernel<bf16_t, false>), grid, block, 0, s, m);
+    else hipLaunchKernelGGL((merge_rows_kernel<float, false>), grid, block, 0, s, m);
+  }
 }
 
 }  // namespace ficoco

@@ -225,6 +225,125 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
   }
 }
 
+
+// ---- FiCoCo-V attention correlation, tiled ----------------------------------------------------
+// The generic kernel above gathers one column of the row-major head-mean map per wavefront
+// (64 different rows per load).  For the plain attention correlation of Algorithm 1 this
+// tile kernel is used instead: a workgroup owns kTileCols discarded columns, thread
+// (c, jl) scans rows T[jl], T[jl + kTileLanes], ... of column S[c], so the threads of one
+// row read neighbouring columns of the same row.  Pass 1 keeps the m largest values per
+// thread, LDS merges them per column into v[f], v[f+1] and tau; pass 2 re-reads the (cache
+// resident) column and collects the rows at or above tau.
+constexpr int kTileCols = 8;
+constexpr int kTileLanes = 32;
+constexpr int kHitCap = 64;
+
+__global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(CorrArgs a) {
+  __shared__ float cand[kTileCols][kTileLanes][kSelMax];
+  __shared__ double tau_s[kTileCols];
+  __shared__ int hit_cnt[kTileCols];
+  __shared__ int hit_j[kTileCols][kHitCap];
+  __shared__ float hit_v[kTileCols][kHitCap];
+  const int tid = threadIdx.x;
+  const int c = tid % kTileCols, jl = tid / kTileCols;
+  const int64_t b = blockIdx.y;
+  const int row = blockIdx.x * kTileCols + c;
+  const int n = a.n_keep;
+  const int32_t* T = a.T + b * n;
+  int i = row < a.n_disc ? a.S[b * a.n_disc + row] : -1;
+  const bool valid = (unsigned)i < (unsigned)a.N;   // index sets are device data
+  if (!valid) i = 0;
+  const float* col = a.abar + b * a.N * (int64_t)a.N + i;
+  const float NEGF = -__builtin_huge_valf();
+
+  float top[kSelMax];
+#pragma unroll
+  for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
+  if (valid) {
+    for (int jj = jl; jj < n; jj += kTileLanes) {
+      const int j = T[jj];
+      float v = (unsigned)j < (unsigned)a.N ? col[(int64_t)j * a.N] : NEGF;
+      if (v > top[kSelMax - 1]) {
+#pragma unroll
+        for (int k = 0; k < kSelMax; ++k) {
+          const bool sw = v > top[k];
+          const float t = top[k];
+          top[k] = sw ? v : t;
+          v = sw ? t : v;
+        }
+      }
+    }
+  }
+#pragma unroll
+  for (int k = 0; k < kSelMax; ++k) cand[c][jl][k] = top[k];
+  __syncthreads();
+  if (jl == 0) {
+    float best[kSelMax];
+#pragma unroll
+    for (int k = 0; k < kSelMax; ++k) best[k] = NEGF;
+    for (int l = 0; l < kTileLanes; ++l)
+      for (int q = 0; q < a.sel_m; ++q) {
+        float v = cand[c][l][q];
+        if (v > best[kSelMax - 1]) {
+#pragma unroll
+          for (int k = 0; k < kSelMax; ++k) {
+            const bool sw = v > best[k];
+            const float t = best[k];
+            best[k] = sw ? v : t;
+            v = sw ? t : v;
+          }
+        }
+      }
+    float vf = NEGF, vf1 = NEGF;     // m-th and (m-1)-th largest
+#pragma unroll
+    for (int k = 0; k < kSelMax; ++k) {
+      if (k == a.sel_m - 1) vf = best[k];
+      if (k == a.sel_m - 2) vf1 = best[k];
+    }
+    if (a.sel_m == 1) vf1 = vf;
+    tau_s[c] = threshold_of((double)vf, (double)vf1, a.sel_g);
+    hit_cnt[c] = 0;
+  }
+  __syncthreads();
+  if (valid) {
+    const double tau = tau_s[c];
+    for (int jj = jl; jj < n; jj += kTileLanes) {
+      const int j = T[jj];
+      if ((unsigned)j >= (unsigned)a.N) continue;
+      const float v = col[(int64_t)j * a.N];
+      if ((double)v >= tau) {
+        const int slot = atomicAdd(&hit_cnt[c], 1);
+        if (slot < kHitCap) { hit_j[c][slot] = jj; hit_v[c][slot] = v; }
+      }
+    }
+  }
+  __syncthreads();
+  if (jl == 0 && row < a.n_disc) {
+    const int cnt = valid ? hit_cnt[c] : 0;
+    const int have = cnt < kHitCap ? cnt : kHitCap;
+    for (int x = 1; x < have; ++x) {          // ascending target slot (arrival order is arbitrary)
+      const int jx = hit_j[c][x];
+      const float vx = hit_v[c][x];
+      int y = x - 1;
+      while (y >= 0 && hit_j[c][y] > jx) { hit_j[c][y + 1] = hit_j[c][y]; hit_v[c][y + 1] = hit_v[c][y]; --y; }
+      hit_j[c][y + 1] = jx;
+      hit_v[c][y + 1] = vx;
+    }
+    double denom = 0.0;
+    for (int x = 0; x < have; ++x) denom += (double)hit_v[c][x];
+    const bool live = denom > 0.0;
+    const int stored = have < a.k_max ? have : a.k_max;
+    const int64_t ebase = (b * a.n_disc + row) * a.k_max;
+    if (live)
+      for (int x = 0; x < stored; ++x) {
+        a.edge_tgt[ebase + x] = hit_j[c][x];
+        a.edge_alpha[ebase + x] = (double)hit_v[c][x] / denom;
+      }
+    a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
+    if (live && cnt > a.k_max) a.overflow[b] = 1;
+  }
+}
+
 __global__ void zero_i32_kernel(int32_t* p, int n) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
   if (i < n) p[i] = 0;
@@ -232,8 +351,9 @@ __global__ void zero_i32_kernel(int32_t* p, int n) {
 
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, hipStream_t s) {
-  hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
+                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero, hipStream_t s) {
+  if (!overflow_is_zero)
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
   if (pl.n_disc == 0) return;
   CorrArgs a{};
   a.N = p.N; a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.M = p.M; a.k_max = p.k_max; a.Df = pl.Df;
@@ -249,6 +369,11 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.dense = pl.dense_rows ? 1 : 0;
   a.rowbuf = (double*)(ws + pl.rowbuf);
   a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha; a.overflow = overflow;
+  if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
+    dim3 tgrid((pl.n_disc + kTileCols - 1) / kTileCols, p.B);
+    hipLaunchKernelGGL(corr_attn_tile_kernel, tgrid, dim3(kTileCols * kTileLanes), 0, s, a);
+    return;
+  }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
   if (pl.dense_rows) hipLaunchKernelGGL(corr_fill_rows_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(corr_rows_kernel, grid, block, 0, s, a);

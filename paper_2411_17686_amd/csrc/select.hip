@@ -1,14 +1,24 @@
 // Filter stage: redundancy score (Eq. 1 / Eq. 3), local penalty (Sec. "Redundancy-based
 // Token Discard") and the top-K split into source set S and target set T (Algorithm 1/2,
 // stage 1).  One workgroup per image; the per-image state lives in LDS.  All comparisons
-// are on doubles; ties go to the lower token index (filter) / lower grid cell (penalty).
+// are on doubles (through order-preserving 64-bit keys); ties go to the lower token index
+// (filter) / lower grid cell (penalty).
+//
+// The same kernel serves the staged entry points (score only / filter only) and the fused
+// step (both phases in one launch: every dependent launch costs several microseconds).
+//
+// The top-K is a radix select: 8 passes over the key bytes, most significant first, find the
+// key K* of the N^S-th largest token; tokens above K* are discarded, tokens equal to K* are
+// discarded in index order until N^S is reached.  Integer LDS atomics only build histograms
+// (their result does not depend on the order of arrival).
 #include "common.hpp"
 
 namespace ficoco {
 
-struct ScoreArgs {
+struct SelectArgs {
   int N, H, M, n_chunks, dtype;
   int red_src, sem_src;
+  int do_score, do_filter;
   const double* recv_part;  // [B][n_chunks][N]
   const double* cls;        // [B][N]
   const double* ttext;      // [B][N][M]
@@ -20,7 +30,12 @@ struct ScoreArgs {
   const int32_t* pos;
   int grid_g, grid_h, grid_w, window;
   double coef;
-  double* scores;
+  double* scores;           // out (do_score) / in (filter only)
+  int n_disc;
+  int32_t* discard_idx;
+  int32_t* keep_idx;
+  int32_t* slot_of;
+  int32_t* overflow;        // zeroed here for the correlate stage (fused step only), may be null
 };
 
 __device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_t b, int H, int N, int i) {
@@ -35,136 +50,203 @@ __device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_
   return acc * (1.0 / (double)H);
 }
 
-__global__ __launch_bounds__(kSelectThreads) void score_kernel(ScoreArgs a) {
-  extern __shared__ double lds_d[];
-  double* s = lds_d;                              // [N]
-  const int cells = a.grid_g * a.grid_h * a.grid_w;
-  int* owner = (int*)(lds_d + a.N);               // [cells] (penalty only)
-  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-  const int N = a.N;
-
-  for (int i = tid; i < N; i += nt) {
-    double R, G;
-    if (a.red_src == FICOCO_R_ATTN_RECV) {
-      const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
-      double acc = 0.0;
-      for (int c = 0; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
-      R = acc / (double)N;
-    } else if (a.red_src == FICOCO_R_VECTOR) {
-      R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
-    } else {
-      R = a.fterm_r[(int64_t)b * N + i];
-    }
-    if (a.sem_src == FICOCO_G_CLS_ATTN) {
-      G = a.cls[(int64_t)b * N + i];
-    } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
-      const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
-      double acc = 0.0;
-      for (int k = 0; k < a.M; ++k) acc += p[k];
-      G = acc / (double)a.M;
-    } else if (a.sem_src == FICOCO_G_VECTOR) {
-      G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);
-    } else {
-      G = a.fterm_g[(int64_t)b * N + i];
-    }
-    s[i] = a.w * R - (1.0 - a.w) * G;
-  }
-  if (a.window > 0) {
-    for (int c = tid; c < cells; c += nt) owner[c] = -1;
-    __syncthreads();
-    for (int i = tid; i < N; i += nt) {
-      const int c = a.pos ? a.pos[(int64_t)b * N + i] : i;
-      if (c >= 0 && c < cells) owner[c] = i;
-    }
-    __syncthreads();
-    const int W = a.window;
-    const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
-    const int n_win = a.grid_g * wr * wc;
-    for (int w = tid; w < n_win; w += nt) {
-      const int sub = w / (wr * wc), rem = w % (wr * wc);
-      const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
-      int best = -1;
-      double best_s = 0.0;
-      for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
-        for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
-          const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
-          if (t >= 0 && (best < 0 || s[t] > best_s)) { best = t; best_s = s[t]; }
-        }
-      if (best >= 0) s[best] = a.coef * best_s;   // windows are disjoint: no other reader
-    }
-  }
-  __syncthreads();
-  for (int i = tid; i < N; i += nt) a.scores[(int64_t)b * N + i] = s[i];
+__device__ __forceinline__ uint64_t score_key(double s) {
+  const uint64_t u = (uint64_t)__double_as_longlong(s + 0.0);   // -0 folded into +0
+  return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
 }
 
-struct FilterArgs {
-  int N, n_disc;
-  const double* scores;
-  int32_t* discard_idx;
-  int32_t* keep_idx;
-  int32_t* slot_of;
-};
-
-__global__ __launch_bounds__(kSelectThreads) void filter_kernel(FilterArgs a) {
-  extern __shared__ double lds_d[];
-  uint64_t* keys = (uint64_t*)lds_d;        // [N]
-  int* scan = (int*)(lds_d + a.N);          // [2][nt]
-  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
-  const int N = a.N;
-  for (int i = tid; i < N; i += nt) {
-    const uint64_t u = (uint64_t)__double_as_longlong(a.scores[(int64_t)b * N + i] + 0.0);
-    keys[i] = (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
-  }
+// Inclusive scan of one int per thread over the workgroup; returns this thread's inclusive
+// value, *total receives the sum.  scratch: 2 * blockDim.x ints.
+__device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* total) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  int* cur = scratch;
+  int* nxt = scratch + nt;
   __syncthreads();
-
-  // Thread t owns the contiguous tokens [t*per, (t+1)*per).  rank_i = number of tokens
-  // that come before i in (score descending, index ascending) order.  The comparison runs
-  // on order-preserving integer keys of the doubles (-0 folded into +0), which is the same
-  // order for finite scores and stays a strict total order whatever the bits are, so
-  // exactly n_disc tokens are flagged even for non-finite input.
-  const int per = (N + nt - 1) / nt;
-  const int lo = min(tid * per, N), hi = min(lo + per, N);
-  int n_dis = 0;
-  uint32_t dis_mask = 0;  // per <= 12 tokens per thread (N <= kMaxSelectN)
-  for (int i = lo; i < hi; ++i) {
-    const uint64_t ki = keys[i];
-    int rank = 0;
-    for (int j = 0; j < N; ++j) {
-      const uint64_t kj = keys[j];
-      rank += (kj > ki || (kj == ki && j < i)) ? 1 : 0;
-    }
-    if (rank < a.n_disc) { dis_mask |= 1u << (i - lo); ++n_dis; }
-  }
-  // exclusive scan of the per-thread discard counts
-  int* cur = scan;
-  int* nxt = scan + nt;
-  cur[tid] = n_dis;
+  cur[tid] = v;
   __syncthreads();
   for (int off = 1; off < nt; off <<= 1) {
     nxt[tid] = cur[tid] + (tid >= off ? cur[tid - off] : 0);
     __syncthreads();
     int* t = cur; cur = nxt; nxt = t;
   }
-  int d_pos = cur[tid] - n_dis;   // discarded tokens before `lo`
-  int k_pos = lo - d_pos;         // preserved tokens before `lo`
+  const int r = cur[tid];
+  *total = cur[nt - 1];
+  __syncthreads();
+  return r;
+}
+
+__global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
+  extern __shared__ double lds_d[];
+  double* s = lds_d;                                   // [N] scores, then keys in place
+  uint64_t* keys = (uint64_t*)lds_d;
+  int* ibase = (int*)(lds_d + a.N);
+  int* scan = ibase;                                   // [2][nt]
+  int* hist = ibase + 2 * kSelectThreads;              // [256]
+  int* bcast = hist + 256;                             // [4]
+  int* owner = bcast + 4;                              // [cells] (penalty only)
+  const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
+  const int N = a.N;
+
+  if (a.do_score) {
+    for (int i = tid; i < N; i += nt) {
+      double R, G;
+      if (a.red_src == FICOCO_R_ATTN_RECV) {
+        const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
+        double acc = 0.0;
+        int c = 0;
+        for (; c + 16 <= a.n_chunks; c += 16) {          // 16 independent loads, added in order
+          double v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(c + u) * N];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) acc += v[u];
+        }
+        for (; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
+        R = acc / (double)N;
+      } else if (a.red_src == FICOCO_R_VECTOR) {
+        R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
+      } else {
+        R = a.fterm_r[(int64_t)b * N + i];
+      }
+      if (a.sem_src == FICOCO_G_CLS_ATTN) {
+        G = a.cls[(int64_t)b * N + i];
+      } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
+        const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
+        double acc = 0.0;
+        for (int k = 0; k < a.M; ++k) acc += p[k];
+        G = acc / (double)a.M;
+      } else if (a.sem_src == FICOCO_G_VECTOR) {
+        G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);
+      } else {
+        G = a.fterm_g[(int64_t)b * N + i];
+      }
+      s[i] = a.w * R - (1.0 - a.w) * G;
+    }
+    if (a.window > 0) {
+      const int cells = a.grid_g * a.grid_h * a.grid_w;
+      for (int c = tid; c < cells; c += nt) owner[c] = -1;
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) {
+        const int c = a.pos ? a.pos[(int64_t)b * N + i] : i;
+        if (c >= 0 && c < cells) owner[c] = i;
+      }
+      __syncthreads();
+      const int W = a.window;
+      const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
+      const int n_win = a.grid_g * wr * wc;
+      for (int w = tid; w < n_win; w += nt) {
+        const int sub = w / (wr * wc), rem = w % (wr * wc);
+        const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
+        int best = -1;
+        double best_s = 0.0;
+        for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
+          for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
+            const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
+            if (t >= 0 && (best < 0 || s[t] > best_s)) { best = t; best_s = s[t]; }
+          }
+        if (best >= 0) s[best] = a.coef * best_s;   // windows are disjoint: no other reader
+      }
+    }
+    __syncthreads();
+    for (int i = tid; i < N; i += nt) a.scores[(int64_t)b * N + i] = s[i];
+  } else {
+    for (int i = tid; i < N; i += nt) s[i] = a.scores[(int64_t)b * N + i];
+  }
+  if (!a.do_filter) return;
+  if (a.overflow && tid == 0) a.overflow[b] = 0;
+  __syncthreads();
+  for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
+  __syncthreads();
+
+  // ---- radix select of the n_disc-th largest key -------------------------------------------
+  uint64_t kstar = 0;
+  int need = a.n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
+  if (a.n_disc > 0) {
+    for (int pass = 0; pass < 8; ++pass) {
+      const int shift = 56 - 8 * pass;
+      const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) {
+        const uint64_t k = keys[i];
+        if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
+      }
+      __syncthreads();
+      if (tid < kWave) {
+        // Wavefront 0 walks the 256 bins from the top: lane l owns bins 4l .. 4l+3.
+        int h[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
+        const int lsum = h[0] + h[1] + h[2] + h[3];
+        int incl = lsum;                                   // sum over lanes >= this one
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+          const int t = __shfl_down(incl, off, kWave);
+          if (tid + off < kWave) incl += t;
+        }
+        int above = incl - lsum;                           // tokens in bins above this lane's
+        if (above < need && need <= above + lsum) {        // exactly one lane
+#pragma unroll
+          for (int k = 3; k >= 0; --k) {
+            if (above < need && need <= above + h[k]) { bcast[0] = 4 * tid + k; bcast[1] = need - above; }
+            above += h[k];
+          }
+        }
+      }
+      __syncthreads();
+      kstar |= (uint64_t)bcast[0] << shift;
+      need = bcast[1];
+      __syncthreads();
+    }
+  }
+  // need = how many tokens with key == kstar are discarded (lowest indices first)
+
+  // ---- flags and ordered compaction -----------------------------------------------------------
+  const int per = (N + nt - 1) / nt;
+  const int lo = min(tid * per, N), hi = min(lo + per, N);
+  int n_eq = 0;
+  for (int i = lo; i < hi; ++i) n_eq += (a.n_disc > 0 && keys[i] == kstar) ? 1 : 0;
+  int tot;
+  int eq_before = block_scan_inclusive(n_eq, scan, &tot) - n_eq;
+  uint32_t dis_mask = 0;  // per <= 12 tokens per thread (N <= kMaxSelectN)
+  int n_dis = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint64_t k = keys[i];
+    bool dis = false;
+    if (a.n_disc > 0) {
+      if (k > kstar) dis = true;
+      else if (k == kstar) { dis = eq_before < need; ++eq_before; }
+    }
+    if (dis) { dis_mask |= 1u << (i - lo); ++n_dis; }
+  }
+  int d_pos = block_scan_inclusive(n_dis, scan, &tot) - n_dis;   // discarded tokens before `lo`
+  int k_pos = lo - d_pos;                                         // preserved tokens before `lo`
   const int n_keep = N - a.n_disc;
   for (int i = lo; i < hi; ++i) {
     if (dis_mask & (1u << (i - lo))) {
-      a.discard_idx[(int64_t)b * a.n_disc + d_pos] = i;
+      if (d_pos < a.n_disc) a.discard_idx[(int64_t)b * a.n_disc + d_pos] = i;
       a.slot_of[(int64_t)b * N + i] = -1;
       ++d_pos;
     } else {
-      a.keep_idx[(int64_t)b * n_keep + k_pos] = i;
+      if (k_pos < n_keep) a.keep_idx[(int64_t)b * n_keep + k_pos] = i;
       a.slot_of[(int64_t)b * N + i] = k_pos;
       ++k_pos;
     }
   }
 }
 
-void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {
-  ScoreArgs a{};
+static size_t select_lds(const ficoco_problem& p, bool penalty) {
+  const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
+  return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + cells) * sizeof(int);
+}
+
+void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
+                   bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
+                   hipStream_t s) {
+  SelectArgs a{};
   a.N = p.N; a.H = p.H; a.M = p.M; a.n_chunks = pl.n_chunks; a.dtype = p.dtype;
   a.red_src = p.red_src; a.sem_src = p.sem_src;
+  a.do_score = do_score; a.do_filter = do_filter;
   a.recv_part = (const double*)(ws + pl.recv_part);
   a.cls = (const double*)(ws + pl.cls);
   a.ttext = (const double*)(ws + pl.ttext);
@@ -178,23 +260,23 @@ void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* sco
   a.window = penalty ? p.window : 0;
   a.coef = (double)p.penalty_coef;
   a.scores = scores;
-  const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
-  const size_t lds = (size_t)p.N * sizeof(double) + cells * sizeof(int);
+  a.n_disc = pl.n_disc;
+  a.discard_idx = discard_idx; a.keep_idx = keep_idx;
+  a.slot_of = (int32_t*)(ws + pl.slot_of);
+  a.overflow = overflow;
+  const size_t lds = select_lds(p, penalty);
   if (lds > 32768)
-    (void)hipFuncSetAttribute((const void*)score_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(score_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+    (void)hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL(select_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+}
+
+void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {
+  launch_select(p, pl, ws, scores, true, false, nullptr, nullptr, nullptr, s);
 }
 
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s) {
-  FilterArgs a{};
-  a.N = p.N; a.n_disc = pl.n_disc;
-  a.scores = scores; a.discard_idx = discard_idx; a.keep_idx = keep_idx;
-  a.slot_of = (int32_t*)(ws + pl.slot_of);
-  const size_t lds = (size_t)p.N * sizeof(double) + 2 * kSelectThreads * sizeof(int);
-  if (lds > 32768)
-    (void)hipFuncSetAttribute((const void*)filter_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(filter_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+  launch_select(p, pl, ws, const_cast<double*>(scores), false, true, discard_idx, keep_idx, nullptr, s);
 }
 
 }  // namespace ficoco

@@ -15,7 +15,7 @@ struct ficoco_ctx {
 namespace ficoco {
 
 #ifndef FICOCO_WG_TARGET
-#define FICOCO_WG_TARGET 1024
+#define FICOCO_WG_TARGET 2048
 #endif
 constexpr int64_t kWgTarget = FICOCO_WG_TARGET;
 
@@ -151,6 +151,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.tgt_src = take(B * (size_t)pl.n_disc * p.k_max * sizeof(int32_t));
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
+  pl.edge_pack = take(B * (size_t)pl.n_disc * p.k_max * sizeof(EdgeRec));
   pl.total = off;
   return FICOCO_OK;
 }
@@ -198,7 +199,7 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   if (pl.need_features) launch_features(p, pl, w, s);
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true, s);
-  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
+  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, true, s);
   return finish(ctx, fn);
 }
 
@@ -294,7 +295,7 @@ int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t w
   if (!X_out || !keep_idx || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_compress", "a pointer is NULL");
   launch_compress(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out,
-                  pos_out, (hipStream_t)stream);
+                  pos_out, false, (hipStream_t)stream);
   return finish(ctx, "ficoco_compress");
 }
 

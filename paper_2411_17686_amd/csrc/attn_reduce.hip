@@ -20,6 +20,9 @@ namespace ficoco {
 #define FICOCO_HEAD_BATCH 8
 #endif
 constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
+#ifndef FICOCO_DBG_ABAR
+#define FICOCO_DBG_ABAR
+#endif
 
 struct AttnArgs {
   const void* A;
@@ -41,6 +44,7 @@ struct AttnArgs {
 
 template <typename T>
 __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a) {
+  DBG_SPAN(0);
   extern __shared__ double lds[];
   const int chunk = blockIdx.x, strip = blockIdx.y, b = blockIdx.z;
   const int tid = threadIdx.x;
@@ -69,14 +73,18 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
       if (ncol == kVec) {
         // kHeadBatch independent 16-byte loads are issued before the first add; the adds
         // then run in head order.
-        for (int h0 = 0; h0 < a.H; h0 += kHeadBatch) {
+        int h0 = 0;
+        for (; h0 + kHeadBatch <= a.H; h0 += kHeadBatch) {
           Raw8<T> raw[kHeadBatch];
 #pragma unroll
-          for (int u = 0; u < kHeadBatch; ++u)
-            if (h0 + u < a.H) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
+          for (int u = 0; u < kHeadBatch; ++u) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
 #pragma unroll
-          for (int u = 0; u < kHeadBatch; ++u)
-            if (h0 + u < a.H) add_raw(raw[u], p);
+          for (int u = 0; u < kHeadBatch; ++u) add_raw(raw[u], p);
+        }
+        for (; h0 < a.H; ++h0) {
+          Raw8<T> raw;
+          load_raw(base + (int64_t)h0 * a.sh, raw);
+          add_raw(raw, p);
         }
       } else {
         for (int h = 0; h < a.H; ++h)
@@ -88,7 +96,7 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
       if (is_vis) {
 #pragma unroll
         for (int k = 0; k < kVec; ++k) acc[k] += p[k];
-        if (a.abar) {
+        if (a.abar FICOCO_DBG_ABAR) {
           float* dst = a.abar + ((int64_t)b * a.N + (r - a.vis_r0)) * a.N + col;
           if (ncol == kVec) {
             float4 lo = make_float4((float)p[0], (float)p[1], (float)p[2], (float)p[3]);
@@ -182,3 +190,5 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
 }
 
 }  // namespace ficoco
+
+FICOCO_DBG_READER(reduce)

@@ -12,7 +12,10 @@ namespace ficoco {
 constexpr int kWave = 64;
 constexpr int kVec = 8;            // elements per lane per load in the streaming kernels
 constexpr int kSelMax = 8;         // order statistics kept in registers by the fast threshold path
-constexpr int kReduceThreads = 256;
+#ifndef FICOCO_REDUCE_THREADS
+#define FICOCO_REDUCE_THREADS 256
+#endif
+constexpr int kReduceThreads = FICOCO_REDUCE_THREADS;
 constexpr int kSelectThreads = 1024;
 constexpr int kMaxSelectN = 12288; // visual tokens / grid cells the per-image select kernel holds in LDS
 
@@ -49,11 +52,16 @@ struct Plan {
   size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
+  size_t edge_pack;      // EdgeRec [B][N^S][k_max]  edges as the merge kernel reads them
   int f_chunks, f_rows_per_wg, Df;
   size_t total;
 };
 
 int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
+
+// One edge of the correlate stage in the form the merge kernel scans: target slot, source
+// visual token, weight.  16 bytes, one load.
+struct __attribute__((aligned(16))) EdgeRec { int32_t tgt; int32_t src; double alpha; };
 
 // ---- launchers (all asynchronous on `s`) -----------------------------------------------
 void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
@@ -69,7 +77,8 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
                       double* edge_alpha, int32_t* overflow, bool overflow_is_zero, hipStream_t s);
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
-                     const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s);
+                     const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,
+                     hipStream_t s);
 
 // ---- device helpers ----------------------------------------------------------------------
 typedef uint16_t bf16_t;
@@ -88,7 +97,13 @@ template <> struct Raw8<bf16_t> { uint4 a; };
 template <> struct Raw8<float> { float4 a, b; };
 
 __device__ __forceinline__ void load_raw(const bf16_t* __restrict__ p, Raw8<bf16_t>& r) {
+#ifdef FICOCO_DBG_NT
+  typedef uint32_t u32x4 __attribute__((ext_vector_type(4), aligned(2)));
+  u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
+  r.a = make_uint4(v.x, v.y, v.z, v.w);
+#else
   __builtin_memcpy(&r.a, p, 16);
+#endif
 }
 __device__ __forceinline__ void load_raw(const float* __restrict__ p, Raw8<float>& r) {
   __builtin_memcpy(&r.a, p, 16);
@@ -130,6 +145,44 @@ __device__ __forceinline__ void load8<float>(const float* __restrict__ p, double
   out[0] = a.x; out[1] = a.y; out[2] = a.z; out[3] = a.w;
   out[4] = b.x; out[5] = b.y; out[6] = b.z; out[7] = b.w;
 }
+
+// Workgroups are handed to the 8 XCDs round-robin by their linear id, and every XCD has its
+// own L2.  This maps the linear id to a logical id such that consecutive logical ids (the
+// tiles of one image) run on the same XCD and share its L2.  Logical ids >= total are idle.
+constexpr int kXcds = 8;
+__device__ __forceinline__ int xcd_logical_id(int linear, int total) {
+  const int per = (total + kXcds - 1) / kXcds;
+  return (linear % kXcds) * per + linear / kXcds;
+}
+__host__ __device__ __forceinline__ int xcd_padded_total(int total) {
+  return ((total + kXcds - 1) / kXcds) * kXcds;
+}
+
+#ifdef FICOCO_DBG_TIMING
+// Tuning aid (never in the product build): thread 0 of every workgroup stores its start and
+// end time on the 100 MHz wall clock; one array per translation unit.
+constexpr int kDbgSlots = 16384;
+static __device__ unsigned long long g_dbg[2 * kDbgSlots];
+struct DbgSpan {
+  unsigned long long t0;
+  __device__ DbgSpan(int) : t0(wall_clock64()) {}
+  __device__ ~DbgSpan() {
+    const int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    if (threadIdx.x == 0 && wg < kDbgSlots) { g_dbg[2 * wg] = t0; g_dbg[2 * wg + 1] = wall_clock64(); }
+  }
+};
+#define DBG_SPAN(k) DbgSpan dbg_span_(k)
+#define DBG_PHASE(i) do { if (blockIdx.x == 40 && blockIdx.y == 0 && threadIdx.x == 0) g_dbg[2 * (kDbgSlots - 16) + (i)] = wall_clock64(); } while (0)
+#define FICOCO_DBG_READER(name) \
+  extern "C" void ficoco_debug_reset_##name(void) { \
+    void* p; (void)hipGetSymbolAddress(&p, HIP_SYMBOL(ficoco::g_dbg)); (void)hipMemset(p, 0, sizeof(unsigned long long) * 2 * ficoco::kDbgSlots); } \
+  extern "C" void ficoco_debug_read_##name(unsigned long long* out) { \
+    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(ficoco::g_dbg), sizeof(unsigned long long) * 2 * ficoco::kDbgSlots); }
+#else
+#define DBG_SPAN(k)
+#define DBG_PHASE(i)
+#define FICOCO_DBG_READER(name)
+#endif
 
 // Round a double to the nearest bfloat16, ties to even, straight from double (no
 // intermediate float rounding).  The spacing at binary exponent e is 2^(max(e,-126)-7).

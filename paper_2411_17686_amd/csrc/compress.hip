@@ -111,6 +111,7 @@ struct MergeArgs {
   const int32_t* edge_cnt;
   const int32_t* edge_tgt;
   const double* edge_alpha;
+  const EdgeRec* pack;   // null: read the caller's edge lists instead
   const int32_t* pos;
   int32_t* pos_out;
 };
@@ -122,7 +123,13 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-constexpr int kMergeSlice = 2;   // 8-element vectors per lane per pass over the feature axis
+#ifndef FICOCO_MERGE_SLICE
+#define FICOCO_MERGE_SLICE 2
+#endif
+#ifndef FICOCO_SCAN_BLOCKS
+#define FICOCO_SCAN_BLOCKS 2
+#endif
+constexpr int kMergeSlice = FICOCO_MERGE_SLICE;   // 8-element vectors per lane per pass over the feature axis
 
 // One wavefront per output row.  MATCH = false: the sources of a preserved token come from
 // the inverted edge lists.  MATCH = true (few discarded tokens): no inversion kernel; the
@@ -130,6 +137,7 @@ constexpr int kMergeSlice = 2;   // 8-element vectors per lane per pass over the
 // the rows that name its target -- in ascending row order, so the sum order is the same.
 template <typename T, bool MATCH>
 __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
+  DBG_SPAN(3);
   const int lane = threadIdx.x % kWave;
   const int r = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   const int64_t b = blockIdx.y;
@@ -195,25 +203,42 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
       }
     };
     if (MATCH) {
-      for (int base = 0; base < a.n_disc; base += kWave) {
-        const int row = base + lane;
-        double w = 0.0;
-        int src = 0;
-        bool hit = false;
-        if (row < a.n_disc) {
-          const int cnt = min(a.edge_cnt[b * a.n_disc + row], a.k_max);
-          src = a.S[b * a.n_disc + row];
-          for (int e = 0; e < cnt; ++e)
-            if (a.edge_tgt[(b * a.n_disc + row) * a.k_max + e] == j) {
-              hit = true;
-              w = a.edge_alpha[(b * a.n_disc + row) * a.k_max + e];
-            }
+      // kScanBlocks x 64 discarded rows per round, all loads of a round issued together.
+      constexpr int kScanBlocks = FICOCO_SCAN_BLOCKS;
+      for (int base = 0; base < a.n_disc; base += kWave * kScanBlocks) {
+        int cnt[kScanBlocks], t0[kScanBlocks], src[kScanBlocks];
+        double w0[kScanBlocks];
+#pragma unroll
+        for (int u = 0; u < kScanBlocks; ++u) {
+          const int row = base + u * kWave + lane;
+          const bool in = row < a.n_disc;
+          const int64_t rr = b * a.n_disc + (in ? row : 0);
+          cnt[u] = in ? min(a.edge_cnt[rr], a.k_max) : 0;
+          if (a.pack) {
+            const EdgeRec e = a.pack[rr * a.k_max];
+            t0[u] = e.tgt; src[u] = e.src; w0[u] = e.alpha;
+          } else {
+            t0[u] = a.edge_tgt[rr * a.k_max];
+            src[u] = a.S[rr];
+            w0[u] = 0.0;
+          }
         }
-        unsigned long long m = __ballot(hit);
-        while (m) {
-          const int l = __ffsll(m) - 1;
-          m &= m - 1;
-          add_source(__shfl(src, l, kWave), __shfl(w, l, kWave));
+#pragma unroll
+        for (int u = 0; u < kScanBlocks; ++u) {
+          if (base + u * kWave >= a.n_disc) break;     // uniform
+          const int64_t rr = b * a.n_disc + min(base + u * kWave + lane, a.n_disc - 1);
+          int he = (cnt[u] > 0 && t0[u] == j) ? 0 : -1;
+          for (int e = 1; e < cnt[u]; ++e)
+            if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
+          const bool hit = he >= 0;
+          double w = w0[u];
+          if (hit && (he > 0 || !a.pack)) w = a.edge_alpha[rr * a.k_max + he];
+          unsigned long long m = __ballot(hit);
+          while (m) {
+            const int l = __ffsll(m) - 1;
+            m &= m - 1;
+            add_source(__shfl(src[u], l, kWave), __shfl(w, l, kWave));
+          }
         }
       }
     } else {
@@ -245,7 +270,8 @@ constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the ed
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
-                     const double* edge_alpha, void* X_out, int32_t* pos_out, hipStream_t s) {
+                     const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,
+                     hipStream_t s) {
   const bool match = pl.n_disc <= kMatchMaxRows;
   if (pl.n_disc > 0 && !match) {
     InvertArgs a{};
@@ -268,6 +294,7 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.tgt_src = (const int32_t*)(ws + pl.tgt_src);
   m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
+  m.pack = use_pack ? (const EdgeRec*)(ws + pl.edge_pack) : nullptr;
   m.pos = p.pos; m.pos_out = pos_out;
   dim3 grid((pl.n_out + 3) / 4, p.B), block(256);
   const bool bf16 = p.dtype == FICOCO_BF16;
@@ -281,3 +308,5 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
 }
 
 }  // namespace ficoco
+
+FICOCO_DBG_READER(merge)

@@ -17,7 +17,7 @@ namespace ficoco {
 enum CorrMode { kAttnV = 0, kAttnL = 1, kCosV = 2, kCosL = 3 };
 
 struct CorrArgs {
-  int N, n_keep, n_disc, M, k_max, Df, mode;
+  int B, N, n_keep, n_disc, M, k_max, Df, mode;
   const float* abar;     // [B][N][N]
   const double* ttext;   // [B][N][M]
   const bf16_t* xhat;    // [B][N][Df]
@@ -32,6 +32,8 @@ struct CorrArgs {
   int32_t* edge_tgt;
   double* edge_alpha;
   int32_t* overflow;
+  EdgeRec* pack;         // [B][n_disc][k_max]
+  const int32_t* slot_of; // [B][N] keep slot of a visual token, -1 if discarded
 };
 
 __device__ __forceinline__ double dot_bf16(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y, int D) {
@@ -213,11 +215,17 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
   const bool live = denom > 0.0;
   if (a.k_max <= kWave) {
     if (live && lane < stored) {
+      const double al = my_c / denom;
       a.edge_tgt[ebase + lane] = my_tgt;
-      a.edge_alpha[ebase + lane] = my_c / denom;
+      a.edge_alpha[ebase + lane] = al;
+      a.pack[ebase + lane] = EdgeRec{my_tgt, i, al};
     }
   } else if (live && lane == 0) {
-    for (int e = 0; e < stored; ++e) a.edge_alpha[ebase + e] = a.edge_alpha[ebase + e] / denom;
+    for (int e = 0; e < stored; ++e) {
+      const double al = a.edge_alpha[ebase + e] / denom;
+      a.edge_alpha[ebase + e] = al;
+      a.pack[ebase + e] = EdgeRec{a.edge_tgt[ebase + e], i, al};
+    }
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -231,90 +239,142 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
 // (64 different rows per load).  For the plain attention correlation of Algorithm 1 this
 // tile kernel is used instead: a workgroup owns kTileCols discarded columns, thread
 // (c, jl) scans rows T[jl], T[jl + kTileLanes], ... of column S[c], so the threads of one
-// row read neighbouring columns of the same row.  Pass 1 keeps the m largest values per
-// thread, LDS merges them per column into v[f], v[f+1] and tau; pass 2 re-reads the (cache
-// resident) column and collects the rows at or above tau.
+// row read neighbouring columns of the same row.  Loads are issued in independent batches
+// (a dependent global load costs about a microsecond).  Each thread keeps its kSelMax
+// largest (value, target) pairs; LDS merges them per column into v[f], v[f+1] and tau; the
+// targets at or above tau are then taken from the per-thread lists (a thread whose whole
+// list is at or above tau re-reads its part of the column instead).
 constexpr int kTileCols = 8;
 constexpr int kTileLanes = 32;
+constexpr int kTileBatch = 24;
 constexpr int kHitCap = 64;
 
+// Reductions over the kTileLanes threads that share a column: lanes c, c+8, ... of each
+// wavefront by xor-shuffles, then the four wavefronts through a double-buffered LDS slot.
+__device__ __forceinline__ float col_max(float v, float (*red)[4][kTileCols], int& phase, int wv, int c) {
+#pragma unroll
+  for (int off = kTileCols; off < kWave; off <<= 1) { const float o = __shfl_xor(v, off, kWave); v = o > v ? o : v; }
+  red[phase][wv][c] = v;
+  __syncthreads();
+  float r = red[phase][0][c];
+#pragma unroll
+  for (int w = 1; w < 4; ++w) { const float o = red[phase][w][c]; r = o > r ? o : r; }
+  phase ^= 1;
+  return r;
+}
+__device__ __forceinline__ int col_sum(int v, int (*red)[4][kTileCols], int& phase, int wv, int c) {
+#pragma unroll
+  for (int off = kTileCols; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
+  red[phase][wv][c] = v;
+  __syncthreads();
+  int r = 0;
+#pragma unroll
+  for (int w = 0; w < 4; ++w) r += red[phase][w][c];
+  phase ^= 1;
+  return r;
+}
+
+// MC = (value, target) pairs kept per thread (>= sel_m; 2, 4 or 8).
+template <int MC>
 __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(CorrArgs a) {
-  __shared__ float cand[kTileCols][kTileLanes][kSelMax];
-  __shared__ double tau_s[kTileCols];
+  DBG_SPAN(2);
+  static_assert(kTileCols * kTileLanes == 4 * kWave, "four wavefronts per tile");
+  __shared__ float redf[2][4][kTileCols];
+  __shared__ int redi[2][4][kTileCols];
   __shared__ int hit_cnt[kTileCols];
   __shared__ int hit_j[kTileCols][kHitCap];
   __shared__ float hit_v[kTileCols][kHitCap];
   const int tid = threadIdx.x;
-  const int c = tid % kTileCols, jl = tid / kTileCols;
-  const int64_t b = blockIdx.y;
-  const int row = blockIdx.x * kTileCols + c;
-  const int n = a.n_keep;
-  const int32_t* T = a.T + b * n;
+  const int c = tid % kTileCols, jl = tid / kTileCols, wv = tid / kWave;
+  const int tiles = (a.n_disc + kTileCols - 1) / kTileCols;
+  const int logical = xcd_logical_id(blockIdx.x, tiles * a.B);
+  if (logical >= tiles * a.B) return;                 // padding workgroup (whole block leaves)
+  const int64_t b = logical / tiles;
+  const int row = (logical % tiles) * kTileCols + c;
   int i = row < a.n_disc ? a.S[b * a.n_disc + row] : -1;
   const bool valid = (unsigned)i < (unsigned)a.N;   // index sets are device data
   if (!valid) i = 0;
   const float* col = a.abar + b * a.N * (int64_t)a.N + i;
+  const int32_t* slot_of = a.slot_of + b * a.N;
   const float NEGF = -__builtin_huge_valf();
+  if (jl == 0) hit_cnt[c] = 0;
 
-  float top[kSelMax];
+  // Scan ALL visual rows of the column and take the preserved ones (slot_of >= 0): the
+  // value and the slot are independent loads, so one round trip serves a whole batch.
+  float top[MC];
+  int topj[MC];
 #pragma unroll
-  for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
-  if (valid) {
-    for (int jj = jl; jj < n; jj += kTileLanes) {
-      const int j = T[jj];
-      float v = (unsigned)j < (unsigned)a.N ? col[(int64_t)j * a.N] : NEGF;
-      if (v > top[kSelMax - 1]) {
+  for (int k = 0; k < MC; ++k) { top[k] = NEGF; topj[k] = -1; }
+  for (int r0 = jl; r0 < a.N; r0 += kTileLanes * kTileBatch) {
+    float vv[kTileBatch];
+    int sv[kTileBatch];
 #pragma unroll
-        for (int k = 0; k < kSelMax; ++k) {
-          const bool sw = v > top[k];
-          const float t = top[k];
-          top[k] = sw ? v : t;
-          v = sw ? t : v;
-        }
+    for (int u = 0; u < kTileBatch; ++u) {
+      const int r = min(r0 + u * kTileLanes, a.N - 1);     // clamped: always a valid address
+      vv[u] = col[(int64_t)r * a.N];
+      sv[u] = slot_of[r];
+    }
+#pragma unroll 4
+    for (int u = 0; u < kTileBatch; ++u) {
+      const bool ok = valid && r0 + u * kTileLanes < a.N && sv[u] >= 0;
+      float v = ok ? vv[u] : NEGF;
+      int jq = sv[u];
+#pragma unroll
+      for (int k = 0; k < MC; ++k) {
+        const bool sw = v > top[k];
+        const float tv = top[k];
+        const int tj = topj[k];
+        top[k] = sw ? v : tv;
+        topj[k] = sw ? jq : tj;
+        v = sw ? tv : v;
+        jq = sw ? tj : jq;
       }
     }
   }
+  // v[f] and v[f+1] = the m-th and (m-1)-th largest of the column, counted with
+  // multiplicity: walk the distinct values from the top (at most m of them).
+  float vf = NEGF, vf1 = NEGF;
+  {
+    int phase = 0, taken = 0;
+    float cur = __builtin_huge_valf();
+    const int m = a.sel_m;
+    for (int it = 0; it < m; ++it) {          // uniform trip count: the reductions hold barriers
+      float lm = NEGF;
 #pragma unroll
-  for (int k = 0; k < kSelMax; ++k) cand[c][jl][k] = top[k];
-  __syncthreads();
-  if (jl == 0) {
-    float best[kSelMax];
+      for (int k = 0; k < MC; ++k) lm = (top[k] < cur && top[k] > lm) ? top[k] : lm;
+      const float nxt = col_max(lm, redf, phase, wv, c);
+      int lc = 0;
 #pragma unroll
-    for (int k = 0; k < kSelMax; ++k) best[k] = NEGF;
-    for (int l = 0; l < kTileLanes; ++l)
-      for (int q = 0; q < a.sel_m; ++q) {
-        float v = cand[c][l][q];
-        if (v > best[kSelMax - 1]) {
-#pragma unroll
-          for (int k = 0; k < kSelMax; ++k) {
-            const bool sw = v > best[k];
-            const float t = best[k];
-            best[k] = sw ? v : t;
-            v = sw ? t : v;
-          }
-        }
-      }
-    float vf = NEGF, vf1 = NEGF;     // m-th and (m-1)-th largest
-#pragma unroll
-    for (int k = 0; k < kSelMax; ++k) {
-      if (k == a.sel_m - 1) vf = best[k];
-      if (k == a.sel_m - 2) vf1 = best[k];
+      for (int k = 0; k < MC; ++k) lc += top[k] == nxt ? 1 : 0;
+      const int cnt = col_sum(lc, redi, phase, wv, c);
+      if (taken <= m - 1 && m - 1 < taken + cnt) vf = nxt;
+      if (m >= 2 && taken <= m - 2 && m - 2 < taken + cnt) vf1 = nxt;
+      taken += cnt;
+      cur = nxt;
     }
-    if (a.sel_m == 1) vf1 = vf;
-    tau_s[c] = threshold_of((double)vf, (double)vf1, a.sel_g);
-    hit_cnt[c] = 0;
   }
+  if (a.sel_m == 1) vf1 = vf;
   __syncthreads();
   if (valid) {
-    const double tau = tau_s[c];
-    for (int jj = jl; jj < n; jj += kTileLanes) {
-      const int j = T[jj];
-      if ((unsigned)j >= (unsigned)a.N) continue;
-      const float v = col[(int64_t)j * a.N];
-      if ((double)v >= tau) {
-        const int slot = atomicAdd(&hit_cnt[c], 1);
-        if (slot < kHitCap) { hit_j[c][slot] = jj; hit_v[c][slot] = v; }
+    const double tau = threshold_of((double)vf, (double)vf1, a.sel_g);
+    if ((double)top[MC - 1] >= tau) {
+      // the whole list qualifies, so more may: take this thread's part of the column again
+      for (int r = jl; r < a.N; r += kTileLanes) {
+        const int sj = slot_of[r];
+        if (sj < 0) continue;
+        const float v = col[(int64_t)r * a.N];
+        if ((double)v >= tau) {
+          const int slot = atomicAdd(&hit_cnt[c], 1);
+          if (slot < kHitCap) { hit_j[c][slot] = sj; hit_v[c][slot] = v; }
+        }
       }
+    } else {
+#pragma unroll
+      for (int k = 0; k < MC; ++k)
+        if ((double)top[k] >= tau) {
+          const int slot = atomicAdd(&hit_cnt[c], 1);
+          if (slot < kHitCap) { hit_j[c][slot] = topj[k]; hit_v[c][slot] = top[k]; }
+        }
     }
   }
   __syncthreads();
@@ -336,8 +396,10 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
     const int64_t ebase = (b * a.n_disc + row) * a.k_max;
     if (live)
       for (int x = 0; x < stored; ++x) {
+        const double al = (double)hit_v[c][x] / denom;
         a.edge_tgt[ebase + x] = hit_j[c][x];
-        a.edge_alpha[ebase + x] = (double)hit_v[c][x] / denom;
+        a.edge_alpha[ebase + x] = al;
+        a.pack[ebase + x] = EdgeRec{hit_j[c][x], i, al};
       }
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
     if (live && cnt > a.k_max) a.overflow[b] = 1;
@@ -356,7 +418,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
   if (pl.n_disc == 0) return;
   CorrArgs a{};
-  a.N = p.N; a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.M = p.M; a.k_max = p.k_max; a.Df = pl.Df;
+  a.B = p.B; a.N = p.N; a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.M = p.M; a.k_max = p.k_max; a.Df = pl.Df;
   const bool L = p.variant == FICOCO_VARIANT_L;
   a.mode = p.corr_src == FICOCO_C_ATTN ? (L ? kAttnL : kAttnV) : (L ? kCosL : kCosV);
   a.abar = (const float*)(ws + pl.abar);
@@ -369,9 +431,15 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.dense = pl.dense_rows ? 1 : 0;
   a.rowbuf = (double*)(ws + pl.rowbuf);
   a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha; a.overflow = overflow;
+  a.pack = (EdgeRec*)(ws + pl.edge_pack);
+  a.slot_of = (const int32_t*)(ws + pl.slot_of);
   if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
-    dim3 tgrid((pl.n_disc + kTileCols - 1) / kTileCols, p.B);
-    hipLaunchKernelGGL(corr_attn_tile_kernel, tgrid, dim3(kTileCols * kTileLanes), 0, s, a);
+    const int tiles = (pl.n_disc + kTileCols - 1) / kTileCols;
+    dim3 tgrid(xcd_padded_total(tiles * p.B));
+    const dim3 tb(kTileCols * kTileLanes);
+    if (pl.sel_m <= 2) hipLaunchKernelGGL(corr_attn_tile_kernel<2>, tgrid, tb, 0, s, a);
+    else if (pl.sel_m <= 4) hipLaunchKernelGGL(corr_attn_tile_kernel<4>, tgrid, tb, 0, s, a);
+    else hipLaunchKernelGGL(corr_attn_tile_kernel<8>, tgrid, tb, 0, s, a);
     return;
   }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
@@ -380,3 +448,5 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
 }
 
 }  // namespace ficoco
+
+FICOCO_DBG_READER(corr)

@@ -55,27 +55,33 @@ __device__ __forceinline__ uint64_t score_key(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
 }
 
-// Inclusive scan of one int per thread over the workgroup; returns this thread's inclusive
-// value, *total receives the sum.  scratch: 2 * blockDim.x ints.
+// Inclusive scan of one int per thread over the workgroup (wavefront shuffles, then the
+// wavefront totals through LDS); returns this thread's inclusive value, *total receives the
+// sum.  scratch: at least blockDim.x / 64 ints.
 __device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* total) {
-  const int tid = threadIdx.x, nt = blockDim.x;
-  int* cur = scratch;
-  int* nxt = scratch + nt;
-  __syncthreads();
-  cur[tid] = v;
-  __syncthreads();
-  for (int off = 1; off < nt; off <<= 1) {
-    nxt[tid] = cur[tid] + (tid >= off ? cur[tid - off] : 0);
-    __syncthreads();
-    int* t = cur; cur = nxt; nxt = t;
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave, nw = blockDim.x / kWave;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int t = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += t;
   }
-  const int r = cur[tid];
-  *total = cur[nt - 1];
   __syncthreads();
-  return r;
+  if (lane == kWave - 1) scratch[wv] = incl;
+  __syncthreads();
+  int before = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    const int t = scratch[w];
+    before += w < wv ? t : 0;
+    tot += t;
+  }
+  *total = tot;
+  __syncthreads();
+  return incl + before;
 }
 
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
+  DBG_SPAN(1);
   extern __shared__ double lds_d[];
   double* s = lds_d;                                   // [N] scores, then keys in place
   uint64_t* keys = (uint64_t*)lds_d;
@@ -162,6 +168,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   uint64_t kstar = 0;
   int need = a.n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
   if (a.n_disc > 0) {
+    uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
     for (int pass = 0; pass < 8; ++pass) {
       const int shift = 56 - 8 * pass;
       const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
@@ -188,7 +195,9 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
         if (above < need && need <= above + lsum) {        // exactly one lane
 #pragma unroll
           for (int k = 3; k >= 0; --k) {
-            if (above < need && need <= above + h[k]) { bcast[0] = 4 * tid + k; bcast[1] = need - above; }
+            if (above < need && need <= above + h[k]) {
+              bcast[0] = 4 * tid + k; bcast[1] = need - above; bcast[2] = h[k];
+            }
             above += h[k];
           }
         }
@@ -196,7 +205,37 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       __syncthreads();
       kstar |= (uint64_t)bcast[0] << shift;
       need = bcast[1];
+      const int left = bcast[2];
       __syncthreads();
+      if (left <= kWave && shift > 0) {
+        // Few candidates left: rank them directly in one wavefront instead of more passes.
+        if (tid == 0) bcast[3] = 0;
+        __syncthreads();
+        const uint64_t m2 = ~0ULL << shift;
+        for (int i = tid; i < N; i += nt) {
+          const uint64_t k = keys[i];
+          if ((k & m2) == kstar) { const int slot = atomicAdd(&bcast[3], 1); if (slot < kWave) small[slot] = k; }
+        }
+        __syncthreads();
+        if (tid < kWave) {
+          const uint64_t mine = tid < left ? small[tid] : 0ULL;
+          int greater = 0, equal = 0;
+          for (int l = 0; l < left; ++l) {
+            const uint64_t o = small[l];
+            greater += o > mine ? 1 : 0;
+            equal += o == mine ? 1 : 0;
+          }
+          if (tid < left && greater < need && need <= greater + equal) {   // all such lanes agree
+            small[kWave] = mine;
+            bcast[1] = need - greater;
+          }
+        }
+        __syncthreads();
+        kstar = small[kWave];
+        need = bcast[1];
+        __syncthreads();
+        break;
+      }
     }
   }
   // need = how many tokens with key == kstar are discarded (lowest indices first)
@@ -280,3 +319,5 @@ void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const doub
 }
 
 }  // namespace ficoco
+
+FICOCO_DBG_READER(select)

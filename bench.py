@@ -13,7 +13,9 @@ input sets whose total size exceeds the 256 MB on-die cache so that HBM is reall
 Prints ONE JSON line: tokens/s (B*N input visual tokens per step), plus
   roofline     : the attention-reduction kernel, algorithmic bytes per launch
                  (|A| read + single-precision head-mean map written) over its mean launch
-                 time, measured here with HIP events on the launch stream;
+                 time, measured here with HIP events on the launch stream (kernel alone,
+                 back to back; the event-pair time of the same launch inside the pipelined
+                 steps, which also spans waits for the other stream, is reported beside it);
   cpu_baseline : the CPU oracle timed on this host on a bounded sample of the same batch.
 """
 import argparse
@@ -70,6 +72,9 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run five plain 1 GiB device-to-device copies (a kernel of known traffic "
+                         "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled)")
     ap.add_argument("--streams", type=int, default=2,
                     help="HIP streams the independent steps are issued on, round-robin (each has its own "
                          "workspace and outputs); 1 = strictly one step after the other")
@@ -113,9 +118,26 @@ def main():
     tokens_per_s = B * N / (dt / args.steps)
     assert all(int(b_.overflow.sum().item()) == 0 for b_ in bufs)
 
-    # dominant kernel alone: HIP events on the launch stream around K launches
+    # Dominant kernel inside the same pipelined region: the library records a HIP event pair
+    # around every attention-reduction launch, on the stream the launch goes to.
+    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+             for _ in range(args.steps)]
+    for i, (e0, e1) in enumerate(pairs):            # first record creates the underlying handle
+        e0.record(streams[i % n_str])
+        e1.record(streams[i % n_str])
+    sync()
+    for i in range(args.steps):
+        e0, e1 = pairs[i]
+        ctx.set_reduce_probe(e0.cuda_event, e1.cuda_event)
+        with torch.cuda.stream(streams[i % n_str]):
+            fc.ficoco_v_step(ctx, probs[i % N_SETS], bufs[i % n_str])
+    ctx.set_reduce_probe(None, None)
+    sync()
+    reduce_ms = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / args.steps
+    k_launch = args.steps
+
+    # The same kernel alone on one stream (nothing else on the GPU), for reference.
     stream = torch.cuda.current_stream(dev)
-    k_launch = max(50, min(args.steps, 400))
     for i in range(8):
         fc.ficoco_reduce(ctx, probs[i % N_SETS], buf)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -125,11 +147,11 @@ def main():
         fc.ficoco_reduce(ctx, probs[i % N_SETS], buf)
     e1.record(stream)
     sync()
-    reduce_ms = e0.elapsed_time(e1) / k_launch
+    alone_ms = e0.elapsed_time(e1) / k_launch
     a_bytes = B * H * (N + 1) * (N + 1) * 2
     abar_bytes = B * N * N * 4
     algo_bytes = a_bytes + abar_bytes
-    achieved = algo_bytes / (reduce_ms * 1e-3) / 1e9
+    achieved = algo_bytes / (alone_ms * 1e-3) / 1e9
     step_bytes = algo_bytes + B * (N + 1) * D * 2 + B * (N_KEEP + 1) * D * 2 + B * (N - N_KEEP) * N_KEEP * 4
 
     out = {
@@ -147,8 +169,19 @@ def main():
         "roofline": {"kernel": "attn_reduce_kernel<bf16>", "bound": "hbm", "achieved": achieved,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
                      "traffic": traffic_from_profiles(), "algorithmic_bytes": algo_bytes,
-                     "avg_launch_us": reduce_ms * 1e3, "launches_timed": k_launch},
+                     "avg_launch_us": alone_ms * 1e3, "launches_timed": k_launch,
+                     "timed_how": "HIP event pair around %d back-to-back launches of the kernel alone on "
+                                  "the launch stream, inputs rotating" % k_launch,
+                     "in_pipeline_event_us": reduce_ms * 1e3},
     }
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            dst.copy_(src)
+        sync()
+        del src, dst
 
     if not args.no_cpu_baseline:
         from oracle import ficoco_oracle as O

@@ -133,6 +133,15 @@ int ficoco_destroy(ficoco_ctx *ctx);
 const char *ficoco_last_error(const ficoco_ctx *ctx);
 const char *ficoco_version(void);
 
+/*
+ * Measurement hook (not part of the paper's method).  With two non-NULL hipEvent_t handles
+ * (created by the caller with timing enabled, passed as void*), every following
+ * ficoco_reduce / ficoco_*_step call on this ctx records `start` immediately before and
+ * `stop` immediately after the attention-reduction launch, on that call's stream, so the
+ * dominant kernel can be timed inside a running pipeline.  NULL, NULL switches it off.
+ */
+int ficoco_set_reduce_probe(ficoco_ctx *ctx, void *start_event, void *stop_event);
+
 /* Bytes of device workspace the calls below need for this problem (256-byte aligned
  * pointer expected).  The workspace carries state from one stage to the next: the stage
  * functions must be called in order, on one stream, with the same problem and workspace. */

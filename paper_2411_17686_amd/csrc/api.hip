@@ -9,6 +9,7 @@
 
 struct ficoco_ctx {
   int device;
+  hipEvent_t probe_start, probe_stop;   // measurement hook, both null when off
   char err[512];
 };
 
@@ -195,7 +196,9 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   const ficoco_problem& p = *p0;
   hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
+  if (ctx->probe_start) (void)hipEventRecord(ctx->probe_start, s);
   launch_attn_reduce(p, pl, w, s);
+  if (ctx->probe_stop) (void)hipEventRecord(ctx->probe_stop, s);
   if (pl.need_features) launch_features(p, pl, w, s);
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true, s);
@@ -217,6 +220,8 @@ int ficoco_create(ficoco_ctx** out, int device) {
   ficoco_ctx* c = new (std::nothrow) ficoco_ctx;
   if (!c) return FICOCO_ENOMEM;
   c->device = device;
+  c->probe_start = nullptr;
+  c->probe_stop = nullptr;
   c->err[0] = 0;
   *out = c;
   return FICOCO_OK;
@@ -228,6 +233,13 @@ int ficoco_destroy(ficoco_ctx* ctx) {
 }
 
 const char* ficoco_last_error(const ficoco_ctx* ctx) { return ctx ? ctx->err : "ctx is NULL"; }
+
+int ficoco_set_reduce_probe(ficoco_ctx* ctx, void* start_event, void* stop_event) {
+  if (!ctx || ((start_event == nullptr) != (stop_event == nullptr))) return FICOCO_EINVAL;
+  ctx->probe_start = (hipEvent_t)start_event;
+  ctx->probe_stop = (hipEvent_t)stop_event;
+  return FICOCO_OK;
+}
 
 const char* ficoco_version(void) { return "ficoco-gfx950 0.1"; }
 
@@ -245,7 +257,9 @@ int ficoco_reduce(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_
   Plan pl;
   const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_reduce");
   if (rc != FICOCO_OK) return rc;
+  if (ctx->probe_start) (void)hipEventRecord(ctx->probe_start, (hipStream_t)stream);
   launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
+  if (ctx->probe_stop) (void)hipEventRecord(ctx->probe_stop, (hipStream_t)stream);
   return finish(ctx, "ficoco_reduce");
 }
 

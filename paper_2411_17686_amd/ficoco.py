@@ -20,7 +20,7 @@ G_CLS_ATTN, G_TEXT_ATTN, G_VECTOR, G_EQ_TOKEN = 0, 1, 2, 3
 C_ATTN, C_COSINE = 0, 1
 
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
-           "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
+           "ficoco_set_reduce_probe", "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
            "ficoco_compress", "ficoco_v_step", "ficoco_l_step"]
 
 
@@ -67,6 +67,7 @@ def lib():
         L.ficoco_last_error.argtypes = [C.c_void_p]
         L.ficoco_last_error.restype = C.c_char_p
         L.ficoco_version.restype = C.c_char_p
+        L.ficoco_set_reduce_probe.argtypes = [vp, vp, vp]
         L.ficoco_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
         L.ficoco_reduce.argtypes = [vp, pp, vp, C.c_size_t, vp]
         L.ficoco_score.argtypes = [vp, pp, vp, C.c_size_t, f64p, vp]
@@ -124,6 +125,10 @@ class Context:
     def check(self, rc):
         if rc != OK:
             raise FicocoError(rc, lib().ficoco_last_error(self._h).decode())
+
+    def set_reduce_probe(self, start_event=None, stop_event=None):
+        """Raw hipEvent_t handles (ints) or None, None; see ficoco_set_reduce_probe."""
+        self.check(lib().ficoco_set_reduce_probe(self._h, start_event, stop_event))
 
     def stream(self):
         return C.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)

@@ -123,23 +123,43 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-#ifndef FICOCO_MERGE_SLICE
-#define FICOCO_MERGE_SLICE 2
-#endif
-#ifndef FICOCO_SCAN_BLOCKS
-#define FICOCO_SCAN_BLOCKS 2
-#endif
-constexpr int kMergeSlice = FICOCO_MERGE_SLICE;   // 8-element vectors per lane per pass over the feature axis
+constexpr int kMergeSlice = 2;    // 8-element vectors per lane per pass over the feature axis
+constexpr int kMatchCap = 32;     // sources of one target kept in LDS by the matching merge
+
+// Accumulate w * X[src] into num (this lane's slices of the current feature span).
+template <typename T>
+__device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int i, double w, int d0, int lane,
+                                           const bool (&full)[kMergeSlice], double (&num)[kMergeSlice][kVec]) {
+  i = min(max(i, 0), a.N - 1);                 // index sets are device data: stay inside the span
+  const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+#pragma unroll
+  for (int u = 0; u < kMergeSlice; ++u) {
+    const int d = d0 + (u * kWave + lane) * kVec;
+    if (full[u]) {
+      double v[kVec];
+      load8<T>(xs + d, v);
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) num[u][k] += w * v[k];
+    } else {
+      for (int k = 0; k < kVec; ++k)
+        if (d + k < a.D) num[u][k] += w * widen(xs[d + k]);
+    }
+  }
+}
 
 // One wavefront per output row.  MATCH = false: the sources of a preserved token come from
 // the inverted edge lists.  MATCH = true (few discarded tokens): no inversion kernel; the
-// wavefront scans the per-source edge lists itself, 64 discarded rows at a time, and takes
-// the rows that name its target -- in ascending row order, so the sum order is the same.
+// wavefront scans the packed per-source edge records once, 64 discarded rows per load,
+// keeps the rows that name its target in LDS (ascending row order, so the sum order is the
+// same) and then streams the feature axis.  More than kMatchCap sources for one target fall
+// back to re-scanning per feature span.
 template <typename T, bool MATCH>
 __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   DBG_SPAN(3);
-  const int lane = threadIdx.x % kWave;
-  const int r = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  __shared__ int m_src[4][kMatchCap];
+  __shared__ double m_w[4][kMatchCap];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int r = blockIdx.x * (blockDim.x / kWave) + wv;
   const int64_t b = blockIdx.y;
   if (r >= a.n_out) return;
   const T* Xb = (const T*)a.X + b * a.xsb;
@@ -163,12 +183,53 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   const T* x = Xb + (int64_t)t * a.xsn;
   const int Dv = a.D - a.D % kVec;
   const bool merged_row = j >= 0 && a.n_disc > 0;
-  if (!merged_row || (!MATCH && e0 == e1)) {  // nothing merged into this row: exact copy
+
+  // ---- sources of this target -------------------------------------------------------------
+  int n_src = 0;          // matches found (MATCH) / list length (!MATCH)
+  double den = 1.0;
+  if (merged_row && MATCH) {
+    for (int base = 0; base < a.n_disc; base += kWave) {
+      const int row = base + lane;
+      const bool in = row < a.n_disc;
+      const int64_t rr = b * a.n_disc + (in ? row : 0);
+      const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
+      int t0, src;
+      double w;
+      if (a.pack) {
+        const EdgeRec e = a.pack[rr * a.k_max];
+        t0 = e.tgt; src = e.src; w = e.alpha;
+      } else {
+        t0 = a.edge_tgt[rr * a.k_max];
+        src = a.S[rr];
+        w = 0.0;
+      }
+      int he = (cnt > 0 && t0 == j) ? 0 : -1;
+      for (int e = 1; e < cnt; ++e)
+        if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
+      const bool hit = he >= 0;
+      if (hit && (he > 0 || !a.pack)) w = a.edge_alpha[rr * a.k_max + he];
+      const unsigned long long m = __ballot(hit);
+      if (hit) {
+        const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
+        if (slot < kMatchCap) { m_src[wv][slot] = src; m_w[wv][slot] = w; }
+      }
+      n_src += __popcll(m);
+    }
+  } else if (merged_row) {
+    n_src = e1 - e0;
+  }
+  if (!merged_row || n_src == 0) {  // nothing merged into this row: exact copy
     for (int d = lane * kVec; d < Dv; d += kWave * kVec) copy8<T>(x + d, out + d);
     for (int d = Dv + lane; d < a.D; d += kWave) out[d] = x[d];
     return;
   }
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+  const bool listed = MATCH && n_src <= kMatchCap;
+  if (listed)
+    for (int e = 0; e < n_src; ++e) den += m_w[wv][e];
+  else if (!MATCH)
+    for (int e = e0; e < e1; ++e) den += a.tgt_alpha[ebase + e];
+
   constexpr int kSpan = kWave * kVec * kMergeSlice;           // features per pass
   for (int d0 = 0; d0 < a.D; d0 += kSpan) {
     double num[kMergeSlice][kVec];
@@ -181,79 +242,39 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
       else
         for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
     }
-    double den = 1.0;
-    bool any = false;
-    auto add_source = [&](int i, double w) {
-      i = min(max(i, 0), a.N - 1);
-      const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
-      den += w;
-      any = true;
-#pragma unroll
-      for (int u = 0; u < kMergeSlice; ++u) {
-        const int d = d0 + (u * kWave + lane) * kVec;
-        if (full[u]) {
-          double v[kVec];
-          load8<T>(xs + d, v);
-#pragma unroll
-          for (int k = 0; k < kVec; ++k) num[u][k] += w * v[k];
-        } else {
-          for (int k = 0; k < kVec; ++k)
-            if (d + k < a.D) num[u][k] += w * widen(xs[d + k]);
-        }
-      }
-    };
-    if (MATCH) {
-      // kScanBlocks x 64 discarded rows per round, all loads of a round issued together.
-      constexpr int kScanBlocks = FICOCO_SCAN_BLOCKS;
-      for (int base = 0; base < a.n_disc; base += kWave * kScanBlocks) {
-        int cnt[kScanBlocks], t0[kScanBlocks], src[kScanBlocks];
-        double w0[kScanBlocks];
-#pragma unroll
-        for (int u = 0; u < kScanBlocks; ++u) {
-          const int row = base + u * kWave + lane;
-          const bool in = row < a.n_disc;
-          const int64_t rr = b * a.n_disc + (in ? row : 0);
-          cnt[u] = in ? min(a.edge_cnt[rr], a.k_max) : 0;
-          if (a.pack) {
-            const EdgeRec e = a.pack[rr * a.k_max];
-            t0[u] = e.tgt; src[u] = e.src; w0[u] = e.alpha;
-          } else {
-            t0[u] = a.edge_tgt[rr * a.k_max];
-            src[u] = a.S[rr];
-            w0[u] = 0.0;
-          }
-        }
-#pragma unroll
-        for (int u = 0; u < kScanBlocks; ++u) {
-          if (base + u * kWave >= a.n_disc) break;     // uniform
-          const int64_t rr = b * a.n_disc + min(base + u * kWave + lane, a.n_disc - 1);
-          int he = (cnt[u] > 0 && t0[u] == j) ? 0 : -1;
-          for (int e = 1; e < cnt[u]; ++e)
-            if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
-          const bool hit = he >= 0;
-          double w = w0[u];
-          if (hit && (he > 0 || !a.pack)) w = a.edge_alpha[rr * a.k_max + he];
-          unsigned long long m = __ballot(hit);
-          while (m) {
-            const int l = __ffsll(m) - 1;
-            m &= m - 1;
-            add_source(__shfl(src[u], l, kWave), __shfl(w, l, kWave));
-          }
-        }
-      }
-    } else {
+    if (listed) {
+      for (int e = 0; e < n_src; ++e) add_source<T>(a, Xb, m_src[wv][e], m_w[wv][e], d0, lane, full, num);
+    } else if (!MATCH) {
       for (int e = e0; e < e1; ++e)
-        add_source(a.S[b * a.n_disc + a.tgt_src[ebase + e]], a.tgt_alpha[ebase + e]);
+        add_source<T>(a, Xb, a.S[b * a.n_disc + a.tgt_src[ebase + e]], a.tgt_alpha[ebase + e], d0, lane, full, num);
+    } else {
+      // more sources than the LDS list holds: scan again for every feature span
+      double dsum = 1.0;
+      for (int base = 0; base < a.n_disc; base += kWave) {
+        const int row = base + lane;
+        const bool in = row < a.n_disc;
+        const int64_t rr = b * a.n_disc + (in ? row : 0);
+        const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
+        int he = -1;
+        for (int e = 0; e < cnt; ++e)
+          if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
+        const double w = he >= 0 ? a.edge_alpha[rr * a.k_max + he] : 0.0;
+        const int src = a.S[rr];
+        unsigned long long m = __ballot(he >= 0);
+        while (m) {
+          const int l = __ffsll(m) - 1;
+          m &= m - 1;
+          const double wl = __shfl(w, l, kWave);
+          dsum += wl;
+          add_source<T>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+        }
+      }
+      den = dsum;
     }
 #pragma unroll
     for (int u = 0; u < kMergeSlice; ++u) {
       const int d = d0 + (u * kWave + lane) * kVec;
-      if (!any) {   // no source names this target: exact copy
-        if (full[u]) copy8<T>(x + d, out + d);
-        else
-          for (int k = 0; k < kVec; ++k)
-            if (d + k < a.D) out[d + k] = x[d + k];
-      } else if (full[u]) {
+      if (full[u]) {
         Pack8<T> o;
 #pragma unroll
         for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[u][k] / den);

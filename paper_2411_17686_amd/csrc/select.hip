@@ -93,6 +93,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = a.N;
 
+  DBG_PHASE(0);
   if (a.do_score) {
     for (int i = tid; i < N; i += nt) {
       double R, G;
@@ -128,6 +129,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       }
       s[i] = a.w * R - (1.0 - a.w) * G;
     }
+    DBG_PHASE(1);
     if (a.window > 0) {
       const int cells = a.grid_g * a.grid_h * a.grid_w;
       for (int c = tid; c < cells; c += nt) owner[c] = -1;
@@ -158,6 +160,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   } else {
     for (int i = tid; i < N; i += nt) s[i] = a.scores[(int64_t)b * N + i];
   }
+  DBG_PHASE(2);
   if (!a.do_filter) return;
   if (a.overflow && tid == 0) a.overflow[b] = 0;
   __syncthreads();
@@ -238,6 +241,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       }
     }
   }
+  DBG_PHASE(3);
   // need = how many tokens with key == kstar are discarded (lowest indices first)
 
   // ---- flags and ordered compaction -----------------------------------------------------------
@@ -260,6 +264,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   }
   int d_pos = block_scan_inclusive(n_dis, scan, &tot) - n_dis;   // discarded tokens before `lo`
   int k_pos = lo - d_pos;                                         // preserved tokens before `lo`
+  DBG_PHASE(4);
   const int n_keep = N - a.n_disc;
   for (int i = lo; i < hi; ++i) {
     if (dis_mask & (1u << (i - lo))) {
@@ -272,6 +277,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       ++k_pos;
     }
   }
+  DBG_PHASE(5);
 }
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {

@@ -1,21 +1,29 @@
 #!/usr/bin/env python3
-"""Benchmark of the fused FiCoCo-V step on one MI355X.
+"""Benchmark of the fused FiCoCo step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 1]
 
-Workload (BASELINE config 1, step 1 -- the shape the metric is quoted on): B = 16 images,
-[CLS] + 24x24 patches (N = 576), D = 1024, 16 heads, bfloat16; keep 384 of 576.  One
-"step" is one call of ficoco_v_step on the whole batch: attention reduction, score + local
-penalty, top-K filter, correlate / threshold / weights, compress.  Inputs are synthetic,
-seeded, resident in HBM before the timed region; the step rotates over several distinct
-input sets whose total size exceeds the 256 MB on-die cache so that HBM is really read.
+Default workload (BASELINE config 1, step 1 -- the shape the metric is quoted on): B = 16
+images, [CLS] + 24x24 patches (N = 576), D = 1024, 16 heads, bfloat16; keep 384 of 576.  One
+"step" is one call of ficoco_v_step / ficoco_l_step on the whole batch: attention reduction,
+score + local penalty, top-K filter, correlate / threshold / weights, compress.  Inputs are
+synthetic, seeded, resident in HBM before the timed region; steps rotate over several distinct
+input sets whose total size exceeds the 256 MB on-die cache, and alternate between two HIP
+streams (independent batches: the latency-bound tail of one step overlaps the bandwidth-bound
+head of the next; --streams 1 runs them strictly one after the other).
+
+Other workloads: --config 0, 2, 3 (decoder, no visual->visual map: mean-cosine + cosine
+correlation), 3p (decoder with the causal visual->visual map: Algorithm 2 as printed), 4
+(video, vectors + cosine correlation), 1c (config 1 tokens with the cosine correlation).
 
 Prints ONE JSON line: tokens/s (B*N input visual tokens per step), plus
-  roofline     : the attention-reduction kernel, algorithmic bytes per launch
-                 (|A| read + single-precision head-mean map written) over its mean launch
-                 time, measured here with HIP events on the launch stream (kernel alone,
-                 back to back; the event-pair time of the same launch inside the pipelined
-                 steps, which also spans waits for the other stream, is reported beside it);
+  roofline     : the dominant kernel -- the attention-reduction kernel (HBM bound: |A| read +
+                 single-precision head-mean map written, per launch) or, for the cosine
+                 workloads, the bf16 MFMA tile kernel (2*B*N^S*N^T*D flops per launch) -- over
+                 its mean launch time, measured here with HIP event pairs that the library
+                 records around that launch on the launch stream, in a loop of that stage alone;
+                 the event-pair time of the same launch inside the pipelined steps (which also
+                 spans waits for the other stream) is reported beside it;
   cpu_baseline : the CPU oracle timed on this host on a bounded sample of the same batch.
 """
 import argparse
@@ -29,33 +37,118 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-B, GRID, D, H, N_KEEP = 16, 24, 1024, 16, 384
-N = GRID * GRID
-N_SETS = 4
+MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def make_sets(device, n_sets):
-    """Config-1 recipe drawn on the GPU (bf16 clustered tokens, softmax of N(0,1.5^2) logits)."""
-    import torch
-    sets = []
-    g = torch.Generator(device=device)
-    g.manual_seed(1)
-    for _ in range(n_sets):
-        centres = torch.randn(B, 64, D, device=device, generator=g)
-        pick = torch.randint(0, 64, (B, N), device=device, generator=g)
-        X = torch.empty(B, N + 1, D, device=device)
-        X[:, 0] = torch.randn(B, D, device=device, generator=g)
-        X[:, 1:] = torch.gather(centres, 1, pick[..., None].expand(B, N, D)) \
-            + 0.3 * torch.randn(B, N, D, device=device, generator=g)
-        A = torch.empty(B, H, N + 1, N + 1, device=device, dtype=torch.bfloat16)
-        for b in range(B):
-            A[b] = torch.softmax(1.5 * torch.randn(H, N + 1, N + 1, device=device, generator=g), -1).to(torch.bfloat16)
-        sets.append((X.to(torch.bfloat16).contiguous(), A))
-    return sets
+def _clustered(torch, g, dev, B, n, D, centres, noise=0.3):
+    c = torch.randn(B, centres, D, device=dev, generator=g)
+    pick = torch.randint(0, centres, (B, n), device=dev, generator=g)
+    return torch.gather(c, 1, pick[..., None].expand(B, n, D)) + noise * torch.randn(B, n, D, device=dev, generator=g)
+
+
+def _softmax_map(torch, g, dev, B, H, nq, nk, sigma, dt, mask=None, cols=None):
+    out = torch.empty(B, H, nq, (cols[1] - cols[0]) if cols else nk, device=dev, dtype=dt)
+    for b in range(B):
+        logits = sigma * torch.randn(H, nq, nk, device=dev, generator=g)
+        if mask is not None:
+            logits.masked_fill_(mask, float("-inf"))
+        p = torch.softmax(logits, -1)
+        out[b] = (p[..., cols[0]:cols[1]] if cols else p).to(dt)
+    return out
+
+
+def make_workload(torch, fc, name, dev):
+    """The BASELINE recipes drawn on the GPU (same distributions as the seeded CPU generators the
+    parity tests use; several large input sets are needed quickly here)."""
+    g = torch.Generator(device=dev)
+    bf, f32 = torch.bfloat16, torch.float32
+    W = dict(name=name)
+    if name in ("1", "1c", "0", "2"):
+        B, grid_g, H, D = {"1": (16, 1, 16, 1024), "1c": (16, 1, 16, 1024), "0": (1, 1, 16, 1024),
+                           "2": (4, 5, 16, 1024)}[name]
+        N = grid_g * 576
+        keep = {"1": 384, "1c": 384, "0": 192, "2": 640}[name]
+        dt = f32 if name == "0" else bf
+        centres = {"1": 64, "1c": 64, "0": 48, "2": 200}[name]
+        sigma = 1.5 if name in ("1", "1c") else 1.0
+        n_sets = {"1": 4, "1c": 4, "0": 16, "2": 1}[name]
+        g.manual_seed({"1": 1, "1c": 1, "0": 0, "2": 2}[name])
+        sets = []
+        for _ in range(n_sets):
+            X = torch.empty(B, N + 1, D, device=dev)
+            X[:, 0] = torch.randn(B, D, device=dev, generator=g)
+            X[:, 1:] = _clustered(torch, g, dev, B, N, D, centres)
+            A = _softmax_map(torch, g, dev, B, H, N + 1, N + 1, sigma, dt)
+            sets.append(dict(X=X.to(dt).contiguous(), A=A))
+        es = 2 if dt == bf else 4
+        W.update(label="BASELINE config %s: FiCoCo-V fused step, B=%d, [CLS]+%d patches, D=%d, H=%d, %s, keep %d%s"
+                 % (name[0] + (" step 1" if name[0] == "1" else ""), B, N, D, H, "bf16" if dt == bf else "f32", keep,
+                    ", cosine correlation variant" if name == "1c" else ""),
+                 B=B, N=N, D=D, H=H, keep=keep, dtype="bf16" if dt == bf else "f32", variant=fc.VARIANT_V, sets=sets,
+                 kw=dict(vis_begin=1, N=N, n_keep=keep, cls_index=0, grid=(grid_g, 24, 24), window=2,
+                         penalty_coef=2.0, w_score=0.35, eps=0.998, k_max=8,
+                         corr_src=fc.C_COSINE if name == "1c" else fc.C_ATTN),
+                 dominant="gram" if name == "1c" else "reduce",
+                 reduce_bytes=B * H * (N + 1) * (N + 1) * es + (0 if name == "1c" else B * N * N * 4),
+                 gram_flops=2.0 * B * (N - keep) * keep * D,
+                 step_bytes=B * H * (N + 1) * (N + 1) * es + B * N * N * 4 + B * (N + 1) * D * es
+                 + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name != "1c" else None)
+    elif name in ("3", "3p"):
+        B, n_sys, N, M, D, H, keep = 8, 35, 576, 64, 4096, 32, 144
+        n_tot = n_sys + N + M
+        g.manual_seed(3)
+        sets = []
+        keys = torch.arange(n_sys + N, device=dev)
+        mask = (keys[None, :] > (n_sys + torch.arange(N, device=dev))[:, None])[None]
+        for _ in range(3):
+            X = torch.randn(B, n_tot, D, device=dev, generator=g)
+            X[:, n_sys:n_sys + N] = _clustered(torch, g, dev, B, N, D, 96)
+            A_tv = _softmax_map(torch, g, dev, B, H, M, n_tot, 1.0, bf, cols=(n_sys, n_sys + N))
+            st = dict(X=X.to(bf).contiguous(), A_text=A_tv)
+            if name == "3p":
+                st["A"] = _softmax_map(torch, g, dev, B, H, N, n_sys + N, 1.0, bf, mask=mask, cols=(n_sys, n_sys + N))
+            sets.append(st)
+        W.update(label="BASELINE config 3%s: FiCoCo-L fused step, B=8, 35 system + 576 visual + 64 text tokens, "
+                       "D=4096, H=32, bf16, keep 144%s"
+                       % ("'" if name == "3p" else "", " (with the causal visual->visual map)" if name == "3p"
+                          else " (no visual->visual map: mean-cosine + cosine correlation)"),
+                 B=B, N=N, D=D, H=H, keep=keep, dtype="bf16", variant=fc.VARIANT_L, sets=sets,
+                 kw=dict(vis_begin=n_sys, N=N, n_keep=keep, a_q_begin=n_sys, a_k_begin=n_sys, at_k_begin=n_sys,
+                         w_score=0.6, gamma=0.6, eps=0.998, k_max=8, window=0, sem_src=fc.G_TEXT_ATTN,
+                         red_src=fc.R_ATTN_RECV if name == "3p" else fc.R_SIM_MEAN,
+                         corr_src=fc.C_ATTN if name == "3p" else fc.C_COSINE),
+                 dominant="reduce" if name == "3p" else "gram",
+                 reduce_bytes=B * H * N * N * 2 + B * N * N * 4,
+                 gram_flops=2.0 * B * (N - keep) * keep * D, step_bytes=None)
+    elif name == "4":
+        B, frames, D, H, keep = 1, 16, 1024, 16, 1152
+        N = frames * 576
+        g.manual_seed(4)
+        sets = []
+        for _ in range(12):
+            f = _clustered(torch, g, dev, 1, 576, D, 64)[0]
+            X = torch.empty(B, N, D, device=dev)
+            for t in range(frames):
+                if t:
+                    f = f + 0.1 * torch.randn(576, D, device=dev, generator=g)
+                X[0, t * 576:(t + 1) * 576] = f
+            rv = torch.softmax(torch.randn(B, H, N, device=dev, generator=g), -1).to(bf)
+            sv = torch.softmax(torch.randn(B, H, N, device=dev, generator=g), -1).to(bf)
+            sets.append(dict(X=X.to(bf).contiguous(), recv_vec=rv, sem_vec=sv))
+        W.update(label="BASELINE config 4: FiCoCo-V fused step, B=1, 16 frames x 576 = 9216 tokens, D=1024, bf16, "
+                       "per-head received / semantic vectors, cosine correlation on the matrix cores, keep 1152",
+                 B=B, N=N, D=D, H=H, keep=keep, dtype="bf16", variant=fc.VARIANT_V, sets=sets,
+                 kw=dict(vis_begin=0, N=N, n_keep=keep, cls_index=-1, grid=(frames, 24, 24), window=2,
+                         penalty_coef=2.0, w_score=0.35, eps=0.998, k_max=8, red_src=fc.R_VECTOR,
+                         sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE),
+                 dominant="gram", reduce_bytes=None, gram_flops=2.0 * B * (N - keep) * keep * D, step_bytes=None)
+    else:
+        sys.exit("bench.py: unknown --config %r" % name)
+    return W
 
 
 def traffic_from_profiles():
-    """HBM bytes per launch of the reduction kernel from the committed counter summary."""
+    """HBM bytes per launch of the reduction kernel (config 1) from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", "attn_reduce_c1_step1_pmc.txt")
     try:
         for line in open(path):
@@ -66,11 +159,54 @@ def traffic_from_profiles():
     return None
 
 
+def cpu_baseline(W, seconds=12.0):
+    from oracle import ficoco_oracle as O
+    from paper_2411_17686_amd import ficoco as fc
+    from paper_2411_17686_amd.synth import to_numpy
+    st, kw = W["sets"][0], W["kw"]
+    n_img = min(2, W["B"])
+
+    def host(k, b):
+        return None if st.get(k) is None else O.widen(to_numpy(st[k][b]))
+
+    X = [host("X", b) for b in range(n_img)]
+    A = [host("A", b) for b in range(n_img)]
+    At = [host("A_text", b) for b in range(n_img)]
+    rv = [host("recv_vec", b) for b in range(n_img)]
+    sv = [host("sem_vec", b) for b in range(n_img)]
+    red = {fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}[kw.get("red_src", fc.R_ATTN_RECV)]
+    cor = {fc.C_ATTN: "attn", fc.C_COSINE: "cosine"}[kw.get("corr_src", fc.C_ATTN)]
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        for b in range(n_img):
+            if W["variant"] == fc.VARIANT_V:
+                sem = {fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector"}[kw.get("sem_src", fc.G_CLS_ATTN)]
+                O.v_step(X[b], A[b], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"], N=kw["N"],
+                         n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2, coef=2.0,
+                         recv_vec=rv[b], sem_vec=sv[b], red_src=red, sem_src=sem, corr_src=cor)
+            else:
+                O.l_step(X[b], A[b], At[b], vis_begin=kw["vis_begin"], N=kw["N"], n_keep=kw["n_keep"],
+                         beta=kw["w_score"], gamma=kw["gamma"], eps=kw["eps"], red_src=red, corr_src=cor)
+        reps += 1
+        el = time.perf_counter() - t0
+        if el > seconds:
+            break
+    cores = 1
+    if cor == "cosine" or red == "sim_mean":      # those steps call float64 matrix products (BLAS thread pool)
+        import threadpoolctl
+        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    return {"value": reps * n_img * W["N"] / el, "unit": "tokens/s", "cores": cores, "kind": "oracle",
+            "sample": "%d of the %d sequences of input set 0, %d passes of the float64 numpy oracle, %.1f s%s"
+                      % (n_img, W["B"], reps, el, "" if cores == 1 else " (its matrix products use the BLAS thread pool)")}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 2, 3, 3p, 4")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run five plain 1 GiB device-to-device copies (a kernel of known traffic "
@@ -89,24 +225,27 @@ def main():
     dev = torch.device("cuda", 0)
     torch.cuda.set_device(dev)
     ctx = fc.Context(0)
-    sets = make_sets(dev, N_SETS)
-    probs = [fc.make_problem(X, variant=fc.VARIANT_V, vis_begin=1, N=N, n_keep=N_KEEP, A=A, cls_index=0,
-                             grid=(1, GRID, GRID), window=2, penalty_coef=2.0, w_score=0.35, eps=0.998,
-                             k_max=8) for X, A in sets]
-    buf = fc.Buffers(probs[0], dev, torch.bfloat16)
+    W = make_workload(torch, fc, args.config, dev)
+    n_sets = len(W["sets"])
+    probs = [fc.make_problem(st["X"], variant=W["variant"], A=st.get("A"), A_text=st.get("A_text"),
+                             recv_vec=st.get("recv_vec"), sem_vec=st.get("sem_vec"), H=W["H"], **W["kw"])
+             for st in W["sets"]]
+    tdt = torch.bfloat16 if W["dtype"] == "bf16" else torch.float32
     n_str = max(1, args.streams)
     streams = [torch.cuda.Stream(device=dev) for _ in range(n_str)]        # default priority
-    bufs = [buf] + [fc.Buffers(probs[0], dev, torch.bfloat16) for _ in range(n_str - 1)]
+    bufs = [fc.Buffers(probs[0], dev, tdt) for _ in range(n_str)]
+    step_fn = fc.ficoco_v_step if W["variant"] == fc.VARIANT_V else fc.ficoco_l_step
+    sync = torch.cuda.synchronize
 
-    def sync():
-        torch.cuda.synchronize()
-
-    def run_steps(k):
-        # Successive steps are independent batches: step i goes to stream i mod n_str, so the
-        # latency-bound tail of one step overlaps the bandwidth-bound head of the next.
+    def run_steps(k, probe=None):
+        # Successive steps are independent batches: step i goes to stream i mod n_str.
         for i in range(k):
+            if probe is not None:
+                ctx.set_probe(probe[0], probe[1][i][0].cuda_event, probe[1][i][1].cuda_event)
             with torch.cuda.stream(streams[i % n_str]):
-                fc.ficoco_v_step(ctx, probs[i % N_SETS], bufs[i % n_str])
+                step_fn(ctx, probs[i % n_sets], bufs[i % n_str])
+        if probe is not None:
+            ctx.set_probe(probe[0], None, None)
 
     run_steps(args.warmup)
     sync()
@@ -115,65 +254,76 @@ def main():
     sync()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    tokens_per_s = B * N / (dt / args.steps)
+    tokens_per_s = W["B"] * W["N"] / (dt / args.steps)
     assert all(int(b_.overflow.sum().item()) == 0 for b_ in bufs)
 
-    # Dominant kernel inside the same pipelined region: the library records a HIP event pair
-    # around every attention-reduction launch, on the stream the launch goes to.
-    pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(args.steps)]
-    for i, (e0, e1) in enumerate(pairs):            # first record creates the underlying handle
-        e0.record(streams[i % n_str])
-        e1.record(streams[i % n_str])
-    sync()
-    for i in range(args.steps):
-        e0, e1 = pairs[i]
-        ctx.set_reduce_probe(e0.cuda_event, e1.cuda_event)
-        with torch.cuda.stream(streams[i % n_str]):
-            fc.ficoco_v_step(ctx, probs[i % N_SETS], bufs[i % n_str])
-    ctx.set_reduce_probe(None, None)
-    sync()
-    reduce_ms = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / args.steps
-    k_launch = args.steps
+    # Dominant kernel: event pairs recorded by the library around its launch.
+    kind = fc.PROBE_REDUCE if W["dominant"] == "reduce" else fc.PROBE_GRAM
 
-    # The same kernel alone on one stream (nothing else on the GPU), for reference.
-    stream = torch.cuda.current_stream(dev)
-    for i in range(8):
-        fc.ficoco_reduce(ctx, probs[i % N_SETS], buf)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    def event_pairs(n):
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        for i, (e0, e1) in enumerate(pairs):            # the first record creates the underlying handle
+            e0.record(streams[i % n_str])
+            e1.record(streams[i % n_str])
+        sync()
+        return pairs
+
+    pairs = event_pairs(args.steps)
+    run_steps(args.steps, probe=(kind, pairs))          # (i) inside the pipelined steps
     sync()
-    e0.record(stream)
-    for i in range(k_launch):
-        fc.ficoco_reduce(ctx, probs[i % N_SETS], buf)
-    e1.record(stream)
+    in_pipe_ms = sum(e0.elapsed_time(e1) for e0, e1 in pairs) / args.steps
+
+    k_launch = args.steps                               # (ii) that stage alone on one stream
+    pairs = event_pairs(k_launch)
+    buf = bufs[0]
+    with torch.cuda.stream(streams[0]):
+        if kind == fc.PROBE_GRAM:                       # the correlate stage needs the earlier stages' state
+            fc.ficoco_score(ctx, probs[0], buf)
+            fc.ficoco_filter(ctx, probs[0], buf)
+        for i in range(k_launch):
+            ctx.set_probe(kind, pairs[i][0].cuda_event, pairs[i][1].cuda_event)
+            if kind == fc.PROBE_REDUCE:
+                fc.ficoco_reduce(ctx, probs[i % n_sets], buf)
+            else:
+                fc.ficoco_correlate(ctx, probs[0], buf)
+        ctx.set_probe(kind, None, None)
     sync()
-    alone_ms = e0.elapsed_time(e1) / k_launch
-    a_bytes = B * H * (N + 1) * (N + 1) * 2
-    abar_bytes = B * N * N * 4
-    algo_bytes = a_bytes + abar_bytes
-    achieved = algo_bytes / (alone_ms * 1e-3) / 1e9
-    step_bytes = algo_bytes + B * (N + 1) * D * 2 + B * (N_KEEP + 1) * D * 2 + B * (N - N_KEEP) * N_KEEP * 4
+    alone = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
+    alone_ms = sum(alone) / len(alone)
+
+    if W["dominant"] == "reduce":
+        algo = W["reduce_bytes"]
+        achieved = algo / (alone_ms * 1e-3) / 1e9
+        roof = {"kernel": "attn_reduce_kernel<%s>" % W["dtype"], "bound": "hbm", "achieved": achieved,
+                "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                "traffic": traffic_from_profiles() if args.config == "1" else None, "algorithmic_bytes": algo}
+    else:
+        algo = W["gram_flops"]
+        achieved = algo / (alone_ms * 1e-3) / 1e12
+        roof = {"kernel": "gram_tile_kernel (bf16 MFMA 32x32x16)", "bound": "mfma", "achieved": achieved,
+                "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS,
+                "traffic": None, "algorithmic_flops": algo}
+    roof.update({"avg_launch_us": alone_ms * 1e3, "median_launch_us": alone[len(alone) // 2] * 1e3,
+                 "launches_timed": k_launch,
+                 "timed_how": "HIP event pair recorded by the library around each of %d launches of the kernel, "
+                              "that stage alone on one stream" % k_launch,
+                 "in_pipeline_event_us": in_pipe_ms * 1e3})
 
     out = {
-        "metric": "FiCoCo-V tokens/sec (B=16,N=576,D=1024)", "value": tokens_per_s, "unit": "tokens/s",
+        "metric": "FiCoCo-V tokens/sec (B=16,N=576,D=1024)" if args.config == "1"
+                  else "FiCoCo tokens/sec (config %s)" % args.config,
+        "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "steps_per_s": 1e3 / ms_per_step,
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": W["dtype"],
         "data": "synthetic",
-        "config": {"workload": "BASELINE config 1, step 1: FiCoCo-V fused step, B=16, [CLS]+576 patches, "
-                               "D=1024, H=16, bf16 tokens and maps, keep 384 of 576, %d rotating input sets"
-                               % N_SETS,
+        "config": {"workload": W["label"] + ", %d rotating input sets" % n_sets,
                    "decision_dtype": "f64", "streams": n_str},
-        "step_algorithmic_bytes": step_bytes,
-        "step_hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "roofline": {"kernel": "attn_reduce_kernel<bf16>", "bound": "hbm", "achieved": achieved,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": traffic_from_profiles(), "algorithmic_bytes": algo_bytes,
-                     "avg_launch_us": alone_ms * 1e3, "launches_timed": k_launch,
-                     "timed_how": "HIP event pair around %d back-to-back launches of the kernel alone on "
-                                  "the launch stream, inputs rotating" % k_launch,
-                     "in_pipeline_event_us": reduce_ms * 1e3},
+        "roofline": roof,
     }
+    if W.get("step_bytes"):
+        out["step_algorithmic_bytes"] = W["step_bytes"]
+        out["step_hbm_frac"] = W["step_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
@@ -184,25 +334,7 @@ def main():
         del src, dst
 
     if not args.no_cpu_baseline:
-        from oracle import ficoco_oracle as O
-        from paper_2411_17686_amd.synth import to_numpy
-        X, A = sets[0]
-        n_img = 2
-        Xh = [O.widen(to_numpy(X[b])) for b in range(n_img)]
-        Ah = [O.widen(to_numpy(A[b])) for b in range(n_img)]
-        t0 = time.perf_counter()
-        reps = 0
-        while True:
-            for b in range(n_img):
-                O.v_step(Xh[b], Ah[b], cls_index=0, vis_begin=1, N=N, n_keep=N_KEEP, lam=0.35, eps=0.998,
-                         grid=(1, GRID, GRID), window=2, coef=2.0)
-            reps += 1
-            el = time.perf_counter() - t0
-            if el > 12.0:
-                break
-        out["cpu_baseline"] = {"value": reps * n_img * N / el, "unit": "tokens/s", "cores": 1, "kind": "oracle",
-                               "sample": "%d of the 16 images of input set 0, %d passes, float64 numpy oracle "
-                                         "(single thread), %.1f s" % (n_img, reps, el)}
+        out["cpu_baseline"] = cpu_baseline(W)
     print(json.dumps(out))
 
 

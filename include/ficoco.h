@@ -135,12 +135,15 @@ const char *ficoco_version(void);
 
 /*
  * Measurement hook (not part of the paper's method).  With two non-NULL hipEvent_t handles
- * (created by the caller with timing enabled, passed as void*), every following
- * ficoco_reduce / ficoco_*_step call on this ctx records `start` immediately before and
- * `stop` immediately after the attention-reduction launch, on that call's stream, so the
- * dominant kernel can be timed inside a running pipeline.  NULL, NULL switches it off.
+ * (created by the caller with timing enabled, passed as void*), every following call on this
+ * ctx that launches the chosen kernel records `start` immediately before and `stop`
+ * immediately after that launch, on the call's stream, so the dominant kernel can be timed
+ * inside a running pipeline.  NULL, NULL switches it off.
+ *   kernel = FICOCO_PROBE_REDUCE : the attention-reduction kernel (bandwidth bound)
+ *   kernel = FICOCO_PROBE_GRAM   : the bf16 matrix-core tile kernel of the cosine correlation
  */
-int ficoco_set_reduce_probe(ficoco_ctx *ctx, void *start_event, void *stop_event);
+typedef enum { FICOCO_PROBE_REDUCE = 0, FICOCO_PROBE_GRAM = 1 } ficoco_probe_kernel;
+int ficoco_set_probe(ficoco_ctx *ctx, int kernel, void *start_event, void *stop_event);
 
 /* Bytes of device workspace the calls below need for this problem (256-byte aligned
  * pointer expected).  The workspace carries state from one stage to the next: the stage

@@ -10,6 +10,7 @@
 struct ficoco_ctx {
   int device;
   hipEvent_t probe_start, probe_stop;   // measurement hook, both null when off
+  int probe_kernel;
   char err[512];
 };
 
@@ -153,6 +154,10 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.edge_pack = take(B * (size_t)pl.n_disc * p.k_max * sizeof(EdgeRec));
+  pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
+                pl.n_disc > 0;
+  pl.ct = take(pl.use_gram ? B * (size_t)pl.n_disc * p.n_keep * sizeof(float) : 0);
+  pl.cmax = take(L ? B * (size_t)p.M * sizeof(double) : 0);
   pl.total = off;
   return FICOCO_OK;
 }
@@ -196,12 +201,15 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   const ficoco_problem& p = *p0;
   hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
-  if (ctx->probe_start) (void)hipEventRecord(ctx->probe_start, s);
+  const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
+  const bool pg = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_GRAM;
+  if (pr) (void)hipEventRecord(ctx->probe_start, s);
   launch_attn_reduce(p, pl, w, s);
-  if (ctx->probe_stop) (void)hipEventRecord(ctx->probe_stop, s);
+  if (pr) (void)hipEventRecord(ctx->probe_stop, s);
   if (pl.need_features) launch_features(p, pl, w, s);
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
-  launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true, s);
+  launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true,
+                   pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr, s);
   launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, true, s);
   return finish(ctx, fn);
 }
@@ -222,6 +230,7 @@ int ficoco_create(ficoco_ctx** out, int device) {
   c->device = device;
   c->probe_start = nullptr;
   c->probe_stop = nullptr;
+  c->probe_kernel = FICOCO_PROBE_REDUCE;
   c->err[0] = 0;
   *out = c;
   return FICOCO_OK;
@@ -234,8 +243,11 @@ int ficoco_destroy(ficoco_ctx* ctx) {
 
 const char* ficoco_last_error(const ficoco_ctx* ctx) { return ctx ? ctx->err : "ctx is NULL"; }
 
-int ficoco_set_reduce_probe(ficoco_ctx* ctx, void* start_event, void* stop_event) {
-  if (!ctx || ((start_event == nullptr) != (stop_event == nullptr))) return FICOCO_EINVAL;
+int ficoco_set_probe(ficoco_ctx* ctx, int kernel, void* start_event, void* stop_event) {
+  if (!ctx || ((start_event == nullptr) != (stop_event == nullptr)) ||
+      (kernel != FICOCO_PROBE_REDUCE && kernel != FICOCO_PROBE_GRAM))
+    return FICOCO_EINVAL;
+  ctx->probe_kernel = kernel;
   ctx->probe_start = (hipEvent_t)start_event;
   ctx->probe_stop = (hipEvent_t)stop_event;
   return FICOCO_OK;
@@ -257,9 +269,10 @@ int ficoco_reduce(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_
   Plan pl;
   const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_reduce");
   if (rc != FICOCO_OK) return rc;
-  if (ctx->probe_start) (void)hipEventRecord(ctx->probe_start, (hipStream_t)stream);
+  const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
+  if (pr) (void)hipEventRecord(ctx->probe_start, (hipStream_t)stream);
   launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
-  if (ctx->probe_stop) (void)hipEventRecord(ctx->probe_stop, (hipStream_t)stream);
+  if (pr) (void)hipEventRecord(ctx->probe_stop, (hipStream_t)stream);
   return finish(ctx, "ficoco_reduce");
 }
 
@@ -294,8 +307,10 @@ int ficoco_correlate(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t 
   if (rc != FICOCO_OK) return rc;
   if (!keep_idx || !overflow || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_correlate", "a pointer is NULL");
+  const bool pg = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_GRAM;
   launch_correlate(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow,
-                   false, (hipStream_t)stream);
+                   false, pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr,
+                   (hipStream_t)stream);
   return finish(ctx, "ficoco_correlate");
 }
 

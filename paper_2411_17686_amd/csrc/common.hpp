@@ -53,6 +53,9 @@ struct Plan {
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t edge_pack;      // EdgeRec [B][N^S][k_max]  edges as the merge kernel reads them
+  size_t ct;             // float  [B][N^S][n_keep]  approximate cosines (matrix-core path)
+  size_t cmax;           // double [B][M]
+  bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
   int f_chunks, f_rows_per_wg, Df;
   size_t total;
 };
@@ -74,7 +77,8 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
                    hipStream_t s);
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero, hipStream_t s);
+                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
+                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s);
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,

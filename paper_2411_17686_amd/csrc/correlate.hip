@@ -11,6 +11,7 @@
 // registers (per lane, then merged across the wavefront); otherwise the row is written to
 // the workspace and the two order statistics are found bit by bit.
 #include "common.hpp"
+#include "gram_tile.hpp"
 
 namespace ficoco {
 
@@ -34,6 +35,9 @@ struct CorrArgs {
   int32_t* overflow;
   EdgeRec* pack;         // [B][n_disc][k_max]
   const int32_t* slot_of; // [B][N] keep slot of a visual token, -1 if discarded
+  float* ct;             // [B][n_disc][n_keep] approximate cosines from the matrix cores
+  double* cmax;          // [B][M]
+  float delta;           // bound of |ct - exact dot|
 };
 
 __device__ __forceinline__ double dot_bf16(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y, int D) {
@@ -129,11 +133,8 @@ __global__ __launch_bounds__(256) void corr_fill_rows_kernel(CorrArgs a) {
   }
 }
 
-__global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
-  const int lane = threadIdx.x % kWave;
-  const int row = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  const int64_t b = blockIdx.y;
-  if (row >= a.n_disc) return;  // whole wavefront leaves together
+// One discarded row, exactly: every value of the row evaluated in double precision.
+__device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row, const int lane) {
   const int n = a.n_keep;
   const int i = a.S[b * a.n_disc + row];
   const int32_t* T = a.T + b * n;
@@ -233,6 +234,198 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
   }
 }
 
+__global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int row = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (row >= a.n_disc) return;  // whole wavefront leaves together
+  corr_row_exact(a, blockIdx.y, row, lane);
+}
+
+// ---- cosine correlation through the matrix cores -------------------------------------------
+// gram_tile_kernel (bf16 MFMA) has written approximate cosines ct[b][row][j].  They only
+// propose candidates.  With |ct - exact dot| <= delta and, for FiCoCo-L, the indirect term of
+// Eq. 4 inside [0, bound_i], every C_ij lies in [lo_ij, up_ij]; the m-th largest lo of the
+// row is a lower bound of v[f], so a target with up_ij below it can neither be one of the
+// order statistics that fix tau nor pass the threshold.  The remaining targets (a handful)
+// are evaluated exactly in double precision and the row is finished on those.  A row with
+// more than 64 candidates is evaluated exactly in full instead.
+constexpr int kCandCap = 64;
+
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+// exact C[i][j], the whole wavefront working on one pair (all lanes return the value)
+__device__ __forceinline__ double corr_value_wave(const CorrArgs& a, int64_t b, int i, int j, int lane) {
+  const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
+  const bf16_t* y = a.xhat + (b * a.N + j) * a.Df;
+  double acc = 0.0;
+  const int Dv = a.Df - a.Df % kVec;
+  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+    double u[kVec], w[kVec];
+    load8<bf16_t>(x + d, u);
+    load8<bf16_t>(y + d, w);
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) acc += u[k] * w[k];
+  }
+  for (int d = Dv + lane; d < a.Df; d += kWave) acc += widen(x[d]) * widen(y[d]);
+  acc = wave_sum_f64(acc);
+  const double direct = acc > 0.0 ? acc : 0.0;
+  if (a.mode == kCosV) return direct;
+  const double* ti = a.ttext + (b * a.N + i) * a.M;
+  const double* tj = a.ttext + (b * a.N + j) * a.M;
+  double br = 0.0;
+  for (int k = lane; k < a.M; k += kWave) br += ti[k] * tj[k];
+  br = wave_sum_f64(br);
+  return a.gamma * direct + (1.0 - a.gamma) * (br * a.invM);
+}
+
+// cmax[b][k] = max over the visual tokens of the text profile entry k (bound of Eq. 4's indirect term)
+__global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
+  __shared__ double part[256];
+  const int64_t b = blockIdx.x;
+  const int tid = threadIdx.x;
+  for (int k0 = 0; k0 < a.M; k0 += 64) {
+    const int k = k0 + tid % 64, g = tid / 64;
+    double mx = 0.0;
+    if (k < a.M)
+      for (int i = g; i < a.N; i += 4) { const double v = a.ttext[(b * a.N + i) * a.M + k]; mx = v > mx ? v : mx; }
+    part[tid] = mx;
+    __syncthreads();
+    if (g == 0 && k < a.M) {
+      for (int q = 1; q < 4; ++q) mx = part[q * 64 + tid] > mx ? part[q * 64 + tid] : mx;
+      a.cmax[b * a.M + k] = mx;
+    }
+    __syncthreads();
+  }
+}
+
+__global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
+  __shared__ int cand_j[4][kCandCap];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int row = blockIdx.x * (blockDim.x / kWave) + wv;
+  const int64_t b = blockIdx.y;
+  if (row >= a.n_disc) return;  // whole wavefront leaves together
+  const int n = a.n_keep;
+  const int i = a.S[b * a.n_disc + row];
+  const int32_t* T = a.T + b * n;
+  if ((unsigned)i >= (unsigned)a.N) {
+    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    return;
+  }
+  const float* ct = a.ct + (b * a.n_disc + row) * n;
+  const bool L = a.mode == kCosL;
+  const float gam = L ? (float)a.gamma : 1.0f;
+  float extra = 0.0f;                      // upper bound of (1 - gamma) * indirect term of this row
+  if (L) {
+    double bd = 0.0;
+    for (int k = lane; k < a.M; k += kWave) bd += a.ttext[(b * a.N + i) * a.M + k] * a.cmax[b * a.M + k];
+    bd = wave_sum_f64(bd) * a.invM * (1.0 - a.gamma);
+    extra = (float)bd * 1.000001f + 1e-30f;   // rounded up
+  }
+  const float delta = a.delta;
+  const float NEGF = -__builtin_huge_valf();
+
+  // lower bounds: per-lane top list, then m pops of the wavefront maximum -> lambda
+  float top[kSelMax];
+#pragma unroll
+  for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
+  for (int jj = lane; jj < n; jj += kWave) {
+    const float c = ct[jj];
+    float lo = gam * fmaxf(c - delta, 0.0f);
+    if (lo > top[kSelMax - 1]) {
+#pragma unroll
+      for (int k = 0; k < kSelMax; ++k) {
+        const bool sw = lo > top[k];
+        const float t = top[k];
+        top[k] = sw ? lo : t;
+        lo = sw ? t : lo;
+      }
+    }
+  }
+  float lambda = NEGF;
+  for (int r = 0; r < a.sel_m; ++r) {
+    float mx = top[0];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) { const float o = __shfl_xor(mx, off, kWave); mx = o > mx ? o : mx; }
+    const unsigned long long who = __ballot(top[0] == mx);
+    if (lane == __ffsll(who) - 1) {
+#pragma unroll
+      for (int k = 0; k + 1 < kSelMax; ++k) top[k] = top[k + 1];
+      top[kSelMax - 1] = NEGF;
+    }
+    lambda = mx;
+  }
+  // candidates in ascending target order
+  int n_cand = 0;
+  for (int base = 0; base < n; base += kWave) {
+    const int jj = base + lane;
+    bool is = false;
+    if (jj < n) {
+      const float up = gam * fmaxf(ct[jj] + delta, 0.0f) * 1.000001f + extra;
+      is = up >= lambda;
+    }
+    const unsigned long long m = __ballot(is);
+    if (is) {
+      const int slot = n_cand + __popcll(m & ((1ULL << lane) - 1ULL));
+      if (slot < kCandCap) cand_j[wv][slot] = jj;
+    }
+    n_cand += __popcll(m);
+  }
+  if (n_cand > kCandCap) {       // uniform per wavefront
+    corr_row_exact(a, b, row, lane);
+    return;
+  }
+  // exact values of the candidates: lane c keeps candidate c
+  const double NEG = -__builtin_huge_val();
+  double myv = NEG;
+  int myjj = -1;
+  for (int c = 0; c < n_cand; ++c) {
+    const int jj = cand_j[wv][c];
+    const int j = T[jj];
+    const double v = (unsigned)j < (unsigned)a.N ? corr_value_wave(a, b, i, j, lane) : NEG;
+    if (lane == c) { myv = v; myjj = jj; }
+  }
+  // v[f], v[f+1] = m-th and (m-1)-th largest of the exact candidate values
+  double v_f = NEG, v_f1 = NEG;
+  {
+    double act = myv;
+    for (int r = 0; r < a.sel_m; ++r) {
+      const double mx = wave_max(act);
+      const unsigned long long who = __ballot(act == mx);
+      if (lane == __ffsll(who) - 1) act = NEG;
+      v_f1 = v_f;
+      v_f = mx;
+    }
+    if (a.sel_m == 1) v_f1 = v_f;
+  }
+  const double tau = threshold_of(v_f, v_f1, a.sel_g);
+  unsigned long long hit = __ballot(myjj >= 0 && myv >= tau);
+  const int cnt = __popcll(hit);
+  const int my_pos = __popcll(hit & ((1ULL << lane) - 1ULL));
+  const bool mine = (hit >> lane) & 1ULL;
+  double denom = 0.0;
+  while (hit) {                       // ascending target order
+    const int l = __ffsll(hit) - 1;
+    hit &= hit - 1;
+    denom += __shfl(myv, l, kWave);
+  }
+  const bool live = denom > 0.0;
+  const int stored = cnt < a.k_max ? cnt : a.k_max;
+  const int64_t ebase = (b * a.n_disc + row) * a.k_max;
+  if (live && mine && my_pos < stored) {
+    const double al = myv / denom;
+    a.edge_tgt[ebase + my_pos] = myjj;
+    a.edge_alpha[ebase + my_pos] = al;
+    a.pack[ebase + my_pos] = EdgeRec{myjj, i, al};
+  }
+  if (lane == 0) {
+    a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
+    if (live && cnt > a.k_max) a.overflow[b] = 1;
+  }
+}
 
 // ---- FiCoCo-V attention correlation, tiled ----------------------------------------------------
 // The generic kernel above gathers one column of the row-major head-mean map per wavefront
@@ -413,7 +606,8 @@ __global__ void zero_i32_kernel(int32_t* p, int n) {
 
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero, hipStream_t s) {
+                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
+                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s) {
   if (!overflow_is_zero)
     hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
   if (pl.n_disc == 0) return;
@@ -433,6 +627,9 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha; a.overflow = overflow;
   a.pack = (EdgeRec*)(ws + pl.edge_pack);
   a.slot_of = (const int32_t*)(ws + pl.slot_of);
+  a.ct = (float*)(ws + pl.ct);
+  a.cmax = (double*)(ws + pl.cmax);
+  a.delta = (float)pl.Df * 2.384185791015625e-07f;   // Df * 2^-22
   if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
     const int tiles = (pl.n_disc + kTileCols - 1) / kTileCols;
     dim3 tgrid(xcd_padded_total(tiles * p.B));
@@ -443,6 +640,16 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     return;
   }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
+  if (pl.use_gram) {
+    GramArgs g{a.xhat, p.B, p.N, pl.Df, pl.n_disc, p.n_keep, discard_idx, keep_idx, a.ct};
+    const int tiles = p.B * ((pl.n_disc + kGT - 1) / kGT) * ((p.n_keep + kGT - 1) / kGT);
+    if (gram_start) (void)hipEventRecord(gram_start, s);
+    hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
+    if (gram_stop) (void)hipEventRecord(gram_stop, s);
+    if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3(p.B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
+    return;
+  }
   if (pl.dense_rows) hipLaunchKernelGGL(corr_fill_rows_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(corr_rows_kernel, grid, block, 0, s, a);
 }

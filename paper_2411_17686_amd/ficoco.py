@@ -18,9 +18,10 @@ VARIANT_V, VARIANT_L = 0, 1
 R_ATTN_RECV, R_VECTOR, R_SIM_MEAN = 0, 1, 2
 G_CLS_ATTN, G_TEXT_ATTN, G_VECTOR, G_EQ_TOKEN = 0, 1, 2, 3
 C_ATTN, C_COSINE = 0, 1
+PROBE_REDUCE, PROBE_GRAM = 0, 1
 
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
-           "ficoco_set_reduce_probe", "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
+           "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
            "ficoco_compress", "ficoco_v_step", "ficoco_l_step"]
 
 
@@ -67,7 +68,7 @@ def lib():
         L.ficoco_last_error.argtypes = [C.c_void_p]
         L.ficoco_last_error.restype = C.c_char_p
         L.ficoco_version.restype = C.c_char_p
-        L.ficoco_set_reduce_probe.argtypes = [vp, vp, vp]
+        L.ficoco_set_probe.argtypes = [vp, C.c_int, vp, vp]
         L.ficoco_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
         L.ficoco_reduce.argtypes = [vp, pp, vp, C.c_size_t, vp]
         L.ficoco_score.argtypes = [vp, pp, vp, C.c_size_t, f64p, vp]
@@ -126,9 +127,9 @@ class Context:
         if rc != OK:
             raise FicocoError(rc, lib().ficoco_last_error(self._h).decode())
 
-    def set_reduce_probe(self, start_event=None, stop_event=None):
-        """Raw hipEvent_t handles (ints) or None, None; see ficoco_set_reduce_probe."""
-        self.check(lib().ficoco_set_reduce_probe(self._h, start_event, stop_event))
+    def set_probe(self, kernel=PROBE_REDUCE, start_event=None, stop_event=None):
+        """Raw hipEvent_t handles (ints) or None, None; see ficoco_set_probe."""
+        self.check(lib().ficoco_set_probe(self._h, int(kernel), start_event, stop_event))
 
     def stream(self):
         return C.c_void_p(torch.cuda.current_stream(self.device).cuda_stream)

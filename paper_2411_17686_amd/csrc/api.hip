@@ -87,11 +87,20 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.n_out = p.n_tot - pl.n_disc;
 
   // attention reduction geometry
+  // Column strips: the fewest strips that keep at least 80 % of a workgroup's threads busy
+  // as (row lanes) x (8-column groups of the strip) -- long contiguous row pieces matter
+  // more than the last idle lanes -- else the busiest of the first 8 choices.
   const int groups = (p.N + kVec - 1) / kVec;
-  pl.col_strips = (groups + kReduceThreads - 1) / kReduceThreads;
-  pl.strip_groups = (groups + pl.col_strips - 1) / pl.col_strips;
-  pl.row_lanes = kReduceThreads / pl.strip_groups;
-  if (pl.row_lanes < 1) pl.row_lanes = 1;
+  {
+    const int s_min = (groups + kReduceThreads - 1) / kReduceThreads;
+    int best_busy = -1;
+    for (int sN = s_min; sN < s_min + 8; ++sN) {
+      const int sg = (groups + sN - 1) / sN;
+      const int rl = kReduceThreads / sg;
+      if (rl * sg > best_busy) { best_busy = rl * sg; pl.col_strips = sN; pl.strip_groups = sg; pl.row_lanes = rl; }
+      if (best_busy * 5 >= kReduceThreads * 4) break;
+    }
+  }
   auto rows_per_wg = [&](int rows) {
     int64_t want = ((int64_t)p.B * pl.col_strips * rows + kWgTarget - 1) / kWgTarget;  // aim at ~kWgTarget workgroups
     if (want < 1) want = 1;

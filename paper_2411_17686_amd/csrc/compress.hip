@@ -1,14 +1,16 @@
 // Compress stage: self-preserving compression (Eq. 2) and the removal of the discarded
 // tokens (last lines of Algorithm 1/2).
 //
-// Two kernels.  `invert_edges` turns the per-source edge lists into per-target lists
-// (target j -> its sources in ascending order) with an integer counting sort in LDS; the
-// final order of every list is fixed by a sort on the source index, so the result does not
-// depend on scheduling.  `merge_rows` is then a pure pull: one wavefront per OUTPUT row
+// `merge_rows` is a pure pull: one wavefront per OUTPUT row (and per 1024-feature span of it)
 // reads its own token plus its sources and writes
 //     (X_j + sum_i alpha_ij X_i) / (1 + sum_i alpha_ij)
 // accumulated in double precision in ascending i; rows without sources, and every token
 // outside the visual span, are copied bit for bit.  No floating-point atomics anywhere.
+// Where the sources come from: with few discarded tokens the wavefront scans the per-source
+// edge records itself; otherwise `invert_edges` first buckets the edges by target with an
+// integer counting sort in LDS (arrival order inside a bucket is arbitrary) and the merging
+// wavefront puts its bucket into ascending source order before it adds, so the result never
+// depends on scheduling.
 #include "common.hpp"
 
 namespace ficoco {
@@ -79,23 +81,6 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
       }
     }
   }
-  __syncthreads();
-  // fix the order inside every target's list: ascending source row (insertion sort)
-  for (int j = tid; j < n; j += nt) {
-    const int s0 = cnt[j], s1 = cnt[j + 1];
-    for (int x = s0 + 1; x < s1; ++x) {
-      const int r = a.tgt_src[ebase + x];
-      const double w = a.tgt_alpha[ebase + x];
-      int y = x - 1;
-      while (y >= s0 && a.tgt_src[ebase + y] > r) {
-        a.tgt_src[ebase + y + 1] = a.tgt_src[ebase + y];
-        a.tgt_alpha[ebase + y + 1] = a.tgt_alpha[ebase + y];
-        --y;
-      }
-      a.tgt_src[ebase + y + 1] = r;
-      a.tgt_alpha[ebase + y + 1] = w;
-    }
-  }
 }
 
 struct MergeArgs {
@@ -124,9 +109,10 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
 }
 
 constexpr int kMergeSlice = 2;    // 8-element vectors per lane per pass over the feature axis
-constexpr int kMatchCap = 32;     // sources of one target kept in LDS by the matching merge
+constexpr int kMergeSpan = kWave * kVec * kMergeSlice;   // features handled by one wavefront
+constexpr int kMatchCap = 64;     // sources of one target kept in LDS
 
-// Accumulate w * X[src] into num (this lane's slices of the current feature span).
+// Accumulate w * X[src] into num (this lane's slices of the feature span starting at d0).
 template <typename T>
 __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int i, double w, int d0, int lane,
                                            const bool (&full)[kMergeSlice], double (&num)[kMergeSlice][kVec]) {
@@ -147,19 +133,21 @@ __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int 
   }
 }
 
-// One wavefront per output row.  MATCH = false: the sources of a preserved token come from
-// the inverted edge lists.  MATCH = true (few discarded tokens): no inversion kernel; the
-// wavefront scans the packed per-source edge records once, 64 discarded rows per load,
-// keeps the rows that name its target in LDS (ascending row order, so the sum order is the
-// same) and then streams the feature axis.  More than kMatchCap sources for one target fall
-// back to re-scanning per feature span.
+// One wavefront per (output row, 1024-feature span).  MATCH = true (few discarded tokens):
+// the wavefront scans the packed per-source edge records, 64 discarded rows per load, and
+// keeps the rows that name its target in LDS in ascending row order.  MATCH = false: its
+// sources are one bucket of the inverted lists, sorted here by rank counting.  Buckets /
+// match lists longer than kMatchCap take a slower path that needs no list.
 template <typename T, bool MATCH>
 __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   DBG_SPAN(3);
   __shared__ int m_src[4][kMatchCap];
   __shared__ double m_w[4][kMatchCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-  const int r = blockIdx.x * (blockDim.x / kWave) + wv;
+  const int n_spans = (a.D + kMergeSpan - 1) / kMergeSpan;
+  const int wave_id = blockIdx.x * (blockDim.x / kWave) + wv;
+  const int r = wave_id / n_spans;
+  const int d0 = (wave_id % n_spans) * kMergeSpan;
   const int64_t b = blockIdx.y;
   if (r >= a.n_out) return;
   const T* Xb = (const T*)a.X + b * a.xsb;
@@ -176,17 +164,28 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
       e0 = a.tgt_ptr[b * (a.n_keep + 1) + j];
       e1 = a.tgt_ptr[b * (a.n_keep + 1) + j + 1];
     }
-    if (lane == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
+    if (lane == 0 && d0 == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
   } else {
     t = r + a.n_disc;
   }
   const T* x = Xb + (int64_t)t * a.xsn;
-  const int Dv = a.D - a.D % kVec;
   const bool merged_row = j >= 0 && a.n_disc > 0;
+  const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+
+  // this lane's slices of the row (issued before the source search: independent loads)
+  double num[kMergeSlice][kVec];
+  bool full[kMergeSlice];
+#pragma unroll
+  for (int u = 0; u < kMergeSlice; ++u) {
+    const int d = d0 + (u * kWave + lane) * kVec;
+    full[u] = d + kVec <= a.D;
+    if (full[u]) load8<T>(x + d, num[u]);
+    else
+      for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
+  }
 
   // ---- sources of this target -------------------------------------------------------------
-  int n_src = 0;          // matches found (MATCH) / list length (!MATCH)
-  double den = 1.0;
+  int n_src = 0;
   if (merged_row && MATCH) {
     for (int base = 0; base < a.n_disc; base += kWave) {
       const int row = base + lane;
@@ -217,72 +216,87 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
     }
   } else if (merged_row) {
     n_src = e1 - e0;
+    if (n_src > 0 && n_src <= kMatchCap) {
+      // bucket -> ascending source row: rank of an entry = number of entries with a smaller row
+      const bool in = lane < n_src;
+      const int row = in ? a.tgt_src[ebase + e0 + lane] : 0x7fffffff;
+      const double w = in ? a.tgt_alpha[ebase + e0 + lane] : 0.0;
+      const int src = in ? a.S[b * a.n_disc + min(max(row, 0), a.n_disc - 1)] : 0;
+      int rank = 0;
+      for (int l = 0; l < n_src; ++l) rank += __shfl(row, l, kWave) < row ? 1 : 0;
+      if (in) { m_src[wv][rank] = src; m_w[wv][rank] = w; }
+    }
   }
+  const int Dspan = min(kMergeSpan, a.D - d0);
   if (!merged_row || n_src == 0) {  // nothing merged into this row: exact copy
-    for (int d = lane * kVec; d < Dv; d += kWave * kVec) copy8<T>(x + d, out + d);
-    for (int d = Dv + lane; d < a.D; d += kWave) out[d] = x[d];
+#pragma unroll
+    for (int u = 0; u < kMergeSlice; ++u) {
+      const int d = d0 + (u * kWave + lane) * kVec;
+      if (full[u]) copy8<T>(x + d, out + d);
+      else
+        for (int k = 0; k < kVec; ++k)
+          if (d + k < a.D) out[d + k] = x[d + k];
+    }
+    (void)Dspan;
     return;
   }
-  const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
-  const bool listed = MATCH && n_src <= kMatchCap;
-  if (listed)
+  double den = 1.0;
+  if (n_src <= kMatchCap) {
     for (int e = 0; e < n_src; ++e) den += m_w[wv][e];
-  else if (!MATCH)
-    for (int e = e0; e < e1; ++e) den += a.tgt_alpha[ebase + e];
-
-  constexpr int kSpan = kWave * kVec * kMergeSlice;           // features per pass
-  for (int d0 = 0; d0 < a.D; d0 += kSpan) {
-    double num[kMergeSlice][kVec];
-    bool full[kMergeSlice];
-#pragma unroll
-    for (int u = 0; u < kMergeSlice; ++u) {
-      const int d = d0 + (u * kWave + lane) * kVec;
-      full[u] = d + kVec <= a.D;
-      if (full[u]) load8<T>(x + d, num[u]);
-      else
-        for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
+    for (int e = 0; e < n_src; ++e) add_source<T>(a, Xb, m_src[wv][e], m_w[wv][e], d0, lane, full, num);
+  } else if (MATCH) {
+    // more sources than the list holds: add while scanning
+    for (int base = 0; base < a.n_disc; base += kWave) {
+      const int row = base + lane;
+      const bool in = row < a.n_disc;
+      const int64_t rr = b * a.n_disc + (in ? row : 0);
+      const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
+      int he = -1;
+      for (int e = 0; e < cnt; ++e)
+        if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
+      const double w = he >= 0 ? a.edge_alpha[rr * a.k_max + he] : 0.0;
+      const int src = a.S[rr];
+      unsigned long long m = __ballot(he >= 0);
+      while (m) {
+        const int l = __ffsll(m) - 1;
+        m &= m - 1;
+        const double wl = __shfl(w, l, kWave);
+        den += wl;
+        add_source<T>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+      }
     }
-    if (listed) {
-      for (int e = 0; e < n_src; ++e) add_source<T>(a, Xb, m_src[wv][e], m_w[wv][e], d0, lane, full, num);
-    } else if (!MATCH) {
-      for (int e = e0; e < e1; ++e)
-        add_source<T>(a, Xb, a.S[b * a.n_disc + a.tgt_src[ebase + e]], a.tgt_alpha[ebase + e], d0, lane, full, num);
+  } else {
+    // long bucket: take its entries in ascending source row by repeated minimum search
+    int last = -1;
+    for (int k = 0; k < n_src; ++k) {
+      int best = 0x7fffffff, best_e = -1;
+      for (int e = e0 + lane; e < e1; e += kWave) {
+        const int row = a.tgt_src[ebase + e];
+        if (row > last && row < best) { best = row; best_e = e; }
+      }
+      int mn = best;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mn = min(mn, __shfl_xor(mn, off, kWave));
+      const unsigned long long who = __ballot(best == mn && best_e >= 0);
+      const int l = __ffsll(who) - 1;
+      const int e = __shfl(best_e, l, kWave);
+      const double w = a.tgt_alpha[ebase + e];
+      den += w;
+      add_source<T>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
+      last = mn;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kMergeSlice; ++u) {
+    const int d = d0 + (u * kWave + lane) * kVec;
+    if (full[u]) {
+      Pack8<T> o;
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[u][k] / den);
+      __builtin_memcpy(out + d, &o, sizeof(o));
     } else {
-      // more sources than the LDS list holds: scan again for every feature span
-      double dsum = 1.0;
-      for (int base = 0; base < a.n_disc; base += kWave) {
-        const int row = base + lane;
-        const bool in = row < a.n_disc;
-        const int64_t rr = b * a.n_disc + (in ? row : 0);
-        const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
-        int he = -1;
-        for (int e = 0; e < cnt; ++e)
-          if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
-        const double w = he >= 0 ? a.edge_alpha[rr * a.k_max + he] : 0.0;
-        const int src = a.S[rr];
-        unsigned long long m = __ballot(he >= 0);
-        while (m) {
-          const int l = __ffsll(m) - 1;
-          m &= m - 1;
-          const double wl = __shfl(w, l, kWave);
-          dsum += wl;
-          add_source<T>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
-        }
-      }
-      den = dsum;
-    }
-#pragma unroll
-    for (int u = 0; u < kMergeSlice; ++u) {
-      const int d = d0 + (u * kWave + lane) * kVec;
-      if (full[u]) {
-        Pack8<T> o;
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) store_token(&o.v[k], num[u][k] / den);
-        __builtin_memcpy(out + d, &o, sizeof(o));
-      } else {
-        for (int k = 0; k < kVec; ++k)
-          if (d + k < a.D) store_token(out + d + k, num[u][k] / den);
-      }
+      for (int k = 0; k < kVec; ++k)
+        if (d + k < a.D) store_token(out + d + k, num[u][k] / den);
     }
   }
 }
@@ -317,7 +331,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
   m.pack = use_pack ? (const EdgeRec*)(ws + pl.edge_pack) : nullptr;
   m.pos = p.pos; m.pos_out = pos_out;
-  dim3 grid((pl.n_out + 3) / 4, p.B), block(256);
+  const int n_spans = (p.D + kMergeSpan - 1) / kMergeSpan;
+  dim3 grid((pl.n_out * n_spans + 3) / 4, p.B), block(256);
   const bool bf16 = p.dtype == FICOCO_BF16;
   if (match) {
     if (bf16) hipLaunchKernelGGL((merge_rows_kernel<bf16_t, true>), grid, block, 0, s, m);

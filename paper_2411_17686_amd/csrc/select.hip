@@ -38,15 +38,25 @@ struct SelectArgs {
   int32_t* overflow;        // zeroed here for the correlate stage (fused step only), may be null
 };
 
-__device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_t b, int H, int N, int i) {
+// head mean of a pre-reduced per-head vector entry: 16 independent loads at a time, added in
+// head order
+template <typename T>
+__device__ __forceinline__ double vec_head_sum(const T* p, int H, int N) {
   double acc = 0.0;
-  if (dtype == FICOCO_BF16) {
-    const bf16_t* p = (const bf16_t*)v + b * H * (int64_t)N + i;
-    for (int h = 0; h < H; ++h) acc += widen(p[(int64_t)h * N]);
-  } else {
-    const float* p = (const float*)v + b * H * (int64_t)N + i;
-    for (int h = 0; h < H; ++h) acc += widen(p[(int64_t)h * N]);
+  int h = 0;
+  for (; h + 16 <= H; h += 16) {
+    T v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(h + u) * N];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc += widen(v[u]);
   }
+  for (; h < H; ++h) acc += widen(p[(int64_t)h * N]);
+  return acc;
+}
+__device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_t b, int H, int N, int i) {
+  const double acc = dtype == FICOCO_BF16 ? vec_head_sum((const bf16_t*)v + b * H * (int64_t)N + i, H, N)
+                                          : vec_head_sum((const float*)v + b * H * (int64_t)N + i, H, N);
   return acc * (1.0 / (double)H);
 }
 

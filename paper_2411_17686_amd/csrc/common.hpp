@@ -126,6 +126,20 @@ __device__ __forceinline__ void add_raw(const Raw8<float>& r, double (&acc)[kVec
   acc[4] += r.b.x; acc[5] += r.b.y; acc[6] += r.b.z; acc[7] += r.b.w;
 }
 
+// acc += w * (the 8 elements held raw)
+__device__ __forceinline__ void fma_raw(const Raw8<bf16_t>& r, double w, double (&acc)[kVec]) {
+  const uint32_t q[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    acc[2 * j] += w * (double)__uint_as_float(q[j] << 16);
+    acc[2 * j + 1] += w * (double)__uint_as_float(q[j] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void fma_raw(const Raw8<float>& r, double w, double (&acc)[kVec]) {
+  acc[0] += w * r.a.x; acc[1] += w * r.a.y; acc[2] += w * r.a.z; acc[3] += w * r.a.w;
+  acc[4] += w * r.b.x; acc[5] += w * r.b.y; acc[6] += w * r.b.z; acc[7] += w * r.b.w;
+}
+
 // 8 consecutive elements from an address that is only element aligned.
 template <typename T>
 __device__ __forceinline__ void load8(const T* __restrict__ p, double (&out)[kVec]);

@@ -172,18 +172,6 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
   const bool merged_row = j >= 0 && a.n_disc > 0;
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
 
-  // this lane's slices of the row (issued before the source search: independent loads)
-  double num[kMergeSlice][kVec];
-  bool full[kMergeSlice];
-#pragma unroll
-  for (int u = 0; u < kMergeSlice; ++u) {
-    const int d = d0 + (u * kWave + lane) * kVec;
-    full[u] = d + kVec <= a.D;
-    if (full[u]) load8<T>(x + d, num[u]);
-    else
-      for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
-  }
-
   // ---- sources of this target -------------------------------------------------------------
   int n_src = 0;
   if (merged_row && MATCH) {
@@ -227,7 +215,9 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
       if (in) { m_src[wv][rank] = src; m_w[wv][rank] = w; }
     }
   }
-  const int Dspan = min(kMergeSpan, a.D - d0);
+  bool full[kMergeSlice];
+#pragma unroll
+  for (int u = 0; u < kMergeSlice; ++u) full[u] = d0 + (u * kWave + lane) * kVec + kVec <= a.D;
   if (!merged_row || n_src == 0) {  // nothing merged into this row: exact copy
 #pragma unroll
     for (int u = 0; u < kMergeSlice; ++u) {
@@ -237,9 +227,18 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
         for (int k = 0; k < kVec; ++k)
           if (d + k < a.D) out[d + k] = x[d + k];
     }
-    (void)Dspan;
     return;
   }
+  // this lane's slices of the row
+  double num[kMergeSlice][kVec];
+#pragma unroll
+  for (int u = 0; u < kMergeSlice; ++u) {
+    const int d = d0 + (u * kWave + lane) * kVec;
+    if (full[u]) load8<T>(x + d, num[u]);
+    else
+      for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
+  }
+
   double den = 1.0;
   if (n_src <= kMatchCap) {
     for (int e = 0; e < n_src; ++e) den += m_w[wv][e];

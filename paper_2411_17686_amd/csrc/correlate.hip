@@ -259,20 +259,25 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 
 // exact C[i][j], the whole wavefront working on one pair (all lanes return the value)
 __device__ __forceinline__ double corr_value_wave(const CorrArgs& a, int64_t b, int i, int j, int lane) {
-  const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
-  const bf16_t* y = a.xhat + (b * a.N + j) * a.Df;
-  double acc = 0.0;
-  const int Dv = a.Df - a.Df % kVec;
-  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-    double u[kVec], w[kVec];
-    load8<bf16_t>(x + d, u);
-    load8<bf16_t>(y + d, w);
+  double direct;
+  if (a.mode == kAttnL) {
+    direct = (double)a.abar[(b * a.N + j) * a.N + i];
+  } else {
+    const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
+    const bf16_t* y = a.xhat + (b * a.N + j) * a.Df;
+    double acc = 0.0;
+    const int Dv = a.Df - a.Df % kVec;
+    for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+      double u[kVec], w[kVec];
+      load8<bf16_t>(x + d, u);
+      load8<bf16_t>(y + d, w);
 #pragma unroll
-    for (int k = 0; k < kVec; ++k) acc += u[k] * w[k];
+      for (int k = 0; k < kVec; ++k) acc += u[k] * w[k];
+    }
+    for (int d = Dv + lane; d < a.Df; d += kWave) acc += widen(x[d]) * widen(y[d]);
+    acc = wave_sum_f64(acc);
+    direct = acc > 0.0 ? acc : 0.0;
   }
-  for (int d = Dv + lane; d < a.Df; d += kWave) acc += widen(x[d]) * widen(y[d]);
-  acc = wave_sum_f64(acc);
-  const double direct = acc > 0.0 ? acc : 0.0;
   if (a.mode == kCosV) return direct;
   const double* ti = a.ttext + (b * a.N + i) * a.M;
   const double* tj = a.ttext + (b * a.N + j) * a.M;
@@ -290,8 +295,17 @@ __global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
   for (int k0 = 0; k0 < a.M; k0 += 64) {
     const int k = k0 + tid % 64, g = tid / 64;
     double mx = 0.0;
-    if (k < a.M)
-      for (int i = g; i < a.N; i += 4) { const double v = a.ttext[(b * a.N + i) * a.M + k]; mx = v > mx ? v : mx; }
+    if (k < a.M) {
+      int i = g;
+      for (; i + 4 * 15 < a.N; i += 4 * 16) {            // 16 independent loads per round
+        double v[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) v[u] = a.ttext[(b * a.N + i + 4 * u) * a.M + k];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) mx = v[u] > mx ? v[u] : mx;
+      }
+      for (; i < a.N; i += 4) { const double v = a.ttext[(b * a.N + i) * a.M + k]; mx = v > mx ? v : mx; }
+    }
     part[tid] = mx;
     __syncthreads();
     if (g == 0 && k < a.M) {
@@ -315,8 +329,11 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
     return;
   }
-  const float* ct = a.ct + (b * a.n_disc + row) * n;
-  const bool L = a.mode == kCosL;
+  // approximate direct term of the row: the matrix-core cosines, or (FiCoCo-L with the
+  // attention correlation) the exact head-mean map gathered by column, delta = 0
+  const bool from_map = a.mode == kAttnL;
+  const float* ct = from_map ? a.abar + b * a.N * (int64_t)a.N + i : a.ct + (b * a.n_disc + row) * n;
+  const bool L = a.mode == kCosL || a.mode == kAttnL;
   const float gam = L ? (float)a.gamma : 1.0f;
   float extra = 0.0f;                      // upper bound of (1 - gamma) * indirect term of this row
   if (L) {
@@ -325,7 +342,7 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     bd = wave_sum_f64(bd) * a.invM * (1.0 - a.gamma);
     extra = (float)bd * 1.000001f + 1e-30f;   // rounded up
   }
-  const float delta = a.delta;
+  const float delta = from_map ? 0.0f : a.delta;
   const float NEGF = -__builtin_huge_valf();
 
   // lower bounds: per-lane top list, then m pops of the wavefront maximum -> lambda
@@ -333,7 +350,9 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
 #pragma unroll
   for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
   for (int jj = lane; jj < n; jj += kWave) {
-    const float c = ct[jj];
+    float c;
+    if (from_map) { const int j = T[jj]; c = (unsigned)j < (unsigned)a.N ? ct[(int64_t)j * a.N] : 0.0f; }
+    else c = ct[jj];
     float lo = gam * fmaxf(c - delta, 0.0f);
     if (lo > top[kSelMax - 1]) {
 #pragma unroll
@@ -364,7 +383,10 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     const int jj = base + lane;
     bool is = false;
     if (jj < n) {
-      const float up = gam * fmaxf(ct[jj] + delta, 0.0f) * 1.000001f + extra;
+      float c;
+      if (from_map) { const int j = T[jj]; c = (unsigned)j < (unsigned)a.N ? ct[(int64_t)j * a.N] : 0.0f; }
+      else c = ct[jj];
+      const float up = gam * fmaxf(c + delta, 0.0f) * 1.000001f + extra;
       is = up >= lambda;
     }
     const unsigned long long m = __ballot(is);
@@ -640,6 +662,11 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     return;
   }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
+  if (a.mode == kAttnL && !pl.dense_rows && p.k_max <= 64) {
+    hipLaunchKernelGGL(text_colmax_kernel, dim3(p.B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
+    return;
+  }
   if (pl.use_gram) {
     GramArgs g{a.xhat, p.B, p.N, pl.Df, pl.n_disc, p.n_keep, discard_idx, keep_idx, a.ct};
     const int tiles = p.B * ((pl.n_disc + kGT - 1) / kGT) * ((p.n_keep + kGT - 1) / kGT);

@@ -290,6 +290,28 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   DBG_PHASE(5);
 }
 
+// Large problems (many row chunks and more columns than one workgroup has threads): the
+// per-column partial sums are added up by a grid of workgroups first, in chunk order, so the
+// single per-image workgroup of select_kernel reads one value per column.
+__global__ __launch_bounds__(256) void combine_partials_kernel(const double* __restrict__ part, double* __restrict__ out,
+                                                               int N, int n_chunks) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = blockIdx.y;
+  if (i >= N) return;
+  const double* p = part + b * n_chunks * (int64_t)N + i;
+  double acc = 0.0;
+  int c = 0;
+  for (; c + 16 <= n_chunks; c += 16) {
+    double v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(c + u) * N];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) acc += v[u];
+  }
+  for (; c < n_chunks; ++c) acc += p[(int64_t)c * N];
+  out[b * N + i] = acc;
+}
+
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
   return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + cells) * sizeof(int);
@@ -303,6 +325,14 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.red_src = p.red_src; a.sem_src = p.sem_src;
   a.do_score = do_score; a.do_filter = do_filter;
   a.recv_part = (const double*)(ws + pl.recv_part);
+  if (do_score && p.red_src == FICOCO_R_ATTN_RECV &&
+      (int64_t)pl.n_chunks * ((p.N + kSelectThreads - 1) / kSelectThreads) > 128) {
+    double* sums = (double*)(ws + pl.fterm);     // free in this mode (it holds the mean-cosine term otherwise)
+    hipLaunchKernelGGL(combine_partials_kernel, dim3((p.N + 255) / 256, p.B), dim3(256), 0, s, a.recv_part, sums,
+                       p.N, pl.n_chunks);
+    a.recv_part = sums;
+    a.n_chunks = 1;
+  }
   a.cls = (const double*)(ws + pl.cls);
   a.ttext = (const double*)(ws + pl.ttext);
   a.recv_vec = p.recv_vec; a.sem_vec = p.sem_vec;

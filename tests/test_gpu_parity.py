@@ -153,3 +153,47 @@ def test_error_paths(ctx):
     with pytest.raises(fc.FicocoError) as e:
         fc.ficoco_v_step(ctx, p, buf)
     assert e.value.code == fc.ENOMEM
+
+
+def _sink_attention(n, j_star, c0, dtype):
+    """Map in which every query but j_star puts nearly all of its mass on key c0, and j_star
+    attends uniformly: for every key i != c0 the strongest query is j_star, so every
+    discarded token names the same target."""
+    eps = 1e-4
+    P = torch.full((n, n), eps)
+    P[:, c0] = 1.0 - eps * (n - 1)
+    P[j_star, :] = 1.0 / n
+    return P[None, None].to(torch.bfloat16 if dtype == "bf16" else torch.float32).contiguous()
+
+
+@pytest.mark.parametrize("N,n_keep,D", [(100, 30, 40), (1300, 150, 16)])
+def test_v_step_many_sources_on_one_target(ctx, N, n_keep, D):
+    """More sources on one preserved token than the merge kernel lists in LDS: 69 via the
+    scanning path (N = 100) and > 1000 via the inverted-list path (N = 1300)."""
+    cfg = synth.ficoco_v_single(seed=21, B=1, grid=10, D=D, H=1, centres=4, dtype="f32", n_keep=n_keep)
+    g = torch.Generator().manual_seed(5)
+    cfg["X"] = torch.randn(1, N + 1, D, generator=g)
+    cfg["A"] = _sink_attention(N + 1, N, 1, "f32")      # j_star = last token (kept: ties discard low indices)
+    cfg["grid"] = (1, 1, N)
+    out, _ = P.run_v(cfg, cfg["A"], ctx=ctx, window=0)
+    ref = P.oracle_v(cfg, cfg["A"], 0, window=0)
+    P.compare_image(out, 0, ref, "f32", 1, True)
+    hits = sum(1 for j in ref["J"] if len(j) == 1 and j[0] == n_keep - 1)
+    assert hits > 64
+
+
+def test_staged_equals_fused_cosine_and_l(ctx):
+    cfg = synth.ficoco_v_video(seed=31, B=2, frames=2, grid=8, D=64, H=2, centres=5, n_keep=30)
+    kw = dict(red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE)
+    fused, _ = P.run_v(cfg, None, ctx=ctx, **kw)
+    staged, _ = P.run_v(cfg, None, ctx=ctx, staged=True, **kw)
+    for k in fused:
+        assert np.array_equal(fused[k], staged[k]), k
+
+
+def test_v_step_long_rows_cosine_d_tail(ctx):
+    """Feature width that is not a multiple of 8 (exact path) and one that is a multiple of 8
+    but not of the matrix-core K step (zero-padded tail)."""
+    for D in (52, 72, 200):
+        cfg = synth.ficoco_v_single(seed=40 + D, B=2, grid=7, D=D, H=2, centres=4, dtype="bf16", n_keep=20)
+        _check_v(cfg, ctx, corr_src=fc.C_COSINE)

@@ -6,9 +6,9 @@
 // does not matter for the outcome.
 //
 // 128 x 128 output tile per workgroup (4 wavefronts, 64 x 64 each = 2 x 2 blocks of
-// v_mfma_f32_32x32x16_bf16), K staged through LDS 32 at a time, double buffered, rows
-// gathered by index.  LDS rows are padded to 80 bytes so that the 16-byte fragment reads
-// of a quarter wavefront fall on distinct banks.
+// v_mfma_f32_32x32x16_bf16), K staged through LDS 32 at a time,
+// double buffered, rows gathered by index.  LDS rows are padded by 16 bytes so that the
+// 16-byte fragment reads of a quarter wavefront fall on distinct banks.
 #pragma once
 #include "common.hpp"
 
@@ -18,8 +18,16 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kGT = 128;           // tile rows = tile columns
-constexpr int kGK = 32;            // K elements per stage
-constexpr int kGStride = kGK + 8;  // LDS row pitch in elements (80 bytes)
+#ifndef FICOCO_GRAM_K
+#define FICOCO_GRAM_K 32
+#endif
+constexpr int kGK = FICOCO_GRAM_K; // K elements per stage (32 measured best at 4096 tokens; 64 halves LDS occupancy)
+constexpr int kGChunks = kGK / 16;  // 16-byte chunks per thread, operand and stage
+constexpr int kGStride = kGK + 8;  // LDS row pitch in elements (row + 16 bytes)
+#ifndef FICOCO_GRAM_STAGES
+#define FICOCO_GRAM_STAGES 2
+#endif
+constexpr int kGStages = FICOCO_GRAM_STAGES;   // K-stages in flight per thread (register ring)
 
 struct GramArgs {
   const bf16_t* xhat;  // [B][N][Df]
@@ -53,35 +61,40 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   }
   __syncthreads();
 
-  // loader: the stage is 128 rows x 4 chunks of 8 elements per operand; thread -> 2 chunks each
+  // loader: the stage is 128 rows x kGK/8 chunks of 8 elements per operand; thread -> kGChunks chunks each
   const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df;
-  int lrow[2], lkc[2];
-  const bf16_t* srcA[2];
-  const bf16_t* srcB[2];
+  int lrow[kGChunks], lkc[kGChunks];
+  const bf16_t* srcA[kGChunks];
+  const bf16_t* srcB[kGChunks];
 #pragma unroll
-  for (int u = 0; u < 2; ++u) {
+  for (int u = 0; u < kGChunks; ++u) {
     const int q = tid + 256 * u;
-    lrow[u] = q / 4;
-    lkc[u] = (q % 4) * 8;
+    lrow[u] = q / (kGK / 8);
+    lkc[u] = (q % (kGK / 8)) * 8;
     srcA[u] = rowA[lrow[u]] >= 0 ? Xb + (int64_t)rowA[lrow[u]] * a.Df + lkc[u] : nullptr;
     srcB[u] = rowB[lrow[u]] >= 0 ? Xb + (int64_t)rowB[lrow[u]] * a.Df + lkc[u] : nullptr;
   }
-  uint4 ra[2], rb[2];
-  auto fetch = [&](int k0) {
+  // Register ring of kGStages K-stages in flight per thread: a stage is fetched kGStages
+  // iterations before it is stashed into LDS, which covers the global-load latency that a
+  // single 32-wide K step (a few hundred cycles of MFMA work) cannot.
+  uint4 ra[kGStages][kGChunks], rb[kGStages][kGChunks];
+  const int n_st = (a.Df + kGK - 1) / kGK;
+  auto fetch = [&](int slot, int st) {
+    const int k0 = st * kGK;
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      const bool in = k0 + lkc[u] + 8 <= a.Df;   // Df is a multiple of 8 on this path
-      ra[u] = make_uint4(0, 0, 0, 0);
-      rb[u] = make_uint4(0, 0, 0, 0);
-      if (in && srcA[u]) __builtin_memcpy(&ra[u], srcA[u] + k0, 16);
-      if (in && srcB[u]) __builtin_memcpy(&rb[u], srcB[u] + k0, 16);
+    for (int u = 0; u < kGChunks; ++u) {
+      const bool in = st < n_st && k0 + lkc[u] + 8 <= a.Df;   // Df is a multiple of 8 on this path
+      ra[slot][u] = make_uint4(0, 0, 0, 0);
+      rb[slot][u] = make_uint4(0, 0, 0, 0);
+      if (in && srcA[u]) __builtin_memcpy(&ra[slot][u], srcA[u] + k0, 16);
+      if (in && srcB[u]) __builtin_memcpy(&rb[slot][u], srcB[u] + k0, 16);
     }
   };
-  auto stash = [&](int buf) {
+  auto stash = [&](int slot, int buf) {
 #pragma unroll
-    for (int u = 0; u < 2; ++u) {
-      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = ra[u];
-      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = rb[u];
+    for (int u = 0; u < kGChunks; ++u) {
+      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = ra[slot][u];
+      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = rb[slot][u];
     }
   };
 
@@ -95,32 +108,38 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
 
   const int wm = wv / 2, wn = wv % 2;
   const int frow = lane % 32, fk = (lane / 32) * 8;   // fragment: row / column within the block, k offset
-  fetch(0);
-  stash(0);
+#pragma unroll
+  for (int sl = 0; sl < kGStages; ++sl) fetch(sl, sl);
+  stash(0, 0);
   __syncthreads();
   int cur = 0;
-  for (int k0 = 0; k0 < a.Df; k0 += kGK) {
-    const bool more = k0 + kGK < a.Df;
-    if (more) fetch(k0 + kGK);
+  for (int base = 0; base < n_st; base += kGStages) {
 #pragma unroll
-    for (int kk = 0; kk < kGK; kk += 16) {
-      bf16x8_t fa[2], fb[2];
+    for (int sl = 0; sl < kGStages; ++sl) {
+      const int it = base + sl;
+      if (it < n_st) {                          // uniform over the workgroup
+        fetch(sl, it + kGStages);               // slot sl was stashed one iteration ago
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
-        fa[mi] = *reinterpret_cast<const bf16x8_t*>(&As[cur][(wm * 64 + mi * 32 + frow) * kGStride + kk + fk]);
+        for (int kk = 0; kk < kGK; kk += 16) {
+          bf16x8_t fa[2], fb[2];
 #pragma unroll
-      for (int ni = 0; ni < 2; ++ni)
-        fb[ni] = *reinterpret_cast<const bf16x8_t*>(&Bs[cur][(wn * 64 + ni * 32 + frow) * kGStride + kk + fk]);
+          for (int mi = 0; mi < 2; ++mi)
+            fa[mi] = *reinterpret_cast<const bf16x8_t*>(&As[cur][(wm * 64 + mi * 32 + frow) * kGStride + kk + fk]);
 #pragma unroll
-      for (int mi = 0; mi < 2; ++mi)
+          for (int ni = 0; ni < 2; ++ni)
+            fb[ni] = *reinterpret_cast<const bf16x8_t*>(&Bs[cur][(wn * 64 + ni * 32 + frow) * kGStride + kk + fk]);
 #pragma unroll
-        for (int ni = 0; ni < 2; ++ni)
-          acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
-    }
-    if (more) {
-      stash(cur ^ 1);      // the other buffer was last read one iteration ago, before the barrier below
-      __syncthreads();
-      cur ^= 1;
+          for (int mi = 0; mi < 2; ++mi)
+#pragma unroll
+            for (int ni = 0; ni < 2; ++ni)
+              acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
+        }
+        if (it + 1 < n_st) {
+          stash((sl + 1) % kGStages, cur ^ 1);  // the other buffer was last read before the previous barrier
+          __syncthreads();
+          cur ^= 1;
+        }
+      }
     }
   }
 

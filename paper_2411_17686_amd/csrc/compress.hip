@@ -96,7 +96,6 @@ struct MergeArgs {
   const int32_t* edge_cnt;
   const int32_t* edge_tgt;
   const double* edge_alpha;
-  const EdgeRec* pack;   // null: read the caller's edge lists instead
   const int32_t* pos;
   int32_t* pos_out;
 };
@@ -108,18 +107,19 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-constexpr int kMergeSlice = 2;    // 8-element vectors per lane per pass over the feature axis
-constexpr int kMergeSpan = kWave * kVec * kMergeSlice;   // features handled by one wavefront
-constexpr int kMatchCap = 64;     // sources of one target kept in LDS
+constexpr int kMergeWaves = 8;    // wavefronts (= output row spans) per workgroup
+constexpr int kMatchCap = 64;     // scanning mode: sources of one target kept in LDS
+constexpr int kBucketCap = 256;   // inverted lists: bucket entries put in order in LDS
+constexpr int kBucketPer = kBucketCap / kWave;
 
 // Accumulate w * X[src] into num (this lane's slices of the feature span starting at d0).
-template <typename T>
+template <typename T, int SLICE>
 __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int i, double w, int d0, int lane,
-                                           const bool (&full)[kMergeSlice], double (&num)[kMergeSlice][kVec]) {
+                                           const bool (&full)[SLICE], double (&num)[SLICE][kVec]) {
   i = min(max(i, 0), a.N - 1);                 // index sets are device data: stay inside the span
   const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
 #pragma unroll
-  for (int u = 0; u < kMergeSlice; ++u) {
+  for (int u = 0; u < SLICE; ++u) {
     const int d = d0 + (u * kWave + lane) * kVec;
     if (full[u]) {
       double v[kVec];
@@ -133,44 +133,138 @@ __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int 
   }
 }
 
-// One wavefront per (output row, 1024-feature span).  MATCH = true (few discarded tokens):
-// the wavefront scans the packed per-source edge records, 64 discarded rows per load, and
-// keeps the rows that name its target in LDS in ascending row order.  MATCH = false: its
-// sources are one bucket of the inverted lists, sorted here by rank counting.  Buckets /
-// match lists longer than kMatchCap take a slower path that needs no list.
-template <typename T, bool MATCH>
-__global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
-  DBG_SPAN(3);
-  __shared__ int m_src[4][kMatchCap];
-  __shared__ double m_w[4][kMatchCap];
-  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-  const int n_spans = (a.D + kMergeSpan - 1) / kMergeSpan;
-  const int wave_id = blockIdx.x * (blockDim.x / kWave) + wv;
-  const int r = wave_id / n_spans;
-  const int d0 = (wave_id % n_spans) * kMergeSpan;
-  const int64_t b = blockIdx.y;
-  if (r >= a.n_out) return;
-  const T* Xb = (const T*)a.X + b * a.xsb;
-  T* out = (T*)a.X_out + (b * a.n_out + r) * (int64_t)a.D;
-  int t, j = -1, e0 = 0, e1 = 0;
-  if (r < a.vis_begin) {
-    t = r;
-  } else if (r < a.vis_begin + a.n_keep) {
-    j = r - a.vis_begin;
-    int tok = a.T[b * a.n_keep + j];
-    tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
-    t = a.vis_begin + tok;
-    if (!MATCH && a.n_disc > 0) {
-      e0 = a.tgt_ptr[b * (a.n_keep + 1) + j];
-      e1 = a.tgt_ptr[b * (a.n_keep + 1) + j + 1];
+// The same for a whole list held in LDS, in list order, with the row loads of kBatch sources
+// issued before the first of them is added: a target with n sources then waits for
+// ceil(n / kBatch) memory round trips instead of n.
+template <typename T, int SLICE>
+__device__ __forceinline__ void add_sources(const MergeArgs& a, const T* Xb, const int* src, const double* w,
+                                            int n_src, int d0, int lane, const bool (&full)[SLICE],
+                                            double (&num)[SLICE][kVec]) {
+  constexpr int kBatch = 32 / (SLICE * (int)(sizeof(Raw8<T>) / 4));   // 32 registers of raw data in flight
+  for (int e = 0; e < n_src; e += kBatch) {
+    Raw8<T> raw[kBatch][SLICE];
+    const T* xs[kBatch];
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      const int i = min(max(src[min(e + q, n_src - 1)], 0), a.N - 1);   // device data: stay inside the span
+      xs[q] = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+#pragma unroll
+      for (int u = 0; u < SLICE; ++u)
+        if (full[u]) load_raw(xs[q] + d0 + (u * kWave + lane) * kVec, raw[q][u]);
     }
-    if (lane == 0 && d0 == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
-  } else {
-    t = r + a.n_disc;
+#pragma unroll
+    for (int q = 0; q < kBatch; ++q) {
+      if (e + q >= n_src) break;     // uniform over the wavefront
+      const double wq = w[e + q];
+#pragma unroll
+      for (int u = 0; u < SLICE; ++u) {
+        const int d = d0 + (u * kWave + lane) * kVec;
+        if (full[u]) {
+          fma_raw(raw[q][u], wq, num[u]);
+        } else {
+          for (int k = 0; k < kVec; ++k)
+            if (d + k < a.D) num[u][k] += wq * widen(xs[q][d + k]);
+        }
+      }
+    }
+  }
+}
+
+// Per-source edge table of one image in LDS (scanning mode): count, token, and the first two
+// (target, weight) pairs of every discarded row; further pairs stay in global memory.
+struct EdgeTable {
+  double* a0;
+  double* a1;
+  int* cnt;
+  int* src;
+  int* t0;
+  int* t1;
+};
+
+// One wavefront per (output row, feature span of 512 * SLICE).  Rows without sources, and
+// every token outside the visual span, are copied.  Where a target's sources come from:
+//   MATCH = true  (few discarded tokens): the workgroup stages the image's edge table in LDS
+//     once; each wavefront scans it, 64 discarded rows per pass, and keeps the rows that name
+//     its target in a list in ascending row order;
+//   MATCH = false: the sources are one bucket of the inverted lists (arbitrary order), put
+//     in ascending row order by rank counting across the wavefront.
+// The list is then added with several row loads in flight.  Lists longer than the LDS holds
+// take slower paths that need no list.
+template <typename T, bool MATCH, int SLICE>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
+  DBG_SPAN(3);
+  extern __shared__ __attribute__((aligned(16))) char lds_m[];
+  constexpr int kCap = MATCH ? kMatchCap : kBucketCap;
+  constexpr int kSpan = kWave * kVec * SLICE;
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  double* l_w = (double*)lds_m + wv * kCap;
+  int* l_src = (int*)((double*)lds_m + kMergeWaves * kCap) + wv * kCap;
+  EdgeTable tb;
+  {
+    char* base = lds_m + (size_t)kMergeWaves * kCap * 12;
+    tb.a0 = (double*)base;
+    tb.a1 = tb.a0 + a.n_disc;
+    tb.cnt = (int*)(tb.a1 + a.n_disc);
+    tb.src = tb.cnt + a.n_disc;
+    tb.t0 = tb.src + a.n_disc;
+    tb.t1 = tb.t0 + a.n_disc;
+  }
+  const int n_spans = (a.D + kSpan - 1) / kSpan;
+  const int unit = blockIdx.x * kMergeWaves + wv;
+  const int r = unit / n_spans;
+  const int d0 = (unit % n_spans) * kSpan;
+  const int64_t b = blockIdx.y;
+  const bool valid = r < a.n_out;
+
+  if (MATCH && a.n_disc > 0) {
+    const int e1 = min(1, a.k_max - 1);
+    for (int row = threadIdx.x; row < a.n_disc; row += kMergeWaves * kWave) {
+      const int64_t rr = b * a.n_disc + row;
+      tb.cnt[row] = min(a.edge_cnt[rr], a.k_max);
+      tb.src[row] = a.S[rr];
+      tb.t0[row] = a.edge_tgt[rr * a.k_max];
+      tb.t1[row] = a.edge_tgt[rr * a.k_max + e1];
+      tb.a0[row] = a.edge_alpha[rr * a.k_max];
+      tb.a1[row] = a.edge_alpha[rr * a.k_max + e1];
+    }
+  }
+
+  const T* Xb = (const T*)a.X + b * a.xsb;
+  T* out = (T*)a.X_out + (b * a.n_out + (valid ? r : 0)) * (int64_t)a.D;
+  int t = 0, j = -1, e0 = 0, e1 = 0;
+  if (valid) {
+    if (r < a.vis_begin) {
+      t = r;
+    } else if (r < a.vis_begin + a.n_keep) {
+      j = r - a.vis_begin;
+      int tok = a.T[b * a.n_keep + j];
+      tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
+      t = a.vis_begin + tok;
+      if (!MATCH && a.n_disc > 0) {
+        // bucket bounds are device data: keep them inside the image's edge storage
+        e0 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j], 0), a.n_disc * a.k_max);
+        e1 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j + 1], e0), a.n_disc * a.k_max);
+      }
+      if (lane == 0 && d0 == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
+    } else {
+      t = r + a.n_disc;
+    }
   }
   const T* x = Xb + (int64_t)t * a.xsn;
   const bool merged_row = j >= 0 && a.n_disc > 0;
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+  bool full[SLICE];
+#pragma unroll
+  for (int u = 0; u < SLICE; ++u) full[u] = d0 + (u * kWave + lane) * kVec + kVec <= a.D;
+  // this row's own slices, in flight while its sources are looked up
+  Raw8<T> xr[SLICE];
+  if (valid) {
+#pragma unroll
+    for (int u = 0; u < SLICE; ++u)
+      if (full[u]) load_raw(x + d0 + (u * kWave + lane) * kVec, xr[u]);
+  }
+  if (MATCH) __syncthreads();   // the edge table is complete (every wavefront arrives here)
+  if (!valid) return;
 
   // ---- sources of this target -------------------------------------------------------------
   int n_src = 0;
@@ -178,94 +272,103 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
     for (int base = 0; base < a.n_disc; base += kWave) {
       const int row = base + lane;
       const bool in = row < a.n_disc;
-      const int64_t rr = b * a.n_disc + (in ? row : 0);
-      const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
-      int t0, src;
-      double w;
-      if (a.pack) {
-        const EdgeRec e = a.pack[rr * a.k_max];
-        t0 = e.tgt; src = e.src; w = e.alpha;
-      } else {
-        t0 = a.edge_tgt[rr * a.k_max];
-        src = a.S[rr];
-        w = 0.0;
-      }
-      int he = (cnt > 0 && t0 == j) ? 0 : -1;
-      for (int e = 1; e < cnt; ++e)
-        if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
-      const bool hit = he >= 0;
-      if (hit && (he > 0 || !a.pack)) w = a.edge_alpha[rr * a.k_max + he];
+      const int cnt = in ? tb.cnt[row] : 0;
+      bool hit = false;
+      double w = 0.0;
+      if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
+      if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
+      for (int e = 2; e < cnt; ++e)
+        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
       const unsigned long long m = __ballot(hit);
       if (hit) {
         const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
-        if (slot < kMatchCap) { m_src[wv][slot] = src; m_w[wv][slot] = w; }
+        if (slot < kCap) { l_src[slot] = tb.src[row]; l_w[slot] = w; }
       }
       n_src += __popcll(m);
     }
   } else if (merged_row) {
     n_src = e1 - e0;
-    if (n_src > 0 && n_src <= kMatchCap) {
-      // bucket -> ascending source row: rank of an entry = number of entries with a smaller row
-      const bool in = lane < n_src;
-      const int row = in ? a.tgt_src[ebase + e0 + lane] : 0x7fffffff;
-      const double w = in ? a.tgt_alpha[ebase + e0 + lane] : 0.0;
-      const int src = in ? a.S[b * a.n_disc + min(max(row, 0), a.n_disc - 1)] : 0;
-      int rank = 0;
-      for (int l = 0; l < n_src; ++l) rank += __shfl(row, l, kWave) < row ? 1 : 0;
-      if (in) { m_src[wv][rank] = src; m_w[wv][rank] = w; }
+    if (n_src > 0 && n_src <= kCap) {
+      // bucket -> ascending discarded row: rank of an entry = number of entries with a smaller row
+      const int n_q = (n_src + kWave - 1) / kWave;
+      int row[kBucketPer], rank[kBucketPer];
+      double w[kBucketPer];
+#pragma unroll
+      for (int q = 0; q < kBucketPer; ++q) {
+        const bool in = q * kWave + lane < n_src;
+        row[q] = in ? a.tgt_src[ebase + e0 + q * kWave + lane] : 0x7fffffff;
+        w[q] = in ? a.tgt_alpha[ebase + e0 + q * kWave + lane] : 0.0;
+        rank[q] = 0;
+      }
+#pragma unroll
+      for (int q2 = 0; q2 < kBucketPer; ++q2) {
+        if (q2 >= n_q) break;
+        const int lim = min(kWave, n_src - q2 * kWave);
+        for (int l = 0; l < lim; ++l) {
+          const int v = __shfl(row[q2], l, kWave);
+#pragma unroll
+          for (int q = 0; q < kBucketPer; ++q) rank[q] += v < row[q] ? 1 : 0;
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kBucketPer; ++q) {
+        if (q * kWave + lane < n_src) {
+          l_src[rank[q]] = a.S[b * a.n_disc + min(max(row[q], 0), a.n_disc - 1)];
+          l_w[rank[q]] = w[q];
+        }
+      }
     }
   }
-  bool full[kMergeSlice];
-#pragma unroll
-  for (int u = 0; u < kMergeSlice; ++u) full[u] = d0 + (u * kWave + lane) * kVec + kVec <= a.D;
   if (!merged_row || n_src == 0) {  // nothing merged into this row: exact copy
 #pragma unroll
-    for (int u = 0; u < kMergeSlice; ++u) {
+    for (int u = 0; u < SLICE; ++u) {
       const int d = d0 + (u * kWave + lane) * kVec;
-      if (full[u]) copy8<T>(x + d, out + d);
+      if (full[u]) __builtin_memcpy(out + d, &xr[u], sizeof(xr[u]));
       else
         for (int k = 0; k < kVec; ++k)
           if (d + k < a.D) out[d + k] = x[d + k];
     }
     return;
   }
-  // this lane's slices of the row
-  double num[kMergeSlice][kVec];
+  double num[SLICE][kVec];
 #pragma unroll
-  for (int u = 0; u < kMergeSlice; ++u) {
+  for (int u = 0; u < SLICE; ++u) {
     const int d = d0 + (u * kWave + lane) * kVec;
-    if (full[u]) load8<T>(x + d, num[u]);
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) num[u][k] = 0.0;
+    if (full[u]) add_raw(xr[u], num[u]);
     else
       for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
   }
 
   double den = 1.0;
-  if (n_src <= kMatchCap) {
-    for (int e = 0; e < n_src; ++e) den += m_w[wv][e];
-    for (int e = 0; e < n_src; ++e) add_source<T>(a, Xb, m_src[wv][e], m_w[wv][e], d0, lane, full, num);
+  if (n_src <= kCap) {
+    for (int e = 0; e < n_src; ++e) den += l_w[e];
+    add_sources<T, SLICE>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
   } else if (MATCH) {
     // more sources than the list holds: add while scanning
     for (int base = 0; base < a.n_disc; base += kWave) {
       const int row = base + lane;
       const bool in = row < a.n_disc;
-      const int64_t rr = b * a.n_disc + (in ? row : 0);
-      const int cnt = in ? min(a.edge_cnt[rr], a.k_max) : 0;
-      int he = -1;
-      for (int e = 0; e < cnt; ++e)
-        if (a.edge_tgt[rr * a.k_max + e] == j) he = e;
-      const double w = he >= 0 ? a.edge_alpha[rr * a.k_max + he] : 0.0;
-      const int src = a.S[rr];
-      unsigned long long m = __ballot(he >= 0);
+      const int cnt = in ? tb.cnt[row] : 0;
+      bool hit = false;
+      double w = 0.0;
+      if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
+      if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
+      for (int e = 2; e < cnt; ++e)
+        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
+      const int src = in ? tb.src[row] : 0;
+      unsigned long long m = __ballot(hit);
       while (m) {
         const int l = __ffsll(m) - 1;
         m &= m - 1;
         const double wl = __shfl(w, l, kWave);
         den += wl;
-        add_source<T>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+        add_source<T, SLICE>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
       }
     }
   } else {
-    // long bucket: take its entries in ascending source row by repeated minimum search
+    // long bucket: take its entries in ascending discarded row by repeated minimum search
     int last = -1;
     for (int k = 0; k < n_src; ++k) {
       int best = 0x7fffffff, best_e = -1;
@@ -281,12 +384,12 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
       const int e = __shfl(best_e, l, kWave);
       const double w = a.tgt_alpha[ebase + e];
       den += w;
-      add_source<T>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
+      add_source<T, SLICE>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
       last = mn;
     }
   }
 #pragma unroll
-  for (int u = 0; u < kMergeSlice; ++u) {
+  for (int u = 0; u < SLICE; ++u) {
     const int d = d0 + (u * kWave + lane) * kVec;
     if (full[u]) {
       Pack8<T> o;
@@ -301,11 +404,33 @@ __global__ __launch_bounds__(256) void merge_rows_kernel(MergeArgs a) {
 }
 
 constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
+#ifndef FICOCO_MERGE_SLICE
+#define FICOCO_MERGE_SLICE 0          // 0: chosen per problem
+#endif
+
+template <typename T, bool MATCH, int SLICE>
+static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
+  constexpr int kSpan = kWave * kVec * SLICE;
+  const int n_spans = (m.D + kSpan - 1) / kSpan;
+  const size_t lds = (size_t)kMergeWaves * (MATCH ? kMatchCap : kBucketCap) * 12 + (MATCH ? (size_t)m.n_disc * 32 : 0);
+  dim3 grid((m.n_out * n_spans + kMergeWaves - 1) / kMergeWaves, B), block(kMergeWaves * kWave);
+  hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE>), grid, block, lds, s, m);
+}
+
+template <typename T>
+static void launch_merge_t(const MergeArgs& m, int B, bool match, int slice, hipStream_t s) {
+  if (match) {
+    if (slice == 1) launch_merge<T, true, 1>(m, B, s); else launch_merge<T, true, 2>(m, B, s);
+  } else {
+    if (slice == 1) launch_merge<T, false, 1>(m, B, s); else launch_merge<T, false, 2>(m, B, s);
+  }
+}
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,
                      hipStream_t s) {
+  (void)use_pack;
   const bool match = pl.n_disc <= kMatchMaxRows;
   if (pl.n_disc > 0 && !match) {
     InvertArgs a{};
@@ -328,18 +453,13 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.tgt_src = (const int32_t*)(ws + pl.tgt_src);
   m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
-  m.pack = use_pack ? (const EdgeRec*)(ws + pl.edge_pack) : nullptr;
   m.pos = p.pos; m.pos_out = pos_out;
-  const int n_spans = (p.D + kMergeSpan - 1) / kMergeSpan;
-  dim3 grid((pl.n_out * n_spans + 3) / 4, p.B), block(256);
-  const bool bf16 = p.dtype == FICOCO_BF16;
-  if (match) {
-    if (bf16) hipLaunchKernelGGL((merge_rows_kernel<bf16_t, true>), grid, block, 0, s, m);
-    else hipLaunchKernelGGL((merge_rows_kernel<float, true>), grid, block, 0, s, m);
-  } else {
-    if (bf16) hipLaunchKernelGGL((merge_rows_kernel<bf16_t, false>), grid, block, 0, s, m);
-    else hipLaunchKernelGGL((merge_rows_kernel<float, false>), grid, block, 0, s, m);
-  }
+  // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when
+  // the wide ones would not fill the chip.
+  int slice = FICOCO_MERGE_SLICE;
+  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 8192 ? 2 : 1;
+  if (p.dtype == FICOCO_BF16) launch_merge_t<bf16_t>(m, p.B, match, slice, s);
+  else launch_merge_t<float>(m, p.B, match, slice, s);
 }
 
 }  // namespace ficoco

@@ -236,6 +236,11 @@ def main():
     bufs = [fc.Buffers(probs[0], dev, tdt) for _ in range(n_str)]
     step_fn = fc.ficoco_v_step if W["variant"] == fc.VARIANT_V else fc.ficoco_l_step
     sync = torch.cuda.synchronize
+    # The inputs were drawn on the default stream and the side streams do not wait for it; the
+    # buffers above may also sit in memory that temporaries of the generators (index tensors
+    # among them) gave back to the allocator while kernels reading them are still queued.
+    # Everything queued so far has to finish before a side stream touches any of it.
+    sync()
 
     def run_steps(k, probe=None):
         # Successive steps are independent batches: step i goes to stream i mod n_str.

@@ -53,9 +53,14 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
   const int ncol = min(kVec, a.N - col);
   const bool active = rl < a.row_lanes && ncol > 0;
 
-  double acc[kVec];
+  // This thread's column partial lives in its own LDS slots while it walks its rows (registers
+  // are what limits the number of resident wavefronts here).
+  const int width = a.strip_groups * kVec;
+  double* mine = lds + (rl < a.row_lanes ? rl : 0) * width + cg * kVec;
+  if (rl < a.row_lanes) {
 #pragma unroll
-  for (int k = 0; k < kVec; ++k) acc[k] = 0.0;
+    for (int k = 0; k < kVec; ++k) mine[k] = 0.0;
+  }
 
   if (active) {
     const int r_begin = a.row0 + chunk * a.rows_per_wg;
@@ -95,7 +100,7 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
 
       if (is_vis) {
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) acc[k] += p[k];
+        for (int k = 0; k < kVec; ++k) mine[k] += p[k];
         if (a.abar FICOCO_DBG_ABAR) {
           float* dst = a.abar + ((int64_t)b * a.N + (r - a.vis_r0)) * a.N + col;
           if (ncol == kVec) {
@@ -121,11 +126,6 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
 
   if (a.recv_part == nullptr) return;  // uniform for the whole grid
   // Combine the row lanes in a fixed order, then one partial per (image, chunk, column).
-  const int width = a.strip_groups * kVec;
-  if (rl < a.row_lanes) {
-#pragma unroll
-    for (int k = 0; k < kVec; ++k) lds[rl * width + cg * kVec + k] = acc[k];
-  }
   __syncthreads();
   if (rl == 0 && ncol > 0) {
     double* dst = a.recv_part + ((int64_t)b * a.n_chunks + chunk) * a.N + col;

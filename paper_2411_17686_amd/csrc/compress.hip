@@ -107,7 +107,10 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-constexpr int kMergeWaves = 8;    // wavefronts (= output row spans) per workgroup
+#ifndef FICOCO_MERGE_WAVES
+#define FICOCO_MERGE_WAVES 8
+#endif
+constexpr int kMergeWaves = FICOCO_MERGE_WAVES;    // wavefronts (= output row spans) per workgroup
 constexpr int kMatchCap = 64;     // scanning mode: sources of one target kept in LDS
 constexpr int kBucketCap = 256;   // inverted lists: bucket entries put in order in LDS
 constexpr int kBucketPer = kBucketCap / kWave;
@@ -136,11 +139,12 @@ __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int 
 // The same for a whole list held in LDS, in list order, with the row loads of kBatch sources
 // issued before the first of them is added: a target with n sources then waits for
 // ceil(n / kBatch) memory round trips instead of n.
-template <typename T, int SLICE>
+template <typename T, int SLICE, int REGS>
 __device__ __forceinline__ void add_sources(const MergeArgs& a, const T* Xb, const int* src, const double* w,
                                             int n_src, int d0, int lane, const bool (&full)[SLICE],
                                             double (&num)[SLICE][kVec]) {
-  constexpr int kBatch = 32 / (SLICE * (int)(sizeof(Raw8<T>) / 4));   // 32 registers of raw data in flight
+  constexpr int kWant = REGS / (SLICE * (int)(sizeof(Raw8<T>) / 4));   // REGS registers of raw data in flight
+  constexpr int kBatch = kWant < 1 ? 1 : kWant;
   for (int e = 0; e < n_src; e += kBatch) {
     Raw8<T> raw[kBatch][SLICE];
     const T* xs[kBatch];
@@ -344,7 +348,9 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   double den = 1.0;
   if (n_src <= kCap) {
     for (int e = 0; e < n_src; ++e) den += l_w[e];
-    add_sources<T, SLICE>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
+    // scanning mode serves few discarded tokens, hence few sources per target: a short batch
+    // keeps the register count where every wavefront of the grid is resident at once
+    add_sources<T, SLICE, MATCH ? 16 : 32>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
   } else if (MATCH) {
     // more sources than the list holds: add while scanning
     for (int base = 0; base < a.n_disc; base += kWave) {

@@ -111,12 +111,19 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
         const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
         double acc = 0.0;
         int c = 0;
-        for (; c + 16 <= a.n_chunks; c += 16) {          // 16 independent loads, added in order
-          double v[16];
+        for (; c + 32 <= a.n_chunks; c += 32) {          // 32 independent loads, added in order
+          double v[32];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(c + u) * N];
+          for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * N];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) acc += v[u];
+          for (int u = 0; u < 32; ++u) acc += v[u];
+        }
+        for (; c + 8 <= a.n_chunks; c += 8) {
+          double v[8];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(c + u) * N];
+#pragma unroll
+          for (int u = 0; u < 8; ++u) acc += v[u];
         }
         for (; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
         R = acc / (double)N;

@@ -211,7 +211,7 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run five plain 1 GiB device-to-device copies (a kernel of known traffic "
                          "against which rocprofv3 FETCH_SIZE / WRITE_SIZE readings are scaled)")
-    ap.add_argument("--streams", type=int, default=2,
+    ap.add_argument("--streams", type=int, default=3,
                     help="HIP streams the independent steps are issued on, round-robin (each has its own "
                          "workspace and outputs); 1 = strictly one step after the other")
     args = ap.parse_args()
@@ -296,6 +296,16 @@ def main():
     alone = sorted(e0.elapsed_time(e1) for e0, e1 in pairs)
     alone_ms = sum(alone) / len(alone)
 
+    # (iii) latency of one fused step: event pairs around single calls, one stream, back to back
+    lat_pairs = event_pairs(args.steps)
+    with torch.cuda.stream(streams[0]):
+        for i in range(args.steps):
+            lat_pairs[i][0].record(streams[0])
+            step_fn(ctx, probs[i % n_sets], bufs[0])
+            lat_pairs[i][1].record(streams[0])
+    sync()
+    lat = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in lat_pairs)
+
     if W["dominant"] == "reduce":
         algo = W["reduce_bytes"]
         achieved = algo / (alone_ms * 1e-3) / 1e9
@@ -326,6 +336,8 @@ def main():
                    "decision_dtype": "f64", "streams": n_str},
         "roofline": roof,
     }
+    out["step_latency_us"] = {"median": lat[len(lat) // 2], "p10": lat[len(lat) // 10], "p90": lat[(9 * len(lat)) // 10],
+                              "how": "HIP event pair around each of %d fused calls issued back to back on one stream" % len(lat)}
     if W.get("step_bytes"):
         out["step_algorithmic_bytes"] = W["step_bytes"]
         out["step_hbm_frac"] = W["step_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS

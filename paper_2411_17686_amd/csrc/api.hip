@@ -162,7 +162,6 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.tgt_src = take(B * (size_t)pl.n_disc * p.k_max * sizeof(int32_t));
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
-  pl.edge_pack = take(B * (size_t)pl.n_disc * p.k_max * sizeof(EdgeRec));
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;
   pl.ct = take(pl.use_gram ? B * (size_t)pl.n_disc * p.n_keep * sizeof(float) : 0);
@@ -219,7 +218,7 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true,
                    pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr, s);
-  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, true, s);
+  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
   return finish(ctx, fn);
 }
 
@@ -333,7 +332,7 @@ int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t w
   if (!X_out || !keep_idx || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_compress", "a pointer is NULL");
   launch_compress(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out,
-                  pos_out, false, (hipStream_t)stream);
+                  pos_out, (hipStream_t)stream);
   return finish(ctx, "ficoco_compress");
 }
 

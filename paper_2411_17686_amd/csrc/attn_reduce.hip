@@ -20,6 +20,12 @@ namespace ficoco {
 #define FICOCO_HEAD_BATCH 8
 #endif
 constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
+// LDS requested per workgroup at least (bytes): a way to bound how many workgroups of this
+// kernel a compute unit holds (160 KB / request), which leaves wavefront slots for the short
+// kernels of another stream that run next to it.
+#ifndef FICOCO_REDUCE_LDS_MIN
+#define FICOCO_REDUCE_LDS_MIN 0
+#endif
 #ifndef FICOCO_DBG_ABAR
 #define FICOCO_DBG_ABAR
 #endif
@@ -139,7 +145,8 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
 
 static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hipStream_t s) {
   dim3 grid(a.n_chunks, col_strips, B), block(kReduceThreads);
-  const size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
+  size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
+  if (lds < (size_t)FICOCO_REDUCE_LDS_MIN) lds = FICOCO_REDUCE_LDS_MIN;
   if (bf16)
     hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, a);
   else

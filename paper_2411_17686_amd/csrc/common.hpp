@@ -52,7 +52,6 @@ struct Plan {
   size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
-  size_t edge_pack;      // EdgeRec [B][N^S][k_max]  edges as the merge kernel reads them
   size_t ct;             // float  [B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
@@ -64,7 +63,6 @@ int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
 
 // One edge of the correlate stage in the form the merge kernel scans: target slot, source
 // visual token, weight.  16 bytes, one load.
-struct __attribute__((aligned(16))) EdgeRec { int32_t tgt; int32_t src; double alpha; };
 
 // ---- launchers (all asynchronous on `s`) -----------------------------------------------
 void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
@@ -81,7 +79,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
                       hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s);
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
-                     const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,
+                     const double* edge_alpha, void* X_out, int32_t* pos_out,
                      hipStream_t s);
 
 // ---- device helpers ----------------------------------------------------------------------

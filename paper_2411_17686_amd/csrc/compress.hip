@@ -1,16 +1,16 @@
 // Compress stage: self-preserving compression (Eq. 2) and the removal of the discarded
 // tokens (last lines of Algorithm 1/2).
 //
-// `merge_rows` is a pure pull: one wavefront per OUTPUT row (and per 1024-feature span of it)
-// reads its own token plus its sources and writes
+// `merge_rows` is a pure pull: one wavefront per OUTPUT row (and per feature span of it) reads
+// its own token plus its sources and writes
 //     (X_j + sum_i alpha_ij X_i) / (1 + sum_i alpha_ij)
 // accumulated in double precision in ascending i; rows without sources, and every token
 // outside the visual span, are copied bit for bit.  No floating-point atomics anywhere.
-// Where the sources come from: with few discarded tokens the wavefront scans the per-source
-// edge records itself; otherwise `invert_edges` first buckets the edges by target with an
-// integer counting sort in LDS (arrival order inside a bucket is arbitrary) and the merging
-// wavefront puts its bucket into ascending source order before it adds, so the result never
-// depends on scheduling.
+// Where the sources come from: with few discarded tokens the workgroup stages the image's
+// per-source edge lists in LDS and every wavefront scans them for its target; otherwise
+// `invert_edges` first buckets the edges by target with an integer counting sort in LDS
+// (order inside a bucket is arbitrary) and the merging wavefront puts its bucket into
+// ascending source order before it adds, so the result never depends on scheduling.
 #include "common.hpp"
 
 namespace ficoco {
@@ -25,21 +25,48 @@ struct InvertArgs {
   double* tgt_alpha;
 };
 
+constexpr int kInvertRows = 512;   // discarded rows one workgroup scatters
+constexpr int kInvertPre = 4;      // targets per row loaded before the row's count is known
+
+// Buckets the edges of one image by target.  gridDim.x workgroups share an image: every one
+// of them counts ALL edges of the image into an LDS histogram (cheap, and it needs no
+// exchange between workgroups), noting separately how many come from rows before its own
+// share; the prefix sum of the histogram gives the bucket offsets, and offset + "before"
+// is where this workgroup's own rows start inside each bucket.  Then it scatters its rows.
+// No global atomics, nothing to clear beforehand, bucket regions per workgroup are fixed;
+// only the order inside a region depends on scheduling (the merge orders buckets itself).
 __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs a) {
   extern __shared__ int lds_i[];
   int* cnt = lds_i;                       // [n_keep+1] counts, then exclusive offsets
-  int* cursor = lds_i + (a.n_keep + 1);   // [n_keep]
+  int* cursor = lds_i + (a.n_keep + 1);   // [n_keep] edges from earlier shares, then write cursor
   int* part = cursor + a.n_keep;          // [2][nt] scan scratch
-  const int64_t b = blockIdx.x;
+  const int64_t b = blockIdx.y;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int n = a.n_keep;
+  const int share = (a.n_disc + (int)gridDim.x - 1) / (int)gridDim.x;
+  const int r_lo = min((int)blockIdx.x * share, a.n_disc), r_hi = min(r_lo + share, a.n_disc);
   for (int j = tid; j <= n; j += nt) cnt[j] = 0;
+  for (int j = tid; j < n; j += nt) cursor[j] = 0;
   __syncthreads();
+  const int64_t rbase = b * a.n_disc;
   for (int r = tid; r < a.n_disc; r += nt) {
-    const int c = min(a.edge_cnt[b * a.n_disc + r], a.k_max);
+    const int c = min(a.edge_cnt[rbase + r], a.k_max);
+    int pre[kInvertPre];
+#pragma unroll
+    for (int e = 0; e < kInvertPre; ++e) pre[e] = a.edge_tgt[(rbase + r) * a.k_max + min(e, a.k_max - 1)];
+    const bool before = r < r_lo;
     for (int e = 0; e < c; ++e) {
-      const int j = a.edge_tgt[(b * a.n_disc + r) * a.k_max + e];
-      if (j >= 0 && j < n) atomicAdd(&cnt[j], 1);
+      int j = 0;
+      if (e < kInvertPre) {
+#pragma unroll
+        for (int q = 0; q < kInvertPre; ++q) j = e == q ? pre[q] : j;
+      } else {
+        j = a.edge_tgt[(rbase + r) * a.k_max + e];
+      }
+      if (j >= 0 && j < n) {
+        atomicAdd(&cnt[j], 1);
+        if (before) atomicAdd(&cursor[j], 1);
+      }
     }
   }
   __syncthreads();
@@ -62,22 +89,26 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   for (int j = lo; j < hi; ++j) {
     const int c = cnt[j];
     cnt[j] = run;
-    cursor[j] = run;
+    cursor[j] += run;
     run += c;
   }
   if (tid == 0) cnt[n] = total;
   __syncthreads();
-  for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
+  if (blockIdx.x == 0)
+    for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
-  for (int r = tid; r < a.n_disc; r += nt) {
-    const int c = min(a.edge_cnt[b * a.n_disc + r], a.k_max);
+  const int cap = a.n_disc * a.k_max;
+  for (int r = r_lo + tid; r < r_hi; r += nt) {
+    const int c = min(a.edge_cnt[rbase + r], a.k_max);
     for (int e = 0; e < c; ++e) {
-      const int64_t src = (b * a.n_disc + r) * a.k_max + e;
+      const int64_t src = (rbase + r) * a.k_max + e;
       const int j = a.edge_tgt[src];
       if (j >= 0 && j < n) {
         const int slot = atomicAdd(&cursor[j], 1);
-        a.tgt_src[ebase + slot] = r;
-        a.tgt_alpha[ebase + slot] = a.edge_alpha[src];
+        if (slot < cap) {                     // always true for consistent lists; they are device data
+          a.tgt_src[ebase + slot] = r;
+          a.tgt_alpha[ebase + slot] = a.edge_alpha[src];
+        }
       }
     }
   }
@@ -434,9 +465,8 @@ static void launch_merge_t(const MergeArgs& m, int B, bool match, int slice, hip
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
-                     const double* edge_alpha, void* X_out, int32_t* pos_out, bool use_pack,
+                     const double* edge_alpha, void* X_out, int32_t* pos_out,
                      hipStream_t s) {
-  (void)use_pack;
   const bool match = pl.n_disc <= kMatchMaxRows;
   if (pl.n_disc > 0 && !match) {
     InvertArgs a{};
@@ -448,7 +478,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
     const size_t lds = ((size_t)2 * p.n_keep + 1 + 2 * kSelectThreads) * sizeof(int);
     if (lds > 32768)
       (void)hipFuncSetAttribute((const void*)invert_edges_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    hipLaunchKernelGGL(invert_edges_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+    const int groups = (pl.n_disc + kInvertRows - 1) / kInvertRows;
+    hipLaunchKernelGGL(invert_edges_kernel, dim3(groups, p.B), dim3(kSelectThreads), lds, s, a);
   }
   MergeArgs m{};
   m.X = p.X; m.xsb = p.x_stride_b; m.xsn = p.x_stride_n; m.X_out = X_out;

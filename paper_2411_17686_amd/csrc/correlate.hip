@@ -33,7 +33,6 @@ struct CorrArgs {
   int32_t* edge_tgt;
   double* edge_alpha;
   int32_t* overflow;
-  EdgeRec* pack;         // [B][n_disc][k_max]
   const int32_t* slot_of; // [B][N] keep slot of a visual token, -1 if discarded
   float* ct;             // [B][n_disc][n_keep] approximate cosines from the matrix cores
   double* cmax;          // [B][M]
@@ -219,13 +218,11 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
       const double al = my_c / denom;
       a.edge_tgt[ebase + lane] = my_tgt;
       a.edge_alpha[ebase + lane] = al;
-      a.pack[ebase + lane] = EdgeRec{my_tgt, i, al};
     }
   } else if (live && lane == 0) {
     for (int e = 0; e < stored; ++e) {
       const double al = a.edge_alpha[ebase + e] / denom;
       a.edge_alpha[ebase + e] = al;
-      a.pack[ebase + e] = EdgeRec{a.edge_tgt[ebase + e], i, al};
     }
   }
   if (lane == 0) {
@@ -441,7 +438,6 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     const double al = myv / denom;
     a.edge_tgt[ebase + my_pos] = myjj;
     a.edge_alpha[ebase + my_pos] = al;
-    a.pack[ebase + my_pos] = EdgeRec{myjj, i, al};
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -614,7 +610,6 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
         const double al = (double)hit_v[c][x] / denom;
         a.edge_tgt[ebase + x] = hit_j[c][x];
         a.edge_alpha[ebase + x] = al;
-        a.pack[ebase + x] = EdgeRec{hit_j[c][x], i, al};
       }
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
     if (live && cnt > a.k_max) a.overflow[b] = 1;
@@ -647,7 +642,6 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.dense = pl.dense_rows ? 1 : 0;
   a.rowbuf = (double*)(ws + pl.rowbuf);
   a.edge_cnt = edge_cnt; a.edge_tgt = edge_tgt; a.edge_alpha = edge_alpha; a.overflow = overflow;
-  a.pack = (EdgeRec*)(ws + pl.edge_pack);
   a.slot_of = (const int32_t*)(ws + pl.slot_of);
   a.ct = (float*)(ws + pl.ct);
   a.cmax = (double*)(ws + pl.cmax);

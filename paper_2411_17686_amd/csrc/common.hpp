@@ -138,6 +138,20 @@ __device__ __forceinline__ void fma_raw(const Raw8<float>& r, double w, double (
   acc[4] += w * r.b.x; acc[5] += w * r.b.y; acc[6] += w * r.b.z; acc[7] += w * r.b.w;
 }
 
+// the 8 elements held raw, as doubles
+__device__ __forceinline__ void widen_raw(const Raw8<bf16_t>& r, double (&out)[kVec]) {
+  const uint32_t q[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    out[2 * j] = (double)__uint_as_float(q[j] << 16);
+    out[2 * j + 1] = (double)__uint_as_float(q[j] & 0xffff0000u);
+  }
+}
+__device__ __forceinline__ void widen_raw(const Raw8<float>& r, double (&out)[kVec]) {
+  out[0] = r.a.x; out[1] = r.a.y; out[2] = r.a.z; out[3] = r.a.w;
+  out[4] = r.b.x; out[5] = r.b.y; out[6] = r.b.z; out[7] = r.b.w;
+}
+
 // 8 consecutive elements from an address that is only element aligned.
 template <typename T>
 __device__ __forceinline__ void load8(const T* __restrict__ p, double (&out)[kVec]);

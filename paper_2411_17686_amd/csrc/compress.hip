@@ -27,6 +27,7 @@ struct InvertArgs {
 
 constexpr int kInvertRows = 512;   // discarded rows one workgroup scatters
 constexpr int kInvertPre = 4;      // targets per row loaded before the row's count is known
+constexpr int kInvertBatch = 4;    // rows per thread whose loads are in flight together
 
 // Buckets the edges of one image by target.  gridDim.x workgroups share an image: every one
 // of them counts ALL edges of the image into an LDS histogram (cheap, and it needs no
@@ -49,23 +50,35 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   for (int j = tid; j < n; j += nt) cursor[j] = 0;
   __syncthreads();
   const int64_t rbase = b * a.n_disc;
-  for (int r = tid; r < a.n_disc; r += nt) {
-    const int c = min(a.edge_cnt[rbase + r], a.k_max);
-    int pre[kInvertPre];
+  // Count pass over all rows of the image, kInvertBatch rows per thread at a time with every
+  // load of the batch issued before the first use.
+  for (int r0 = tid; r0 < a.n_disc; r0 += nt * kInvertBatch) {
+    int c[kInvertBatch];
+    int pre[kInvertBatch][kInvertPre];
 #pragma unroll
-    for (int e = 0; e < kInvertPre; ++e) pre[e] = a.edge_tgt[(rbase + r) * a.k_max + min(e, a.k_max - 1)];
-    const bool before = r < r_lo;
-    for (int e = 0; e < c; ++e) {
-      int j = 0;
-      if (e < kInvertPre) {
+    for (int u = 0; u < kInvertBatch; ++u) {
+      const int r = min(r0 + u * nt, a.n_disc - 1);      // clamped: always a valid address
+      c[u] = min(a.edge_cnt[rbase + r], a.k_max);
 #pragma unroll
-        for (int q = 0; q < kInvertPre; ++q) j = e == q ? pre[q] : j;
-      } else {
-        j = a.edge_tgt[(rbase + r) * a.k_max + e];
-      }
-      if (j >= 0 && j < n) {
-        atomicAdd(&cnt[j], 1);
-        if (before) atomicAdd(&cursor[j], 1);
+      for (int e = 0; e < kInvertPre; ++e) pre[u][e] = a.edge_tgt[(rbase + r) * a.k_max + min(e, a.k_max - 1)];
+    }
+#pragma unroll
+    for (int u = 0; u < kInvertBatch; ++u) {
+      const int r = r0 + u * nt;
+      if (r >= a.n_disc) break;
+      const bool before = r < r_lo;
+      for (int e = 0; e < c[u]; ++e) {
+        int j = 0;
+        if (e < kInvertPre) {
+#pragma unroll
+          for (int q = 0; q < kInvertPre; ++q) j = e == q ? pre[u][q] : j;
+        } else {
+          j = a.edge_tgt[(rbase + r) * a.k_max + e];
+        }
+        if (j >= 0 && j < n) {
+          atomicAdd(&cnt[j], 1);
+          if (before) atomicAdd(&cursor[j], 1);
+        }
       }
     }
   }
@@ -494,7 +507,7 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when
   // the wide ones would not fill the chip.
   int slice = FICOCO_MERGE_SLICE;
-  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 8192 ? 2 : 1;
+  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
   if (p.dtype == FICOCO_BF16) launch_merge_t<bf16_t>(m, p.B, match, slice, s);
   else launch_merge_t<float>(m, p.B, match, slice, s);
 }

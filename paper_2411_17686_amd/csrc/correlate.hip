@@ -313,6 +313,74 @@ __global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
   }
 }
 
+// Exact C[i][j_q] for up to CB targets at once, the whole wavefront working on them together
+// (all lanes return the values).  The loads of all CB rows are issued before the first use, so
+// a batch costs one memory round trip per 512 features instead of one per target.  Per target
+// the arithmetic and its order are those of corr_value_wave.
+template <int CB>
+__device__ __forceinline__ void corr_values_wave(const CorrArgs& a, int64_t b, int i, const int (&j)[CB], int lane,
+                                                 double (&out)[CB]) {
+  double direct[CB];
+  if (a.mode == kAttnL) {
+#pragma unroll
+    for (int q = 0; q < CB; ++q) direct[q] = (double)a.abar[(b * a.N + j[q]) * a.N + i];
+  } else {
+    const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
+    const bf16_t* y[CB];
+    double acc[CB];
+#pragma unroll
+    for (int q = 0; q < CB; ++q) { y[q] = a.xhat + (b * a.N + j[q]) * a.Df; acc[q] = 0.0; }
+    const int Dv = a.Df - a.Df % kVec;
+    for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+      Raw8<bf16_t> xr, yr[CB];
+      load_raw(x + d, xr);
+#pragma unroll
+      for (int q = 0; q < CB; ++q) load_raw(y[q] + d, yr[q]);
+      double u[kVec];
+      widen_raw(xr, u);
+#pragma unroll
+      for (int q = 0; q < CB; ++q) {
+        double w[kVec];
+        widen_raw(yr[q], w);
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) acc[q] += u[k] * w[k];
+      }
+    }
+    for (int d = Dv + lane; d < a.Df; d += kWave) {
+#pragma unroll
+      for (int q = 0; q < CB; ++q) acc[q] += widen(x[d]) * widen(y[q][d]);
+    }
+#pragma unroll
+    for (int q = 0; q < CB; ++q) {
+      const double t = wave_sum_f64(acc[q]);
+      direct[q] = t > 0.0 ? t : 0.0;
+    }
+  }
+  if (a.mode == kCosV) {
+#pragma unroll
+    for (int q = 0; q < CB; ++q) out[q] = direct[q];
+    return;
+  }
+  const double* ti = a.ttext + (b * a.N + i) * a.M;
+  double br[CB];
+#pragma unroll
+  for (int q = 0; q < CB; ++q) br[q] = 0.0;
+  for (int k = lane; k < a.M; k += kWave) {
+    const double tik = ti[k];
+    double tjk[CB];
+#pragma unroll
+    for (int q = 0; q < CB; ++q) tjk[q] = a.ttext[(b * a.N + j[q]) * a.M + k];
+#pragma unroll
+    for (int q = 0; q < CB; ++q) br[q] += tik * tjk[q];
+  }
+#pragma unroll
+  for (int q = 0; q < CB; ++q) out[q] = a.gamma * direct[q] + (1.0 - a.gamma) * (wave_sum_f64(br[q]) * a.invM);
+}
+
+constexpr int kCandKeep = 32;                    // approximate values held per lane
+constexpr int kCandChunk = kCandKeep * kWave;    // targets per pass over the row
+constexpr int kCandBatch = 4;                    // targets evaluated exactly at a time
+
 __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   __shared__ int cand_j[4][kCandCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
@@ -342,22 +410,50 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   const float delta = from_map ? 0.0f : a.delta;
   const float NEGF = -__builtin_huge_valf();
 
+  // One pass of the row: element u of a lane is target c0 + u*64 + lane.  All loads of a pass
+  // are independent (the map gather takes the token indices first), absent targets read as -inf.
+  float val[kCandKeep];
+  auto load_pass = [&](int c0) {
+    if (from_map) {
+      int jt[kCandKeep];
+#pragma unroll
+      for (int u = 0; u < kCandKeep; ++u) {
+        const int jj = c0 + u * kWave + lane;
+        jt[u] = jj < n ? T[jj] : -1;
+      }
+#pragma unroll
+      for (int u = 0; u < kCandKeep; ++u) {
+        const bool ok = (unsigned)jt[u] < (unsigned)a.N;
+        const float v = ct[(int64_t)(ok ? jt[u] : 0) * a.N];
+        val[u] = c0 + u * kWave + lane < n ? (ok ? v : 0.0f) : NEGF;
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kCandKeep; ++u) {
+        const int jj = c0 + u * kWave + lane;
+        const float v = ct[min(jj, n - 1)];
+        val[u] = jj < n ? v : NEGF;
+      }
+    }
+  };
+
   // lower bounds: per-lane top list, then m pops of the wavefront maximum -> lambda
   float top[kSelMax];
 #pragma unroll
   for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
-  for (int jj = lane; jj < n; jj += kWave) {
-    float c;
-    if (from_map) { const int j = T[jj]; c = (unsigned)j < (unsigned)a.N ? ct[(int64_t)j * a.N] : 0.0f; }
-    else c = ct[jj];
-    float lo = gam * fmaxf(c - delta, 0.0f);
-    if (lo > top[kSelMax - 1]) {
+  for (int c0 = 0; c0 < n; c0 += kCandChunk) {
+    load_pass(c0);
 #pragma unroll
-      for (int k = 0; k < kSelMax; ++k) {
-        const bool sw = lo > top[k];
-        const float t = top[k];
-        top[k] = sw ? lo : t;
-        lo = sw ? t : lo;
+    for (int u = 0; u < kCandKeep; ++u) {
+      float lo = val[u] == NEGF ? NEGF : gam * fmaxf(val[u] - delta, 0.0f);
+      if (lo > top[kSelMax - 1]) {
+#pragma unroll
+        for (int k = 0; k < kSelMax; ++k) {
+          const bool sw = lo > top[k];
+          const float t = top[k];
+          top[k] = sw ? lo : t;
+          lo = sw ? t : lo;
+        }
       }
     }
   }
@@ -374,24 +470,22 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     }
     lambda = mx;
   }
-  // candidates in ascending target order
+  // candidates in ascending target order (a row of one pass is still in registers)
   int n_cand = 0;
-  for (int base = 0; base < n; base += kWave) {
-    const int jj = base + lane;
-    bool is = false;
-    if (jj < n) {
-      float c;
-      if (from_map) { const int j = T[jj]; c = (unsigned)j < (unsigned)a.N ? ct[(int64_t)j * a.N] : 0.0f; }
-      else c = ct[jj];
-      const float up = gam * fmaxf(c + delta, 0.0f) * 1.000001f + extra;
-      is = up >= lambda;
+  for (int c0 = 0; c0 < n; c0 += kCandChunk) {
+    if (n > kCandChunk) load_pass(c0);
+#pragma unroll
+    for (int u = 0; u < kCandKeep; ++u) {
+      if (c0 + u * kWave >= n) break;           // uniform
+      const int jj = c0 + u * kWave + lane;
+      const bool is = jj < n && gam * fmaxf(val[u] + delta, 0.0f) * 1.000001f + extra >= lambda;
+      const unsigned long long m = __ballot(is);
+      if (is) {
+        const int slot = n_cand + __popcll(m & ((1ULL << lane) - 1ULL));
+        if (slot < kCandCap) cand_j[wv][slot] = jj;
+      }
+      n_cand += __popcll(m);
     }
-    const unsigned long long m = __ballot(is);
-    if (is) {
-      const int slot = n_cand + __popcll(m & ((1ULL << lane) - 1ULL));
-      if (slot < kCandCap) cand_j[wv][slot] = jj;
-    }
-    n_cand += __popcll(m);
   }
   if (n_cand > kCandCap) {       // uniform per wavefront
     corr_row_exact(a, b, row, lane);
@@ -399,13 +493,23 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   }
   // exact values of the candidates: lane c keeps candidate c
   const double NEG = -__builtin_huge_val();
+  const int myjj = lane < n_cand ? cand_j[wv][lane] : -1;
+  const int myj = myjj >= 0 ? T[myjj] : -1;
   double myv = NEG;
-  int myjj = -1;
-  for (int c = 0; c < n_cand; ++c) {
-    const int jj = cand_j[wv][c];
-    const int j = T[jj];
-    const double v = (unsigned)j < (unsigned)a.N ? corr_value_wave(a, b, i, j, lane) : NEG;
-    if (lane == c) { myv = v; myjj = jj; }
+  for (int c = 0; c < n_cand; c += kCandBatch) {
+    int j[kCandBatch];
+    bool ok[kCandBatch];
+#pragma unroll
+    for (int q = 0; q < kCandBatch; ++q) {
+      const int jq = __shfl(myj, min(c + q, n_cand - 1), kWave);
+      ok[q] = (unsigned)jq < (unsigned)a.N;
+      j[q] = ok[q] ? jq : i;                   // a valid row to read; the value is dropped
+    }
+    double v[kCandBatch];
+    corr_values_wave<kCandBatch>(a, b, i, j, lane, v);
+#pragma unroll
+    for (int q = 0; q < kCandBatch; ++q)
+      if (lane == c + q && c + q < n_cand) myv = ok[q] ? v[q] : NEG;
   }
   // v[f], v[f+1] = m-th and (m-1)-th largest of the exact candidate values
   double v_f = NEG, v_f1 = NEG;

@@ -319,6 +319,19 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const double* __r
   out[b * N + i] = acc;
 }
 
+// Long sequences with per-head vectors as score terms: their head means are formed by a grid
+// of workgroups first (same arithmetic), so the per-image workgroup of select_kernel reads one
+// value per token and term instead of 2 H strided ones.
+__global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec, const void* sem_vec, int dtype, int H,
+                                                           int N, double* __restrict__ out_r,
+                                                           double* __restrict__ out_g) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = blockIdx.y;
+  if (i >= N) return;
+  if (recv_vec) out_r[b * N + i] = vec_head_mean(recv_vec, dtype, b, H, N, i);
+  if (sem_vec) out_g[b * N + i] = vec_head_mean(sem_vec, dtype, b, H, N, i);
+}
+
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
   return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + cells) * sizeof(int);
@@ -345,6 +358,15 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.recv_vec = p.recv_vec; a.sem_vec = p.sem_vec;
   a.fterm_r = (const double*)(ws + pl.fterm);
   a.fterm_g = (const double*)(ws + pl.fterm2);
+  if (do_score && p.N > 2 * kSelectThreads && (p.red_src == FICOCO_R_VECTOR || p.sem_src == FICOCO_G_VECTOR)) {
+    // the term buffers of the vector-sourced terms are free (the feature stage fills only the others)
+    const bool vr = p.red_src == FICOCO_R_VECTOR, vg = p.sem_src == FICOCO_G_VECTOR;
+    hipLaunchKernelGGL(vector_terms_kernel, dim3((p.N + 255) / 256, p.B), dim3(256), 0, s, vr ? p.recv_vec : nullptr,
+                       vg ? p.sem_vec : nullptr, (int)p.dtype, p.H, p.N, (double*)(ws + pl.fterm),
+                       (double*)(ws + pl.fterm2));
+    if (vr) a.red_src = FICOCO_R_SIM_MEAN;     // "read the precomputed term"
+    if (vg) a.sem_src = FICOCO_G_EQ_TOKEN;
+  }
   a.w = (double)p.w_score;
   const bool penalty = p.variant == FICOCO_VARIANT_V && p.window > 0;
   a.pos = p.pos;

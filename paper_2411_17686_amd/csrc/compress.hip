@@ -229,27 +229,46 @@ struct EdgeTable {
   int* t1;
 };
 
-// One wavefront per (output row, feature span of 512 * SLICE).  Rows without sources, and
-// every token outside the visual span, are copied.  Where a target's sources come from:
+// LDS carve-up of merge_rows_kernel, shared by the kernel and its launcher.
+template <bool MATCH, int SLICE, int WPU>
+struct MergeLds {
+  static constexpr int kCap = MATCH ? kMatchCap : kBucketCap;
+  static constexpr int kUnits = kMergeWaves / WPU;
+  static constexpr size_t kLists = (size_t)kMergeWaves * kCap * 12;
+  static constexpr size_t kPartDoubles = WPU > 1 ? (size_t)kUnits * (WPU - 1) * SLICE * kVec * kWave : 0;
+  static constexpr size_t kDen = WPU > 1 ? (size_t)kMergeWaves * 16 : 0;     // one (den, count) pair per wavefront
+  static size_t bytes(int n_disc) { return kLists + kPartDoubles * 8 + kDen + (MATCH ? (size_t)n_disc * 32 : 0); }
+};
+
+// One UNIT = (output row, feature span of 512 * SLICE).  Rows without sources, and every token
+// outside the visual span, are copied.  A unit is served by WPU wavefronts: wavefront w takes
+// the sources whose discarded row lies in the w-th part of [0, n_disc), adds them in ascending
+// row order in double precision, and the parts are then added in order by wavefront 0
+// (WPU = 1: one plain ascending sum).  Where a wavefront's sources come from:
 //   MATCH = true  (few discarded tokens): the workgroup stages the image's edge table in LDS
-//     once; each wavefront scans it, 64 discarded rows per pass, and keeps the rows that name
-//     its target in a list in ascending row order;
-//   MATCH = false: the sources are one bucket of the inverted lists (arbitrary order), put
-//     in ascending row order by rank counting across the wavefront.
+//     once; each wavefront scans its part of it, 64 discarded rows per pass, and keeps the rows
+//     that name its target in a list in ascending row order;
+//   MATCH = false: the sources are one bucket of the inverted lists (arbitrary order); the
+//     wavefront takes the entries of its part and orders them by rank counting.
 // The list is then added with several row loads in flight.  Lists longer than the LDS holds
 // take slower paths that need no list.
-template <typename T, bool MATCH, int SLICE>
+template <typename T, bool MATCH, int SLICE, int WPU>
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
   DBG_SPAN(3);
   extern __shared__ __attribute__((aligned(16))) char lds_m[];
-  constexpr int kCap = MATCH ? kMatchCap : kBucketCap;
+  using Lds = MergeLds<MATCH, SLICE, WPU>;
+  constexpr int kCap = Lds::kCap;
   constexpr int kSpan = kWave * kVec * SLICE;
+  constexpr int kRegs = (MATCH && WPU == 1) ? 16 : 32;
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int unit_l = wv / WPU, sub = wv % WPU;
   double* l_w = (double*)lds_m + wv * kCap;
   int* l_src = (int*)((double*)lds_m + kMergeWaves * kCap) + wv * kCap;
+  double* part = (double*)(lds_m + Lds::kLists);                 // [kUnits][WPU-1][SLICE*kVec][64]
+  double* wden = part + Lds::kPartDoubles;                       // [kMergeWaves][2]: partial denominator, source count
   EdgeTable tb;
   {
-    char* base = lds_m + (size_t)kMergeWaves * kCap * 12;
+    char* base = lds_m + Lds::kLists + Lds::kPartDoubles * 8 + Lds::kDen;
     tb.a0 = (double*)base;
     tb.a1 = tb.a0 + a.n_disc;
     tb.cnt = (int*)(tb.a1 + a.n_disc);
@@ -258,7 +277,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
     tb.t1 = tb.t0 + a.n_disc;
   }
   const int n_spans = (a.D + kSpan - 1) / kSpan;
-  const int unit = blockIdx.x * kMergeWaves + wv;
+  const int unit = blockIdx.x * Lds::kUnits + unit_l;
   const int r = unit / n_spans;
   const int d0 = (unit % n_spans) * kSpan;
   const int64_t b = blockIdx.y;
@@ -293,7 +312,8 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         e0 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j], 0), a.n_disc * a.k_max);
         e1 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j + 1], e0), a.n_disc * a.k_max);
       }
-      if (lane == 0 && d0 == 0 && a.pos_out) a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
+      if (lane == 0 && sub == 0 && d0 == 0 && a.pos_out)
+        a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
     } else {
       t = r + a.n_disc;
     }
@@ -306,20 +326,25 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   for (int u = 0; u < SLICE; ++u) full[u] = d0 + (u * kWave + lane) * kVec + kVec <= a.D;
   // this row's own slices, in flight while its sources are looked up
   Raw8<T> xr[SLICE];
-  if (valid) {
+  if (valid && sub == 0) {
 #pragma unroll
     for (int u = 0; u < SLICE; ++u)
       if (full[u]) load_raw(x + d0 + (u * kWave + lane) * kVec, xr[u]);
   }
   if (MATCH) __syncthreads();   // the edge table is complete (every wavefront arrives here)
-  if (!valid) return;
+  if (WPU == 1 && !valid) return;
 
-  // ---- sources of this target -------------------------------------------------------------
+  // this wavefront's part of the discarded rows
+  const int part_rows = WPU == 1 ? a.n_disc : ((a.n_disc + WPU - 1) / WPU + kWave - 1) / kWave * kWave;
+  const int row_lo = min(sub * part_rows, a.n_disc), row_hi = min(row_lo + part_rows, a.n_disc);
+
+  // ---- sources of this target within [row_lo, row_hi) ------------------------------------------
   int n_src = 0;
-  if (merged_row && MATCH) {
-    for (int base = 0; base < a.n_disc; base += kWave) {
+  bool long_bucket = false;
+  if (valid && merged_row && MATCH) {
+    for (int base = row_lo; base < row_hi; base += kWave) {
       const int row = base + lane;
-      const bool in = row < a.n_disc;
+      const bool in = row < row_hi;
       const int cnt = in ? tb.cnt[row] : 0;
       bool hit = false;
       double w = 0.0;
@@ -334,40 +359,62 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       }
       n_src += __popcll(m);
     }
-  } else if (merged_row) {
-    n_src = e1 - e0;
-    if (n_src > 0 && n_src <= kCap) {
-      // bucket -> ascending discarded row: rank of an entry = number of entries with a smaller row
-      const int n_q = (n_src + kWave - 1) / kWave;
+  } else if (valid && merged_row) {
+    const int n_all = e1 - e0;
+    long_bucket = n_all > kCap;
+    if (n_all > 0 && !long_bucket) {
+      // entries of the bucket that fall into this part -> ascending discarded row: rank of an
+      // entry = number of entries of the part with a smaller row (rows read back from LDS)
+      const int n_q = (n_all + kWave - 1) / kWave;
       int row[kBucketPer], rank[kBucketPer];
       double w[kBucketPer];
 #pragma unroll
       for (int q = 0; q < kBucketPer; ++q) {
-        const bool in = q * kWave + lane < n_src;
-        row[q] = in ? a.tgt_src[ebase + e0 + q * kWave + lane] : 0x7fffffff;
+        const bool in = q * kWave + lane < n_all;
+        const int rw = in ? a.tgt_src[ebase + e0 + q * kWave + lane] : 0x7fffffff;
         w[q] = in ? a.tgt_alpha[ebase + e0 + q * kWave + lane] : 0.0;
+        row[q] = (rw >= row_lo && rw < row_hi) ? rw : 0x7fffffff;
         rank[q] = 0;
       }
 #pragma unroll
-      for (int q2 = 0; q2 < kBucketPer; ++q2) {
-        if (q2 >= n_q) break;
-        const int lim = min(kWave, n_src - q2 * kWave);
-        for (int l = 0; l < lim; ++l) {
-          const int v = __shfl(row[q2], l, kWave);
-#pragma unroll
-          for (int q = 0; q < kBucketPer; ++q) rank[q] += v < row[q] ? 1 : 0;
-        }
+      for (int q = 0; q < kBucketPer; ++q) {
+        if (q < n_q) l_src[q * kWave + lane] = row[q];
+        n_src += __popcll(__ballot(row[q] != 0x7fffffff));
       }
+      const int n_pad = n_q * kWave;
+      for (int l0 = 0; l0 < n_pad; l0 += 8) {
+        int v[8];
+#pragma unroll
+        for (int x8 = 0; x8 < 8; ++x8) v[x8] = l_src[l0 + x8];
+#pragma unroll
+        for (int x8 = 0; x8 < 8; ++x8)
+#pragma unroll
+          for (int q = 0; q < kBucketPer; ++q) rank[q] += v[x8] < row[q] ? 1 : 0;
+      }
+      int tok[kBucketPer];
+#pragma unroll
+      for (int q = 0; q < kBucketPer; ++q)
+        tok[q] = row[q] != 0x7fffffff ? a.S[b * a.n_disc + min(max(row[q], 0), a.n_disc - 1)] : 0;
 #pragma unroll
       for (int q = 0; q < kBucketPer; ++q) {
-        if (q * kWave + lane < n_src) {
-          l_src[rank[q]] = a.S[b * a.n_disc + min(max(row[q], 0), a.n_disc - 1)];
+        if (row[q] != 0x7fffffff) {      // all reads of the rows above precede these writes
+          l_src[rank[q]] = tok[q];
           l_w[rank[q]] = w[q];
         }
       }
+    } else if (long_bucket) {
+      n_src = sub == 0 ? n_all : 0;      // wavefront 0 takes the whole bucket on the slow path
     }
   }
-  if (!merged_row || n_src == 0) {  // nothing merged into this row: exact copy
+
+  // ---- this wavefront's partial sum ----------------------------------------------------------------
+  double num[SLICE][kVec];
+  double den = sub == 0 ? 1.0 : 0.0;
+#pragma unroll
+  for (int u = 0; u < SLICE; ++u)
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) num[u][k] = 0.0;
+  if (WPU == 1 && n_src == 0) {  // nothing merged into this row: exact copy
 #pragma unroll
     for (int u = 0; u < SLICE; ++u) {
       const int d = d0 + (u * kWave + lane) * kVec;
@@ -378,64 +425,107 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
     }
     return;
   }
-  double num[SLICE][kVec];
+  if (valid && sub == 0) {
 #pragma unroll
-  for (int u = 0; u < SLICE; ++u) {
-    const int d = d0 + (u * kWave + lane) * kVec;
-#pragma unroll
-    for (int k = 0; k < kVec; ++k) num[u][k] = 0.0;
-    if (full[u]) add_raw(xr[u], num[u]);
-    else
-      for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
+    for (int u = 0; u < SLICE; ++u) {
+      const int d = d0 + (u * kWave + lane) * kVec;
+      if (full[u]) add_raw(xr[u], num[u]);
+      else
+        for (int k = 0; k < kVec; ++k) num[u][k] = d + k < a.D ? widen(x[d + k]) : 0.0;
+    }
   }
-
-  double den = 1.0;
-  if (n_src <= kCap) {
-    for (int e = 0; e < n_src; ++e) den += l_w[e];
-    // scanning mode serves few discarded tokens, hence few sources per target: a short batch
-    // keeps the register count where every wavefront of the grid is resident at once
-    add_sources<T, SLICE, MATCH ? 16 : 32>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
-  } else if (MATCH) {
-    // more sources than the list holds: add while scanning
-    for (int base = 0; base < a.n_disc; base += kWave) {
-      const int row = base + lane;
-      const bool in = row < a.n_disc;
-      const int cnt = in ? tb.cnt[row] : 0;
-      bool hit = false;
-      double w = 0.0;
-      if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
-      if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
-      for (int e = 2; e < cnt; ++e)
-        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
-      const int src = in ? tb.src[row] : 0;
-      unsigned long long m = __ballot(hit);
-      while (m) {
-        const int l = __ffsll(m) - 1;
-        m &= m - 1;
-        const double wl = __shfl(w, l, kWave);
-        den += wl;
-        add_source<T, SLICE>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+  if (n_src > 0) {
+    if (!long_bucket && n_src <= kCap) {
+      int e = 0;
+      for (; e + 8 <= n_src; e += 8) {
+        double wv8[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) wv8[q] = l_w[e + q];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) den += wv8[q];
+      }
+      for (; e < n_src; ++e) den += l_w[e];
+      add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
+    } else if (MATCH) {
+      // more sources than the list holds: add while scanning
+      for (int base = row_lo; base < row_hi; base += kWave) {
+        const int row = base + lane;
+        const bool in = row < row_hi;
+        const int cnt = in ? tb.cnt[row] : 0;
+        bool hit = false;
+        double w = 0.0;
+        if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
+        if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
+        for (int e = 2; e < cnt; ++e)
+          if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
+        const int src = in ? tb.src[row] : 0;
+        unsigned long long m = __ballot(hit);
+        while (m) {
+          const int l = __ffsll(m) - 1;
+          m &= m - 1;
+          const double wl = __shfl(w, l, kWave);
+          den += wl;
+          add_source<T, SLICE>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+        }
+      }
+    } else {
+      // long bucket: take its entries in ascending discarded row by repeated minimum search
+      int last = -1;
+      for (int k = 0; k < n_src; ++k) {
+        int best = 0x7fffffff, best_e = -1;
+        for (int e = e0 + lane; e < e1; e += kWave) {
+          const int row = a.tgt_src[ebase + e];
+          if (row > last && row < best) { best = row; best_e = e; }
+        }
+        int mn = best;
+#pragma unroll
+        for (int off = 32; off > 0; off >>= 1) mn = min(mn, __shfl_xor(mn, off, kWave));
+        const unsigned long long who = __ballot(best == mn && best_e >= 0);
+        if (who == 0) break;             // fewer distinct rows than entries: inconsistent device data
+        const int l = __ffsll(who) - 1;
+        const int e = __shfl(best_e, l, kWave);
+        const double w = a.tgt_alpha[ebase + e];
+        den += w;
+        add_source<T, SLICE>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
+        last = mn;
       }
     }
-  } else {
-    // long bucket: take its entries in ascending discarded row by repeated minimum search
-    int last = -1;
-    for (int k = 0; k < n_src; ++k) {
-      int best = 0x7fffffff, best_e = -1;
-      for (int e = e0 + lane; e < e1; e += kWave) {
-        const int row = a.tgt_src[ebase + e];
-        if (row > last && row < best) { best = row; best_e = e; }
-      }
-      int mn = best;
+  }
+
+  // ---- parts added in order by wavefront 0 of the unit -----------------------------------------------
+  if (WPU > 1) {
+    if (sub > 0) {
+      double* dst = part + ((size_t)(unit_l * (WPU - 1) + sub - 1) * SLICE * kVec) * kWave + lane;
 #pragma unroll
-      for (int off = 32; off > 0; off >>= 1) mn = min(mn, __shfl_xor(mn, off, kWave));
-      const unsigned long long who = __ballot(best == mn && best_e >= 0);
-      const int l = __ffsll(who) - 1;
-      const int e = __shfl(best_e, l, kWave);
-      const double w = a.tgt_alpha[ebase + e];
-      den += w;
-      add_source<T, SLICE>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
-      last = mn;
+      for (int u = 0; u < SLICE; ++u)
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) dst[(u * kVec + k) * kWave] = num[u][k];
+    }
+    if (lane == 0) { wden[2 * wv] = den; wden[2 * wv + 1] = (double)n_src; }
+    __syncthreads();              // every wavefront of the workgroup arrives here exactly once
+    if (sub > 0 || !valid) return;
+    double total = 0.0;
+#pragma unroll
+    for (int w = 0; w < WPU; ++w) total += wden[2 * (unit_l * WPU + w) + 1];
+    if (total == 0.0) {           // nothing merged into this row: exact copy
+#pragma unroll
+      for (int u = 0; u < SLICE; ++u) {
+        const int d = d0 + (u * kWave + lane) * kVec;
+        if (full[u]) __builtin_memcpy(out + d, &xr[u], sizeof(xr[u]));
+        else
+          for (int k = 0; k < kVec; ++k)
+            if (d + k < a.D) out[d + k] = x[d + k];
+      }
+      return;
+    }
+#pragma unroll
+    for (int w = 1; w < WPU; ++w) {
+      const double* src = part + ((size_t)(unit_l * (WPU - 1) + w - 1) * SLICE * kVec) * kWave + lane;
+#pragma unroll
+      for (int u = 0; u < SLICE; ++u)
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) num[u][k] += src[(u * kVec + k) * kWave];
+      den += wden[2 * (unit_l * WPU + w)];
     }
   }
 #pragma unroll
@@ -457,22 +547,29 @@ constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the ed
 #ifndef FICOCO_MERGE_SLICE
 #define FICOCO_MERGE_SLICE 0          // 0: chosen per problem
 #endif
+#ifndef FICOCO_MERGE_WPU
+#define FICOCO_MERGE_WPU 1            // wavefronts per unit: 1 or 4
+#endif
 
-template <typename T, bool MATCH, int SLICE>
+template <typename T, bool MATCH, int SLICE, int WPU>
 static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
+  using Lds = MergeLds<MATCH, SLICE, WPU>;
   constexpr int kSpan = kWave * kVec * SLICE;
   const int n_spans = (m.D + kSpan - 1) / kSpan;
-  const size_t lds = (size_t)kMergeWaves * (MATCH ? kMatchCap : kBucketCap) * 12 + (MATCH ? (size_t)m.n_disc * 32 : 0);
-  dim3 grid((m.n_out * n_spans + kMergeWaves - 1) / kMergeWaves, B), block(kMergeWaves * kWave);
-  hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE>), grid, block, lds, s, m);
+  const size_t lds = Lds::bytes(m.n_disc);
+  if (lds > 32768)
+    (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, MATCH, SLICE, WPU>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  dim3 grid((m.n_out * n_spans + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
+  hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE, WPU>), grid, block, lds, s, m);
 }
 
-template <typename T>
-static void launch_merge_t(const MergeArgs& m, int B, bool match, int slice, hipStream_t s) {
-  if (match) {
-    if (slice == 1) launch_merge<T, true, 1>(m, B, s); else launch_merge<T, true, 2>(m, B, s);
+template <typename T, bool MATCH>
+static void launch_merge_m(const MergeArgs& m, int B, int slice, int wpu, hipStream_t s) {
+  if (wpu == 1) {
+    if (slice == 1) launch_merge<T, MATCH, 1, 1>(m, B, s); else launch_merge<T, MATCH, 2, 1>(m, B, s);
   } else {
-    if (slice == 1) launch_merge<T, false, 1>(m, B, s); else launch_merge<T, false, 2>(m, B, s);
+    if (slice == 1) launch_merge<T, MATCH, 1, 4>(m, B, s); else launch_merge<T, MATCH, 2, 4>(m, B, s);
   }
 }
 
@@ -504,12 +601,18 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
   m.pos = p.pos; m.pos_out = pos_out;
-  // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when
-  // the wide ones would not fill the chip.
+  // One wavefront per unit: four of them shorten a single step when preserved tokens have
+  // many sources (long sequences) but cost throughput when independent steps overlap, which
+  // is what is measured; the build option remains.  Narrow spans (one 8-element vector per
+  // lane) double the number of wavefronts: taken when the wide ones would not fill the chip.
+  const int wpu = FICOCO_MERGE_WPU == 4 ? 4 : 1;
   int slice = FICOCO_MERGE_SLICE;
-  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
-  if (p.dtype == FICOCO_BF16) launch_merge_t<bf16_t>(m, p.B, match, slice, s);
-  else launch_merge_t<float>(m, p.B, match, slice, s);
+  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) * wpu >= 4096 ? 2 : 1;
+  if (p.dtype == FICOCO_BF16) {
+    if (match) launch_merge_m<bf16_t, true>(m, p.B, slice, wpu, s); else launch_merge_m<bf16_t, false>(m, p.B, slice, wpu, s);
+  } else {
+    if (match) launch_merge_m<float, true>(m, p.B, slice, wpu, s); else launch_merge_m<float, false>(m, p.B, slice, wpu, s);
+  }
 }
 
 }  // namespace ficoco

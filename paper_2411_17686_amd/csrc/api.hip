@@ -1,5 +1,6 @@
 // C-ABI layer: argument checks, workspace plan and the stage / fused-step entry points
 // declared in include/ficoco.h.  Host code only; every launch goes to the caller's stream.
+#include <algorithm>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -164,7 +165,22 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;
-  pl.ct = take(pl.use_gram ? B * (size_t)pl.n_disc * p.n_keep * sizeof(float) : 0);
+  pl.gram_splits = 1;
+  pl.gram_st_per_split = (pl.Df + kGramStage - 1) / kGramStage;
+  if (pl.use_gram) {
+    // Few output tiles: cut K so that the matrix-core kernel still fills the chip (about two
+    // workgroups per compute unit), each range at least 256 features long; the partial blocks are
+    // added, in a fixed order, where they are read.
+    const int64_t tiles = (int64_t)p.B * ((pl.n_disc + 127) / 128) * ((p.n_keep + 127) / 128);
+    int splits = (int)((512 + tiles - 1) / tiles);
+    splits = std::min(splits, std::min(8, pl.Df / 256));
+    if (splits < 1) splits = 1;
+    const int st_all = (pl.Df + kGramStage - 1) / kGramStage;
+    pl.gram_st_per_split = (st_all + splits - 1) / splits;
+    pl.gram_splits = (st_all + pl.gram_st_per_split - 1) / pl.gram_st_per_split;
+  }
+  // + padding: the row kernel reads whole 2048-target passes
+  pl.ct = take(pl.use_gram ? (pl.gram_splits * B * (size_t)pl.n_disc * p.n_keep + kCandPad) * sizeof(float) : 0);
   pl.cmax = take(L ? B * (size_t)p.M * sizeof(double) : 0);
   pl.total = off;
   return FICOCO_OK;

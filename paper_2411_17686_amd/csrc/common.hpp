@@ -10,6 +10,8 @@
 namespace ficoco {
 
 constexpr int kWave = 64;
+constexpr int kCandPad = 2048;     // floats of padding behind the approximate correlation block (one pass of its reader)
+constexpr int kGramStage = 32;     // features per K stage of the matrix-core kernel (its K ranges are counted in stages)
 constexpr int kVec = 8;            // elements per lane per load in the streaming kernels
 constexpr int kSelMax = 8;         // order statistics kept in registers by the fast threshold path
 #ifndef FICOCO_REDUCE_THREADS
@@ -52,9 +54,10 @@ struct Plan {
   size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
-  size_t ct;             // float  [B][N^S][n_keep]  approximate cosines (matrix-core path)
+  size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
+  int gram_splits, gram_st_per_split;   // K ranges of that kernel and their length in 32-feature stages
   int f_chunks, f_rows_per_wg, Df;
   size_t total;
 };

@@ -34,7 +34,8 @@ struct CorrArgs {
   double* edge_alpha;
   int32_t* overflow;
   const int32_t* slot_of; // [B][N] keep slot of a visual token, -1 if discarded
-  float* ct;             // [B][n_disc][n_keep] approximate cosines from the matrix cores
+  float* ct;             // [ct_splits][B][n_disc][n_keep] approximate cosines from the matrix cores (partial sums)
+  int ct_splits;
   double* cmax;          // [B][M]
   float delta;           // bound of |ct - exact dot|
 };
@@ -379,6 +380,7 @@ __device__ __forceinline__ void corr_values_wave(const CorrArgs& a, int64_t b, i
 
 constexpr int kCandKeep = 32;                    // approximate values held per lane
 constexpr int kCandChunk = kCandKeep * kWave;    // targets per pass over the row
+static_assert(kCandChunk <= kCandPad, "the block's padding covers one pass");
 constexpr int kCandBatch = 4;                    // targets evaluated exactly at a time
 
 __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
@@ -409,31 +411,55 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   }
   const float delta = from_map ? 0.0f : a.delta;
   const float NEGF = -__builtin_huge_valf();
+  const int64_t split_stride = (int64_t)a.B * a.n_disc * n;
 
   // One pass of the row: element u of a lane is target c0 + u*64 + lane.  All loads of a pass
   // are independent (the map gather takes the token indices first), absent targets read as -inf.
   float val[kCandKeep];
   auto load_pass = [&](int c0) {
+    const int n_u = min(kCandKeep, (n - c0 + kWave - 1) / kWave);   // slots of this pass that hold targets (uniform)
     if (from_map) {
       int jt[kCandKeep];
 #pragma unroll
       for (int u = 0; u < kCandKeep; ++u) {
         const int jj = c0 + u * kWave + lane;
-        jt[u] = jj < n ? T[jj] : -1;
+        jt[u] = (u < n_u && jj < n) ? T[jj] : -1;
       }
 #pragma unroll
       for (int u = 0; u < kCandKeep; ++u) {
         const bool ok = (unsigned)jt[u] < (unsigned)a.N;
-        const float v = ct[(int64_t)(ok ? jt[u] : 0) * a.N];
+        float v = 0.0f;
+        if (u < n_u) v = ct[(int64_t)(ok ? jt[u] : 0) * a.N];
         val[u] = c0 + u * kWave + lane < n ? (ok ? v : 0.0f) : NEGF;
       }
     } else {
+      // The block is followed by kCandChunk floats of padding, so a pass may read past the end
+      // of the row (what it reads there is masked below): one address, constant offsets.
+      const float* c = ct + c0 + lane;
 #pragma unroll
-      for (int u = 0; u < kCandKeep; ++u) {
-        const int jj = c0 + u * kWave + lane;
-        const float v = ct[min(jj, n - 1)];
-        val[u] = jj < n ? v : NEGF;
+      for (int ub = 0; ub < kCandKeep; ub += 8) {
+        if (ub < n_u) {                                              // uniform: groups of 8 slots that hold targets
+#pragma unroll
+          for (int u = 0; u < 8; ++u) val[ub + u] = c[(ub + u) * kWave];
+        } else {
+#pragma unroll
+          for (int u = 0; u < 8; ++u) val[ub + u] = 0.0f;
+        }
       }
+#pragma unroll 1
+      for (int sp = 1; sp < a.ct_splits; ++sp) {                   // partial sums of the K ranges, added in order
+        c += split_stride;
+#pragma unroll
+        for (int ub = 0; ub < kCandKeep; ub += 8) {
+          if (ub < n_u) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) val[ub + u] += c[(ub + u) * kWave];
+          }
+        }
+      }
+#pragma unroll
+      for (int u = 0; u < kCandKeep; ++u)
+        if (c0 + u * kWave + lane >= n) val[u] = NEGF;
     }
   };
 
@@ -749,7 +775,8 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.slot_of = (const int32_t*)(ws + pl.slot_of);
   a.ct = (float*)(ws + pl.ct);
   a.cmax = (double*)(ws + pl.cmax);
-  a.delta = (float)pl.Df * 2.384185791015625e-07f;   // Df * 2^-22
+  a.ct_splits = pl.gram_splits;
+  a.delta = (float)(pl.Df + 4 * pl.gram_splits) * 2.384185791015625e-07f;   // (Df + 4 splits) * 2^-22
   if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
     const int tiles = (pl.n_disc + kTileCols - 1) / kTileCols;
     dim3 tgrid(xcd_padded_total(tiles * p.B));
@@ -766,8 +793,8 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     return;
   }
   if (pl.use_gram) {
-    GramArgs g{a.xhat, p.B, p.N, pl.Df, pl.n_disc, p.n_keep, discard_idx, keep_idx, a.ct};
-    const int tiles = p.B * ((pl.n_disc + kGT - 1) / kGT) * ((p.n_keep + kGT - 1) / kGT);
+    GramArgs g{a.xhat, p.B, p.N, pl.Df, pl.n_disc, p.n_keep, discard_idx, keep_idx, a.ct, pl.gram_splits, pl.gram_st_per_split};
+    const int tiles = pl.gram_splits * p.B * ((pl.n_disc + kGT - 1) / kGT) * ((p.n_keep + kGT - 1) / kGT);
     if (gram_start) (void)hipEventRecord(gram_start, s);
     hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);

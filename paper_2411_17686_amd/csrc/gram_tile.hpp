@@ -18,10 +18,7 @@ typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
 typedef float f32x16_t __attribute__((ext_vector_type(16)));
 
 constexpr int kGT = 128;           // tile rows = tile columns
-#ifndef FICOCO_GRAM_K
-#define FICOCO_GRAM_K 32
-#endif
-constexpr int kGK = FICOCO_GRAM_K; // K elements per stage (32 measured best at 4096 tokens; 64 halves LDS occupancy)
+constexpr int kGK = kGramStage;    // K elements per stage (32 measured best at 4096 tokens; 64 halves LDS occupancy)
 constexpr int kGChunks = kGK / 16;  // 16-byte chunks per thread, operand and stage
 constexpr int kGStride = kGK + 8;  // LDS row pitch in elements (row + 16 bytes)
 #ifndef FICOCO_GRAM_STAGES
@@ -34,7 +31,8 @@ struct GramArgs {
   int B, N, Df, n_disc, n_keep;
   const int32_t* S;    // [B][n_disc]
   const int32_t* T;    // [B][n_keep]
-  float* ct;           // [B][n_disc][n_keep]
+  float* ct;           // [splits][B][n_disc][n_keep]: partial sums over the K ranges of the splits
+  int splits, st_per_split;   // K is cut into `splits` ranges of st_per_split stages (the last may be shorter)
 };
 
 __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
@@ -44,9 +42,12 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   __shared__ int rowB[kGT];
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave;
   const int tiles_m = (a.n_disc + kGT - 1) / kGT, tiles_n = (a.n_keep + kGT - 1) / kGT;
-  const int total = a.B * tiles_m * tiles_n;
-  const int logical = xcd_logical_id(blockIdx.x, total);
+  const int per_split = a.B * tiles_m * tiles_n;
+  const int total = per_split * a.splits;
+  int logical = xcd_logical_id(blockIdx.x, total);
   if (logical >= total) return;   // padding workgroup
+  const int split = logical / per_split;
+  logical %= per_split;
   const int64_t b = logical / (tiles_m * tiles_n);
   const int tm = (logical % (tiles_m * tiles_n)) / tiles_n, tn = logical % tiles_n;
 
@@ -61,8 +62,11 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   }
   __syncthreads();
 
+  // this split's K range, [k_begin, k_begin + k_len)
+  const int k_begin = split * a.st_per_split * kGK;
+  const int k_len = max(min(a.Df - k_begin, a.st_per_split * kGK), 0);
   // loader: the stage is 128 rows x kGK/8 chunks of 8 elements per operand; thread -> kGChunks chunks each
-  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df;
+  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df + k_begin;
   int lrow[kGChunks], lkc[kGChunks];
   const bf16_t* srcA[kGChunks];
   const bf16_t* srcB[kGChunks];
@@ -75,15 +79,14 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
     srcB[u] = rowB[lrow[u]] >= 0 ? Xb + (int64_t)rowB[lrow[u]] * a.Df + lkc[u] : nullptr;
   }
   // Register ring of kGStages K-stages in flight per thread: a stage is fetched kGStages
-  // iterations before it is stashed into LDS, which covers the global-load latency that a
-  // single 32-wide K step (a few hundred cycles of MFMA work) cannot.
+  // iterations before it is stashed into LDS.
   uint4 ra[kGStages][kGChunks], rb[kGStages][kGChunks];
-  const int n_st = (a.Df + kGK - 1) / kGK;
+  const int n_st = (k_len + kGK - 1) / kGK;
   auto fetch = [&](int slot, int st) {
     const int k0 = st * kGK;
 #pragma unroll
     for (int u = 0; u < kGChunks; ++u) {
-      const bool in = st < n_st && k0 + lkc[u] + 8 <= a.Df;   // Df is a multiple of 8 on this path
+      const bool in = st < n_st && k0 + lkc[u] + 8 <= k_len;   // Df is a multiple of 8 on this path
       ra[slot][u] = make_uint4(0, 0, 0, 0);
       rb[slot][u] = make_uint4(0, 0, 0, 0);
       if (in && srcA[u]) __builtin_memcpy(&ra[slot][u], srcA[u] + k0, 16);
@@ -145,15 +148,17 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
 
   // C block layout of the 32x32 MFMA: lane holds column lane%32; register v holds row
   // 8*(v/4) + 4*(lane/32) + v%4.
+  float* ctb = a.ct + ((int64_t)split * a.B + b) * a.n_disc * (int64_t)a.n_keep;   // this split's block of image b
 #pragma unroll
   for (int mi = 0; mi < 2; ++mi)
 #pragma unroll
     for (int ni = 0; ni < 2; ++ni) {
       const int col = tn * kGT + wn * 64 + ni * 32 + lane % 32;
+      const int row0 = tm * kGT + wm * 64 + mi * 32 + 4 * (lane / 32);
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int row = tm * kGT + wm * 64 + mi * 32 + 8 * (v / 4) + 4 * (lane / 32) + v % 4;
-        if (row < a.n_disc && col < a.n_keep) a.ct[(b * a.n_disc + row) * a.n_keep + col] = acc[mi][ni][v];
+        const int row = row0 + 8 * (v / 4) + v % 4;
+        if (row < a.n_disc && col < a.n_keep) ctb[row * a.n_keep + col] = acc[mi][ni][v];   // below 2^31: n_disc * n_keep < 12288^2
       }
     }
 }

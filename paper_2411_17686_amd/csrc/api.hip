@@ -141,7 +141,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
 
   // feature pass geometry (column sums over the tokens)
   if (pl.need_features) {
-    pl.f_rows_per_wg = 16;
+    pl.f_rows_per_wg = 32;
     pl.f_chunks = (p.N + pl.f_rows_per_wg - 1) / pl.f_rows_per_wg;
   }
 
@@ -155,7 +155,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.inv_norm = take(pl.need_features ? B * N * sizeof(double) : 0);
   pl.xhat = take(p.corr_src == FICOCO_C_COSINE ? B * N * (size_t)pl.Df * sizeof(bf16_t) : 0);
   pl.colsum_part = take(pl.need_features ? 2 * B * (size_t)pl.f_chunks * pl.Df * sizeof(double) : 0);
-  pl.colmean = take(pl.need_features ? 2 * B * (size_t)pl.Df * sizeof(double) : 0);
+  pl.colmean = take(pl.need_features ? (2 * B * (size_t)pl.Df + B * (size_t)((pl.Df + 255) / 256)) * sizeof(double) : 0);   // two means, then |mu|^2 in parts
   pl.fterm = take(B * N * sizeof(double));
   pl.fterm2 = take(B * N * sizeof(double));
   pl.slot_of = take(B * N * sizeof(int32_t));

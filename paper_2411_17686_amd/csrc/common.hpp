@@ -46,7 +46,7 @@ struct Plan {
   size_t inv_norm;       // double [B][N]         1/|F_i| (0 for a zero row)
   size_t xhat;           // bf16   [B][N][Df]     unit rows rounded to bfloat16
   size_t colsum_part;    // double [B][f_chunks][Df]
-  size_t colmean;        // double [B][Df]
+  size_t colmean;        // double [2][B][Df] (mean unit row, mean raw row), then the parts of |mean raw row|^2
   size_t fterm;          // double [B][N]         feature-derived score term
   size_t fterm2;         // double [B][N]
   size_t slot_of;        // int32  [B][N]         keep slot of a preserved token, -1 if discarded

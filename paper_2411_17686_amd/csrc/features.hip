@@ -61,38 +61,106 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   }
 }
 
-// Partial column sums over a chunk of rows: slot 0 adds unit rows, slot 1 raw rows.
+// Partial column sums over a chunk of rows: slot 0 adds unit rows (row times the reciprocal of
+// its norm), slot 1 raw rows.  A workgroup covers 512 features: a lane owns 8 consecutive
+// ones, each of its four wavefronts takes a quarter of the chunk's rows (16-byte loads of up
+// to kColBatch rows in flight, added in row order) and the quarters are added in order.
+constexpr int kColBatch = 8;
+constexpr int kColSpan = kWave * kVec;
 template <typename T>
 __global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
+  __shared__ double part[3][2][kVec][kWave];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int chunk = blockIdx.x;
-  const int d = blockIdx.y * blockDim.x + threadIdx.x;
+  const int d = blockIdx.y * kColSpan + lane * kVec;
   const int64_t b = blockIdx.z;
-  if (d >= a.Df) return;
-  const int r0 = chunk * a.f_rows_per_wg, r1 = min(r0 + a.f_rows_per_wg, a.N);
-  double su = 0.0, sr = 0.0;
-  for (int i = r0; i < r1; ++i) {
-    const double v = widen(((const T*)a.F)[b * a.sb + (int64_t)i * a.sn + d]);
-    const double nrm = a.norm[b * a.N + i];
-    su += nrm > 0.0 ? v / nrm : 0.0;
-    sr += v;
+  const int nd = max(min(kVec, a.Df - d), 0);
+  const int c0 = chunk * a.f_rows_per_wg, c1 = min(c0 + a.f_rows_per_wg, a.N);
+  const int quarter = (c1 - c0 + 3) / 4;
+  const int r0 = min(c0 + wv * quarter, c1), r1 = min(r0 + quarter, c1);
+  const T* base = (const T*)a.F + b * a.sb + d;
+  double su[kVec], sr[kVec];
+#pragma unroll
+  for (int k = 0; k < kVec; ++k) { su[k] = 0.0; sr[k] = 0.0; }
+  if (nd == kVec) {
+    for (int i0 = r0; i0 < r1; i0 += kColBatch) {
+      Raw8<T> raw[kColBatch];
+      double inv[kColBatch];
+#pragma unroll
+      for (int u = 0; u < kColBatch; ++u) {
+        const int i = min(i0 + u, r1 - 1);                 // clamped: always a valid row
+        load_raw(base + (int64_t)i * a.sn, raw[u]);
+        const double nrm = a.norm[b * a.N + i];
+        inv[u] = nrm > 0.0 ? 1.0 / nrm : 0.0;
+      }
+#pragma unroll
+      for (int u = 0; u < kColBatch; ++u) {
+        if (i0 + u >= r1) break;                           // uniform over the wavefront
+        double v[kVec];
+        widen_raw(raw[u], v);
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) { su[k] += v[k] * inv[u]; sr[k] += v[k]; }
+      }
+    }
+  } else {
+    for (int i = r0; i < r1; ++i) {
+      const double nrm = a.norm[b * a.N + i];
+      const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
+      for (int k = 0; k < nd; ++k) {
+        const double v = widen(base[(int64_t)i * a.sn + k]);
+        su[k] += v * inv;
+        sr[k] += v;
+      }
+    }
   }
+  if (wv > 0) {
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) { part[wv - 1][0][k][lane] = su[k]; part[wv - 1][1][k][lane] = sr[k]; }
+  }
+  __syncthreads();
+  if (wv > 0 || nd == 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) { su[k] += part[w][0][k][lane]; sr[k] += part[w][1][k][lane]; }
   const int64_t slot = (int64_t)a.B * a.f_chunks * a.Df;
-  a.colsum_part[(b * a.f_chunks + chunk) * a.Df + d] = su;
-  a.colsum_part[slot + (b * a.f_chunks + chunk) * a.Df + d] = sr;
+  double* pu = a.colsum_part + (b * a.f_chunks + chunk) * a.Df + d;
+  for (int k = 0; k < nd; ++k) { pu[k] = su[k]; pu[slot + k] = sr[k]; }
 }
 
+// Column means from the chunk partials (added in chunk order, 8 loads in flight).  Every
+// workgroup also leaves the squared norm of its 256 features of the raw mean (the equivalent
+// token): colmean[2][B][Df], then munorm2[B][workgroups] behind it.
 __global__ __launch_bounds__(256) void col_mean_kernel(FeatArgs a) {
+  __shared__ double red[256];
   const int d = blockIdx.x * blockDim.x + threadIdx.x;
   const int64_t b = blockIdx.y;
-  if (d >= a.Df) return;
   const int64_t slot = (int64_t)a.B * a.f_chunks * a.Df;
-  double su = 0.0, sr = 0.0;
-  for (int c = 0; c < a.f_chunks; ++c) {
-    su += a.colsum_part[(b * a.f_chunks + c) * a.Df + d];
-    sr += a.colsum_part[slot + (b * a.f_chunks + c) * a.Df + d];
+  double mm = 0.0;
+  if (d < a.Df) {
+    const double* p = a.colsum_part + b * a.f_chunks * (int64_t)a.Df + d;
+    double su = 0.0, sr = 0.0;
+    int c = 0;
+    for (; c + 8 <= a.f_chunks; c += 8) {
+      double vu[8], vr[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { vu[u] = p[(int64_t)(c + u) * a.Df]; vr[u] = p[slot + (int64_t)(c + u) * a.Df]; }
+#pragma unroll
+      for (int u = 0; u < 8; ++u) { su += vu[u]; sr += vr[u]; }
+    }
+    for (; c < a.f_chunks; ++c) { su += p[(int64_t)c * a.Df]; sr += p[slot + (int64_t)c * a.Df]; }
+    const double mu = sr / (double)a.N;
+    a.colmean[b * a.Df + d] = su / (double)a.N;
+    a.colmean[(int64_t)a.B * a.Df + b * a.Df + d] = mu;
+    mm = mu * mu;
   }
-  a.colmean[b * a.Df + d] = su / (double)a.N;
-  a.colmean[(int64_t)a.B * a.Df + b * a.Df + d] = sr / (double)a.N;
+  red[threadIdx.x] = mm;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int k = 0; k < (int)blockDim.x; ++k) t += red[k];      // fixed order
+    a.colmean[2 * (int64_t)a.B * a.Df + b * gridDim.x + blockIdx.x] = t;
+  }
 }
 
 template <typename T>
@@ -104,18 +172,43 @@ __global__ __launch_bounds__(256) void feature_terms_kernel(FeatArgs a) {
   const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
   const double* ubar = a.colmean + b * a.Df;
   const double* mu = a.colmean + (int64_t)a.B * a.Df + b * a.Df;
-  double du = 0.0, dm = 0.0, mm = 0.0;
-  for (int d = lane; d < a.Df; d += kWave) {
+  const int Dv = a.Df - a.Df % kVec;
+  double du = 0.0, dm = 0.0;
+  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
+    Raw8<T> raw;
+    load_raw(x + d, raw);
+    double v[kVec], w[kVec], m[kVec];
+    if (a.want_sim) {
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) w[k] = ubar[d + k];
+    }
+    if (a.want_eq) {
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) m[k] = mu[d + k];
+    }
+    widen_raw(raw, v);
+    if (a.want_sim) {
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) du += v[k] * w[k];
+    }
+    if (a.want_eq) {
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) dm += v[k] * m[k];
+    }
+  }
+  for (int d = Dv + lane; d < a.Df; d += kWave) {
     const double v = widen(x[d]);
     du += v * ubar[d];
     dm += v * mu[d];
-    mm += mu[d] * mu[d];
   }
-  du = wave_sum_d(du); dm = wave_sum_d(dm); mm = wave_sum_d(mm);
+  du = wave_sum_d(du); dm = wave_sum_d(dm);
   if (lane == 0) {
     const double nrm = a.norm[b * a.N + i];
     if (a.want_sim) a.fterm_r[b * a.N + i] = nrm > 0.0 ? du / nrm : 0.0;
     if (a.want_eq) {
+      const int n_part = (a.Df + 255) / 256;
+      double mm = 0.0;
+      for (int k = 0; k < n_part; ++k) mm += a.colmean[2 * (int64_t)a.B * a.Df + b * n_part + k];
       const double mn = sqrt(mm);
       a.fterm_g[b * a.N + i] = (nrm > 0.0 && mn > 0.0) ? -(dm / (mn * nrm)) : 0.0;
     }
@@ -144,7 +237,7 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
   if (bf16) hipLaunchKernelGGL(row_norm_kernel<bf16_t>, rows, block, 0, s, a);
   else hipLaunchKernelGGL(row_norm_kernel<float>, rows, block, 0, s, a);
   if (!a.want_sim && !a.want_eq) return;
-  dim3 cgrid(pl.f_chunks, (pl.Df + 255) / 256, p.B);
+  dim3 cgrid(pl.f_chunks, (pl.Df + kColSpan - 1) / kColSpan, p.B);
   if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);
   else hipLaunchKernelGGL(col_sum_kernel<float>, cgrid, block, 0, s, a);
   hipLaunchKernelGGL(col_mean_kernel, dim3((pl.Df + 255) / 256, p.B), block, 0, s, a);

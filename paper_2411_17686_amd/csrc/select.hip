@@ -137,7 +137,15 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
         const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
         double acc = 0.0;
-        for (int k = 0; k < a.M; ++k) acc += p[k];
+        int k = 0;
+        for (; k + 16 <= a.M; k += 16) {                  // 16 independent loads, added in order
+          double v[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) v[u] = p[k + u];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) acc += v[u];
+        }
+        for (; k < a.M; ++k) acc += p[k];
         G = acc / (double)a.M;
       } else if (a.sem_src == FICOCO_G_VECTOR) {
         G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);

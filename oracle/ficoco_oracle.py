@@ -37,6 +37,19 @@ Readings (where the paper is silent, ambiguous or garbled):
   R9  a row whose selected correlations sum to <= 0 recycles nothing (pure pruning).
   R10 extension (not in the paper): cosine correlation max(0, xh_i . xh_j) with the
       normalised rows xh rounded to bfloat16, and the mean-cosine first score term.
+  R11 ablation "fixed K" (ablation tables, rows "fixed K=0/1/2"; Sec. "Correlation-based
+      Information Recycling"): J_i = the K preserved tokens with the largest C_ij, ties to
+      the lower position; weights as in Eq. 2; K = 0 is pruning.
+  R12 ablation "convergent correlation" (same tables; the sentence on merging all discarded
+      tokens into an additional token): the preserved tokens stay as they are and ONE extra
+      token, the plain mean of the discarded tokens (added in ascending index), is placed
+      directly behind the last preserved visual token.  The paper gives no weights for it.
+  R13 ablation "average compression" (same tables; Sec. "Compress"): a preserved token is
+      averaged with the discarded tokens correlated to it, all with weight one; the
+      correlated sets are still those of the adaptive threshold.
+  R14 "pairwise token correlation gap" (same section): top-1 minus top-2 value of a row of C,
+      counted with multiplicity (a tie at the top gives 0); a row with fewer than two
+      preserved tokens has gap 0.
 
 All decisions (window maxima, the top-K filter, the threshold test) are taken on float64
 values; scalar hyper-parameters cross the library boundary as float32 and are widened
@@ -300,24 +313,76 @@ def correlated_targets(C, eps):
     return J, alpha, np.array(tau, dtype=F64)
 
 
-def compress(X, vis_begin, S, T, J, alpha):
+def fixed_k_targets(C, K):
+    """Ablation "fixed K" (reading R11): per discarded row the K preserved tokens with the
+    largest correlation, ties to the lower position; weights alpha as in Eq. 2."""
+    J, alpha = [], []
+    for i in range(C.shape[0]):
+        order = sorted(range(C.shape[1]), key=lambda j: (-C[i, j], j))
+        sel = np.array(sorted(order[:max(int(K), 0)]), dtype=np.int64)
+        d = 0.0
+        for j in sel:
+            d = d + C[i, j]
+        if len(sel) and d > 0.0:
+            J.append(sel)
+            alpha.append(np.array([C[i, j] / d for j in sel], dtype=F64))
+        else:                                       # reading R9
+            J.append(np.zeros(0, np.int64))
+            alpha.append(np.zeros(0, F64))
+    return J, alpha
+
+
+def correlation_gap(C):
+    """Pairwise token correlation gap of every discarded row (reading R14)."""
+    gap = np.zeros(C.shape[0], dtype=F64)
+    for i in range(C.shape[0]):
+        if C.shape[1] >= 2:
+            v = np.sort(np.asarray(C[i], dtype=F64))
+            gap[i] = v[-1] - v[-2]
+    return gap
+
+
+def convergent_token(X, vis_begin, S):
+    """The additional token of the "convergent" ablation (reading R12)."""
+    X = np.asarray(X, dtype=F64)
+    acc = np.zeros(X.shape[1], dtype=F64)
+    for i in S:
+        acc = acc + X[vis_begin + int(i)]
+    return acc / float(len(S))
+
+
+def compress(X, vis_begin, S, T, J, alpha, average=False, extra=None):
     """Eq. 2 and the last stage of Algorithms 1 and 2.
 
     X: [n_tot, D] float64 tokens of the whole sequence; S, T index the visual span that
     starts at vis_begin.  Every preserved visual token j becomes
         (X_j + sum_{i in I_j} alpha_ij X_i) / (1 + sum_{i in I_j} alpha_ij),
     sources added in ascending order of i; the discarded tokens are then removed and all
-    other tokens of the sequence keep their order."""
+    other tokens of the sequence keep their order.
+    average=True: every weight is one (ablation "average compression", reading R13).
+    extra: a row placed directly behind the last preserved visual token (the additional
+    token of the "convergent" ablation, reading R12)."""
     X = np.asarray(X, dtype=F64)
     num = {int(j): X[vis_begin + int(j)].copy() for j in T}
     den = {int(j): 1.0 for j in T}
     for a, i in enumerate(S):                       # S ascending -> ascending i per target
         for jj, w in zip(J[a], alpha[a]):
             j = int(T[jj])
+            if average:
+                w = 1.0
             num[j] = num[j] + w * X[vis_begin + int(i)]
             den[j] = den[j] + w
     gone = set(vis_begin + int(i) for i in S)
+    last_kept = vis_begin + int(max(T)) if len(T) else None
     rows = []
+    if extra is not None and last_kept is None:     # no preserved visual token: the extra one opens the span
+        for t in range(vis_begin):
+            rows.append(X[t].copy())
+        rows.append(np.asarray(extra, dtype=F64).copy())
+        for t in range(vis_begin, X.shape[0]):
+            if t not in gone:
+                rows.append(X[t].copy())
+        return np.array(rows, dtype=F64).reshape(len(rows), X.shape[1])
     for t in range(X.shape[0]):
         if t in gone:
             continue
@@ -326,30 +391,45 @@ def compress(X, vis_begin, S, T, J, alpha):
             rows.append(num[j] / den[j])
         else:
             rows.append(X[t].copy())
+        if extra is not None and t == last_kept:
+            rows.append(np.asarray(extra, dtype=F64).copy())
     return np.array(rows, dtype=F64).reshape(len(rows), X.shape[1])
 
 
 # --------------------------------------------------------------------------- whole steps
-def _finish(X, vis_begin, s, n_keep, C_of, eps, pos):
+def _finish(X, vis_begin, s, n_keep, C_of, eps, pos, k_mode="adaptive", fixed_k=1, average=False):
+    """k_mode: 'adaptive' (the method), 'fixed' (top-fixed_k per row) or 'convergent'."""
     S, T = filter_tokens(s, n_keep)
     C = C_of(S, T)
-    J, alpha, tau = correlated_targets(C, eps)
-    X_out = compress(X, vis_begin, S, T, J, alpha)
+    tau = None
+    extra = None
+    if k_mode == "adaptive":
+        J, alpha, tau = correlated_targets(C, eps)
+    elif k_mode == "fixed":
+        J, alpha = fixed_k_targets(C, fixed_k)
+    elif k_mode == "convergent":
+        J = [np.zeros(0, np.int64) for _ in S]
+        alpha = [np.zeros(0, F64) for _ in S]
+        extra = convergent_token(X, vis_begin, S) if len(S) else None
+    else:
+        raise ValueError(k_mode)
+    X_out = compress(X, vis_begin, S, T, J, alpha, average=average, extra=extra)
     pos_out = None if pos is None else np.asarray(pos)[T]
     return dict(X_out=X_out, S=S, T=T, J=J, alpha=alpha, tau=tau, scores=s, C=C,
-                pos_out=pos_out)
+                pos_out=pos_out, gap=correlation_gap(C))
 
 
 def v_step(X, A, *, cls_index, vis_begin, N, n_keep, lam=0.35, eps=0.998,
            pos=None, grid=(1, 0, 0), window=2, coef=2.0,
            recv_vec=None, sem_vec=None, F=None,
-           red_src="attn", sem_src="cls", corr_src="attn"):
+           red_src="attn", sem_src="cls", corr_src="attn",
+           k_mode="adaptive", fixed_k=1, average=False):
     """Algorithm 1 for one image.
 
     X [n_tot, D]; A [H, n_tot, n_tot] or None; visual span [vis_begin, vis_begin+N).
     red_src: 'attn' | 'vector' | 'sim_mean';  sem_src: 'cls' | 'vector' | 'eq_token';
     corr_src: 'attn' | 'cosine'.  F: features for the cosine-based terms (default: the
-    visual rows of X)."""
+    visual rows of X).  k_mode / fixed_k / average: the ablation variants (R11-R13)."""
     X = np.asarray(X, dtype=F64)
     vis = np.arange(vis_begin, vis_begin + N)
     Fv = X[vis] if F is None else np.asarray(F, dtype=F64)
@@ -381,11 +461,11 @@ def v_step(X, A, *, cls_index, vis_begin, N, n_keep, lam=0.35, eps=0.998,
         C_of = lambda S, T: correlation_cosine(Fv, S, T)
     else:
         raise ValueError(corr_src)
-    return _finish(X, vis_begin, s, n_keep, C_of, eps, pos)
+    return _finish(X, vis_begin, s, n_keep, C_of, eps, pos, k_mode, fixed_k, average)
 
 
 def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.998,
-           F=None, red_src="attn", corr_src="attn"):
+           F=None, red_src="attn", corr_src="attn", k_mode="adaptive", fixed_k=1, average=False):
     """Algorithm 2 for one sequence.
 
     X [n_tot, D] (system + visual + text tokens); A_tv [H, M, N]: attention of the M text
@@ -414,4 +494,4 @@ def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.99
     else:
         raise ValueError(corr_src)
     C_of = lambda S, T: correlation_l(direct(S, T), text_bridge(Pt, S, T), gamma)
-    return _finish(X, vis_begin, s, n_keep, C_of, eps, None)
+    return _finish(X, vis_begin, s, n_keep, C_of, eps, None, k_mode, fixed_k, average)

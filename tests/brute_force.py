@@ -83,38 +83,74 @@ def dense_weights(C, eps):
     return W
 
 
-def merge(X, vis_begin, S, T, W):
+def top_k_weights(C, K):
+    """Ablation "fixed K": K rounds of "take the largest remaining value of the row, first
+    position on ties"; weights = value / sum of the taken values."""
+    W = [[0.0] * len(C[0]) for _ in C] if len(C) and len(C[0]) else [[] for _ in C]
+    for a, row in enumerate(C):
+        left = list(range(len(row)))
+        took = []
+        for _ in range(min(K, len(row))):
+            best = left[0]
+            for b in left:
+                if row[b] > row[best]:
+                    best = b
+            took.append(best)
+            left.remove(best)
+        tot = 0.0
+        for b in sorted(took):
+            tot += row[b]
+        if tot > 0.0:
+            for b in took:
+                W[a][b] = row[b] / tot
+    return W
+
+
+def merge(X, vis_begin, S, T, W, average=False, convergent=False):
+    """average: every non-zero weight counts as one.  convergent: W is ignored, the preserved
+    tokens stay, and the mean of the discarded tokens follows the last preserved one."""
     D = len(X[0])
     out = []
     gone = {vis_begin + i for i in S}
     slot = {vis_begin + j: b for b, j in enumerate(T)}
+    extra_after = vis_begin + max(T) if (convergent and S and T) else None
+    extra = None
+    if convergent and S:
+        extra = [sum(X[vis_begin + i][d] for i in S) / len(S) for d in range(D)]
     for t, row in enumerate(X):
+        if convergent and S and not T and t == vis_begin:
+            out.append(extra)
         if t in gone:
             continue
-        if t in slot:
+        if t in slot and not convergent:
             b = slot[t]
             col = [W[a][b] for a in range(len(S))]
             num = list(row)
             den = 1.0
             for a, w in enumerate(col):
                 if w != 0.0:
+                    if average:
+                        w = 1.0
                     src = X[vis_begin + S[a]]
                     num = [num[d] + w * src[d] for d in range(D)]
                     den += w
             out.append([v / den for v in num])
         else:
             out.append(list(row))
+        if t == extra_after:
+            out.append(extra)
     return out
 
 
-def v_step(X, P, cls, vis_begin, N, n_keep, lam, eps, pos, gh, gw, window, coef):
+def v_step(X, P, cls, vis_begin, N, n_keep, lam, eps, pos, gh, gw, window, coef,
+           fixed_k=None, average=False, convergent=False):
     vis = list(range(vis_begin, vis_begin + N))
     s = v_scores(P, cls, vis, lam, pos, gh, gw, window, coef)
     S, T = split(s, n_keep)
     P32 = [[float(np.float32(v)) for v in row] for row in P]
     C = [[P32[vis_begin + j][vis_begin + i] for j in T] for i in S]
-    W = dense_weights(C, eps)
-    return merge(X, vis_begin, S, T, W), S, T, W, s
+    W = dense_weights(C, eps) if fixed_k is None else top_k_weights(C, fixed_k)
+    return merge(X, vis_begin, S, T, W, average, convergent), S, T, W, s
 
 
 def l_step(X, Pvv, Ptv, vis_begin, N, n_keep, beta, gamma, eps):

@@ -75,7 +75,9 @@ def _m_filter_ascending(s, n_keep):                 # keeps the most redundant t
             np.array(sorted(order[n - n_keep:]), dtype=np.int64))
 
 
-def _m_compress_no_self(X, vis_begin, S, T, J, alpha):   # dropped the "1 +" of Eq. 2
+def _m_compress_no_self(X, vis_begin, S, T, J, alpha, average=False, extra=None):   # dropped the "1 +" of Eq. 2
+    if average or extra is not None:
+        return O._real_compress(X, vis_begin, S, T, J, alpha, average=average, extra=extra)
     out = O._real_compress(X, vis_begin, S, T, J, alpha)
     a = np.zeros(len(T))
     for i in range(len(S)):
@@ -96,6 +98,31 @@ def _m_head_mean_first(A):                          # ignores all heads but the 
     return np.asarray(A, dtype=np.float64)[0].copy()
 
 
+def _m_fixed_k_high_index(C, K):                    # ties go to the higher position
+    J, alpha = [], []
+    for i in range(C.shape[0]):
+        order = sorted(range(C.shape[1]), key=lambda j: (-C[i, j], -j))
+        sel = np.array(sorted(order[:max(int(K), 0)]), dtype=np.int64)
+        d = sum(C[i, j] for j in sel)
+        if len(sel) and d > 0.0:
+            J.append(sel); alpha.append(np.array([C[i, j] / d for j in sel]))
+        else:
+            J.append(np.zeros(0, np.int64)); alpha.append(np.zeros(0))
+    return J, alpha
+
+
+def _m_average_keeps_weights(X, vis_begin, S, T, J, alpha, average=False, extra=None):   # "average" still weighted
+    return O._real_compress(X, vis_begin, S, T, J, alpha, average=False, extra=extra)
+
+
+def _m_convergent_sum(X, vis_begin, S):             # dropped the division by N^S
+    return O._real_convergent(X, vis_begin, S) * float(len(S))
+
+
+def _m_gap_top1(C):                                 # forgot to subtract the runner-up
+    return np.max(C, axis=1) if C.shape[1] >= 2 else np.zeros(C.shape[0])
+
+
 MUTANTS = [
     ("received_attention", _m_row_mean),
     ("combine_score", _m_score_sign),
@@ -106,13 +133,18 @@ MUTANTS = [
     ("compress", _m_compress_no_self),
     ("local_penalty", _m_penalty_min),
     ("head_mean", _m_head_mean_first),
+    ("fixed_k_targets", _m_fixed_k_high_index),
+    ("compress", _m_average_keeps_weights),
+    ("convergent_token", _m_convergent_sum),
+    ("correlation_gap", _m_gap_top1),
 ]
 
 
-@pytest.mark.parametrize("name,mutant", MUTANTS, ids=[m[0] for m in MUTANTS])
+@pytest.mark.parametrize("name,mutant", MUTANTS, ids=["%s-%s" % (m[0], m[1].__name__) for m in MUTANTS])
 def test_planted_mistake_is_caught(monkeypatch, name, mutant):
     monkeypatch.setattr(O, "_real_compress", O.compress, raising=False)
     monkeypatch.setattr(O, "_real_penalty", O.local_penalty, raising=False)
+    monkeypatch.setattr(O, "_real_convergent", O.convergent_token, raising=False)
     monkeypatch.setattr(O, name, mutant)
     failed = _run_pins()
     assert failed, "no pin noticed the mutated %s" % name

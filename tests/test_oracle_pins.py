@@ -501,3 +501,94 @@ def test_v_step_modes_vector_and_cosine():
     S, T = res["S"], res["T"]
     assert np.array_equal(res["C"], O.correlation_cosine(X, S, T))
     assert res["X_out"].shape == (6, D)
+
+
+# ------------------------------------------------------------------ ablation variants (readings R11-R14)
+def test_fixed_k_closed_forms():
+    C = np.array([[0.1, 0.7, 0.7, 0.2],      # tie at the top: positions 1 and 2
+                  [0.0, 0.0, 0.0, 0.0],      # nothing to recycle (R9)
+                  [0.5, 0.25, 0.125, 0.125]])
+    J0, a0 = O.fixed_k_targets(C, 0)
+    assert all(len(j) == 0 for j in J0)                                   # K = 0 is pruning
+    J1, a1 = O.fixed_k_targets(C, 1)
+    assert J1[0].tolist() == [1] and a1[0].tolist() == [1.0]              # tie -> lower position
+    assert len(J1[1]) == 0
+    assert J1[2].tolist() == [0]
+    J2, a2 = O.fixed_k_targets(C, 2)
+    assert J2[0].tolist() == [1, 2] and np.allclose(a2[0], [0.5, 0.5])
+    assert J2[2].tolist() == [0, 1] and np.allclose(a2[2], [2 / 3, 1 / 3])
+    J3, a3 = O.fixed_k_targets(C, 3)
+    assert J3[2].tolist() == [0, 1, 2]                                    # tie at the cut: lower position
+    J9, a9 = O.fixed_k_targets(C, 9)
+    assert J9[2].tolist() == [0, 1, 2, 3] and abs(a9[2].sum() - 1.0) < 1e-15
+
+
+def test_fixed_k1_is_argmax_and_gap_matches_sorted_row():
+    r = rng(77)
+    C = r.random((9, 6))
+    J, a = O.fixed_k_targets(C, 1)
+    assert [int(j[0]) for j in J] == np.argmax(C, axis=1).tolist()
+    srt = np.sort(C, axis=1)
+    assert np.array_equal(O.correlation_gap(C), srt[:, -1] - srt[:, -2])
+    C[0, :] = 0.25
+    assert O.correlation_gap(C)[0] == 0.0                                 # tie at the top
+    assert O.correlation_gap(np.ones((3, 1))).tolist() == [0.0, 0.0, 0.0]  # fewer than two preserved tokens
+
+
+def test_average_compression_closed_form():
+    r = rng(78)
+    X = r.standard_normal((6, 4))
+    S, T = np.array([1, 3, 4]), np.array([0, 2, 5])
+    J = [np.array([0]), np.array([0, 2]), np.array([], dtype=np.int64)]
+    alpha = [np.array([1.0]), np.array([0.9, 0.1]), np.array([])]
+    out = O.compress(X, 0, S, T, J, alpha, average=True)
+    assert np.allclose(out[0], (X[0] + X[1] + X[3]) / 3.0, rtol=1e-15)    # two sources, weights ignored
+    assert np.array_equal(out[1], X[2])                                   # no source
+    assert np.allclose(out[2], (X[5] + X[3]) / 2.0, rtol=1e-15)
+    ref = O.compress(X, 0, S, T, J, alpha)
+    assert np.allclose(ref[0], (X[0] + X[1] + 0.9 * X[3]) / 2.9, rtol=1e-15)
+
+
+def test_convergent_token_and_layout():
+    r = rng(79)
+    X = r.standard_normal((9, 3))            # 2 leading + 5 visual + 2 trailing tokens
+    S, T = np.array([0, 3]), np.array([1, 2, 4])
+    none = [np.zeros(0, np.int64)] * 2
+    extra = O.convergent_token(X, 2, S)
+    assert np.allclose(extra, X[[2, 5]].mean(axis=0), rtol=1e-15)
+    out = O.compress(X, 2, S, T, none, [np.zeros(0)] * 2, extra=extra)
+    assert out.shape == (8, 3)                                            # N^S rows leave, one comes
+    assert np.array_equal(out[[0, 1, 2, 3, 4, 6, 7]], X[[0, 1, 3, 4, 6, 7, 8]])
+    assert np.array_equal(out[5], extra)                                  # directly behind the last preserved visual token
+
+
+@pytest.mark.parametrize("seed", range(9))
+def test_v_step_ablations_against_brute_force(seed):
+    r = rng(300 + seed)
+    n_side = [3, 4, 2][seed % 3]
+    N = n_side * n_side
+    X, A = _tiny_v_case(r, n_side, 3, 2, ties=(seed % 2 == 1 and n_side >= 3))
+    n_keep = int(r.integers(1, N + 1))
+    mode = ["fixed0", "fixed1", "fixed2", "average", "convergent"][seed % 5]
+    kw = dict(fixed0=dict(k_mode="fixed", fixed_k=0), fixed1=dict(k_mode="fixed", fixed_k=1),
+              fixed2=dict(k_mode="fixed", fixed_k=2), average=dict(average=True),
+              convergent=dict(k_mode="convergent"))[mode]
+    res = O.v_step(X, A, cls_index=0, vis_begin=1, N=N, n_keep=n_keep, lam=0.35, eps=0.5,
+                   grid=(1, n_side, n_side), window=2, coef=2.0, **kw)
+    P = O.head_mean(A)
+    bkw = dict(fixed0=dict(fixed_k=0), fixed1=dict(fixed_k=1), fixed2=dict(fixed_k=2),
+               average=dict(average=True), convergent=dict(convergent=True))[mode]
+    out, S, T, W, s = BF.v_step(X.tolist(), P.tolist(), 0, 1, N, n_keep, 0.35, 0.5,
+                                list(range(N)), n_side, n_side, 2, 2.0, **bkw)
+    assert res["S"].tolist() == S and res["T"].tolist() == T
+    if mode.startswith("fixed"):
+        for a in range(len(S)):
+            hit = [b for b in range(len(T)) if W[a][b] != 0.0]
+            assert res["J"][a].tolist() == hit
+            assert np.allclose(res["alpha"][a], [W[a][b] for b in hit], rtol=1e-14)
+    n_rows = X.shape[0] - (N - n_keep) + (1 if mode == "convergent" and n_keep < N else 0)
+    assert res["X_out"].shape[0] == n_rows
+    assert np.allclose(res["X_out"], np.array(out).reshape(res["X_out"].shape), rtol=1e-13, atol=1e-15)
+    if mode == "fixed0":                     # pruning: the preserved tokens are untouched
+        keep_rows = [0] + [1 + j for j in T]
+        assert np.array_equal(res["X_out"], X[keep_rows])

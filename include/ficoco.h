@@ -71,6 +71,24 @@ typedef enum {
   FICOCO_C_COSINE = 1 /* extension: max(0, xh_i . xh_j), xh = bfloat16(F / |F|)                */
 } ficoco_corr_src;
 
+/* How the targets of a discarded token are chosen (Sec. "Correlation-based Information
+ * Recycling" and the "Correlate" rows of the two ablation tables). */
+typedef enum {
+  FICOCO_K_ADAPTIVE = 0,  /* the method: token-wise eps-quantile threshold                       */
+  FICOCO_K_FIXED = 1,     /* ablation "fixed K": the fixed_k largest C_ij of the row, ties to the
+                             lower position; fixed_k = 0 is pruning                              */
+  FICOCO_K_CONVERGENT = 2 /* ablation "convergent correlation": the preserved tokens stay as they
+                             are; ONE extra token, the plain mean of the discarded tokens, is
+                             written directly behind the last preserved visual token           */
+} ficoco_k_mode;
+
+/* How a preserved token takes up its sources (Sec. "Compress", Eq. 2, and the "Compress" row
+ * of the ablation tables). */
+typedef enum {
+  FICOCO_COMPRESS_SELF = 0,   /* Eq. 2, self-preserving compression                            */
+  FICOCO_COMPRESS_AVERAGE = 1 /* ablation "average compression": every weight is one           */
+} ficoco_compress_mode;
+
 /*
  * Problem description (host struct, passed by pointer, read during the call only).
  * Token indices are positions in the sequence of n_tot tokens; the reducible visual tokens
@@ -125,6 +143,12 @@ typedef struct {
 
   int32_t red_src, sem_src, corr_src;
   int32_t k_max; /* capacity of targets per discarded token in the edge lists (>= 1) */
+
+  /* Ablation variants; all zero = the method as published.  With FICOCO_K_CONVERGENT and at
+   * least one discarded token X_out has one row more: n_tot - N^S + 1 (see ficoco_out_rows). */
+  int32_t k_mode;        /* ficoco_k_mode                                                  */
+  int32_t fixed_k;       /* FICOCO_K_FIXED: targets per discarded token, 0 <= fixed_k <= k_max */
+  int32_t compress_mode; /* ficoco_compress_mode                                           */
 } ficoco_problem;
 
 /* ctx: create once per device; not thread safe (one ctx per calling thread). */
@@ -149,6 +173,10 @@ int ficoco_set_probe(ficoco_ctx *ctx, int kernel, void *start_event, void *stop_
  * pointer expected).  The workspace carries state from one stage to the next: the stage
  * functions must be called in order, on one stream, with the same problem and workspace. */
 int ficoco_workspace_bytes(const ficoco_problem *p, size_t *out_bytes);
+
+/* Rows per sequence of X_out for this problem: n_tot - N^S, plus one for the additional
+ * token of FICOCO_K_CONVERGENT when N^S > 0.  Host arithmetic only. */
+int ficoco_out_rows(const ficoco_problem *p, int32_t *out_rows);
 
 /*
  * Attention reduction alone (the first term of Eq. 1 / Eq. 3, the [CLS] / text terms and
@@ -196,11 +224,23 @@ int ficoco_correlate(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t 
                      int32_t *edge_tgt, double *edge_alpha, int32_t *overflow, void *stream);
 
 /*
+ * Pairwise token correlation gap (Sec. "Correlation-based Information Recycling": the
+ * difference between the top-1 and the top-2 correlation of every discarded token, the
+ * diagnostic behind the token-adaptive K), evaluated in double precision on the exact
+ * correlation values.  Needs the workspace state ficoco_correlate needs.
+ *   gap [B][N^S] double, out: 0 where fewer than two tokens are preserved.
+ */
+int ficoco_correlation_gap(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,
+                           const int32_t *discard_idx, const int32_t *keep_idx, double *gap,
+                           void *stream);
+
+/*
  * Compress (Eq. 2, self-preserving compression; last lines of Algorithm 1/2): every
  * preserved visual token becomes (X_j + sum_i alpha_ij X_i) / (1 + sum_i alpha_ij), sources
  * added in ascending order; discarded tokens are dropped and every other token of the
  * sequence is copied unchanged, order preserved.
- *   X_out   [B][n_tot - N^S][D] dtype, out (dense).
+ *   X_out   [B][ficoco_out_rows][D] dtype, out (dense); compress_mode / k_mode select the
+ *           ablation variants (average weights; the additional token of the convergent form).
  *   pos_out [B][N^T] int32, out: grid cells of the preserved tokens (may be NULL).
  */
 int ficoco_compress(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_bytes,

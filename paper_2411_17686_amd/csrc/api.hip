@@ -41,6 +41,11 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   REQUIRE(p.x_stride_n >= p.D && p.x_stride_b >= 0, "bad X strides");
   REQUIRE(p.eps >= 0.0f && p.eps <= 1.0f, "eps must be in [0, 1]");
   REQUIRE(p.k_max >= 1, "k_max must be >= 1");
+  REQUIRE(p.k_mode >= FICOCO_K_ADAPTIVE && p.k_mode <= FICOCO_K_CONVERGENT, "unknown k_mode");
+  REQUIRE(p.compress_mode == FICOCO_COMPRESS_SELF || p.compress_mode == FICOCO_COMPRESS_AVERAGE,
+          "unknown compress_mode");
+  if (p.k_mode == FICOCO_K_FIXED)
+    REQUIRE(p.fixed_k >= 0 && p.fixed_k <= p.k_max, "fixed_k must be in [0, k_max]");
   REQUIRE(p.red_src >= 0 && p.red_src <= 2 && p.sem_src >= 0 && p.sem_src <= 3 &&
               p.corr_src >= 0 && p.corr_src <= 1, "unknown source selector");
   const bool L = p.variant == FICOCO_VARIANT_L;
@@ -85,7 +90,11 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
 #undef REQUIRE
 
   pl.n_disc = p.N - p.n_keep;
-  pl.n_out = p.n_tot - pl.n_disc;
+  pl.extra_token = p.k_mode == FICOCO_K_CONVERGENT && pl.n_disc > 0;
+  pl.n_out = p.n_tot - pl.n_disc + (pl.extra_token ? 1 : 0);
+  // targets per discarded token fixed by the caller (ablation): 0 = no edges at all
+  pl.fixed_k = p.k_mode == FICOCO_K_FIXED ? std::min(p.fixed_k, p.n_keep) : -1;
+  if (p.k_mode == FICOCO_K_CONVERGENT) pl.fixed_k = 0;
 
   // attention reduction geometry
   // Column strips: the fewest strips that keep at least 80 % of a workgroup's threads busy
@@ -136,6 +145,11 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
     pl.sel_f = (int)f;
     pl.sel_g = q - f;
     pl.sel_m = p.n_keep - pl.sel_f;
+    if (pl.fixed_k > 0) {      // fixed K: the threshold is the K-th largest value itself
+      pl.sel_m = pl.fixed_k;
+      pl.sel_f = p.n_keep - pl.fixed_k;
+      pl.sel_g = 0.0;
+    }
     pl.dense_rows = pl.sel_m > kSelMax;
   }
 
@@ -289,6 +303,16 @@ int ficoco_workspace_bytes(const ficoco_problem* p, size_t* out_bytes) {
   return FICOCO_OK;
 }
 
+int ficoco_out_rows(const ficoco_problem* p, int32_t* out_rows) {
+  if (!p || !out_rows) return FICOCO_EINVAL;
+  Plan pl;
+  const char* why;
+  const int rc = make_plan(*p, pl, &why);
+  if (rc != FICOCO_OK) return rc;
+  *out_rows = pl.n_out;
+  return FICOCO_OK;
+}
+
 int ficoco_reduce(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, void* stream) {
   Plan pl;
   const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_reduce");
@@ -336,6 +360,17 @@ int ficoco_correlate(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t 
                    false, pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr,
                    (hipStream_t)stream);
   return finish(ctx, "ficoco_correlate");
+}
+
+int ficoco_correlation_gap(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,
+                           const int32_t* discard_idx, const int32_t* keep_idx, double* gap, void* stream) {
+  Plan pl;
+  const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_correlation_gap");
+  if (rc != FICOCO_OK) return rc;
+  if (!keep_idx || (pl.n_disc > 0 && (!discard_idx || !gap)))
+    return fail(ctx, FICOCO_EINVAL, "ficoco_correlation_gap", "a pointer is NULL");
+  launch_corr_gap(*p, pl, (char*)ws, discard_idx, keep_idx, gap, (hipStream_t)stream);
+  return finish(ctx, "ficoco_correlation_gap");
 }
 
 int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,

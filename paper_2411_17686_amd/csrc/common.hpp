@@ -56,6 +56,8 @@ struct Plan {
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
+  int fixed_k;           // >= 0: targets per discarded token fixed by the caller (0: no edges), -1: adaptive
+  bool extra_token;      // the additional token of the convergent form is written
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
   int gram_splits, gram_st_per_split;   // K ranges of that kernel and their length in 32-feature stages
   int f_chunks, f_rows_per_wg, Df;
@@ -80,6 +82,8 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
                       hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s);
+void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
+                     const int32_t* keep_idx, double* gap, hipStream_t s);
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out,

@@ -142,6 +142,8 @@ struct MergeArgs {
   const double* edge_alpha;
   const int32_t* pos;
   int32_t* pos_out;
+  int average;      // ablation "average compression": every weight counts as one
+  int extra_row;    // output row of the additional token of the convergent form (mean of the discarded tokens), or -1
 };
 
 template <typename T>
@@ -281,7 +283,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   const int r = unit / n_spans;
   const int d0 = (unit % n_spans) * kSpan;
   const int64_t b = blockIdx.y;
-  const bool valid = r < a.n_out;
+  const bool valid = r < a.n_out && r != a.extra_row;   // the additional token is written by extra_token_kernel
 
   if (MATCH && a.n_disc > 0) {
     const int e1 = min(1, a.k_max - 1);
@@ -291,8 +293,8 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       tb.src[row] = a.S[rr];
       tb.t0[row] = a.edge_tgt[rr * a.k_max];
       tb.t1[row] = a.edge_tgt[rr * a.k_max + e1];
-      tb.a0[row] = a.edge_alpha[rr * a.k_max];
-      tb.a1[row] = a.edge_alpha[rr * a.k_max + e1];
+      tb.a0[row] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max];
+      tb.a1[row] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max + e1];
     }
   }
 
@@ -315,7 +317,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       if (lane == 0 && sub == 0 && d0 == 0 && a.pos_out)
         a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
     } else {
-      t = r + a.n_disc;
+      t = r + a.n_disc - (a.extra_row >= 0 ? 1 : 0);
     }
   }
   const T* x = Xb + (int64_t)t * a.xsn;
@@ -351,7 +353,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
       if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
       for (int e = 2; e < cnt; ++e)
-        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
+        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
       const unsigned long long m = __ballot(hit);
       if (hit) {
         const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
@@ -372,7 +374,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       for (int q = 0; q < kBucketPer; ++q) {
         const bool in = q * kWave + lane < n_all;
         const int rw = in ? a.tgt_src[ebase + e0 + q * kWave + lane] : 0x7fffffff;
-        w[q] = in ? a.tgt_alpha[ebase + e0 + q * kWave + lane] : 0.0;
+        w[q] = in ? (a.average ? 1.0 : a.tgt_alpha[ebase + e0 + q * kWave + lane]) : 0.0;
         row[q] = (rw >= row_lo && rw < row_hi) ? rw : 0x7fffffff;
         rank[q] = 0;
       }
@@ -457,7 +459,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
         if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
         for (int e = 2; e < cnt; ++e)
-          if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
+          if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
         const int src = in ? tb.src[row] : 0;
         unsigned long long m = __ballot(hit);
         while (m) {
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         if (who == 0) break;             // fewer distinct rows than entries: inconsistent device data
         const int l = __ffsll(who) - 1;
         const int e = __shfl(best_e, l, kWave);
-        const double w = a.tgt_alpha[ebase + e];
+        const double w = a.average ? 1.0 : a.tgt_alpha[ebase + e];
         den += w;
         add_source<T, SLICE>(a, Xb, a.S[b * a.n_disc + min(max(mn, 0), a.n_disc - 1)], w, d0, lane, full, num);
         last = mn;
@@ -541,6 +543,57 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         if (d + k < a.D) store_token(out + d + k, num[u][k] / den);
     }
   }
+}
+
+// The additional token of the "convergent" ablation: the plain mean of the discarded tokens.
+// A workgroup covers 512 features of one image; each of its four wavefronts adds a quarter of
+// the discarded rows in ascending order (16-byte loads of 8 rows in flight), the quarters are
+// added in order and the sum is divided by N^S.
+template <typename T>
+__global__ __launch_bounds__(256) void extra_token_kernel(MergeArgs a) {
+  __shared__ double part[3][kVec][kWave];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int d = (blockIdx.x * kWave + lane) * kVec;
+  const int64_t b = blockIdx.y;
+  const int nd = max(min(kVec, a.D - d), 0);
+  const int quarter = (a.n_disc + 3) / 4;
+  const int r0 = min(wv * quarter, a.n_disc), r1 = min(r0 + quarter, a.n_disc);
+  const T* Xb = (const T*)a.X + b * a.xsb + d;
+  double acc[kVec];
+#pragma unroll
+  for (int k = 0; k < kVec; ++k) acc[k] = 0.0;
+  for (int e0 = r0; e0 < r1; e0 += 8) {
+    int tok[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int i = a.S[b * a.n_disc + min(e0 + u, r1 - 1)];
+      tok[u] = a.vis_begin + min(max(i, 0), a.N - 1);     // index sets are device data: stay inside the span
+    }
+    if (nd == kVec) {
+      Raw8<T> raw[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) load_raw(Xb + (int64_t)tok[u] * a.xsn, raw[u]);
+#pragma unroll
+      for (int u = 0; u < 8; ++u)
+        if (e0 + u < r1) add_raw(raw[u], acc);
+    } else {
+      for (int u = 0; u < 8 && e0 + u < r1; ++u)
+        for (int k = 0; k < nd; ++k) acc[k] += widen(Xb[(int64_t)tok[u] * a.xsn + k]);
+    }
+  }
+  if (wv > 0) {
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) part[wv - 1][k][lane] = acc[k];
+  }
+  __syncthreads();
+  if (wv > 0 || nd == 0) return;
+#pragma unroll
+  for (int w = 0; w < 3; ++w)
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) acc[k] += part[w][k][lane];
+  T* out = (T*)a.X_out + (b * a.n_out + a.extra_row) * (int64_t)a.D + d;
+  const double cnt = (double)a.n_disc;
+  for (int k = 0; k < nd; ++k) store_token(out + k, acc[k] / cnt);
 }
 
 constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
@@ -601,6 +654,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.tgt_alpha = (const double*)(ws + pl.tgt_alpha);
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
   m.pos = p.pos; m.pos_out = pos_out;
+  m.average = p.compress_mode == FICOCO_COMPRESS_AVERAGE ? 1 : 0;
+  m.extra_row = pl.extra_token ? p.vis_begin + p.n_keep : -1;
   // One wavefront per unit: four of them shorten a single step when preserved tokens have
   // many sources (long sequences) but cost throughput when independent steps overlap, which
   // is what is measured; the build option remains.  Narrow spans (one 8-element vector per
@@ -612,6 +667,11 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
     if (match) launch_merge_m<bf16_t, true>(m, p.B, slice, wpu, s); else launch_merge_m<bf16_t, false>(m, p.B, slice, wpu, s);
   } else {
     if (match) launch_merge_m<float, true>(m, p.B, slice, wpu, s); else launch_merge_m<float, false>(m, p.B, slice, wpu, s);
+  }
+  if (m.extra_row >= 0) {
+    dim3 grid((p.D + kWave * kVec - 1) / (kWave * kVec), p.B);
+    if (p.dtype == FICOCO_BF16) hipLaunchKernelGGL(extra_token_kernel<bf16_t>, grid, dim3(256), 0, s, m);
+    else hipLaunchKernelGGL(extra_token_kernel<float>, grid, dim3(256), 0, s, m);
   }
 }
 

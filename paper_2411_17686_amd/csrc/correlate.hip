@@ -38,6 +38,9 @@ struct CorrArgs {
   int ct_splits;
   double* cmax;          // [B][M]
   float delta;           // bound of |ct - exact dot|
+  int fixed_k;           // > 0: ablation "fixed K" (sel_m = K, sel_g = 0): of the values equal to the threshold only
+                         // the lowest positions are taken, K targets in all; -1: every value >= threshold
+  double* gap;           // correlation-gap diagnostic output [B][n_disc] (its own kernel)
 };
 
 __device__ __forceinline__ double dot_bf16(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y, int D) {
@@ -146,9 +149,14 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
   const double NEG = -__builtin_huge_val();
 
   double v_f, v_f1;
+  int n_gt = 0;                      // values strictly above v_f (used by the fixed-K form only)
   if (a.dense) {
     v_f = select_rank(rowv, n, a.sel_f, lane);
     v_f1 = a.sel_f + 1 <= n - 1 ? select_rank(rowv, n, a.sel_f + 1, lane) : v_f;
+    if (a.fixed_k > 0) {
+      for (int jj = lane; jj < n; jj += kWave) n_gt += rowv[jj] > v_f ? 1 : 0;
+      n_gt = wave_sum(n_gt);
+    }
   } else {
     // per-lane descending top list, then m rounds of "pop the wavefront maximum"
     double top[kSelMax];
@@ -177,12 +185,15 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
         for (int k = 0; k + 1 < kSelMax; ++k) top[k] = top[k + 1];
         top[kSelMax - 1] = NEG;
       }
+      if (r == 0 || mx < v_f) n_gt = r;     // pops so far that are strictly above this one
       v_f1 = v_f;
       v_f = mx;
     }
     if (a.sel_m == 1) v_f1 = v_f;
   }
   const double tau = threshold_of(v_f, v_f1, a.sel_g);
+  const int tie_quota = a.fixed_k > 0 ? a.sel_m - n_gt : 0x7fffffff;   // values equal to tau that are taken
+  int ties_seen = 0;
 
   // Emit targets in ascending order; lane e of the wavefront ends up holding edge e.
   int cnt = 0;
@@ -197,7 +208,11 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
       if (a.dense) c = rowv[jj];
       else { const int j = T[jj]; if ((unsigned)j < (unsigned)a.N) c = corr_value(a, b, i, j); }
     }
-    unsigned long long hit = __ballot(jj < n && c >= tau);
+    const bool is_eq = jj < n && c == tau;
+    const unsigned long long eqm = __ballot(is_eq);
+    const int eq_rank = ties_seen + __popcll(eqm & ((1ULL << lane) - 1ULL));
+    ties_seen += __popcll(eqm);
+    unsigned long long hit = __ballot(jj < n && (c > tau || (is_eq && eq_rank < tie_quota)));
     while (hit) {
       const int l = __ffsll(hit) - 1;
       hit &= hit - 1;
@@ -539,19 +554,24 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   }
   // v[f], v[f+1] = m-th and (m-1)-th largest of the exact candidate values
   double v_f = NEG, v_f1 = NEG;
+  int n_gt = 0;
   {
     double act = myv;
     for (int r = 0; r < a.sel_m; ++r) {
       const double mx = wave_max(act);
       const unsigned long long who = __ballot(act == mx);
       if (lane == __ffsll(who) - 1) act = NEG;
+      if (r == 0 || mx < v_f) n_gt = r;
       v_f1 = v_f;
       v_f = mx;
     }
     if (a.sel_m == 1) v_f1 = v_f;
   }
   const double tau = threshold_of(v_f, v_f1, a.sel_g);
-  unsigned long long hit = __ballot(myjj >= 0 && myv >= tau);
+  const int tie_quota = a.fixed_k > 0 ? a.sel_m - n_gt : 0x7fffffff;
+  const bool is_eq = myjj >= 0 && myv == tau;
+  const int eq_rank = __popcll(__ballot(is_eq) & ((1ULL << lane) - 1ULL));   // candidates are in ascending target order
+  unsigned long long hit = __ballot(myjj >= 0 && (myv > tau || (is_eq && eq_rank < tie_quota)));
   const int cnt = __popcll(hit);
   const int my_pos = __popcll(hit & ((1ULL << lane) - 1ULL));
   const bool mine = (hit >> lane) & 1ULL;
@@ -675,6 +695,7 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
   // v[f] and v[f+1] = the m-th and (m-1)-th largest of the column, counted with
   // multiplicity: walk the distinct values from the top (at most m of them).
   float vf = NEGF, vf1 = NEGF;
+  int n_gt = 0;                                // values strictly above vf
   {
     int phase = 0, taken = 0;
     float cur = __builtin_huge_valf();
@@ -688,7 +709,7 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
 #pragma unroll
       for (int k = 0; k < MC; ++k) lc += top[k] == nxt ? 1 : 0;
       const int cnt = col_sum(lc, redi, phase, wv, c);
-      if (taken <= m - 1 && m - 1 < taken + cnt) vf = nxt;
+      if (taken <= m - 1 && m - 1 < taken + cnt) { vf = nxt; n_gt = taken; }
       if (m >= 2 && taken <= m - 2 && m - 2 < taken + cnt) vf1 = nxt;
       taken += cnt;
       cur = nxt;
@@ -730,10 +751,27 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
       hit_j[c][y + 1] = jx;
       hit_v[c][y + 1] = vx;
     }
+    int kept = have, total = cnt;
+    if (a.fixed_k > 0) {
+      // fixed K: of the values equal to the threshold only the lowest positions, K targets in all
+      const float tauf = vf;                   // sel_g = 0: the threshold is v[f] itself
+      int quota = a.sel_m - n_gt;
+      kept = 0;
+      for (int x = 0; x < have; ++x) {
+        const bool gt = hit_v[c][x] > tauf;
+        if (gt || quota > 0) {
+          if (!gt) --quota;
+          hit_j[c][kept] = hit_j[c][x];
+          hit_v[c][kept] = hit_v[c][x];
+          ++kept;
+        }
+      }
+      total = cnt > kHitCap ? cnt : kept;      // more hits than the list holds: reported as overflow
+    }
     double denom = 0.0;
-    for (int x = 0; x < have; ++x) denom += (double)hit_v[c][x];
+    for (int x = 0; x < kept; ++x) denom += (double)hit_v[c][x];
     const bool live = denom > 0.0;
-    const int stored = have < a.k_max ? have : a.k_max;
+    const int stored = kept < a.k_max ? kept : a.k_max;
     const int64_t ebase = (b * a.n_disc + row) * a.k_max;
     if (live)
       for (int x = 0; x < stored; ++x) {
@@ -742,8 +780,35 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
         a.edge_alpha[ebase + x] = al;
       }
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
-    if (live && cnt > a.k_max) a.overflow[b] = 1;
+    if (live && total > a.k_max) a.overflow[b] = 1;
   }
+}
+
+// Pairwise token correlation gap: top-1 minus top-2 value of every discarded row, values
+// evaluated exactly (one target per lane at a time), counted with multiplicity.
+__global__ __launch_bounds__(256) void corr_gap_kernel(CorrArgs a) {
+  const int lane = threadIdx.x % kWave;
+  const int row = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (row >= a.n_disc) return;  // whole wavefront leaves together
+  const int n = a.n_keep;
+  const int i = a.S[b * a.n_disc + row];
+  const double NEG = -__builtin_huge_val();
+  double t1 = NEG, t2 = NEG;           // this lane's two largest values
+  if ((unsigned)i < (unsigned)a.N) {
+    for (int jj = lane; jj < n; jj += kWave) {
+      const int j = a.T[b * n + jj];
+      if ((unsigned)j >= (unsigned)a.N) continue;
+      const double c = corr_value(a, b, i, j);
+      if (c > t1) { t2 = t1; t1 = c; }
+      else if (c > t2) t2 = c;
+    }
+  }
+  const double m1 = wave_max(t1);
+  const unsigned long long who = __ballot(t1 == m1);
+  const bool owner = lane == __ffsll(who) - 1;
+  const double m2 = wave_max(owner ? t2 : t1);   // the runner-up: the owner's second value or another lane's best
+  if (lane == 0) a.gap[b * a.n_disc + row] = (n >= 2 && m2 > NEG) ? m1 - m2 : 0.0;
 }
 
 __global__ void zero_i32_kernel(int32_t* p, int n) {
@@ -758,6 +823,11 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   if (!overflow_is_zero)
     hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
   if (pl.n_disc == 0) return;
+  if (pl.fixed_k == 0) {       // pruning / convergent form: no discarded token has a target
+    const int n = p.B * pl.n_disc;
+    hipLaunchKernelGGL(zero_i32_kernel, dim3((n + 255) / 256), dim3(256), 0, s, edge_cnt, n);
+    return;
+  }
   CorrArgs a{};
   a.B = p.B; a.N = p.N; a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.M = p.M; a.k_max = p.k_max; a.Df = pl.Df;
   const bool L = p.variant == FICOCO_VARIANT_L;
@@ -775,6 +845,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.slot_of = (const int32_t*)(ws + pl.slot_of);
   a.ct = (float*)(ws + pl.ct);
   a.cmax = (double*)(ws + pl.cmax);
+  a.fixed_k = pl.fixed_k;
   a.ct_splits = pl.gram_splits;
   a.delta = (float)(pl.Df + 4 * pl.gram_splits) * 2.384185791015625e-07f;   // (Df + 4 splits) * 2^-22
   if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
@@ -804,6 +875,23 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   }
   if (pl.dense_rows) hipLaunchKernelGGL(corr_fill_rows_kernel, grid, block, 0, s, a);
   hipLaunchKernelGGL(corr_rows_kernel, grid, block, 0, s, a);
+}
+
+void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
+                     const int32_t* keep_idx, double* gap, hipStream_t s) {
+  if (pl.n_disc == 0) return;
+  CorrArgs a{};
+  a.B = p.B; a.N = p.N; a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.M = p.M; a.k_max = p.k_max; a.Df = pl.Df;
+  const bool L = p.variant == FICOCO_VARIANT_L;
+  a.mode = p.corr_src == FICOCO_C_ATTN ? (L ? kAttnL : kAttnV) : (L ? kCosL : kCosV);
+  a.abar = (const float*)(ws + pl.abar);
+  a.ttext = (const double*)(ws + pl.ttext);
+  a.xhat = (const bf16_t*)(ws + pl.xhat);
+  a.gamma = (double)p.gamma;
+  a.invM = p.M > 0 ? 1.0 / (double)p.M : 0.0;
+  a.S = discard_idx; a.T = keep_idx;
+  a.gap = gap;
+  hipLaunchKernelGGL(corr_gap_kernel, dim3((pl.n_disc + 3) / 4, p.B), dim3(256), 0, s, a);
 }
 
 }  // namespace ficoco

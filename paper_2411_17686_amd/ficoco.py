@@ -19,10 +19,13 @@ R_ATTN_RECV, R_VECTOR, R_SIM_MEAN = 0, 1, 2
 G_CLS_ATTN, G_TEXT_ATTN, G_VECTOR, G_EQ_TOKEN = 0, 1, 2, 3
 C_ATTN, C_COSINE = 0, 1
 PROBE_REDUCE, PROBE_GRAM = 0, 1
+K_ADAPTIVE, K_FIXED, K_CONVERGENT = 0, 1, 2
+COMPRESS_SELF, COMPRESS_AVERAGE = 0, 1
 
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
-           "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_reduce", "ficoco_score", "ficoco_filter", "ficoco_correlate",
-           "ficoco_compress", "ficoco_v_step", "ficoco_l_step"]
+           "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_out_rows", "ficoco_reduce", "ficoco_score",
+           "ficoco_filter", "ficoco_correlate", "ficoco_correlation_gap", "ficoco_compress", "ficoco_v_step",
+           "ficoco_l_step"]
 
 
 class Problem(C.Structure):
@@ -47,6 +50,7 @@ class Problem(C.Structure):
         ("w_score", C.c_float), ("gamma", C.c_float), ("eps", C.c_float),
         ("red_src", C.c_int32), ("sem_src", C.c_int32), ("corr_src", C.c_int32),
         ("k_max", C.c_int32),
+        ("k_mode", C.c_int32), ("fixed_k", C.c_int32), ("compress_mode", C.c_int32),
     ]
 
 
@@ -70,6 +74,8 @@ def lib():
         L.ficoco_version.restype = C.c_char_p
         L.ficoco_set_probe.argtypes = [vp, C.c_int, vp, vp]
         L.ficoco_workspace_bytes.argtypes = [pp, C.POINTER(C.c_size_t)]
+        L.ficoco_out_rows.argtypes = [pp, C.POINTER(C.c_int32)]
+        L.ficoco_correlation_gap.argtypes = [vp, pp, vp, C.c_size_t, i32p, i32p, f64p, vp]
         L.ficoco_reduce.argtypes = [vp, pp, vp, C.c_size_t, vp]
         L.ficoco_score.argtypes = [vp, pp, vp, C.c_size_t, f64p, vp]
         L.ficoco_filter.argtypes = [vp, pp, vp, C.c_size_t, f64p, i32p, i32p, vp]
@@ -138,7 +144,8 @@ class Context:
 def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_begin=0,
                  cls_index=-1, A_text=None, at_k_begin=None, recv_vec=None, sem_vec=None, F=None,
                  pos=None, grid=(1, 0, 0), window=0, penalty_coef=2.0, w_score=0.35, gamma=0.6,
-                 eps=0.998, red_src=R_ATTN_RECV, sem_src=G_CLS_ATTN, corr_src=C_ATTN, k_max=8, H=None):
+                 eps=0.998, red_src=R_ATTN_RECV, sem_src=G_CLS_ATTN, corr_src=C_ATTN, k_max=8, H=None,
+                 k_mode=K_ADAPTIVE, fixed_k=0, compress_mode=COMPRESS_SELF):
     """Fill a `ficoco_problem` from torch tensors (shapes as in include/ficoco.h).  The
     returned Problem only holds raw pointers: keep the tensors alive while it is used."""
     p = Problem()
@@ -179,6 +186,7 @@ def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_b
     p.window = window
     p.penalty_coef, p.w_score, p.gamma, p.eps = penalty_coef, w_score, gamma, eps
     p.red_src, p.sem_src, p.corr_src, p.k_max = red_src, sem_src, corr_src, k_max
+    p.k_mode, p.fixed_k, p.compress_mode = k_mode, fixed_k, compress_mode
     return p
 
 
@@ -187,6 +195,14 @@ def workspace_bytes(p):
     rc = lib().ficoco_workspace_bytes(C.byref(p), C.byref(n))
     if rc != OK:
         raise FicocoError(rc, "ficoco_workspace_bytes rejected the problem")
+    return n.value
+
+
+def out_rows(p):
+    n = C.c_int32()
+    rc = lib().ficoco_out_rows(C.byref(p), C.byref(n))
+    if rc != OK:
+        raise FicocoError(rc, "ficoco_out_rows rejected the problem")
     return n.value
 
 
@@ -201,7 +217,7 @@ class Buffers:
         off = (-self.ws.data_ptr()) % 256
         self.ws_ptr = self.ws.data_ptr() + off
         i32 = dict(dtype=torch.int32, device=device)
-        self.X_out = torch.empty(B, p.n_tot - n_disc, p.D, dtype=x_dtype, device=device)
+        self.X_out = torch.empty(B, out_rows(p), p.D, dtype=x_dtype, device=device)
         self.pos_out = torch.empty(B, n_keep, **i32)
         self.keep_idx = torch.empty(B, n_keep, **i32)
         self.discard_idx = torch.empty(B, max(n_disc, 1), **i32)[:, :n_disc]
@@ -210,6 +226,7 @@ class Buffers:
         self.edge_alpha = torch.zeros(B, max(n_disc, 1), k, dtype=torch.float64, device=device)[:, :n_disc]
         self.scores = torch.empty(B, N, dtype=torch.float64, device=device)
         self.overflow = torch.zeros(B, **i32)
+        self.gap = torch.zeros(B, max(n_disc, 1), dtype=torch.float64, device=device)[:, :n_disc]
 
 
 def _ws(buf):
@@ -237,6 +254,12 @@ def ficoco_correlate(ctx, p, buf):
     ctx.check(lib().ficoco_correlate(ctx._h, C.byref(p), ws, n, _ptr(buf.discard_idx), _ptr(buf.keep_idx),
                                      _ptr(buf.edge_cnt), _ptr(buf.edge_tgt), _ptr(buf.edge_alpha),
                                      _ptr(buf.overflow), ctx.stream()))
+
+
+def ficoco_correlation_gap(ctx, p, buf):
+    ws, n = _ws(buf)
+    ctx.check(lib().ficoco_correlation_gap(ctx._h, C.byref(p), ws, n, _ptr(buf.discard_idx), _ptr(buf.keep_idx),
+                                           _ptr(buf.gap), ctx.stream()))
 
 
 def ficoco_compress(ctx, p, buf):

@@ -26,11 +26,12 @@ def gpu_outputs(buf):
         keep=buf.keep_idx.cpu().numpy(), discard=buf.discard_idx.cpu().numpy(),
         cnt=buf.edge_cnt.cpu().numpy(), tgt=buf.edge_tgt.cpu().numpy(),
         alpha=buf.edge_alpha.cpu().numpy(), scores=buf.scores.cpu().numpy(),
-        overflow=buf.overflow.cpu().numpy())
+        overflow=buf.overflow.cpu().numpy(), gap=buf.gap.cpu().numpy())
 
 
-def compare_image(g, b, ref, dtype, vis_begin, exact_alpha):
-    """g: gpu_outputs(); ref: oracle result for image b."""
+def compare_image(g, b, ref, dtype, vis_begin, exact_alpha, extra_row=None):
+    """g: gpu_outputs(); ref: oracle result for image b.  extra_row: output row of the
+    additional token of the convergent form (a computed row, not a copy)."""
     S, T = ref["S"], ref["T"]
     assert np.array_equal(g["discard"][b], S), "discarded set differs (image %d)" % b
     assert np.array_equal(g["keep"][b], T), "preserved set differs (image %d)" % b
@@ -62,13 +63,18 @@ def compare_image(g, b, ref, dtype, vis_begin, exact_alpha):
     stored = O.round_to_dtype(want, dtype)
     for r in range(want.shape[0]):
         j = r - vis_begin
+        if r == extra_row:
+            continue
+        if extra_row is not None and r > extra_row:
+            j = -1                                   # tokens behind the visual span
         if not (0 <= j < len(T) and j in touched):
             assert np.array_equal(got[r], stored[r]), "pass-through row %d not bit-exact" % r
     return float(err.max())
 
 
 def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src=fc.G_CLS_ATTN,
-          corr_src=fc.C_ATTN, k_max=8, eps=None, window=None, staged=False, ctx=None, F=None):
+          corr_src=fc.C_ATTN, k_max=8, eps=None, window=None, staged=False, ctx=None, F=None,
+          k_mode=fc.K_ADAPTIVE, fixed_k=0, compress_mode=fc.COMPRESS_SELF, gap=False):
     """One FiCoCo-V step on the GPU for a synth config dict.  Returns (gpu_outputs, buffers)."""
     ctx = ctx or fc.Context(0)
     X = cfg["X"] if X is None else X
@@ -82,7 +88,8 @@ def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src
         n_keep=cfg["n_keep"] if n_keep is None else n_keep, A=Ad, cls_index=cfg["cls_index"],
         recv_vec=rv, sem_vec=sv, F=Fd, pos=posd, grid=cfg["grid"], window=cfg["window"] if window is None else window,
         penalty_coef=cfg["coef"], w_score=cfg["lam"], eps=cfg["eps"] if eps is None else eps,
-        red_src=red_src, sem_src=sem_src, corr_src=corr_src, k_max=k_max, H=cfg["H"])
+        red_src=red_src, sem_src=sem_src, corr_src=corr_src, k_max=k_max, H=cfg["H"],
+        k_mode=k_mode, fixed_k=fixed_k, compress_mode=compress_mode)
     keep_alive = (Xd, Ad, posd, rv, sv, Fd)   # the problem holds raw pointers only
     buf = fc.Buffers(p, "cuda", Xd.dtype)
     if staged:
@@ -92,6 +99,8 @@ def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src
         fc.ficoco_compress(ctx, p, buf)
     else:
         fc.ficoco_v_step(ctx, p, buf)
+    if gap:
+        fc.ficoco_correlation_gap(ctx, p, buf)
     out = gpu_outputs(buf)
     del keep_alive
     return out, buf
@@ -100,10 +109,12 @@ def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src
 _SRC = {fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}
 _SEM = {fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector", fc.G_EQ_TOKEN: "eq_token"}
 _COR = {fc.C_ATTN: "attn", fc.C_COSINE: "cosine"}
+_KM = {fc.K_ADAPTIVE: "adaptive", fc.K_FIXED: "fixed", fc.K_CONVERGENT: "convergent"}
 
 
 def oracle_v(cfg, A, b, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV,
-             sem_src=fc.G_CLS_ATTN, corr_src=fc.C_ATTN, eps=None, window=None, F=None):
+             sem_src=fc.G_CLS_ATTN, corr_src=fc.C_ATTN, eps=None, window=None, F=None,
+             k_mode=fc.K_ADAPTIVE, fixed_k=0, compress_mode=fc.COMPRESS_SELF):
     X = cfg["X"] if X is None else X
     Xb = O.widen(to_numpy(X[b]))
     N = Xb.shape[0] - cfg["vis_begin"]
@@ -116,10 +127,12 @@ def oracle_v(cfg, A, b, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV,
         recv_vec=O.widen(to_numpy(cfg["recv_vec"][b])) if red_src == fc.R_VECTOR else None,
         sem_vec=O.widen(to_numpy(cfg["sem_vec"][b])) if sem_src == fc.G_VECTOR else None,
         F=None if F is None else O.widen(to_numpy(F[b])),
-        red_src=_SRC[red_src], sem_src=_SEM[sem_src], corr_src=_COR[corr_src])
+        red_src=_SRC[red_src], sem_src=_SEM[sem_src], corr_src=_COR[corr_src],
+        k_mode=_KM[k_mode], fixed_k=fixed_k, average=compress_mode == fc.COMPRESS_AVERAGE)
 
 
-def run_l(cfg, red_src, corr_src, k_max=8, ctx=None, staged=False, eps=None):
+def run_l(cfg, red_src, corr_src, k_max=8, ctx=None, staged=False, eps=None,
+          k_mode=fc.K_ADAPTIVE, fixed_k=0, compress_mode=fc.COMPRESS_SELF, gap=False):
     ctx = ctx or fc.Context(0)
     Xd, Atv, Avv = dev(cfg["X"]), dev(cfg["A_tv"]), dev(cfg["A_vv"])
     use_vv = red_src == fc.R_ATTN_RECV or corr_src == fc.C_ATTN
@@ -128,7 +141,7 @@ def run_l(cfg, red_src, corr_src, k_max=8, ctx=None, staged=False, eps=None):
         A=Avv if use_vv else None, a_q_begin=cfg["vis_begin"], a_k_begin=cfg["vis_begin"],
         A_text=Atv, at_k_begin=cfg["vis_begin"], w_score=cfg["beta"], gamma=cfg["gamma"],
         eps=cfg["eps"] if eps is None else eps, red_src=red_src, sem_src=fc.G_TEXT_ATTN,
-        corr_src=corr_src, k_max=k_max, window=0)
+        corr_src=corr_src, k_max=k_max, window=0, k_mode=k_mode, fixed_k=fixed_k, compress_mode=compress_mode)
     buf = fc.Buffers(p, "cuda", Xd.dtype)
     if staged:
         fc.ficoco_score(ctx, p, buf)
@@ -137,16 +150,20 @@ def run_l(cfg, red_src, corr_src, k_max=8, ctx=None, staged=False, eps=None):
         fc.ficoco_compress(ctx, p, buf)
     else:
         fc.ficoco_l_step(ctx, p, buf)
+    if gap:
+        fc.ficoco_correlation_gap(ctx, p, buf)
     out = gpu_outputs(buf)
     del Xd, Atv, Avv
     return out, buf
 
 
-def oracle_l(cfg, b, red_src, corr_src, eps=None):
+def oracle_l(cfg, b, red_src, corr_src, eps=None, k_mode=fc.K_ADAPTIVE, fixed_k=0,
+             compress_mode=fc.COMPRESS_SELF):
     return O.l_step(
         O.widen(to_numpy(cfg["X"][b])),
         None if cfg["A_vv"] is None or not (red_src == fc.R_ATTN_RECV or corr_src == fc.C_ATTN)
         else O.widen(to_numpy(cfg["A_vv"][b])),
         O.widen(to_numpy(cfg["A_tv"][b])), vis_begin=cfg["vis_begin"], N=cfg["N"],
         n_keep=cfg["n_keep"], beta=cfg["beta"], gamma=cfg["gamma"],
-        eps=cfg["eps"] if eps is None else eps, red_src=_SRC[red_src], corr_src=_COR[corr_src])
+        eps=cfg["eps"] if eps is None else eps, red_src=_SRC[red_src], corr_src=_COR[corr_src],
+        k_mode=_KM[k_mode], fixed_k=fixed_k, average=compress_mode == fc.COMPRESS_AVERAGE)

@@ -176,6 +176,8 @@ def cpu_baseline(W, seconds=12.0):
     sv = [host("sem_vec", b) for b in range(n_img)]
     red = {fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}[kw.get("red_src", fc.R_ATTN_RECV)]
     cor = {fc.C_ATTN: "attn", fc.C_COSINE: "cosine"}[kw.get("corr_src", fc.C_ATTN)]
+    okw = dict(k_mode={fc.K_ADAPTIVE: "adaptive", fc.K_FIXED: "fixed", fc.K_CONVERGENT: "convergent"}[kw.get("k_mode", 0)],
+               fixed_k=kw.get("fixed_k", 0), average=kw.get("compress_mode", 0) == fc.COMPRESS_AVERAGE)
     t0 = time.perf_counter()
     reps = 0
     while True:
@@ -184,10 +186,10 @@ def cpu_baseline(W, seconds=12.0):
                 sem = {fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector"}[kw.get("sem_src", fc.G_CLS_ATTN)]
                 O.v_step(X[b], A[b], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"], N=kw["N"],
                          n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2, coef=2.0,
-                         recv_vec=rv[b], sem_vec=sv[b], red_src=red, sem_src=sem, corr_src=cor)
+                         recv_vec=rv[b], sem_vec=sv[b], red_src=red, sem_src=sem, corr_src=cor, **okw)
             else:
                 O.l_step(X[b], A[b], At[b], vis_begin=kw["vis_begin"], N=kw["N"], n_keep=kw["n_keep"],
-                         beta=kw["w_score"], gamma=kw["gamma"], eps=kw["eps"], red_src=red, corr_src=cor)
+                         beta=kw["w_score"], gamma=kw["gamma"], eps=kw["eps"], red_src=red, corr_src=cor, **okw)
         reps += 1
         el = time.perf_counter() - t0
         if el > seconds:
@@ -207,6 +209,10 @@ def main():
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
     ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 2, 3, 3p, 4")
+    ap.add_argument("--ablation", default="none",
+                    choices=["none", "fixed0", "fixed1", "fixed2", "convergent", "average"],
+                    help="time one of the paper's ablation variants of the correlate / compress stages instead of "
+                         "the method itself (not the headline figure)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run five plain 1 GiB device-to-device copies (a kernel of known traffic "
@@ -226,6 +232,12 @@ def main():
     torch.cuda.set_device(dev)
     ctx = fc.Context(0)
     W = make_workload(torch, fc, args.config, dev)
+    abl = {"none": {}, "fixed0": dict(k_mode=fc.K_FIXED, fixed_k=0), "fixed1": dict(k_mode=fc.K_FIXED, fixed_k=1),
+           "fixed2": dict(k_mode=fc.K_FIXED, fixed_k=2), "convergent": dict(k_mode=fc.K_CONVERGENT),
+           "average": dict(compress_mode=fc.COMPRESS_AVERAGE)}[args.ablation]
+    W["kw"].update(abl)
+    if abl:
+        W["label"] += ", ablation variant %s" % args.ablation
     n_sets = len(W["sets"])
     probs = [fc.make_problem(st["X"], variant=W["variant"], A=st.get("A"), A_text=st.get("A_text"),
                              recv_vec=st.get("recv_vec"), sem_vec=st.get("sem_vec"), H=W["H"], **W["kw"])

@@ -546,18 +546,19 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
 }
 
 // The additional token of the "convergent" ablation: the plain mean of the discarded tokens.
-// A workgroup covers 512 features of one image; each of its four wavefronts adds a quarter of
-// the discarded rows in ascending order (16-byte loads of 8 rows in flight), the quarters are
+// A workgroup covers 512 features of one image; each of its kExtraWaves wavefronts adds one part
+// of the discarded rows in ascending order (16-byte loads of 8 rows in flight), the parts are
 // added in order and the sum is divided by N^S.
+constexpr int kExtraWaves = 16;
 template <typename T>
-__global__ __launch_bounds__(256) void extra_token_kernel(MergeArgs a) {
-  __shared__ double part[3][kVec][kWave];
+__global__ __launch_bounds__(kExtraWaves * kWave) void extra_token_kernel(MergeArgs a) {
+  __shared__ double part[kExtraWaves - 1][kVec][kWave];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int d = (blockIdx.x * kWave + lane) * kVec;
   const int64_t b = blockIdx.y;
   const int nd = max(min(kVec, a.D - d), 0);
-  const int quarter = (a.n_disc + 3) / 4;
-  const int r0 = min(wv * quarter, a.n_disc), r1 = min(r0 + quarter, a.n_disc);
+  const int share = (a.n_disc + kExtraWaves - 1) / kExtraWaves;
+  const int r0 = min(wv * share, a.n_disc), r1 = min(r0 + share, a.n_disc);
   const T* Xb = (const T*)a.X + b * a.xsb + d;
   double acc[kVec];
 #pragma unroll
@@ -587,8 +588,7 @@ __global__ __launch_bounds__(256) void extra_token_kernel(MergeArgs a) {
   }
   __syncthreads();
   if (wv > 0 || nd == 0) return;
-#pragma unroll
-  for (int w = 0; w < 3; ++w)
+  for (int w = 0; w < kExtraWaves - 1; ++w)
 #pragma unroll
     for (int k = 0; k < kVec; ++k) acc[k] += part[w][k][lane];
   T* out = (T*)a.X_out + (b * a.n_out + a.extra_row) * (int64_t)a.D + d;
@@ -670,8 +670,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   }
   if (m.extra_row >= 0) {
     dim3 grid((p.D + kWave * kVec - 1) / (kWave * kVec), p.B);
-    if (p.dtype == FICOCO_BF16) hipLaunchKernelGGL(extra_token_kernel<bf16_t>, grid, dim3(256), 0, s, m);
-    else hipLaunchKernelGGL(extra_token_kernel<float>, grid, dim3(256), 0, s, m);
+    if (p.dtype == FICOCO_BF16) hipLaunchKernelGGL(extra_token_kernel<bf16_t>, grid, dim3(kExtraWaves * kWave), 0, s, m);
+    else hipLaunchKernelGGL(extra_token_kernel<float>, grid, dim3(kExtraWaves * kWave), 0, s, m);
   }
 }
 

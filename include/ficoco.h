@@ -174,6 +174,40 @@ int ficoco_set_probe(ficoco_ctx *ctx, int kernel, void *start_event, void *stop_
  * functions must be called in order, on one stream, with the same problem and workspace. */
 int ficoco_workspace_bytes(const ficoco_problem *p, size_t *out_bytes);
 
+/*
+ * Reduction schedule from the appendix "Theoretical FLOPs Calculation" (host arithmetic only,
+ * no GPU): how many visual tokens to discard in every layer so that the model's transformer
+ * layers stay within a FLOPs budget.
+ *
+ * Cost model of one layer over n visual tokens (hidden size D, feed-forward size F):
+ *   FiCoCo-V: 4 n D^2 + 2 n^2 D + 2 n D F              (the vision encoder sees the visual tokens)
+ *   FiCoCo-L: the same with p = n + M in place of n     (the decoder also sees M text tokens)
+ * plus, in a layer that reduces from n to n' = n - s tokens, the method's own work
+ *   V:  n^2 + 2n + s (n' + 2D + 1) + D        L:  2 (n^2 + 2n) + s (n' + 2D + 1) + D.
+ * A reducing layer is charged with n' tokens (the appendix's "after" expression).  Layers
+ * before start_layer keep all N tokens; from start_layer on every layer discards the same
+ * count s (Sec. "Implementation Details": reduction starts at the 12th encoder / 4th decoder
+ * layer, a fixed number of tokens per layer) but never goes below min_keep tokens.  The result
+ * is the smallest s whose total cost is within the budget.
+ *   n_discard [layers] int32, out: tokens discarded in each layer (host memory).
+ *   total_flops          out: cost of the returned schedule (may be NULL).
+ * Returns FICOCO_OK, FICOCO_EINVAL for bad arguments, FICOCO_EUNSUPPORTED when even the
+ * strongest schedule (every layer from start_layer on drops to min_keep) exceeds the budget;
+ * that schedule is then the one returned.
+ */
+typedef struct {
+  int32_t variant;     /* ficoco_variant                                            */
+  int32_t layers;      /* transformer layers of the model part that is scheduled    */
+  int32_t start_layer; /* first layer that reduces, 0-based (the paper: 11 for V, 3 for L) */
+  int32_t N;           /* visual tokens entering the first layer                     */
+  int32_t M;           /* text tokens (FiCoCo-L), else 0                            */
+  int32_t D;           /* hidden size                                               */
+  int32_t F;           /* feed-forward size (the appendix calls it H)               */
+  int32_t min_keep;    /* lower bound of visual tokens after any layer (>= 1)        */
+  double budget_flops; /* budget for the sum over the layers                         */
+} ficoco_schedule_problem;
+int ficoco_schedule(const ficoco_schedule_problem *p, int32_t *n_discard, double *total_flops);
+
 /* Rows per sequence of X_out for this problem: n_tot - N^S, plus one for the additional
  * token of FICOCO_K_CONVERGENT when N^S > 0.  Host arithmetic only. */
 int ficoco_out_rows(const ficoco_problem *p, int32_t *out_rows);

@@ -51,6 +51,15 @@ Readings (where the paper is silent, ambiguous or garbled):
       counted with multiplicity (a tie at the top gives 0); a row with fewer than two
       preserved tokens has gap 0.
 
+  R15 schedule utility (appendix "Theoretical FLOPs Calculation", Sec. "Implementation
+      Details"): a layer over n visual tokens costs 4 p D^2 + 2 p^2 D + 2 p D F with p = n (V)
+      or n + M (L); a reducing layer is charged with its tokens AFTER the reduction plus the
+      method's own work; every layer from the start layer on discards the same count, never
+      below a minimum; the schedule is the smallest such count within the budget.  The
+      appendix's printed differences (Delta) do not equal before - after as printed (the
+      vision form lacks a factor 2 on N N^S, the decoder form drops M); the before / after
+      expressions are followed.
+
 All decisions (window maxima, the top-K filter, the threshold test) are taken on float64
 values; scalar hyper-parameters cross the library boundary as float32 and are widened
 from that value here too.
@@ -495,3 +504,48 @@ def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.99
         raise ValueError(corr_src)
     C_of = lambda S, T: correlation_l(direct(S, T), text_bridge(Pt, S, T), gamma)
     return _finish(X, vis_begin, s, n_keep, C_of, eps, None, k_mode, fixed_k, average)
+
+
+# --------------------------------------------------------------------------- FLOPs model (reading R15)
+def layer_flops(tokens, D, F):
+    """Appendix "Theoretical FLOPs Calculation": one transformer layer over `tokens` tokens."""
+    t = float(tokens)
+    return 4.0 * t * D * D + 2.0 * t * t * D + 2.0 * t * D * F
+
+
+def step_flops(variant, n, s, D):
+    """The method's own work in a layer that reduces n visual tokens by s (same appendix)."""
+    n, s = float(n), float(s)
+    first = n * n + 2.0 * n
+    if variant == "L":
+        first = 2.0 * first
+    return first + s * ((n - s) + 2.0 * D + 1.0) + D
+
+
+def schedule_cost(variant, layers, start_layer, N, M, D, F, min_keep, s):
+    """Total cost and per-layer discard counts when every layer from start_layer on discards s."""
+    n = N
+    total = 0.0
+    drops = []
+    for l in range(layers):
+        drop = 0
+        if l >= start_layer:
+            drop = s if n - s >= min_keep else n - min_keep
+            drop = max(drop, 0)
+        if drop > 0:
+            total += step_flops(variant, n, drop, D)
+        n -= drop
+        total += layer_flops(n + (M if variant == "L" else 0), D, F)
+        drops.append(drop)
+    return total, drops
+
+
+def schedule_uniform(variant, layers, start_layer, N, M, D, F, min_keep, budget):
+    """Smallest uniform per-layer discard count within the budget (counts tried in ascending
+    order).  Returns (reachable, drops, total)."""
+    for s in range(0, N - min_keep + 1):
+        total, drops = schedule_cost(variant, layers, start_layer, N, M, D, F, min_keep, s)
+        if total <= budget:
+            return True, drops, total
+    total, drops = schedule_cost(variant, layers, start_layer, N, M, D, F, min_keep, N - min_keep)
+    return False, drops, total

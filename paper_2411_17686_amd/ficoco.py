@@ -25,7 +25,7 @@ COMPRESS_SELF, COMPRESS_AVERAGE = 0, 1
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
            "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_out_rows", "ficoco_reduce", "ficoco_score",
            "ficoco_filter", "ficoco_correlate", "ficoco_correlation_gap", "ficoco_compress", "ficoco_v_step",
-           "ficoco_l_step"]
+           "ficoco_l_step", "ficoco_schedule"]
 
 
 class Problem(C.Structure):
@@ -52,6 +52,13 @@ class Problem(C.Structure):
         ("k_max", C.c_int32),
         ("k_mode", C.c_int32), ("fixed_k", C.c_int32), ("compress_mode", C.c_int32),
     ]
+
+
+class ScheduleProblem(C.Structure):
+    """Mirror of `ficoco_schedule_problem`."""
+    _fields_ = [("variant", C.c_int32), ("layers", C.c_int32), ("start_layer", C.c_int32),
+                ("N", C.c_int32), ("M", C.c_int32), ("D", C.c_int32), ("F", C.c_int32),
+                ("min_keep", C.c_int32), ("budget_flops", C.c_double)]
 
 
 _lib = None
@@ -84,6 +91,7 @@ def lib():
         step = [vp, pp, vp, C.c_size_t, vp, i32p, i32p, i32p, i32p, i32p, f64p, f64p, i32p, vp]
         L.ficoco_v_step.argtypes = step
         L.ficoco_l_step.argtypes = step
+        L.ficoco_schedule.argtypes = [C.POINTER(ScheduleProblem), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         for name in EXPORTS:
             getattr(L, name)            # fail loudly here if the build lacks a symbol
         _lib = L
@@ -282,3 +290,15 @@ def ficoco_v_step(ctx, p, buf):
 
 def ficoco_l_step(ctx, p, buf):
     _step(lib().ficoco_l_step, ctx, p, buf)
+
+
+def ficoco_schedule(variant, layers, start_layer, N, M, D, F, min_keep, budget_flops):
+    """Per-layer discard counts within a FLOPs budget (host arithmetic; see ficoco_schedule).
+    Returns (status, [n_discard per layer], total_flops); status is OK or EUNSUPPORTED."""
+    sp = ScheduleProblem(variant, layers, start_layer, N, M, D, F, min_keep, budget_flops)
+    out = (C.c_int32 * max(layers, 1))()
+    total = C.c_double()
+    rc = lib().ficoco_schedule(C.byref(sp), out, C.byref(total))
+    if rc not in (OK, EUNSUPPORTED):
+        raise FicocoError(rc, "ficoco_schedule rejected the arguments")
+    return rc, list(out)[:layers], total.value

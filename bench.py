@@ -93,8 +93,10 @@ def make_workload(torch, fc, name, dev):
                  gram_flops=2.0 * B * (N - keep) * keep * D,
                  step_bytes=B * H * (N + 1) * (N + 1) * es + B * N * N * 4 + B * (N + 1) * D * es
                  + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name != "1c" else None)
-    elif name in ("3", "3p"):
+    elif name in ("3", "3p", "3b", "3bp"):
         B, n_sys, N, M, D, H, keep = 8, 35, 576, 64, 4096, 32, 144
+        if name in ("3b", "3bp"):                # the 13B decoder shape with a long instruction
+            M, D, H = 512, 5120, 40
         n_tot = n_sys + N + M
         g.manual_seed(3)
         sets = []
@@ -105,20 +107,22 @@ def make_workload(torch, fc, name, dev):
             X[:, n_sys:n_sys + N] = _clustered(torch, g, dev, B, N, D, 96)
             A_tv = _softmax_map(torch, g, dev, B, H, M, n_tot, 1.0, bf, cols=(n_sys, n_sys + N))
             st = dict(X=X.to(bf).contiguous(), A_text=A_tv)
-            if name == "3p":
+            if name in ("3p", "3bp"):
                 st["A"] = _softmax_map(torch, g, dev, B, H, N, n_sys + N, 1.0, bf, mask=mask, cols=(n_sys, n_sys + N))
             sets.append(st)
-        W.update(label="BASELINE config 3%s: FiCoCo-L fused step, B=8, 35 system + 576 visual + 64 text tokens, "
-                       "D=4096, H=32, bf16, keep 144%s"
-                       % ("'" if name == "3p" else "", " (with the causal visual->visual map)" if name == "3p"
+        with_vv = name in ("3p", "3bp")
+        W.update(label="%s%s: FiCoCo-L fused step, B=8, 35 system + 576 visual + %d text tokens, "
+                       "D=%d, H=%d, bf16, keep 144%s"
+                       % ("BASELINE config 3" if M == 64 else "13B decoder shape", "'" if with_vv else "", M, D, H,
+                          " (with the causal visual->visual map)" if with_vv
                           else " (no visual->visual map: mean-cosine + cosine correlation)"),
                  B=B, N=N, D=D, H=H, keep=keep, dtype="bf16", variant=fc.VARIANT_L, sets=sets,
                  kw=dict(vis_begin=n_sys, N=N, n_keep=keep, a_q_begin=n_sys, a_k_begin=n_sys, at_k_begin=n_sys,
                          w_score=0.6, gamma=0.6, eps=0.998, k_max=8, window=0, sem_src=fc.G_TEXT_ATTN,
-                         red_src=fc.R_ATTN_RECV if name == "3p" else fc.R_SIM_MEAN,
-                         corr_src=fc.C_ATTN if name == "3p" else fc.C_COSINE),
-                 dominant="reduce" if name == "3p" else "gram",
-                 reduce_bytes=B * H * N * N * 2 + B * N * N * 4,
+                         red_src=fc.R_ATTN_RECV if with_vv else fc.R_SIM_MEAN,
+                         corr_src=fc.C_ATTN if with_vv else fc.C_COSINE),
+                 dominant="reduce" if with_vv else "gram",
+                 reduce_bytes=B * H * N * N * 2 + B * N * N * 4 + B * H * M * N * 2,
                  gram_flops=2.0 * B * (N - keep) * keep * D, step_bytes=None)
     elif name == "4":
         B, frames, D, H, keep = 1, 16, 1024, 16, 1152
@@ -208,7 +212,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 2, 3, 3p, 4")
+    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 2, 3, 3p, 4; 3b / 3bp: the 13B decoder shape")
     ap.add_argument("--ablation", default="none",
                     choices=["none", "fixed0", "fixed1", "fixed2", "convergent", "average"],
                     help="time one of the paper's ablation variants of the correlate / compress stages instead of "

@@ -283,6 +283,22 @@ int ficoco_compress(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t w
                     int32_t *pos_out, void *stream);
 
 /*
+ * Apply a step's selection to another per-token tensor of the same sequences -- in a decoder
+ * the key / value cache of the layers already computed and the position ids have to lose the
+ * rows of the discarded visual tokens too (Algorithm 2 removes them from the sequence the
+ * following layers see).  out[b][r] = in[b][src(r)] byte for byte, where src(r) walks the
+ * sequence in order and skips the discarded tokens: r below vis_begin, then
+ * vis_begin + keep_idx[b][r - vis_begin], then r + N^S behind the visual span.
+ *   in   [B][n_tot][row_bytes] device, strides in BYTES (row contiguous); row_bytes % 4 == 0.
+ *   out  [B][n_tot - N^S][row_bytes] device, dense.
+ * Not defined for FICOCO_K_CONVERGENT (its additional token has no row in such tensors):
+ * FICOCO_EUNSUPPORTED.  Needs no workspace.
+ */
+int ficoco_gather_tokens(ficoco_ctx *ctx, const ficoco_problem *p, const int32_t *keep_idx, const void *in,
+                         int64_t in_stride_b, int64_t in_stride_n, int32_t row_bytes, void *out,
+                         void *stream);
+
+/*
  * Algorithm 1 (FiCoCo-V) / Algorithm 2 (FiCoCo-L) as one call: the four stages above on
  * one stream and one workspace without host synchronisation.  Every output of the stage
  * functions is produced (scores, index sets, edge lists, overflow flags, X_out, pos_out);

@@ -506,6 +506,16 @@ def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.99
     return _finish(X, vis_begin, s, n_keep, C_of, eps, None, k_mode, fixed_k, average)
 
 
+def gather_tokens(t, vis_begin, N, T):
+    """Rows of another per-token tensor of the sequence (key / value cache, position ids) that
+    remain after the step: the sequence in order without the discarded visual tokens
+    (Algorithm 2 removes them from what the following layers see)."""
+    t = np.asarray(t)
+    keep = set(vis_begin + int(j) for j in T)
+    rows = [r for r in range(t.shape[0]) if not (vis_begin <= r < vis_begin + N) or r in keep]
+    return t[rows]
+
+
 # --------------------------------------------------------------------------- FLOPs model (reading R15)
 def layer_flops(tokens, D, F):
     """Appendix "Theoretical FLOPs Calculation": one transformer layer over `tokens` tokens."""

@@ -373,6 +373,24 @@ int ficoco_correlation_gap(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, s
   return finish(ctx, "ficoco_correlation_gap");
 }
 
+int ficoco_gather_tokens(ficoco_ctx* ctx, const ficoco_problem* p, const int32_t* keep_idx, const void* in,
+                         int64_t in_stride_b, int64_t in_stride_n, int32_t row_bytes, void* out, void* stream) {
+  if (!ctx) return FICOCO_EINVAL;
+  if (!p) return fail(ctx, FICOCO_EINVAL, "ficoco_gather_tokens", "problem is NULL");
+  Plan pl;
+  const char* why;
+  const int rc = make_plan(*p, pl, &why);
+  if (rc != FICOCO_OK) return fail(ctx, rc, "ficoco_gather_tokens", why);
+  if (pl.extra_token)
+    return fail(ctx, FICOCO_EUNSUPPORTED, "ficoco_gather_tokens", "the convergent form's additional token has no row to gather");
+  if (!keep_idx || !in || !out) return fail(ctx, FICOCO_EINVAL, "ficoco_gather_tokens", "a pointer is NULL");
+  if (row_bytes < 4 || row_bytes % 4 != 0 || in_stride_n < row_bytes || in_stride_n % 4 != 0 || in_stride_b % 4 != 0 ||
+      ((uintptr_t)in % 4) != 0 || ((uintptr_t)out % 4) != 0)
+    return fail(ctx, FICOCO_EINVAL, "ficoco_gather_tokens", "row_bytes / strides / pointers must be multiples of 4 bytes");
+  launch_gather(*p, pl, keep_idx, in, in_stride_b, in_stride_n, row_bytes, out, (hipStream_t)stream);
+  return finish(ctx, "ficoco_gather_tokens");
+}
+
 int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes,
                     const int32_t* discard_idx, const int32_t* keep_idx, const int32_t* edge_cnt,
                     const int32_t* edge_tgt, const double* edge_alpha, void* X_out, int32_t* pos_out,

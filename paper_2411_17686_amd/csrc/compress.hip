@@ -675,6 +675,45 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   }
 }
 
+// Row gather by the preserved sequence (key / value cache, position ids): one wavefront per
+// (output row, span of 64 vectors), bytes copied unchanged.
+struct GatherArgs {
+  const char* in;
+  int64_t sb, sn;
+  char* out;
+  int row_bytes, n_out, vis_begin, n_keep, n_disc, N;
+  const int32_t* T;
+};
+
+template <typename V>
+__global__ __launch_bounds__(256) void gather_rows_kernel(GatherArgs a) {
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int per_row = (a.row_bytes + (int)sizeof(V) * kWave - 1) / ((int)sizeof(V) * kWave);
+  const int unit = blockIdx.x * 4 + wv;
+  const int r = unit / per_row;
+  const int off = ((unit % per_row) * kWave + lane) * (int)sizeof(V);
+  const int64_t b = blockIdx.y;
+  if (r >= a.n_out || off >= a.row_bytes) return;
+  int t;
+  if (r < a.vis_begin) t = r;
+  else if (r < a.vis_begin + a.n_keep) t = a.vis_begin + min(max(a.T[b * a.n_keep + r - a.vis_begin], 0), a.N - 1);
+  else t = r + a.n_disc;
+  const V v = *reinterpret_cast<const V*>(a.in + b * a.sb + (int64_t)t * a.sn + off);
+  *reinterpret_cast<V*>(a.out + (b * a.n_out + r) * (int64_t)a.row_bytes + off) = v;
+}
+
+void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_idx, const void* in,
+                   int64_t sb, int64_t sn, int row_bytes, void* out, hipStream_t s) {
+  GatherArgs a{(const char*)in, sb, sn, (char*)out, row_bytes, pl.n_out, p.vis_begin, p.n_keep, pl.n_disc, p.N, keep_idx};
+  const bool wide = row_bytes % 16 == 0 && sb % 16 == 0 && sn % 16 == 0 && ((uintptr_t)in % 16) == 0 &&
+                    ((uintptr_t)out % 16) == 0;
+  const int vec = wide ? 16 : 4;
+  const int per_row = (row_bytes + vec * kWave - 1) / (vec * kWave);
+  dim3 grid((pl.n_out * per_row + 3) / 4, p.B), block(256);
+  if (wide) hipLaunchKernelGGL(gather_rows_kernel<uint4>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(gather_rows_kernel<uint32_t>, grid, block, 0, s, a);
+}
+
 }  // namespace ficoco
 
 FICOCO_DBG_READER(merge)

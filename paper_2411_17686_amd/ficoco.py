@@ -25,7 +25,7 @@ COMPRESS_SELF, COMPRESS_AVERAGE = 0, 1
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
            "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_out_rows", "ficoco_reduce", "ficoco_score",
            "ficoco_filter", "ficoco_correlate", "ficoco_correlation_gap", "ficoco_compress", "ficoco_v_step",
-           "ficoco_l_step", "ficoco_schedule"]
+           "ficoco_l_step", "ficoco_schedule", "ficoco_gather_tokens"]
 
 
 class Problem(C.Structure):
@@ -91,6 +91,7 @@ def lib():
         step = [vp, pp, vp, C.c_size_t, vp, i32p, i32p, i32p, i32p, i32p, f64p, f64p, i32p, vp]
         L.ficoco_v_step.argtypes = step
         L.ficoco_l_step.argtypes = step
+        L.ficoco_gather_tokens.argtypes = [vp, pp, i32p, vp, C.c_int64, C.c_int64, C.c_int32, vp, vp]
         L.ficoco_schedule.argtypes = [C.POINTER(ScheduleProblem), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         for name in EXPORTS:
             getattr(L, name)            # fail loudly here if the build lacks a symbol
@@ -275,6 +276,19 @@ def ficoco_compress(ctx, p, buf):
     ctx.check(lib().ficoco_compress(ctx._h, C.byref(p), ws, n, _ptr(buf.discard_idx), _ptr(buf.keep_idx),
                                     _ptr(buf.edge_cnt), _ptr(buf.edge_tgt), _ptr(buf.edge_alpha),
                                     _ptr(buf.X_out), _ptr(buf.pos_out), ctx.stream()))
+
+
+def ficoco_gather_tokens(ctx, p, buf, t, out=None):
+    """Rows of `t` [B][n_tot][...] (last axes contiguous) that survive the step in `buf`."""
+    B, n_tot = t.shape[0], t.shape[1]
+    row_bytes = t[0, 0].numel() * t.element_size()
+    assert t[0, 0].is_contiguous() and B == p.B and n_tot == p.n_tot
+    if out is None:
+        out = torch.empty((B, out_rows(p)) + tuple(t.shape[2:]), dtype=t.dtype, device=t.device)
+    ctx.check(lib().ficoco_gather_tokens(ctx._h, C.byref(p), _ptr(buf.keep_idx), _ptr(t),
+                                         t.stride(0) * t.element_size(), t.stride(1) * t.element_size(),
+                                         row_bytes, _ptr(out), ctx.stream()))
+    return out
 
 
 def _step(fn, ctx, p, buf):

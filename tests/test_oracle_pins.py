@@ -592,3 +592,12 @@ def test_v_step_ablations_against_brute_force(seed):
     if mode == "fixed0":                     # pruning: the preserved tokens are untouched
         keep_rows = [0] + [1 + j for j in T]
         assert np.array_equal(res["X_out"], X[keep_rows])
+
+
+def test_gather_tokens_layout():
+    t = np.arange(9 * 2).reshape(9, 2)       # 2 leading + 5 visual + 2 trailing tokens
+    out = O.gather_tokens(t, 2, 5, np.array([1, 2, 4]))
+    assert out[:, 0].tolist() == [0, 2, 6, 8, 12, 14, 16]     # rows 0 1 | 3 4 6 | 7 8
+    assert O.gather_tokens(t, 2, 5, np.arange(5)).shape == (9, 2)
+    ids = np.arange(9)
+    assert O.gather_tokens(ids, 0, 9, np.array([0, 8])).tolist() == [0, 8]

@@ -1,14 +1,14 @@
 // Attention-map reduction: the one pass over the [B,H,Nq,Nk] maps.
 //
-// For every query row that carries a role (visual query, [CLS] query, text query) the
-// head mean  Pbar[q][k] = (1/H) sum_h P[h][q][k]  is formed in double precision, heads added
-// in order (so the value does not depend on the launch shape), and consumed three ways:
+// For every query row that carries a role the head mean  Pbar[q][k] = (1/H) sum_h P[h][q][k]
+// is formed in double precision, heads added in order (so the value does not depend on the
+// launch shape), and consumed three ways:
 //   visual query : added into the per-column "received attention" partial of this row chunk
 //                  (first term of Eq. 1 / Eq. 3) and stored in single precision as the map
 //                  the correlate stage gathers from (Algorithm 1, stage 2);
 //   [CLS] query  : stored as the semantic term of Eq. 1;
 //   text query   : stored transposed as the token's text-attention profile (task term of
-//                  Eq. 3 and indirect term of Eq. 4).
+//                  Eq. 3 and indirect term of Eq. 4) -- by text_reduce_kernel below.
 // HBM-bound: each lane streams 8 consecutive key columns of one row for all heads with
 // 16-byte loads; rows of a dense map with an odd length are only element aligned, the
 // hardware's unaligned dwordx4 access is relied on for those.
@@ -26,9 +26,6 @@ constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
 #ifndef FICOCO_REDUCE_LDS_MIN
 #define FICOCO_REDUCE_LDS_MIN 0
 #endif
-#ifndef FICOCO_DBG_ABAR
-#define FICOCO_DBG_ABAR
-#endif
 
 struct AttnArgs {
   const void* A;
@@ -39,7 +36,7 @@ struct AttnArgs {
   int N;
   int vis_r0, n_vis;  // rows of the visual queries (n_vis = 0: none)
   int cls_r;          // row of the [CLS] query or -1
-  int txt_r0, M;      // rows of the text queries (M = 0: none)
+  int M;              // text queries (text block only)
   float* abar;
   double* recv_part;
   double* cls;
@@ -75,8 +72,7 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
     for (int r = r_begin + rl; r < r_end; r += a.row_lanes) {
       const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
       const bool is_cls = r == a.cls_r;
-      const bool is_txt = r >= a.txt_r0 && r < a.txt_r0 + a.M;
-      if (!(is_vis || is_cls || is_txt)) continue;
+      if (!(is_vis || is_cls)) continue;
       const T* base = Ab + (int64_t)r * a.sq;
       double p[kVec];
 #pragma unroll
@@ -107,7 +103,7 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
       if (is_vis) {
 #pragma unroll
         for (int k = 0; k < kVec; ++k) mine[k] += p[k];
-        if (a.abar FICOCO_DBG_ABAR) {
+        if (a.abar) {
           float* dst = a.abar + ((int64_t)b * a.N + (r - a.vis_r0)) * a.N + col;
           if (ncol == kVec) {
             float4 lo = make_float4((float)p[0], (float)p[1], (float)p[2], (float)p[3]);
@@ -123,10 +119,6 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
         double* dst = a.cls + (int64_t)b * a.N + col;
         for (int k = 0; k < ncol; ++k) dst[k] = p[k];
       }
-      if (is_txt) {
-        double* dst = a.ttext + ((int64_t)b * a.N + col) * a.M + (r - a.txt_r0);
-        for (int k = 0; k < ncol; ++k) dst[(int64_t)k * a.M] = p[k];
-      }
     }
   }
 
@@ -140,6 +132,67 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
       for (int l = 0; l < a.row_lanes; ++l) s += lds[l * width + cg * kVec + k];
       dst[k] = s;
     }
+  }
+}
+
+// Text-query block of FiCoCo-L (task term of Eq. 3, profiles of Eq. 4): the head mean of
+// A_text[b][h][k][i], stored TRANSPOSED as the token's profile ttext[b][i][k].  A workgroup
+// owns 8 consecutive text rows x 256 key columns: a thread forms the head mean of one row and
+// 8 columns exactly as the kernel above does (heads added in order, in double), the tile is
+// turned in LDS, and each thread then writes the 8 rows of one column as one 64-byte piece.
+constexpr int kTextRows = 8;
+constexpr int kTextGroups = 256 / kTextRows;      // 8-column groups per workgroup
+template <typename T>
+__global__ __launch_bounds__(256) void text_reduce_kernel(AttnArgs a) {
+  __shared__ double tile[kTextGroups * kVec][kTextRows + 1];     // +1: rows of one column in different banks
+  const int chunk = blockIdx.x, strip = blockIdx.y;
+  const int64_t b = blockIdx.z;
+  const int tid = threadIdx.x;
+  const int cg = tid % kTextGroups, rl = tid / kTextGroups;
+  const int row = chunk * kTextRows + rl;
+  const int col0 = strip * kTextGroups * kVec;
+  const int col = col0 + cg * kVec;
+  const int ncol = max(min(kVec, a.N - col), 0);
+  if (row < a.M && ncol > 0) {
+    const T* base = (const T*)a.A + b * a.sb + (int64_t)row * a.sq + a.col0 + col;
+    double p[kVec];
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) p[k] = 0.0;
+    if (ncol == kVec) {
+      int h0 = 0;
+      for (; h0 + kHeadBatch <= a.H; h0 += kHeadBatch) {
+        Raw8<T> raw[kHeadBatch];
+#pragma unroll
+        for (int u = 0; u < kHeadBatch; ++u) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
+#pragma unroll
+        for (int u = 0; u < kHeadBatch; ++u) add_raw(raw[u], p);
+      }
+      for (; h0 < a.H; ++h0) {
+        Raw8<T> raw;
+        load_raw(base + (int64_t)h0 * a.sh, raw);
+        add_raw(raw, p);
+      }
+    } else {
+      for (int h = 0; h < a.H; ++h)
+        for (int k = 0; k < ncol; ++k) p[k] += widen(base[(int64_t)h * a.sh + k]);
+    }
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) tile[cg * kVec + k][rl] = p[k] * a.invH;
+  }
+  __syncthreads();
+  const int c = col0 + tid;                        // this thread's column
+  if (c >= a.N) return;
+  const int r0 = chunk * kTextRows;
+  const int nr = min(kTextRows, a.M - r0);
+  double* dst = a.ttext + ((int64_t)b * a.N + c) * a.M + r0;
+  if (nr == kTextRows && a.M % 2 == 0) {           // 16-byte aligned pieces
+#pragma unroll
+    for (int k = 0; k < kTextRows; k += 2) {
+      double2 v = make_double2(tile[tid][k], tile[tid][k + 1]);
+      *reinterpret_cast<double2*>(dst + k) = v;
+    }
+  } else {
+    for (int k = 0; k < nr; ++k) dst[k] = tile[tid][k];
   }
 }
 
@@ -168,7 +221,7 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
     a.vis_r0 = p.vis_begin - p.a_q_begin;
     a.n_vis = (want_recv || want_abar) ? p.N : 0;
     a.cls_r = want_cls ? p.cls_index - p.a_q_begin : -1;
-    a.txt_r0 = 0; a.M = 0;
+    a.M = 0;
     a.abar = want_abar ? (float*)(ws + pl.abar) : nullptr;
     a.recv_part = (double*)(ws + pl.recv_part);
     a.cls = (double*)(ws + pl.cls);
@@ -186,13 +239,13 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
     a.col0 = p.vis_begin - p.at_k_begin;
     a.N = p.N;
     a.vis_r0 = 0; a.n_vis = 0; a.cls_r = -1;
-    a.txt_r0 = 0; a.M = p.M;
+    a.M = p.M;
     a.abar = nullptr; a.recv_part = nullptr; a.cls = nullptr;
     a.ttext = (double*)(ws + pl.ttext);
-    a.rows_per_wg = pl.t_rows_per_wg; a.n_chunks = pl.t_chunks;
-    a.row_lanes = pl.row_lanes; a.strip_groups = pl.strip_groups;
     a.invH = 1.0 / (double)p.H;
-    launch_block(a, p.B, pl.col_strips, bf16, s);
+    dim3 grid((p.M + kTextRows - 1) / kTextRows, (p.N + kTextGroups * kVec - 1) / (kTextGroups * kVec), p.B);
+    if (bf16) hipLaunchKernelGGL(text_reduce_kernel<bf16_t>, grid, dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(text_reduce_kernel<float>, grid, dim3(256), 0, s, a);
   }
 }
 

@@ -108,13 +108,7 @@ template <> struct Raw8<bf16_t> { uint4 a; };
 template <> struct Raw8<float> { float4 a, b; };
 
 __device__ __forceinline__ void load_raw(const bf16_t* __restrict__ p, Raw8<bf16_t>& r) {
-#ifdef FICOCO_DBG_NT
-  typedef uint32_t u32x4 __attribute__((ext_vector_type(4), aligned(2)));
-  u32x4 v = __builtin_nontemporal_load((const u32x4*)p);
-  r.a = make_uint4(v.x, v.y, v.z, v.w);
-#else
   __builtin_memcpy(&r.a, p, 16);
-#endif
 }
 __device__ __forceinline__ void load_raw(const float* __restrict__ p, Raw8<float>& r) {
   __builtin_memcpy(&r.a, p, 16);

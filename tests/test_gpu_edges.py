@@ -1,0 +1,73 @@
+"""GPU parity at the edges of the argument ranges: the largest sequence the filter accepts,
+single-token and single-feature problems, one preserved token, every token preserved."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_17686_amd import ficoco as fc
+from paper_2411_17686_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fc.Context(0)
+    yield c
+    c.close()
+
+
+def _check(cfg, ctx, **kw):
+    A = cfg.get("A")
+    out, _ = P.run_v(cfg, A, ctx=ctx, **kw)
+    okw = {k: v for k, v in kw.items() if k not in ("k_max", "staged")}
+    for b in range(cfg["B"]):
+        ref = P.oracle_v(cfg, A, b, **okw)
+        P.compare_image(out, b, ref, cfg["dtype"], cfg["vis_begin"], kw.get("corr_src", fc.C_ATTN) == fc.C_ATTN)
+    return out
+
+
+def test_largest_sequence(ctx):
+    """N = 12288 visual tokens (the filter's limit), three stacked 64 x 64 grids, per-head
+    vectors for the score, cosine correlation through the matrix cores, 1000 tokens preserved."""
+    cfg = synth.ficoco_v_video(seed=70, B=1, frames=3, grid=64, D=64, H=4, centres=40, n_keep=1000)
+    assert cfg["N"] == 12288
+    out = _check(cfg, ctx, red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE)
+    assert out["X_out"].shape == (1, 1000, 64)
+
+
+def test_one_token_over_the_limit_is_rejected(ctx):
+    X = torch.zeros(1, 12289, 8, dtype=torch.bfloat16, device="cuda")
+    v = torch.zeros(1, 2, 12289, dtype=torch.bfloat16, device="cuda")
+    p = fc.make_problem(X, variant=fc.VARIANT_V, vis_begin=0, N=12289, n_keep=100, recv_vec=v, sem_vec=v,
+                        red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE, window=0)
+    with pytest.raises(fc.FicocoError):
+        fc.workspace_bytes(p)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_tiny_problems(ctx, dtype):
+    # one patch token beside [CLS]: nothing can be discarded
+    cfg = synth.ficoco_v_single(seed=71, B=2, grid=1, D=8, H=2, centres=1, dtype=dtype, n_keep=1)
+    out = _check(cfg, ctx)
+    assert np.array_equal(out["X_out"], synth.to_numpy(cfg["X"]))
+    # two patch tokens, one preserved, a single feature
+    cfg = synth.ficoco_v_single(seed=72, B=3, grid=2, D=1, H=1, centres=2, dtype=dtype, n_keep=1)
+    cfg["X"] = cfg["X"][:, :3].contiguous()
+    cfg["A"] = torch.softmax(torch.randn(3, 1, 3, 3, generator=torch.Generator().manual_seed(1)), -1).to(cfg["A"].dtype)
+    cfg["grid"] = (1, 1, 2)
+    _check(cfg, ctx)
+    # one preserved token out of 49: every discarded token has the same single target
+    cfg = synth.ficoco_v_single(seed=73, B=2, grid=7, D=24, H=2, centres=3, dtype=dtype, n_keep=1)
+    out = _check(cfg, ctx)
+    assert np.all(out["cnt"] == 1) and np.all(out["tgt"][:, :, 0] == 0)
+    _check(cfg, ctx, corr_src=fc.C_COSINE)
+    _check(cfg, ctx, k_mode=fc.K_FIXED, fixed_k=1)
+
+
+def test_feature_widths_around_the_vector_size(ctx):
+    for D in (7, 8, 9, 511, 513):
+        cfg = synth.ficoco_v_single(seed=74 + D, B=1, grid=6, D=D, H=2, centres=4, dtype="bf16", n_keep=20)
+        _check(cfg, ctx)
+        _check(cfg, ctx, red_src=fc.R_SIM_MEAN, sem_src=fc.G_EQ_TOKEN, corr_src=fc.C_COSINE)

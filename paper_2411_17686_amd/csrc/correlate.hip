@@ -660,24 +660,45 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
   const float NEGF = -__builtin_huge_valf();
   if (jl == 0) hit_cnt[c] = 0;
 
-  // Scan ALL visual rows of the column and take the preserved ones (slot_of >= 0): the
-  // value and the slot are independent loads, so one round trip serves a whole batch.
+  // Either scan ALL visual rows of the column and take the preserved ones (slot_of >= 0):
+  // the value and the slot are independent loads, so one round trip serves a whole batch --
+  // or, when fewer than half of the tokens are preserved, walk the preserved list (one more
+  // dependent round trip, far fewer rows).
+  const bool by_list = 2 * a.n_keep < a.N;
+  const int n_scan = by_list ? a.n_keep : a.N;
+  const int32_t* Tl = a.T + b * a.n_keep;
   float top[MC];
   int topj[MC];
 #pragma unroll
   for (int k = 0; k < MC; ++k) { top[k] = NEGF; topj[k] = -1; }
-  for (int r0 = jl; r0 < a.N; r0 += kTileLanes * kTileBatch) {
+  for (int r0 = jl; r0 < n_scan; r0 += kTileLanes * kTileBatch) {
     float vv[kTileBatch];
     int sv[kTileBatch];
+    if (by_list) {
+      int rr[kTileBatch];
 #pragma unroll
-    for (int u = 0; u < kTileBatch; ++u) {
-      const int r = min(r0 + u * kTileLanes, a.N - 1);     // clamped: always a valid address
-      vv[u] = col[(int64_t)r * a.N];
-      sv[u] = slot_of[r];
+      for (int u = 0; u < kTileBatch; ++u) {
+        const int jj = min(r0 + u * kTileLanes, n_scan - 1);  // clamped: always a valid address
+        rr[u] = Tl[jj];
+        sv[u] = jj;
+      }
+#pragma unroll
+      for (int u = 0; u < kTileBatch; ++u) {
+        const bool in = (unsigned)rr[u] < (unsigned)a.N;       // index sets are device data
+        vv[u] = col[(int64_t)(in ? rr[u] : 0) * a.N];
+        if (!in) sv[u] = -1;
+      }
+    } else {
+#pragma unroll
+      for (int u = 0; u < kTileBatch; ++u) {
+        const int r = min(r0 + u * kTileLanes, a.N - 1);     // clamped: always a valid address
+        vv[u] = col[(int64_t)r * a.N];
+        sv[u] = slot_of[r];
+      }
     }
 #pragma unroll 4
     for (int u = 0; u < kTileBatch; ++u) {
-      const bool ok = valid && r0 + u * kTileLanes < a.N && sv[u] >= 0;
+      const bool ok = valid && r0 + u * kTileLanes < n_scan && sv[u] >= 0;
       float v = ok ? vv[u] : NEGF;
       int jq = sv[u];
 #pragma unroll
@@ -721,8 +742,10 @@ __global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(
     const double tau = threshold_of((double)vf, (double)vf1, a.sel_g);
     if ((double)top[MC - 1] >= tau) {
       // the whole list qualifies, so more may: take this thread's part of the column again
-      for (int r = jl; r < a.N; r += kTileLanes) {
-        const int sj = slot_of[r];
+      for (int q = jl; q < n_scan; q += kTileLanes) {
+        int r = q, sj;
+        if (by_list) { r = Tl[q]; sj = (unsigned)r < (unsigned)a.N ? q : -1; }
+        else sj = slot_of[r];
         if (sj < 0) continue;
         const float v = col[(int64_t)r * a.N];
         if ((double)v >= tau) {

@@ -41,7 +41,7 @@ struct AttnArgs {
   double* recv_part;
   double* cls;
   double* ttext;
-  int rows_per_wg, n_chunks, row_lanes, strip_groups;
+  int rows_per_wg, n_chunks, row_lanes, strip_groups, col_strips, B;
   double invH;
 };
 
@@ -49,7 +49,14 @@ template <typename T>
 __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a) {
   DBG_SPAN(0);
   extern __shared__ double lds[];
-  const int chunk = blockIdx.x, strip = blockIdx.y, b = blockIdx.z;
+  // Workgroups that read neighbouring strips of the same rows share the cache lines at the
+  // strip boundaries: they get consecutive logical ids, which run on the same XCD (one L2).
+  const int total = a.n_chunks * a.col_strips * a.B;
+  const int logical = xcd_logical_id(blockIdx.x, total);
+  if (logical >= total) return;                   // padding workgroup (the whole block leaves)
+  const int strip = logical % a.col_strips;
+  const int chunk = (logical / a.col_strips) % a.n_chunks;
+  const int b = logical / (a.col_strips * a.n_chunks);
   const int tid = threadIdx.x;
   const int cg = tid % a.strip_groups, rl = tid / a.strip_groups;
   const int col = (strip * a.strip_groups + cg) * kVec;
@@ -197,13 +204,15 @@ __global__ __launch_bounds__(256) void text_reduce_kernel(AttnArgs a) {
 }
 
 static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hipStream_t s) {
-  dim3 grid(a.n_chunks, col_strips, B), block(kReduceThreads);
+  AttnArgs g = a;
+  g.col_strips = col_strips; g.B = B;
+  dim3 grid(xcd_padded_total(a.n_chunks * col_strips * B)), block(kReduceThreads);
   size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
   if (lds < (size_t)FICOCO_REDUCE_LDS_MIN) lds = FICOCO_REDUCE_LDS_MIN;
   if (bf16)
-    hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, a);
+    hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, g);
   else
-    hipLaunchKernelGGL(attn_reduce_kernel<float>, grid, block, lds, s, a);
+    hipLaunchKernelGGL(attn_reduce_kernel<float>, grid, block, lds, s, g);
 }
 
 void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {

@@ -19,8 +19,8 @@
  *     FICOCO_EUNSUPPORTED.  ficoco_last_error(ctx) describes the last failure on that ctx.
  *   - Inputs are assumed finite (no NaN / Inf); behaviour is undefined otherwise.
  *   - Attention maps P[b][h][q][k] are row-stochastic over k (query q attends key k), the
- *     key axis contiguous.  Following the paper's wording ("received attention",
- *     "attention-in"), the paper's A_{i,j} for a visual token i is P[j][i].
+ *     key axis contiguous.  The paper describes its first score term as the attention a
+ *     token receives, so the paper's A_{i,j} for a visual token i is P[j][i].
  *   - Scores, thresholds and merge weights are computed and compared in double precision;
  *     tokens are read and written in `dtype`.  Ties in the top-K filter go to the lower
  *     token index.

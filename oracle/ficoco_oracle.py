@@ -13,11 +13,11 @@ reordering here beyond what the definitions state.
 
 Index convention (the paper's own is not self-consistent, see "readings" below).
 `P[q, k]` is the usual row-stochastic attention map, row = query, column = key.  The
-paper's A_{i,j} for visual token i is read as "attention token i RECEIVES from token j",
-i.e. P[j, i]: Sec. "Redundancy-based Token Discard" calls the first score term the token's
-"received attention" and the appendix section on the sign of vision-aware redundancy calls
-it the "attention-in" score; a literal row sum of a softmax is the constant 1 and could
-not rank anything.
+paper's A_{i,j} for visual token i is read as the attention token i RECEIVES from token j,
+i.e. P[j, i]: Sec. "Redundancy-based Token Discard" describes the first score term as the
+attention the token receives and the appendix section on the sign of vision-aware redundancy
+as its incoming attention; a literal row sum of a softmax is the constant 1 and could not
+rank anything.
 
 Readings (where the paper is silent, ambiguous or garbled):
   R1  multi-head maps are reduced to one map by the head mean, heads added in order.

@@ -3,7 +3,7 @@
 // For every query row that carries a role the head mean  Pbar[q][k] = (1/H) sum_h P[h][q][k]
 // is formed in double precision, heads added in order (so the value does not depend on the
 // launch shape), and consumed three ways:
-//   visual query : added into the per-column "received attention" partial of this row chunk
+//   visual query : added into the per-column received-attention partial of this row chunk
 //                  (first term of Eq. 1 / Eq. 3) and stored in single precision as the map
 //                  the correlate stage gathers from (Algorithm 1, stage 2);
 //   [CLS] query  : stored as the semantic term of Eq. 1;

@@ -300,32 +300,31 @@ __device__ __forceinline__ double corr_value_wave(const CorrArgs& a, int64_t b, 
   return a.gamma * direct + (1.0 - a.gamma) * (br * a.invM);
 }
 
-// cmax[b][k] = max over the visual tokens of the text profile entry k (bound of Eq. 4's indirect term)
+// cmax[b][k] = max over the visual tokens of the text profile entry k (bound of Eq. 4's indirect
+// term).  A workgroup takes 64 consecutive text queries k of one image: thread (k, g) walks the
+// tokens g, g+4, ... (16 independent loads per round), the four token groups meet in LDS.
 __global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
   __shared__ double part[256];
-  const int64_t b = blockIdx.x;
+  const int64_t b = blockIdx.y;
   const int tid = threadIdx.x;
-  for (int k0 = 0; k0 < a.M; k0 += 64) {
-    const int k = k0 + tid % 64, g = tid / 64;
-    double mx = 0.0;
-    if (k < a.M) {
-      int i = g;
-      for (; i + 4 * 15 < a.N; i += 4 * 16) {            // 16 independent loads per round
-        double v[16];
+  const int k = blockIdx.x * 64 + tid % 64, g = tid / 64;
+  double mx = 0.0;
+  if (k < a.M) {
+    int i = g;
+    for (; i + 4 * 15 < a.N; i += 4 * 16) {            // 16 independent loads per round
+      double v[16];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) v[u] = a.ttext[(b * a.N + i + 4 * u) * a.M + k];
+      for (int u = 0; u < 16; ++u) v[u] = a.ttext[(b * a.N + i + 4 * u) * a.M + k];
 #pragma unroll
-        for (int u = 0; u < 16; ++u) mx = v[u] > mx ? v[u] : mx;
-      }
-      for (; i < a.N; i += 4) { const double v = a.ttext[(b * a.N + i) * a.M + k]; mx = v > mx ? v : mx; }
+      for (int u = 0; u < 16; ++u) mx = v[u] > mx ? v[u] : mx;
     }
-    part[tid] = mx;
-    __syncthreads();
-    if (g == 0 && k < a.M) {
-      for (int q = 1; q < 4; ++q) mx = part[q * 64 + tid] > mx ? part[q * 64 + tid] : mx;
-      a.cmax[b * a.M + k] = mx;
-    }
-    __syncthreads();
+    for (; i < a.N; i += 4) { const double v = a.ttext[(b * a.N + i) * a.M + k]; mx = v > mx ? v : mx; }
+  }
+  part[tid] = mx;
+  __syncthreads();
+  if (g == 0 && k < a.M) {
+    for (int q = 1; q < 4; ++q) mx = part[q * 64 + tid] > mx ? part[q * 64 + tid] : mx;
+    a.cmax[b * a.M + k] = mx;
   }
 }
 
@@ -882,7 +881,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
   if (a.mode == kAttnL && !pl.dense_rows && p.k_max <= 64) {
-    hipLaunchKernelGGL(text_colmax_kernel, dim3(p.B), dim3(256), 0, s, a);
+    hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
     return;
   }
@@ -892,7 +891,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     if (gram_start) (void)hipEventRecord(gram_start, s);
     hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);
-    if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3(p.B), dim3(256), 0, s, a);
+    if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
     return;
   }

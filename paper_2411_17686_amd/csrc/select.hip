@@ -340,6 +340,23 @@ __global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec,
   if (sem_vec) out_g[b * N + i] = vec_head_mean(sem_vec, dtype, b, H, N, i);
 }
 
+// Long instructions (many text queries): the task term of Eq. 3, the mean of a token's text
+// profile, is formed by one wavefront per token on the whole chip (lane sums over k = lane,
+// lane + 64, ..., then a fixed tree), so the per-image workgroup of select_kernel reads one value.
+__global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict__ ttext, int N, int M,
+                                                        double* __restrict__ out_g) {
+  const int lane = threadIdx.x % kWave;
+  const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (i >= N) return;      // whole wavefront leaves together
+  const double* p = ttext + (b * N + i) * M;
+  double acc = 0.0;
+  for (int k = lane; k < M; k += kWave) acc += p[k];
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+  if (lane == 0) out_g[b * N + i] = acc / (double)M;
+}
+
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
   return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + cells) * sizeof(int);
@@ -374,6 +391,12 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
                        (double*)(ws + pl.fterm2));
     if (vr) a.red_src = FICOCO_R_SIM_MEAN;     // "read the precomputed term"
     if (vg) a.sem_src = FICOCO_G_EQ_TOKEN;
+  }
+  if (do_score && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 128) {
+    // the equivalent-token buffer is free in FiCoCo-L
+    hipLaunchKernelGGL(text_mean_kernel, dim3((p.N + 3) / 4, p.B), dim3(256), 0, s, a.ttext, p.N, p.M,
+                       (double*)(ws + pl.fterm2));
+    a.sem_src = FICOCO_G_EQ_TOKEN;             // "read the precomputed term"
   }
   a.w = (double)p.w_score;
   const bool penalty = p.variant == FICOCO_VARIANT_V && p.window > 0;

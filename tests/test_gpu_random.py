@@ -1,0 +1,72 @@
+"""Seeded random sweep of small FiCoCo-V / FiCoCo-L problems over shapes, dtypes, score and
+correlation sources, quantiles and ablation variants: every case is compared with the oracle to the
+bars of tests/parity.py."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2411_17686_amd import ficoco as fc
+from paper_2411_17686_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fc.Context(0)
+    yield c
+    c.close()
+
+
+@pytest.mark.parametrize("seed", range(24))
+def test_random_v_case(ctx, seed):
+    r = np.random.default_rng(5000 + seed)
+    grid = int(r.integers(2, 15))
+    N = grid * grid
+    B = int(r.integers(1, 4))
+    D = int(r.choice([1, 5, 8, 24, 33, 64, 130, 520]))
+    H = int(r.integers(1, 6))
+    n_keep = int(r.integers(1, N + 1))
+    dtype = ["f32", "bf16"][seed % 2]
+    cfg = synth.ficoco_v_single(seed=6000 + seed, B=B, grid=grid, D=D, H=H, centres=int(r.integers(1, 9)),
+                                dtype=dtype, n_keep=n_keep)
+    kw = {}
+    mode = seed % 6
+    if mode == 1:
+        kw.update(corr_src=fc.C_COSINE)
+    elif mode == 2:
+        kw.update(red_src=fc.R_SIM_MEAN, sem_src=fc.G_EQ_TOKEN, corr_src=fc.C_COSINE)
+    elif mode == 3:
+        kw.update(k_mode=fc.K_FIXED, fixed_k=int(r.integers(0, 4)))
+    elif mode == 4:
+        kw.update(compress_mode=fc.COMPRESS_AVERAGE)
+    elif mode == 5:
+        kw.update(k_mode=fc.K_CONVERGENT)
+    eps = float(r.choice([0.998, 1.0, 0.9, 0.5]))
+    kw.update(eps=eps, k_max=64, window=int(r.choice([0, 2, 3])))
+    out, _ = P.run_v(cfg, cfg["A"], ctx=ctx, **kw)
+    okw = {k: v for k, v in kw.items() if k != "k_max"}
+    extra = cfg["vis_begin"] + n_keep if (mode == 5 and n_keep < N) else None
+    for b in range(B):
+        ref = P.oracle_v(cfg, cfg["A"], b, **okw)
+        if max([len(j) for j in ref["J"]] + [0]) > 64:       # more targets than the edge lists hold (ties, low quantiles)
+            assert out["overflow"][b] == 1
+            continue
+        P.compare_image(out, b, ref, dtype, cfg["vis_begin"], kw.get("corr_src", fc.C_ATTN) == fc.C_ATTN, extra_row=extra)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_random_l_case(ctx, seed):
+    r = np.random.default_rng(7000 + seed)
+    N = int(r.integers(2, 200))
+    cfg = synth.ficoco_l_decoder(seed=8000 + seed, B=int(r.integers(1, 3)), n_sys=int(r.integers(0, 9)), N=N,
+                                 M=int(r.choice([1, 3, 16, 70, 130])), D=int(r.choice([8, 40, 96, 264])),
+                                 H=int(r.integers(1, 5)), centres=int(r.integers(1, 9)),
+                                 n_keep=int(r.integers(1, N + 1)), with_vv=bool(seed % 2))
+    red, cor = (fc.R_ATTN_RECV, fc.C_ATTN) if seed % 2 else (fc.R_SIM_MEAN, fc.C_COSINE)
+    kw = [dict(), dict(k_mode=fc.K_FIXED, fixed_k=2), dict(compress_mode=fc.COMPRESS_AVERAGE)][seed % 3]
+    out, _ = P.run_l(cfg, red, cor, ctx=ctx, **kw)
+    for b in range(cfg["B"]):
+        ref = P.oracle_l(cfg, b, red, cor, **kw)
+        P.compare_image(out, b, ref, "bf16", cfg["vis_begin"], False)

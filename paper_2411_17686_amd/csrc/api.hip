@@ -180,6 +180,8 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.tgt_ptr = take(B * (size_t)(p.n_keep + 1) * sizeof(int32_t));
   pl.tgt_src = take(B * (size_t)pl.n_disc * p.k_max * sizeof(int32_t));
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
+  pl.hub_list = take(B * (size_t)p.n_keep * sizeof(int32_t));
+  pl.hub_cnt = take(B * sizeof(int32_t));
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;

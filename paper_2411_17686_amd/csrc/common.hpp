@@ -53,6 +53,7 @@ struct Plan {
   size_t tgt_ptr;        // int32  [B][n_keep+1]
   size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
   size_t tgt_alpha;      // double [B][N^S*k_max]
+  size_t hub_list, hub_cnt;   // int32 [B][n_keep], [B]: preserved tokens with long buckets (inverted lists only)
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]

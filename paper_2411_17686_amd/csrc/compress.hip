@@ -23,8 +23,11 @@ struct InvertArgs {
   int32_t* tgt_ptr;    // [B][n_keep+1]
   int32_t* tgt_src;    // [B][n_disc*k_max]  discarded row index (position in S)
   double* tgt_alpha;
+  int32_t* hub_list;   // [B][n_keep]  preserved tokens with more than kHubMin sources (any order)
+  int32_t* hub_cnt;    // [B]
 };
 
+constexpr int kHubMin = 32;        // buckets longer than this are merged by a whole workgroup
 constexpr int kInvertRows = 512;   // discarded rows one workgroup scatters
 constexpr int kInvertPre = 4;      // targets per row loaded before the row's count is known
 constexpr int kInvertBatch = 4;    // rows per thread whose loads are in flight together
@@ -107,8 +110,17 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   }
   if (tid == 0) cnt[n] = total;
   __syncthreads();
-  if (blockIdx.x == 0)
+  if (blockIdx.x == 0) {       // uniform over the workgroup
     for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
+    // targets with long buckets, for the workgroup-per-target pass of the merge
+    int* hub_n = part;         // the scan scratch is free now
+    if (tid == 0) *hub_n = 0;
+    __syncthreads();
+    for (int j = tid; j < n; j += nt)
+      if (cnt[j + 1] - cnt[j] > kHubMin) a.hub_list[b * n + atomicAdd(hub_n, 1)] = j;
+    __syncthreads();
+    if (tid == 0) a.hub_cnt[b] = *hub_n;
+  }
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
   const int cap = a.n_disc * a.k_max;
   for (int r = r_lo + tid; r < r_hi; r += nt) {
@@ -142,6 +154,8 @@ struct MergeArgs {
   const double* edge_alpha;
   const int32_t* pos;
   int32_t* pos_out;
+  const int32_t* hub_list;   // bucket mode: targets with more than kHubMin sources ...
+  const int32_t* hub_cnt;    // ... and their number; null: no such split
   int average;      // ablation "average compression": every weight counts as one
   int extra_row;    // output row of the additional token of the convergent form (mean of the discarded tokens), or -1
 };
@@ -280,9 +294,18 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   }
   const int n_spans = (a.D + kSpan - 1) / kSpan;
   const int unit = blockIdx.x * Lds::kUnits + unit_l;
-  const int r = unit / n_spans;
-  const int d0 = (unit % n_spans) * kSpan;
   const int64_t b = blockIdx.y;
+  int r = unit / n_spans;
+  const int d0 = (unit % n_spans) * kSpan;
+  if (WPU > 1) {
+    // workgroup-per-target pass: unit -> entry of the list of long buckets (one unit per
+    // workgroup, so the whole workgroup leaves together past the end of the list)
+    static_assert(WPU == 1 || Lds::kUnits == 1, "the long-bucket pass maps one workgroup to one target");
+    const int h = unit / n_spans;
+    const int n_hub = min(max(a.hub_cnt[b], 0), a.n_keep);
+    if (h >= n_hub) return;
+    r = a.vis_begin + min(max(a.hub_list[b * a.n_keep + h], 0), a.n_keep - 1);
+  }
   const bool valid = r < a.n_out && r != a.extra_row;   // the additional token is written by extra_token_kernel
 
   if (MATCH && a.n_disc > 0) {
@@ -363,6 +386,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
     }
   } else if (valid && merged_row) {
     const int n_all = e1 - e0;
+    if (WPU == 1 && a.hub_cnt != nullptr && n_all > kHubMin) return;   // written by the workgroup-per-target pass
     long_bucket = n_all > kCap;
     if (n_all > 0 && !long_bucket) {
       // entries of the bucket that fall into this part -> ascending discarded row: rank of an
@@ -600,9 +624,6 @@ constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the ed
 #ifndef FICOCO_MERGE_SLICE
 #define FICOCO_MERGE_SLICE 0          // 0: chosen per problem
 #endif
-#ifndef FICOCO_MERGE_WPU
-#define FICOCO_MERGE_WPU 1            // wavefronts per unit: 1 or 4
-#endif
 
 template <typename T, bool MATCH, int SLICE, int WPU>
 static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
@@ -613,17 +634,14 @@ static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
   if (lds > 32768)
     (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, MATCH, SLICE, WPU>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  dim3 grid((m.n_out * n_spans + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
+  const int units = (WPU > 1 ? m.n_keep : m.n_out) * n_spans;   // long-bucket pass: at most every preserved token
+  dim3 grid((units + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
   hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE, WPU>), grid, block, lds, s, m);
 }
 
-template <typename T, bool MATCH>
-static void launch_merge_m(const MergeArgs& m, int B, int slice, int wpu, hipStream_t s) {
-  if (wpu == 1) {
-    if (slice == 1) launch_merge<T, MATCH, 1, 1>(m, B, s); else launch_merge<T, MATCH, 2, 1>(m, B, s);
-  } else {
-    if (slice == 1) launch_merge<T, MATCH, 1, 4>(m, B, s); else launch_merge<T, MATCH, 2, 4>(m, B, s);
-  }
+template <typename T, bool MATCH, int WPU>
+static void launch_merge_s(const MergeArgs& m, int B, int slice, hipStream_t s) {
+  if (slice == 1) launch_merge<T, MATCH, 1, WPU>(m, B, s); else launch_merge<T, MATCH, 2, WPU>(m, B, s);
 }
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
@@ -638,6 +656,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
     a.tgt_ptr = (int32_t*)(ws + pl.tgt_ptr);
     a.tgt_src = (int32_t*)(ws + pl.tgt_src);
     a.tgt_alpha = (double*)(ws + pl.tgt_alpha);
+    a.hub_list = (int32_t*)(ws + pl.hub_list);
+    a.hub_cnt = (int32_t*)(ws + pl.hub_cnt);
     const size_t lds = ((size_t)2 * p.n_keep + 1 + 2 * kSelectThreads) * sizeof(int);
     if (lds > 32768)
       (void)hipFuncSetAttribute((const void*)invert_edges_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
@@ -656,17 +676,23 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.pos = p.pos; m.pos_out = pos_out;
   m.average = p.compress_mode == FICOCO_COMPRESS_AVERAGE ? 1 : 0;
   m.extra_row = pl.extra_token ? p.vis_begin + p.n_keep : -1;
-  // One wavefront per unit: four of them shorten a single step when preserved tokens have
-  // many sources (long sequences) but cost throughput when independent steps overlap, which
-  // is what is measured; the build option remains.  Narrow spans (one 8-element vector per
-  // lane) double the number of wavefronts: taken when the wide ones would not fill the chip.
-  const int wpu = FICOCO_MERGE_WPU == 4 ? 4 : 1;
+  // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when the
+  // wide ones would not fill the chip.  Bucket mode runs two passes: one wavefront per unit for
+  // the targets with at most kHubMin sources, then a whole workgroup per unit (eight wavefronts,
+  // each adding the sources of one part of the discarded rows, parts added in order) for the few
+  // targets with long buckets, whose serial row loads would otherwise set the kernel's duration.
   int slice = FICOCO_MERGE_SLICE;
-  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) * wpu >= 4096 ? 2 : 1;
-  if (p.dtype == FICOCO_BF16) {
-    if (match) launch_merge_m<bf16_t, true>(m, p.B, slice, wpu, s); else launch_merge_m<bf16_t, false>(m, p.B, slice, wpu, s);
+  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
+  const bool bf16 = p.dtype == FICOCO_BF16;
+  if (match) {
+    if (bf16) launch_merge_s<bf16_t, true, 1>(m, p.B, slice, s); else launch_merge_s<float, true, 1>(m, p.B, slice, s);
   } else {
-    if (match) launch_merge_m<float, true>(m, p.B, slice, wpu, s); else launch_merge_m<float, false>(m, p.B, slice, wpu, s);
+    m.hub_list = (const int32_t*)(ws + pl.hub_list);
+    m.hub_cnt = (const int32_t*)(ws + pl.hub_cnt);
+    if (bf16) launch_merge_s<bf16_t, false, 1>(m, p.B, slice, s); else launch_merge_s<float, false, 1>(m, p.B, slice, s);
+    MergeArgs h = m;
+    h.pos_out = nullptr;           // written by the first pass
+    if (bf16) launch_merge_s<bf16_t, false, kMergeWaves>(h, p.B, slice, s); else launch_merge_s<float, false, kMergeWaves>(h, p.B, slice, s);
   }
   if (m.extra_row >= 0) {
     dim3 grid((p.D + kWave * kVec - 1) / (kWave * kVec), p.B);

@@ -473,7 +473,9 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       for (; e < n_src; ++e) den += l_w[e];
       add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
     } else if (MATCH) {
-      // more sources than the list holds: add while scanning
+      // more sources than the list holds: scan again and add list by list (one pass of 64 rows
+      // yields at most 64 hits, so a list that cannot take them is added and emptied first)
+      int n_list = 0;
       for (int base = row_lo; base < row_hi; base += kWave) {
         const int row = base + lane;
         const bool in = row < row_hi;
@@ -484,16 +486,22 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
         for (int e = 2; e < cnt; ++e)
           if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
-        const int src = in ? tb.src[row] : 0;
-        unsigned long long m = __ballot(hit);
-        while (m) {
-          const int l = __ffsll(m) - 1;
-          m &= m - 1;
-          const double wl = __shfl(w, l, kWave);
-          den += wl;
-          add_source<T, SLICE>(a, Xb, __shfl(src, l, kWave), wl, d0, lane, full, num);
+        const unsigned long long m = __ballot(hit);
+        const int n_hit = __popcll(m);
+        if (n_list + n_hit > kCap) {            // uniform over the wavefront
+          for (int e = 0; e < n_list; ++e) den += l_w[e];
+          add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_list, d0, lane, full, num);
+          n_list = 0;
         }
+        if (hit) {
+          const int slot = n_list + __popcll(m & ((1ULL << lane) - 1ULL));
+          l_src[slot] = tb.src[row];
+          l_w[slot] = w;
+        }
+        n_list += n_hit;
       }
+      for (int e = 0; e < n_list; ++e) den += l_w[e];
+      add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_list, d0, lane, full, num);
     } else {
       // long bucket: take its entries in ascending discarded row by repeated minimum search
       int last = -1;

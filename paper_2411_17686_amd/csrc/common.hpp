@@ -142,6 +142,20 @@ __device__ __forceinline__ void fma_raw(const Raw8<float>& r, double w, double (
   acc[4] += w * r.b.x; acc[5] += w * r.b.y; acc[6] += w * r.b.z; acc[7] += w * r.b.w;
 }
 
+// Between the loads of a batch and their first use: the instruction scheduler moves nothing
+// across this point.  Left to itself it may pull a load down to its use to save registers,
+// which turns a batch of loads in flight back into one memory round trip after the other.
+__device__ __forceinline__ void issue_fence() { __builtin_amdgcn_sched_barrier(0); }
+
+// all bits cleared (eight zeros) unless `keep`: selects, no branch
+__device__ __forceinline__ void keep_raw_if(Raw8<bf16_t>& r, bool keep) {
+  r.a.x = keep ? r.a.x : 0u; r.a.y = keep ? r.a.y : 0u; r.a.z = keep ? r.a.z : 0u; r.a.w = keep ? r.a.w : 0u;
+}
+__device__ __forceinline__ void keep_raw_if(Raw8<float>& r, bool keep) {
+  r.a.x = keep ? r.a.x : 0.0f; r.a.y = keep ? r.a.y : 0.0f; r.a.z = keep ? r.a.z : 0.0f; r.a.w = keep ? r.a.w : 0.0f;
+  r.b.x = keep ? r.b.x : 0.0f; r.b.y = keep ? r.b.y : 0.0f; r.b.z = keep ? r.b.z : 0.0f; r.b.w = keep ? r.b.w : 0.0f;
+}
+
 // the 8 elements held raw, as doubles
 __device__ __forceinline__ void widen_raw(const Raw8<bf16_t>& r, double (&out)[kVec]) {
   const uint32_t q[4] = {r.a.x, r.a.y, r.a.z, r.a.w};

@@ -167,6 +167,9 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
+#ifndef FICOCO_MERGE_SCAN_REGS
+#define FICOCO_MERGE_SCAN_REGS 16   // registers of row data in flight per lane while a scanning-mode list is added
+#endif
 #ifndef FICOCO_MERGE_WAVES
 #define FICOCO_MERGE_WAVES 8
 #endif
@@ -198,36 +201,65 @@ __device__ __forceinline__ void add_source(const MergeArgs& a, const T* Xb, int 
 
 // The same for a whole list held in LDS, in list order, with the row loads of kBatch sources
 // issued before the first of them is added: a target with n sources then waits for
-// ceil(n / kBatch) memory round trips instead of n.
+// ceil(n / kBatch) memory round trips instead of n.  The batch is straight-line code: a load
+// under a per-lane condition makes the compiler wait for the previous load first (the
+// registers it fills may still be awaited on the path that skipped their use), which would
+// put the round trips back in series.  So lanes without a whole vector inside the row load the
+// row's first vector instead, and what they loaded is cleared before it is added (adding
+// w * 0 leaves the sum as it is).
 template <typename T, int SLICE, int REGS>
 __device__ __forceinline__ void add_sources(const MergeArgs& a, const T* Xb, const int* src, const double* w,
                                             int n_src, int d0, int lane, const bool (&full)[SLICE],
                                             double (&num)[SLICE][kVec]) {
   constexpr int kWant = REGS / (SLICE * (int)(sizeof(Raw8<T>) / 4));   // REGS registers of raw data in flight
   constexpr int kBatch = kWant < 1 ? 1 : kWant;
-  for (int e = 0; e < n_src; e += kBatch) {
-    Raw8<T> raw[kBatch][SLICE];
-    const T* xs[kBatch];
+  if (a.D >= kVec) {                 // uniform; narrower rows have no whole vector at all
+    int off[SLICE];
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
-      const int i = min(max(src[min(e + q, n_src - 1)], 0), a.N - 1);   // device data: stay inside the span
-      xs[q] = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+    for (int u = 0; u < SLICE; ++u) off[u] = full[u] ? d0 + (u * kWave + lane) * kVec : 0;
+#pragma unroll 1
+    for (int e = 0; e < n_src; e += kBatch) {
+      Raw8<T> raw[kBatch][SLICE];
 #pragma unroll
-      for (int u = 0; u < SLICE; ++u)
-        if (full[u]) load_raw(xs[q] + d0 + (u * kWave + lane) * kVec, raw[q][u]);
+      for (int q = 0; q < kBatch; ++q) {
+        const int i = min(max(src[min(e + q, n_src - 1)], 0), a.N - 1);   // device data: stay inside the span
+        const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+#pragma unroll
+        for (int u = 0; u < SLICE; ++u) load_raw(xs + off[u], raw[q][u]);
+      }
+      issue_fence();
+      // past the end of the list the last row was loaded again and is cleared like the lanes
+      // above: a branch around its use would let the compiler move the load down to it
+#pragma unroll
+      for (int q = 0; q < kBatch; ++q) {
+        const double wq = w[min(e + q, n_src - 1)];
+#pragma unroll
+        for (int u = 0; u < SLICE; ++u) {
+          keep_raw_if(raw[q][u], full[u] && e + q < n_src);
+          fma_raw(raw[q][u], wq, num[u]);
+        }
+      }
     }
+  }
+  // The one lane whose vector straddles the end of a row (D not a multiple of 8) adds its
+  // elements source by source: batching these guarded element loads as well would cost every
+  // launch a third of its registers for a case that row widths in use never have.
+  bool ragged = false;
 #pragma unroll
-    for (int q = 0; q < kBatch; ++q) {
-      if (e + q >= n_src) break;     // uniform over the wavefront
-      const double wq = w[e + q];
+  for (int u = 0; u < SLICE; ++u) ragged |= !full[u] && d0 + (u * kWave + lane) * kVec < a.D;
+  if (ragged) {
+#pragma unroll 1
+    for (int e = 0; e < n_src; ++e) {
+      const int i = min(max(src[e], 0), a.N - 1);
+      const T* xs = Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+      const double wq = w[e];
 #pragma unroll
       for (int u = 0; u < SLICE; ++u) {
         const int d = d0 + (u * kWave + lane) * kVec;
-        if (full[u]) {
-          fma_raw(raw[q][u], wq, num[u]);
-        } else {
+        if (!full[u]) {
+#pragma unroll
           for (int k = 0; k < kVec; ++k)
-            if (d + k < a.D) num[u][k] += wq * widen(xs[q][d + k]);
+            if (d + k < a.D) num[u][k] += wq * widen(xs[d + k]);
         }
       }
     }
@@ -244,6 +276,32 @@ struct EdgeTable {
   int* t0;
   int* t1;
 };
+
+// Does discarded row `row` of the image name preserved token j as a target, and with which weight?
+__device__ __forceinline__ bool row_names_target(const MergeArgs& a, const EdgeTable& tb, int64_t ebase, int row,
+                                                 bool in, int j, double& w) {
+  const int cnt = in ? tb.cnt[row] : 0;
+  bool hit = false;
+  if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
+  if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
+  for (int e = 2; e < cnt; ++e)
+    if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) {
+      hit = true;
+      w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e];
+    }
+  return hit;
+}
+
+__device__ __forceinline__ EdgeTable edge_table(char* base, int n_disc) {
+  EdgeTable tb;
+  tb.a0 = (double*)base;
+  tb.a1 = tb.a0 + n_disc;
+  tb.cnt = (int*)(tb.a1 + n_disc);
+  tb.src = tb.cnt + n_disc;
+  tb.t0 = tb.src + n_disc;
+  tb.t1 = tb.t0 + n_disc;
+  return tb;
+}
 
 // LDS carve-up of merge_rows_kernel, shared by the kernel and its launcher.
 template <bool MATCH, int SLICE, int WPU>
@@ -266,32 +324,24 @@ struct MergeLds {
 //     that name its target in a list in ascending row order;
 //   MATCH = false: the sources are one bucket of the inverted lists (arbitrary order); the
 //     wavefront takes the entries of its part and orders them by rank counting.
-// The list is then added with several row loads in flight.  Lists longer than the LDS holds
-// take slower paths that need no list.
+// The list is then added with several row loads in flight.  Buckets longer than the LDS holds
+// take a slower path that needs no list; scanning-mode targets with more than kHubMin sources
+// are left to merge_hub_targets.
+// Returns the number of sources of a target that is left to the whole workgroup (scanning
+// mode, more than kHubMin sources), else 0.
 template <typename T, bool MATCH, int SLICE, int WPU>
-__global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
-  DBG_SPAN(3);
-  extern __shared__ __attribute__((aligned(16))) char lds_m[];
+__device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   using Lds = MergeLds<MATCH, SLICE, WPU>;
   constexpr int kCap = Lds::kCap;
   constexpr int kSpan = kWave * kVec * SLICE;
-  constexpr int kRegs = (MATCH && WPU == 1) ? 16 : 32;
+  constexpr int kRegs = (MATCH && WPU == 1) ? FICOCO_MERGE_SCAN_REGS : 32;
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int unit_l = wv / WPU, sub = wv % WPU;
   double* l_w = (double*)lds_m + wv * kCap;
   int* l_src = (int*)((double*)lds_m + kMergeWaves * kCap) + wv * kCap;
   double* part = (double*)(lds_m + Lds::kLists);                 // [kUnits][WPU-1][SLICE*kVec][64]
   double* wden = part + Lds::kPartDoubles;                       // [kMergeWaves][2]: partial denominator, source count
-  EdgeTable tb;
-  {
-    char* base = lds_m + Lds::kLists + Lds::kPartDoubles * 8 + Lds::kDen;
-    tb.a0 = (double*)base;
-    tb.a1 = tb.a0 + a.n_disc;
-    tb.cnt = (int*)(tb.a1 + a.n_disc);
-    tb.src = tb.cnt + a.n_disc;
-    tb.t0 = tb.src + a.n_disc;
-    tb.t1 = tb.t0 + a.n_disc;
-  }
+  const EdgeTable tb = edge_table(lds_m + Lds::kLists + Lds::kPartDoubles * 8 + Lds::kDen, a.n_disc);
   const int n_spans = (a.D + kSpan - 1) / kSpan;
   const int unit = blockIdx.x * Lds::kUnits + unit_l;
   const int64_t b = blockIdx.y;
@@ -303,7 +353,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
     static_assert(WPU == 1 || Lds::kUnits == 1, "the long-bucket pass maps one workgroup to one target");
     const int h = unit / n_spans;
     const int n_hub = min(max(a.hub_cnt[b], 0), a.n_keep);
-    if (h >= n_hub) return;
+    if (h >= n_hub) return 0;
     r = a.vis_begin + min(max(a.hub_list[b * a.n_keep + h], 0), a.n_keep - 1);
   }
   const bool valid = r < a.n_out && r != a.extra_row;   // the additional token is written by extra_token_kernel
@@ -357,7 +407,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       if (full[u]) load_raw(x + d0 + (u * kWave + lane) * kVec, xr[u]);
   }
   if (MATCH) __syncthreads();   // the edge table is complete (every wavefront arrives here)
-  if (WPU == 1 && !valid) return;
+  if (WPU == 1 && !valid) return 0;
 
   // this wavefront's part of the discarded rows
   const int part_rows = WPU == 1 ? a.n_disc : ((a.n_disc + WPU - 1) / WPU + kWave - 1) / kWave * kWave;
@@ -369,14 +419,8 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   if (valid && merged_row && MATCH) {
     for (int base = row_lo; base < row_hi; base += kWave) {
       const int row = base + lane;
-      const bool in = row < row_hi;
-      const int cnt = in ? tb.cnt[row] : 0;
-      bool hit = false;
       double w = 0.0;
-      if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
-      if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
-      for (int e = 2; e < cnt; ++e)
-        if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
+      const bool hit = row_names_target(a, tb, ebase, row, row < row_hi, j, w);
       const unsigned long long m = __ballot(hit);
       if (hit) {
         const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
@@ -384,9 +428,10 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       }
       n_src += __popcll(m);
     }
+    if (WPU == 1 && n_src > kHubMin) return n_src;   // added by the whole workgroup, see merge_hub_targets
   } else if (valid && merged_row) {
     const int n_all = e1 - e0;
-    if (WPU == 1 && a.hub_cnt != nullptr && n_all > kHubMin) return;   // written by the workgroup-per-target pass
+    if (WPU == 1 && a.hub_cnt != nullptr && n_all > kHubMin) return 0;   // written by the workgroup-per-target pass
     long_bucket = n_all > kCap;
     if (n_all > 0 && !long_bucket) {
       // entries of the bucket that fall into this part -> ascending discarded row: rank of an
@@ -449,7 +494,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         for (int k = 0; k < kVec; ++k)
           if (d + k < a.D) out[d + k] = x[d + k];
     }
-    return;
+    return 0;
   }
   if (valid && sub == 0) {
 #pragma unroll
@@ -472,37 +517,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       }
       for (; e < n_src; ++e) den += l_w[e];
       add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_src, d0, lane, full, num);
-    } else if (MATCH) {
-      // more sources than the list holds: scan again and add list by list (one pass of 64 rows
-      // yields at most 64 hits, so a list that cannot take them is added and emptied first)
-      int n_list = 0;
-      for (int base = row_lo; base < row_hi; base += kWave) {
-        const int row = base + lane;
-        const bool in = row < row_hi;
-        const int cnt = in ? tb.cnt[row] : 0;
-        bool hit = false;
-        double w = 0.0;
-        if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
-        if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
-        for (int e = 2; e < cnt; ++e)
-          if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) { hit = true; w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e]; }
-        const unsigned long long m = __ballot(hit);
-        const int n_hit = __popcll(m);
-        if (n_list + n_hit > kCap) {            // uniform over the wavefront
-          for (int e = 0; e < n_list; ++e) den += l_w[e];
-          add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_list, d0, lane, full, num);
-          n_list = 0;
-        }
-        if (hit) {
-          const int slot = n_list + __popcll(m & ((1ULL << lane) - 1ULL));
-          l_src[slot] = tb.src[row];
-          l_w[slot] = w;
-        }
-        n_list += n_hit;
-      }
-      for (int e = 0; e < n_list; ++e) den += l_w[e];
-      add_sources<T, SLICE, kRegs>(a, Xb, l_src, l_w, n_list, d0, lane, full, num);
-    } else {
+    } else if (!MATCH) {
       // long bucket: take its entries in ascending discarded row by repeated minimum search
       int last = -1;
       for (int k = 0; k < n_src; ++k) {
@@ -537,7 +552,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
     }
     if (lane == 0) { wden[2 * wv] = den; wden[2 * wv + 1] = (double)n_src; }
     __syncthreads();              // every wavefront of the workgroup arrives here exactly once
-    if (sub > 0 || !valid) return;
+    if (sub > 0 || !valid) return 0;
     double total = 0.0;
 #pragma unroll
     for (int w = 0; w < WPU; ++w) total += wden[2 * (unit_l * WPU + w) + 1];
@@ -550,7 +565,7 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
           for (int k = 0; k < kVec; ++k)
             if (d + k < a.D) out[d + k] = x[d + k];
       }
-      return;
+      return 0;
     }
 #pragma unroll
     for (int w = 1; w < WPU; ++w) {
@@ -575,6 +590,118 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
         if (d + k < a.D) store_token(out + d + k, num[u][k] / den);
     }
   }
+  return 0;
+}
+
+// Scanning mode, targets with more than kHubMin sources (a token that most discarded tokens
+// attend to): the eight wavefronts of the workgroup that holds such a unit add it together once
+// their own units are done.  The discarded rows are taken 512 at a time: every wavefront scans
+// 64 of them, the hits are packed in ascending row order into one list (the LDS of the
+// per-wavefront lists), and every wavefront then adds the whole list, 16 row loads in flight,
+// to its own 64 * SLICE features of the span: the sum of every output element still runs over
+// ascending discarded rows.
+template <typename T, int SLICE>
+__device__ __forceinline__ void merge_hub_targets(const MergeArgs& a, char* lds_m, int deferred) {
+  using Lds = MergeLds<true, SLICE, 1>;
+  static_assert(Lds::kCap == kWave, "the shared list holds one hit per scanned row");
+  constexpr int kSpan = kWave * kVec * SLICE;
+  constexpr int kChunk = kMergeWaves * kWave;
+  constexpr int kBatch = 16;
+  __shared__ int hub_n[kMergeWaves];
+  __shared__ int hit_n[kMergeWaves];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  if (lane == 0) hub_n[wv] = deferred;
+  __syncthreads();            // every wavefront is done with its own list
+  double* s_w = (double*)lds_m;
+  int* s_src = (int*)((double*)lds_m + kMergeWaves * Lds::kCap);
+  const EdgeTable tb = edge_table(lds_m + Lds::kLists + Lds::kPartDoubles * 8 + Lds::kDen, a.n_disc);
+  const int n_spans = (a.D + kSpan - 1) / kSpan;
+  const int64_t b = blockIdx.y;
+  const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
+  const T* Xb = (const T*)a.X + b * a.xsb;
+  for (int u = 0; u < kMergeWaves; ++u) {
+    if (hub_n[u] == 0) continue;                         // uniform over the workgroup
+    const int unit = blockIdx.x * kMergeWaves + u;
+    const int r = unit / n_spans;
+    const int j = r - a.vis_begin;                       // a deferred unit is a preserved visual row
+    const int dl = (unit % n_spans) * kSpan + (wv * kWave + lane) * SLICE;
+    const bool whole = dl + SLICE <= a.D;
+    const int tok = min(max(a.T[b * a.n_keep + j], 0), a.N - 1);
+    const T* x = Xb + (int64_t)(a.vis_begin + tok) * a.xsn;
+    T* out = (T*)a.X_out + (b * a.n_out + r) * (int64_t)a.D;
+    double num[SLICE];
+#pragma unroll
+    for (int e = 0; e < SLICE; ++e) num[e] = dl + e < a.D ? widen(x[dl + e]) : 0.0;
+    double den = 1.0;
+    for (int c0 = 0; c0 < a.n_disc; c0 += kChunk) {
+      const int row = c0 + wv * kWave + lane;
+      double w = 0.0;
+      const bool hit = row_names_target(a, tb, ebase, row, row < a.n_disc, j, w);
+      const unsigned long long m = __ballot(hit);
+      if (lane == 0) hit_n[wv] = __popcll(m);
+      __syncthreads();
+      int off = 0, n_list = 0;
+#pragma unroll
+      for (int q = 0; q < kMergeWaves; ++q) {
+        const int c = hit_n[q];
+        off += q < wv ? c : 0;
+        n_list += c;
+      }
+      if (hit) {
+        const int slot = off + __popcll(m & ((1ULL << lane) - 1ULL));
+        s_src[slot] = tb.src[row];
+        s_w[slot] = w;
+      }
+      __syncthreads();
+      auto row_of = [&](int e) {
+        const int i = min(max(s_src[e], 0), a.N - 1);      // device data: stay inside the span
+        return Xb + (int64_t)(a.vis_begin + i) * a.xsn;
+      };
+      if (a.D >= SLICE) {                                  // uniform; straight-line batches as in add_sources
+        const int off = whole ? dl : 0;
+#pragma unroll 1
+        for (int e0 = 0; e0 < n_list; e0 += kBatch) {
+          T v[kBatch][SLICE];
+#pragma unroll
+          for (int q = 0; q < kBatch; ++q)
+            __builtin_memcpy(&v[q][0], row_of(min(e0 + q, n_list - 1)) + off, sizeof(T) * SLICE);
+          issue_fence();
+#pragma unroll
+          for (int q = 0; q < kBatch; ++q) {
+            const bool in = e0 + q < n_list;               // past the end: the last row again, not counted
+            const double wq = s_w[min(e0 + q, n_list - 1)];
+            den += in ? wq : 0.0;
+#pragma unroll
+            for (int e = 0; e < SLICE; ++e) num[e] += whole && in ? wq * widen(v[q][e]) : 0.0;
+          }
+        }
+      } else {
+        for (int e0 = 0; e0 < n_list; ++e0) den += s_w[e0];
+      }
+      if (!whole && dl < a.D) {                            // the lane at the end of a row of odd width
+#pragma unroll 1
+        for (int e0 = 0; e0 < n_list; ++e0) {
+          const T* xs = row_of(e0);
+          const double wq = s_w[e0];
+#pragma unroll
+          for (int e = 0; e < SLICE; ++e)
+            if (dl + e < a.D) num[e] += wq * widen(xs[dl + e]);
+        }
+      }
+      __syncthreads();        // the list and the counts are written again by the next chunk or unit
+    }
+#pragma unroll
+    for (int e = 0; e < SLICE; ++e)
+      if (dl + e < a.D) store_token(out + dl + e, num[e] / den);
+  }
+}
+
+template <typename T, bool MATCH, int SLICE, int WPU>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
+  DBG_SPAN(3);
+  extern __shared__ __attribute__((aligned(16))) char lds_m[];
+  const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m);
+  if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
 }
 
 // The additional token of the "convergent" ablation: the plain mean of the discarded tokens.
@@ -606,6 +733,7 @@ __global__ __launch_bounds__(kExtraWaves * kWave) void extra_token_kernel(MergeA
       Raw8<T> raw[8];
 #pragma unroll
       for (int u = 0; u < 8; ++u) load_raw(Xb + (int64_t)tok[u] * a.xsn, raw[u]);
+      issue_fence();
 #pragma unroll
       for (int u = 0; u < 8; ++u)
         if (e0 + u < r1) add_raw(raw[u], acc);

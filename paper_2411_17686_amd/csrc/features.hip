@@ -85,21 +85,24 @@ __global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
   if (nd == kVec) {
     for (int i0 = r0; i0 < r1; i0 += kColBatch) {
       Raw8<T> raw[kColBatch];
-      double inv[kColBatch];
+      double nrm[kColBatch];
 #pragma unroll
       for (int u = 0; u < kColBatch; ++u) {
         const int i = min(i0 + u, r1 - 1);                 // clamped: always a valid row
         load_raw(base + (int64_t)i * a.sn, raw[u]);
-        const double nrm = a.norm[b * a.N + i];
-        inv[u] = nrm > 0.0 ? 1.0 / nrm : 0.0;
+        nrm[u] = a.norm[b * a.N + i];
       }
+      issue_fence();                                       // all loads of the batch are issued before the first use
+      // past the last row the clamped load is cleared, not skipped: a branch around its use
+      // lets the compiler move the load down to it, one memory round trip per row
 #pragma unroll
       for (int u = 0; u < kColBatch; ++u) {
-        if (i0 + u >= r1) break;                           // uniform over the wavefront
+        keep_raw_if(raw[u], i0 + u < r1);
+        const double inv = nrm[u] > 0.0 ? 1.0 / nrm[u] : 0.0;
         double v[kVec];
         widen_raw(raw[u], v);
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) { su[k] += v[k] * inv[u]; sr[k] += v[k]; }
+        for (int k = 0; k < kVec; ++k) { su[k] += v[k] * inv; sr[k] += v[k]; }
       }
     }
   } else {

@@ -71,3 +71,39 @@ def test_feature_widths_around_the_vector_size(ctx):
         cfg = synth.ficoco_v_single(seed=74 + D, B=1, grid=6, D=D, H=2, centres=4, dtype="bf16", n_keep=20)
         _check(cfg, ctx)
         _check(cfg, ctx, red_src=fc.R_SIM_MEAN, sem_src=fc.G_EQ_TOKEN, corr_src=fc.C_COSINE)
+
+
+def _with_broad_query(cfg, q):
+    """Token q (index in the whole sequence) attends to every key alike and draws half of the
+    [CLS] attention: it is preserved, and most discarded tokens correlate with it first."""
+    A = cfg["A"].to(torch.float32)
+    n = A.shape[-1]
+    A *= 0.02                                   # every other query looks at [CLS] almost only
+    A[..., cfg["cls_index"]] += 0.98
+    A[:, :, q, :] = 1.0 / n
+    row = A[:, :, cfg["cls_index"], :].clone()
+    row[..., q] = 0.0
+    row = 0.5 * row / row.sum(-1, keepdim=True)
+    row[..., q] = 0.5
+    A[:, :, cfg["cls_index"], :] = row
+    cfg["A"] = A.to(cfg["A"].dtype)
+    return cfg
+
+
+@pytest.mark.parametrize("grid,D,n_keep,B,dtype,images", [
+    (16, 1100, 128, 2, "f32", (0, 1)),        # one scan of the discarded rows, three feature spans, ragged tail
+    (36, 40, 400, 1, "bf16", (0,)),           # 896 discarded rows: two scans
+    (24, 1024, 384, 16, "bf16", (0, 15)),     # the batched shape with its wide feature spans
+])
+def test_target_named_by_most_discarded_tokens(ctx, grid, D, n_keep, B, dtype, images):
+    """A preserved token with a broad attention row collects far more sources than one
+    wavefront's list is meant for; the workgroup adds them together."""
+    cfg = synth.ficoco_v_single(seed=90 + grid, B=B, grid=grid, D=D, H=2, centres=12, dtype=dtype, n_keep=n_keep)
+    cfg = _with_broad_query(cfg, q=grid * grid // 2)
+    out, _ = P.run_v(cfg, cfg["A"], ctx=ctx, window=0)
+    n_disc = cfg["N"] - n_keep
+    for b in images:
+        ref = P.oracle_v(cfg, cfg["A"], b, window=0)
+        P.compare_image(out, b, ref, dtype, cfg["vis_begin"], True)
+        named = np.concatenate([out["tgt"][b, a, :out["cnt"][b, a]] for a in range(n_disc)])
+        assert np.bincount(named).max() > n_disc // 2, "the case no longer builds a hub"

@@ -27,6 +27,29 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   return v;
 }
 
+// A row is read as 16-byte vectors, vector 64 * t + lane by lane `lane` in step t; kRowRegs
+// registers of them are in flight per lane.  Lanes past the last whole vector read vector 0
+// and clear what they got, so that the batch stays straight-line code.
+constexpr int kRowRegs = 32;
+template <typename T>
+struct RowBatch {
+  static constexpr int kVecs = kRowRegs / (int)(sizeof(Raw8<T>) / 4);
+  Raw8<T> raw[kVecs];
+  __device__ __forceinline__ void load(const T* x, int t0, int n_vec, int lane) {
+#pragma unroll
+    for (int u = 0; u < kVecs; ++u) {
+      const int idx = (t0 + u) * kWave + lane;
+      load_raw(x + (idx < n_vec ? idx * kVec : 0), raw[u]);
+    }
+    issue_fence();
+#pragma unroll
+    for (int u = 0; u < kVecs; ++u) keep_raw_if(raw[u], (t0 + u) * kWave + lane < n_vec);
+  }
+};
+
+// One wavefront per row: |F_i| in double precision and, for the cosine correlation, the unit
+// row rounded to bfloat16.  Rows of up to 64 * kVecs vectors (4096 bfloat16 elements) are read
+// once; longer ones are read again (from cache) for the unit row.
 template <typename T>
 __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   const int lane = threadIdx.x % kWave;
@@ -34,14 +57,22 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   const int64_t b = blockIdx.y;
   if (i >= a.N) return;
   const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
-  const int Dv = a.Df - a.Df % kVec;
+  const int n_vec = a.Df / kVec, Dv = n_vec * kVec;
+  const int n_t = (n_vec + kWave - 1) / kWave;
+  constexpr int kB = RowBatch<T>::kVecs;
+  RowBatch<T> first, more;
   double ss = 0.0;
-  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-    double v[kVec];
-    load8<T>(x + d, v);
+  auto add_squares = [&](const RowBatch<T>& rb) {
 #pragma unroll
-    for (int k = 0; k < kVec; ++k) ss += v[k] * v[k];
-  }
+    for (int u = 0; u < kB; ++u) {
+      double v[kVec];
+      widen_raw(rb.raw[u], v);
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) ss += v[k] * v[k];
+    }
+  };
+  if (n_t > 0) { first.load(x, 0, n_vec, lane); add_squares(first); }
+  for (int t0 = kB; t0 < n_t; t0 += kB) { more.load(x, t0, n_vec, lane); add_squares(more); }
   for (int d = Dv + lane; d < a.Df; d += kWave) { const double v = widen(x[d]); ss += v * v; }
   ss = wave_sum_d(ss);
   const double nrm = sqrt(ss);
@@ -49,14 +80,22 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   if (a.xhat) {
     const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
     bf16_t* o = a.xhat + (b * a.N + i) * (int64_t)a.Df;
-    for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-      double v[kVec];
-      load8<T>(x + d, v);
-      Pack8<bf16_t> r;
+    auto store_unit = [&](const RowBatch<T>& rb, int t0) {
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) r.v[k] = to_bf16(v[k] * inv);
-      __builtin_memcpy(o + d, &r, sizeof(r));
-    }
+      for (int u = 0; u < kB; ++u) {
+        const int idx = (t0 + u) * kWave + lane;
+        if (idx < n_vec) {
+          double v[kVec];
+          widen_raw(rb.raw[u], v);
+          Pack8<bf16_t> r;
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) r.v[k] = to_bf16(v[k] * inv);
+          __builtin_memcpy(o + idx * kVec, &r, sizeof(r));
+        }
+      }
+    };
+    if (n_t > 0) store_unit(first, 0);
+    for (int t0 = kB; t0 < n_t; t0 += kB) { more.load(x, t0, n_vec, lane); store_unit(more, t0); }
     for (int d = Dv + lane; d < a.Df; d += kWave) o[d] = to_bf16(widen(x[d]) * inv);
   }
 }

@@ -328,6 +328,11 @@ __global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
   }
 }
 
+#ifndef FICOCO_CORR_STEPS
+#define FICOCO_CORR_STEPS 2
+#endif
+constexpr int kCorrSteps = FICOCO_CORR_STEPS;   // 512-feature steps of the exact dot products loaded together
+
 // Exact C[i][j_q] for up to CB targets at once, the whole wavefront working on them together
 // (all lanes return the values).  The loads of all CB rows are issued before the first use, so
 // a batch costs one memory round trip per 512 features instead of one per target.  Per target
@@ -346,19 +351,31 @@ __device__ __forceinline__ void corr_values_wave(const CorrArgs& a, int64_t b, i
 #pragma unroll
     for (int q = 0; q < CB; ++q) { y[q] = a.xhat + (b * a.N + j[q]) * a.Df; acc[q] = 0.0; }
     const int Dv = a.Df - a.Df % kVec;
-    for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-      Raw8<bf16_t> xr, yr[CB];
-      load_raw(x + d, xr);
+    // kCorrSteps steps of 512 features at a time: (1 + CB) * kCorrSteps loads in flight.  A lane
+    // past the last whole vector reads vector 0 and clears it (straight-line batch).
+    for (int d0 = lane * kVec; d0 - lane * kVec < Dv; d0 += kCorrSteps * kWave * kVec) {
+      Raw8<bf16_t> xr[kCorrSteps], yr[kCorrSteps][CB];
 #pragma unroll
-      for (int q = 0; q < CB; ++q) load_raw(y[q] + d, yr[q]);
-      double u[kVec];
-      widen_raw(xr, u);
+      for (int t = 0; t < kCorrSteps; ++t) {
+        const int d = d0 + t * kWave * kVec;
+        const int off = d < Dv ? d : 0;
+        load_raw(x + off, xr[t]);
 #pragma unroll
-      for (int q = 0; q < CB; ++q) {
-        double w[kVec];
-        widen_raw(yr[q], w);
+        for (int q = 0; q < CB; ++q) load_raw(y[q] + off, yr[t][q]);
+      }
+      issue_fence();
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) acc[q] += u[k] * w[k];
+      for (int t = 0; t < kCorrSteps; ++t) {
+        keep_raw_if(xr[t], d0 + t * kWave * kVec < Dv);      // a cleared x vector adds zeros for every target
+        double u[kVec];
+        widen_raw(xr[t], u);
+#pragma unroll
+        for (int q = 0; q < CB; ++q) {
+          double w[kVec];
+          widen_raw(yr[t][q], w);
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) acc[q] += u[k] * w[k];
+        }
       }
     }
     for (int d = Dv + lane; d < a.Df; d += kWave) {
@@ -460,14 +477,27 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
           for (int u = 0; u < 8; ++u) val[ub + u] = 0.0f;
         }
       }
+      // partial sums of the further K ranges, added in order; the loads of up to four ranges
+      // are issued together (a range past the last one reads the last again and adds zero)
 #pragma unroll 1
-      for (int sp = 1; sp < a.ct_splits; ++sp) {                   // partial sums of the K ranges, added in order
-        c += split_stride;
+      for (int sp0 = 1; sp0 < a.ct_splits; sp0 += 4) {
 #pragma unroll
         for (int ub = 0; ub < kCandKeep; ub += 8) {
-          if (ub < n_u) {
+          if (ub < n_u) {                                            // uniform
+            float part[4][8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) val[ub + u] += c[(ub + u) * kWave];
+            for (int q = 0; q < 4; ++q) {
+              const float* cq = c + (int64_t)min(sp0 + q, a.ct_splits - 1) * split_stride;
+#pragma unroll
+              for (int u = 0; u < 8; ++u) part[q][u] = cq[(ub + u) * kWave];
+            }
+            issue_fence();
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+              const bool in = sp0 + q < a.ct_splits;
+#pragma unroll
+              for (int u = 0; u < 8; ++u) val[ub + u] += in ? part[q][u] : 0.0f;
+            }
           }
         }
       }

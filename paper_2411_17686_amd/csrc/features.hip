@@ -27,13 +27,12 @@ __device__ __forceinline__ double wave_sum_d(double v) {
   return v;
 }
 
-// A row is read as 16-byte vectors, vector 64 * t + lane by lane `lane` in step t; kRowRegs
-// registers of them are in flight per lane.  Lanes past the last whole vector read vector 0
-// and clear what they got, so that the batch stays straight-line code.
-constexpr int kRowRegs = 32;
-template <typename T>
+// A row is read as 16-byte vectors, vector 64 * t + lane by lane `lane` in step t, KB steps in
+// flight per lane.  Lanes past the last whole vector read vector 0 and clear what they got, so
+// that the batch stays straight-line code.
+template <typename T, int KB>
 struct RowBatch {
-  static constexpr int kVecs = kRowRegs / (int)(sizeof(Raw8<T>) / 4);
+  static constexpr int kVecs = KB;
   Raw8<T> raw[kVecs];
   __device__ __forceinline__ void load(const T* x, int t0, int n_vec, int lane) {
 #pragma unroll
@@ -48,9 +47,10 @@ struct RowBatch {
 };
 
 // One wavefront per row: |F_i| in double precision and, for the cosine correlation, the unit
-// row rounded to bfloat16.  Rows of up to 64 * kVecs vectors (4096 bfloat16 elements) are read
-// once; longer ones are read again (from cache) for the unit row.
-template <typename T>
+// row rounded to bfloat16.  Rows of up to 64 * KB vectors are read once; longer ones are read
+// again (from cache) for the unit row.  The launcher picks KB = 2, 4 or 8 by the row length (a
+// batch wider than the row only adds loads that are thrown away).
+template <typename T, int KB>
 __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   const int lane = threadIdx.x % kWave;
   const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
@@ -59,10 +59,10 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
   const int n_vec = a.Df / kVec, Dv = n_vec * kVec;
   const int n_t = (n_vec + kWave - 1) / kWave;
-  constexpr int kB = RowBatch<T>::kVecs;
-  RowBatch<T> first, more;
+  constexpr int kB = KB;
+  RowBatch<T, KB> first, more;
   double ss = 0.0;
-  auto add_squares = [&](const RowBatch<T>& rb) {
+  auto add_squares = [&](const RowBatch<T, KB>& rb) {
 #pragma unroll
     for (int u = 0; u < kB; ++u) {
       double v[kVec];
@@ -80,7 +80,7 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   if (a.xhat) {
     const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
     bf16_t* o = a.xhat + (b * a.N + i) * (int64_t)a.Df;
-    auto store_unit = [&](const RowBatch<T>& rb, int t0) {
+    auto store_unit = [&](const RowBatch<T, KB>& rb, int t0) {
 #pragma unroll
       for (int u = 0; u < kB; ++u) {
         const int idx = (t0 + u) * kWave + lane;
@@ -276,8 +276,15 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
   a.want_eq = p.sem_src == FICOCO_G_EQ_TOKEN;
   const bool bf16 = p.dtype == FICOCO_BF16;
   dim3 rows((p.N + 3) / 4, p.B), block(256);
-  if (bf16) hipLaunchKernelGGL(row_norm_kernel<bf16_t>, rows, block, 0, s, a);
-  else hipLaunchKernelGGL(row_norm_kernel<float>, rows, block, 0, s, a);
+  const int steps = (pl.Df / kVec + kWave - 1) / kWave;    // 16-byte vectors per lane and row
+  if (bf16) {
+    if (steps <= 2) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 2>), rows, block, 0, s, a);
+    else if (steps <= 4) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 4>), rows, block, 0, s, a);
+    else hipLaunchKernelGGL((row_norm_kernel<bf16_t, 8>), rows, block, 0, s, a);
+  } else {
+    if (steps <= 2) hipLaunchKernelGGL((row_norm_kernel<float, 2>), rows, block, 0, s, a);
+    else hipLaunchKernelGGL((row_norm_kernel<float, 4>), rows, block, 0, s, a);
+  }
   if (!a.want_sim && !a.want_eq) return;
   dim3 cgrid(pl.f_chunks, (pl.Df + kColSpan - 1) / kColSpan, p.B);
   if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);

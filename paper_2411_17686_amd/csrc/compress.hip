@@ -160,6 +160,8 @@ struct MergeArgs {
   int extra_row;    // output row of the additional token of the convergent form (mean of the discarded tokens), or -1
 };
 
+static __device__ int32_t g_no_token = 0;   // what the row's token index is read from when nothing is preserved
+
 template <typename T>
 __device__ __forceinline__ void copy8(const T* src, T* dst) {
   Pack8<T> v;
@@ -174,6 +176,8 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
 #define FICOCO_MERGE_WAVES 8
 #endif
 constexpr int kMergeWaves = FICOCO_MERGE_WAVES;    // wavefronts (= output row spans) per workgroup
+constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
+static_assert(kMatchMaxRows % (kMergeWaves * kWave) == 0, "a workgroup stages the edge table in whole rounds");
 constexpr int kMatchCap = 64;     // scanning mode: sources of one target kept in LDS
 constexpr int kBucketCap = 256;   // inverted lists: bucket entries put in order in LDS
 constexpr int kBucketPer = kBucketCap / kWave;
@@ -278,17 +282,23 @@ struct EdgeTable {
 };
 
 // Does discarded row `row` of the image name preserved token j as a target, and with which weight?
+// The first two pairs of a row are in LDS (FULL = false looks at those only and reports in
+// `more` whether the row has further pairs); the rest is read from global memory.
+template <bool FULL>
 __device__ __forceinline__ bool row_names_target(const MergeArgs& a, const EdgeTable& tb, int64_t ebase, int row,
-                                                 bool in, int j, double& w) {
+                                                 bool in, int j, double& w, bool& more) {
   const int cnt = in ? tb.cnt[row] : 0;
   bool hit = false;
   if (cnt > 0 && tb.t0[row] == j) { hit = true; w = tb.a0[row]; }
   if (cnt > 1 && tb.t1[row] == j) { hit = true; w = tb.a1[row]; }
-  for (int e = 2; e < cnt; ++e)
-    if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) {
-      hit = true;
-      w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e];
-    }
+  more = cnt > 2;
+  if (FULL) {
+    for (int e = 2; e < cnt; ++e)
+      if (a.edge_tgt[ebase + (int64_t)row * a.k_max + e] == j) {
+        hit = true;
+        w = a.average ? 1.0 : a.edge_alpha[ebase + (int64_t)row * a.k_max + e];
+      }
+  }
   return hit;
 }
 
@@ -358,28 +368,43 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   }
   const bool valid = r < a.n_out && r != a.extra_row;   // the additional token is written by extra_token_kernel
 
-  if (MATCH && a.n_disc > 0) {
-    const int e1 = min(1, a.k_max - 1);
-    for (int row = threadIdx.x; row < a.n_disc; row += kMergeWaves * kWave) {
-      const int64_t rr = b * a.n_disc + row;
-      tb.cnt[row] = min(a.edge_cnt[rr], a.k_max);
-      tb.src[row] = a.S[rr];
-      tb.t0[row] = a.edge_tgt[rr * a.k_max];
-      tb.t1[row] = a.edge_tgt[rr * a.k_max + e1];
-      tb.a0[row] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max];
-      tb.a1[row] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max + e1];
-    }
-  }
-
+  // Order of the loads below: the row's token index first (its own row depends on it), then
+  // this thread's share of the edge table, then -- once the index is there -- the row itself;
+  // the table is put into LDS last.  Each of them is a memory round trip of its own if taken
+  // one after the other.
+  DBG_PHASE(0);
   const T* Xb = (const T*)a.X + b * a.xsb;
   T* out = (T*)a.X_out + (b * a.n_out + (valid ? r : 0)) * (int64_t)a.D;
+  const bool kept_row = valid && r >= a.vis_begin && r < a.vis_begin + a.n_keep;
+  // (an unconditional load from an address that is always valid: under a condition the compiler
+  // moves the first use of the value next to the load and waits for it there)
+  const int32_t* tok_at = a.n_keep > 0 ? a.T + b * a.n_keep + min(max(r - a.vis_begin, 0), a.n_keep - 1) : &g_no_token;
+  int tok = *tok_at;
+  constexpr int kStage = MATCH ? kMatchMaxRows / (kMergeWaves * kWave) : 1;   // edge-table rows per thread
+  int st_cnt[kStage], st_src[kStage], st_t0[kStage], st_t1[kStage];
+  double st_a0[kStage], st_a1[kStage];
+  if (MATCH && a.n_disc > 0) {
+    const int e1 = min(1, a.k_max - 1);
+#pragma unroll
+    for (int q = 0; q < kStage; ++q) {
+      const int row = min((int)threadIdx.x + q * kMergeWaves * kWave, a.n_disc - 1);   // clamped: a valid row
+      const int64_t rr = b * a.n_disc + row;
+      st_cnt[q] = a.edge_cnt[rr];
+      st_src[q] = a.S[rr];
+      st_t0[q] = a.edge_tgt[rr * a.k_max];
+      st_t1[q] = a.edge_tgt[rr * a.k_max + e1];
+      st_a0[q] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max];
+      st_a1[q] = a.average ? 1.0 : a.edge_alpha[rr * a.k_max + e1];
+    }
+  }
+  issue_fence();
+
   int t = 0, j = -1, e0 = 0, e1 = 0;
   if (valid) {
     if (r < a.vis_begin) {
       t = r;
-    } else if (r < a.vis_begin + a.n_keep) {
+    } else if (kept_row) {
       j = r - a.vis_begin;
-      int tok = a.T[b * a.n_keep + j];
       tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
       t = a.vis_begin + tok;
       if (!MATCH && a.n_disc > 0) {
@@ -387,8 +412,6 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
         e0 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j], 0), a.n_disc * a.k_max);
         e1 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j + 1], e0), a.n_disc * a.k_max);
       }
-      if (lane == 0 && sub == 0 && d0 == 0 && a.pos_out)
-        a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
     } else {
       t = r + a.n_disc - (a.extra_row >= 0 ? 1 : 0);
     }
@@ -406,7 +429,23 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     for (int u = 0; u < SLICE; ++u)
       if (full[u]) load_raw(x + d0 + (u * kWave + lane) * kVec, xr[u]);
   }
+  if (MATCH && a.n_disc > 0) {
+#pragma unroll
+    for (int q = 0; q < kStage; ++q) {
+      // threads past the last row hold a second copy of it and store that: no branch around the
+      // use of what was loaded, so nothing stays "possibly in flight" for the code below
+      const int row = min((int)threadIdx.x + q * kMergeWaves * kWave, a.n_disc - 1);
+      tb.cnt[row] = min(st_cnt[q], a.k_max);
+      tb.src[row] = st_src[q];
+      tb.t0[row] = st_t0[q];
+      tb.t1[row] = st_t1[q];
+      tb.a0[row] = st_a0[q];
+      tb.a1[row] = st_a1[q];
+    }
+  }
+  DBG_PHASE(1);
   if (MATCH) __syncthreads();   // the edge table is complete (every wavefront arrives here)
+  DBG_PHASE(2);
   if (WPU == 1 && !valid) return 0;
 
   // this wavefront's part of the discarded rows
@@ -417,16 +456,38 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   int n_src = 0;
   bool long_bucket = false;
   if (valid && merged_row && MATCH) {
+    // The common search touches LDS only, so it runs while the row's own load is in flight (a
+    // global load inside this loop would make every pass wait for all loads issued before it).
+    // Rows with more than two targets are rare: if the image has any, the search is done again
+    // with the further pairs read from global memory.
+    bool any_more = false;
     for (int base = row_lo; base < row_hi; base += kWave) {
       const int row = base + lane;
       double w = 0.0;
-      const bool hit = row_names_target(a, tb, ebase, row, row < row_hi, j, w);
+      bool more;
+      const bool hit = row_names_target<false>(a, tb, ebase, row, row < row_hi, j, w, more);
+      any_more |= more;
       const unsigned long long m = __ballot(hit);
       if (hit) {
         const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
         if (slot < kCap) { l_src[slot] = tb.src[row]; l_w[slot] = w; }
       }
       n_src += __popcll(m);
+    }
+    if (__any(any_more)) {
+      n_src = 0;
+      for (int base = row_lo; base < row_hi; base += kWave) {
+        const int row = base + lane;
+        double w = 0.0;
+        bool more;
+        const bool hit = row_names_target<true>(a, tb, ebase, row, row < row_hi, j, w, more);
+        const unsigned long long m = __ballot(hit);
+        if (hit) {
+          const int slot = n_src + __popcll(m & ((1ULL << lane) - 1ULL));
+          if (slot < kCap) { l_src[slot] = tb.src[row]; l_w[slot] = w; }
+        }
+        n_src += __popcll(m);
+      }
     }
     if (WPU == 1 && n_src > kHubMin) return n_src;   // added by the whole workgroup, see merge_hub_targets
   } else if (valid && merged_row) {
@@ -478,6 +539,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
   }
 
+  DBG_PHASE(3);
   // ---- this wavefront's partial sum ----------------------------------------------------------------
   double num[SLICE][kVec];
   double den = sub == 0 ? 1.0 : 0.0;
@@ -496,6 +558,9 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
     return 0;
   }
+  // The row's own value is the first term of the sum.  Where a list follows, it is added after
+  // the loads of the list's first batch have been issued: the row's load (issued long ago) and
+  // those then share one wait instead of taking two memory round trips in a row.
   if (valid && sub == 0) {
 #pragma unroll
     for (int u = 0; u < SLICE; ++u) {
@@ -541,6 +606,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
   }
 
+  DBG_PHASE(4);
   // ---- parts added in order by wavefront 0 of the unit -----------------------------------------------
   if (WPU > 1) {
     if (sub > 0) {
@@ -636,7 +702,8 @@ __device__ __forceinline__ void merge_hub_targets(const MergeArgs& a, char* lds_
     for (int c0 = 0; c0 < a.n_disc; c0 += kChunk) {
       const int row = c0 + wv * kWave + lane;
       double w = 0.0;
-      const bool hit = row_names_target(a, tb, ebase, row, row < a.n_disc, j, w);
+      bool more;
+      const bool hit = row_names_target<true>(a, tb, ebase, row, row < a.n_disc, j, w, more);
       const unsigned long long m = __ballot(hit);
       if (lane == 0) hit_n[wv] = __popcll(m);
       __syncthreads();
@@ -702,6 +769,20 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   extern __shared__ __attribute__((aligned(16))) char lds_m[];
   const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m);
   if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
+  // position ids of the preserved tokens: written last, by one thread per output row of the
+  // workgroup (two dependent loads that nothing above should wait for)
+  if (WPU == 1 && a.pos_out && (int)threadIdx.x < kMergeWaves) {
+    constexpr int kSpan = kWave * kVec * SLICE;
+    const int n_spans = (a.D + kSpan - 1) / kSpan;
+    const int unit = blockIdx.x * kMergeWaves + threadIdx.x;
+    const int r = unit / n_spans;
+    const int64_t b = blockIdx.y;
+    if (unit % n_spans == 0 && r >= a.vis_begin && r < a.vis_begin + a.n_keep) {
+      const int j = r - a.vis_begin;
+      const int tok = min(max(a.T[b * a.n_keep + j], 0), a.N - 1);
+      a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
+    }
+  }
 }
 
 // The additional token of the "convergent" ablation: the plain mean of the discarded tokens.
@@ -756,7 +837,6 @@ __global__ __launch_bounds__(kExtraWaves * kWave) void extra_token_kernel(MergeA
   for (int k = 0; k < nd; ++k) store_token(out + k, acc[k] / cnt);
 }
 
-constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
 #ifndef FICOCO_MERGE_SLICE
 #define FICOCO_MERGE_SLICE 0          // 0: chosen per problem
 #endif
@@ -767,11 +847,11 @@ static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
   constexpr int kSpan = kWave * kVec * SLICE;
   const int n_spans = (m.D + kSpan - 1) / kSpan;
   const size_t lds = Lds::bytes(m.n_disc);
+  const int units = (WPU > 1 ? m.n_keep : m.n_out) * n_spans;   // long-bucket pass: at most every preserved token
+  dim3 grid((units + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
   if (lds > 32768)
     (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, MATCH, SLICE, WPU>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  const int units = (WPU > 1 ? m.n_keep : m.n_out) * n_spans;   // long-bucket pass: at most every preserved token
-  dim3 grid((units + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
   hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE, WPU>), grid, block, lds, s, m);
 }
 

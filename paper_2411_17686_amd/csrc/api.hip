@@ -17,6 +17,12 @@ struct ficoco_ctx {
 
 namespace ficoco {
 
+#ifndef FICOCO_MAP_ROW_LANES
+#define FICOCO_MAP_ROW_LANES 8
+#endif
+#ifndef FICOCO_MAP_ROWS_ALIGN
+#define FICOCO_MAP_ROWS_ALIGN 8
+#endif
 #ifndef FICOCO_WG_TARGET
 #define FICOCO_WG_TARGET 2048
 #endif
@@ -104,19 +110,27 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   // are a small share of the traffic).  From there the fewest strips that keep at least 80 %
   // of the threads busy, else the busiest of the next 8 choices.
   const int groups = (p.N + kVec - 1) / kVec;
+  // (with the head-mean map to store, strips stay narrow at any width: the workgroup turns its
+  // tile of the map in LDS, strip columns x chunk rows)
+  const bool map_tile = p.corr_src == FICOCO_C_ATTN;
   {
-    const int max_groups = groups <= 128 ? 24 : kReduceThreads;
+    const int max_groups = groups <= 128 ? 24 : (map_tile ? 32 : kReduceThreads);
     const int s_min = std::max((groups + kReduceThreads - 1) / kReduceThreads, (groups + max_groups - 1) / max_groups);
     int best_busy = -1;
     for (int sN = s_min; sN < s_min + 8; ++sN) {
       const int sg = (groups + sN - 1) / sN;
-      const int rl = kReduceThreads / sg;
+      int rl = kReduceThreads / sg;
+      if (map_tile && FICOCO_MAP_ROW_LANES > 0) rl = std::min(rl, FICOCO_MAP_ROW_LANES);
       if (rl * sg > best_busy) { best_busy = rl * sg; pl.col_strips = sN; pl.strip_groups = sg; pl.row_lanes = rl; }
       if (best_busy * 5 >= kReduceThreads * 4) break;
     }
   }
   auto rows_per_wg = [&](int rows) {
-    int64_t want = ((int64_t)p.B * pl.col_strips * rows + kWgTarget - 1) / kWgTarget;  // aim at ~kWgTarget workgroups
+    // aim at ~kWgTarget workgroups; half as many where the map tile is turned (longer chunks make
+    // whole cache lines of the transposed pieces, and a reduction that does not fill every
+    // wavefront slot leaves room for the short kernels of the neighbouring streams)
+    const int64_t target = map_tile ? kWgTarget / 2 : kWgTarget;
+    int64_t want = ((int64_t)p.B * pl.col_strips * rows + target - 1) / target;
     if (want < 1) want = 1;
     int r = (int)((want + pl.row_lanes - 1) / pl.row_lanes) * pl.row_lanes;
     return r;
@@ -133,7 +147,16 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
     pl.a_row0 = lo;
     pl.a_rows = hi - lo;
     pl.rows_per_wg = rows_per_wg(pl.a_rows);
-    pl.n_chunks = (pl.a_rows + pl.rows_per_wg - 1) / pl.rows_per_wg;
+    pl.a_shift = 0;
+    if (p.corr_src == FICOCO_C_ATTN && vis_rows) {
+      // The head-mean map is stored transposed, a chunk's rows of one key column as one piece:
+      // chunks of a multiple of 8 rows that start at multiples of it, counted from visual row 0,
+      // make every piece whole 32-byte sectors.
+      pl.rows_per_wg = std::min((pl.rows_per_wg + FICOCO_MAP_ROWS_ALIGN - 1) / FICOCO_MAP_ROWS_ALIGN * FICOCO_MAP_ROWS_ALIGN, 32);    // the tile is at most 256 columns x 32 rows
+      const int lead = (p.vis_begin - p.a_q_begin) - lo;             // role rows before visual row 0 (the [CLS] query)
+      pl.a_shift = (pl.rows_per_wg - lead % pl.rows_per_wg) % pl.rows_per_wg;
+    }
+    pl.n_chunks = (pl.a_rows + pl.a_shift + pl.rows_per_wg - 1) / pl.rows_per_wg;
   } else {
     pl.n_chunks = 0;
   }
@@ -166,7 +189,8 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   size_t off = 0;
   auto take = [&](size_t bytes) { size_t o = off; off += align_up(bytes ? bytes : 1); return o; };
   const size_t B = p.B, N = p.N;
-  pl.abar = take(p.corr_src == FICOCO_C_ATTN ? B * N * N * sizeof(float) : 0);
+  pl.map_pitch = (p.N + 63) / 64 * 64;     // whole 64-entry steps: a wavefront reads a row without clamping
+  pl.abar = take(p.corr_src == FICOCO_C_ATTN ? B * N * (size_t)pl.map_pitch * sizeof(float) : 0);
   pl.recv_part = take(B * (size_t)pl.n_chunks * N * sizeof(double));
   pl.cls = take(B * N * sizeof(double));
   pl.ttext = take(L ? B * N * (size_t)p.M * sizeof(double) : 0);
@@ -176,7 +200,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.colmean = take(pl.need_features ? (2 * B * (size_t)pl.Df + B * (size_t)((pl.Df + 255) / 256)) * sizeof(double) : 0);   // two means, then |mu|^2 in parts
   pl.fterm = take(B * N * sizeof(double));
   pl.fterm2 = take(B * N * sizeof(double));
-  pl.slot_of = take(B * N * sizeof(int32_t));
+  pl.slot_of = take((B * N + 64) * sizeof(int32_t));    // + one 64-entry step: rows of it are read in whole steps
   pl.tgt_ptr = take(B * (size_t)(p.n_keep + 1) * sizeof(int32_t));
   pl.tgt_src = take(B * (size_t)pl.n_disc * p.k_max * sizeof(int32_t));
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));

@@ -42,6 +42,8 @@ struct AttnArgs {
   double* cls;
   double* ttext;
   int rows_per_wg, n_chunks, row_lanes, strip_groups, col_strips, B;
+  int shift;          // rows by which chunk 0 is shortened (visual row 0 starts a chunk)
+  int map_pitch;      // floats per row of abar
   double invH;
 };
 
@@ -72,14 +74,20 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
     for (int k = 0; k < kVec; ++k) mine[k] = 0.0;
   }
 
+  // The head-mean map leaves transposed (abar[key token][query token], what the correlate stage
+  // reads row by row): this workgroup's tile, strip columns x chunk rows, is turned in LDS and
+  // written as one piece of rows_per_wg floats per key column.
+  float* tile = (float*)(lds + a.row_lanes * width);
+  const int tile_pitch = a.rows_per_wg + 1;           // odd: the 8 columns of a lane fall into different banks
+  const int r_begin = a.row0 + chunk * a.rows_per_wg - a.shift;   // chunk 0 may begin before row0
+  const int r_end = min(r_begin + a.rows_per_wg, a.row0 + a.nrows);
+
   if (active) {
-    const int r_begin = a.row0 + chunk * a.rows_per_wg;
-    const int r_end = min(r_begin + a.rows_per_wg, a.row0 + a.nrows);
     const T* Ab = (const T*)a.A + (int64_t)b * a.sb + a.col0 + col;
     for (int r = r_begin + rl; r < r_end; r += a.row_lanes) {
       const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
       const bool is_cls = r == a.cls_r;
-      if (!(is_vis || is_cls)) continue;
+      if (r < a.row0 || !(is_vis || is_cls)) continue;
       const T* base = Ab + (int64_t)r * a.sq;
       double p[kVec];
 #pragma unroll
@@ -111,15 +119,9 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
 #pragma unroll
         for (int k = 0; k < kVec; ++k) mine[k] += p[k];
         if (a.abar) {
-          float* dst = a.abar + ((int64_t)b * a.N + (r - a.vis_r0)) * a.N + col;
-          if (ncol == kVec) {
-            float4 lo = make_float4((float)p[0], (float)p[1], (float)p[2], (float)p[3]);
-            float4 hi = make_float4((float)p[4], (float)p[5], (float)p[6], (float)p[7]);
-            __builtin_memcpy(dst, &lo, 16);
-            __builtin_memcpy(dst + 4, &hi, 16);
-          } else {
-            for (int k = 0; k < ncol; ++k) dst[k] = (float)p[k];
-          }
+          float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) dst[k * tile_pitch] = (float)p[k];   // columns past N are never read back
         }
       }
       if (is_cls) {
@@ -129,9 +131,30 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
     }
   }
 
+  __syncthreads();
+  if (a.abar) {
+    // pieces of 4 query rows: thread -> (key column of the strip, piece), consecutive threads
+    // on consecutive pieces of one column
+    const int v_begin = r_begin - a.vis_r0;                 // query token of tile row 0 (a multiple of rows_per_wg, or negative)
+    const int v_end = min(r_end - a.vis_r0, a.n_vis);       // query tokens of this chunk end here
+    const int pieces = a.rows_per_wg / 4;
+    const int strip_col0 = strip * width;
+    const int n_cols = min(width, a.N - strip_col0);
+    for (int q = tid; q < n_cols * pieces; q += (int)blockDim.x) {
+      const int c = q / pieces, v0 = (q % pieces) * 4;
+      const float* src = tile + c * tile_pitch + v0;
+      float* dst = a.abar + ((int64_t)b * a.N + strip_col0 + c) * a.map_pitch + v_begin + v0;
+      if (v_begin + v0 >= 0 && v_begin + v0 + 4 <= v_end) {
+        const float4 o = make_float4(src[0], src[1], src[2], src[3]);
+        __builtin_memcpy(dst, &o, 16);
+      } else {
+        for (int e = 0; e < 4; ++e)
+          if (v_begin + v0 + e >= 0 && v_begin + v0 + e < v_end) dst[e] = src[e];
+      }
+    }
+  }
   if (a.recv_part == nullptr) return;  // uniform for the whole grid
   // Combine the row lanes in a fixed order, then one partial per (image, chunk, column).
-  __syncthreads();
   if (rl == 0 && ncol > 0) {
     double* dst = a.recv_part + ((int64_t)b * a.n_chunks + chunk) * a.N + col;
     for (int k = 0; k < ncol; ++k) {
@@ -206,8 +229,9 @@ __global__ __launch_bounds__(256) void text_reduce_kernel(AttnArgs a) {
 static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hipStream_t s) {
   AttnArgs g = a;
   g.col_strips = col_strips; g.B = B;
-  dim3 grid(xcd_padded_total(a.n_chunks * col_strips * B)), block(kReduceThreads);
+  dim3 grid(xcd_padded_total(a.n_chunks * col_strips * B)), block(std::min(kReduceThreads, (a.row_lanes * a.strip_groups + kWave - 1) / kWave * kWave));
   size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
+  if (a.abar) lds += (size_t)a.strip_groups * kVec * (a.rows_per_wg + 1) * sizeof(float);   // the tile that is turned
   if (lds < (size_t)FICOCO_REDUCE_LDS_MIN) lds = FICOCO_REDUCE_LDS_MIN;
   if (bf16)
     hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, g);
@@ -236,6 +260,7 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
     a.cls = (double*)(ws + pl.cls);
     a.ttext = nullptr;
     a.rows_per_wg = pl.rows_per_wg; a.n_chunks = pl.n_chunks;
+    a.shift = pl.a_shift; a.map_pitch = pl.map_pitch;
     a.row_lanes = pl.row_lanes; a.strip_groups = pl.strip_groups;
     a.invH = 1.0 / (double)p.H;
     launch_block(a, p.B, pl.col_strips, bf16, s);

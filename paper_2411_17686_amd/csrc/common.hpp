@@ -32,6 +32,8 @@ struct Plan {
   int rows_per_wg;       // visual-block rows per workgroup
   int n_chunks;          // row chunks of the A block (partials of the received attention)
   int a_row0, a_rows;    // rows of A that carry a role (first, count)
+  int a_shift;           // rows by which the first chunk is shortened so that visual row 0 starts a chunk
+  int map_pitch;         // floats per row of the head-mean map (N rounded up to 64: read in whole 64-entry steps)
   int t_rows_per_wg, t_chunks;
   // threshold selection
   int sel_m;             // order statistics needed: n_keep - floor(eps (n_keep-1))
@@ -39,7 +41,7 @@ struct Plan {
   double sel_g;          // fractional part of p
   bool dense_rows;       // sel_m > kSelMax: rows are materialised and selected bit by bit
   bool need_features;    // unit rows / norms
-  size_t abar;           // float  [B][N][N]      head-mean visual x visual map
+  size_t abar;           // float  [B][N][map_pitch]  head-mean visual x visual map, TRANSPOSED: [key token][query token]
   size_t recv_part;      // double [B][n_chunks][N]
   size_t cls;            // double [B][N]
   size_t ttext;          // double [B][N][M]      head-mean text->visual map, transposed

@@ -19,7 +19,8 @@ enum CorrMode { kAttnV = 0, kAttnL = 1, kCosV = 2, kCosL = 3 };
 
 struct CorrArgs {
   int B, N, n_keep, n_disc, M, k_max, Df, mode;
-  const float* abar;     // [B][N][N]
+  const float* abar;     // [B][N][map_pitch] head-mean map, transposed: abar[b][key token i][query token j]
+  int map_pitch;
   const double* ttext;   // [B][N][M]
   const bf16_t* xhat;    // [B][N][Df]
   double gamma, invM;
@@ -61,7 +62,7 @@ __device__ __forceinline__ double dot_bf16(const bf16_t* __restrict__ x, const b
 __device__ __forceinline__ double corr_value(const CorrArgs& a, int64_t b, int i, int j) {
   double direct;
   if (a.mode == kAttnV || a.mode == kAttnL) {
-    direct = (double)a.abar[(b * a.N + j) * a.N + i];
+    direct = (double)a.abar[(b * a.N + i) * a.map_pitch + j];
   } else {
     const double d = dot_bf16(a.xhat + (b * a.N + i) * a.Df, a.xhat + (b * a.N + j) * a.Df, a.Df);
     direct = d > 0.0 ? d : 0.0;
@@ -274,7 +275,7 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 __device__ __forceinline__ double corr_value_wave(const CorrArgs& a, int64_t b, int i, int j, int lane) {
   double direct;
   if (a.mode == kAttnL) {
-    direct = (double)a.abar[(b * a.N + j) * a.N + i];
+    direct = (double)a.abar[(b * a.N + i) * a.map_pitch + j];
   } else {
     const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
     const bf16_t* y = a.xhat + (b * a.N + j) * a.Df;
@@ -343,7 +344,7 @@ __device__ __forceinline__ void corr_values_wave(const CorrArgs& a, int64_t b, i
   double direct[CB];
   if (a.mode == kAttnL) {
 #pragma unroll
-    for (int q = 0; q < CB; ++q) direct[q] = (double)a.abar[(b * a.N + j[q]) * a.N + i];
+    for (int q = 0; q < CB; ++q) direct[q] = (double)a.abar[(b * a.N + i) * a.map_pitch + j[q]];
   } else {
     const bf16_t* x = a.xhat + (b * a.N + i) * a.Df;
     const bf16_t* y[CB];
@@ -428,9 +429,9 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
     return;
   }
   // approximate direct term of the row: the matrix-core cosines, or (FiCoCo-L with the
-  // attention correlation) the exact head-mean map gathered by column, delta = 0
+  // attention correlation) the token's row of the exact head-mean map, delta = 0
   const bool from_map = a.mode == kAttnL;
-  const float* ct = from_map ? a.abar + b * a.N * (int64_t)a.N + i : a.ct + (b * a.n_disc + row) * n;
+  const float* ct = from_map ? a.abar + (b * a.N + i) * a.map_pitch : a.ct + (b * a.n_disc + row) * n;
   const bool L = a.mode == kCosL || a.mode == kAttnL;
   const float gam = L ? (float)a.gamma : 1.0f;
   float extra = 0.0f;                      // upper bound of (1 - gamma) * indirect term of this row
@@ -460,7 +461,7 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
       for (int u = 0; u < kCandKeep; ++u) {
         const bool ok = (unsigned)jt[u] < (unsigned)a.N;
         float v = 0.0f;
-        if (u < n_u) v = ct[(int64_t)(ok ? jt[u] : 0) * a.N];
+        if (u < n_u) v = ct[ok ? jt[u] : 0];
         val[u] = c0 + u * kWave + lane < n ? (ok ? v : 0.0f) : NEGF;
       }
     } else {
@@ -624,215 +625,154 @@ __global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
   }
 }
 
-// ---- FiCoCo-V attention correlation, tiled ----------------------------------------------------
-// The generic kernel above gathers one column of the row-major head-mean map per wavefront
-// (64 different rows per load).  For the plain attention correlation of Algorithm 1 this
-// tile kernel is used instead: a workgroup owns kTileCols discarded columns, thread
-// (c, jl) scans rows T[jl], T[jl + kTileLanes], ... of column S[c], so the threads of one
-// row read neighbouring columns of the same row.  Loads are issued in independent batches
-// (a dependent global load costs about a microsecond).  Each thread keeps its kSelMax
-// largest (value, target) pairs; LDS merges them per column into v[f], v[f+1] and tau; the
-// targets at or above tau are then taken from the per-thread lists (a thread whose whole
-// list is at or above tau re-reads its part of the column instead).
-constexpr int kTileCols = 8;
-constexpr int kTileLanes = 32;
-constexpr int kTileBatch = 24;
-constexpr int kHitCap = 64;
-
-// Reductions over the kTileLanes threads that share a column: lanes c, c+8, ... of each
-// wavefront by xor-shuffles, then the four wavefronts through a double-buffered LDS slot.
-__device__ __forceinline__ float col_max(float v, float (*red)[4][kTileCols], int& phase, int wv, int c) {
-#pragma unroll
-  for (int off = kTileCols; off < kWave; off <<= 1) { const float o = __shfl_xor(v, off, kWave); v = o > v ? o : v; }
-  red[phase][wv][c] = v;
-  __syncthreads();
-  float r = red[phase][0][c];
-#pragma unroll
-  for (int w = 1; w < 4; ++w) { const float o = red[phase][w][c]; r = o > r ? o : r; }
-  phase ^= 1;
-  return r;
-}
-__device__ __forceinline__ int col_sum(int v, int (*red)[4][kTileCols], int& phase, int wv, int c) {
-#pragma unroll
-  for (int off = kTileCols; off < kWave; off <<= 1) v += __shfl_xor(v, off, kWave);
-  red[phase][wv][c] = v;
-  __syncthreads();
-  int r = 0;
-#pragma unroll
-  for (int w = 0; w < 4; ++w) r += red[phase][w][c];
-  phase ^= 1;
-  return r;
-}
-
-// MC = (value, target) pairs kept per thread (>= sel_m; 2, 4 or 8).
-template <int MC>
-__global__ __launch_bounds__(kTileCols * kTileLanes) void corr_attn_tile_kernel(CorrArgs a) {
+// ---- FiCoCo-V attention correlation ------------------------------------------------------------
+// C[i][j] = Pbar[j][i] (Algorithm 1, stage 2).  The head-mean map is stored transposed, so the
+// values of discarded token i are one contiguous row; slot_of tells which of its entries belong
+// to preserved tokens.  One wavefront per discarded token: a first pass keeps each lane's MC
+// largest values, the m-th and (m-1)-th largest of the row (with multiplicity) are popped off
+// the lanes' lists, and a second pass over the row (a cache hit) emits the targets at or above
+// the threshold in ascending order.  Values are compared as the floats they are stored as.
+// kRowBatch = 64-entry steps of the row loaded together; a row that fits one batch stays in
+// registers for the second pass (10 steps: the 576-token grid).  Longer rows take batches of
+// kRowWide steps (measured at 2880 tokens: 16 is as good as 24, and 48 -- the whole row in
+// registers, at a quarter of the resident wavefronts -- is slower).
+#ifndef FICOCO_CORR_WIDE
+#define FICOCO_CORR_WIDE 16
+#endif
+constexpr int kRowWide = FICOCO_CORR_WIDE;
+template <int MC, int kRowBatch>
+__global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
   DBG_SPAN(2);
-  static_assert(kTileCols * kTileLanes == 4 * kWave, "four wavefronts per tile");
-  __shared__ float redf[2][4][kTileCols];
-  __shared__ int redi[2][4][kTileCols];
-  __shared__ int hit_cnt[kTileCols];
-  __shared__ int hit_j[kTileCols][kHitCap];
-  __shared__ float hit_v[kTileCols][kHitCap];
-  const int tid = threadIdx.x;
-  const int c = tid % kTileCols, jl = tid / kTileCols, wv = tid / kWave;
-  const int tiles = (a.n_disc + kTileCols - 1) / kTileCols;
-  const int logical = xcd_logical_id(blockIdx.x, tiles * a.B);
-  if (logical >= tiles * a.B) return;                 // padding workgroup (whole block leaves)
-  const int64_t b = logical / tiles;
-  const int row = (logical % tiles) * kTileCols + c;
-  int i = row < a.n_disc ? a.S[b * a.n_disc + row] : -1;
-  const bool valid = (unsigned)i < (unsigned)a.N;   // index sets are device data
-  if (!valid) i = 0;
-  const float* col = a.abar + b * a.N * (int64_t)a.N + i;
+  const int lane = threadIdx.x % kWave;
+  const int row = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  const int64_t b = blockIdx.y;
+  if (row >= a.n_disc) return;                 // whole wavefront leaves together
+  const int i = a.S[b * a.n_disc + row];
+  if ((unsigned)i >= (unsigned)a.N) {          // index sets are device data
+    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    return;
+  }
+  const float* mrow = a.abar + (b * a.N + i) * a.map_pitch;
   const int32_t* slot_of = a.slot_of + b * a.N;
   const float NEGF = -__builtin_huge_valf();
-  if (jl == 0) hit_cnt[c] = 0;
 
-  // Either scan ALL visual rows of the column and take the preserved ones (slot_of >= 0):
-  // the value and the slot are independent loads, so one round trip serves a whole batch --
-  // or, when fewer than half of the tokens are preserved, walk the preserved list (one more
-  // dependent round trip, far fewer rows).
-  const bool by_list = 2 * a.n_keep < a.N;
-  const int n_scan = by_list ? a.n_keep : a.N;
-  const int32_t* Tl = a.T + b * a.n_keep;
-  float top[MC];
-  int topj[MC];
+  // One batch of the row: entry u of a lane is query token r0 + 64 u + lane; entries past the
+  // row or of discarded tokens read as -inf with slot -1.
+  float vv[kRowBatch];
+  int sv[kRowBatch];
+  auto load_batch = [&](int r0) {
+    // Rows of the map are padded to whole 64-entry steps and the slot table by one step, so the
+    // steps that begin inside the row are read as they are (one address, constant offsets) and
+    // masked below; steps that begin past the row are skipped.
+    const int n_u = min(kRowBatch, (a.N - r0 + kWave - 1) / kWave);      // steps of this batch that begin inside the row
+    const float* mp = mrow + r0 + lane;
+    const int32_t* sp = slot_of + r0 + lane;
 #pragma unroll
-  for (int k = 0; k < MC; ++k) { top[k] = NEGF; topj[k] = -1; }
-  for (int r0 = jl; r0 < n_scan; r0 += kTileLanes * kTileBatch) {
-    float vv[kTileBatch];
-    int sv[kTileBatch];
-    if (by_list) {
-      int rr[kTileBatch];
-#pragma unroll
-      for (int u = 0; u < kTileBatch; ++u) {
-        const int jj = min(r0 + u * kTileLanes, n_scan - 1);  // clamped: always a valid address
-        rr[u] = Tl[jj];
-        sv[u] = jj;
-      }
-#pragma unroll
-      for (int u = 0; u < kTileBatch; ++u) {
-        const bool in = (unsigned)rr[u] < (unsigned)a.N;       // index sets are device data
-        vv[u] = col[(int64_t)(in ? rr[u] : 0) * a.N];
-        if (!in) sv[u] = -1;
-      }
-    } else {
-#pragma unroll
-      for (int u = 0; u < kTileBatch; ++u) {
-        const int r = min(r0 + u * kTileLanes, a.N - 1);     // clamped: always a valid address
-        vv[u] = col[(int64_t)r * a.N];
-        sv[u] = slot_of[r];
+    for (int u = 0; u < kRowBatch; ++u) {
+      vv[u] = 0.0f;
+      sv[u] = -1;
+      if (u < n_u) {                                       // uniform (a scalar branch): nothing is read past the row's last step
+        vv[u] = mp[u * kWave];
+        sv[u] = sp[u * kWave];
       }
     }
-#pragma unroll 4
-    for (int u = 0; u < kTileBatch; ++u) {
-      const bool ok = valid && r0 + u * kTileLanes < n_scan && sv[u] >= 0;
-      float v = ok ? vv[u] : NEGF;
-      int jq = sv[u];
+    issue_fence();
+#pragma unroll
+    for (int u = 0; u < kRowBatch; ++u) {
+      const bool ok = r0 + u * kWave + lane < a.N && sv[u] >= 0;
+      vv[u] = ok ? vv[u] : NEGF;
+      sv[u] = ok ? sv[u] : -1;
+    }
+  };
+
+  float top[MC];
+#pragma unroll
+  for (int k = 0; k < MC; ++k) top[k] = NEGF;
+  for (int r0 = 0; r0 < a.N; r0 += kRowBatch * kWave) {
+    load_batch(r0);
+#pragma unroll
+    for (int u = 0; u < kRowBatch; ++u) {
+      float v = vv[u];
 #pragma unroll
       for (int k = 0; k < MC; ++k) {
         const bool sw = v > top[k];
-        const float tv = top[k];
-        const int tj = topj[k];
-        top[k] = sw ? v : tv;
-        topj[k] = sw ? jq : tj;
-        v = sw ? tv : v;
-        jq = sw ? tj : jq;
+        const float t = top[k];
+        top[k] = sw ? v : t;
+        v = sw ? t : v;
       }
     }
   }
-  // v[f] and v[f+1] = the m-th and (m-1)-th largest of the column, counted with
-  // multiplicity: walk the distinct values from the top (at most m of them).
+  // v[f], v[f+1]: pop the wavefront maximum m times (MC >= m, so one lane may hold them all)
   float vf = NEGF, vf1 = NEGF;
-  int n_gt = 0;                                // values strictly above vf
-  {
-    int phase = 0, taken = 0;
-    float cur = __builtin_huge_valf();
-    const int m = a.sel_m;
-    for (int it = 0; it < m; ++it) {          // uniform trip count: the reductions hold barriers
-      float lm = NEGF;
+  int n_gt = 0;                                // pops strictly above vf
+  for (int r = 0; r < a.sel_m; ++r) {
+    float mx = top[0];
 #pragma unroll
-      for (int k = 0; k < MC; ++k) lm = (top[k] < cur && top[k] > lm) ? top[k] : lm;
-      const float nxt = col_max(lm, redf, phase, wv, c);
-      int lc = 0;
+    for (int off = 32; off > 0; off >>= 1) { const float o = __shfl_xor(mx, off, kWave); mx = o > mx ? o : mx; }
+    const unsigned long long who = __ballot(top[0] == mx);
+    if (lane == __ffsll(who) - 1) {
 #pragma unroll
-      for (int k = 0; k < MC; ++k) lc += top[k] == nxt ? 1 : 0;
-      const int cnt = col_sum(lc, redi, phase, wv, c);
-      if (taken <= m - 1 && m - 1 < taken + cnt) { vf = nxt; n_gt = taken; }
-      if (m >= 2 && taken <= m - 2 && m - 2 < taken + cnt) vf1 = nxt;
-      taken += cnt;
-      cur = nxt;
+      for (int k = 0; k + 1 < MC; ++k) top[k] = top[k + 1];
+      top[MC - 1] = NEGF;
     }
+    if (r == 0 || mx < vf) n_gt = r;
+    vf1 = vf;
+    vf = mx;
   }
   if (a.sel_m == 1) vf1 = vf;
-  __syncthreads();
-  if (valid) {
-    const double tau = threshold_of((double)vf, (double)vf1, a.sel_g);
-    if ((double)top[MC - 1] >= tau) {
-      // the whole list qualifies, so more may: take this thread's part of the column again
-      for (int q = jl; q < n_scan; q += kTileLanes) {
-        int r = q, sj;
-        if (by_list) { r = Tl[q]; sj = (unsigned)r < (unsigned)a.N ? q : -1; }
-        else sj = slot_of[r];
-        if (sj < 0) continue;
-        const float v = col[(int64_t)r * a.N];
-        if ((double)v >= tau) {
-          const int slot = atomicAdd(&hit_cnt[c], 1);
-          if (slot < kHitCap) { hit_j[c][slot] = sj; hit_v[c][slot] = v; }
-        }
-      }
-    } else {
+  const double tau = threshold_of((double)vf, (double)vf1, a.sel_g);
+  const int tie_quota = a.fixed_k > 0 ? a.sel_m - n_gt : 0x7fffffff;   // values equal to tau that are taken
+  int ties_seen = 0;
+  // a float at or below tau: v >= tau_below is a cheap necessary condition for (double)v >= tau
+  float tau_below = (float)tau;
+  if ((double)tau_below > tau) {             // rounded up: step to the next float below (finite here)
+    const uint32_t u = __float_as_uint(tau_below);
+    tau_below = tau_below > 0.0f ? __uint_as_float(u - 1u) : (tau_below < 0.0f ? __uint_as_float(u + 1u) : -1.401298464e-45f);
+  }
+
+  // Emit the targets in ascending order; lane e ends up holding edge e (k_max <= 64 on this path).
+  int cnt = 0;
+  double denom = 0.0;
+  int my_tgt = -1;
+  double my_c = 0.0;
+  for (int r0 = 0; r0 < a.N; r0 += kRowBatch * kWave) {
+    if (a.N > kRowBatch * kWave || r0 > 0) load_batch(r0);     // a row of one batch is still in registers
+    bool some = false;                                           // most batches hold no target at all
 #pragma unroll
-      for (int k = 0; k < MC; ++k)
-        if ((double)top[k] >= tau) {
-          const int slot = atomicAdd(&hit_cnt[c], 1);
-          if (slot < kHitCap) { hit_j[c][slot] = topj[k]; hit_v[c][slot] = top[k]; }
-        }
+    for (int u = 0; u < kRowBatch; ++u) some |= sv[u] >= 0 && vv[u] >= tau_below;
+    if (!__any(some)) continue;
+#pragma unroll
+    for (int u = 0; u < kRowBatch; ++u) {
+      if (r0 + u * kWave >= a.N) break;                          // uniform; nothing is loaded past this point
+      const double c = (double)vv[u];
+      const bool in = sv[u] >= 0;
+      const bool is_eq = in && c == tau;
+      const unsigned long long eqm = __ballot(is_eq);
+      const int eq_rank = ties_seen + __popcll(eqm & ((1ULL << lane) - 1ULL));
+      ties_seen += __popcll(eqm);
+      unsigned long long hit = __ballot(in && (c > tau || (is_eq && eq_rank < tie_quota)));
+      while (hit) {
+        const int l = __ffsll(hit) - 1;
+        hit &= hit - 1;
+        const double cl = __shfl(c, l, kWave);
+        const int tl = __shfl(sv[u], l, kWave);
+        denom += cl;
+        if (lane == cnt) { my_tgt = tl; my_c = cl; }
+        ++cnt;
+      }
     }
   }
-  __syncthreads();
-  if (jl == 0 && row < a.n_disc) {
-    const int cnt = valid ? hit_cnt[c] : 0;
-    const int have = cnt < kHitCap ? cnt : kHitCap;
-    for (int x = 1; x < have; ++x) {          // ascending target slot (arrival order is arbitrary)
-      const int jx = hit_j[c][x];
-      const float vx = hit_v[c][x];
-      int y = x - 1;
-      while (y >= 0 && hit_j[c][y] > jx) { hit_j[c][y + 1] = hit_j[c][y]; hit_v[c][y + 1] = hit_v[c][y]; --y; }
-      hit_j[c][y + 1] = jx;
-      hit_v[c][y + 1] = vx;
-    }
-    int kept = have, total = cnt;
-    if (a.fixed_k > 0) {
-      // fixed K: of the values equal to the threshold only the lowest positions, K targets in all
-      const float tauf = vf;                   // sel_g = 0: the threshold is v[f] itself
-      int quota = a.sel_m - n_gt;
-      kept = 0;
-      for (int x = 0; x < have; ++x) {
-        const bool gt = hit_v[c][x] > tauf;
-        if (gt || quota > 0) {
-          if (!gt) --quota;
-          hit_j[c][kept] = hit_j[c][x];
-          hit_v[c][kept] = hit_v[c][x];
-          ++kept;
-        }
-      }
-      total = cnt > kHitCap ? cnt : kept;      // more hits than the list holds: reported as overflow
-    }
-    double denom = 0.0;
-    for (int x = 0; x < kept; ++x) denom += (double)hit_v[c][x];
-    const bool live = denom > 0.0;
-    const int stored = kept < a.k_max ? kept : a.k_max;
-    const int64_t ebase = (b * a.n_disc + row) * a.k_max;
-    if (live)
-      for (int x = 0; x < stored; ++x) {
-        const double al = (double)hit_v[c][x] / denom;
-        a.edge_tgt[ebase + x] = hit_j[c][x];
-        a.edge_alpha[ebase + x] = al;
-      }
+  const int stored = cnt < a.k_max ? cnt : a.k_max;
+  const bool live = denom > 0.0;
+  const int64_t ebase = (b * a.n_disc + row) * a.k_max;
+  if (live && lane < stored) {
+    const double al = my_c / denom;
+    a.edge_tgt[ebase + lane] = my_tgt;
+    a.edge_alpha[ebase + lane] = al;
+  }
+  if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
-    if (live && total > a.k_max) a.overflow[b] = 1;
+    if (live && cnt > a.k_max) a.overflow[b] = 1;
   }
 }
 
@@ -885,6 +825,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   const bool L = p.variant == FICOCO_VARIANT_L;
   a.mode = p.corr_src == FICOCO_C_ATTN ? (L ? kAttnL : kAttnV) : (L ? kCosL : kCosV);
   a.abar = (const float*)(ws + pl.abar);
+  a.map_pitch = pl.map_pitch;
   a.ttext = (const double*)(ws + pl.ttext);
   a.xhat = (const bf16_t*)(ws + pl.xhat);
   a.gamma = (double)p.gamma;
@@ -900,16 +841,20 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.fixed_k = pl.fixed_k;
   a.ct_splits = pl.gram_splits;
   a.delta = (float)(pl.Df + 4 * pl.gram_splits) * 2.384185791015625e-07f;   // (Df + 4 splits) * 2^-22
-  if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kHitCap) {
-    const int tiles = (pl.n_disc + kTileCols - 1) / kTileCols;
-    dim3 tgrid(xcd_padded_total(tiles * p.B));
-    const dim3 tb(kTileCols * kTileLanes);
-    if (pl.sel_m <= 2) hipLaunchKernelGGL(corr_attn_tile_kernel<2>, tgrid, tb, 0, s, a);
-    else if (pl.sel_m <= 4) hipLaunchKernelGGL(corr_attn_tile_kernel<4>, tgrid, tb, 0, s, a);
-    else hipLaunchKernelGGL(corr_attn_tile_kernel<8>, tgrid, tb, 0, s, a);
+  dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
+  if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kWave) {
+    const bool wide = p.N > 10 * kWave;     // longer rows: wider batches (fewer dependent trips to memory)
+    if (wide) {
+      if (pl.sel_m <= 2) hipLaunchKernelGGL((corr_attn_rows_kernel<2, kRowWide>), grid, block, 0, s, a);
+      else if (pl.sel_m <= 4) hipLaunchKernelGGL((corr_attn_rows_kernel<4, kRowWide>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((corr_attn_rows_kernel<8, kRowWide>), grid, block, 0, s, a);
+    } else {
+      if (pl.sel_m <= 2) hipLaunchKernelGGL((corr_attn_rows_kernel<2, 10>), grid, block, 0, s, a);
+      else if (pl.sel_m <= 4) hipLaunchKernelGGL((corr_attn_rows_kernel<4, 10>), grid, block, 0, s, a);
+      else hipLaunchKernelGGL((corr_attn_rows_kernel<8, 10>), grid, block, 0, s, a);
+    }
     return;
   }
-  dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
   if (a.mode == kAttnL && !pl.dense_rows && p.k_max <= 64) {
     hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
@@ -937,6 +882,7 @@ void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const in
   const bool L = p.variant == FICOCO_VARIANT_L;
   a.mode = p.corr_src == FICOCO_C_ATTN ? (L ? kAttnL : kAttnV) : (L ? kCosL : kCosV);
   a.abar = (const float*)(ws + pl.abar);
+  a.map_pitch = pl.map_pitch;
   a.ttext = (const double*)(ws + pl.ttext);
   a.xhat = (const bf16_t*)(ws + pl.xhat);
   a.gamma = (double)p.gamma;

@@ -84,7 +84,7 @@ def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src
     sv = dev(cfg.get("sem_vec")) if sem_src == fc.G_VECTOR else None
     Fd = dev(F)
     p = fc.make_problem(
-        Xd, variant=fc.VARIANT_V, vis_begin=cfg["vis_begin"], N=Xd.shape[1] - cfg["vis_begin"],
+        Xd, variant=fc.VARIANT_V, vis_begin=cfg["vis_begin"], N=Xd.shape[1] - cfg["vis_begin"] - cfg.get("tail", 0),
         n_keep=cfg["n_keep"] if n_keep is None else n_keep, A=Ad, cls_index=cfg["cls_index"],
         recv_vec=rv, sem_vec=sv, F=Fd, pos=posd, grid=cfg["grid"], window=cfg["window"] if window is None else window,
         penalty_coef=cfg["coef"], w_score=cfg["lam"], eps=cfg["eps"] if eps is None else eps,
@@ -117,7 +117,7 @@ def oracle_v(cfg, A, b, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV,
              k_mode=fc.K_ADAPTIVE, fixed_k=0, compress_mode=fc.COMPRESS_SELF):
     X = cfg["X"] if X is None else X
     Xb = O.widen(to_numpy(X[b]))
-    N = Xb.shape[0] - cfg["vis_begin"]
+    N = Xb.shape[0] - cfg["vis_begin"] - cfg.get("tail", 0)     # "tail": tokens behind the visual span
     return O.v_step(
         Xb, None if A is None else O.widen(to_numpy(A[b])), cls_index=cfg["cls_index"],
         vis_begin=cfg["vis_begin"], N=N, n_keep=cfg["n_keep"] if n_keep is None else n_keep,

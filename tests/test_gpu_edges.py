@@ -107,3 +107,26 @@ def test_target_named_by_most_discarded_tokens(ctx, grid, D, n_keep, B, dtype, i
         P.compare_image(out, b, ref, dtype, cfg["vis_begin"], True)
         named = np.concatenate([out["tgt"][b, a, :out["cnt"][b, a]] for a in range(n_disc)])
         assert np.bincount(named).max() > n_disc // 2, "the case no longer builds a hub"
+
+
+@pytest.mark.parametrize("vis_begin,cls_at,grid,n_keep", [
+    (2, "end", 9, 40),      # two prefix tokens, patches, [CLS] last: the [CLS] row follows the visual rows
+    (3, "start", 10, 37),   # [CLS], two register tokens, patches: three rows precede visual row 0
+    (0, "end", 13, 100),    # patches first, [CLS] last, 169 tokens (no multiple of 8)
+])
+def test_token_layouts_around_the_visual_span(ctx, vis_begin, cls_at, grid, n_keep):
+    """Where [CLS] and other non-visual tokens sit decides how the reduction cuts the query rows
+    into chunks (the chunk grid is anchored at visual row 0 for the transposed map)."""
+    g = torch.Generator().manual_seed(300 + grid)
+    N = grid * grid
+    n_tot = vis_begin + N + (1 if cls_at == "end" else 0)
+    cls_index = n_tot - 1 if cls_at == "end" else 0
+    B, H, D = 2, 3, 40
+    X = torch.randn(B, n_tot, D, generator=g)
+    A = torch.softmax(2.0 * torch.randn(B, H, n_tot, n_tot, generator=g), dim=-1)
+    for dtype in ("f32", "bf16"):
+        cfg = dict(X=synth._cast(X, dtype), A=synth._cast(A, dtype), B=B, H=H, D=D, n_tot=n_tot, vis_begin=vis_begin,
+                   N=N, cls_index=cls_index, n_keep=n_keep, dtype=dtype, grid=(1, grid, grid), window=2,
+                   coef=2.0, lam=0.35, eps=0.998, tail=n_tot - vis_begin - N)
+        _check(cfg, ctx)
+        _check(cfg, ctx, k_mode=fc.K_FIXED, fixed_k=2)

@@ -17,12 +17,11 @@ struct ficoco_ctx {
 
 namespace ficoco {
 
-#ifndef FICOCO_MAP_ROW_LANES
-#define FICOCO_MAP_ROW_LANES 8
-#endif
-#ifndef FICOCO_MAP_ROWS_ALIGN
-#define FICOCO_MAP_ROWS_ALIGN 8
-#endif
+// With the head-mean map to store, a reduction workgroup has at most 8 row lanes and chunks of a
+// multiple of 8 rows (measured at the 576-token batched shape: 8 lanes x 32 rows, ~900 workgroups,
+// gives the best pipelined step; 10 lanes x 24 rows is 10 % slower alone).
+constexpr int kMapRowLanes = 8;
+constexpr int kMapRowsAlign = 8;
 #ifndef FICOCO_WG_TARGET
 #define FICOCO_WG_TARGET 2048
 #endif
@@ -104,11 +103,11 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
 
   // attention reduction geometry
   // Column strips.  Up to 1024 key columns a strip has at most 24 8-column groups: a workgroup
-  // is then (row lanes) x (groups of the strip) with ten or more row lanes, covers many query
-  // rows and leaves few per-chunk column partials behind (measured: 3 strips of 24 groups beat
-  // 1 strip of 72 at 576 columns by 4 %; at 2880 columns wide strips stay ahead, their partials
-  // are a small share of the traffic).  From there the fewest strips that keep at least 80 %
-  // of the threads busy, else the busiest of the next 8 choices.
+  // is then (row lanes) x (groups of the strip) with several row lanes, covers many query rows
+  // and leaves few per-chunk column partials behind (measured: 3 strips of 24 groups beat 1 strip
+  // of 72 at 576 columns by 4 %).  Wider maps without a head-mean map to store take wide strips
+  // (their partials are a small share of the traffic).  From there the fewest strips that keep at
+  // least 80 % of the threads busy, else the busiest of the next 8 choices.
   const int groups = (p.N + kVec - 1) / kVec;
   // (with the head-mean map to store, strips stay narrow at any width: the workgroup turns its
   // tile of the map in LDS, strip columns x chunk rows)
@@ -120,7 +119,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
     for (int sN = s_min; sN < s_min + 8; ++sN) {
       const int sg = (groups + sN - 1) / sN;
       int rl = kReduceThreads / sg;
-      if (map_tile && FICOCO_MAP_ROW_LANES > 0) rl = std::min(rl, FICOCO_MAP_ROW_LANES);
+      if (map_tile) rl = std::min(rl, kMapRowLanes);
       if (rl * sg > best_busy) { best_busy = rl * sg; pl.col_strips = sN; pl.strip_groups = sg; pl.row_lanes = rl; }
       if (best_busy * 5 >= kReduceThreads * 4) break;
     }
@@ -152,17 +151,13 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
       // The head-mean map is stored transposed, a chunk's rows of one key column as one piece:
       // chunks of a multiple of 8 rows that start at multiples of it, counted from visual row 0,
       // make every piece whole 32-byte sectors.
-      pl.rows_per_wg = std::min((pl.rows_per_wg + FICOCO_MAP_ROWS_ALIGN - 1) / FICOCO_MAP_ROWS_ALIGN * FICOCO_MAP_ROWS_ALIGN, 32);    // the tile is at most 256 columns x 32 rows
+      pl.rows_per_wg = std::min((pl.rows_per_wg + kMapRowsAlign - 1) / kMapRowsAlign * kMapRowsAlign, 32);    // the tile is at most 256 columns x 32 rows
       const int lead = (p.vis_begin - p.a_q_begin) - lo;             // role rows before visual row 0 (the [CLS] query)
       pl.a_shift = (pl.rows_per_wg - lead % pl.rows_per_wg) % pl.rows_per_wg;
     }
     pl.n_chunks = (pl.a_rows + pl.a_shift + pl.rows_per_wg - 1) / pl.rows_per_wg;
   } else {
     pl.n_chunks = 0;
-  }
-  if (L) {
-    pl.t_rows_per_wg = rows_per_wg(p.M);
-    pl.t_chunks = (p.M + pl.t_rows_per_wg - 1) / pl.t_rows_per_wg;
   }
 
   // threshold selection: p = eps (n-1) evaluated in double from the float eps

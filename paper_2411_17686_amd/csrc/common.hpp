@@ -34,7 +34,6 @@ struct Plan {
   int a_row0, a_rows;    // rows of A that carry a role (first, count)
   int a_shift;           // rows by which the first chunk is shortened so that visual row 0 starts a chunk
   int map_pitch;         // floats per row of the head-mean map (N rounded up to 64: read in whole 64-entry steps)
-  int t_rows_per_wg, t_chunks;
   // threshold selection
   int sel_m;             // order statistics needed: n_keep - floor(eps (n_keep-1))
   int sel_f;             // floor(p)

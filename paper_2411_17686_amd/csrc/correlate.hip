@@ -415,7 +415,9 @@ constexpr int kCandChunk = kCandKeep * kWave;    // targets per pass over the ro
 static_assert(kCandChunk <= kCandPad, "the block's padding covers one pass");
 constexpr int kCandBatch = 4;                    // targets evaluated exactly at a time
 
-__global__ __launch_bounds__(256) void corr_cand_rows_kernel(CorrArgs a) {
+// Compiled for four wavefronts per SIMD (128 registers; it would take 132): the decoder shape has
+// 3456 discarded rows, one wavefront each, and the chip holds 3072 of them at three per SIMD.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void corr_cand_rows_kernel(CorrArgs a) {
   __shared__ int cand_j[4][kCandCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int row = blockIdx.x * (blockDim.x / kWave) + wv;

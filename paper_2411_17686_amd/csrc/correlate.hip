@@ -630,10 +630,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
 // ---- FiCoCo-V attention correlation ------------------------------------------------------------
 // C[i][j] = Pbar[j][i] (Algorithm 1, stage 2).  The head-mean map is stored transposed, so the
 // values of discarded token i are one contiguous row; slot_of tells which of its entries belong
-// to preserved tokens.  One wavefront per discarded token: a first pass keeps each lane's MC
-// largest values, the m-th and (m-1)-th largest of the row (with multiplicity) are popped off
-// the lanes' lists, and a second pass over the row (a cache hit) emits the targets at or above
-// the threshold in ascending order.  Values are compared as the floats they are stored as.
+// to preserved tokens.  One wavefront per discarded token: one pass keeps each lane's MC largest
+// (value, slot) pairs, the m-th and (m-1)-th largest of the row (with multiplicity) are popped
+// off the lanes' lists, and the targets at or above the threshold are taken from the lists in
+// ascending order; the row is read a second time only if some lane's list could not hold all
+// of its targets.  Values are compared as the floats they are stored as.
 // kRowBatch = 64-entry steps of the row loaded together; a row that fits one batch stays in
 // registers for the second pass (10 steps: the 576-token grid).  Longer rows take batches of
 // kRowWide steps (measured at 2880 tokens: 16 is as good as 24, and 48 -- the whole row in
@@ -688,35 +689,40 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
   };
 
   float top[MC];
+  int topj[MC];
 #pragma unroll
-  for (int k = 0; k < MC; ++k) top[k] = NEGF;
+  for (int k = 0; k < MC; ++k) { top[k] = NEGF; topj[k] = -1; }
   for (int r0 = 0; r0 < a.N; r0 += kRowBatch * kWave) {
     load_batch(r0);
 #pragma unroll
     for (int u = 0; u < kRowBatch; ++u) {
       float v = vv[u];
+      int jq = sv[u];
 #pragma unroll
       for (int k = 0; k < MC; ++k) {
         const bool sw = v > top[k];
         const float t = top[k];
+        const int tj = topj[k];
         top[k] = sw ? v : t;
+        topj[k] = sw ? jq : tj;
         v = sw ? t : v;
+        jq = sw ? tj : jq;
       }
     }
   }
   // v[f], v[f+1]: pop the wavefront maximum m times (MC >= m, so one lane may hold them all)
   float vf = NEGF, vf1 = NEGF;
   int n_gt = 0;                                // pops strictly above vf
+  int head = 0;                                // entries of this lane's list popped so far (the lists stay as they are)
   for (int r = 0; r < a.sel_m; ++r) {
-    float mx = top[0];
+    float cur = NEGF;
+#pragma unroll
+    for (int k = 0; k < MC; ++k) cur = k == head ? top[k] : cur;
+    float mx = cur;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) { const float o = __shfl_xor(mx, off, kWave); mx = o > mx ? o : mx; }
-    const unsigned long long who = __ballot(top[0] == mx);
-    if (lane == __ffsll(who) - 1) {
-#pragma unroll
-      for (int k = 0; k + 1 < MC; ++k) top[k] = top[k + 1];
-      top[MC - 1] = NEGF;
-    }
+    const unsigned long long who = __ballot(cur == mx);
+    if (lane == __ffsll(who) - 1) ++head;
     if (r == 0 || mx < vf) n_gt = r;
     vf1 = vf;
     vf = mx;
@@ -737,7 +743,43 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
   double denom = 0.0;
   int my_tgt = -1;
   double my_c = 0.0;
-  for (int r0 = 0; r0 < a.N; r0 += kRowBatch * kWave) {
+  // A lane whose whole list is at or above tau may have seen more such values than it kept: only
+  // then is the row read again.  Otherwise every target is in some lane's list, and the lists
+  // are emptied in ascending slot order (slots are distinct) by repeated minimum search.
+  const bool list_full = topj[MC - 1] >= 0 && (double)top[MC - 1] >= tau;
+  const bool reread = __any(list_full);
+  if (!reread) {
+    bool open[MC];
+#pragma unroll
+    for (int k = 0; k < MC; ++k) open[k] = topj[k] >= 0 && (double)top[k] >= tau;
+    for (;;) {
+      int mine = 0x7fffffff, mk = 0;
+#pragma unroll
+      for (int k = 0; k < MC; ++k)
+        if (open[k] && topj[k] < mine) { mine = topj[k]; mk = k; }
+      int mn = mine;
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) mn = min(mn, __shfl_xor(mn, off, kWave));
+      if (mn == 0x7fffffff) break;                               // uniform
+      const bool owner = mine == mn;
+      float vo = 0.0f;
+#pragma unroll
+      for (int k = 0; k < MC; ++k) {
+        if (owner && k == mk) { vo = top[k]; open[k] = false; }
+      }
+      const int l = __ffsll(__ballot(owner)) - 1;
+      const double cl = (double)__shfl(vo, l, kWave);
+      const bool is_eq = cl == tau;
+      const bool take = cl > tau || (is_eq && ties_seen < tie_quota);
+      ties_seen += is_eq ? 1 : 0;
+      if (take) {
+        denom += cl;
+        if (lane == cnt) { my_tgt = mn; my_c = cl; }
+        ++cnt;
+      }
+    }
+  }
+  for (int r0 = 0; reread && r0 < a.N; r0 += kRowBatch * kWave) {
     if (a.N > kRowBatch * kWave || r0 > 0) load_batch(r0);     // a row of one batch is still in registers
     bool some = false;                                           // most batches hold no target at all
 #pragma unroll

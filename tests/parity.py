@@ -35,7 +35,10 @@ def compare_image(g, b, ref, dtype, vis_begin, exact_alpha, extra_row=None):
     S, T = ref["S"], ref["T"]
     assert np.array_equal(g["discard"][b], S), "discarded set differs (image %d)" % b
     assert np.array_equal(g["keep"][b], T), "preserved set differs (image %d)" % b
-    np.testing.assert_allclose(g["scores"][b], ref["scores"], rtol=SCORE_RTOL, atol=1e-300)
+    # the score is a difference of two terms: where they nearly cancel, the error is relative to
+    # the terms (bounded here by the largest score of the image), not to the small difference
+    scale = float(np.max(np.abs(ref["scores"]))) if len(ref["scores"]) else 0.0
+    np.testing.assert_allclose(g["scores"][b], ref["scores"], rtol=SCORE_RTOL, atol=1e-4 * SCORE_RTOL * scale + 1e-300)
     assert g["overflow"][b] == 0
     for a in range(len(S)):
         J = ref["J"][a]

@@ -19,7 +19,7 @@ def ctx():
     c.close()
 
 
-@pytest.mark.parametrize("seed", range(24))
+@pytest.mark.parametrize("seed", range(60))
 def test_random_v_case(ctx, seed):
     r = np.random.default_rng(5000 + seed)
     grid = int(r.integers(2, 15))
@@ -29,10 +29,12 @@ def test_random_v_case(ctx, seed):
     H = int(r.integers(1, 6))
     n_keep = int(r.integers(1, N + 1))
     dtype = ["f32", "bf16"][seed % 2]
+    mode = seed % 6
+    if mode == 2 and D == 1:
+        D = 5          # one feature: all tokens collinear, the cosine-derived scores tie in exact arithmetic only
     cfg = synth.ficoco_v_single(seed=6000 + seed, B=B, grid=grid, D=D, H=H, centres=int(r.integers(1, 9)),
                                 dtype=dtype, n_keep=n_keep)
     kw = {}
-    mode = seed % 6
     if mode == 1:
         kw.update(corr_src=fc.C_COSINE)
     elif mode == 2:
@@ -56,7 +58,7 @@ def test_random_v_case(ctx, seed):
         P.compare_image(out, b, ref, dtype, cfg["vis_begin"], kw.get("corr_src", fc.C_ATTN) == fc.C_ATTN, extra_row=extra)
 
 
-@pytest.mark.parametrize("seed", range(10))
+@pytest.mark.parametrize("seed", range(20))
 def test_random_l_case(ctx, seed):
     r = np.random.default_rng(7000 + seed)
     N = int(r.integers(2, 200))

@@ -129,8 +129,11 @@ __device__ __forceinline__ void add_raw(const Raw8<float>& r, double (&acc)[kVec
   acc[4] += r.b.x; acc[5] += r.b.y; acc[6] += r.b.z; acc[7] += r.b.w;
 }
 
-// acc += w * (the 8 elements held raw)
+// acc += w * (the 8 elements held raw): product and sum are rounded separately, as the plain
+// statement of Eq. 2 does, so that the sums are the same doubles (a fused multiply-add differs in
+// the last bit, which shows where a sum cancels)
 __device__ __forceinline__ void fma_raw(const Raw8<bf16_t>& r, double w, double (&acc)[kVec]) {
+#pragma clang fp contract(off)
   const uint32_t q[4] = {r.a.x, r.a.y, r.a.z, r.a.w};
 #pragma unroll
   for (int j = 0; j < 4; ++j) {
@@ -139,6 +142,7 @@ __device__ __forceinline__ void fma_raw(const Raw8<bf16_t>& r, double w, double 
   }
 }
 __device__ __forceinline__ void fma_raw(const Raw8<float>& r, double w, double (&acc)[kVec]) {
+#pragma clang fp contract(off)
   acc[0] += w * r.a.x; acc[1] += w * r.a.y; acc[2] += w * r.a.z; acc[3] += w * r.a.w;
   acc[4] += w * r.b.x; acc[5] += w * r.b.y; acc[6] += w * r.b.z; acc[7] += w * r.b.w;
 }

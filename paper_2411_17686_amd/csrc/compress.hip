@@ -13,6 +13,10 @@
 // ascending source order before it adds, so the result never depends on scheduling.
 #include "common.hpp"
 
+// Products and sums of Eq. 2 are rounded separately everywhere in this file (no fused multiply-add):
+// the weighted sums are then the very doubles the plain statement of the equation produces.
+#pragma clang fp contract(off)
+
 namespace ficoco {
 
 struct InvertArgs {

@@ -59,19 +59,26 @@ def compare_image(g, b, ref, dtype, vis_begin, exact_alpha, extra_row=None):
     else:
         assert np.all(err <= 2e-2 * np.abs(want) + 1e-2)
         assert np.all(err <= 2.0 ** -8 * np.abs(want) + 1e-38), "beyond one bfloat16 rounding"
-    # rows nothing was merged into are bit-exact copies
-    touched = set()
+    # Rows nothing was merged into are bit-exact copies.  With bit-exact weights (attention
+    # correlation) the merged rows are bit-exact too: the kernel adds the same doubles in the same
+    # order with the same roundings and rounds once to the token dtype.  The one exception is a
+    # target with more than 32 sources in the inverted-list mode (more than 1024 discarded tokens),
+    # whose sum is associated in eight ranges.
+    n_src = {}
     for a in range(len(S)):
-        touched.update(int(j) for j in ref["J"][a])
-    stored = O.round_to_dtype(want, dtype)
+        for j in ref["J"][a]:
+            n_src[int(j)] = n_src.get(int(j), 0) + 1
+    stored = O.widen(O.round_to_dtype(want, dtype))
     for r in range(want.shape[0]):
         j = r - vis_begin
         if r == extra_row:
             continue
         if extra_row is not None and r > extra_row:
             j = -1                                   # tokens behind the visual span
-        if not (0 <= j < len(T) and j in touched):
+        if not (0 <= j < len(T) and j in n_src):
             assert np.array_equal(got[r], stored[r]), "pass-through row %d not bit-exact" % r
+        elif exact_alpha and not (len(S) > 1024 and n_src[j] > 32):
+            assert np.array_equal(got[r], stored[r]), "merged row %d not bit-exact" % r
     return float(err.max())
 
 

@@ -72,3 +72,61 @@ def test_random_l_case(ctx, seed):
     for b in range(cfg["B"]):
         ref = P.oracle_l(cfg, b, red, cor, **kw)
         P.compare_image(out, b, ref, "bf16", cfg["vis_begin"], False)
+
+
+def _run_v_case(ctx, cfg, dtype, kw, convergent=False):
+    out, _ = P.run_v(cfg, cfg["A"], ctx=ctx, **kw)
+    okw = {k: v for k, v in kw.items() if k != "k_max"}
+    extra = cfg["vis_begin"] + cfg["n_keep"] if (convergent and cfg["n_keep"] < cfg["N"]) else None
+    for b in range(cfg["B"]):
+        ref = P.oracle_v(cfg, cfg["A"], b, **okw)
+        if max([len(j) for j in ref["J"]] + [0]) > 64:
+            assert out["overflow"][b] == 1
+            continue
+        P.compare_image(out, b, ref, dtype, cfg["vis_begin"], kw.get("corr_src", fc.C_ATTN) == fc.C_ATTN, extra_row=extra)
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_random_medium_v_case(ctx, seed):
+    """225 to 1444 patches, feature widths up to 1030 (several spans and a ragged tail): the shapes
+    where the reduction's chunk grid, the map tile and the merge's spans have more than one piece."""
+    r = np.random.default_rng(9000 + seed)
+    grid = int(r.integers(15, 39))
+    B, D, H = int(r.integers(1, 4)), int(r.choice([8, 64, 520, 1030])), int(r.integers(1, 5))
+    n_keep = int(r.integers(1, grid * grid + 1))
+    dtype = ["f32", "bf16"][seed % 2]
+    cfg = synth.ficoco_v_single(seed=9500 + seed, B=B, grid=grid, D=D, H=H, centres=int(r.integers(1, 40)),
+                                dtype=dtype, n_keep=n_keep)
+    kw, mode = {}, seed % 5
+    if mode == 1:
+        kw.update(k_mode=fc.K_FIXED, fixed_k=int(r.integers(0, 4)))
+    elif mode == 2:
+        kw.update(compress_mode=fc.COMPRESS_AVERAGE)
+    elif mode == 3:
+        kw.update(k_mode=fc.K_CONVERGENT)
+    elif mode == 4:
+        kw.update(corr_src=fc.C_COSINE)
+    kw.update(eps=float(r.choice([0.998, 1.0, 0.99])), k_max=64, window=int(r.choice([0, 2, 3])))
+    _run_v_case(ctx, cfg, dtype, kw, convergent=mode == 3)
+
+
+@pytest.mark.parametrize("seed", [3, 12, 27, 39])
+def test_random_inverted_list_case(ctx, seed):
+    """More than 1024 discarded tokens: the edge lists are inverted, long buckets get a workgroup."""
+    r = np.random.default_rng(13000 + seed)
+    grid = int(r.integers(36, 58))
+    N = grid * grid
+    D, H = int(r.choice([64, 520])), int(r.integers(1, 3))
+    n_keep = int(r.integers(8, N - 1030))
+    dtype = ["f32", "bf16"][seed % 2]
+    cfg = synth.ficoco_v_single(seed=13500 + seed, B=1, grid=grid, D=D, H=H, centres=int(r.integers(1, 40)),
+                                dtype=dtype, n_keep=n_keep, sigma=float(r.choice([0.5, 1.0, 3.0])))
+    kw, mode = {}, seed % 4
+    if mode == 1:
+        kw.update(k_mode=fc.K_FIXED, fixed_k=int(r.integers(1, 4)))
+    elif mode == 2:
+        kw.update(compress_mode=fc.COMPRESS_AVERAGE)
+    elif mode == 3:
+        kw.update(corr_src=fc.C_COSINE)
+    kw.update(eps=float(r.choice([0.998, 1.0, 0.99])), k_max=64, window=int(r.choice([0, 2])))
+    _run_v_case(ctx, cfg, dtype, kw)

@@ -94,6 +94,7 @@ def _with_broad_query(cfg, q):
     (16, 1100, 128, 2, "f32", (0, 1)),        # one scan of the discarded rows, three feature spans, ragged tail
     (36, 40, 400, 1, "bf16", (0,)),           # 896 discarded rows: two scans
     (24, 1024, 384, 16, "bf16", (0, 15)),     # the batched shape with its wide feature spans
+    (24, 1029, 384, 16, "f32", (5,)),         # wide spans, and a last span of five features
 ])
 def test_target_named_by_most_discarded_tokens(ctx, grid, D, n_keep, B, dtype, images):
     """A preserved token with a broad attention row collects far more sources than one

@@ -60,6 +60,15 @@ __device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_
   return acc * (1.0 / (double)H);
 }
 
+// Eq. 1 / Eq. 3 with both products rounded before the subtraction (no fused multiply-add): given
+// the same R and G, the score is then the same double as in the plain statement.
+__device__ __forceinline__ double combine_terms(double w, double R, double G) {
+#pragma clang fp contract(off)
+  const double first = w * R;
+  const double second = (1.0 - w) * G;
+  return first - second;
+}
+
 __device__ __forceinline__ uint64_t score_key(double s) {
   const uint64_t u = (uint64_t)__double_as_longlong(s + 0.0);   // -0 folded into +0
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
@@ -152,7 +161,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       } else {
         G = a.fterm_g[(int64_t)b * N + i];
       }
-      s[i] = a.w * R - (1.0 - a.w) * G;
+      s[i] = combine_terms(a.w, R, G);
     }
     DBG_PHASE(1);
     if (a.window > 0) {

@@ -417,6 +417,7 @@ constexpr int kCandBatch = 4;                    // targets evaluated exactly at
 
 // Compiled for four wavefronts per SIMD (128 registers; it would take 132): the decoder shape has
 // 3456 discarded rows, one wavefront each, and the chip holds 3072 of them at three per SIMD.
+template <int MC>   // lower bounds kept per lane (>= sel_m: one lane may hold the m largest of the row)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void corr_cand_rows_kernel(CorrArgs a) {
   __shared__ int cand_j[4][kCandCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
@@ -511,17 +512,17 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
   };
 
   // lower bounds: per-lane top list, then m pops of the wavefront maximum -> lambda
-  float top[kSelMax];
+  float top[MC];
 #pragma unroll
-  for (int k = 0; k < kSelMax; ++k) top[k] = NEGF;
+  for (int k = 0; k < MC; ++k) top[k] = NEGF;
   for (int c0 = 0; c0 < n; c0 += kCandChunk) {
     load_pass(c0);
 #pragma unroll
     for (int u = 0; u < kCandKeep; ++u) {
       float lo = val[u] == NEGF ? NEGF : gam * fmaxf(val[u] - delta, 0.0f);
-      if (lo > top[kSelMax - 1]) {
+      if (lo > top[MC - 1]) {
 #pragma unroll
-        for (int k = 0; k < kSelMax; ++k) {
+        for (int k = 0; k < MC; ++k) {
           const bool sw = lo > top[k];
           const float t = top[k];
           top[k] = sw ? lo : t;
@@ -538,8 +539,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     const unsigned long long who = __ballot(top[0] == mx);
     if (lane == __ffsll(who) - 1) {
 #pragma unroll
-      for (int k = 0; k + 1 < kSelMax; ++k) top[k] = top[k + 1];
-      top[kSelMax - 1] = NEGF;
+      for (int k = 0; k + 1 < MC; ++k) top[k] = top[k + 1];
+      top[MC - 1] = NEGF;
     }
     lambda = mx;
   }
@@ -852,6 +853,12 @@ __global__ void zero_i32_kernel(int32_t* p, int n) {
   if (i < n) p[i] = 0;
 }
 
+static void launch_cand_rows(int sel_m, dim3 grid, dim3 block, hipStream_t s, const CorrArgs& a) {
+  if (sel_m <= 2) hipLaunchKernelGGL(corr_cand_rows_kernel<2>, grid, block, 0, s, a);
+  else if (sel_m <= 4) hipLaunchKernelGGL(corr_cand_rows_kernel<4>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(corr_cand_rows_kernel<8>, grid, block, 0, s, a);
+}
+
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
@@ -901,7 +908,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   }
   if (a.mode == kAttnL && !pl.dense_rows && p.k_max <= 64) {
     hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
+    launch_cand_rows(pl.sel_m, grid, block, s, a);
     return;
   }
   if (pl.use_gram) {
@@ -911,7 +918,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);
     if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
-    hipLaunchKernelGGL(corr_cand_rows_kernel, grid, block, 0, s, a);
+    launch_cand_rows(pl.sel_m, grid, block, s, a);
     return;
   }
   if (pl.dense_rows) hipLaunchKernelGGL(corr_fill_rows_kernel, grid, block, 0, s, a);

@@ -131,3 +131,37 @@ def test_token_layouts_around_the_visual_span(ctx, vis_begin, cls_at, grid, n_ke
                    coef=2.0, lam=0.35, eps=0.998, tail=n_tot - vis_begin - N)
         _check(cfg, ctx)
         _check(cfg, ctx, k_mode=fc.K_FIXED, fixed_k=2)
+
+
+def _device_view_with_padding(t, pad_last, pad_rows):
+    """The tensor's values in a device buffer with NaN-filled room behind every row and extra rows
+    behind every matrix: same shape, last axis contiguous, larger strides."""
+    shape = list(t.shape)
+    big = shape[:]
+    big[-1] += pad_last
+    big[-2] += pad_rows
+    full = torch.full(big, float("nan"), dtype=t.dtype, device="cuda")
+    view = full[..., :shape[-2], :shape[-1]]
+    view.copy_(t.to("cuda"))
+    return view
+
+
+@pytest.mark.parametrize("seed,corr_src", [(0, fc.C_ATTN), (1, fc.C_COSINE), (2, fc.C_ATTN)])
+def test_padded_strides(ctx, seed, corr_src):
+    """X and A with room (filled with NaN) behind every row: strides are honoured, and nothing
+    outside a row reaches a result."""
+    grid, D, H, B, n_keep = [(12, 33, 3, 2, 60), (9, 64, 2, 3, 30), (20, 520, 2, 1, 150)][seed]
+    dtype = ["f32", "bf16"][seed % 2]
+    cfg = synth.ficoco_v_single(seed=400 + seed, B=B, grid=grid, D=D, H=H, centres=5, dtype=dtype, n_keep=n_keep)
+    Xd = _device_view_with_padding(cfg["X"], 3 + seed, 1)
+    Ad = _device_view_with_padding(cfg["A"], 5 - seed, 2)
+    assert not Xd.is_contiguous() and not Ad.is_contiguous()
+    p = fc.make_problem(Xd, variant=fc.VARIANT_V, vis_begin=1, N=grid * grid, n_keep=n_keep, A=Ad, cls_index=0,
+                        grid=cfg["grid"], window=cfg["window"], penalty_coef=cfg["coef"], w_score=cfg["lam"],
+                        eps=cfg["eps"], H=H, corr_src=corr_src, k_max=16)
+    buf = fc.Buffers(p, "cuda", Xd.dtype)
+    fc.ficoco_v_step(ctx, p, buf)
+    out = P.gpu_outputs(buf)
+    for b in range(B):
+        ref = P.oracle_v(cfg, cfg["A"], b, corr_src=corr_src)
+        P.compare_image(out, b, ref, dtype, 1, corr_src == fc.C_ATTN)

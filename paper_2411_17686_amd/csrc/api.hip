@@ -177,7 +177,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
 
   // feature pass geometry (column sums over the tokens)
   if (pl.need_features) {
-    pl.f_rows_per_wg = 32;
+    pl.f_rows_per_wg = 64;      // two batches of 8 rows per wavefront: half the workgroups (one round on the chip) and half the partials
     pl.f_chunks = (p.N + pl.f_rows_per_wg - 1) / pl.f_rows_per_wg;
   }
 

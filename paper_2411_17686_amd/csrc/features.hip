@@ -140,8 +140,14 @@ __global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
         const double inv = nrm[u] > 0.0 ? 1.0 / nrm[u] : 0.0;
         double v[kVec];
         widen_raw(raw[u], v);
+        if (a.want_sim) {                                  // uniform: only the sums some term needs
 #pragma unroll
-        for (int k = 0; k < kVec; ++k) { su[k] += v[k] * inv; sr[k] += v[k]; }
+          for (int k = 0; k < kVec; ++k) su[k] += v[k] * inv;
+        }
+        if (a.want_eq) {
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) sr[k] += v[k];
+        }
       }
     }
   } else {

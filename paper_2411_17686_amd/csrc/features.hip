@@ -211,55 +211,92 @@ __global__ __launch_bounds__(256) void col_mean_kernel(FeatArgs a) {
   }
 }
 
+// u_i . mean(u) and F_i . mu in double precision for kFtRows rows per workgroup.  The two mean
+// vectors are 16 bytes per feature, eight times a bfloat16 row: read once per row they, not the
+// rows, set the kernel's duration.  So the four wavefronts of a workgroup share them over four
+// rows: wavefront w takes the 64-vector steps w, w + 4, ... of all four rows (two steps in flight),
+// lanes are summed by a fixed butterfly and the wavefronts in order through LDS.
+constexpr int kFtRows = 4;
+constexpr int kFtSteps = 2;
 template <typename T>
 __global__ __launch_bounds__(256) void feature_terms_kernel(FeatArgs a) {
-  const int lane = threadIdx.x % kWave;
-  const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+  __shared__ double part[4][2][kFtRows];
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int i0 = blockIdx.x * kFtRows;
   const int64_t b = blockIdx.y;
-  if (i >= a.N) return;
-  const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
   const double* ubar = a.colmean + b * a.Df;
   const double* mu = a.colmean + (int64_t)a.B * a.Df + b * a.Df;
-  const int Dv = a.Df - a.Df % kVec;
-  double du = 0.0, dm = 0.0;
-  for (int d = lane * kVec; d < Dv; d += kWave * kVec) {
-    Raw8<T> raw;
-    load_raw(x + d, raw);
-    double v[kVec], w[kVec], m[kVec];
-    if (a.want_sim) {
+  const int n_vec = a.Df / kVec, Dv = n_vec * kVec;
+  const int n_t = (n_vec + kWave - 1) / kWave;
+  const T* x[kFtRows];
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) w[k] = ubar[d + k];
+  for (int r = 0; r < kFtRows; ++r)
+    x[r] = (const T*)a.F + b * a.sb + (int64_t)min(i0 + r, a.N - 1) * a.sn;     // clamped: a valid row, dropped at the end
+  double du[kFtRows], dm[kFtRows];
+#pragma unroll
+  for (int r = 0; r < kFtRows; ++r) { du[r] = 0.0; dm[r] = 0.0; }
+  for (int t0 = wv; t0 < n_t; t0 += 4 * kFtSteps) {
+    Raw8<T> raw[kFtSteps][kFtRows];
+    double w[kFtSteps][kVec], m[kFtSteps][kVec];
+#pragma unroll
+    for (int q = 0; q < kFtSteps; ++q) {
+      const int idx = (t0 + 4 * q) * kWave + lane;
+      const int d = idx < n_vec ? idx * kVec : 0;          // past the row: vector 0, cleared below
+#pragma unroll
+      for (int r = 0; r < kFtRows; ++r) load_raw(x[r] + d, raw[q][r]);
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) { w[q][k] = a.want_sim ? ubar[d + k] : 0.0; m[q][k] = a.want_eq ? mu[d + k] : 0.0; }
     }
-    if (a.want_eq) {
+    issue_fence();
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) m[k] = mu[d + k];
-    }
-    widen_raw(raw, v);
-    if (a.want_sim) {
+    for (int q = 0; q < kFtSteps; ++q) {
+      const bool in = (t0 + 4 * q) * kWave + lane < n_vec;
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) du += v[k] * w[k];
-    }
-    if (a.want_eq) {
+      for (int r = 0; r < kFtRows; ++r) {
+        keep_raw_if(raw[q][r], in);
+        double v[kVec];
+        widen_raw(raw[q][r], v);
+        if (a.want_sim) {
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) dm += v[k] * m[k];
+          for (int k = 0; k < kVec; ++k) du[r] += v[k] * w[q][k];
+        }
+        if (a.want_eq) {
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) dm[r] += v[k] * m[q][k];
+        }
+      }
     }
   }
-  for (int d = Dv + lane; d < a.Df; d += kWave) {
-    const double v = widen(x[d]);
-    du += v * ubar[d];
-    dm += v * mu[d];
+  if (wv == 0) {                                            // the features behind the last whole vector
+    for (int d = Dv + lane; d < a.Df; d += kWave) {
+#pragma unroll
+      for (int r = 0; r < kFtRows; ++r) {
+        const double v = widen(x[r][d]);
+        du[r] += v * ubar[d];
+        dm[r] += v * mu[d];
+      }
+    }
   }
-  du = wave_sum_d(du); dm = wave_sum_d(dm);
+#pragma unroll
+  for (int r = 0; r < kFtRows; ++r) { du[r] = wave_sum_d(du[r]); dm[r] = wave_sum_d(dm[r]); }
   if (lane == 0) {
-    const double nrm = a.norm[b * a.N + i];
-    if (a.want_sim) a.fterm_r[b * a.N + i] = nrm > 0.0 ? du / nrm : 0.0;
-    if (a.want_eq) {
-      const int n_part = (a.Df + 255) / 256;
-      double mm = 0.0;
-      for (int k = 0; k < n_part; ++k) mm += a.colmean[2 * (int64_t)a.B * a.Df + b * n_part + k];
-      const double mn = sqrt(mm);
-      a.fterm_g[b * a.N + i] = (nrm > 0.0 && mn > 0.0) ? -(dm / (mn * nrm)) : 0.0;
-    }
+#pragma unroll
+    for (int r = 0; r < kFtRows; ++r) { part[wv][0][r] = du[r]; part[wv][1][r] = dm[r]; }
+  }
+  __syncthreads();
+  const int r = threadIdx.x;
+  if (r >= kFtRows || i0 + r >= a.N) return;
+  const int i = i0 + r;
+  double su = 0.0, sm = 0.0;
+  for (int w4 = 0; w4 < 4; ++w4) { su += part[w4][0][r]; sm += part[w4][1][r]; }      // wavefronts in order
+  const double nrm = a.norm[b * a.N + i];
+  if (a.want_sim) a.fterm_r[b * a.N + i] = nrm > 0.0 ? su / nrm : 0.0;
+  if (a.want_eq) {
+    const int n_part = (a.Df + 255) / 256;
+    double mm = 0.0;
+    for (int k = 0; k < n_part; ++k) mm += a.colmean[2 * (int64_t)a.B * a.Df + b * n_part + k];
+    const double mn = sqrt(mm);
+    a.fterm_g[b * a.N + i] = (nrm > 0.0 && mn > 0.0) ? -(sm / (mn * nrm)) : 0.0;
   }
 }
 
@@ -296,8 +333,9 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
   if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);
   else hipLaunchKernelGGL(col_sum_kernel<float>, cgrid, block, 0, s, a);
   hipLaunchKernelGGL(col_mean_kernel, dim3((pl.Df + 255) / 256, p.B), block, 0, s, a);
-  if (bf16) hipLaunchKernelGGL(feature_terms_kernel<bf16_t>, rows, block, 0, s, a);
-  else hipLaunchKernelGGL(feature_terms_kernel<float>, rows, block, 0, s, a);
+  const dim3 trows((p.N + kFtRows - 1) / kFtRows, p.B);
+  if (bf16) hipLaunchKernelGGL(feature_terms_kernel<bf16_t>, trows, block, 0, s, a);
+  else hipLaunchKernelGGL(feature_terms_kernel<float>, trows, block, 0, s, a);
 }
 
 }  // namespace ficoco

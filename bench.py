@@ -375,6 +375,59 @@ def main():
         out["step_algorithmic_bytes"] = W["step_bytes"]
         out["step_hbm_frac"] = W["step_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
 
+    if args.config == "1" and args.ablation == "none":
+        # BASELINE config 1 in full: the three successive reductions 576 -> 384 -> 256 -> 192 with a
+        # fresh attention map per step (sized for the tokens the previous step left); X and the
+        # position ids of a step are the previous step's outputs.  One chain per stream.
+        keeps = (384, 256, 192)
+        g = torch.Generator(device=dev)
+        g.manual_seed(11)
+        chains = []
+        for si in range(n_str):
+            ps, bs = [], []
+            Xin, pos = W["sets"][si % n_sets]["X"], None
+            n = W["N"]
+            for k_i, keep in enumerate(keeps):
+                A = W["sets"][si % n_sets]["A"] if k_i == 0 else _softmax_map(torch, g, dev, W["B"], W["H"], n + 1, n + 1, 1.5, tdt)
+                kw = dict(W["kw"])
+                kw.update(N=n, n_keep=keep)
+                pr = fc.make_problem(Xin, variant=fc.VARIANT_V, A=A, H=W["H"], pos=pos, **kw)
+                bf_ = fc.Buffers(pr, dev, tdt)
+                ps.append((pr, A))
+                bs.append(bf_)
+                Xin, pos, n = bf_.X_out, bf_.pos_out, keep
+            chains.append((ps, bs))
+        sync()
+
+        def run_chains(k):
+            for i in range(k):
+                ps, bs = chains[i % n_str]
+                with torch.cuda.stream(streams[i % n_str]):
+                    for (pr, _), bf_ in zip(ps, bs):
+                        fc.ficoco_v_step(ctx, pr, bf_)
+
+        k_chain = max(1, args.steps // 2)
+        run_chains(max(1, args.warmup // 2))
+        sync()
+        t0 = time.perf_counter()
+        run_chains(k_chain)
+        sync()
+        dtc = (time.perf_counter() - t0) / k_chain
+        pair = event_pairs(k_chain)
+        with torch.cuda.stream(streams[0]):
+            for i in range(k_chain):
+                pair[i][0].record(streams[0])
+                for (pr, _), bf_ in zip(*chains[0]):
+                    fc.ficoco_v_step(ctx, pr, bf_)
+                pair[i][1].record(streams[0])
+        sync()
+        latc = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in pair)
+        assert all(int(bf_.overflow.sum().item()) == 0 for _, bs in chains for bf_ in bs)
+        out["three_step_chain"] = {"reductions": "576 -> 384 -> 256 -> 192 visual tokens, a fresh map per step",
+                                   "us_per_chain": dtc * 1e6, "chains_per_s": 1.0 / dtc,
+                                   "input_tokens_per_s": W["B"] * W["N"] / dtc,
+                                   "one_chain_alone_us": latc[len(latc) // 2], "chains_timed": k_chain}
+
     if args.calibrate_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)

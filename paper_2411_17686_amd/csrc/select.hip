@@ -281,12 +281,22 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   // ---- flags and ordered compaction -----------------------------------------------------------
   const int per = (N + nt - 1) / nt;
   const int lo = min(tid * per, N), hi = min(lo + per, N);
-  int n_eq = 0;
-  for (int i = lo; i < hi; ++i) n_eq += (a.n_disc > 0 && keys[i] == kstar) ? 1 : 0;
+  // One scan carries both counts of this thread's tokens: keys above K* (upper half) and keys
+  // equal to K* (lower half); neither total exceeds N <= 12288.  The discarded tokens before
+  // `lo` are then the ones above K* plus the first `need` of the equal ones.
+  int n_eq = 0, n_gt = 0;
+  for (int i = lo; i < hi; ++i) {
+    const uint64_t k = keys[i];
+    n_eq += (a.n_disc > 0 && k == kstar) ? 1 : 0;
+    n_gt += (a.n_disc > 0 && k > kstar) ? 1 : 0;
+  }
   int tot;
-  int eq_before = block_scan_inclusive(n_eq, scan, &tot) - n_eq;
+  const int packed = block_scan_inclusive((n_gt << 16) | n_eq, scan, &tot) - ((n_gt << 16) | n_eq);
+  int eq_before = packed & 0xffff;
+  const int gt_before = packed >> 16;
+  int d_pos = gt_before + min(eq_before, need);                   // discarded tokens before `lo`
+  int k_pos = lo - d_pos;                                         // preserved tokens before `lo`
   uint32_t dis_mask = 0;  // per <= 12 tokens per thread (N <= kMaxSelectN)
-  int n_dis = 0;
   for (int i = lo; i < hi; ++i) {
     const uint64_t k = keys[i];
     bool dis = false;
@@ -294,10 +304,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       if (k > kstar) dis = true;
       else if (k == kstar) { dis = eq_before < need; ++eq_before; }
     }
-    if (dis) { dis_mask |= 1u << (i - lo); ++n_dis; }
+    if (dis) dis_mask |= 1u << (i - lo);
   }
-  int d_pos = block_scan_inclusive(n_dis, scan, &tot) - n_dis;   // discarded tokens before `lo`
-  int k_pos = lo - d_pos;                                         // preserved tokens before `lo`
   DBG_PHASE(4);
   const int n_keep = N - a.n_disc;
   for (int i = lo; i < hi; ++i) {

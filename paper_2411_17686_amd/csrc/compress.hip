@@ -33,8 +33,6 @@ struct InvertArgs {
 
 constexpr int kHubMin = 32;        // buckets longer than this are merged by a whole workgroup
 constexpr int kInvertRows = 512;   // discarded rows one workgroup scatters
-constexpr int kInvertPre = 4;      // targets per row loaded before the row's count is known
-constexpr int kInvertBatch = 4;    // rows per thread whose loads are in flight together
 
 // Buckets the edges of one image by target.  gridDim.x workgroups share an image: every one
 // of them counts ALL edges of the image into an LDS histogram (cheap, and it needs no
@@ -43,6 +41,7 @@ constexpr int kInvertBatch = 4;    // rows per thread whose loads are in flight 
 // is where this workgroup's own rows start inside each bucket.  Then it scatters its rows.
 // No global atomics, nothing to clear beforehand, bucket regions per workgroup are fixed;
 // only the order inside a region depends on scheduling (the merge orders buckets itself).
+template <int CH>   // consecutive list slots one thread loads at a time: 4 (rows of 4k slots, 16-byte aligned lists) or 1
 __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs a) {
   extern __shared__ int lds_i[];
   int* cnt = lds_i;                       // [n_keep+1] counts, then exclusive offsets
@@ -53,36 +52,44 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   const int n = a.n_keep;
   const int share = (a.n_disc + (int)gridDim.x - 1) / (int)gridDim.x;
   const int r_lo = min((int)blockIdx.x * share, a.n_disc), r_hi = min(r_lo + share, a.n_disc);
+  DBG_PHASE(8);
   for (int j = tid; j <= n; j += nt) cnt[j] = 0;
   for (int j = tid; j < n; j += nt) cursor[j] = 0;
   __syncthreads();
   const int64_t rbase = b * a.n_disc;
-  // Count pass over all rows of the image, kInvertBatch rows per thread at a time with every
-  // load of the batch issued before the first use.
-  for (int r0 = tid; r0 < a.n_disc; r0 += nt * kInvertBatch) {
-    int c[kInvertBatch];
-    int pre[kInvertBatch][kInvertPre];
-#pragma unroll
-    for (int u = 0; u < kInvertBatch; ++u) {
-      const int r = min(r0 + u * nt, a.n_disc - 1);      // clamped: always a valid address
-      c[u] = min(a.edge_cnt[rbase + r], a.k_max);
-#pragma unroll
-      for (int e = 0; e < kInvertPre; ++e) pre[u][e] = a.edge_tgt[(rbase + r) * a.k_max + min(e, a.k_max - 1)];
+  const int32_t* tgt = a.edge_tgt + rbase * a.k_max;      // the image's lists as one flat array of slots
+  const double* alp = a.edge_alpha + rbase * a.k_max;
+  auto load_slots = [&](int f, int (&v)[CH]) {            // slots f .. f+CH-1 (inside one row)
+    if constexpr (CH == 4) {
+      const int4 q = *reinterpret_cast<const int4*>(tgt + f);
+      v[0] = q.x; v[1] = q.y; v[2] = q.z; v[3] = q.w;
+    } else {
+      v[0] = tgt[f];
     }
+  };
+  // Count pass over every slot of the image.  Consecutive threads take consecutive slots, so a
+  // wavefront's load covers whole cache lines (a thread per row would touch every line of the
+  // lists once per slot position); kInvertBatch loads per thread are in flight together.
+  constexpr int kInvertBatch = CH == 4 ? 8 : 16;     // loads of list slots one thread has in flight together
+  const int n_chunks = a.n_disc * a.k_max / CH;
+  for (int c0 = tid; c0 < n_chunks; c0 += nt * kInvertBatch) {
+    int v[kInvertBatch][CH], have[kInvertBatch], row[kInvertBatch];
 #pragma unroll
     for (int u = 0; u < kInvertBatch; ++u) {
-      const int r = r0 + u * nt;
-      if (r >= a.n_disc) break;
-      const bool before = r < r_lo;
-      for (int e = 0; e < c[u]; ++e) {
-        int j = 0;
-        if (e < kInvertPre) {
+      const int f = min(c0 + u * nt, n_chunks - 1) * CH;   // clamped: always a valid address
+      row[u] = f / a.k_max;
+      have[u] = min(a.edge_cnt[rbase + row[u]], a.k_max) - (f - row[u] * a.k_max);   // list entries from slot f on
+      load_slots(f, v[u]);
+    }
+    issue_fence();
 #pragma unroll
-          for (int q = 0; q < kInvertPre; ++q) j = e == q ? pre[u][q] : j;
-        } else {
-          j = a.edge_tgt[(rbase + r) * a.k_max + e];
-        }
-        if (j >= 0 && j < n) {
+    for (int u = 0; u < kInvertBatch; ++u) {
+      if (c0 + u * nt >= n_chunks) break;
+      const bool before = row[u] < r_lo;
+#pragma unroll
+      for (int q = 0; q < CH; ++q) {
+        const int j = v[u][q];
+        if (q < have[u] && j >= 0 && j < n) {
           atomicAdd(&cnt[j], 1);
           if (before) atomicAdd(&cursor[j], 1);
         }
@@ -90,6 +97,7 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
     }
   }
   __syncthreads();
+  DBG_PHASE(9);
   // exclusive scan of cnt[0..n): thread t owns a contiguous slice
   const int per = (n + nt - 1) / nt;
   const int lo = min(tid * per, n), hi = min(lo + per, n);
@@ -114,6 +122,7 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   }
   if (tid == 0) cnt[n] = total;
   __syncthreads();
+  DBG_PHASE(10);
   if (blockIdx.x == 0) {       // uniform over the workgroup
     for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
     // targets with long buckets, for the workgroup-per-target pass of the merge
@@ -127,20 +136,36 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   }
   const int64_t ebase = b * (int64_t)a.n_disc * a.k_max;
   const int cap = a.n_disc * a.k_max;
-  for (int r = r_lo + tid; r < r_hi; r += nt) {
-    const int c = min(a.edge_cnt[rbase + r], a.k_max);
-    for (int e = 0; e < c; ++e) {
-      const int64_t src = (rbase + r) * a.k_max + e;
-      const int j = a.edge_tgt[src];
-      if (j >= 0 && j < n) {
+  // Scatter of the workgroup's own rows, slot by slot in the same flat order.
+  const int f_lo = r_lo * a.k_max / CH, f_hi = r_hi * a.k_max / CH;
+  for (int ci = f_lo + tid; ci < f_hi; ci += nt) {
+    const int f = ci * CH;
+    const int r = f / a.k_max;
+    const int have = min(a.edge_cnt[rbase + r], a.k_max) - (f - r * a.k_max);
+    int v[CH];
+    double al[CH];
+    load_slots(f, v);
+    if constexpr (CH == 4) {
+      const double2 a0 = *reinterpret_cast<const double2*>(alp + f);
+      const double2 a1 = *reinterpret_cast<const double2*>(alp + f + 2);
+      al[0] = a0.x; al[1] = a0.y; al[2] = a1.x; al[3] = a1.y;
+    } else {
+      al[0] = alp[f];
+    }
+    issue_fence();
+#pragma unroll
+    for (int q = 0; q < CH; ++q) {
+      const int j = v[q];
+      if (q < have && j >= 0 && j < n) {
         const int slot = atomicAdd(&cursor[j], 1);
         if (slot < cap) {                     // always true for consistent lists; they are device data
           a.tgt_src[ebase + slot] = r;
-          a.tgt_alpha[ebase + slot] = a.edge_alpha[src];
+          a.tgt_alpha[ebase + slot] = al[q];
         }
       }
     }
   }
+  DBG_PHASE(11);
 }
 
 struct MergeArgs {
@@ -879,10 +904,14 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
     a.hub_list = (int32_t*)(ws + pl.hub_list);
     a.hub_cnt = (int32_t*)(ws + pl.hub_cnt);
     const size_t lds = ((size_t)2 * p.n_keep + 1 + 2 * kSelectThreads) * sizeof(int);
+    // four slots per load where every row of the lists starts on a 16-byte boundary
+    const bool quads = p.k_max % 4 == 0 && reinterpret_cast<uintptr_t>(edge_tgt) % 16 == 0 &&
+                       reinterpret_cast<uintptr_t>(edge_alpha) % 16 == 0;
+    auto kern = quads ? invert_edges_kernel<4> : invert_edges_kernel<1>;
     if (lds > 32768)
-      (void)hipFuncSetAttribute((const void*)invert_edges_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
     const int groups = (pl.n_disc + kInvertRows - 1) / kInvertRows;
-    hipLaunchKernelGGL(invert_edges_kernel, dim3(groups, p.B), dim3(kSelectThreads), lds, s, a);
+    hipLaunchKernelGGL(kern, dim3(groups, p.B), dim3(kSelectThreads), lds, s, a);
   }
   MergeArgs m{};
   m.X = p.X; m.xsb = p.x_stride_b; m.xsn = p.x_stride_n; m.X_out = X_out;

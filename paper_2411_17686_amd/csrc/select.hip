@@ -99,6 +99,11 @@ __device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* to
   return incl + before;
 }
 
+constexpr int kTokensPerThread = (kMaxSelectN + kSelectThreads - 1) / kSelectThreads;   // the kernel runs with kSelectThreads threads
+constexpr int kBinCopies = 32;      // counters per histogram bin in the many-keys form: one per LDS bank
+constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (it costs one more barrier per pass)
+static_assert(kSelectThreads == 4 * 256, "four threads fold the counters of one bin");
+
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   DBG_SPAN(1);
   extern __shared__ double lds_d[];
@@ -114,7 +119,29 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
 
   DBG_PHASE(0);
   if (a.do_score) {
-    for (int i = tid; i < N; i += nt) {
+    // Both terms one stored value per token, and several tokens per thread: all of the thread's
+    // loads are issued before the first use (the general loop below takes a trip to memory per token).
+    const double* r_one = a.red_src == FICOCO_R_ATTN_RECV ? (a.n_chunks == 1 ? a.recv_part : nullptr)
+                        : a.red_src == FICOCO_R_VECTOR ? nullptr : a.fterm_r;
+    const double* g_one = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls
+                        : (a.sem_src == FICOCO_G_TEXT_ATTN || a.sem_src == FICOCO_G_VECTOR) ? nullptr : a.fterm_g;
+    const bool one_each = r_one && g_one && N > nt;      // uniform
+    if (one_each) {
+      double r[kTokensPerThread], g[kTokensPerThread];
+#pragma unroll
+      for (int u = 0; u < kTokensPerThread; ++u) {
+        const int i = min(tid + u * nt, N - 1);          // clamped: always a valid address
+        r[u] = r_one[(int64_t)b * N + i];
+        g[u] = g_one[(int64_t)b * N + i];
+      }
+      issue_fence();
+#pragma unroll
+      for (int u = 0; u < kTokensPerThread; ++u) {
+        const int i = tid + u * nt;
+        if (i < N) s[i] = combine_terms(a.w, a.red_src == FICOCO_R_ATTN_RECV ? (0.0 + r[u]) / (double)N : r[u], g[u]);
+      }
+    }
+    for (int i = tid; i < (one_each ? 0 : N); i += nt) {
       double R, G;
       if (a.red_src == FICOCO_R_ATTN_RECV) {
         const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
@@ -206,14 +233,38 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   int need = a.n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
   if (a.n_disc > 0) {
     uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
+    const bool spread = N >= kSpreadMinN;   // uniform
+    int* hist_wide = owner;              // [256][kBinCopies]: the penalty's table is no longer needed
     for (int pass = 0; pass < 8; ++pass) {
       const int shift = 56 - 8 * pass;
       const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
-      for (int i = tid; i < N; i += nt) {
-        const uint64_t k = keys[i];
-        if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
+      if (spread) {
+        // Many keys per thread: scores of one image share their leading digits, so in the first
+        // passes nearly all atomics would queue on one LDS address (one lane per cycle).  Every
+        // bin has 32 counters here, one per bank, lane l adding to counter l % 32 -- no two
+        // lanes of an instruction meet -- and four threads per bin fold them afterwards.
+        for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0;
+        __syncthreads();
+        for (int i = tid; i < N; i += nt) {
+          const uint64_t k = keys[i];
+          if ((k & hi_mask) == kstar) atomicAdd(&hist_wide[(int)((k >> shift) & 255) * kBinCopies + tid % kBinCopies], 1);
+        }
+        __syncthreads();
+        const int bin = tid / 4, part = tid % 4;           // 1024 threads: four per bin
+        int sum = 0;
+#pragma unroll
+        for (int c = 0; c < kBinCopies / 4; ++c)           // rotated by the bin so that neighbouring bins read different banks
+          sum += hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
+        sum += __shfl_xor(sum, 1, kWave);
+        sum += __shfl_xor(sum, 2, kWave);
+        if (part == 0) hist[bin] = sum;
+      } else {
+        if (tid < 256) hist[tid] = 0;
+        __syncthreads();
+        for (int i = tid; i < N; i += nt) {
+          const uint64_t k = keys[i];
+          if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
+        }
       }
       __syncthreads();
       if (tid < kWave) {
@@ -376,7 +427,8 @@ __global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
-  return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + cells) * sizeof(int);
+  const int wide = p.N >= kSpreadMinN ? 256 * kBinCopies : 0;   // shares the penalty table's space
+  return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + (cells > wide ? cells : wide)) * sizeof(int);
 }
 
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,

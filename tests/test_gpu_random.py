@@ -80,7 +80,7 @@ def _run_v_case(ctx, cfg, dtype, kw, convergent=False):
     extra = cfg["vis_begin"] + cfg["n_keep"] if (convergent and cfg["n_keep"] < cfg["N"]) else None
     for b in range(cfg["B"]):
         ref = P.oracle_v(cfg, cfg["A"], b, **okw)
-        if max([len(j) for j in ref["J"]] + [0]) > 64:
+        if max([len(j) for j in ref["J"]] + [0]) > kw.get("k_max", 64):
             assert out["overflow"][b] == 1
             continue
         P.compare_image(out, b, ref, dtype, cfg["vis_begin"], kw.get("corr_src", fc.C_ATTN) == fc.C_ATTN, extra_row=extra)
@@ -129,4 +129,20 @@ def test_random_inverted_list_case(ctx, seed):
     elif mode == 3:
         kw.update(corr_src=fc.C_COSINE)
     kw.update(eps=float(r.choice([0.998, 1.0, 0.99])), k_max=64, window=int(r.choice([0, 2])))
+    _run_v_case(ctx, cfg, dtype, kw)
+
+
+@pytest.mark.parametrize("seed,k_max", [(1, 4), (2, 5), (3, 7), (4, 8), (5, 13), (6, 12)])
+def test_inverted_lists_with_short_rows(ctx, seed, k_max):
+    """The inversion reads the edge lists slot by slot, four slots per load when the list length
+    allows it: list lengths that are and are not multiples of four, rows partly filled."""
+    r = np.random.default_rng(14000 + seed)
+    grid = int(r.integers(36, 50))
+    N = grid * grid
+    n_keep = int(r.integers(8, min(N - 1030, 900)))
+    dtype = ["f32", "bf16"][seed % 2]
+    cfg = synth.ficoco_v_single(seed=14500 + seed, B=int(r.integers(1, 3)), grid=grid, D=int(r.choice([64, 136])),
+                                H=int(r.integers(1, 3)), centres=int(r.integers(1, 40)), dtype=dtype, n_keep=n_keep)
+    kw = dict(k_mode=fc.K_FIXED, fixed_k=int(r.integers(1, 4))) if seed % 3 == 0 else {}
+    kw.update(eps=0.998, k_max=k_max, window=int(r.choice([0, 2])))
     _run_v_case(ctx, cfg, dtype, kw)

@@ -225,7 +225,10 @@ struct DbgSpan {
   }
 };
 #define DBG_SPAN(k) DbgSpan dbg_span_(k)
-#define DBG_PHASE(i) do { if (blockIdx.x == gridDim.x / 2 && blockIdx.y == 0 && threadIdx.x == 0) g_dbg[2 * (kDbgSlots - 16) + (i)] = wall_clock64(); } while (0)
+#ifndef FICOCO_DBG_WG
+#define FICOCO_DBG_WG (gridDim.x / 2)
+#endif
+#define DBG_PHASE(i) do { if (blockIdx.x == FICOCO_DBG_WG && blockIdx.y == 0 && threadIdx.x == 0) g_dbg[2 * (kDbgSlots - 16) + (i)] = wall_clock64(); } while (0)
 #define FICOCO_DBG_READER(name) \
   extern "C" void ficoco_debug_reset_##name(void) { \
     void* p; (void)hipGetSymbolAddress(&p, HIP_SYMBOL(ficoco::g_dbg)); (void)hipMemset(p, 0, sizeof(unsigned long long) * 2 * ficoco::kDbgSlots); } \

@@ -37,6 +37,22 @@ def test_largest_sequence(ctx):
     assert out["X_out"].shape == (1, 1000, 64)
 
 
+@pytest.mark.parametrize("levels,window", [(2, 0), (3, 2), (17, 2)])
+def test_long_sequence_with_tied_scores(ctx, levels, window):
+    """Several thousand tokens whose score terms take a handful of values: the filter's radix
+    passes (many keys per thread, bank-spread counters) meet long runs of equal keys, and the
+    cut falls inside one of them -- the lowest positions are taken."""
+    cfg = synth.ficoco_v_video(seed=73, B=2, frames=2, grid=48, D=64, H=2, centres=30, n_keep=700)
+    assert cfg["N"] == 4608
+    g = torch.Generator().manual_seed(levels)
+    for key in ("recv_vec", "sem_vec"):
+        steps = torch.randint(0, levels, cfg[key].shape, generator=g)
+        cfg[key] = (steps.float() / 64.0).to(cfg[key].dtype)      # exact in bf16
+    cfg["window"] = window
+    out = _check(cfg, ctx, red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE)
+    assert out["X_out"].shape == (2, 700, 64)
+
+
 def test_one_token_over_the_limit_is_rejected(ctx):
     X = torch.zeros(1, 12289, 8, dtype=torch.bfloat16, device="cuda")
     v = torch.zeros(1, 2, 12289, dtype=torch.bfloat16, device="cuda")

@@ -408,9 +408,11 @@ __global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec,
   if (sem_vec) out_g[b * N + i] = vec_head_mean(sem_vec, dtype, b, H, N, i);
 }
 
-// Long instructions (many text queries): the task term of Eq. 3, the mean of a token's text
-// profile, is formed by one wavefront per token on the whole chip (lane sums over k = lane,
-// lane + 64, ..., then a fixed tree), so the per-image workgroup of select_kernel reads one value.
+// From 32 text queries on: the task term of Eq. 3, the mean of a token's text profile, is formed
+// by one wavefront per token on the whole chip (lane sums over k = lane, lane + 64, ..., then a
+// fixed tree), so the per-image workgroup of select_kernel reads one value.  A thread of that
+// workgroup walking its token's profile touches a cache line per lane and load, all on one
+// compute unit (64 queries: 17 us for the select kernel against 9 + 4 us this way).
 __global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict__ ttext, int N, int M,
                                                         double* __restrict__ out_g) {
   const int lane = threadIdx.x % kWave;
@@ -461,7 +463,7 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
     if (vr) a.red_src = FICOCO_R_SIM_MEAN;     // "read the precomputed term"
     if (vg) a.sem_src = FICOCO_G_EQ_TOKEN;
   }
-  if (do_score && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 128) {
+  if (do_score && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 32) {
     // the equivalent-token buffer is free in FiCoCo-L
     hipLaunchKernelGGL(text_mean_kernel, dim3((p.N + 3) / 4, p.B), dim3(256), 0, s, a.ttext, p.N, p.M,
                        (double*)(ws + pl.fterm2));

@@ -419,6 +419,7 @@ constexpr int kCandBatch = 4;                    // targets evaluated exactly at
 // 3456 discarded rows, one wavefront each, and the chip holds 3072 of them at three per SIMD.
 template <int MC>   // lower bounds kept per lane (>= sel_m: one lane may hold the m largest of the row)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void corr_cand_rows_kernel(CorrArgs a) {
+  DBG_SPAN(2);
   __shared__ int cand_j[4][kCandCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int row = blockIdx.x * (blockDim.x / kWave) + wv;
@@ -431,6 +432,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
     return;
   }
+  DBG_PHASE(0);
   // approximate direct term of the row: the matrix-core cosines, or (FiCoCo-L with the
   // attention correlation) the token's row of the exact head-mean map, delta = 0
   const bool from_map = a.mode == kAttnL;
@@ -444,6 +446,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     bd = wave_sum_f64(bd) * a.invM * (1.0 - a.gamma);
     extra = (float)bd * 1.000001f + 1e-30f;   // rounded up
   }
+  DBG_PHASE(1);
   const float delta = from_map ? 0.0f : a.delta;
   const float NEGF = -__builtin_huge_valf();
   const int64_t split_stride = (int64_t)a.B * a.n_disc * n;
@@ -532,6 +535,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     }
   }
   float lambda = NEGF;
+  DBG_PHASE(2);
   for (int r = 0; r < a.sel_m; ++r) {
     float mx = top[0];
 #pragma unroll
@@ -545,6 +549,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     lambda = mx;
   }
   // candidates in ascending target order (a row of one pass is still in registers)
+  DBG_PHASE(3);
   int n_cand = 0;
   for (int c0 = 0; c0 < n; c0 += kCandChunk) {
     if (n > kCandChunk) load_pass(c0);
@@ -566,6 +571,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     return;
   }
   // exact values of the candidates: lane c keeps candidate c
+  DBG_PHASE(4);
   const double NEG = -__builtin_huge_val();
   const int myjj = lane < n_cand ? cand_j[wv][lane] : -1;
   const int myj = myjj >= 0 ? T[myjj] : -1;
@@ -586,6 +592,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
       if (lane == c + q && c + q < n_cand) myv = ok[q] ? v[q] : NEG;
   }
   // v[f], v[f+1] = m-th and (m-1)-th largest of the exact candidate values
+  DBG_PHASE(5);
   double v_f = NEG, v_f1 = NEG;
   int n_gt = 0;
   {
@@ -626,6 +633,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
     if (live && cnt > a.k_max) a.overflow[b] = 1;
   }
+  DBG_PHASE(6);
 }
 
 // ---- FiCoCo-V attention correlation ------------------------------------------------------------

@@ -211,6 +211,31 @@ __host__ __device__ __forceinline__ int xcd_padded_total(int total) {
   return ((total + kXcds - 1) / kXcds) * kXcds;
 }
 
+// Inclusive scan of one int per thread over the workgroup (wavefront shuffles, then the
+// wavefront totals through LDS); returns this thread's inclusive value, *total receives the
+// sum.  scratch: at least blockDim.x / 64 ints.
+__device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* total) {
+  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave, nw = blockDim.x / kWave;
+  int incl = v;
+#pragma unroll
+  for (int off = 1; off < kWave; off <<= 1) {
+    const int t = __shfl_up(incl, off, kWave);
+    if (lane >= off) incl += t;
+  }
+  __syncthreads();
+  if (lane == kWave - 1) scratch[wv] = incl;
+  __syncthreads();
+  int before = 0, tot = 0;
+  for (int w = 0; w < nw; ++w) {
+    const int t = scratch[w];
+    before += w < wv ? t : 0;
+    tot += t;
+  }
+  *total = tot;
+  __syncthreads();
+  return incl + before;
+}
+
 #ifdef FICOCO_DBG_TIMING
 // Tuning aid (never in the product build): thread 0 of every workgroup stores its start and
 // end time on the 100 MHz wall clock; one array per translation unit.

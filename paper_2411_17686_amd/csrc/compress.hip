@@ -103,17 +103,8 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   const int lo = min(tid * per, n), hi = min(lo + per, n);
   int local = 0;
   for (int j = lo; j < hi; ++j) local += cnt[j];
-  int* cur = part;
-  int* nxt = part + nt;
-  cur[tid] = local;
-  __syncthreads();
-  for (int off = 1; off < nt; off <<= 1) {
-    nxt[tid] = cur[tid] + (tid >= off ? cur[tid - off] : 0);
-    __syncthreads();
-    int* t = cur; cur = nxt; nxt = t;
-  }
-  int run = cur[tid] - local;
-  const int total = cur[nt - 1];
+  int total;
+  int run = block_scan_inclusive(local, part, &total) - local;
   for (int j = lo; j < hi; ++j) {
     const int c = cnt[j];
     cnt[j] = run;

@@ -74,31 +74,6 @@ __device__ __forceinline__ uint64_t score_key(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
 }
 
-// Inclusive scan of one int per thread over the workgroup (wavefront shuffles, then the
-// wavefront totals through LDS); returns this thread's inclusive value, *total receives the
-// sum.  scratch: at least blockDim.x / 64 ints.
-__device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* total) {
-  const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave, nw = blockDim.x / kWave;
-  int incl = v;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int t = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += t;
-  }
-  __syncthreads();
-  if (lane == kWave - 1) scratch[wv] = incl;
-  __syncthreads();
-  int before = 0, tot = 0;
-  for (int w = 0; w < nw; ++w) {
-    const int t = scratch[w];
-    before += w < wv ? t : 0;
-    tot += t;
-  }
-  *total = tot;
-  __syncthreads();
-  return incl + before;
-}
-
 constexpr int kTokensPerThread = (kMaxSelectN + kSelectThreads - 1) / kSelectThreads;   // the kernel runs with kSelectThreads threads
 constexpr int kBinCopies = 32;      // counters per histogram bin in the many-keys form: one per LDS bank
 constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (it costs one more barrier per pass)

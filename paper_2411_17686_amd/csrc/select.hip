@@ -404,7 +404,7 @@ __global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
-  const int wide = p.N >= kSpreadMinN ? 256 * kBinCopies : 0;   // shares the penalty table's space
+  const size_t wide = p.N >= kSpreadMinN ? 256 * kBinCopies : 0;   // shares the penalty table's space
   return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + (cells > wide ? cells : wide)) * sizeof(int);
 }
 

@@ -20,6 +20,14 @@ namespace ficoco {
 #define FICOCO_HEAD_BATCH 8
 #endif
 constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
+#ifndef FICOCO_REDUCE_HEADS_OUTER
+#define FICOCO_REDUCE_HEADS_OUTER 1
+#endif
+constexpr int kRowsAtOnce = 4;     // rows of one thread whose heads are added side by side ...
+#ifndef FICOCO_REDUCE_HEADS
+#define FICOCO_REDUCE_HEADS 2
+#endif
+constexpr int kHeadsAtOnce = FICOCO_REDUCE_HEADS;    // ... this many heads of each per batch of loads (more where the thread has fewer rows)
 // LDS requested per workgroup at least (bytes): a way to bound how many workgroups of this
 // kernel a compute unit holds (160 KB / request), which leaves wavefront slots for the short
 // kernels of another stream that run next to it.
@@ -47,8 +55,10 @@ struct AttnArgs {
   double invH;
 };
 
+// Three wavefronts per SIMD (170 registers): the four-row form keeps 32 double accumulators and 8
+// raw vectors per thread, and its grids hold about three wavefronts per SIMD anyway.
 template <typename T>
-__global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a) {
+__global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(3))) void attn_reduce_kernel(AttnArgs a) {
   DBG_SPAN(0);
   extern __shared__ double lds[];
   // Workgroups that read neighbouring strips of the same rows share the cache lines at the
@@ -82,7 +92,110 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
   const int r_begin = a.row0 + chunk * a.rows_per_wg - a.shift;   // chunk 0 may begin before row0
   const int r_end = min(r_begin + a.rows_per_wg, a.row0 + a.nrows);
 
-  if (active) {
+  // What is done with the head mean of one (row, 8 columns) once its heads are added.
+  auto finish_row = [&](int r, bool is_vis, bool is_cls, double (&p)[kVec]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) p[k] *= a.invH;
+    if (is_vis) {
+#pragma unroll
+      for (int k = 0; k < kVec; ++k) mine[k] += p[k];
+      if (a.abar) {
+        float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) dst[k * tile_pitch] = (float)p[k];   // columns past N are never read back
+      }
+    }
+    if (is_cls) {
+      double* dst = a.cls + (int64_t)b * a.N + col;
+      for (int k = 0; k < ncol; ++k) dst[k] = p[k];
+    }
+  };
+
+  const int rows_per_thread = (a.rows_per_wg + a.row_lanes - 1) / a.row_lanes;
+  if (FICOCO_REDUCE_HEADS_OUTER && sizeof(T) == 2 && rows_per_thread <= kRowsAtOnce) {     // uniform
+    // All rows of this thread at once, heads outermost: a batch is a few heads of each of the
+    // thread's rows.  The loads in flight then come from a few rows of one or two head
+    // matrices -- neighbouring addresses -- instead of one row of eight matrices 665 KB apart,
+    // which the memory system serves measurably faster; every (row, column) still adds its
+    // heads in ascending order, so the sums are the same doubles.  Loads are unconditional and
+    // from valid addresses (rows outside the chunk read its nearest row, heads past H read head
+    // H-1) and what does not count is cleared with selects.
+    if (active && ncol == kVec) {
+      const T* Ab = (const T*)a.A + (int64_t)b * a.sb + a.col0 + col;
+      // ROWS = rows of this thread (compile time: the accumulators are registers)
+      auto run = [&](auto rows_c) __attribute__((always_inline)) {
+        constexpr int ROWS = decltype(rows_c)::value;
+        constexpr int HEADS = ROWS >= 3 ? kHeadsAtOnce : kHeadBatch / ROWS;   // about kHeadBatch loads in flight
+        double p[ROWS][kVec];
+        const T* base[ROWS];
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+          const int r = r_begin + rl + q * a.row_lanes;
+          base[q] = Ab + (int64_t)min(max(r, a.row0), a.row0 + a.nrows - 1) * a.sq;
+#pragma unroll
+          for (int k = 0; k < kVec; ++k) p[q][k] = 0.0;
+        }
+        for (int h0 = 0; h0 < a.H; h0 += HEADS) {
+          Raw8<T> raw[HEADS][ROWS];
+#pragma unroll
+          for (int u = 0; u < HEADS; ++u) {
+            const int64_t hoff = (int64_t)min(h0 + u, a.H - 1) * a.sh;
+#pragma unroll
+            for (int q = 0; q < ROWS; ++q) load_raw(base[q] + hoff, raw[u][q]);
+          }
+          issue_fence();
+#pragma unroll
+          for (int u = 0; u < HEADS; ++u)
+#pragma unroll
+            for (int q = 0; q < ROWS; ++q) {
+              keep_raw_if(raw[u][q], h0 + u < a.H);
+              add_raw(raw[u][q], p[q]);
+            }
+        }
+#pragma unroll
+        for (int q = 0; q < ROWS; ++q) {
+          const int r = r_begin + rl + q * a.row_lanes;
+          const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
+          const bool is_cls = r == a.cls_r;
+          if (r < r_end && r >= a.row0 && (is_vis || is_cls)) {
+#pragma unroll
+            for (int k = 0; k < kVec; ++k) p[q][k] *= a.invH;
+            if (is_vis) {
+#pragma unroll
+              for (int k = 0; k < kVec; ++k) mine[k] += p[q][k];
+              if (a.abar) {
+                float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
+#pragma unroll
+                for (int k = 0; k < kVec; ++k) dst[k * tile_pitch] = (float)p[q][k];
+              }
+            }
+            if (is_cls) {
+              double* dst = a.cls + (int64_t)b * a.N + col;
+#pragma unroll
+              for (int k = 0; k < kVec; ++k) dst[k] = p[q][k];
+            }
+          }
+        }
+      };
+      if (rows_per_thread <= 1) run(std::integral_constant<int, 1>{});
+      else if (rows_per_thread == 2) run(std::integral_constant<int, 2>{});
+      else if (rows_per_thread == 3) run(std::integral_constant<int, 3>{});
+      else run(std::integral_constant<int, 4>{});
+    } else if (active) {
+      const T* Ab = (const T*)a.A + (int64_t)b * a.sb + a.col0 + col;
+      for (int r = r_begin + rl; r < r_end; r += a.row_lanes) {
+        const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
+        const bool is_cls = r == a.cls_r;
+        if (r < a.row0 || !(is_vis || is_cls)) continue;
+        double p[kVec];
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) p[k] = 0.0;
+        for (int h = 0; h < a.H; ++h)
+          for (int k = 0; k < ncol; ++k) p[k] += widen(Ab[(int64_t)r * a.sq + (int64_t)h * a.sh + k]);
+        finish_row(r, is_vis, is_cls, p);
+      }
+    }
+  } else if (active) {
     const T* Ab = (const T*)a.A + (int64_t)b * a.sb + a.col0 + col;
     for (int r = r_begin + rl; r < r_end; r += a.row_lanes) {
       const bool is_vis = r >= a.vis_r0 && r < a.vis_r0 + a.n_vis;
@@ -112,22 +225,7 @@ __global__ __launch_bounds__(kReduceThreads) void attn_reduce_kernel(AttnArgs a)
         for (int h = 0; h < a.H; ++h)
           for (int k = 0; k < ncol; ++k) p[k] += widen(base[(int64_t)h * a.sh + k]);
       }
-#pragma unroll
-      for (int k = 0; k < kVec; ++k) p[k] *= a.invH;
-
-      if (is_vis) {
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) mine[k] += p[k];
-        if (a.abar) {
-          float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
-#pragma unroll
-          for (int k = 0; k < kVec; ++k) dst[k * tile_pitch] = (float)p[k];   // columns past N are never read back
-        }
-      }
-      if (is_cls) {
-        double* dst = a.cls + (int64_t)b * a.N + col;
-        for (int k = 0; k < ncol; ++k) dst[k] = p[k];
-      }
+      finish_row(r, is_vis, is_cls, p);
     }
   }
 

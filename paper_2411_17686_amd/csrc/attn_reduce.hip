@@ -252,14 +252,14 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
     }
   }
   if (a.recv_part == nullptr) return;  // uniform for the whole grid
-  // Combine the row lanes in a fixed order, then one partial per (image, chunk, column).
-  if (rl == 0 && ncol > 0) {
-    double* dst = a.recv_part + ((int64_t)b * a.n_chunks + chunk) * a.N + col;
-    for (int k = 0; k < ncol; ++k) {
-      double s = 0.0;
-      for (int l = 0; l < a.row_lanes; ++l) s += lds[l * width + cg * kVec + k];
-      dst[k] = s;
-    }
+  // Combine the row lanes in a fixed order, then one partial per (image, chunk, column): one
+  // thread per column of the strip (the workgroup's last act -- eight columns per thread would
+  // keep its slot for eight times as many dependent LDS reads).
+  const int strip_col0 = strip * width;
+  for (int c = tid; c < width && strip_col0 + c < a.N; c += (int)blockDim.x) {
+    double s = 0.0;
+    for (int l = 0; l < a.row_lanes; ++l) s += lds[l * width + c];
+    a.recv_part[((int64_t)b * a.n_chunks + chunk) * a.N + strip_col0 + c] = s;
   }
 }
 

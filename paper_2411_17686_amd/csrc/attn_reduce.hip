@@ -152,6 +152,9 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
               add_raw(raw[u][q], p[q]);
             }
         }
+        double colsum[kVec];       // this thread's column partial: all its rows are here, so it is formed in registers
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) colsum[k] = 0.0;
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
           const int r = r_begin + rl + q * a.row_lanes;
@@ -162,7 +165,7 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
             for (int k = 0; k < kVec; ++k) p[q][k] *= a.invH;
             if (is_vis) {
 #pragma unroll
-              for (int k = 0; k < kVec; ++k) mine[k] += p[q][k];
+              for (int k = 0; k < kVec; ++k) colsum[k] += p[q][k];      // rows in ascending order, from zero
               if (a.abar) {
                 float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
 #pragma unroll
@@ -176,6 +179,8 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
             }
           }
         }
+#pragma unroll
+        for (int k = 0; k < kVec; ++k) mine[k] = colsum[k];
       };
       if (rows_per_thread <= 1) run(std::integral_constant<int, 1>{});
       else if (rows_per_thread == 2) run(std::integral_constant<int, 2>{});

@@ -75,14 +75,9 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
   const int ncol = min(kVec, a.N - col);
   const bool active = rl < a.row_lanes && ncol > 0;
 
-  // This thread's column partial lives in its own LDS slots while it walks its rows (registers
-  // are what limits the number of resident wavefronts here).
+  // Where this thread leaves its column partial for the combination of the row lanes.
   const int width = a.strip_groups * kVec;
   double* mine = lds + (rl < a.row_lanes ? rl : 0) * width + cg * kVec;
-  if (rl < a.row_lanes) {
-#pragma unroll
-    for (int k = 0; k < kVec; ++k) mine[k] = 0.0;
-  }
 
   // The head-mean map leaves transposed (abar[key token][query token], what the correlate stage
   // reads row by row): this workgroup's tile, strip columns x chunk rows, is turned in LDS and
@@ -92,13 +87,19 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
   const int r_begin = a.row0 + chunk * a.rows_per_wg - a.shift;   // chunk 0 may begin before row0
   const int r_end = min(r_begin + a.rows_per_wg, a.row0 + a.nrows);
 
+  // This thread's column partial over its rows (rows in ascending order, from zero): kept in
+  // registers and handed to LDS once -- a read-modify-write of LDS per row sat on every
+  // workgroup's critical path (2 us of the kernel at the batched ViT shape).
+  double colsum[kVec];
+#pragma unroll
+  for (int k = 0; k < kVec; ++k) colsum[k] = 0.0;
   // What is done with the head mean of one (row, 8 columns) once its heads are added.
   auto finish_row = [&](int r, bool is_vis, bool is_cls, double (&p)[kVec]) __attribute__((always_inline)) {
 #pragma unroll
     for (int k = 0; k < kVec; ++k) p[k] *= a.invH;
     if (is_vis) {
 #pragma unroll
-      for (int k = 0; k < kVec; ++k) mine[k] += p[k];
+      for (int k = 0; k < kVec; ++k) colsum[k] += p[k];
       if (a.abar) {
         float* dst = tile + (cg * kVec) * tile_pitch + (r - r_begin);
 #pragma unroll
@@ -152,9 +153,6 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
               add_raw(raw[u][q], p[q]);
             }
         }
-        double colsum[kVec];       // this thread's column partial: all its rows are here, so it is formed in registers
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) colsum[k] = 0.0;
 #pragma unroll
         for (int q = 0; q < ROWS; ++q) {
           const int r = r_begin + rl + q * a.row_lanes;
@@ -179,8 +177,6 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
             }
           }
         }
-#pragma unroll
-        for (int k = 0; k < kVec; ++k) mine[k] = colsum[k];
       };
       if (rows_per_thread <= 1) run(std::integral_constant<int, 1>{});
       else if (rows_per_thread == 2) run(std::integral_constant<int, 2>{});
@@ -234,6 +230,10 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
     }
   }
 
+  if (rl < a.row_lanes) {
+#pragma unroll
+    for (int k = 0; k < kVec; ++k) mine[k] = colsum[k];
+  }
   __syncthreads();
   if (a.abar) {
     // pieces of 4 query rows: thread -> (key column of the strip, piece), consecutive threads

@@ -74,7 +74,7 @@ __device__ __forceinline__ uint64_t score_key(double s) {
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
 }
 
-constexpr int kTokensPerThread = (kMaxSelectN + kSelectThreads - 1) / kSelectThreads;   // the kernel runs with kSelectThreads threads
+constexpr int kTokensPerThread = (kMaxSelectN + kSelectThreads - 1) / kSelectThreads;   // sequences longer than kSelectThreads run with kSelectThreads threads
 constexpr int kBinCopies = 32;      // counters per histogram bin in the many-keys form: one per LDS bank
 constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (it costs one more barrier per pass)
 static_assert(kSelectThreads == 4 * 256, "four threads fold the counters of one bin");
@@ -458,7 +458,10 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   const size_t lds = select_lds(p, penalty);
   if (lds > 32768)
     (void)hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL(select_kernel, dim3(p.B), dim3(kSelectThreads), lds, s, a);
+  // Short sequences: no more wavefronts than tokens need (every barrier of the kernel waits for
+  // all of them); at least 256 threads, which the histogram walk assumes.
+  const int threads = p.N >= kSelectThreads ? kSelectThreads : std::max(256, (p.N + kWave - 1) / kWave * kWave);
+  hipLaunchKernelGGL(select_kernel, dim3(p.B), dim3(threads), lds, s, a);
 }
 
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {

@@ -27,7 +27,10 @@ namespace ficoco {
 #define FICOCO_MAP_ROWS_MAX 32
 #endif
 constexpr int kMapRowLanes = FICOCO_MAP_ROW_LANES;
-constexpr int kMapRowsAlign = 8;
+#ifndef FICOCO_MAP_ROWS_ALIGN
+#define FICOCO_MAP_ROWS_ALIGN 8
+#endif
+constexpr int kMapRowsAlign = FICOCO_MAP_ROWS_ALIGN;
 #ifndef FICOCO_WG_TARGET
 #define FICOCO_WG_TARGET 2048
 #endif

@@ -31,8 +31,11 @@ constexpr int kMapRowLanes = FICOCO_MAP_ROW_LANES;
 #define FICOCO_MAP_ROWS_ALIGN 8
 #endif
 constexpr int kMapRowsAlign = FICOCO_MAP_ROWS_ALIGN;
+// Workgroups the reduction aims at (half of it where the map tile is turned).  Measured: 1024 against
+// 2048 changes nothing at the batched ViT shapes and gives the decoder shape (8 sequences, 32 heads)
+// 32-row chunks instead of 16-row ones, 42.5 against 44.0 us.
 #ifndef FICOCO_WG_TARGET
-#define FICOCO_WG_TARGET 2048
+#define FICOCO_WG_TARGET 1024
 #endif
 constexpr int64_t kWgTarget = FICOCO_WG_TARGET;
 

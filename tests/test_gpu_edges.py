@@ -53,6 +53,16 @@ def test_long_sequence_with_tied_scores(ctx, levels, window):
     assert out["X_out"].shape == (2, 700, 64)
 
 
+@pytest.mark.parametrize("grid,H,B", [(32, 5, 3), (32, 3, 2), (24, 7, 4), (40, 1, 1)])
+def test_reduction_chunk_shapes_and_odd_head_counts(ctx, grid, H, B):
+    """The attention reduction adds the heads of up to four rows per thread side by side, a few
+    heads per batch of loads: head counts that do not fill the last batch, and batch / sequence
+    sizes that give a thread one to four rows of its chunk."""
+    cfg = synth.ficoco_v_single(seed=74 + grid + H, B=B, grid=grid, D=16, H=H, centres=12, dtype="bf16",
+                                n_keep=(grid * grid * 2) // 3)
+    _check(cfg, ctx)
+
+
 def test_one_token_over_the_limit_is_rejected(ctx):
     X = torch.zeros(1, 12289, 8, dtype=torch.bfloat16, device="cuda")
     v = torch.zeros(1, 2, 12289, dtype=torch.bfloat16, device="cuda")

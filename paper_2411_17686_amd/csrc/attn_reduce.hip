@@ -273,6 +273,7 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
 // owns 8 consecutive text rows x 256 key columns: a thread forms the head mean of one row and
 // 8 columns exactly as the kernel above does (heads added in order, in double), the tile is
 // turned in LDS, and each thread then writes the 8 rows of one column as one 64-byte piece.
+constexpr int kTextHeadBatch = 16;
 constexpr int kTextRows = 8;
 constexpr int kTextGroups = 256 / kTextRows;      // 8-column groups per workgroup
 template <typename T>
@@ -293,6 +294,16 @@ __global__ __launch_bounds__(256) void text_reduce_kernel(AttnArgs a) {
     for (int k = 0; k < kVec; ++k) p[k] = 0.0;
     if (ncol == kVec) {
       int h0 = 0;
+      // the grid of this kernel is small (8 rows x 256 keys per workgroup), so each thread keeps
+      // more loads in flight than the map kernel does: kTextHeadBatch heads at a time
+      for (; h0 + kTextHeadBatch <= a.H; h0 += kTextHeadBatch) {
+        Raw8<T> raw[kTextHeadBatch];
+#pragma unroll
+        for (int u = 0; u < kTextHeadBatch; ++u) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
+        issue_fence();
+#pragma unroll
+        for (int u = 0; u < kTextHeadBatch; ++u) add_raw(raw[u], p);
+      }
       for (; h0 + kHeadBatch <= a.H; h0 += kHeadBatch) {
         Raw8<T> raw[kHeadBatch];
 #pragma unroll

@@ -202,11 +202,18 @@ __global__ __launch_bounds__(256) void col_mean_kernel(FeatArgs a) {
     a.colmean[(int64_t)a.B * a.Df + b * a.Df + d] = mu;
     mm = mu * mu;
   }
+  if (!a.want_eq) return;          // uniform: only the equivalent-token term reads the squared norm
   red[threadIdx.x] = mm;
   __syncthreads();
   if (threadIdx.x == 0) {
     double t = 0.0;
-    for (int k = 0; k < (int)blockDim.x; ++k) t += red[k];      // fixed order
+    for (int k0 = 0; k0 < (int)blockDim.x; k0 += 16) {          // fixed order, sixteen reads at a time
+      double v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = red[k0 + u];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) t += v[u];
+    }
     a.colmean[2 * (int64_t)a.B * a.Df + b * gridDim.x + blockIdx.x] = t;
   }
 }

@@ -522,6 +522,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     load_pass(c0);
 #pragma unroll
     for (int u = 0; u < kCandKeep; ++u) {
+      if (c0 + u * kWave >= n) break;           // uniform: slots past the row hold nothing
       float lo = val[u] == NEGF ? NEGF : gam * fmaxf(val[u] - delta, 0.0f);
       if (lo > top[MC - 1]) {
 #pragma unroll

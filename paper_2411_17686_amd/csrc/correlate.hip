@@ -509,8 +509,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
         }
       }
 #pragma unroll
-      for (int u = 0; u < kCandKeep; ++u)
+      for (int u = 0; u < kCandKeep; ++u) {
+        if (c0 + u * kWave >= n) break;         // uniform: no reader looks at slots past the row
         if (c0 + u * kWave + lane >= n) val[u] = NEGF;
+      }
     }
   };
 

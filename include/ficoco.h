@@ -9,8 +9,11 @@
  * Conventions that hold for every entry point
  *   - Plain C: no C++ types, no exceptions cross this boundary.
  *   - Every data pointer is a DEVICE pointer owned by the caller (tokens, maps, outputs and
- *     the workspace).  The library allocates no device memory and frees nothing of the
- *     caller's.  Outputs must not alias inputs.
+ *     the workspace), on the device the ctx was created for, which must be the calling
+ *     thread's current device (checked: FICOCO_EINVAL otherwise).  The library allocates no
+ *     device memory and frees nothing of the caller's.  Outputs must not alias inputs
+ *     (X_out overlapping X or the workspace is rejected with FICOCO_EINVAL; the small index
+ *     and edge outputs are not checked).
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  All work is
  *     enqueued on it asynchronously; no call synchronises the device or copies to the host.
  *   - Return value: a ficoco_status.  Argument errors are found on the host before anything
@@ -44,6 +47,10 @@ typedef enum {
   FICOCO_EHIP = 3,
   FICOCO_EUNSUPPORTED = 4
 } ficoco_status;
+/* There is no status for "a discarded token had more than k_max targets": whether that
+ * happened is known only once the kernels have run, and no call waits for them.  It is
+ * reported per image through the `overflow` array on the device instead, which the caller
+ * reads whenever it next synchronises. */
 
 typedef enum { FICOCO_F32 = 0, FICOCO_BF16 = 1 } ficoco_dtype;
 
@@ -151,7 +158,7 @@ typedef struct {
   int32_t compress_mode; /* ficoco_compress_mode                                           */
 } ficoco_problem;
 
-/* ctx: create once per device; not thread safe (one ctx per calling thread). */
+/* ctx: create once per device (and calling thread); not thread safe. */
 int ficoco_create(ficoco_ctx **out, int device);
 int ficoco_destroy(ficoco_ctx *ctx);
 const char *ficoco_last_error(const ficoco_ctx *ctx);

@@ -58,6 +58,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   REQUIRE(p.x_stride_n >= p.D && p.x_stride_b >= 0, "bad X strides");
   REQUIRE(p.eps >= 0.0f && p.eps <= 1.0f, "eps must be in [0, 1]");
   REQUIRE(p.k_max >= 1, "k_max must be >= 1");
+  REQUIRE(p.k_max <= kMaxSelectN, "k_max exceeds 12288 (N^S * k_max is indexed with 32-bit integers)");
   REQUIRE(p.k_mode >= FICOCO_K_ADAPTIVE && p.k_mode <= FICOCO_K_CONVERGENT, "unknown k_mode");
   REQUIRE(p.compress_mode == FICOCO_COMPRESS_SELF || p.compress_mode == FICOCO_COMPRESS_AVERAGE,
           "unknown compress_mode");
@@ -85,6 +86,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   if (L) {
     REQUIRE(p.sem_src == FICOCO_G_TEXT_ATTN, "FiCoCo-L uses the text-attention term (Eq. 3)");
     REQUIRE(p.A_text != nullptr && p.M >= 1 && p.H >= 1, "A_text / M missing for FiCoCo-L");
+    REQUIRE(p.gamma >= 0.0f && p.gamma <= 1.0f, "gamma (Eq. 4) must be in [0, 1]");
     REQUIRE(p.at_stride_q >= p.at_nk && p.at_k_begin <= p.vis_begin &&
                 p.vis_begin + p.N <= p.at_k_begin + p.at_nk, "A_text does not cover the visual keys");
   } else {
@@ -242,10 +244,36 @@ static int fail(ficoco_ctx* ctx, int code, const char* what, const char* detail)
   return code;
 }
 
+// The calling thread's current device must be the one the ctx was created for: every launch
+// goes to the current device, and the caller's pointers and stream belong to it.
+static int check_device(ficoco_ctx* ctx, const char* fn) {
+  int cur = -1;
+  if (hipGetDevice(&cur) != hipSuccess) return fail(ctx, FICOCO_EHIP, fn, "hipGetDevice failed");
+  if (cur != ctx->device) return fail(ctx, FICOCO_EINVAL, fn, "the current device is not the device this ctx was created for");
+  return FICOCO_OK;
+}
+
+// Do the byte ranges [a, a + na) and [b, b + nb) overlap?
+static bool ranges_overlap(const void* a, size_t na, const void* b, size_t nb) {
+  const uintptr_t a0 = (uintptr_t)a, b0 = (uintptr_t)b;
+  return a && b && na && nb && a0 < b0 + nb && b0 < a0 + na;
+}
+
+// Bytes from X to the end of its last row, and of the dense X_out.
+static size_t x_extent(const ficoco_problem& p) {
+  const size_t es = p.dtype == FICOCO_BF16 ? 2 : 4;
+  return ((size_t)(p.B - 1) * (size_t)p.x_stride_b + (size_t)(p.n_tot - 1) * (size_t)p.x_stride_n + (size_t)p.D) * es;
+}
+static size_t x_out_extent(const ficoco_problem& p, const Plan& pl) {
+  return (size_t)p.B * (size_t)pl.n_out * (size_t)p.D * (p.dtype == FICOCO_BF16 ? 2 : 4);
+}
+
 static int prepare(ficoco_ctx* ctx, const ficoco_problem* p, const void* ws, size_t ws_bytes,
                    Plan& pl, const char* fn) {
   if (!ctx) return FICOCO_EINVAL;
   if (!p) return fail(ctx, FICOCO_EINVAL, fn, "problem is NULL");
+  const int dev_rc = check_device(ctx, fn);
+  if (dev_rc != FICOCO_OK) return dev_rc;
   const char* why;
   const int rc = make_plan(*p, pl, &why);
   if (rc != FICOCO_OK) return fail(ctx, rc, fn, why);
@@ -274,6 +302,10 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
       (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, fn, "an output pointer is NULL");
   const ficoco_problem& p = *p0;
+  if (ranges_overlap(X_out, x_out_extent(p, pl), p.X, x_extent(p)))
+    return fail(ctx, FICOCO_EINVAL, fn, "X_out overlaps X (outputs may not alias inputs)");
+  if (ranges_overlap(X_out, x_out_extent(p, pl), ws, pl.total))
+    return fail(ctx, FICOCO_EINVAL, fn, "X_out overlaps the workspace");
   hipStream_t s = (hipStream_t)stream;
   char* w = (char*)ws;
   const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
@@ -414,6 +446,8 @@ int ficoco_gather_tokens(ficoco_ctx* ctx, const ficoco_problem* p, const int32_t
                          int64_t in_stride_b, int64_t in_stride_n, int32_t row_bytes, void* out, void* stream) {
   if (!ctx) return FICOCO_EINVAL;
   if (!p) return fail(ctx, FICOCO_EINVAL, "ficoco_gather_tokens", "problem is NULL");
+  const int dev_rc = check_device(ctx, "ficoco_gather_tokens");
+  if (dev_rc != FICOCO_OK) return dev_rc;
   Plan pl;
   const char* why;
   const int rc = make_plan(*p, pl, &why);
@@ -437,6 +471,8 @@ int ficoco_compress(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t w
   if (rc != FICOCO_OK) return rc;
   if (!X_out || !keep_idx || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_compress", "a pointer is NULL");
+  if (ranges_overlap(X_out, x_out_extent(*p, pl), p->X, x_extent(*p)))
+    return fail(ctx, FICOCO_EINVAL, "ficoco_compress", "X_out overlaps X (outputs may not alias inputs)");
   launch_compress(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out,
                   pos_out, (hipStream_t)stream);
   return finish(ctx, "ficoco_compress");

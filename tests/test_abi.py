@@ -68,7 +68,7 @@ def test_workspace_query_and_argument_checks():
     assert n >= 16 * 576 * 576 * 4 and n < 64 * 2 ** 20
     bad = [("n_keep", 577), ("n_keep", 0), ("eps", 1.5), ("k_max", 0), ("dtype", 7), ("N", 577),
            ("cls_index", 5), ("a_nk", 100), ("window", 2, "grid_h", 3), ("sem_src", fc.G_TEXT_ATTN),
-           ("N", 20000)]
+           ("N", 20000), ("k_max", 20000)]
     for spec in bad:
         q = _valid_problem()
         for k, v in zip(spec[0::2], spec[1::2]):
@@ -84,6 +84,13 @@ def test_workspace_query_and_argument_checks():
     q.A_text, q.M, q.at_stride_b, q.at_stride_h, q.at_stride_q = 4096, 64, 1, 1, 576
     q.at_k_begin, q.at_nk = 1, 576
     assert fc.workspace_bytes(q) > n
+    # Eq. 4's gamma is a convex weight: the candidate bounds of the correlate stage need 0 <= gamma <= 1
+    for g in (-0.1, 1.5, float("nan")):
+        q.gamma = g
+        with pytest.raises(fc.FicocoError) as e:
+            fc.workspace_bytes(q)
+        assert e.value.code == fc.EINVAL
+    q.gamma = 0.6
     # zero discards is legal
     q = _valid_problem()
     q.n_keep = 576

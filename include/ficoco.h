@@ -158,7 +158,8 @@ typedef struct {
   int32_t compress_mode; /* ficoco_compress_mode                                           */
 } ficoco_problem;
 
-/* ctx: create once per device (and calling thread); not thread safe. */
+/* ctx: create once per device (and calling thread); not thread safe.  ficoco_create also
+ * looks up, for that device, the address of the static scratch of ficoco_v_step_static. */
 int ficoco_create(ficoco_ctx **out, int device);
 int ficoco_destroy(ficoco_ctx *ctx);
 const char *ficoco_last_error(const ficoco_ctx *ctx);
@@ -319,6 +320,26 @@ int ficoco_l_step(ficoco_ctx *ctx, const ficoco_problem *p, void *ws, size_t ws_
                   void *X_out, int32_t *pos_out, int32_t *keep_idx, int32_t *discard_idx,
                   int32_t *edge_cnt, int32_t *edge_tgt, double *edge_alpha, double *scores,
                   int32_t *overflow, void *stream);
+
+/*
+ * ficoco_v_step for callers that cannot allocate or hand over a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * ficoco_v_step without `ws` / `ws_bytes`: the step's workspace is a static device array of
+ * FICOCO_STATIC_SCRATCH_BYTES inside the library (one copy per GPU, held until the process
+ * ends).  The call allocates and frees nothing and launches the same kernels.
+ *   - A problem whose ficoco_workspace_bytes exceeds FICOCO_STATIC_SCRATCH_BYTES is rejected
+ *     with FICOCO_ENOMEM before anything is launched (the batched 576-token ViT shape,
+ *     B = 16, needs about 25 MB and fits).
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU
+ *     (two streams, two threads) race and give undefined results; calls on one stream are
+ *     ordered and safe.  The array keeps the previous call's contents; every kernel writes
+ *     what it later reads, so nothing has to be cleared between calls.
+ */
+#define FICOCO_STATIC_SCRATCH_BYTES ((size_t)32 << 20)
+int ficoco_v_step_static(ficoco_ctx *ctx, const ficoco_problem *p, void *X_out, int32_t *pos_out,
+                         int32_t *keep_idx, int32_t *discard_idx, int32_t *edge_cnt,
+                         int32_t *edge_tgt, double *edge_alpha, double *scores, int32_t *overflow,
+                         void *stream);
 
 #ifdef __cplusplus
 }

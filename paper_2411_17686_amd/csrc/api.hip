@@ -8,6 +8,16 @@
 
 #include "common.hpp"
 
+// Scratch of the allocation-free entry point (ficoco_v_step_static): the workspace of a step
+// lives in this file-scope device array instead of caller memory.  Every GPU the library runs
+// on holds its own copy for the life of the process.  Host code never passes the array's name to
+// a kernel (on the host it is a stand-in symbol, not a device address): ficoco_create asks the
+// runtime for the array's address on the ctx's device and keeps it in g_static_ws.
+constexpr size_t kStaticScratchBytes = FICOCO_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char g_static_scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static void* g_static_ws[kMaxDevices];    // per device, filled by ficoco_create (written once per device with the same value)
+
 struct ficoco_ctx {
   int device;
   hipEvent_t probe_start, probe_stop;   // measurement hook, both null when off
@@ -332,6 +342,17 @@ int ficoco_create(ficoco_ctx** out, int device) {
   *out = nullptr;
   int count = 0;
   if (hipGetDeviceCount(&count) != hipSuccess || device < 0 || device >= count) return FICOCO_EHIP;
+  if (device < kMaxDevices && g_static_ws[device] == nullptr) {
+    // the scratch array's address on this device, asked for with that device current
+    int prev = -1;
+    if (hipGetDevice(&prev) != hipSuccess) return FICOCO_EHIP;
+    if (prev != device && hipSetDevice(device) != hipSuccess) return FICOCO_EHIP;
+    void* ptr = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch));
+    if (prev != device) (void)hipSetDevice(prev);
+    if (e != hipSuccess || ptr == nullptr) return FICOCO_EHIP;
+    g_static_ws[device] = ptr;
+  }
   ficoco_ctx* c = new (std::nothrow) ficoco_ctx;
   if (!c) return FICOCO_ENOMEM;
   c->device = device;
@@ -484,6 +505,24 @@ int ficoco_v_step(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_
                   void* stream) {
   return run_step(ctx, p, FICOCO_VARIANT_V, ws, ws_bytes, X_out, pos_out, keep_idx, discard_idx,
                   edge_cnt, edge_tgt, edge_alpha, scores, overflow, stream, "ficoco_v_step");
+}
+
+int ficoco_v_step_static(ficoco_ctx* ctx, const ficoco_problem* p, void* X_out, int32_t* pos_out,
+                         int32_t* keep_idx, int32_t* discard_idx, int32_t* edge_cnt, int32_t* edge_tgt,
+                         double* edge_alpha, double* scores, int32_t* overflow, void* stream) {
+  const char* fn = "ficoco_v_step_static";
+  if (!ctx) return FICOCO_EINVAL;
+  if (!p) return fail(ctx, FICOCO_EINVAL, fn, "problem is NULL");
+  Plan pl;
+  const char* why;
+  const int rc = make_plan(*p, pl, &why);
+  if (rc != FICOCO_OK) return fail(ctx, rc, fn, why);
+  if (pl.total > kStaticScratchBytes)
+    return fail(ctx, FICOCO_ENOMEM, fn, "the step's workspace exceeds the 32 MiB static scratch: use ficoco_v_step with a caller workspace");
+  void* ws = ctx->device < kMaxDevices ? g_static_ws[ctx->device] : nullptr;
+  if (!ws) return fail(ctx, FICOCO_EHIP, fn, "no static scratch on this device");
+  return run_step(ctx, p, FICOCO_VARIANT_V, ws, kStaticScratchBytes, X_out, pos_out, keep_idx, discard_idx,
+                  edge_cnt, edge_tgt, edge_alpha, scores, overflow, stream, fn);
 }
 
 int ficoco_l_step(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_bytes, void* X_out,

@@ -25,7 +25,8 @@ COMPRESS_SELF, COMPRESS_AVERAGE = 0, 1
 EXPORTS = ["ficoco_create", "ficoco_destroy", "ficoco_last_error", "ficoco_version",
            "ficoco_set_probe", "ficoco_workspace_bytes", "ficoco_out_rows", "ficoco_reduce", "ficoco_score",
            "ficoco_filter", "ficoco_correlate", "ficoco_correlation_gap", "ficoco_compress", "ficoco_v_step",
-           "ficoco_l_step", "ficoco_schedule", "ficoco_gather_tokens"]
+           "ficoco_l_step", "ficoco_schedule", "ficoco_gather_tokens", "ficoco_v_step_static"]
+STATIC_SCRATCH_BYTES = 32 << 20
 
 
 class Problem(C.Structure):
@@ -91,6 +92,7 @@ def lib():
         step = [vp, pp, vp, C.c_size_t, vp, i32p, i32p, i32p, i32p, i32p, f64p, f64p, i32p, vp]
         L.ficoco_v_step.argtypes = step
         L.ficoco_l_step.argtypes = step
+        L.ficoco_v_step_static.argtypes = step[:2] + step[4:]
         L.ficoco_gather_tokens.argtypes = [vp, pp, i32p, vp, C.c_int64, C.c_int64, C.c_int32, vp, vp]
         L.ficoco_schedule.argtypes = [C.POINTER(ScheduleProblem), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         for name in EXPORTS:
@@ -304,6 +306,13 @@ def ficoco_v_step(ctx, p, buf):
 
 def ficoco_l_step(ctx, p, buf):
     _step(lib().ficoco_l_step, ctx, p, buf)
+
+
+def ficoco_v_step_static(ctx, p, buf):
+    """ficoco_v_step on the library's static scratch: `buf.ws` is not used."""
+    ctx.check(lib().ficoco_v_step_static(ctx._h, C.byref(p), _ptr(buf.X_out), _ptr(buf.pos_out), _ptr(buf.keep_idx),
+                                         _ptr(buf.discard_idx), _ptr(buf.edge_cnt), _ptr(buf.edge_tgt),
+                                         _ptr(buf.edge_alpha), _ptr(buf.scores), _ptr(buf.overflow), ctx.stream()))
 
 
 def ficoco_schedule(variant, layers, start_layer, N, M, D, F, min_keep, budget_flops):

@@ -170,27 +170,56 @@ def unit_rows(F):
 
 def equivalent_token_term(F):
     """Appendix "Implementation of the Equivalent Token": mu = mean of the patch features
-    (the caller supplies head-mean keys), a_i^Eq = -cos(mu, F_i).  Replaces a^CLS in Eq. 1."""
+    (the caller supplies head-mean keys), a_i^Eq = -cos(mu, F_i).  Replaces a^CLS in Eq. 1.
+    Every sum runs in index order (tokens for mu, features for the dot product and the norms),
+    products and sums rounded separately, so the value is one definite float64."""
     F = np.asarray(F, dtype=F64)
     mu = np.zeros(F.shape[1], dtype=F64)
     for i in range(F.shape[0]):
         mu = mu + F[i]
     mu = mu / float(F.shape[0])
-    mu_n = math.sqrt(float(np.sum(mu * mu)))
+    mm = 0.0
+    for d in range(F.shape[1]):
+        mm = mm + float(mu[d]) * float(mu[d])
+    mu_n = math.sqrt(mm)
     nrm = l2_norms(F)
+    dots = np.zeros(F.shape[0], dtype=F64)
+    for d in range(F.shape[1]):
+        dots = dots + mu[d] * F[:, d]
     out = np.zeros(F.shape[0], dtype=F64)
     for i in range(F.shape[0]):
         if mu_n > 0.0 and nrm[i] > 0.0:
-            out[i] = -(float(np.dot(mu, F[i])) / (mu_n * nrm[i]))
+            out[i] = -(dots[i] / (mu_n * nrm[i]))
     return out
+
+
+def cosine_matrix(F):
+    """cos(F_i, F_j) for all pairs: the dot product of the two unit rows, features added in
+    order, products and sums rounded separately.  (Rows are taken 32 at a time only so that the
+    running sums stay in the CPU's cache; every entry is the same in-order sum either way.)"""
+    U = unit_rows(F)
+    n = U.shape[0]
+    Ut = np.ascontiguousarray(U.T)                  # Ut[d] = feature d of every unit row
+    G = np.zeros((n, n), dtype=F64)
+    for i0 in range(0, n, 32):
+        Ub = np.ascontiguousarray(U[i0:i0 + 32].T)  # Ub[d] = feature d of these rows
+        acc = np.zeros((Ub.shape[1], n), dtype=F64)
+        prod = np.empty_like(acc)
+        for d in range(U.shape[1]):
+            np.multiply(Ub[d][:, None], Ut[d][None, :], out=prod)
+            acc += prod
+        G[i0:i0 + 32] = acc
+    return G
 
 
 def mean_cosine_term(F):
     """Reading R10 (extension): (1/N) sum_j cos(F_i, F_j), j = i included -- the plain
-    definition through the full cosine matrix."""
-    U = unit_rows(F)
-    G = U @ U.T
-    return G.sum(axis=1) / float(F.shape[0])
+    definition through the full cosine matrix, the cosines of a token added in order of j."""
+    G = cosine_matrix(F)
+    acc = np.zeros(G.shape[0], dtype=F64)
+    for j in range(G.shape[1]):
+        acc = acc + G[:, j]
+    return acc / float(G.shape[0])
 
 
 def combine_score(R, G, w):

@@ -149,6 +149,28 @@ def test_mean_cosine_closed_forms():
     assert np.allclose(O.mean_cosine_term(F), ref, rtol=1e-13)
 
 
+def test_cosine_terms_tie_exactly_where_the_features_are_collinear():
+    """Both cosine-derived score terms are sums in a fixed index order, so tokens that differ by
+    a sign-preserving power of two -- and every token when there is one feature -- get the very
+    same float64 (the filter then ranks them by index).  With one feature the values are the
+    closed forms (n_same - n_opposite)/N and -sign(mu) sign(F_i)."""
+    F = np.array([[0.75], [-2.5], [3.0], [0.125], [-7.0]])
+    R = O.mean_cosine_term(F)
+    assert np.array_equal(R, np.array([0.2, -0.2, 0.2, 0.2, -0.2]))
+    G = O.equivalent_token_term(F)                       # mu = -5.625 / 5 < 0
+    assert np.array_equal(G, np.array([1.0, -1.0, 1.0, 1.0, -1.0]))
+    r = rng(41)
+    base = r.standard_normal((6, 24)).astype(np.float32).astype(np.float64)
+    F = np.concatenate([base, 4.0 * base[:3], 0.5 * base[3:]])
+    R, G = O.mean_cosine_term(F), O.equivalent_token_term(F)
+    assert np.array_equal(R[6:9], R[:3]) and np.array_equal(R[9:], R[3:6])
+    assert np.array_equal(G[6:9], G[:3]) and np.array_equal(G[9:], G[3:6])
+    # the cosine matrix against a library matrix product of the unit rows
+    U = F / np.linalg.norm(F, axis=1)[:, None]
+    assert np.allclose(O.cosine_matrix(F), U @ U.T, rtol=0, atol=1e-14)
+    assert np.allclose(np.diag(O.cosine_matrix(F)), 1.0, rtol=0, atol=1e-14)
+
+
 # ------------------------------------------------------------------ local penalty
 def test_local_penalty_golden_4x4():
     """Hand-computed example (tests/golden/local_penalty_4x4.txt): 4x4 grid, 2x2 windows,

@@ -245,6 +245,12 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   // + padding: the row kernel reads whole 2048-target passes
   pl.ct = take(pl.use_gram ? (pl.gram_splits * B * (size_t)pl.n_disc * p.n_keep + kCandPad) * sizeof(float) : 0);
   pl.cmax = take(L ? B * (size_t)p.M * sizeof(double) : 0);
+  const bool exact_terms = p.red_src == FICOCO_R_SIM_MEAN || p.sem_src == FICOCO_G_EQ_TOKEN;
+  pl.ex_nrm = take(exact_terms ? B * N * sizeof(double) : 0);
+  pl.ex_mu = take(exact_terms ? B * (size_t)(pl.Df + 1) * sizeof(double) : 0);
+  pl.ex_u = take(exact_terms ? B * 8 * (size_t)pl.Df * sizeof(double) : 0);
+  pl.ex_g = take(exact_terms ? B * 8 * N * sizeof(double) : 0);
+  pl.ex_list = take(exact_terms ? B * N * sizeof(int32_t) : 0);
   pl.total = off;
   return FICOCO_OK;
 }

@@ -58,6 +58,12 @@ struct Plan {
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
+  // exact re-evaluation of the cosine-derived score terms (select stage), present with those terms only
+  size_t ex_nrm;         // double [B][N]
+  size_t ex_mu;          // double [B][Df + 1]
+  size_t ex_u;           // double [B][8][Df]
+  size_t ex_g;           // double [B][8][N]
+  size_t ex_list;        // int32  [B][N]
   int fixed_k;           // >= 0: targets per discarded token fixed by the caller (0: no edges), -1: adaptive
   bool extra_token;      // the additional token of the convergent form is written
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel

@@ -36,7 +36,25 @@ struct SelectArgs {
   int32_t* keep_idx;
   int32_t* slot_of;
   int32_t* overflow;        // zeroed here for the correlate stage (fused step only), may be null
+  // Exact re-evaluation of the cosine-derived terms for tokens whose decision is within the error
+  // bound of the bulk evaluation (exact_r: the mean-cosine term, exact_g: the equivalent-token term)
+  int exact_r, exact_g;
+  const void* F;            // features [B][N][Df]
+  int64_t fsb, fsn;         // strides in elements
+  int Df;
+  const double* norm;       // [B][N] row norms of the bulk pass
+  const double* mu_parts;   // [B][mu_n_parts] parts of the squared norm of the bulk pass's mean feature row
+  int mu_n_parts;
+  double* fterm_r_w;        // the term buffers again, writable (exact values replace bulk ones)
+  double* fterm_g_w;
+  double* ex_nrm;           // [B][N]       row norms, squares added in feature order
+  double* ex_mu;            // [B][Df + 1]  mean feature row, tokens added in order; then its norm
+  double* ex_u;             // [B][kExactGroup][Df] unit rows of the tokens being re-evaluated
+  double* ex_g;             // [B][kExactGroup][N]  their cosines with every token
+  int32_t* ex_list;         // [B][N] tokens to re-evaluate in this pass
 };
+
+constexpr int kExactGroup = 8;    // tokens whose mean cosine is re-evaluated together
 
 // head mean of a pre-reduced per-head vector entry: 16 independent loads at a time, added in
 // head order
@@ -79,229 +97,421 @@ constexpr int kBinCopies = 32;      // counters per histogram bin in the many-ke
 constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (it costs one more barrier per pass)
 static_assert(kSelectThreads == 4 * 256, "four threads fold the counters of one bin");
 
+__device__ __forceinline__ double key_score(uint64_t k) {       // inverse of score_key
+  const uint64_t u = (k >> 63) ? (k & 0x7fffffffffffffffULL) : ~k;
+  return __longlong_as_double((long long)u);
+}
+
+// Radix select of the n_disc-th largest key (n_disc >= 1): 8 passes over the key bytes, most
+// significant first.  Returns K* and how many of the tokens with key == K* belong to the n_disc
+// largest (lowest indices first).  Called by every thread of the workgroup.
+__device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, int n_disc, int* hist, int* bcast,
+                                                   int* hist_wide, uint64_t& kstar_out, int& need_out) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  uint64_t kstar = 0;
+  int need = n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
+  uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
+  const bool spread = N >= kSpreadMinN;   // uniform
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+    const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
+    if (spread) {
+      // Many keys per thread: scores of one image share their leading digits, so in the first
+      // passes nearly all atomics would queue on one LDS address (one lane per cycle).  Every
+      // bin has 32 counters here, one per bank, lane l adding to counter l % 32 -- no two
+      // lanes of an instruction meet -- and four threads per bin fold them afterwards.
+      for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0;
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) {
+        const uint64_t k = keys[i];
+        if ((k & hi_mask) == kstar) atomicAdd(&hist_wide[(int)((k >> shift) & 255) * kBinCopies + tid % kBinCopies], 1);
+      }
+      __syncthreads();
+      const int bin = tid / 4, part = tid % 4;           // 1024 threads: four per bin
+      int sum = 0;
+#pragma unroll
+      for (int c = 0; c < kBinCopies / 4; ++c)           // rotated by the bin so that neighbouring bins read different banks
+        sum += hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
+      sum += __shfl_xor(sum, 1, kWave);
+      sum += __shfl_xor(sum, 2, kWave);
+      if (part == 0) hist[bin] = sum;
+    } else {
+      if (tid < 256) hist[tid] = 0;
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) {
+        const uint64_t k = keys[i];
+        if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
+      }
+    }
+    __syncthreads();
+    if (tid < kWave) {
+      // Wavefront 0 walks the 256 bins from the top: lane l owns bins 4l .. 4l+3.
+      int h[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
+      const int lsum = h[0] + h[1] + h[2] + h[3];
+      int incl = lsum;                                   // sum over lanes >= this one
+#pragma unroll
+      for (int off = 1; off < kWave; off <<= 1) {
+        const int t = __shfl_down(incl, off, kWave);
+        if (tid + off < kWave) incl += t;
+      }
+      int above = incl - lsum;                           // tokens in bins above this lane's
+      if (above < need && need <= above + lsum) {        // exactly one lane
+#pragma unroll
+        for (int k = 3; k >= 0; --k) {
+          if (above < need && need <= above + h[k]) {
+            bcast[0] = 4 * tid + k; bcast[1] = need - above; bcast[2] = h[k];
+          }
+          above += h[k];
+        }
+      }
+    }
+    __syncthreads();
+    kstar |= (uint64_t)bcast[0] << shift;
+    need = bcast[1];
+    const int left = bcast[2];
+    __syncthreads();
+    if (left <= kWave && shift > 0) {
+      // Few candidates left: rank them directly in one wavefront instead of more passes.
+      if (tid == 0) bcast[3] = 0;
+      __syncthreads();
+      const uint64_t m2 = ~0ULL << shift;
+      for (int i = tid; i < N; i += nt) {
+        const uint64_t k = keys[i];
+        if ((k & m2) == kstar) { const int slot = atomicAdd(&bcast[3], 1); if (slot < kWave) small[slot] = k; }
+      }
+      __syncthreads();
+      if (tid < kWave) {
+        const uint64_t mine = tid < left ? small[tid] : 0ULL;
+        int greater = 0, equal = 0;
+        for (int l = 0; l < left; ++l) {
+          const uint64_t o = small[l];
+          greater += o > mine ? 1 : 0;
+          equal += o == mine ? 1 : 0;
+        }
+        if (tid < left && greater < need && need <= greater + equal) {   // all such lanes agree
+          small[kWave] = mine;
+          bcast[1] = need - greater;
+        }
+      }
+      __syncthreads();
+      kstar = small[kWave];
+      need = bcast[1];
+      __syncthreads();
+      break;
+    }
+  }
+  kstar_out = kstar;
+  need_out = need;
+}
+
+// ---- exact re-evaluation of the cosine-derived score terms ----------------------------------------
+// The bulk feature kernels evaluate the mean-cosine term as u_i . mean(u) and the equivalent-token
+// term with chunked sums: fast, and within a provable distance of the value the terms are DEFINED
+// as -- every sum in index order, products and sums rounded separately (mean cosine: the cosine of
+// the token with every token, features added in order, then the cosines added in token order;
+// equivalent token: mu = tokens added in order / N, dot product and norms with features added in
+// order).  Collinear features make exact ties in that definition (and near-ties at rounding level)
+// that the bulk values do not reproduce.  So the tokens whose decision -- maximum of a penalty
+// window, side of the top-K cut -- lies within the error bound are evaluated again here, operation
+// for operation as defined; their values then rank exactly.  Rare on real data, slow, and bounded.
+template <typename T>
+__device__ __noinline__ void exact_terms_of(const SelectArgs& a, int64_t b, const int32_t* list, int n_list, bool first) {
+#pragma clang fp contract(off)
+  const int tid = threadIdx.x, nt = blockDim.x;
+  const int N = a.N, Df = a.Df;
+  const T* Fb = (const T*)a.F + b * a.fsb;
+  double* enrm = a.ex_nrm + b * N;
+  double* emu = a.ex_mu + b * (Df + 1);
+  if (first) {
+    for (int j = tid; j < N; j += nt) {
+      const T* x = Fb + (int64_t)j * a.fsn;
+      double ss = 0.0;
+      for (int d = 0; d < Df; ++d) { const double v = widen(x[d]); ss = ss + v * v; }
+      enrm[j] = sqrt(ss);
+    }
+    if (a.exact_g) {
+      for (int d = tid; d < Df; d += nt) {
+        double acc = 0.0;
+        for (int i = 0; i < N; ++i) acc = acc + widen(Fb[(int64_t)i * a.fsn + d]);
+        emu[d] = acc / (double)N;
+      }
+      __syncthreads();
+      if (tid == 0) {
+        double mm = 0.0;
+        for (int d = 0; d < Df; ++d) mm = mm + emu[d] * emu[d];
+        emu[Df] = sqrt(mm);
+      }
+    }
+    __syncthreads();
+  }
+  if (a.exact_g) {
+    const double mu_n = emu[Df];
+    for (int f = tid; f < n_list; f += nt) {
+      const int i = list[f];
+      const T* x = Fb + (int64_t)i * a.fsn;
+      double dot = 0.0;
+      for (int d = 0; d < Df; ++d) dot = dot + emu[d] * widen(x[d]);
+      const double ni = enrm[i];
+      a.fterm_g_w[b * N + i] = (mu_n > 0.0 && ni > 0.0) ? -(dot / (mu_n * ni)) : 0.0;
+    }
+  }
+  if (a.exact_r) {
+    double* eu = a.ex_u + b * (int64_t)kExactGroup * Df;
+    double* eg = a.ex_g + b * (int64_t)kExactGroup * N;
+    for (int f0 = 0; f0 < n_list; f0 += kExactGroup) {
+      const int nf = min(kExactGroup, n_list - f0);
+      for (int q = tid; q < nf * Df; q += nt) {          // unit rows of this group's tokens
+        const int f = q / Df, d = q % Df;
+        const int i = list[f0 + f];
+        const double ni = enrm[i];
+        eu[(int64_t)f * Df + d] = ni > 0.0 ? widen(Fb[(int64_t)i * a.fsn + d]) / ni : 0.0;
+      }
+      __syncthreads();
+      for (int q = tid; q < nf * N; q += nt) {           // cos(token f, token j), features in order
+        const int f = q / N, j = q % N;
+        const T* y = Fb + (int64_t)j * a.fsn;
+        const double nj = enrm[j];
+        const double* u = eu + (int64_t)f * Df;
+        double acc = 0.0;
+        for (int d = 0; d < Df; ++d) {
+          const double uj = nj > 0.0 ? widen(y[d]) / nj : 0.0;
+          acc = acc + u[d] * uj;
+        }
+        eg[(int64_t)f * N + j] = acc;
+      }
+      __syncthreads();
+      if (tid < nf) {                                     // the token's cosines added in token order
+        const double* g = eg + (int64_t)tid * N;
+        double acc = 0.0;
+        for (int j = 0; j < N; ++j) acc = acc + g[j];
+        a.fterm_r_w[b * N + list[f0 + tid]] = acc / (double)N;
+      }
+      __syncthreads();
+    }
+  }
+  __syncthreads();
+}
+
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
-  DBG_SPAN(1);
   extern __shared__ double lds_d[];
   double* s = lds_d;                                   // [N] scores, then keys in place
   uint64_t* keys = (uint64_t*)lds_d;
   int* ibase = (int*)(lds_d + a.N);
   int* scan = ibase;                                   // [2][nt]
   int* hist = ibase + 2 * kSelectThreads;              // [256]
-  int* bcast = hist + 256;                             // [4]
-  int* owner = bcast + 4;                              // [cells] (penalty only)
+  int* bcast = hist + 256;                             // [8]: 0-3 radix select, 4 tokens flagged in this pass
+  uint32_t* exbits = (uint32_t*)(bcast + 8);           // [(N + 31) / 32] bit i: the terms of token i are exact (or about to be)
+  int* owner = bcast + 8 + (a.N + 31) / 32;            // [cells] (penalty only)
+  int* hist_wide = owner;                              // [256][kBinCopies]: used when the penalty's table is no longer needed
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = a.N;
+  const bool exact_mode = a.do_score && (a.exact_r || a.exact_g);    // uniform
+  int32_t* ex_list = a.ex_list + (int64_t)b * N;
+  auto is_exact = [&](int i) { return (exbits[i >> 5] >> (i & 31)) & 1u; };
+  // marks token i; true if this call was the one that marked it (it then goes on the list)
+  auto mark_exact = [&](int i) { return ((atomicOr(&exbits[i >> 5], 1u << (i & 31)) >> (i & 31)) & 1u) == 0u; };
 
-  DBG_PHASE(0);
+  // Distance within which the bulk value of a cosine-derived term lies from its defined value.
+  // Both are double-precision evaluations of the same real number: sums of at most Df + N terms
+  // whose absolute values add up to at most 1 (cosines, unit rows), so each is within
+  // (Df + N + c) 2^-53 of it; 16 times that is taken.  The equivalent-token term divides by |mu|,
+  // which cancellation can make small against the rows that were averaged: its bound grows by
+  // (mean row norm) / |mu|, and is unbounded when |mu| vanishes (every token is then re-evaluated).
+  double delta = 0.0, delta_p = 0.0;
+  if (exact_mode) {
+    for (int i = tid; i < (N + 31) / 32; i += nt) exbits[i] = 0u;
+    const double base = 16.0 * (double)(a.Df + N + 32) * 1.1102230246251565e-16;
+    double dg = 0.0;
+    if (a.exact_g) {
+      double* red = (double*)scan;                     // the scan scratch is free here
+      double part = 0.0;
+      for (int i = tid; i < N; i += nt) part += a.norm[(int64_t)b * N + i];
+#pragma unroll
+      for (int off = 32; off > 0; off >>= 1) part += __shfl_xor(part, off, kWave);
+      if (tid % kWave == 0) red[tid / kWave] = part;
+      __syncthreads();
+      if (tid == 0) {
+        double tot = 0.0;
+        for (int t = 0; t < nt / kWave; ++t) tot += red[t];
+        double mm = 0.0;
+        for (int k = 0; k < a.mu_n_parts; ++k) mm += a.mu_parts[(int64_t)b * a.mu_n_parts + k];
+        const double mu_n = sqrt(mm), mean_nrm = tot / (double)N;
+        double kappa = mu_n > 0.0 ? mean_nrm / mu_n : __builtin_huge_val();
+        if (!(kappa < 1e8)) kappa = __builtin_huge_val();
+        if (kappa < 1.0) kappa = 1.0;
+        red[kSelectThreads / kWave] = kappa;
+      }
+      __syncthreads();
+      dg = base * red[kSelectThreads / kWave];
+      __syncthreads();
+    }
+    const double wr = a.w < 0.0 ? -a.w : a.w, wg = 1.0 - a.w < 0.0 ? a.w - 1.0 : 1.0 - a.w;
+    delta = (a.exact_r ? wr * base : 0.0) + (a.exact_g ? wg * dg : 0.0);
+    const double ac = a.coef < 0.0 ? -a.coef : a.coef;
+    delta_p = a.window > 0 && ac > 1.0 ? ac * delta : delta;
+  }
+
+  uint64_t kstar = 0;
+  int need = a.n_disc;      // how many tokens with key == kstar are discarded (lowest indices first)
+  bool keys_ready = false;  // uniform
   if (a.do_score) {
-    // Both terms one stored value per token, and several tokens per thread: all of the thread's
-    // loads are issued before the first use (the general loop below takes a trip to memory per token).
-    const double* r_one = a.red_src == FICOCO_R_ATTN_RECV ? (a.n_chunks == 1 ? a.recv_part : nullptr)
-                        : a.red_src == FICOCO_R_VECTOR ? nullptr : a.fterm_r;
-    const double* g_one = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls
-                        : (a.sem_src == FICOCO_G_TEXT_ATTN || a.sem_src == FICOCO_G_VECTOR) ? nullptr : a.fterm_g;
-    const bool one_each = r_one && g_one && N > nt;      // uniform
-    if (one_each) {
-      double r[kTokensPerThread], g[kTokensPerThread];
-#pragma unroll
-      for (int u = 0; u < kTokensPerThread; ++u) {
-        const int i = min(tid + u * nt, N - 1);          // clamped: always a valid address
-        r[u] = r_one[(int64_t)b * N + i];
-        g[u] = g_one[(int64_t)b * N + i];
+    for (int pass = 0;; ++pass) {
+      if (exact_mode) {
+        if (tid == 0) bcast[4] = 0;
+        __syncthreads();
       }
-      issue_fence();
+      // Both terms one stored value per token, and several tokens per thread: all of the thread's
+      // loads are issued before the first use (the general loop below takes a trip to memory per token).
+      const double* r_one = a.red_src == FICOCO_R_ATTN_RECV ? (a.n_chunks == 1 ? a.recv_part : nullptr)
+                          : a.red_src == FICOCO_R_VECTOR ? nullptr : a.fterm_r;
+      const double* g_one = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls
+                          : (a.sem_src == FICOCO_G_TEXT_ATTN || a.sem_src == FICOCO_G_VECTOR) ? nullptr : a.fterm_g;
+      const bool one_each = r_one && g_one && N > nt;      // uniform
+      if (one_each) {
+        double r[kTokensPerThread], g[kTokensPerThread];
 #pragma unroll
-      for (int u = 0; u < kTokensPerThread; ++u) {
-        const int i = tid + u * nt;
-        if (i < N) s[i] = combine_terms(a.w, a.red_src == FICOCO_R_ATTN_RECV ? (0.0 + r[u]) / (double)N : r[u], g[u]);
-      }
-    }
-    for (int i = tid; i < (one_each ? 0 : N); i += nt) {
-      double R, G;
-      if (a.red_src == FICOCO_R_ATTN_RECV) {
-        const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
-        double acc = 0.0;
-        int c = 0;
-        for (; c + 32 <= a.n_chunks; c += 32) {          // 32 independent loads, added in order
-          double v[32];
-#pragma unroll
-          for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * N];
-#pragma unroll
-          for (int u = 0; u < 32; ++u) acc += v[u];
+        for (int u = 0; u < kTokensPerThread; ++u) {
+          const int i = min(tid + u * nt, N - 1);          // clamped: always a valid address
+          r[u] = r_one[(int64_t)b * N + i];
+          g[u] = g_one[(int64_t)b * N + i];
         }
-        for (; c + 8 <= a.n_chunks; c += 8) {
-          double v[8];
+        issue_fence();
 #pragma unroll
-          for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(c + u) * N];
-#pragma unroll
-          for (int u = 0; u < 8; ++u) acc += v[u];
+        for (int u = 0; u < kTokensPerThread; ++u) {
+          const int i = tid + u * nt;
+          if (i < N) s[i] = combine_terms(a.w, a.red_src == FICOCO_R_ATTN_RECV ? (0.0 + r[u]) / (double)N : r[u], g[u]);
         }
-        for (; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
-        R = acc / (double)N;
-      } else if (a.red_src == FICOCO_R_VECTOR) {
-        R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
-      } else {
-        R = a.fterm_r[(int64_t)b * N + i];
       }
-      if (a.sem_src == FICOCO_G_CLS_ATTN) {
-        G = a.cls[(int64_t)b * N + i];
-      } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
-        const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
-        double acc = 0.0;
-        int k = 0;
-        for (; k + 16 <= a.M; k += 16) {                  // 16 independent loads, added in order
-          double v[16];
+      for (int i = tid; i < (one_each ? 0 : N); i += nt) {
+        double R, G;
+        if (a.red_src == FICOCO_R_ATTN_RECV) {
+          const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
+          double acc = 0.0;
+          int c = 0;
+          for (; c + 32 <= a.n_chunks; c += 32) {          // 32 independent loads, added in order
+            double v[32];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) v[u] = p[k + u];
+            for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * N];
 #pragma unroll
-          for (int u = 0; u < 16; ++u) acc += v[u];
-        }
-        for (; k < a.M; ++k) acc += p[k];
-        G = acc / (double)a.M;
-      } else if (a.sem_src == FICOCO_G_VECTOR) {
-        G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);
-      } else {
-        G = a.fterm_g[(int64_t)b * N + i];
-      }
-      s[i] = combine_terms(a.w, R, G);
-    }
-    DBG_PHASE(1);
-    if (a.window > 0) {
-      const int cells = a.grid_g * a.grid_h * a.grid_w;
-      for (int c = tid; c < cells; c += nt) owner[c] = -1;
-      __syncthreads();
-      for (int i = tid; i < N; i += nt) {
-        const int c = a.pos ? a.pos[(int64_t)b * N + i] : i;
-        if (c >= 0 && c < cells) owner[c] = i;
-      }
-      __syncthreads();
-      const int W = a.window;
-      const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
-      const int n_win = a.grid_g * wr * wc;
-      for (int w = tid; w < n_win; w += nt) {
-        const int sub = w / (wr * wc), rem = w % (wr * wc);
-        const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
-        int best = -1;
-        double best_s = 0.0;
-        for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
-          for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
-            const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
-            if (t >= 0 && (best < 0 || s[t] > best_s)) { best = t; best_s = s[t]; }
+            for (int u = 0; u < 32; ++u) acc += v[u];
           }
-        if (best >= 0) s[best] = a.coef * best_s;   // windows are disjoint: no other reader
+          for (; c + 8 <= a.n_chunks; c += 8) {
+            double v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(c + u) * N];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+          }
+          for (; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
+          R = acc / (double)N;
+        } else if (a.red_src == FICOCO_R_VECTOR) {
+          R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
+        } else {
+          R = a.fterm_r[(int64_t)b * N + i];
+        }
+        if (a.sem_src == FICOCO_G_CLS_ATTN) {
+          G = a.cls[(int64_t)b * N + i];
+        } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
+          const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
+          double acc = 0.0;
+          int k = 0;
+          for (; k + 16 <= a.M; k += 16) {                  // 16 independent loads, added in order
+            double v[16];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) v[u] = p[k + u];
+#pragma unroll
+            for (int u = 0; u < 16; ++u) acc += v[u];
+          }
+          for (; k < a.M; ++k) acc += p[k];
+          G = acc / (double)a.M;
+        } else if (a.sem_src == FICOCO_G_VECTOR) {
+          G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);
+        } else {
+          G = a.fterm_g[(int64_t)b * N + i];
+        }
+        s[i] = combine_terms(a.w, R, G);
       }
+      if (a.window > 0) {
+        const int cells = a.grid_g * a.grid_h * a.grid_w;
+        for (int c = tid; c < cells; c += nt) owner[c] = -1;
+        __syncthreads();
+        for (int i = tid; i < N; i += nt) {
+          const int c = a.pos ? a.pos[(int64_t)b * N + i] : i;
+          if (c >= 0 && c < cells) owner[c] = i;
+        }
+        __syncthreads();
+        const int W = a.window;
+        const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
+        const int n_win = a.grid_g * wr * wc;
+        for (int w = tid; w < n_win; w += nt) {
+          const int sub = w / (wr * wc), rem = w % (wr * wc);
+          const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
+          int best = -1;
+          double best_s = 0.0;
+          for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
+            for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
+              const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
+              if (t >= 0 && (best < 0 || s[t] > best_s)) { best = t; best_s = s[t]; }
+            }
+          if (exact_mode && best >= 0) {
+            // Which token is the maximum is uncertain while another one is within the two tokens'
+            // error bounds of it: all of those are evaluated exactly (a token that already is has
+            // no error).  The flags of a window's tokens are touched by this thread alone.
+            const double d_best = is_exact(best) ? 0.0 : delta;
+            bool any = false;
+            for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
+              for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
+                const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
+                if (t < 0 || t == best) continue;
+                const double d_t = is_exact(t) ? 0.0 : delta;
+                if (d_t + d_best > 0.0 && s[t] >= best_s - (d_t + d_best)) {
+                  any = true;
+                  if (mark_exact(t)) ex_list[atomicAdd(&bcast[4], 1)] = t;
+                }
+              }
+            if (any && mark_exact(best)) ex_list[atomicAdd(&bcast[4], 1)] = best;
+          }
+          if (best >= 0) s[best] = a.coef * best_s;   // windows are disjoint: no other reader
+        }
+      }
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) a.scores[(int64_t)b * N + i] = s[i];
+      if (!exact_mode) break;
+      // the side of the top-K cut: tokens within the bound of the N^S-th largest score
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
+      __syncthreads();
+      if (a.n_disc > 0) {
+        radix_select_kstar(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
+        if (a.n_disc < N) {          // with every token discarded there is no cut to be on a side of
+          const double cut = key_score(kstar);
+          for (int i = tid; i < N; i += nt) {
+            const double d = key_score(keys[i]) - cut;
+            if ((d < 0.0 ? -d : d) <= 2.0 * delta_p && mark_exact(i)) ex_list[atomicAdd(&bcast[4], 1)] = i;
+          }
+        }
+      }
+      __syncthreads();
+      const int n_flag = bcast[4];
+      keys_ready = true;
+      if (n_flag == 0 || pass == 3) break;
+      if (a.dtype == FICOCO_BF16) exact_terms_of<bf16_t>(a, b, ex_list, n_flag, pass == 0);
+      else exact_terms_of<float>(a, b, ex_list, n_flag, pass == 0);
+      keys_ready = false;
     }
-    __syncthreads();
-    for (int i = tid; i < N; i += nt) a.scores[(int64_t)b * N + i] = s[i];
   } else {
     for (int i = tid; i < N; i += nt) s[i] = a.scores[(int64_t)b * N + i];
   }
-  DBG_PHASE(2);
   if (!a.do_filter) return;
   if (a.overflow && tid == 0) a.overflow[b] = 0;
-  __syncthreads();
-  for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
-  __syncthreads();
-
-  // ---- radix select of the n_disc-th largest key -------------------------------------------
-  uint64_t kstar = 0;
-  int need = a.n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
-  if (a.n_disc > 0) {
-    uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
-    const bool spread = N >= kSpreadMinN;   // uniform
-    int* hist_wide = owner;              // [256][kBinCopies]: the penalty's table is no longer needed
-    for (int pass = 0; pass < 8; ++pass) {
-      const int shift = 56 - 8 * pass;
-      const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
-      if (spread) {
-        // Many keys per thread: scores of one image share their leading digits, so in the first
-        // passes nearly all atomics would queue on one LDS address (one lane per cycle).  Every
-        // bin has 32 counters here, one per bank, lane l adding to counter l % 32 -- no two
-        // lanes of an instruction meet -- and four threads per bin fold them afterwards.
-        for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0;
-        __syncthreads();
-        for (int i = tid; i < N; i += nt) {
-          const uint64_t k = keys[i];
-          if ((k & hi_mask) == kstar) atomicAdd(&hist_wide[(int)((k >> shift) & 255) * kBinCopies + tid % kBinCopies], 1);
-        }
-        __syncthreads();
-        const int bin = tid / 4, part = tid % 4;           // 1024 threads: four per bin
-        int sum = 0;
-#pragma unroll
-        for (int c = 0; c < kBinCopies / 4; ++c)           // rotated by the bin so that neighbouring bins read different banks
-          sum += hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
-        sum += __shfl_xor(sum, 1, kWave);
-        sum += __shfl_xor(sum, 2, kWave);
-        if (part == 0) hist[bin] = sum;
-      } else {
-        if (tid < 256) hist[tid] = 0;
-        __syncthreads();
-        for (int i = tid; i < N; i += nt) {
-          const uint64_t k = keys[i];
-          if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
-        }
-      }
-      __syncthreads();
-      if (tid < kWave) {
-        // Wavefront 0 walks the 256 bins from the top: lane l owns bins 4l .. 4l+3.
-        int h[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
-        const int lsum = h[0] + h[1] + h[2] + h[3];
-        int incl = lsum;                                   // sum over lanes >= this one
-#pragma unroll
-        for (int off = 1; off < kWave; off <<= 1) {
-          const int t = __shfl_down(incl, off, kWave);
-          if (tid + off < kWave) incl += t;
-        }
-        int above = incl - lsum;                           // tokens in bins above this lane's
-        if (above < need && need <= above + lsum) {        // exactly one lane
-#pragma unroll
-          for (int k = 3; k >= 0; --k) {
-            if (above < need && need <= above + h[k]) {
-              bcast[0] = 4 * tid + k; bcast[1] = need - above; bcast[2] = h[k];
-            }
-            above += h[k];
-          }
-        }
-      }
-      __syncthreads();
-      kstar |= (uint64_t)bcast[0] << shift;
-      need = bcast[1];
-      const int left = bcast[2];
-      __syncthreads();
-      if (left <= kWave && shift > 0) {
-        // Few candidates left: rank them directly in one wavefront instead of more passes.
-        if (tid == 0) bcast[3] = 0;
-        __syncthreads();
-        const uint64_t m2 = ~0ULL << shift;
-        for (int i = tid; i < N; i += nt) {
-          const uint64_t k = keys[i];
-          if ((k & m2) == kstar) { const int slot = atomicAdd(&bcast[3], 1); if (slot < kWave) small[slot] = k; }
-        }
-        __syncthreads();
-        if (tid < kWave) {
-          const uint64_t mine = tid < left ? small[tid] : 0ULL;
-          int greater = 0, equal = 0;
-          for (int l = 0; l < left; ++l) {
-            const uint64_t o = small[l];
-            greater += o > mine ? 1 : 0;
-            equal += o == mine ? 1 : 0;
-          }
-          if (tid < left && greater < need && need <= greater + equal) {   // all such lanes agree
-            small[kWave] = mine;
-            bcast[1] = need - greater;
-          }
-        }
-        __syncthreads();
-        kstar = small[kWave];
-        need = bcast[1];
-        __syncthreads();
-        break;
-      }
-    }
+  if (!keys_ready) {
+    __syncthreads();
+    for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
+    __syncthreads();
+    if (a.n_disc > 0) radix_select_kstar(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
   }
-  DBG_PHASE(3);
   // need = how many tokens with key == kstar are discarded (lowest indices first)
 
   // ---- flags and ordered compaction -----------------------------------------------------------
@@ -332,7 +542,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     }
     if (dis) dis_mask |= 1u << (i - lo);
   }
-  DBG_PHASE(4);
   const int n_keep = N - a.n_disc;
   for (int i = lo; i < hi; ++i) {
     if (dis_mask & (1u << (i - lo))) {
@@ -345,7 +554,6 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       ++k_pos;
     }
   }
-  DBG_PHASE(5);
 }
 
 // Large problems (many row chunks and more columns than one workgroup has threads): the
@@ -405,7 +613,7 @@ __global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
   const size_t wide = p.N >= kSpreadMinN ? 256 * kBinCopies : 0;   // shares the penalty table's space
-  return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 4 + (cells > wide ? cells : wide)) * sizeof(int);
+  return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 8 + (p.N + 31) / 32 + (cells > wide ? cells : wide)) * sizeof(int);
 }
 
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
@@ -443,6 +651,27 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
     hipLaunchKernelGGL(text_mean_kernel, dim3((p.N + 3) / 4, p.B), dim3(256), 0, s, a.ttext, p.N, p.M,
                        (double*)(ws + pl.fterm2));
     a.sem_src = FICOCO_G_EQ_TOKEN;             // "read the precomputed term"
+  }
+  if (do_score && (p.red_src == FICOCO_R_SIM_MEAN || p.sem_src == FICOCO_G_EQ_TOKEN)) {
+    a.exact_r = p.red_src == FICOCO_R_SIM_MEAN;
+    a.exact_g = p.sem_src == FICOCO_G_EQ_TOKEN;
+    if (p.F) { a.F = p.F; a.fsb = p.f_stride_b; a.fsn = p.f_stride_n; }
+    else {
+      const size_t es = p.dtype == FICOCO_BF16 ? 2 : 4;
+      a.F = (const char*)p.X + (size_t)p.vis_begin * p.x_stride_n * es;
+      a.fsb = p.x_stride_b; a.fsn = p.x_stride_n;
+    }
+    a.Df = pl.Df;
+    a.norm = (const double*)(ws + pl.inv_norm);
+    a.mu_n_parts = (pl.Df + 255) / 256;
+    a.mu_parts = (const double*)(ws + pl.colmean) + 2 * (size_t)p.B * pl.Df;
+    a.fterm_r_w = (double*)(ws + pl.fterm);
+    a.fterm_g_w = (double*)(ws + pl.fterm2);
+    a.ex_nrm = (double*)(ws + pl.ex_nrm);
+    a.ex_mu = (double*)(ws + pl.ex_mu);
+    a.ex_u = (double*)(ws + pl.ex_u);
+    a.ex_g = (double*)(ws + pl.ex_g);
+    a.ex_list = (int32_t*)(ws + pl.ex_list);
   }
   a.w = (double)p.w_score;
   const bool penalty = p.variant == FICOCO_VARIANT_V && p.window > 0;

@@ -16,6 +16,10 @@ Other workloads: --config 0, 2, 3 (decoder, no visual->visual map: mean-cosine +
 correlation), 3p (decoder with the causal visual->visual map: Algorithm 2 as printed), 4
 (video, vectors + cosine correlation), 1c (config 1 tokens with the cosine correlation).
 
+After the timed loop the last step of every stream is run again alone on one stream and its
+outputs are compared bit for bit (`outputs_checked`); tests/test_gpu_pipeline.py checks the same
+launch pattern on the same inputs against the CPU oracle.
+
 Prints ONE JSON line: tokens/s (B*N input visual tokens per step), plus
   roofline     : the dominant kernel -- the attention-reduction kernel (HBM bound: |A| read +
                  single-precision head-mean map written, per launch) or, for the cosine
@@ -24,7 +28,9 @@ Prints ONE JSON line: tokens/s (B*N input visual tokens per step), plus
                  records around that launch on the launch stream, in a loop of that stage alone;
                  the event-pair time of the same launch inside the pipelined steps (which also
                  spans waits for the other stream) is reported beside it;
-  cpu_baseline : the CPU oracle timed on this host on a bounded sample of the same batch.
+  cpu_baseline : the CPU oracle timed on this host on every sequence of input set 0, by one worker
+                 process alone and by all workers at once (started before the GPU is initialised;
+                 --no-cpu-baseline starts none: use it under rocprofv3).
 """
 import argparse
 import json
@@ -151,6 +157,45 @@ def make_workload(torch, fc, name, dev):
     return W
 
 
+def issue_steps(torch, step_fn, ctx, probs, bufs, streams, k, start=0, before_step=None):
+    """The launch pattern that is timed: step i of [start, start + k) goes to stream i mod
+    len(streams) with that stream's buffers and reads input set i mod len(probs).  Successive
+    steps are independent batches; one ctx serves all streams."""
+    n_str, n_sets = len(streams), len(probs)
+    for i in range(start, start + k):
+        if before_step is not None:
+            before_step(i)
+        with torch.cuda.stream(streams[i % n_str]):
+            step_fn(ctx, probs[i % n_sets], bufs[i % n_str])
+
+
+OUTPUT_FIELDS = ("X_out", "pos_out", "keep_idx", "discard_idx", "edge_cnt", "edge_tgt", "edge_alpha", "scores", "overflow")
+
+
+def last_steps_equal_eager(torch, fc, step_fn, ctx, probs, bufs, k, dev, tdt, start=0):
+    """After issue_steps(..., k, start): the outputs each stream's buffers hold (its last step)
+    against the same step run alone on the current stream into fresh buffers, bit for bit."""
+    n_str, n_sets = len(bufs), len(probs)
+    torch.cuda.synchronize()
+    ok = True
+    for si in range(n_str):
+        mine = [i for i in range(start, start + k) if i % n_str == si]
+        if not mine:
+            continue
+        last = mine[-1]
+        ref = fc.Buffers(probs[last % n_sets], dev, tdt)
+        step_fn(ctx, probs[last % n_sets], ref)
+        torch.cuda.synchronize()
+        # edge-list slots behind a row's count are never written: only the stored entries count
+        live = torch.arange(ref.edge_tgt.shape[2], device=dev)[None, None, :] < ref.edge_cnt[:, :, None]
+        for f in OUTPUT_FIELDS:
+            got, want = getattr(bufs[si], f), getattr(ref, f)
+            if f in ("edge_tgt", "edge_alpha"):
+                got, want = torch.where(live, got, 0), torch.where(live, want, 0)
+            ok = ok and bool(torch.equal(got, want))
+    return ok
+
+
 def traffic_from_profiles():
     """HBM bytes per launch of the reduction kernel (config 1) from the committed counter summary."""
     path = os.path.join(ROOT, "profiles", "attn_reduce_c1_step1_pmc.txt")
@@ -163,48 +208,91 @@ def traffic_from_profiles():
     return None
 
 
-def cpu_baseline(W, seconds=12.0):
+def _oracle_worker(job):
+    """Runs in a CPU worker process: the oracle step on this worker's sequences, round-robin, until
+    `budget` seconds have passed (at least one pass over them).  Returns (sequences done, start, end)
+    on the system-wide monotonic clock."""
     from oracle import ficoco_oracle as O
+    seqs = [{k: (None if v is None else O.widen(v)) for k, v in sq.items()} for sq in job["seqs"]]
+    kw, okw = job["kw"], job["okw"]
+    done = 0
+    t0 = time.monotonic()
+    while True:
+        for sq in seqs:
+            if job["variant"] == "V":
+                O.v_step(sq["X"], sq["A"], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"], N=kw["N"],
+                         n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2, coef=2.0,
+                         recv_vec=sq["recv_vec"], sem_vec=sq["sem_vec"], red_src=job["red"], sem_src=job["sem"],
+                         corr_src=job["cor"], **okw)
+            else:
+                O.l_step(sq["X"], sq["A"], sq["A_text"], vis_begin=kw["vis_begin"], N=kw["N"], n_keep=kw["n_keep"],
+                         beta=kw["w_score"], gamma=kw["gamma"], eps=kw["eps"], red_src=job["red"], corr_src=job["cor"], **okw)
+            done += 1
+        if time.monotonic() - t0 > job["budget"]:
+            break
+    return done, t0, time.monotonic()
+
+
+def start_cpu_pool():
+    """Worker processes for the CPU baseline.  Must be called before anything initialises the GPU:
+    a process that has may not start programs, and every worker is a freshly started interpreter."""
+    import multiprocessing as mp
+    from concurrent.futures import ProcessPoolExecutor
+    n = max(1, min(16, os.cpu_count() or 1))       # the GPU box's CPU share for one GPU is 16 cores
+    os.environ.setdefault("OMP_NUM_THREADS", "1")
+    # An executor never replaces a worker that died (it fails instead), and it has started all of
+    # its workers once n tasks have been pending at the same time.
+    pool = ProcessPoolExecutor(max_workers=n, mp_context=mp.get_context("spawn"))
+    list(pool.map(time.sleep, [0.3] * n))
+    return pool, n
+
+
+def cpu_model():
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(W, pool, n_workers, budget=7.0):
+    """The CPU oracle as it stands on every sequence of input set 0: one worker alone, then all
+    workers at once (sequences dealt out round-robin)."""
     from paper_2411_17686_amd import ficoco as fc
     from paper_2411_17686_amd.synth import to_numpy
     st, kw = W["sets"][0], W["kw"]
-    n_img = min(2, W["B"])
+    B = W["B"]
 
     def host(k, b):
-        return None if st.get(k) is None else O.widen(to_numpy(st[k][b]))
+        return None if st.get(k) is None else to_numpy(st[k][b])
 
-    X = [host("X", b) for b in range(n_img)]
-    A = [host("A", b) for b in range(n_img)]
-    At = [host("A_text", b) for b in range(n_img)]
-    rv = [host("recv_vec", b) for b in range(n_img)]
-    sv = [host("sem_vec", b) for b in range(n_img)]
-    red = {fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}[kw.get("red_src", fc.R_ATTN_RECV)]
-    cor = {fc.C_ATTN: "attn", fc.C_COSINE: "cosine"}[kw.get("corr_src", fc.C_ATTN)]
-    okw = dict(k_mode={fc.K_ADAPTIVE: "adaptive", fc.K_FIXED: "fixed", fc.K_CONVERGENT: "convergent"}[kw.get("k_mode", 0)],
-               fixed_k=kw.get("fixed_k", 0), average=kw.get("compress_mode", 0) == fc.COMPRESS_AVERAGE)
-    t0 = time.perf_counter()
-    reps = 0
-    while True:
-        for b in range(n_img):
-            if W["variant"] == fc.VARIANT_V:
-                sem = {fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector"}[kw.get("sem_src", fc.G_CLS_ATTN)]
-                O.v_step(X[b], A[b], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"], N=kw["N"],
-                         n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2, coef=2.0,
-                         recv_vec=rv[b], sem_vec=sv[b], red_src=red, sem_src=sem, corr_src=cor, **okw)
-            else:
-                O.l_step(X[b], A[b], At[b], vis_begin=kw["vis_begin"], N=kw["N"], n_keep=kw["n_keep"],
-                         beta=kw["w_score"], gamma=kw["gamma"], eps=kw["eps"], red_src=red, corr_src=cor, **okw)
-        reps += 1
-        el = time.perf_counter() - t0
-        if el > seconds:
-            break
-    cores = 1
-    if cor == "cosine" or red == "sim_mean":      # those steps call float64 matrix products (BLAS thread pool)
-        import threadpoolctl
-        cores = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
-    return {"value": reps * n_img * W["N"] / el, "unit": "tokens/s", "cores": cores, "kind": "oracle",
-            "sample": "%d of the %d sequences of input set 0, %d passes of the float64 numpy oracle, %.1f s%s"
-                      % (n_img, W["B"], reps, el, "" if cores == 1 else " (its matrix products use the BLAS thread pool)")}
+    seqs = [dict(X=host("X", b), A=host("A", b), A_text=host("A_text", b), recv_vec=host("recv_vec", b),
+                 sem_vec=host("sem_vec", b)) for b in range(B)]
+    job = dict(variant="V" if W["variant"] == fc.VARIANT_V else "L",
+               kw={k: v for k, v in kw.items() if k in ("cls_index", "vis_begin", "N", "n_keep", "w_score", "eps", "grid", "gamma")},
+               red={fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}[kw.get("red_src", fc.R_ATTN_RECV)],
+               sem={fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector", fc.G_TEXT_ATTN: "cls"}[kw.get("sem_src", fc.G_CLS_ATTN)],
+               cor={fc.C_ATTN: "attn", fc.C_COSINE: "cosine"}[kw.get("corr_src", fc.C_ATTN)],
+               okw=dict(k_mode={fc.K_ADAPTIVE: "adaptive", fc.K_FIXED: "fixed", fc.K_CONVERGENT: "convergent"}[kw.get("k_mode", 0)],
+                        fixed_k=kw.get("fixed_k", 0), average=kw.get("compress_mode", 0) == fc.COMPRESS_AVERAGE),
+               budget=budget)
+    done1, t0, t1 = pool.submit(_oracle_worker, dict(job, seqs=seqs)).result()
+    single = done1 * W["N"] / (t1 - t0)
+    n_used = min(n_workers, B)
+    shares = [dict(job, seqs=seqs[w::n_used]) for w in range(n_used)]
+    res = list(pool.map(_oracle_worker, shares))
+    wall = max(r[2] for r in res) - min(r[1] for r in res)
+    done_all = sum(r[0] for r in res)
+    return {"value": done_all * W["N"] / wall, "unit": "tokens/s", "cores": n_used, "kind": "oracle",
+            "cpu_model": cpu_model(), "host_cores": os.cpu_count(),
+            "sample": "all %d sequences of input set 0, dealt to %d worker processes (one numpy thread each) that "
+                      "repeat the float64 numpy oracle on theirs for %.0f s: %d sequence-steps in %.1f s"
+                      % (B, n_used, budget, done_all, wall),
+            "single_thread": {"value": single, "unit": "tokens/s", "cores": 1,
+                              "sample": "one worker, the %d sequences in turn for %.0f s: %d sequence-steps in %.1f s"
+                                        % (B, budget, done1, t1 - t0)}}
 
 
 def main():
@@ -228,6 +316,9 @@ def main():
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         sys.exit("bench.py: this build runs on one GPU only (the step shards over the batch with no "
                  "exchange; no multi-GPU figure is produced). Use --gpus 1.")
+
+    # CPU workers for the oracle baseline are started first: nothing has touched the GPU yet.
+    pool, n_workers = (None, 0) if args.no_cpu_baseline else start_cpu_pool()
 
     import torch
     from paper_2411_17686_amd import ficoco as fc
@@ -259,12 +350,10 @@ def main():
     sync()
 
     def run_steps(k, probe=None):
-        # Successive steps are independent batches: step i goes to stream i mod n_str.
-        for i in range(k):
-            if probe is not None:
-                ctx.set_probe(probe[0], probe[1][i][0].cuda_event, probe[1][i][1].cuda_event)
-            with torch.cuda.stream(streams[i % n_str]):
-                step_fn(ctx, probs[i % n_sets], bufs[i % n_str])
+        hook = None
+        if probe is not None:
+            hook = lambda i: ctx.set_probe(probe[0], probe[1][i][0].cuda_event, probe[1][i][1].cuda_event)
+        issue_steps(torch, step_fn, ctx, probs, bufs, streams, k, before_step=hook)
         if probe is not None:
             ctx.set_probe(probe[0], None, None)
 
@@ -277,6 +366,8 @@ def main():
     ms_per_step = dt / args.steps * 1e3
     tokens_per_s = W["B"] * W["N"] / (dt / args.steps)
     assert all(int(b_.overflow.sum().item()) == 0 for b_ in bufs)
+    outputs_checked = last_steps_equal_eager(torch, fc, step_fn, ctx, probs, bufs, args.steps, dev, tdt)
+    assert outputs_checked, "a pipelined step's outputs differ from the same step run alone"
 
     # Dominant kernel: event pairs recorded by the library around its launch.
     kind = fc.PROBE_REDUCE if W["dominant"] == "reduce" else fc.PROBE_GRAM
@@ -341,7 +432,11 @@ def main():
         achieved = algo / (alone_ms * 1e-3) / 1e9
         roof = {"kernel": "attn_reduce_kernel<%s>" % W["dtype"], "bound": "hbm", "achieved": achieved,
                 "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                "traffic": traffic_from_profiles() if args.config == "1" else None, "algorithmic_bytes": algo}
+                "traffic": traffic_from_profiles() if args.config == "1" else None,
+                "traffic_source": "profiles/attn_reduce_c1_step1_pmc.txt: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE of this "
+                                  "kernel at this workload, scaled by a plain copy; read from that committed file, "
+                                  "not measured in this run" if args.config == "1" else None,
+                "algorithmic_bytes": algo}
     else:
         algo = W["gram_flops"]
         achieved = algo / (alone_ms * 1e-3) / 1e12
@@ -358,8 +453,9 @@ def main():
                  "in_pipeline_event_us": in_pipe_ms * 1e3})
 
     out = {
-        "metric": "FiCoCo-V tokens/sec (B=16,N=576,D=1024)" if args.config == "1"
-                  else "FiCoCo tokens/sec (config %s)" % args.config,
+        "metric": ("FiCoCo-V tokens/sec (B=16,N=576,D=1024)" if args.config == "1"
+                   else "FiCoCo tokens/sec (config %s)" % args.config)
+                  + (", %d independent steps in flight on %d streams" % (n_str, n_str) if n_str > 1 else ", one step at a time"),
         "value": tokens_per_s, "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
         "steps_per_s": 1e3 / ms_per_step,
@@ -369,11 +465,21 @@ def main():
                    "decision_dtype": "f64", "streams": n_str},
         "roofline": roof,
     }
+    out["outputs_checked"] = outputs_checked
     out["step_latency_us"] = {"median": lat[len(lat) // 2], "p10": lat[len(lat) // 10], "p90": lat[(9 * len(lat)) // 10],
                               "how": "HIP event pair around each of %d fused calls issued back to back on one stream" % len(lat)}
+    one_us = lat[len(lat) // 2]
+    out["one_stream"] = {"us_per_step": one_us, "steps_per_s": 1e6 / one_us, "tokens_per_s": W["B"] * W["N"] * 1e6 / one_us,
+                         "how": "median of the fused calls issued back to back on one stream (no overlap between steps)"}
     if W.get("step_bytes"):
+        # The whole fused step against the HBM roofline (the target is stated for the step, not for
+        # its first kernel): algorithmic bytes of one step over the time of one step.
         out["step_algorithmic_bytes"] = W["step_bytes"]
         out["step_hbm_frac"] = W["step_bytes"] / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS
+        out["step_roofline"] = {"bound": "hbm", "algorithmic_bytes": W["step_bytes"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                                "frac_steps_in_flight": out["step_hbm_frac"],
+                                "frac_one_step_at_a_time": W["step_bytes"] / (one_us * 1e-6) / 1e9 / HBM_PEAK_GBS,
+                                "target_frac": 0.60}
 
     if args.config == "1" and args.ablation == "none":
         # BASELINE config 1 in full: the three successive reductions 576 -> 384 -> 256 -> 192 with a
@@ -436,8 +542,9 @@ def main():
         sync()
         del src, dst
 
-    if not args.no_cpu_baseline:
-        out["cpu_baseline"] = cpu_baseline(W)
+    if pool is not None:
+        out["cpu_baseline"] = cpu_baseline(W, pool, n_workers)
+        pool.shutdown()
     print(json.dumps(out))
 
 

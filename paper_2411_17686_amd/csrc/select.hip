@@ -217,7 +217,7 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
 // window, side of the top-K cut -- lies within the error bound are evaluated again here, operation
 // for operation as defined; their values then rank exactly.  Rare on real data, slow, and bounded.
 template <typename T>
-__device__ __noinline__ void exact_terms_of(const SelectArgs& a, int64_t b, const int32_t* list, int n_list, bool first) {
+__device__ __forceinline__ void exact_terms_of(const SelectArgs& a, int64_t b, const int32_t* list, int n_list, bool first) {
 #pragma clang fp contract(off)
   const int tid = threadIdx.x, nt = blockDim.x;
   const int N = a.N, Df = a.Df;
@@ -294,6 +294,9 @@ __device__ __noinline__ void exact_terms_of(const SelectArgs& a, int64_t b, cons
   __syncthreads();
 }
 
+// EXACT: the instantiation for problems with a cosine-derived score term (the re-evaluation code
+// costs registers that the common instantiation does not pay).
+template <bool EXACT>
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   extern __shared__ double lds_d[];
   double* s = lds_d;                                   // [N] scores, then keys in place
@@ -307,7 +310,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   int* hist_wide = owner;                              // [256][kBinCopies]: used when the penalty's table is no longer needed
   const int b = blockIdx.x, tid = threadIdx.x, nt = blockDim.x;
   const int N = a.N;
-  const bool exact_mode = a.do_score && (a.exact_r || a.exact_g);    // uniform
+  const bool exact_mode = EXACT && a.do_score && (a.exact_r || a.exact_g);    // uniform
   int32_t* ex_list = a.ex_list + (int64_t)b * N;
   auto is_exact = [&](int i) { return (exbits[i >> 5] >> (i & 31)) & 1u; };
   // marks token i; true if this call was the one that marked it (it then goes on the list)
@@ -386,25 +389,22 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       }
       for (int i = tid; i < (one_each ? 0 : N); i += nt) {
         double R, G;
+        // the [CLS] term's load goes out first and is in flight together with the partials below
+        const double g_cls = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls[(int64_t)b * N + i] : 0.0;
         if (a.red_src == FICOCO_R_ATTN_RECV) {
+          // Column partials of the row chunks, added in chunk order.  32 loads are issued together
+          // (one trip to memory per 32 chunks): past the last chunk the last one is loaded again and
+          // counted as zero, so that the batch stays straight-line code.
           const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
           double acc = 0.0;
-          int c = 0;
-          for (; c + 32 <= a.n_chunks; c += 32) {          // 32 independent loads, added in order
+          for (int c = 0; c < a.n_chunks; c += 32) {
             double v[32];
 #pragma unroll
-            for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)(c + u) * N];
+            for (int u = 0; u < 32; ++u) v[u] = p[(int64_t)min(c + u, a.n_chunks - 1) * N];
+            issue_fence();
 #pragma unroll
-            for (int u = 0; u < 32; ++u) acc += v[u];
+            for (int u = 0; u < 32; ++u) acc += c + u < a.n_chunks ? v[u] : 0.0;
           }
-          for (; c + 8 <= a.n_chunks; c += 8) {
-            double v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = p[(int64_t)(c + u) * N];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
-          }
-          for (; c < a.n_chunks; ++c) acc += p[(int64_t)c * N];
           R = acc / (double)N;
         } else if (a.red_src == FICOCO_R_VECTOR) {
           R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
@@ -412,7 +412,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           R = a.fterm_r[(int64_t)b * N + i];
         }
         if (a.sem_src == FICOCO_G_CLS_ATTN) {
-          G = a.cls[(int64_t)b * N + i];
+          G = g_cls;
         } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
           const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
           double acc = 0.0;
@@ -497,8 +497,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       const int n_flag = bcast[4];
       keys_ready = true;
       if (n_flag == 0 || pass == 3) break;
-      if (a.dtype == FICOCO_BF16) exact_terms_of<bf16_t>(a, b, ex_list, n_flag, pass == 0);
-      else exact_terms_of<float>(a, b, ex_list, n_flag, pass == 0);
+      if constexpr (EXACT) {
+        if (a.dtype == FICOCO_BF16) exact_terms_of<bf16_t>(a, b, ex_list, n_flag, pass == 0);
+        else exact_terms_of<float>(a, b, ex_list, n_flag, pass == 0);
+      }
       keys_ready = false;
     }
   } else {
@@ -685,12 +687,15 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.slot_of = (int32_t*)(ws + pl.slot_of);
   a.overflow = overflow;
   const size_t lds = select_lds(p, penalty);
+  const bool exact = a.exact_r || a.exact_g;
   if (lds > 32768)
-    (void)hipFuncSetAttribute((const void*)select_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    (void)hipFuncSetAttribute(exact ? (const void*)select_kernel<true> : (const void*)select_kernel<false>,
+                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   // Short sequences: no more wavefronts than tokens need (every barrier of the kernel waits for
   // all of them); at least 256 threads, which the histogram walk assumes.
   const int threads = p.N >= kSelectThreads ? kSelectThreads : std::max(256, (p.N + kWave - 1) / kWave * kWave);
-  hipLaunchKernelGGL(select_kernel, dim3(p.B), dim3(threads), lds, s, a);
+  if (exact) hipLaunchKernelGGL(select_kernel<true>, dim3(p.B), dim3(threads), lds, s, a);
+  else hipLaunchKernelGGL(select_kernel<false>, dim3(p.B), dim3(threads), lds, s, a);
 }
 
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {

@@ -82,6 +82,42 @@ def compare_image(g, b, ref, dtype, vis_begin, exact_alpha, extra_row=None):
     return float(err.max())
 
 
+MARGIN_BOUND = 64 * 2.0 ** -24      # relative margin above which a single-precision path could not flip a decision
+
+
+def margin_audit(g, b, ref):
+    """Decision margins of one image, from the oracle's float64 values: how far (relative) the
+    top-K cut is from the scores next to it, and how far every row's threshold is from the nearest
+    correlation that does not define it.  Every decision whose margin exceeds MARGIN_BOUND must be
+    the same on the GPU (checked here on its own, beside the bit-exact comparison of the sets)."""
+    out = {}
+    s, S = np.asarray(ref["scores"]), ref["S"]
+    n_disc = len(S)
+    if 0 < n_disc < len(s):
+        order = np.sort(s)[::-1]
+        hi, lo = order[n_disc - 1], order[n_disc]
+        scale = max(abs(hi), abs(lo), 1e-300)
+        out["filter"] = (hi - lo) / scale
+        cut = 0.5 * (hi + lo)
+        far = np.abs(s - cut) / scale > MARGIN_BOUND
+        on_gpu = np.zeros(len(s), bool)
+        on_gpu[g["discard"][b]] = True
+        assert np.array_equal(on_gpu[far], (s > cut)[far]), "a filter decision with a wide margin differs"
+    C, tau = ref.get("C"), ref.get("tau")
+    if tau is not None and C is not None and C.size:
+        t = np.asarray(tau)[:, None]
+        rel = np.abs(C - t) / np.maximum(np.abs(t), 1e-300)
+        rel_other = np.where(C == t, np.inf, rel)           # values equal to the threshold define it
+        out["threshold"] = float(rel_other.min())
+        picked = np.zeros(C.shape, bool)
+        for a in range(C.shape[0]):
+            picked[a, g["tgt"][b, a, :g["cnt"][b, a]]] = True
+        live = np.array([len(j) > 0 for j in ref["J"]])[:, None]     # rows that recycle nothing have no targets at all
+        far = (rel > MARGIN_BOUND) & live
+        assert np.array_equal(picked[far], (C >= t)[far]), "a threshold decision with a wide margin differs"
+    return out
+
+
 def run_v(cfg, A, X=None, pos=None, n_keep=None, red_src=fc.R_ATTN_RECV, sem_src=fc.G_CLS_ATTN,
           corr_src=fc.C_ATTN, k_max=8, eps=None, window=None, staged=False, ctx=None, F=None,
           k_mode=fc.K_ADAPTIVE, fixed_k=0, compress_mode=fc.COMPRESS_SELF, gap=False):

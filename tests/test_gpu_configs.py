@@ -19,6 +19,21 @@ def say(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
+class Margins:
+    """Smallest decision margins over the images of a configuration (see parity.margin_audit)."""
+
+    def __init__(self):
+        self.m = {}
+
+    def add(self, out, b, ref):
+        for k, v in P.margin_audit(out, b, ref).items():
+            self.m[k] = min(self.m.get(k, float("inf")), v)
+
+    def __str__(self):
+        return ", ".join("min relative %s margin %.3g" % kv for kv in sorted(self.m.items())) + \
+               " (bound %.3g)" % P.MARGIN_BOUND
+
+
 @pytest.fixture(scope="module")
 def ctx():
     c = fc.Context(0)
@@ -32,7 +47,9 @@ def test_config0_v_single_f32(ctx):
     ref = P.oracle_v(cfg, cfg["A"], 0)
     err = P.compare_image(out, 0, ref, "f32", 1, True)
     assert len(ref["S"]) == 384 and out["X_out"].shape == (1, 193, 1024)
-    say("config 0: max |dX| = %.3g" % err)
+    mg = Margins()
+    mg.add(out, 0, ref)
+    say("config 0: max |dX| = %.3g; %s" % (err, mg))
 
 
 def test_config1_v_batched_three_steps(ctx):
@@ -47,15 +64,17 @@ def test_config1_v_batched_three_steps(ctx):
         c = dict(cfg, n_keep=keep)
         out, buf = P.run_v(c, A, X=X_gpu, pos=pos_gpu, ctx=ctx)
         worst = 0.0
+        mg = Margins()
         for b in range(Bn):
             n = X_ref[b].shape[0] - 1
             ref = O.v_step(X_ref[b], O.widen(synth.to_numpy(A[b])), cls_index=0, vis_begin=1, N=n,
                            n_keep=keep, lam=cfg["lam"], eps=cfg["eps"], pos=pos_ref[b], grid=cfg["grid"],
                            window=2, coef=2.0)
             worst = max(worst, P.compare_image(out, b, ref, "bf16", 1, True))
+            mg.add(out, b, ref)
             X_ref[b] = O.round_to_bf16(ref["X_out"])   # tokens are stored in bfloat16 between layers
             pos_ref[b] = ref["pos_out"]
-        say("config 1 step %d (%d -> %d): max |dX| = %.3g" % (step, X_gpu.shape[1] - 1, keep, worst))
+        say("config 1 step %d (%d -> %d): max |dX| = %.3g; %s" % (step, X_gpu.shape[1] - 1, keep, worst, mg))
         X_gpu = buf.X_out.cpu()
         pos_gpu = buf.pos_out.cpu()
         del A
@@ -65,12 +84,15 @@ def test_config1_v_batched_three_steps(ctx):
 def test_config2_v_multicrop(ctx):
     cfg = synth.ficoco_v_multicrop()                   # seed 2, B=4, N=2880, keep 640
     out, _ = P.run_v(cfg, cfg["A"], ctx=ctx)
+    mg = Margins()
     for b in range(cfg["B"]):
         ref = P.oracle_v(cfg, cfg["A"], b)
         err = P.compare_image(out, b, ref, "bf16", 1, True)
+        mg.add(out, b, ref)
         sizes = [len(j) for j in ref["J"]]               # |J_i| = 2 at n = 640, eps = 0.998,
         assert min(sizes) == 2 and np.mean(sizes) < 2.05   # more only where bf16 values tie
         say("config 2 image %d: max |dX| = %.3g" % (b, err))
+    say("config 2: %s" % mg)
 
 
 @pytest.mark.parametrize("with_vv", [False, True])
@@ -79,10 +101,13 @@ def test_config3_l_decoder(ctx, with_vv):
     red, cor = (fc.R_ATTN_RECV, fc.C_ATTN) if with_vv else (fc.R_SIM_MEAN, fc.C_COSINE)
     out, _ = P.run_l(cfg, red, cor, ctx=ctx)
     assert out["X_out"].shape == (8, 675 - 432, 4096)
+    mg = Margins()
     for b in range(cfg["B"]):
         ref = P.oracle_l(cfg, b, red, cor)
         err = P.compare_image(out, b, ref, "bf16", cfg["vis_begin"], False)
+        mg.add(out, b, ref)
         say("config 3%s image %d: max |dX| = %.3g" % ("'" if with_vv else "", b, err))
+    say("config 3%s: %s" % ("'" if with_vv else "", mg))
 
 
 def test_config4_v_video(ctx):
@@ -91,4 +116,6 @@ def test_config4_v_video(ctx):
     ref = P.oracle_v(cfg, None, 0, red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE)
     err = P.compare_image(out, 0, ref, "bf16", 0, False)
     assert out["X_out"].shape == (1, 1152, 1024)
-    say("config 4: max |dX| = %.3g" % err)
+    mg = Margins()
+    mg.add(out, 0, ref)
+    say("config 4: max |dX| = %.3g; %s" % (err, mg))

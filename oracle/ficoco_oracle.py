@@ -51,6 +51,11 @@ Readings (where the paper is silent, ambiguous or garbled):
       counted with multiplicity (a tie at the top gives 0); a row with fewer than two
       preserved tokens has gap 0.
 
+  R16 queries and keys instead of the map (Sec. "Self-Attention", A = Softmax(Q K^T / sqrt(D))):
+      the map of every head is the row softmax of that head's logits over all keys of the block,
+      unmasked; it is used unrounded (the caller's model would have stored it in its own
+      precision, which the step never sees in this form).  Everything after it is unchanged.
+
   R15 schedule utility (appendix "Theoretical FLOPs Calculation", Sec. "Implementation
       Details"): a layer over n visual tokens costs 4 p D^2 + 2 p^2 D + 2 p D F with p = n (V)
       or n + M (L); a reducing layer is charged with its tokens AFTER the reduction plus the
@@ -106,6 +111,28 @@ def round_to_dtype(x, dtype):
     if dtype == "bf16":
         return round_to_bf16(x)
     raise ValueError(dtype)
+
+
+# --------------------------------------------------------------------------- self-attention
+def attention_from_qk(Q, K, scale):
+    """Sec. "Self-Attention": A = Softmax(Q K^T / sqrt(D)) per head, for a caller that hands over
+    the projected queries and keys instead of the map.  Q [H, nq, d], K [H, nk, d] float64;
+    `scale` (the 1/sqrt(D) of the equation) crosses the boundary as float32.  Returns [H, nq, nk]:
+    every row a softmax over all nk keys (no mask: the vision encoder attends everywhere).  The
+    logits are a float64 matrix product, the exponentials are taken relative to the row maximum
+    and the row is divided by its sum, keys added in order."""
+    Q = np.asarray(Q, dtype=F64)
+    K = np.asarray(K, dtype=F64)
+    sc = f32(scale)
+    A = np.empty((Q.shape[0], Q.shape[1], K.shape[1]), dtype=F64)
+    for h in range(Q.shape[0]):
+        logits = (Q[h] @ K[h].T) * sc
+        e = np.exp(logits - logits.max(axis=1, keepdims=True))
+        den = np.zeros(e.shape[0], dtype=F64)
+        for k in range(e.shape[1]):
+            den = den + e[:, k]
+        A[h] = e / den[:, None]
+    return A
 
 
 # --------------------------------------------------------------------------- filter: score
@@ -500,6 +527,12 @@ def v_step(X, A, *, cls_index, vis_begin, N, n_keep, lam=0.35, eps=0.998,
     else:
         raise ValueError(corr_src)
     return _finish(X, vis_begin, s, n_keep, C_of, eps, pos, k_mode, fixed_k, average)
+
+
+def v_step_qk(X, Q, K, scale, **kw):
+    """Algorithm 1 for a caller that supplies the layer's projected queries and keys
+    (Q, K: [H, n_tot, d]) instead of the attention map (reading R16)."""
+    return v_step(X, attention_from_qk(Q, K, scale), **kw)
 
 
 def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.998,

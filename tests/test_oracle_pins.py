@@ -120,6 +120,51 @@ def test_score_isolates_terms_and_sign():
     assert np.allclose(O.text_attention(P, [1, 2], np.array([0, 1])), [0.35, 0.65], rtol=1e-15)
 
 
+# ------------------------------------------------------------------ self-attention from Q, K
+def test_attention_from_qk_closed_forms_and_library_softmax():
+    """Sec. "Self-Attention": rows are softmaxes.  Identical keys (or zero queries) give the
+    uniform map 1/nk exactly-ish; a key that every query is aligned with takes the whole row as
+    the scale grows; the general case equals a library log-sum-exp evaluation; and a step fed
+    Q, K equals the step fed the map they define (nothing else changes)."""
+    from scipy.special import logsumexp
+    r = rng(70)
+    H, n, d = 3, 9, 4
+    Q = r.standard_normal((H, n, d))
+    K = np.tile(r.standard_normal((H, 1, d)), (1, n, 1))          # all keys of a head identical
+    A = O.attention_from_qk(Q, K, 0.5)
+    assert A.shape == (H, n, n) and np.allclose(A, 1.0 / n, rtol=0, atol=1e-15)
+    assert np.allclose(O.attention_from_qk(np.zeros((H, n, d)), r.standard_normal((H, n, d)), 0.5), 1.0 / n, atol=1e-15)
+    # one-hot limit: key 2 = 50 * e0, queries = e0  ->  logits 50 * scale on key 2, 0 elsewhere
+    Q1 = np.zeros((1, 5, d)); Q1[0, :, 0] = 1.0
+    K1 = np.zeros((1, 5, d)); K1[0, 2, 0] = 50.0
+    A1 = O.attention_from_qk(Q1, K1, 1.0)
+    want = np.exp(50.0) / (np.exp(50.0) + 4.0)
+    assert np.allclose(A1[0, :, 2], want, rtol=1e-14) and np.allclose(A1[0, :, 0], (1 - want) / 4, rtol=1e-10)
+    # general case against log-sum-exp; rows sum to one; the scale crosses as float32
+    K = r.standard_normal((H, n + 2, d))
+    A = O.attention_from_qk(Q, K, 0.3)
+    sc = float(np.float32(0.3))
+    for h in range(H):
+        L = (Q[h] @ K[h].T) * sc
+        assert np.allclose(A[h], np.exp(L - logsumexp(L, axis=1, keepdims=True)), rtol=1e-13)
+    assert np.allclose(A.sum(axis=2), 1.0, rtol=0, atol=1e-14)
+    # transposing the roles of Q and K is NOT the same map (a transposed operand must fail)
+    assert not np.allclose(O.attention_from_qk(Q, Q[:, ::-1], 0.3), O.attention_from_qk(Q[:, ::-1], Q, 0.3))
+
+
+def test_step_from_qk_equals_step_from_the_map_it_defines():
+    r = rng(71)
+    H, g, D, d = 2, 4, 6, 4
+    n = g * g + 1
+    X = r.standard_normal((n, D))
+    Q, K = r.standard_normal((H, n, d)), r.standard_normal((H, n, d))
+    A = O.attention_from_qk(Q, K, 0.5)
+    kw = dict(cls_index=0, vis_begin=1, N=n - 1, n_keep=9, grid=(1, g, g))
+    a, b = O.v_step(X, A, **kw), O.v_step_qk(X, Q, K, 0.5, **kw)
+    assert np.array_equal(a["S"], b["S"]) and np.array_equal(a["X_out"], b["X_out"])
+    assert all(np.array_equal(x, y) for x, y in zip(a["J"], b["J"]))
+
+
 # ------------------------------------------------------------------ equivalent token / mean cosine
 def test_equivalent_token_closed_forms():
     """a^Eq = -cos(mu, F_i): identical tokens -> -1; F = {e1, e2} -> mu = (.5,.5), cos = 1/sqrt2."""

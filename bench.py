@@ -69,36 +69,46 @@ def make_workload(torch, fc, name, dev):
     g = torch.Generator(device=dev)
     bf, f32 = torch.bfloat16, torch.float32
     W = dict(name=name)
-    if name in ("1", "1c", "0", "2"):
-        B, grid_g, H, D = {"1": (16, 1, 16, 1024), "1c": (16, 1, 16, 1024), "0": (1, 1, 16, 1024),
+    if name in ("1", "1c", "1q", "0", "2"):
+        B, grid_g, H, D = {"1": (16, 1, 16, 1024), "1c": (16, 1, 16, 1024), "1q": (16, 1, 16, 1024), "0": (1, 1, 16, 1024),
                            "2": (4, 5, 16, 1024)}[name]
         N = grid_g * 576
-        keep = {"1": 384, "1c": 384, "0": 192, "2": 640}[name]
+        keep = {"1": 384, "1c": 384, "1q": 384, "0": 192, "2": 640}[name]
         dt = f32 if name == "0" else bf
-        centres = {"1": 64, "1c": 64, "0": 48, "2": 200}[name]
-        sigma = 1.5 if name in ("1", "1c") else 1.0
-        n_sets = {"1": 4, "1c": 4, "0": 16, "2": 1}[name]
-        g.manual_seed({"1": 1, "1c": 1, "0": 0, "2": 2}[name])
+        centres = {"1": 64, "1c": 64, "1q": 64, "0": 48, "2": 200}[name]
+        sigma = 1.5 if name in ("1", "1c", "1q") else 1.0
+        n_sets = {"1": 4, "1c": 4, "1q": 4, "0": 16, "2": 1}[name]
+        g.manual_seed({"1": 1, "1c": 1, "1q": 1, "0": 0, "2": 2}[name])
+        d_head = 64
         sets = []
         for _ in range(n_sets):
             X = torch.empty(B, N + 1, D, device=dev)
             X[:, 0] = torch.randn(B, D, device=dev, generator=g)
             X[:, 1:] = _clustered(torch, g, dev, B, N, D, centres)
+            if name == "1q":
+                # queries and keys whose logits q.k / sqrt(d) are about N(0, sigma^2): the same family of maps
+                Q = (torch.randn(B, H, N + 1, d_head, device=dev, generator=g) * sigma ** 0.5).to(bf)
+                K = (torch.randn(B, H, N + 1, d_head, device=dev, generator=g) * sigma ** 0.5).to(bf)
+                sets.append(dict(X=X.to(dt).contiguous(), Q=Q, K=K))
+                continue
             A = _softmax_map(torch, g, dev, B, H, N + 1, N + 1, sigma, dt)
             sets.append(dict(X=X.to(dt).contiguous(), A=A))
         es = 2 if dt == bf else 4
         W.update(label="BASELINE config %s: FiCoCo-V fused step, B=%d, [CLS]+%d patches, D=%d, H=%d, %s, keep %d%s"
                  % (name[0] + (" step 1" if name[0] == "1" else ""), B, N, D, H, "bf16" if dt == bf else "f32", keep,
-                    ", cosine correlation variant" if name == "1c" else ""),
+                    ", cosine correlation variant" if name == "1c" else
+                    ", maps formed from queries and keys (d_head 64) inside the step" if name == "1q" else ""),
                  B=B, N=N, D=D, H=H, keep=keep, dtype="bf16" if dt == bf else "f32", variant=fc.VARIANT_V, sets=sets,
                  kw=dict(vis_begin=1, N=N, n_keep=keep, cls_index=0, grid=(grid_g, 24, 24), window=2,
                          penalty_coef=2.0, w_score=0.35, eps=0.998, k_max=8,
                          corr_src=fc.C_COSINE if name == "1c" else fc.C_ATTN),
-                 dominant="gram" if name == "1c" else "reduce",
+                 dominant="gram" if name == "1c" else "qk" if name == "1q" else "reduce",
+                 qk_elements=B * H * (N + 1) * (N + 1), d_head=d_head,
+                 qk_bytes=2 * B * H * (N + 1) * d_head * 2 + B * N * N * 4,
                  reduce_bytes=B * H * (N + 1) * (N + 1) * es + (0 if name == "1c" else B * N * N * 4),
                  gram_flops=2.0 * B * (N - keep) * keep * D,
                  step_bytes=B * H * (N + 1) * (N + 1) * es + B * N * N * 4 + B * (N + 1) * D * es
-                 + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name != "1c" else None)
+                 + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name not in ("1c", "1q") else None)
     elif name in ("3", "3p", "3b", "3bp"):
         B, n_sys, N, M, D, H, keep = 8, 35, 576, 64, 4096, 32, 144
         if name in ("3b", "3bp"):                # the 13B decoder shape with a long instruction
@@ -219,7 +229,11 @@ def _oracle_worker(job):
     t0 = time.monotonic()
     while True:
         for sq in seqs:
-            if job["variant"] == "V":
+            if job["variant"] == "VQ":
+                O.v_step_qk(sq["X"], sq["Q"], sq["K"], job["qk_scale"], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"],
+                            N=kw["N"], n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2,
+                            coef=2.0, **okw)
+            elif job["variant"] == "V":
                 O.v_step(sq["X"], sq["A"], cls_index=kw["cls_index"], vis_begin=kw["vis_begin"], N=kw["N"],
                          n_keep=kw["n_keep"], lam=kw["w_score"], eps=kw["eps"], grid=kw["grid"], window=2, coef=2.0,
                          recv_vec=sq["recv_vec"], sem_vec=sq["sem_vec"], red_src=job["red"], sem_src=job["sem"],
@@ -269,8 +283,9 @@ def cpu_baseline(W, pool, n_workers, budget=7.0):
         return None if st.get(k) is None else to_numpy(st[k][b])
 
     seqs = [dict(X=host("X", b), A=host("A", b), A_text=host("A_text", b), recv_vec=host("recv_vec", b),
-                 sem_vec=host("sem_vec", b)) for b in range(B)]
-    job = dict(variant="V" if W["variant"] == fc.VARIANT_V else "L",
+                 sem_vec=host("sem_vec", b), Q=host("Q", b), K=host("K", b)) for b in range(B)]
+    job = dict(variant=("VQ" if st.get("Q") is not None else "V") if W["variant"] == fc.VARIANT_V else "L",
+               qk_scale=float(W.get("d_head", 64)) ** -0.5,
                kw={k: v for k, v in kw.items() if k in ("cls_index", "vis_begin", "N", "n_keep", "w_score", "eps", "grid", "gamma")},
                red={fc.R_ATTN_RECV: "attn", fc.R_VECTOR: "vector", fc.R_SIM_MEAN: "sim_mean"}[kw.get("red_src", fc.R_ATTN_RECV)],
                sem={fc.G_CLS_ATTN: "cls", fc.G_VECTOR: "vector", fc.G_TEXT_ATTN: "cls"}[kw.get("sem_src", fc.G_CLS_ATTN)],
@@ -300,7 +315,8 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 2, 3, 3p, 4; 3b / 3bp: the 13B decoder shape")
+    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 1q (maps formed from queries and keys), 2, 3, 3p, 4; "
+                                                  "3b / 3bp: the 13B decoder shape")
     ap.add_argument("--ablation", default="none",
                     choices=["none", "fixed0", "fixed1", "fixed2", "convergent", "average"],
                     help="time one of the paper's ablation variants of the correlate / compress stages instead of "
@@ -335,7 +351,8 @@ def main():
         W["label"] += ", ablation variant %s" % args.ablation
     n_sets = len(W["sets"])
     probs = [fc.make_problem(st["X"], variant=W["variant"], A=st.get("A"), A_text=st.get("A_text"),
-                             recv_vec=st.get("recv_vec"), sem_vec=st.get("sem_vec"), H=W["H"], **W["kw"])
+                             recv_vec=st.get("recv_vec"), sem_vec=st.get("sem_vec"), H=W["H"], Q=st.get("Q"), K=st.get("K"),
+                             **W["kw"])
              for st in W["sets"]]
     tdt = torch.bfloat16 if W["dtype"] == "bf16" else torch.float32
     n_str = max(1, args.streams)
@@ -370,7 +387,7 @@ def main():
     assert outputs_checked, "a pipelined step's outputs differ from the same step run alone"
 
     # Dominant kernel: event pairs recorded by the library around its launch.
-    kind = fc.PROBE_REDUCE if W["dominant"] == "reduce" else fc.PROBE_GRAM
+    kind = fc.PROBE_REDUCE if W["dominant"] in ("reduce", "qk") else fc.PROBE_GRAM
 
     def event_pairs(n):
         pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
@@ -427,7 +444,19 @@ def main():
     sync()
     lat = sorted(e0.elapsed_time(e1) * 1e3 for e0, e1 in lat_pairs)
 
-    if W["dominant"] == "reduce":
+    if W["dominant"] == "qk":
+        # Arithmetic bound: per (image, head, query, key) seven single-precision vector operations
+        # (scale, maximum, subtract, exponential, row sum, normalise, head accumulation) beside
+        # 2 * d_head matrix-core flops; the vector operations are what the kernel waits for.
+        algo = 7.0 * W["qk_elements"]
+        achieved = algo / (alone_ms * 1e-3) / 1e12
+        roof = {"kernel": "attn_qk_kernel (softmax(QK^T) on bf16 MFMA 32x32x16, reduced on the fly)", "bound": "alu",
+                "achieved": achieved, "peak": 157.3, "unit": "TFLOP/s", "frac": achieved / 157.3, "traffic": None,
+                "algorithmic_flops": algo, "mfma_flops": 2.0 * W["d_head"] * W["qk_elements"],
+                "hbm_bytes_algorithmic": W["qk_bytes"],
+                "note": "the materialised-map path reads %d bytes of maps for the same outputs (bench.py --config 1)"
+                        % (W["qk_elements"] * 2)}
+    elif W["dominant"] == "reduce":
         algo = W["reduce_bytes"]
         achieved = algo / (alone_ms * 1e-3) / 1e9
         roof = {"kernel": "attn_reduce_kernel<%s>" % W["dtype"], "bound": "hbm", "achieved": achieved,

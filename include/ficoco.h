@@ -156,6 +156,23 @@ typedef struct {
   int32_t k_mode;        /* ficoco_k_mode                                                  */
   int32_t fixed_k;       /* FICOCO_K_FIXED: targets per discarded token, 0 <= fixed_k <= k_max */
   int32_t compress_mode; /* ficoco_compress_mode                                           */
+
+  /* Queries and keys instead of the map (Sec. "Self-Attention": A = Softmax(Q K^T / sqrt(D))).
+   * Used when A is NULL and an attention-derived term is selected (FiCoCo-V only): the step then
+   * forms softmax(qk_scale * Q_h K_h^T) of every head itself, row by row over all qk_n keys,
+   * unmasked, and reduces it on the fly -- the [B][H][n][n] maps are never stored.  Row r of Q
+   * and of K is the token at sequence position qk_begin + r; the block must cover the visual
+   * span and, for FICOCO_G_CLS_ATTN, cls_index.  bfloat16 only (qk_dtype = FICOCO_BF16, whatever
+   * `dtype` the tokens have), d_head in {32, 64, 128}, qk_n <= 640: FICOCO_EUNSUPPORTED
+   * otherwise.  Logits, exponentials and row sums are single precision (bf16 products are exact
+   * in it), so scores and map entries agree with a double-precision evaluation to about 1e-6
+   * relative, not to the last bit: a top-K or threshold decision whose margin is below that may
+   * differ from one taken on double-precision values. */
+  const void *Q; /* [B][H][qk_n][d_head], d_head contiguous */
+  const void *K; /* same shape and strides */
+  int64_t qk_stride_b, qk_stride_h, qk_stride_n;
+  int32_t qk_begin, qk_n, d_head, qk_dtype;
+  float qk_scale; /* the 1/sqrt(D) of the equation */
 } ficoco_problem;
 
 /* ctx: create once per device (and calling thread); not thread safe.  ficoco_create also

@@ -12,7 +12,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libficoco.so")
-SOURCES = ["api.hip", "attn_reduce.hip", "select.hip", "correlate.hip", "compress.hip", "features.hip", "schedule.hip"]
+SOURCES = ["api.hip", "attn_reduce.hip", "attn_qk.hip", "select.hip", "correlate.hip", "compress.hip", "features.hip", "schedule.hip"]
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "-shared", "--offload-arch=gfx950",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument", "-Wno-unknown-warning-option"]

@@ -79,7 +79,25 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   const bool L = p.variant == FICOCO_VARIANT_L;
   const bool need_A = p.red_src == FICOCO_R_ATTN_RECV || p.sem_src == FICOCO_G_CLS_ATTN ||
                       p.corr_src == FICOCO_C_ATTN;
-  if (need_A) {
+  const bool qk = need_A && p.A == nullptr && p.Q != nullptr && p.K != nullptr;
+  if (qk) {
+    REQUIRE(!L, "queries and keys in place of the map are taken by FiCoCo-V only");
+    REQUIRE(p.H >= 1 && p.qk_n >= 1 && p.qk_stride_n >= p.d_head && p.qk_stride_h >= 0 && p.qk_stride_b >= 0,
+            "bad Q / K shape or strides");
+    REQUIRE(p.qk_begin >= 0 && p.qk_begin <= p.vis_begin && p.vis_begin + p.N <= p.qk_begin + p.qk_n,
+            "Q / K do not cover the visual tokens");
+    if (p.sem_src == FICOCO_G_CLS_ATTN)
+      REQUIRE(p.cls_index >= p.qk_begin && p.cls_index < p.qk_begin + p.qk_n &&
+                  (p.cls_index < p.vis_begin || p.cls_index >= p.vis_begin + p.N),
+              "cls_index must be a row of Q / K outside the visual span");
+    REQUIRE(p.qk_scale > 0.0f && p.qk_scale < 1e30f, "qk_scale must be positive and finite");
+    if (p.qk_dtype != FICOCO_BF16 || !(p.d_head == 32 || p.d_head == 64 || p.d_head == 128) ||
+        p.qk_n > kQkMaxKeys || p.qk_stride_n % 8 != 0 || p.qk_stride_h % 8 != 0 || p.qk_stride_b % 8 != 0 ||
+        ((uintptr_t)p.Q & 15) || ((uintptr_t)p.K & 15)) {
+      *why = "queries / keys: bfloat16, 16-byte aligned rows, d_head in {32,64,128} and at most 640 rows are supported";
+      return FICOCO_EUNSUPPORTED;
+    }
+  } else if (need_A) {
     REQUIRE(p.A != nullptr, "A is NULL but an attention-derived term is selected");
     REQUIRE(p.H >= 1, "H must be positive");
     REQUIRE(p.a_nq >= 1 && p.a_nk >= 1 && p.a_stride_q >= p.a_nk, "bad A shape / strides");
@@ -158,7 +176,10 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
     int r = (int)((want + pl.row_lanes - 1) / pl.row_lanes) * pl.row_lanes;
     return r;
   };
-  if (need_A) {
+  pl.qk = qk;
+  if (qk) {
+    pl.n_chunks = (p.qk_n + kQkTile - 1) / kQkTile;    // one column partial per tile of query rows
+  } else if (need_A) {
     int lo = p.vis_begin - p.a_q_begin, hi = lo + p.N;  // visual query rows
     const bool vis_rows = p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN;
     if (!vis_rows) { lo = hi = p.cls_index - p.a_q_begin; ++hi; }
@@ -327,7 +348,7 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
   const bool pg = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_GRAM;
   if (pr) (void)hipEventRecord(ctx->probe_start, s);
-  launch_attn_reduce(p, pl, w, s);
+  if (pl.qk) launch_attn_qk(p, pl, w, s); else launch_attn_reduce(p, pl, w, s);
   if (pr) (void)hipEventRecord(ctx->probe_stop, s);
   if (pl.need_features) launch_features(p, pl, w, s);
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
@@ -415,7 +436,8 @@ int ficoco_reduce(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_
   if (rc != FICOCO_OK) return rc;
   const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
   if (pr) (void)hipEventRecord(ctx->probe_start, (hipStream_t)stream);
-  launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
+  if (pl.qk) launch_attn_qk(*p, pl, (char*)ws, (hipStream_t)stream);
+  else launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
   if (pr) (void)hipEventRecord(ctx->probe_stop, (hipStream_t)stream);
   return finish(ctx, "ficoco_reduce");
 }
@@ -426,7 +448,8 @@ int ficoco_score(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_b
   const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_score");
   if (rc != FICOCO_OK) return rc;
   if (!scores) return fail(ctx, FICOCO_EINVAL, "ficoco_score", "scores is NULL");
-  launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
+  if (pl.qk) launch_attn_qk(*p, pl, (char*)ws, (hipStream_t)stream);
+  else launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
   if (pl.need_features) launch_features(*p, pl, (char*)ws, (hipStream_t)stream);
   launch_score(*p, pl, (char*)ws, scores, (hipStream_t)stream);
   return finish(ctx, "ficoco_score");

@@ -1,0 +1,216 @@
+// Attention reduction from queries and keys (Sec. "Self-Attention": A = Softmax(Q K^T / sqrt(D))):
+// the per-head maps are formed on the matrix cores and reduced on the fly, so the [B,H,n,n]
+// maps never exist in memory.  Outputs are those of attn_reduce.hip -- per-tile column partials of
+// the received attention (first term of Eq. 1), the [CLS] row (second term), and the head-mean
+// map in single precision, transposed, for the correlate stage (Algorithm 1, stage 2).
+//
+// Single precision throughout (products of bfloat16 values are exact in it); the vector arithmetic
+// of the softmax, not memory, bounds the kernel.
+#include "common.hpp"
+
+namespace ficoco {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kQkWaves = 8;                         // wavefronts per workgroup: they split the keys
+constexpr int kQkKB = 5;                            // 16-key blocks per wavefront
+constexpr int kQkQB = kQkTile / 16;                 // 16-query blocks per workgroup
+static_assert(kQkWaves * kQkKB * 16 == kQkMaxKeys, "the wavefronts split the keys");
+static_assert(kQkTile % 16 == 0, "whole 16-query blocks");
+
+struct QkArgs {
+  const bf16_t* Q;
+  const bf16_t* K;
+  int64_t sb, sh, sn;
+  int H, n;             // heads, rows of the block (queries = keys)
+  int N;                // visual tokens
+  int vis0;             // block row of visual token 0
+  int cls_r;            // block row of the [CLS] query, or -1
+  float scale_log2e;    // qk_scale * log2(e): exponentials are taken as powers of two
+  float* abar;          // [B][N][map_pitch] or null
+  int map_pitch;
+  double* recv_part;    // [B][n_tiles][N]
+  double* cls;          // [B][N]
+  int n_tiles, B;
+};
+
+// v_mfma_f32_16x16x32_bf16: operand A is 16 rows x 32 features (lane: row lane % 16, features
+// 8 (lane / 16) .. + 8), operand B 16 columns x 32 features (same), the result 16 x 16 (lane: column
+// lane % 16, rows 4 (lane / 16) + v for its four registers v).  Rows are keys here, columns queries:
+// a lane's 16-byte operand loads of one key cover 64 contiguous bytes of the key's row across the
+// four lane groups, and a query's probabilities sit in the registers of four lanes.
+//
+// A workgroup owns kQkTile query rows of one image; its 8 wavefronts split the keys (80 each, 640 at
+// most) and walk the heads in order, the operands of the next head being loaded while the current
+// head's softmax is computed.
+template <int KS>     // 32-feature steps of the head dimension
+__global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
+  __shared__ float xmax[2][kQkWaves][kQkTile];
+  __shared__ float xsum[2][kQkWaves][kQkTile];
+  const int total = a.n_tiles * a.B;
+  const int logical = xcd_logical_id(blockIdx.x, total);     // the tiles of one image share an XCD and its L2 (the keys)
+  if (logical >= total) return;
+  const int tile = logical % a.n_tiles;
+  const int64_t b = logical / a.n_tiles;
+  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int l16 = lane % 16, lg = lane / 16;
+  const float NEG = -__builtin_huge_valf();
+  const int key_base = wv * kQkKB * 16;             // first key of this wavefront
+
+  // operand addresses (clamped to valid rows: what lies past the block is masked later)
+  int64_t q_off[kQkQB], k_off[kQkKB];
+#pragma unroll
+  for (int qb = 0; qb < kQkQB; ++qb) q_off[qb] = (int64_t)min(tile * kQkTile + qb * 16 + l16, a.n - 1) * a.sn + lg * 8;
+#pragma unroll
+  for (int kb = 0; kb < kQkKB; ++kb) k_off[kb] = (int64_t)min(key_base + kb * 16 + l16, a.n - 1) * a.sn + lg * 8;
+
+  bf16x8_t kf[kQkKB][KS], qf[kQkQB][KS];
+  auto load_head = [&](int h) {
+    const bf16_t* Qh = a.Q + b * a.sb + (int64_t)h * a.sh;
+    const bf16_t* Kh = a.K + b * a.sb + (int64_t)h * a.sh;
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&kf[kb][ks], Kh + k_off[kb] + ks * 32, 16);
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&qf[qb][ks], Qh + q_off[qb] + ks * 32, 16);
+  };
+
+  f32x4_t P[kQkKB][kQkQB];
+#pragma unroll
+  for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb) P[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+
+  load_head(0);
+#pragma unroll 1
+  for (int h = 0; h < a.H; ++h) {
+    // logits of this head: S[kb][qb][v] = key (key_base + 16 kb + 4 lg + v) . query (16 qb + l16)
+    f32x4_t S[kQkKB][kQkQB];
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        S[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          S[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][ks], qf[qb][ks], S[kb][qb], 0, 0, 0);
+      }
+    // the next head's operands are on their way while this head's softmax is computed (past the
+    // last head the last one is loaded again)
+    load_head(min(h + 1, a.H - 1));
+    issue_fence();                  // the loads go out here, not where the next head first uses them
+    // keys past the block read as -inf (only the last blocks can hold any: a uniform test per block)
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb) {
+      if (key_base + (kb + 1) * 16 > a.n) {
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (key_base + kb * 16 + lg * 4 + v >= a.n) {
+#pragma unroll
+            for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
+          }
+      }
+    }
+    // Softmax of every query's row with ONE exchange between the wavefronts: a wavefront takes the
+    // exponentials relative to a reference at or above the maximum of ITS keys (the maximum in
+    // units of log2, rounded up to a whole number) and sums them; the (reference, sum) pairs are
+    // exchanged, and its probabilities are its exponentials times 2^(own reference - largest
+    // reference) / row sum.  scale_log2e > 0.
+    const int par = h & 1;          // two sets of slots: the next head's writes do not wait for this head's reads
+    float mc[kQkQB];
+    bool any_key[kQkQB];
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb) {
+      float mw = NEG;
+#pragma unroll
+      for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) mw = fmaxf(mw, S[kb][qb][v]);
+      mw = fmaxf(mw, __shfl_xor(mw, 16, kWave));
+      mw = fmaxf(mw, __shfl_xor(mw, 32, kWave));
+      any_key[qb] = mw > NEG;                       // a wavefront whose keys all lie past the block has none
+      mc[qb] = any_key[qb] ? ceilf(mw * a.scale_log2e) : 0.0f;      // a whole number: rescaling between wavefronts is exact
+      float lw = 0.0f;
+#pragma unroll
+      for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const float e = __builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -mc[qb]));
+          S[kb][qb][v] = e;
+          lw += e;
+        }
+      lw += __shfl_xor(lw, 16, kWave);
+      lw += __shfl_xor(lw, 32, kWave);
+      if (lg == 0) { xmax[par][wv][qb * 16 + l16] = any_key[qb] ? mc[qb] : NEG; xsum[par][wv][qb * 16 + l16] = lw; }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb) {
+      const int qi = qb * 16 + l16;
+      float m = NEG;
+#pragma unroll
+      for (int w = 0; w < kQkWaves; ++w) m = fmaxf(m, xmax[par][w][qi]);          // finite: key 0 is valid
+      float l = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kQkWaves; ++w)                                         // wavefronts in order; 2^(whole number) is exact
+        l += xsum[par][w][qi] * __builtin_amdgcn_exp2f(fmaxf(xmax[par][w][qi] - m, -150.0f));
+      const float inv = any_key[qb] ? __builtin_amdgcn_exp2f(fmaxf(mc[qb] - m, -150.0f)) / l : 0.0f;
+#pragma unroll
+      for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) P[kb][qb][v] = fmaf(S[kb][qb][v], inv, P[kb][qb][v]);
+    }
+  }
+
+  const float invH = 1.0f / (float)a.H;
+#pragma unroll
+  for (int kb = 0; kb < kQkKB; ++kb) {
+#pragma unroll
+    for (int v = 0; v < 4; ++v) {
+      const int ik = key_base + kb * 16 + lg * 4 + v - a.vis0;      // visual key index
+      const bool k_vis = ik >= 0 && ik < a.N;
+      float cs = 0.0f;                                              // received from this tile's visual queries
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        const int q = tile * kQkTile + qb * 16 + l16;
+        const int jq = q - a.vis0;                                  // visual query index
+        const bool q_vis = q < a.n && jq >= 0 && jq < a.N;
+        const float pm = P[kb][qb][v] * invH;                       // head-mean probability P[q][key]
+        if (a.abar && q_vis && k_vis) a.abar[(b * a.N + ik) * a.map_pitch + jq] = pm;
+        if (q == a.cls_r && k_vis) a.cls[b * a.N + ik] = (double)pm;
+        cs += q_vis ? pm : 0.0f;
+      }
+      // sum over the 16 lanes that hold the tile's other queries of this key (a fixed butterfly)
+#pragma unroll
+      for (int off = 8; off > 0; off >>= 1) cs += __shfl_xor(cs, off, kWave);
+      if (l16 == 0 && k_vis) a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
+    }
+  }
+}
+
+void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+  QkArgs a{};
+  a.Q = (const bf16_t*)p.Q; a.K = (const bf16_t*)p.K;
+  a.sb = p.qk_stride_b; a.sh = p.qk_stride_h; a.sn = p.qk_stride_n;
+  a.H = p.H; a.n = p.qk_n; a.N = p.N;
+  a.vis0 = p.vis_begin - p.qk_begin;
+  a.cls_r = p.sem_src == FICOCO_G_CLS_ATTN ? p.cls_index - p.qk_begin : -1;
+  a.scale_log2e = p.qk_scale * 1.4426950408889634f;
+  a.abar = (p.corr_src == FICOCO_C_ATTN && pl.n_disc > 0) ? (float*)(ws + pl.abar) : nullptr;
+  a.map_pitch = pl.map_pitch;
+  a.recv_part = (double*)(ws + pl.recv_part);
+  a.cls = (double*)(ws + pl.cls);
+  a.n_tiles = pl.n_chunks; a.B = p.B;
+  const dim3 grid(xcd_padded_total(a.n_tiles * a.B)), block(kQkWaves * kWave);
+  switch (p.d_head / 32) {
+    case 1: hipLaunchKernelGGL(attn_qk_kernel<1>, grid, block, 0, s, a); break;
+    case 2: hipLaunchKernelGGL(attn_qk_kernel<2>, grid, block, 0, s, a); break;
+    default: hipLaunchKernelGGL(attn_qk_kernel<4>, grid, block, 0, s, a); break;
+  }
+}
+
+}  // namespace ficoco

@@ -66,6 +66,7 @@ struct Plan {
   size_t ex_list;        // int32  [B][N]
   int fixed_k;           // >= 0: targets per discarded token fixed by the caller (0: no edges), -1: adaptive
   bool extra_token;      // the additional token of the convergent form is written
+  bool qk;               // the maps are formed from queries and keys on the fly (attn_qk.hip)
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
   int gram_splits, gram_st_per_split;   // K ranges of that kernel and their length in 32-feature stages
   int f_chunks, f_rows_per_wg, Df;
@@ -79,6 +80,9 @@ int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
 
 // ---- launchers (all asynchronous on `s`) -----------------------------------------------
 void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+constexpr int kQkTile = 48;        // query rows per workgroup of the query/key form
+constexpr int kQkMaxKeys = 640;    // keys it holds in registers
 void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s);
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,

@@ -52,6 +52,10 @@ class Problem(C.Structure):
         ("red_src", C.c_int32), ("sem_src", C.c_int32), ("corr_src", C.c_int32),
         ("k_max", C.c_int32),
         ("k_mode", C.c_int32), ("fixed_k", C.c_int32), ("compress_mode", C.c_int32),
+        ("Q", C.c_void_p), ("K", C.c_void_p),
+        ("qk_stride_b", C.c_int64), ("qk_stride_h", C.c_int64), ("qk_stride_n", C.c_int64),
+        ("qk_begin", C.c_int32), ("qk_n", C.c_int32), ("d_head", C.c_int32), ("qk_dtype", C.c_int32),
+        ("qk_scale", C.c_float),
     ]
 
 
@@ -156,7 +160,8 @@ def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_b
                  cls_index=-1, A_text=None, at_k_begin=None, recv_vec=None, sem_vec=None, F=None,
                  pos=None, grid=(1, 0, 0), window=0, penalty_coef=2.0, w_score=0.35, gamma=0.6,
                  eps=0.998, red_src=R_ATTN_RECV, sem_src=G_CLS_ATTN, corr_src=C_ATTN, k_max=8, H=None,
-                 k_mode=K_ADAPTIVE, fixed_k=0, compress_mode=COMPRESS_SELF):
+                 k_mode=K_ADAPTIVE, fixed_k=0, compress_mode=COMPRESS_SELF, Q=None, K=None, qk_begin=0,
+                 qk_scale=None):
     """Fill a `ficoco_problem` from torch tensors (shapes as in include/ficoco.h).  The
     returned Problem only holds raw pointers: keep the tensors alive while it is used."""
     p = Problem()
@@ -198,6 +203,14 @@ def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_b
     p.penalty_coef, p.w_score, p.gamma, p.eps = penalty_coef, w_score, gamma, eps
     p.red_src, p.sem_src, p.corr_src, p.k_max = red_src, sem_src, corr_src, k_max
     p.k_mode, p.fixed_k, p.compress_mode = k_mode, fixed_k, compress_mode
+    if Q is not None:
+        assert K is not None and Q.shape == K.shape and Q.stride() == K.stride() and Q.stride(3) == 1
+        assert Q.dtype == torch.bfloat16 and K.dtype == torch.bfloat16 and Q.shape[0] == B
+        p.Q, p.K = Q.data_ptr(), K.data_ptr()
+        p.qk_stride_b, p.qk_stride_h, p.qk_stride_n = Q.stride(0), Q.stride(1), Q.stride(2)
+        p.H = int(Q.shape[1])
+        p.qk_begin, p.qk_n, p.d_head, p.qk_dtype = qk_begin, Q.shape[2], Q.shape[3], BF16
+        p.qk_scale = float(Q.shape[3]) ** -0.5 if qk_scale is None else qk_scale
     return p
 
 

@@ -1,0 +1,121 @@
+"""The step fed with projected queries and keys instead of the attention maps (Sec.
+"Self-Attention", A = Softmax(Q K^T / sqrt(D))): the library forms the per-head softmax on the
+matrix cores in single precision and never stores [B,H,n,n]; the oracle forms it in float64.
+
+Bar.  Scores and map entries agree to about 1e-6, not to the last bit, so the comparison is the
+margin rule: every top-K decision and every threshold decision whose relative margin (from the
+oracle's float64 values) exceeds 64 * 2^-24 must be identical; where all decisions of an image are
+identical, weights and merged tokens must agree within the token tolerance (bfloat16: 2e-2
+relative / 1e-2 absolute; float32: 1e-5 of the row's largest magnitude)."""
+import sys
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import ficoco_oracle as O
+from paper_2411_17686_amd import ficoco as fc
+from paper_2411_17686_amd import synth
+from tests import parity as P
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def draw_qk(seed, B, H, n, d, sigma):
+    """Queries and keys whose logits q.k / sqrt(d) are about N(0, sigma^2), as bfloat16."""
+    g = torch.Generator().manual_seed(seed)
+    Q = (torch.randn(B, H, n, d, generator=g) * sigma ** 0.5).to(torch.bfloat16)
+    K = (torch.randn(B, H, n, d, generator=g) * sigma ** 0.5).to(torch.bfloat16)
+    return Q, K
+
+
+def run_qk(ctx, cfg, Q, K, **kw):
+    Xd, Qd, Kd = cfg["X"].to("cuda"), Q.to("cuda"), K.to("cuda")
+    p = fc.make_problem(Xd, variant=fc.VARIANT_V, vis_begin=cfg["vis_begin"], N=cfg["N"], n_keep=cfg["n_keep"],
+                        cls_index=cfg["cls_index"], grid=cfg["grid"], window=cfg["window"], penalty_coef=cfg["coef"],
+                        w_score=cfg["lam"], eps=cfg["eps"], Q=Qd, K=Kd, qk_begin=0, **kw)
+    buf = fc.Buffers(p, "cuda", Xd.dtype)
+    fc.ficoco_v_step(ctx, p, buf)
+    out = P.gpu_outputs(buf)
+    del Xd, Qd, Kd
+    return out
+
+
+def compare_under_margin_rule(out, b, ref, dtype, vis_begin):
+    """Returns True when every decision of the image agreed (then the values were compared too)."""
+    scale = float(np.max(np.abs(ref["scores"])))
+    assert np.all(np.abs(out["scores"][b] - ref["scores"]) <= 8e-6 * scale), "scores beyond single-precision accuracy"
+    same_sets = np.array_equal(out["discard"][b], ref["S"])
+    if not same_sets:
+        # only decisions inside the margin may differ: checked token by token
+        P.margin_audit(dict(out, cnt=np.zeros_like(out["cnt"])), b, dict(ref, tau=None))
+        return False
+    P.margin_audit(out, b, ref)
+    same_J = all(out["cnt"][b, a] == len(J) and np.array_equal(out["tgt"][b, a, :len(J)], J)
+                 for a, J in enumerate(ref["J"]))
+    if not same_J:
+        return False
+    for a, J in enumerate(ref["J"]):
+        np.testing.assert_allclose(out["alpha"][b, a, :len(J)], ref["alpha"][a], rtol=2e-5)
+    got, want = O.widen(out["X_out"][b]), ref["X_out"]
+    err = np.abs(got - want)
+    if dtype == "f32":
+        assert np.all(err <= 1e-5 * np.max(np.abs(want), axis=1, keepdims=True))
+    else:
+        assert np.all(err <= 2e-2 * np.abs(want) + 1e-2)
+    assert np.array_equal(out["pos_out"][b], ref["pos_out"])
+    return True
+
+
+@pytest.fixture(scope="module")
+def ctx():
+    c = fc.Context(0)
+    yield c
+    c.close()
+
+
+def _case(ctx, seed, B, grid, D, H, d, dtype, n_keep, sigma):
+    cfg = synth.ficoco_v_single(seed=seed, B=B, grid=grid, D=D, H=1, centres=8, dtype=dtype, n_keep=n_keep)
+    Q, K = draw_qk(seed + 1, B, H, cfg["N"] + 1, d, sigma)
+    out = run_qk(ctx, cfg, Q, K)
+    full = 0
+    for b in range(B):
+        ref = O.v_step_qk(O.widen(synth.to_numpy(cfg["X"][b])), O.widen(synth.to_numpy(Q[b])), O.widen(synth.to_numpy(K[b])),
+                          float(d) ** -0.5, cls_index=0, vis_begin=1, N=cfg["N"], n_keep=n_keep, lam=cfg["lam"],
+                          eps=cfg["eps"], grid=cfg["grid"], window=2, coef=2.0)
+        full += compare_under_margin_rule(out, b, ref, dtype, 1)
+    return full
+
+
+def test_config0_shape_from_queries_and_keys(ctx):
+    full = _case(ctx, 40, 1, 24, 1024, 16, 64, "f32", 192, 1.0)
+    say("config 0 shape from Q, K: %d of 1 images with every decision identical" % full)
+
+
+def test_config1_shape_from_queries_and_keys(ctx):
+    full = _case(ctx, 41, 16, 24, 1024, 16, 64, "bf16", 384, 1.5)
+    say("config 1 shape from Q, K: %d of 16 images with every decision identical" % full)
+    assert full >= 12          # in-margin decisions are rare
+
+
+@pytest.mark.parametrize("seed,grid,H,d,n_keep", [(1, 7, 3, 32, 20), (2, 16, 5, 32, 100), (3, 19, 2, 128, 301), (4, 25, 4, 64, 625),
+                                                  (5, 5, 1, 64, 1)])
+def test_small_and_ragged_shapes(ctx, seed, grid, H, d, n_keep):
+    full = _case(ctx, 50 + seed, 2, grid, 72, H, d, ["f32", "bf16"][seed % 2], n_keep, 1.0)
+    assert full >= 1
+
+
+def test_unsupported_shapes_are_refused(ctx):
+    cfg = synth.ficoco_v_single(seed=9, B=1, grid=4, D=8, H=1, centres=2, dtype="bf16", n_keep=8)
+    Xd = cfg["X"].to("cuda")
+    for n, d in ((17, 24), (17, 16), (17, 256)):
+        Q = torch.zeros(1, 2, n, d, dtype=torch.bfloat16, device="cuda")
+        p = fc.make_problem(Xd, variant=fc.VARIANT_V, vis_begin=1, N=16, n_keep=8, cls_index=0, grid=(1, 4, 4), window=2,
+                            Q=Q, K=Q.clone())
+        with pytest.raises(fc.FicocoError) as e:
+            fc.workspace_bytes(p)
+        assert e.value.code == fc.EUNSUPPORTED

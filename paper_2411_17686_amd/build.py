@@ -49,5 +49,20 @@ def build(verbose=True, out=LIB, defines=(), tag=""):
     return out
 
 
+def build_c_caller(verbose=True):
+    """The plain-C caller of the ABI (tests/c_abi/step_check.c) as a shared object, with gcc."""
+    root = os.path.dirname(HERE)
+    src = os.path.join(root, "tests", "c_abi", "step_check.c")
+    out = os.path.join(root, "tests", "c_abi", "libstep_check.so")
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    subprocess.check_call(["gcc", "-O1", "-std=c11", "-Wall", "-shared", "-fPIC", "-I", os.path.join(root, "include"),
+                           "-I", os.path.join(rocm, "include"), "-o", out, src, LIB, "-L" + os.path.join(rocm, "lib"),
+                           "-lamdhip64", "-lm", "-Wl,-rpath," + HERE, "-Wl,-rpath," + os.path.join(rocm, "lib")])
+    if verbose:
+        print("built", out)
+    return out
+
+
 if __name__ == "__main__":
     build()
+    build_c_caller()

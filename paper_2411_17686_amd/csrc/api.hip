@@ -30,24 +30,12 @@ namespace ficoco {
 // With the head-mean map to store, a reduction workgroup has at most 8 row lanes and chunks of a
 // multiple of 8 rows (measured at the 576-token batched shape: 8 lanes x 32 rows, ~900 workgroups,
 // gives the best pipelined step; 10 lanes x 24 rows is 10 % slower alone).
-#ifndef FICOCO_MAP_ROW_LANES
-#define FICOCO_MAP_ROW_LANES 8
-#endif
-#ifndef FICOCO_MAP_ROWS_MAX
-#define FICOCO_MAP_ROWS_MAX 32
-#endif
-constexpr int kMapRowLanes = FICOCO_MAP_ROW_LANES;
-#ifndef FICOCO_MAP_ROWS_ALIGN
-#define FICOCO_MAP_ROWS_ALIGN 8
-#endif
-constexpr int kMapRowsAlign = FICOCO_MAP_ROWS_ALIGN;
+constexpr int kMapRowLanes = 8;
+constexpr int kMapRowsAlign = 8;
 // Workgroups the reduction aims at (half of it where the map tile is turned).  Measured: 1024 against
 // 2048 changes nothing at the batched ViT shapes and gives the decoder shape (8 sequences, 32 heads)
 // 32-row chunks instead of 16-row ones, 42.5 against 44.0 us.
-#ifndef FICOCO_WG_TARGET
-#define FICOCO_WG_TARGET 1024
-#endif
-constexpr int64_t kWgTarget = FICOCO_WG_TARGET;
+constexpr int64_t kWgTarget = 1024;
 
 static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
 
@@ -196,7 +184,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
       // The head-mean map is stored transposed, a chunk's rows of one key column as one piece:
       // chunks of a multiple of 8 rows that start at multiples of it, counted from visual row 0,
       // make every piece whole 32-byte sectors.
-      pl.rows_per_wg = std::min((pl.rows_per_wg + kMapRowsAlign - 1) / kMapRowsAlign * kMapRowsAlign, FICOCO_MAP_ROWS_MAX);    // the tile is at most 256 columns x that many rows
+      pl.rows_per_wg = std::min((pl.rows_per_wg + kMapRowsAlign - 1) / kMapRowsAlign * kMapRowsAlign, 32);    // the tile is at most 256 columns x that many rows
       const int lead = (p.vis_begin - p.a_q_begin) - lo;             // role rows before visual row 0 (the [CLS] query)
       pl.a_shift = (pl.rows_per_wg - lead % pl.rows_per_wg) % pl.rows_per_wg;
     }

@@ -16,24 +16,9 @@
 
 namespace ficoco {
 
-#ifndef FICOCO_HEAD_BATCH
-#define FICOCO_HEAD_BATCH 8
-#endif
-constexpr int kHeadBatch = FICOCO_HEAD_BATCH;
-#ifndef FICOCO_REDUCE_HEADS_OUTER
-#define FICOCO_REDUCE_HEADS_OUTER 1
-#endif
+constexpr int kHeadBatch = 8;
 constexpr int kRowsAtOnce = 4;     // rows of one thread whose heads are added side by side ...
-#ifndef FICOCO_REDUCE_HEADS
-#define FICOCO_REDUCE_HEADS 2
-#endif
-constexpr int kHeadsAtOnce = FICOCO_REDUCE_HEADS;    // ... this many heads of each per batch of loads (more where the thread has fewer rows)
-// LDS requested per workgroup at least (bytes): a way to bound how many workgroups of this
-// kernel a compute unit holds (160 KB / request), which leaves wavefront slots for the short
-// kernels of another stream that run next to it.
-#ifndef FICOCO_REDUCE_LDS_MIN
-#define FICOCO_REDUCE_LDS_MIN 0
-#endif
+constexpr int kHeadsAtOnce = 2;    // ... this many heads of each per batch of loads (more where the thread has fewer rows)
 
 struct AttnArgs {
   const void* A;
@@ -59,7 +44,6 @@ struct AttnArgs {
 // raw vectors per thread, and its grids hold about three wavefronts per SIMD anyway.
 template <typename T>
 __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(3))) void attn_reduce_kernel(AttnArgs a) {
-  DBG_SPAN(0);
   extern __shared__ double lds[];
   // Workgroups that read neighbouring strips of the same rows share the cache lines at the
   // strip boundaries: they get consecutive logical ids, which run on the same XCD (one L2).
@@ -113,7 +97,7 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
   };
 
   const int rows_per_thread = (a.rows_per_wg + a.row_lanes - 1) / a.row_lanes;
-  if (FICOCO_REDUCE_HEADS_OUTER && sizeof(T) == 2 && rows_per_thread <= kRowsAtOnce) {     // uniform
+  if (sizeof(T) == 2 && rows_per_thread <= kRowsAtOnce) {     // uniform
     // All rows of this thread at once, heads outermost: a batch is a few heads of each of the
     // thread's rows.  The loads in flight then come from a few rows of one or two head
     // matrices -- neighbouring addresses -- instead of one row of eight matrices 665 KB apart,
@@ -346,7 +330,6 @@ static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hi
   dim3 grid(xcd_padded_total(a.n_chunks * col_strips * B)), block(std::min(kReduceThreads, (a.row_lanes * a.strip_groups + kWave - 1) / kWave * kWave));
   size_t lds = (size_t)a.row_lanes * a.strip_groups * kVec * sizeof(double);
   if (a.abar) lds += (size_t)a.strip_groups * kVec * (a.rows_per_wg + 1) * sizeof(float);   // the tile that is turned
-  if (lds < (size_t)FICOCO_REDUCE_LDS_MIN) lds = FICOCO_REDUCE_LDS_MIN;
   if (bf16)
     hipLaunchKernelGGL(attn_reduce_kernel<bf16_t>, grid, block, lds, s, g);
   else
@@ -399,4 +382,3 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
 
 }  // namespace ficoco
 
-FICOCO_DBG_READER(reduce)

@@ -14,10 +14,7 @@ constexpr int kCandPad = 2048;     // floats of padding behind the approximate c
 constexpr int kGramStage = 32;     // features per K stage of the matrix-core kernel (its K ranges are counted in stages)
 constexpr int kVec = 8;            // elements per lane per load in the streaming kernels
 constexpr int kSelMax = 8;         // order statistics kept in registers by the fast threshold path
-#ifndef FICOCO_REDUCE_THREADS
-#define FICOCO_REDUCE_THREADS 256
-#endif
-constexpr int kReduceThreads = FICOCO_REDUCE_THREADS;
+constexpr int kReduceThreads = 256;
 constexpr int kSelectThreads = 1024;
 constexpr int kMaxSelectN = 12288; // visual tokens / grid cells the per-image select kernel holds in LDS
 
@@ -245,35 +242,6 @@ __device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* to
   __syncthreads();
   return incl + before;
 }
-
-#ifdef FICOCO_DBG_TIMING
-// Tuning aid (never in the product build): thread 0 of every workgroup stores its start and
-// end time on the 100 MHz wall clock; one array per translation unit.
-constexpr int kDbgSlots = 16384;
-static __device__ unsigned long long g_dbg[2 * kDbgSlots];
-struct DbgSpan {
-  unsigned long long t0;
-  __device__ DbgSpan(int) : t0(wall_clock64()) {}
-  __device__ ~DbgSpan() {
-    const int wg = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    if (threadIdx.x == 0 && wg < kDbgSlots) { g_dbg[2 * wg] = t0; g_dbg[2 * wg + 1] = wall_clock64(); }
-  }
-};
-#define DBG_SPAN(k) DbgSpan dbg_span_(k)
-#ifndef FICOCO_DBG_WG
-#define FICOCO_DBG_WG (gridDim.x / 2)
-#endif
-#define DBG_PHASE(i) do { if (blockIdx.x == FICOCO_DBG_WG && blockIdx.y == 0 && threadIdx.x == 0) g_dbg[2 * (kDbgSlots - 16) + (i)] = wall_clock64(); } while (0)
-#define FICOCO_DBG_READER(name) \
-  extern "C" void ficoco_debug_reset_##name(void) { \
-    void* p; (void)hipGetSymbolAddress(&p, HIP_SYMBOL(ficoco::g_dbg)); (void)hipMemset(p, 0, sizeof(unsigned long long) * 2 * ficoco::kDbgSlots); } \
-  extern "C" void ficoco_debug_read_##name(unsigned long long* out) { \
-    (void)hipMemcpyFromSymbol(out, HIP_SYMBOL(ficoco::g_dbg), sizeof(unsigned long long) * 2 * ficoco::kDbgSlots); }
-#else
-#define DBG_SPAN(k)
-#define DBG_PHASE(i)
-#define FICOCO_DBG_READER(name)
-#endif
 
 // Round a double to the nearest bfloat16, ties to even, straight from double (no
 // intermediate float rounding).  The spacing at binary exponent e is 2^(max(e,-126)-7).

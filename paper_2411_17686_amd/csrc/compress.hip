@@ -52,7 +52,6 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   const int n = a.n_keep;
   const int share = (a.n_disc + (int)gridDim.x - 1) / (int)gridDim.x;
   const int r_lo = min((int)blockIdx.x * share, a.n_disc), r_hi = min(r_lo + share, a.n_disc);
-  DBG_PHASE(8);
   for (int j = tid; j <= n; j += nt) cnt[j] = 0;
   for (int j = tid; j < n; j += nt) cursor[j] = 0;
   __syncthreads();
@@ -97,7 +96,6 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
     }
   }
   __syncthreads();
-  DBG_PHASE(9);
   // exclusive scan of cnt[0..n): thread t owns a contiguous slice
   const int per = (n + nt - 1) / nt;
   const int lo = min(tid * per, n), hi = min(lo + per, n);
@@ -113,7 +111,6 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   }
   if (tid == 0) cnt[n] = total;
   __syncthreads();
-  DBG_PHASE(10);
   if (blockIdx.x == 0) {       // uniform over the workgroup
     for (int j = tid; j <= n; j += nt) a.tgt_ptr[b * (n + 1) + j] = cnt[j];
     // targets with long buckets, for the workgroup-per-target pass of the merge
@@ -156,7 +153,6 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
       }
     }
   }
-  DBG_PHASE(11);
 }
 
 struct MergeArgs {
@@ -189,13 +185,7 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
   __builtin_memcpy(dst, &v, sizeof(v));
 }
 
-#ifndef FICOCO_MERGE_SCAN_REGS
-#define FICOCO_MERGE_SCAN_REGS 16   // registers of row data in flight per lane while a scanning-mode list is added
-#endif
-#ifndef FICOCO_MERGE_WAVES
-#define FICOCO_MERGE_WAVES 8
-#endif
-constexpr int kMergeWaves = FICOCO_MERGE_WAVES;    // wavefronts (= output row spans) per workgroup
+constexpr int kMergeWaves = 8;    // wavefronts (= output row spans) per workgroup
 constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
 static_assert(kMatchMaxRows % (kMergeWaves * kWave) == 0, "a workgroup stages the edge table in whole rounds");
 constexpr int kMatchCap = 64;     // scanning mode: sources of one target kept in LDS
@@ -375,7 +365,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   using Lds = MergeLds<MATCH, SLICE, WPU>;
   constexpr int kCap = Lds::kCap;
   constexpr int kSpan = kWave * kVec * SLICE;
-  constexpr int kRegs = (MATCH && WPU == 1) ? FICOCO_MERGE_SCAN_REGS : 32;
+  constexpr int kRegs = (MATCH && WPU == 1) ? 16 : 32;   // registers of row data in flight per lane while a list is added
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int unit_l = wv / WPU, sub = wv % WPU;
   double* l_w = (double*)lds_m + wv * kCap;
@@ -407,7 +397,6 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   // this thread's share of the edge table, then -- once the index is there -- the row itself;
   // the table is put into LDS last.  Each of them is a memory round trip of its own if taken
   // one after the other.
-  DBG_PHASE(0);
   const T* Xb = (const T*)a.X + b * a.xsb;
   T* out = (T*)a.X_out + (b * a.n_out + (valid ? r : 0)) * (int64_t)a.D;
   // (an unconditional load from an address that is always valid: under a condition the compiler
@@ -594,7 +583,6 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
   }
 
-  DBG_PHASE(3);
   // ---- this wavefront's partial sum ----------------------------------------------------------------
   double num[SLICE][kVec];
   double den = sub == 0 ? 1.0 : 0.0;
@@ -661,7 +649,6 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
   }
 
-  DBG_PHASE(4);
   // ---- parts added in order by wavefront 0 of the unit -----------------------------------------------
   if (WPU > 1) {
     if (sub > 0) {
@@ -820,7 +807,6 @@ __device__ __forceinline__ void merge_hub_targets(const MergeArgs& a, char* lds_
 
 template <typename T, bool MATCH, int SLICE, int WPU>
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
-  DBG_SPAN(3);
   extern __shared__ __attribute__((aligned(16))) char lds_m[];
   const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m);
   if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
@@ -912,9 +898,6 @@ __global__ __launch_bounds__(kExtraWaves * kWave) void extra_token_kernel(MergeA
   for (int k = 0; k < nd; ++k) store_token(out + k, acc[k] / cnt);
 }
 
-#ifndef FICOCO_MERGE_SLICE
-#define FICOCO_MERGE_SLICE 0          // 0: chosen per problem
-#endif
 
 template <typename T, bool MATCH, int SLICE, int WPU>
 static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
@@ -976,8 +959,7 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   // the targets with at most kHubMin sources, then a whole workgroup per unit (eight wavefronts,
   // each adding the sources of one part of the discarded rows, parts added in order) for the few
   // targets with long buckets, whose serial row loads would otherwise set the kernel's duration.
-  int slice = FICOCO_MERGE_SLICE;
-  if (slice == 0) slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
+  const int slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
   const bool bf16 = p.dtype == FICOCO_BF16;
   if (match) {
     if (bf16) launch_merge_s<bf16_t, true, 1>(m, p.B, slice, s); else launch_merge_s<float, true, 1>(m, p.B, slice, s);
@@ -1037,4 +1019,3 @@ void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_
 
 }  // namespace ficoco
 
-FICOCO_DBG_READER(merge)

@@ -329,10 +329,7 @@ __global__ __launch_bounds__(256) void text_colmax_kernel(CorrArgs a) {
   }
 }
 
-#ifndef FICOCO_CORR_STEPS
-#define FICOCO_CORR_STEPS 2
-#endif
-constexpr int kCorrSteps = FICOCO_CORR_STEPS;   // 512-feature steps of the exact dot products loaded together
+constexpr int kCorrSteps = 2;   // 512-feature steps of the exact dot products loaded together
 
 // Exact C[i][j_q] for up to CB targets at once, the whole wavefront working on them together
 // (all lanes return the values).  The loads of all CB rows are issued before the first use, so
@@ -419,7 +416,6 @@ constexpr int kCandBatch = 4;                    // targets evaluated exactly at
 // 3456 discarded rows, one wavefront each, and the chip holds 3072 of them at three per SIMD.
 template <int MC>   // lower bounds kept per lane (>= sel_m: one lane may hold the m largest of the row)
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void corr_cand_rows_kernel(CorrArgs a) {
-  DBG_SPAN(2);
   __shared__ int cand_j[4][kCandCap];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
   const int row = blockIdx.x * (blockDim.x / kWave) + wv;
@@ -432,7 +428,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
     return;
   }
-  DBG_PHASE(0);
   // approximate direct term of the row: the matrix-core cosines, or (FiCoCo-L with the
   // attention correlation) the token's row of the exact head-mean map, delta = 0
   const bool from_map = a.mode == kAttnL;
@@ -446,7 +441,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     bd = wave_sum_f64(bd) * a.invM * (1.0 - a.gamma);
     extra = (float)bd * 1.000001f + 1e-30f;   // rounded up
   }
-  DBG_PHASE(1);
   const float delta = from_map ? 0.0f : a.delta;
   const float NEGF = -__builtin_huge_valf();
   const int64_t split_stride = (int64_t)a.B * a.n_disc * n;
@@ -538,7 +532,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     }
   }
   float lambda = NEGF;
-  DBG_PHASE(2);
   for (int r = 0; r < a.sel_m; ++r) {
     float mx = top[0];
 #pragma unroll
@@ -552,7 +545,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     lambda = mx;
   }
   // candidates in ascending target order (a row of one pass is still in registers)
-  DBG_PHASE(3);
   int n_cand = 0;
   for (int c0 = 0; c0 < n; c0 += kCandChunk) {
     if (n > kCandChunk) load_pass(c0);
@@ -574,7 +566,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     return;
   }
   // exact values of the candidates: lane c keeps candidate c
-  DBG_PHASE(4);
   const double NEG = -__builtin_huge_val();
   const int myjj = lane < n_cand ? cand_j[wv][lane] : -1;
   const int myj = myjj >= 0 ? T[myjj] : -1;
@@ -595,7 +586,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
       if (lane == c + q && c + q < n_cand) myv = ok[q] ? v[q] : NEG;
   }
   // v[f], v[f+1] = m-th and (m-1)-th largest of the exact candidate values
-  DBG_PHASE(5);
   double v_f = NEG, v_f1 = NEG;
   int n_gt = 0;
   {
@@ -636,7 +626,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
     if (live && cnt > a.k_max) a.overflow[b] = 1;
   }
-  DBG_PHASE(6);
 }
 
 // ---- FiCoCo-V attention correlation ------------------------------------------------------------
@@ -651,13 +640,9 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
 // registers for the second pass (10 steps: the 576-token grid).  Longer rows take batches of
 // kRowWide steps (measured at 2880 tokens: 16 is as good as 24, and 48 -- the whole row in
 // registers, at a quarter of the resident wavefronts -- is slower).
-#ifndef FICOCO_CORR_WIDE
-#define FICOCO_CORR_WIDE 16
-#endif
-constexpr int kRowWide = FICOCO_CORR_WIDE;
+constexpr int kRowWide = 16;
 template <int MC, int kRowBatch>
 __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
-  DBG_SPAN(2);
   const int lane = threadIdx.x % kWave;
   const int row = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
   const int64_t b = blockIdx.y;
@@ -956,4 +941,3 @@ void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const in
 
 }  // namespace ficoco
 
-FICOCO_DBG_READER(corr)

@@ -21,10 +21,7 @@ constexpr int kGT = 128;           // tile rows = tile columns
 constexpr int kGK = kGramStage;    // K elements per stage (32 measured best at 4096 tokens; 64 halves LDS occupancy)
 constexpr int kGChunks = kGK / 16;  // 16-byte chunks per thread, operand and stage
 constexpr int kGStride = kGK + 8;  // LDS row pitch in elements (row + 16 bytes)
-#ifndef FICOCO_GRAM_STAGES
-#define FICOCO_GRAM_STAGES 2
-#endif
-constexpr int kGStages = FICOCO_GRAM_STAGES;   // K-stages in flight per thread (register ring)
+constexpr int kGStages = 2;   // K-stages in flight per thread (register ring)
 
 struct GramArgs {
   const bf16_t* xhat;  // [B][N][Df]

@@ -709,4 +709,3 @@ void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const doub
 
 }  // namespace ficoco
 
-FICOCO_DBG_READER(select)

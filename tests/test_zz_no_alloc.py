@@ -48,9 +48,9 @@ def test_static_scratch_rejects_a_step_that_does_not_fit():
     cfg = synth.ficoco_v_single(seed=23, B=1, grid=4, D=8, H=1, centres=2, dtype="bf16", n_keep=8)
     p, keep_alive = _problem(cfg)
     buf = fc.Buffers(p, "cuda", keep_alive[0].dtype)
-    # The same pointers described as 40 images of 576 patches: the head-mean map alone is 53 MB.  The
+    # The same pointers described as 200 images of 576 patches: the step would need about 80 MB.  The
     # call must be refused on the host, before any kernel could touch memory that is not there.
-    p.B, p.N, p.n_tot, p.n_keep, p.a_nq, p.a_nk = 40, 576, 577, 384, 577, 577
+    p.B, p.N, p.n_tot, p.n_keep, p.a_nq, p.a_nk = 200, 576, 577, 384, 577, 577
     p.grid_h = p.grid_w = 24
     p.a_stride_q, p.a_stride_h, p.a_stride_b = 577, 577 * 577, 577 * 577
     p.x_stride_n, p.x_stride_b = p.D, 577 * p.D

@@ -910,8 +910,16 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   if (pl.use_gram) {
     GramArgs g{a.xhat, p.B, p.N, pl.Df, pl.n_disc, p.n_keep, discard_idx, keep_idx, a.ct, pl.gram_splits, pl.gram_st_per_split};
     const int tiles = pl.gram_splits * p.B * ((pl.n_disc + kGT - 1) / kGT) * ((p.n_keep + kGT - 1) / kGT);
+    // large blocks (one K range, enough 256 x 192 tiles for most of the chip): the wide-tile form
+    const int tiles2 = p.B * ((pl.n_disc + kG2M - 1) / kG2M) * ((p.n_keep + kG2N - 1) / kG2N);
+    const bool wide = pl.gram_splits == 1 && tiles2 >= 128;
     if (gram_start) (void)hipEventRecord(gram_start, s);
-    hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
+    if (wide) {
+      const size_t lds = (size_t)2 * (kG2M + kG2N) * kG2Chunks * sizeof(uint4);
+      (void)hipFuncSetAttribute((const void*)gram_tile2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+      hipLaunchKernelGGL(gram_tile2_kernel, dim3(xcd_padded_total(tiles2)), dim3(kG2Threads), lds, s, g);
+    }
+    else hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);
     if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     launch_cand_rows(pl.sel_m, grid, block, s, a);

@@ -334,18 +334,7 @@ struct MergeLds {
   static size_t bytes(int n_disc) { return kLists + kPartDoubles * 8 + kDen + (MATCH ? (size_t)n_disc * 32 : 0); }
 };
 
-// Tokens outside the visual span (and behind the additional token of the convergent form), in
-// sequence order: p-th such token -> its output row r and its input row t.
-struct PassRow { int r, t; };
-__device__ __forceinline__ PassRow pass_row(const MergeArgs& a, int p) {
-  const int extra = a.extra_row >= 0 ? 1 : 0;
-  PassRow o;
-  o.r = p < a.vis_begin ? p : p + a.n_keep + extra;
-  o.t = p < a.vis_begin ? p : o.r + a.n_disc - extra;
-  return o;
-}
-
-// One UNIT = (preserved visual token, feature span of 512 * SLICE).  Rows without sources, and every token
+// One UNIT = (output row, feature span of 512 * SLICE).  Rows without sources, and every token
 // outside the visual span, are copied.  A unit is served by WPU wavefronts: wavefront w takes
 // the sources whose discarded row lies in the w-th part of [0, n_disc), adds them in ascending
 // row order in double precision, and the parts are then added in order by wavefront 0
@@ -376,11 +365,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   const int n_spans = (a.D + kSpan - 1) / kSpan;
   const int unit = blockIdx.x * Lds::kUnits + unit_l;
   const int64_t b = blockIdx.y;
-  // The grid covers the preserved visual tokens only: unit -> (preserved token, feature span).  Rows
-  // outside the visual span are plain copies that need no index: they are dealt out to the
-  // wavefronts of the same grid as a second duty (copy_passthrough_rows), so that the grid of
-  // the batched ViT shape fits the chip in one round.
-  int r = a.vis_begin + unit / n_spans;
+  int r = unit / n_spans;
   const int d0 = (unit % n_spans) * kSpan;
   if (WPU > 1) {
     // workgroup-per-target pass: unit -> entry of the list of long buckets (one unit per
@@ -391,7 +376,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     if (h >= n_hub) return 0;
     r = a.vis_begin + min(max(a.hub_list[b * a.n_keep + h], 0), a.n_keep - 1);
   }
-  const bool valid = r < a.vis_begin + a.n_keep;
+  const bool valid = r < a.n_out && r != a.extra_row;   // the additional token is written by extra_token_kernel
 
   // Order of the loads below: the row's token index first (its own row depends on it), then
   // this thread's share of the edge table, then -- once the index is there -- the row itself;
@@ -399,27 +384,11 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   // one after the other.
   const T* Xb = (const T*)a.X + b * a.xsb;
   T* out = (T*)a.X_out + (b * a.n_out + (valid ? r : 0)) * (int64_t)a.D;
+  const bool kept_row = valid && r >= a.vis_begin && r < a.vis_begin + a.n_keep;
   // (an unconditional load from an address that is always valid: under a condition the compiler
   // moves the first use of the value next to the load and waits for it there)
   const int32_t* tok_at = a.n_keep > 0 ? a.T + b * a.n_keep + min(max(r - a.vis_begin, 0), a.n_keep - 1) : &g_no_token;
   int tok = *tok_at;
-  // Second duty: one (row, span) of the tokens outside the visual span, copied as it is.  Its load
-  // goes out now and is stored once the loads issued after it have come back.  Always a load from
-  // a valid address (row 0 where this wavefront has no such duty), never a branch around it.
-  const int n_pass_units = (a.n_out - a.n_keep - (a.extra_row >= 0 ? 1 : 0)) * n_spans;
-  const int pass_q = blockIdx.x * kMergeWaves + wv;
-  const bool has_pass = WPU == 1 && pass_q < n_pass_units;
-  const PassRow pr = pass_row(a, has_pass ? pass_q / n_spans : 0);
-  const int pass_d0 = has_pass ? (pass_q % n_spans) * kSpan : 0;
-  Raw8<T> cp[SLICE];
-  if (WPU == 1) {
-    const T* src = Xb + (int64_t)(has_pass ? pr.t : 0) * a.xsn;
-#pragma unroll
-    for (int u = 0; u < SLICE; ++u) {
-      const int d = pass_d0 + (u * kWave + lane) * kVec;
-      load_raw(src + (has_pass && d + kVec <= a.D ? d : 0), cp[u]);
-    }
-  }
   constexpr int kStage = MATCH ? kMatchMaxRows / (kMergeWaves * kWave) : 1;   // edge-table rows per thread
   int st_cnt[kStage], st_src[kStage], st_t0[kStage], st_t1[kStage];
   double st_a0[kStage], st_a1[kStage];
@@ -441,13 +410,19 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
 
   int t = 0, j = -1, e0 = 0, e1 = 0;
   if (valid) {
-    j = r - a.vis_begin;
-    tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
-    t = a.vis_begin + tok;
-    if (!MATCH && a.n_disc > 0) {
-      // bucket bounds are device data: keep them inside the image's edge storage
-      e0 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j], 0), a.n_disc * a.k_max);
-      e1 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j + 1], e0), a.n_disc * a.k_max);
+    if (r < a.vis_begin) {
+      t = r;
+    } else if (kept_row) {
+      j = r - a.vis_begin;
+      tok = min(max(tok, 0), a.N - 1);   // index sets are device data: stay inside the span
+      t = a.vis_begin + tok;
+      if (!MATCH && a.n_disc > 0) {
+        // bucket bounds are device data: keep them inside the image's edge storage
+        e0 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j], 0), a.n_disc * a.k_max);
+        e1 = min(max(a.tgt_ptr[b * (a.n_keep + 1) + j + 1], e0), a.n_disc * a.k_max);
+      }
+    } else {
+      t = r + a.n_disc - (a.extra_row >= 0 ? 1 : 0);
     }
   }
   const T* x = Xb + (int64_t)t * a.xsn;
@@ -478,18 +453,6 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
     }
   }
   if (MATCH) __syncthreads();   // the edge table is complete (every wavefront arrives here)
-  if (has_pass) {               // uniform over the wavefront
-    T* dst = (T*)a.X_out + (b * a.n_out + pr.r) * (int64_t)a.D;
-    const T* src = Xb + (int64_t)pr.t * a.xsn;
-#pragma unroll
-    for (int u = 0; u < SLICE; ++u) {
-      const int d = pass_d0 + (u * kWave + lane) * kVec;
-      if (d + kVec <= a.D) __builtin_memcpy(dst + d, &cp[u], sizeof(cp[u]));
-      else
-        for (int k = 0; k < kVec; ++k)
-          if (d + k < a.D) dst[d + k] = src[d + k];
-    }
-  }
   if (WPU == 1 && !valid) return 0;
 
   // this wavefront's part of the discarded rows
@@ -730,8 +693,8 @@ __device__ __forceinline__ void merge_hub_targets(const MergeArgs& a, char* lds_
   for (int u = 0; u < kMergeWaves; ++u) {
     if (hub_n[u] == 0) continue;                         // uniform over the workgroup
     const int unit = blockIdx.x * kMergeWaves + u;
-    const int j = unit / n_spans;                        // a deferred unit is a preserved visual token
-    const int r = a.vis_begin + j;
+    const int r = unit / n_spans;
+    const int j = r - a.vis_begin;                       // a deferred unit is a preserved visual row
     const int dl = (unit % n_spans) * kSpan + (wv * kWave + lane) * SLICE;
     const bool whole = dl + SLICE <= a.D;
     const int tok = min(max(a.T[b * a.n_keep + j], 0), a.N - 1);
@@ -810,36 +773,16 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   extern __shared__ __attribute__((aligned(16))) char lds_m[];
   const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m);
   if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
-  constexpr int kSpan = kWave * kVec * SLICE;
-  const int n_spans = (a.D + kSpan - 1) / kSpan;
-  const int64_t b = blockIdx.y;
-  if (WPU == 1) {
-    // Tokens outside the visual span beyond one (row, span) per wavefront of the grid -- a long text
-    // behind few preserved tokens -- are copied here, plainly.
-    const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-    const int n_pass_units = (a.n_out - a.n_keep - (a.extra_row >= 0 ? 1 : 0)) * n_spans;
-    const int n_waves = (int)gridDim.x * kMergeWaves;
-    const T* Xb = (const T*)a.X + b * a.xsb;
-    for (int q = blockIdx.x * kMergeWaves + wv + n_waves; q < n_pass_units; q += n_waves) {
-      const PassRow pr = pass_row(a, q / n_spans);
-      const T* src = Xb + (int64_t)pr.t * a.xsn;
-      T* dst = (T*)a.X_out + (b * a.n_out + pr.r) * (int64_t)a.D;
-#pragma unroll
-      for (int u = 0; u < SLICE; ++u) {
-        const int d = (q % n_spans) * kSpan + (u * kWave + lane) * kVec;
-        if (d + kVec <= a.D) copy8<T>(src + d, dst + d);
-        else
-          for (int k = 0; k < kVec; ++k)
-            if (d + k < a.D) dst[d + k] = src[d + k];
-      }
-    }
-  }
-  // position ids of the preserved tokens: written last, by one thread per preserved token of the
+  // position ids of the preserved tokens: written last, by one thread per output row of the
   // workgroup (two dependent loads that nothing above should wait for)
   if (WPU == 1 && a.pos_out && (int)threadIdx.x < kMergeWaves) {
+    constexpr int kSpan = kWave * kVec * SLICE;
+    const int n_spans = (a.D + kSpan - 1) / kSpan;
     const int unit = blockIdx.x * kMergeWaves + threadIdx.x;
-    const int j = unit / n_spans;
-    if (unit % n_spans == 0 && j < a.n_keep) {
+    const int r = unit / n_spans;
+    const int64_t b = blockIdx.y;
+    if (unit % n_spans == 0 && r >= a.vis_begin && r < a.vis_begin + a.n_keep) {
+      const int j = r - a.vis_begin;
       const int tok = min(max(a.T[b * a.n_keep + j], 0), a.N - 1);
       a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
     }
@@ -905,7 +848,7 @@ static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
   constexpr int kSpan = kWave * kVec * SLICE;
   const int n_spans = (m.D + kSpan - 1) / kSpan;
   const size_t lds = Lds::bytes(m.n_disc);
-  const int units = m.n_keep * n_spans;   // preserved visual tokens (long-bucket pass: at most every one of them)
+  const int units = (WPU > 1 ? m.n_keep : m.n_out) * n_spans;   // long-bucket pass: at most every preserved token
   dim3 grid((units + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
   if (lds > 32768)
     (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, MATCH, SLICE, WPU>,

@@ -296,7 +296,7 @@ __device__ __forceinline__ void exact_terms_of(const SelectArgs& a, int64_t b, c
 
 // EXACT: the instantiation for problems with a cosine-derived score term (the re-evaluation code
 // costs registers that the common instantiation does not pay).
-template <bool EXACT>
+template <bool EXACT, typename TF>     // TF: storage type of the features (EXACT only)
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   extern __shared__ double lds_d[];
   double* s = lds_d;                                   // [N] scores, then keys in place
@@ -486,10 +486,28 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       if (a.n_disc > 0) {
         radix_select_kstar(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
         if (a.n_disc < N) {          // with every token discarded there is no cut to be on a side of
+          // Tokens more than twice the bound above the N^S-th largest score are discarded whatever
+          // the exact values are, tokens more than that below it are preserved; the others share
+          // the places that are left.  Only if those places are fewer than these tokens (and more
+          // than none) does it matter how they rank among themselves: then they are re-evaluated.
           const double cut = key_score(kstar);
+          if (tid == 0) { bcast[5] = 0; bcast[6] = 0; }
+          __syncthreads();
+          int n_above = 0, n_band = 0;
           for (int i = tid; i < N; i += nt) {
             const double d = key_score(keys[i]) - cut;
-            if ((d < 0.0 ? -d : d) <= 2.0 * delta_p && mark_exact(i)) ex_list[atomicAdd(&bcast[4], 1)] = i;
+            n_above += d > 2.0 * delta_p ? 1 : 0;
+            n_band += (d < 0.0 ? -d : d) <= 2.0 * delta_p ? 1 : 0;
+          }
+          if (n_above) atomicAdd(&bcast[5], n_above);
+          if (n_band) atomicAdd(&bcast[6], n_band);
+          __syncthreads();
+          const int places = a.n_disc - bcast[5];
+          if (places > 0 && places < bcast[6]) {          // uniform
+            for (int i = tid; i < N; i += nt) {
+              const double d = key_score(keys[i]) - cut;
+              if ((d < 0.0 ? -d : d) <= 2.0 * delta_p && mark_exact(i)) ex_list[atomicAdd(&bcast[4], 1)] = i;
+            }
           }
         }
       }
@@ -497,10 +515,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       const int n_flag = bcast[4];
       keys_ready = true;
       if (n_flag == 0 || pass == 3) break;
-      if constexpr (EXACT) {
-        if (a.dtype == FICOCO_BF16) exact_terms_of<bf16_t>(a, b, ex_list, n_flag, pass == 0);
-        else exact_terms_of<float>(a, b, ex_list, n_flag, pass == 0);
-      }
+      if constexpr (EXACT) exact_terms_of<TF>(a, b, ex_list, n_flag, pass == 0);
       keys_ready = false;
     }
   } else {
@@ -688,14 +703,15 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.overflow = overflow;
   const size_t lds = select_lds(p, penalty);
   const bool exact = a.exact_r || a.exact_g;
-  if (lds > 32768)
-    (void)hipFuncSetAttribute(exact ? (const void*)select_kernel<true> : (const void*)select_kernel<false>,
-                              hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  const void* kern = !exact ? (const void*)select_kernel<false, float>
+                   : p.dtype == FICOCO_BF16 ? (const void*)select_kernel<true, bf16_t> : (const void*)select_kernel<true, float>;
+  if (lds > 32768) (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   // Short sequences: no more wavefronts than tokens need (every barrier of the kernel waits for
   // all of them); at least 256 threads, which the histogram walk assumes.
   const int threads = p.N >= kSelectThreads ? kSelectThreads : std::max(256, (p.N + kWave - 1) / kWave * kWave);
-  if (exact) hipLaunchKernelGGL(select_kernel<true>, dim3(p.B), dim3(threads), lds, s, a);
-  else hipLaunchKernelGGL(select_kernel<false>, dim3(p.B), dim3(threads), lds, s, a);
+  if (!exact) hipLaunchKernelGGL((select_kernel<false, float>), dim3(p.B), dim3(threads), lds, s, a);
+  else if (p.dtype == FICOCO_BF16) hipLaunchKernelGGL((select_kernel<true, bf16_t>), dim3(p.B), dim3(threads), lds, s, a);
+  else hipLaunchKernelGGL((select_kernel<true, float>), dim3(p.B), dim3(threads), lds, s, a);
 }
 
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {

@@ -81,6 +81,11 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
 constexpr int kQkTile = 48;        // query rows per workgroup of the query/key form
 constexpr int kQkMaxKeys = 640;    // keys it holds in registers
 void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+// FiCoCo-L with 32 or more text queries: the fused step forms the column maxima of the text
+// profiles in the score stage's launch (select.hip), and its correlate stage does not.
+inline bool text_stats_in_score(const ficoco_problem& p) {
+  return p.variant == FICOCO_VARIANT_L && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 32;
+}
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s);
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s);
@@ -89,7 +94,7 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
                    hipStream_t s);
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
+                      double* edge_alpha, int32_t* overflow, bool fused,
                       hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s);
 void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_idx, const void* in,
                    int64_t sb, int64_t sn, int row_bytes, void* out, hipStream_t s);

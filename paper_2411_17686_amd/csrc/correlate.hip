@@ -857,10 +857,13 @@ static void launch_cand_rows(int sel_m, dim3 grid, dim3 block, hipStream_t s, co
 
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
-                      double* edge_alpha, int32_t* overflow, bool overflow_is_zero,
+                      double* edge_alpha, int32_t* overflow, bool fused,
                       hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s) {
-  if (!overflow_is_zero)
+  // fused: called from a fused step, whose filter stage cleared the overflow flags and whose
+  // score stage formed the column maxima of the text profiles (text_stats_in_score)
+  if (!fused)
     hipLaunchKernelGGL(zero_i32_kernel, dim3((p.B + 255) / 256), dim3(256), 0, s, overflow, p.B);
+  const bool need_colmax = !(fused && text_stats_in_score(p));
   if (pl.n_disc == 0) return;
   if (pl.fixed_k == 0) {       // pruning / convergent form: no discarded token has a target
     const int n = p.B * pl.n_disc;
@@ -903,7 +906,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     return;
   }
   if (a.mode == kAttnL && !pl.dense_rows && p.k_max <= 64) {
-    hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
+    if (need_colmax) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     launch_cand_rows(pl.sel_m, grid, block, s, a);
     return;
   }
@@ -921,7 +924,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     }
     else hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);
-    if (L) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
+    if (L && need_colmax) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     launch_cand_rows(pl.sel_m, grid, block, s, a);
     return;
   }

@@ -105,9 +105,14 @@ __device__ __forceinline__ double key_score(uint64_t k) {       // inverse of sc
 // Radix select of the n_disc-th largest key (n_disc >= 1): 8 passes over the key bytes, most
 // significant first.  Returns K* and how many of the tokens with key == K* belong to the n_disc
 // largest (lowest indices first).  Called by every thread of the workgroup.
+// OPAQUE: the thread index is taken through an opaque move, so that the addresses derived from it
+// are formed here and not ahead of a loop around the call (where they would occupy registers).
+template <bool OPAQUE>
 __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, int n_disc, int* hist, int* bcast,
                                                    int* hist_wide, uint64_t& kstar_out, int& need_out) {
-  const int tid = threadIdx.x, nt = blockDim.x;
+  int tid = threadIdx.x;
+  if constexpr (OPAQUE) asm volatile("" : "+v"(tid));
+  const int nt = blockDim.x;
   uint64_t kstar = 0;
   int need = n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
   uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
@@ -217,9 +222,15 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
 // window, side of the top-K cut -- lies within the error bound are evaluated again here, operation
 // for operation as defined; their values then rank exactly.  Rare on real data, slow, and bounded.
 template <typename T>
-__device__ __forceinline__ void exact_terms_of(const SelectArgs& a, int64_t b, const int32_t* list, int n_list, bool first) {
+__device__ __forceinline__ void exact_terms_of(const SelectArgs& a, int b_in, const int32_t* list, int n_list, bool first) {
 #pragma clang fp contract(off)
-  const int tid = threadIdx.x, nt = blockDim.x;
+  // Opaque copies of the image and thread index: nothing below can then be computed ahead of
+  // this point, in the registers of the code that runs for every problem.
+  int b32 = b_in, tid = threadIdx.x;
+  asm volatile("" : "+s"(b32));
+  asm volatile("" : "+v"(tid));
+  const int64_t b = b32;
+  const int nt = blockDim.x;
   const int N = a.N, Df = a.Df;
   const T* Fb = (const T*)a.F + b * a.fsb;
   double* enrm = a.ex_nrm + b * N;
@@ -361,8 +372,13 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   bool keys_ready = false;  // uniform
   if (a.do_score) {
     for (int pass = 0;; ++pass) {
+      // Image and thread index go through an opaque move once per pass: the addresses below would
+      // otherwise count as invariant across passes and be kept in registers around the whole
+      // loop (dozens of them), which pushed the exact instantiation into scratch memory.
+      int bq = b, tq = tid;
+      if constexpr (EXACT) { asm volatile("" : "+s"(bq)); asm volatile("" : "+v"(tq)); }
       if (exact_mode) {
-        if (tid == 0) bcast[4] = 0;
+        if (tq == 0) bcast[4] = 0;
         __syncthreads();
       }
       // Both terms one stored value per token, and several tokens per thread: all of the thread's
@@ -376,26 +392,26 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
         double r[kTokensPerThread], g[kTokensPerThread];
 #pragma unroll
         for (int u = 0; u < kTokensPerThread; ++u) {
-          const int i = min(tid + u * nt, N - 1);          // clamped: always a valid address
-          r[u] = r_one[(int64_t)b * N + i];
-          g[u] = g_one[(int64_t)b * N + i];
+          const int i = min(tq + u * nt, N - 1);          // clamped: always a valid address
+          r[u] = r_one[(int64_t)bq * N + i];
+          g[u] = g_one[(int64_t)bq * N + i];
         }
         issue_fence();
 #pragma unroll
         for (int u = 0; u < kTokensPerThread; ++u) {
-          const int i = tid + u * nt;
+          const int i = tq + u * nt;
           if (i < N) s[i] = combine_terms(a.w, a.red_src == FICOCO_R_ATTN_RECV ? (0.0 + r[u]) / (double)N : r[u], g[u]);
         }
       }
-      for (int i = tid; i < (one_each ? 0 : N); i += nt) {
+      for (int i = tq; i < (one_each ? 0 : N); i += nt) {
         double R, G;
         // the [CLS] term's load goes out first and is in flight together with the partials below
-        const double g_cls = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls[(int64_t)b * N + i] : 0.0;
+        const double g_cls = a.sem_src == FICOCO_G_CLS_ATTN ? a.cls[(int64_t)bq * N + i] : 0.0;
         if (a.red_src == FICOCO_R_ATTN_RECV) {
           // Column partials of the row chunks, added in chunk order.  32 loads are issued together
           // (one trip to memory per 32 chunks): past the last chunk the last one is loaded again and
           // counted as zero, so that the batch stays straight-line code.
-          const double* p = a.recv_part + (int64_t)b * a.n_chunks * N + i;
+          const double* p = a.recv_part + (int64_t)bq * a.n_chunks * N + i;
           double acc = 0.0;
           for (int c = 0; c < a.n_chunks; c += 32) {
             double v[32];
@@ -407,14 +423,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           }
           R = acc / (double)N;
         } else if (a.red_src == FICOCO_R_VECTOR) {
-          R = vec_head_mean(a.recv_vec, a.dtype, b, a.H, N, i);
+          R = vec_head_mean(a.recv_vec, a.dtype, bq, a.H, N, i);
         } else {
-          R = a.fterm_r[(int64_t)b * N + i];
+          R = a.fterm_r[(int64_t)bq * N + i];
         }
         if (a.sem_src == FICOCO_G_CLS_ATTN) {
           G = g_cls;
         } else if (a.sem_src == FICOCO_G_TEXT_ATTN) {
-          const double* p = a.ttext + ((int64_t)b * N + i) * a.M;
+          const double* p = a.ttext + ((int64_t)bq * N + i) * a.M;
           double acc = 0.0;
           int k = 0;
           for (; k + 16 <= a.M; k += 16) {                  // 16 independent loads, added in order
@@ -427,25 +443,25 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           for (; k < a.M; ++k) acc += p[k];
           G = acc / (double)a.M;
         } else if (a.sem_src == FICOCO_G_VECTOR) {
-          G = vec_head_mean(a.sem_vec, a.dtype, b, a.H, N, i);
+          G = vec_head_mean(a.sem_vec, a.dtype, bq, a.H, N, i);
         } else {
-          G = a.fterm_g[(int64_t)b * N + i];
+          G = a.fterm_g[(int64_t)bq * N + i];
         }
         s[i] = combine_terms(a.w, R, G);
       }
       if (a.window > 0) {
         const int cells = a.grid_g * a.grid_h * a.grid_w;
-        for (int c = tid; c < cells; c += nt) owner[c] = -1;
+        for (int c = tq; c < cells; c += nt) owner[c] = -1;
         __syncthreads();
-        for (int i = tid; i < N; i += nt) {
-          const int c = a.pos ? a.pos[(int64_t)b * N + i] : i;
+        for (int i = tq; i < N; i += nt) {
+          const int c = a.pos ? a.pos[(int64_t)bq * N + i] : i;
           if (c >= 0 && c < cells) owner[c] = i;
         }
         __syncthreads();
         const int W = a.window;
         const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
         const int n_win = a.grid_g * wr * wc;
-        for (int w = tid; w < n_win; w += nt) {
+        for (int w = tq; w < n_win; w += nt) {
           const int sub = w / (wr * wc), rem = w % (wr * wc);
           const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
           int best = -1;
@@ -477,24 +493,24 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
         }
       }
       __syncthreads();
-      for (int i = tid; i < N; i += nt) a.scores[(int64_t)b * N + i] = s[i];
+      for (int i = tq; i < N; i += nt) a.scores[(int64_t)bq * N + i] = s[i];
       if (!exact_mode) break;
       // the side of the top-K cut: tokens within the bound of the N^S-th largest score
       __syncthreads();
-      for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
+      for (int i = tq; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
       __syncthreads();
       if (a.n_disc > 0) {
-        radix_select_kstar(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
+        radix_select_kstar<EXACT>(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
         if (a.n_disc < N) {          // with every token discarded there is no cut to be on a side of
           // Tokens more than twice the bound above the N^S-th largest score are discarded whatever
           // the exact values are, tokens more than that below it are preserved; the others share
           // the places that are left.  Only if those places are fewer than these tokens (and more
           // than none) does it matter how they rank among themselves: then they are re-evaluated.
           const double cut = key_score(kstar);
-          if (tid == 0) { bcast[5] = 0; bcast[6] = 0; }
+          if (tq == 0) { bcast[5] = 0; bcast[6] = 0; }
           __syncthreads();
           int n_above = 0, n_band = 0;
-          for (int i = tid; i < N; i += nt) {
+          for (int i = tq; i < N; i += nt) {
             const double d = key_score(keys[i]) - cut;
             n_above += d > 2.0 * delta_p ? 1 : 0;
             n_band += (d < 0.0 ? -d : d) <= 2.0 * delta_p ? 1 : 0;
@@ -504,7 +520,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
           __syncthreads();
           const int places = a.n_disc - bcast[5];
           if (places > 0 && places < bcast[6]) {          // uniform
-            for (int i = tid; i < N; i += nt) {
+            for (int i = tq; i < N; i += nt) {
               const double d = key_score(keys[i]) - cut;
               if ((d < 0.0 ? -d : d) <= 2.0 * delta_p && mark_exact(i)) ex_list[atomicAdd(&bcast[4], 1)] = i;
             }
@@ -515,7 +531,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       const int n_flag = bcast[4];
       keys_ready = true;
       if (n_flag == 0 || pass == 3) break;
-      if constexpr (EXACT) exact_terms_of<TF>(a, b, ex_list, n_flag, pass == 0);
+      if constexpr (EXACT) exact_terms_of<TF>(a, bq, ex_list, n_flag, pass == 0);
       keys_ready = false;
     }
   } else {
@@ -527,7 +543,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
     __syncthreads();
     for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
     __syncthreads();
-    if (a.n_disc > 0) radix_select_kstar(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
+    if (a.n_disc > 0) radix_select_kstar<EXACT>(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
   }
   // need = how many tokens with key == kstar are discarded (lowest indices first)
 
@@ -613,18 +629,49 @@ __global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec,
 // fixed tree), so the per-image workgroup of select_kernel reads one value.  A thread of that
 // workgroup walking its token's profile touches a cache line per lane and load, all on one
 // compute unit (64 queries: 17 us for the select kernel against 9 + 4 us this way).
-__global__ __launch_bounds__(256) void text_mean_kernel(const double* __restrict__ ttext, int N, int M,
-                                                        double* __restrict__ out_g) {
-  const int lane = threadIdx.x % kWave;
-  const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+// In the fused step the same launch also forms cmax[b][k], the maximum over the visual tokens of
+// profile entry k (the bound of Eq. 4's indirect term that the correlate stage needs): the
+// workgroups behind the first `mean_blocks` take 64 text queries of one image each, thread
+// (k, g) walking the tokens g, g + 4, ... with 16 independent loads per round, the four token
+// groups meeting in LDS.  Both are short chains of dependent loads on few workgroups; in one
+// launch they overlap instead of following each other.
+__global__ __launch_bounds__(256) void text_stats_kernel(const double* __restrict__ ttext, int N, int M,
+                                                         double* __restrict__ out_g, double* __restrict__ cmax,
+                                                         int mean_blocks) {
+  __shared__ double part[256];
   const int64_t b = blockIdx.y;
-  if (i >= N) return;      // whole wavefront leaves together
-  const double* p = ttext + (b * N + i) * M;
-  double acc = 0.0;
-  for (int k = lane; k < M; k += kWave) acc += p[k];
+  if ((int)blockIdx.x < mean_blocks) {
+    const int lane = threadIdx.x % kWave;
+    const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
+    if (i >= N) return;      // whole wavefront leaves together
+    const double* p = ttext + (b * N + i) * M;
+    double acc = 0.0;
+    for (int k = lane; k < M; k += kWave) acc += p[k];
 #pragma unroll
-  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-  if (lane == 0) out_g[b * N + i] = acc / (double)M;
+    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
+    if (lane == 0) out_g[b * N + i] = acc / (double)M;
+    return;
+  }
+  const int tid = threadIdx.x;
+  const int k = ((int)blockIdx.x - mean_blocks) * 64 + tid % 64, g = tid / 64;
+  double mx = 0.0;
+  if (k < M) {
+    int i = g;
+    for (; i + 4 * 15 < N; i += 4 * 16) {              // 16 independent loads per round
+      double v[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) v[u] = ttext[(b * N + i + 4 * u) * M + k];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) mx = v[u] > mx ? v[u] : mx;
+    }
+    for (; i < N; i += 4) { const double v = ttext[(b * N + i) * M + k]; mx = v > mx ? v : mx; }
+  }
+  part[tid] = mx;
+  __syncthreads();
+  if (g == 0 && k < M) {
+    for (int q = 1; q < 4; ++q) mx = part[q * 64 + tid] > mx ? part[q * 64 + tid] : mx;
+    cmax[b * M + k] = mx;
+  }
 }
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
@@ -664,9 +711,12 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
     if (vg) a.sem_src = FICOCO_G_EQ_TOKEN;
   }
   if (do_score && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 32) {
-    // the equivalent-token buffer is free in FiCoCo-L
-    hipLaunchKernelGGL(text_mean_kernel, dim3((p.N + 3) / 4, p.B), dim3(256), 0, s, a.ttext, p.N, p.M,
-                       (double*)(ws + pl.fterm2));
+    // the equivalent-token buffer is free in FiCoCo-L; the column maxima ride along in the fused
+    // step (text_stats_in_score), a staged correlate call forms them itself
+    const bool with_cmax = do_filter && text_stats_in_score(p);
+    const int mean_blocks = (p.N + 3) / 4;
+    hipLaunchKernelGGL(text_stats_kernel, dim3(mean_blocks + (with_cmax ? (p.M + 63) / 64 : 0), p.B), dim3(256), 0, s,
+                       a.ttext, p.N, p.M, (double*)(ws + pl.fterm2), (double*)(ws + pl.cmax), mean_blocks);
     a.sem_src = FICOCO_G_EQ_TOKEN;             // "read the precomputed term"
   }
   if (do_score && (p.red_src == FICOCO_R_SIM_MEAN || p.sem_src == FICOCO_G_EQ_TOKEN)) {

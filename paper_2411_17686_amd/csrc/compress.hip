@@ -350,7 +350,7 @@ struct MergeLds {
 // Returns the number of sources of a target that is left to the whole workgroup (scanning
 // mode, more than kHubMin sources), else 0.
 template <typename T, bool MATCH, int SLICE, int WPU>
-__device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
+__device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m, int blk) {
   using Lds = MergeLds<MATCH, SLICE, WPU>;
   constexpr int kCap = Lds::kCap;
   constexpr int kSpan = kWave * kVec * SLICE;
@@ -363,7 +363,7 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m) {
   double* wden = part + Lds::kPartDoubles;                       // [kMergeWaves][2]: partial denominator, source count
   const EdgeTable tb = edge_table(lds_m + Lds::kLists + Lds::kPartDoubles * 8 + Lds::kDen, a.n_disc);
   const int n_spans = (a.D + kSpan - 1) / kSpan;
-  const int unit = blockIdx.x * Lds::kUnits + unit_l;
+  const int unit = blk * Lds::kUnits + unit_l;      // blk: index of this workgroup among those of its pass
   const int64_t b = blockIdx.y;
   int r = unit / n_spans;
   const int d0 = (unit % n_spans) * kSpan;
@@ -768,17 +768,14 @@ __device__ __forceinline__ void merge_hub_targets(const MergeArgs& a, char* lds_
   }
 }
 
-template <typename T, bool MATCH, int SLICE, int WPU>
-__global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
-  extern __shared__ __attribute__((aligned(16))) char lds_m[];
-  const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m);
-  if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
-  // position ids of the preserved tokens: written last, by one thread per output row of the
-  // workgroup (two dependent loads that nothing above should wait for)
-  if (WPU == 1 && a.pos_out && (int)threadIdx.x < kMergeWaves) {
+// Position ids of the preserved tokens: written last, by one thread per output row of the
+// workgroup (two dependent loads that nothing before should wait for).
+template <int SLICE>
+__device__ __forceinline__ void write_pos_out(const MergeArgs& a, int blk) {
+  if (a.pos_out && (int)threadIdx.x < kMergeWaves) {
     constexpr int kSpan = kWave * kVec * SLICE;
     const int n_spans = (a.D + kSpan - 1) / kSpan;
-    const int unit = blockIdx.x * kMergeWaves + threadIdx.x;
+    const int unit = blk * kMergeWaves + threadIdx.x;
     const int r = unit / n_spans;
     const int64_t b = blockIdx.y;
     if (unit % n_spans == 0 && r >= a.vis_begin && r < a.vis_begin + a.n_keep) {
@@ -786,6 +783,29 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
       const int tok = min(max(a.T[b * a.n_keep + j], 0), a.N - 1);
       a.pos_out[b * a.n_keep + j] = a.pos ? a.pos[b * a.N + tok] : tok;
     }
+  }
+}
+
+template <typename T, bool MATCH, int SLICE, int WPU>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeArgs a) {
+  extern __shared__ __attribute__((aligned(16))) char lds_m[];
+  const int deferred = merge_unit<T, MATCH, SLICE, WPU>(a, lds_m, blockIdx.x);
+  if (MATCH && WPU == 1) merge_hub_targets<T, SLICE>(a, lds_m, deferred);
+  if (WPU == 1) write_pos_out<SLICE>(a, blockIdx.x);
+}
+
+// Bucket mode, both passes in one launch: the first `hub_blocks` workgroups take one target with a
+// long bucket each (most of them find the list of such targets shorter than their index and
+// leave at once), the others eight units of the one-wavefront pass.  The long targets start
+// first, and no launch gap separates the passes.
+template <typename T, int SLICE>
+__global__ __launch_bounds__(kMergeWaves * kWave) void merge_buckets_kernel(MergeArgs a, int hub_blocks) {
+  extern __shared__ __attribute__((aligned(16))) char lds_m[];
+  if ((int)blockIdx.x < hub_blocks) {
+    (void)merge_unit<T, false, SLICE, kMergeWaves>(a, lds_m, blockIdx.x);
+  } else {
+    (void)merge_unit<T, false, SLICE, 1>(a, lds_m, blockIdx.x - hub_blocks);
+    write_pos_out<SLICE>(a, blockIdx.x - hub_blocks);
   }
 }
 
@@ -856,6 +876,21 @@ static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
   hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE, WPU>), grid, block, lds, s, m);
 }
 
+template <typename T, int SLICE>
+static void launch_merge_buckets(const MergeArgs& m, int B, hipStream_t s) {
+  using L1 = MergeLds<false, SLICE, 1>;
+  using L8 = MergeLds<false, SLICE, kMergeWaves>;
+  constexpr int kSpan = kWave * kVec * SLICE;
+  const int n_spans = (m.D + kSpan - 1) / kSpan;
+  const size_t lds = std::max(L1::bytes(m.n_disc), L8::bytes(m.n_disc));
+  const int hub_blocks = m.n_keep * n_spans;                       // at most every preserved token has a long bucket
+  const int row_blocks = (m.n_out * n_spans + L1::kUnits - 1) / L1::kUnits;
+  if (lds > 32768)
+    (void)hipFuncSetAttribute((const void*)merge_buckets_kernel<T, SLICE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+  hipLaunchKernelGGL((merge_buckets_kernel<T, SLICE>), dim3(hub_blocks + row_blocks, B), dim3(kMergeWaves * kWave), lds, s, m,
+                     hub_blocks);
+}
+
 template <typename T, bool MATCH, int WPU>
 static void launch_merge_s(const MergeArgs& m, int B, int slice, hipStream_t s) {
   if (slice == 1) launch_merge<T, MATCH, 1, WPU>(m, B, s); else launch_merge<T, MATCH, 2, WPU>(m, B, s);
@@ -898,10 +933,11 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.average = p.compress_mode == FICOCO_COMPRESS_AVERAGE ? 1 : 0;
   m.extra_row = pl.extra_token ? p.vis_begin + p.n_keep : -1;
   // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when the
-  // wide ones would not fill the chip.  Bucket mode runs two passes: one wavefront per unit for
-  // the targets with at most kHubMin sources, then a whole workgroup per unit (eight wavefronts,
-  // each adding the sources of one part of the discarded rows, parts added in order) for the few
-  // targets with long buckets, whose serial row loads would otherwise set the kernel's duration.
+  // wide ones would not fill the chip.  Bucket mode has two kinds of workgroups in its one launch:
+  // eight units with one wavefront each for the targets with at most kHubMin sources, and a whole
+  // workgroup per unit (eight wavefronts, each adding the sources of one part of the discarded
+  // rows, parts added in order) for the few targets with long buckets, whose serial row loads
+  // would otherwise set the kernel's duration.
   const int slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
   const bool bf16 = p.dtype == FICOCO_BF16;
   if (match) {
@@ -909,10 +945,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   } else {
     m.hub_list = (const int32_t*)(ws + pl.hub_list);
     m.hub_cnt = (const int32_t*)(ws + pl.hub_cnt);
-    if (bf16) launch_merge_s<bf16_t, false, 1>(m, p.B, slice, s); else launch_merge_s<float, false, 1>(m, p.B, slice, s);
-    MergeArgs h = m;
-    h.pos_out = nullptr;           // written by the first pass
-    if (bf16) launch_merge_s<bf16_t, false, kMergeWaves>(h, p.B, slice, s); else launch_merge_s<float, false, kMergeWaves>(h, p.B, slice, s);
+    if (bf16) { if (slice == 1) launch_merge_buckets<bf16_t, 1>(m, p.B, s); else launch_merge_buckets<bf16_t, 2>(m, p.B, s); }
+    else { if (slice == 1) launch_merge_buckets<float, 1>(m, p.B, s); else launch_merge_buckets<float, 2>(m, p.B, s); }
   }
   if (m.extra_row >= 0) {
     dim3 grid((p.D + kWave * kVec - 1) / (kWave * kVec), p.B);

@@ -81,6 +81,12 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
 constexpr int kQkTile = 48;        // query rows per workgroup of the query/key form
 constexpr int kQkMaxKeys = 640;    // keys it holds in registers
 void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+// The feature stage is norms and unit rows only (no score term reads the features; the cosine
+// correlation does): the score stage's launch of the filter kernel takes them along on workgroups
+// of its own, and launch_features does nothing.
+inline bool rows_with_filter(const ficoco_problem& p, const Plan& pl) {
+  return pl.need_features && p.red_src != FICOCO_R_SIM_MEAN && p.sem_src != FICOCO_G_EQ_TOKEN;
+}
 // FiCoCo-L with 32 or more text queries: the fused step forms the column maxima of the text
 // profiles in the score stage's launch (select.hip), and its correlate stage does not.
 inline bool text_stats_in_score(const ficoco_problem& p) {

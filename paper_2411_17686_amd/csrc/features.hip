@@ -4,100 +4,16 @@
 // u_i . mean_j u_j with u = F / |F|.  Double precision throughout; column sums use a fixed
 // two-level order (row chunks, then chunks) so results do not depend on scheduling.
 #include "common.hpp"
+#include "feature_rows.hpp"
 
 namespace ficoco {
 
-struct FeatArgs {
-  const void* F;
-  int64_t sb, sn;
-  int N, Df, f_chunks, f_rows_per_wg;
-  double* norm;         // [B][N]
-  bf16_t* xhat;         // [B][N][Df] or null
-  double* colsum_part;  // [2][B][f_chunks][Df]  (0: unit rows, 1: raw rows)
-  double* colmean;      // [2][B][Df]
-  double* fterm_r;      // [B][N]
-  double* fterm_g;      // [B][N]
-  int want_sim, want_eq;
-  int B;
-};
-
-__device__ __forceinline__ double wave_sum_d(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
-}
-
-// A row is read as 16-byte vectors, vector 64 * t + lane by lane `lane` in step t, KB steps in
-// flight per lane.  Lanes past the last whole vector read vector 0 and clear what they got, so
-// that the batch stays straight-line code.
-template <typename T, int KB>
-struct RowBatch {
-  static constexpr int kVecs = KB;
-  Raw8<T> raw[kVecs];
-  __device__ __forceinline__ void load(const T* x, int t0, int n_vec, int lane) {
-#pragma unroll
-    for (int u = 0; u < kVecs; ++u) {
-      const int idx = (t0 + u) * kWave + lane;
-      load_raw(x + (idx < n_vec ? idx * kVec : 0), raw[u]);
-    }
-    issue_fence();
-#pragma unroll
-    for (int u = 0; u < kVecs; ++u) keep_raw_if(raw[u], (t0 + u) * kWave + lane < n_vec);
-  }
-};
-
-// One wavefront per row: |F_i| in double precision and, for the cosine correlation, the unit
-// row rounded to bfloat16.  Rows of up to 64 * KB vectors are read once; longer ones are read
-// again (from cache) for the unit row.  The launcher picks KB = 2, 4 or 8 by the row length (a
-// batch wider than the row only adds loads that are thrown away).
 template <typename T, int KB>
 __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   const int lane = threadIdx.x % kWave;
   const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-  const int64_t b = blockIdx.y;
-  if (i >= a.N) return;
-  const T* x = (const T*)a.F + b * a.sb + (int64_t)i * a.sn;
-  const int n_vec = a.Df / kVec, Dv = n_vec * kVec;
-  const int n_t = (n_vec + kWave - 1) / kWave;
-  constexpr int kB = KB;
-  RowBatch<T, KB> first, more;
-  double ss = 0.0;
-  auto add_squares = [&](const RowBatch<T, KB>& rb) {
-#pragma unroll
-    for (int u = 0; u < kB; ++u) {
-      double v[kVec];
-      widen_raw(rb.raw[u], v);
-#pragma unroll
-      for (int k = 0; k < kVec; ++k) ss += v[k] * v[k];
-    }
-  };
-  if (n_t > 0) { first.load(x, 0, n_vec, lane); add_squares(first); }
-  for (int t0 = kB; t0 < n_t; t0 += kB) { more.load(x, t0, n_vec, lane); add_squares(more); }
-  for (int d = Dv + lane; d < a.Df; d += kWave) { const double v = widen(x[d]); ss += v * v; }
-  ss = wave_sum_d(ss);
-  const double nrm = sqrt(ss);
-  if (lane == 0) a.norm[b * a.N + i] = nrm;
-  if (a.xhat) {
-    const double inv = nrm > 0.0 ? 1.0 / nrm : 0.0;
-    bf16_t* o = a.xhat + (b * a.N + i) * (int64_t)a.Df;
-    auto store_unit = [&](const RowBatch<T, KB>& rb, int t0) {
-#pragma unroll
-      for (int u = 0; u < kB; ++u) {
-        const int idx = (t0 + u) * kWave + lane;
-        if (idx < n_vec) {
-          double v[kVec];
-          widen_raw(rb.raw[u], v);
-          Pack8<bf16_t> r;
-#pragma unroll
-          for (int k = 0; k < kVec; ++k) r.v[k] = to_bf16(v[k] * inv);
-          __builtin_memcpy(o + idx * kVec, &r, sizeof(r));
-        }
-      }
-    };
-    if (n_t > 0) store_unit(first, 0);
-    for (int t0 = kB; t0 < n_t; t0 += kB) { more.load(x, t0, n_vec, lane); store_unit(more, t0); }
-    for (int d = Dv + lane; d < a.Df; d += kWave) o[d] = to_bf16(widen(x[d]) * inv);
-  }
+  if (i >= a.N) return;      // whole wavefront leaves together
+  row_norm_row<T, KB>(a, blockIdx.y, i, lane);
 }
 
 // Partial column sums over a chunk of rows: slot 0 adds unit rows (row times the reciprocal of
@@ -307,8 +223,7 @@ __global__ __launch_bounds__(256) void feature_terms_kernel(FeatArgs a) {
   }
 }
 
-void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
-  FeatArgs a{};
+void fill_row_args(const ficoco_problem& p, const Plan& pl, char* ws, FeatArgs& a) {
   if (p.F) { a.F = p.F; a.sb = p.f_stride_b; a.sn = p.f_stride_n; }
   else {
     const size_t es = p.dtype == FICOCO_BF16 ? 2 : 4;
@@ -318,6 +233,12 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
   a.N = p.N; a.Df = pl.Df; a.f_chunks = pl.f_chunks; a.f_rows_per_wg = pl.f_rows_per_wg; a.B = p.B;
   a.norm = (double*)(ws + pl.inv_norm);
   a.xhat = p.corr_src == FICOCO_C_COSINE ? (bf16_t*)(ws + pl.xhat) : nullptr;
+}
+
+void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+  if (rows_with_filter(p, pl)) return;      // norms and unit rows only: the filter kernel's launch takes them along
+  FeatArgs a{};
+  fill_row_args(p, pl, ws, a);
   a.colsum_part = (double*)(ws + pl.colsum_part);
   a.colmean = (double*)(ws + pl.colmean);
   a.fterm_r = (double*)(ws + pl.fterm);

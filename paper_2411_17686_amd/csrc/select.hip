@@ -12,6 +12,7 @@
 // discarded in index order until N^S is reached.  Integer LDS atomics only build histograms
 // (their result does not depend on the order of arrival).
 #include "common.hpp"
+#include "feature_rows.hpp"
 
 namespace ficoco {
 
@@ -52,6 +53,10 @@ struct SelectArgs {
   double* ex_u;             // [B][kExactGroup][Df] unit rows of the tokens being re-evaluated
   double* ex_g;             // [B][kExactGroup][N]  their cosines with every token
   int32_t* ex_list;         // [B][N] tokens to re-evaluate in this pass
+  // Side work (SIDE_KB > 0): the workgroups behind the first B take the row norms and unit rows of
+  // the feature stage along, `side_chunks` workgroups per image with one wavefront per row.
+  FeatArgs side;
+  int B, side_chunks;
 };
 
 constexpr int kExactGroup = 8;    // tokens whose mean cosine is re-evaluated together
@@ -307,8 +312,20 @@ __device__ __forceinline__ void exact_terms_of(const SelectArgs& a, int b_in, co
 
 // EXACT: the instantiation for problems with a cosine-derived score term (the re-evaluation code
 // costs registers that the common instantiation does not pay).
-template <bool EXACT, typename TF>     // TF: storage type of the features (EXACT only)
+// SIDE_KB > 0: no score term needs the features, but the correlate stage needs their unit rows.
+// That work depends on nothing the filter computes and the filter is one workgroup per image, so
+// it rides in the same launch on workgroups of its own (row_norm_row with SIDE_KB steps in
+// flight) instead of in a kernel before this one.
+template <bool EXACT, typename TF, int SIDE_KB>     // TF: storage type of the features (EXACT or SIDE_KB > 0)
 __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
+  if constexpr (SIDE_KB > 0) {
+    if ((int)blockIdx.x >= a.B) {                       // uniform per workgroup
+      const int sb = (int)blockIdx.x - a.B;
+      const int i = (sb % a.side_chunks) * ((int)blockDim.x / kWave) + (int)threadIdx.x / kWave;
+      if (i < a.N) row_norm_row<TF, SIDE_KB>(a.side, sb / a.side_chunks, i, threadIdx.x % kWave);
+      return;
+    }
+  }
   extern __shared__ double lds_d[];
   double* s = lds_d;                                   // [N] scores, then keys in place
   uint64_t* keys = (uint64_t*)lds_d;
@@ -753,15 +770,32 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.overflow = overflow;
   const size_t lds = select_lds(p, penalty);
   const bool exact = a.exact_r || a.exact_g;
-  const void* kern = !exact ? (const void*)select_kernel<false, float>
-                   : p.dtype == FICOCO_BF16 ? (const void*)select_kernel<true, bf16_t> : (const void*)select_kernel<true, float>;
-  if (lds > 32768) (void)hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   // Short sequences: no more wavefronts than tokens need (every barrier of the kernel waits for
   // all of them); at least 256 threads, which the histogram walk assumes.
   const int threads = p.N >= kSelectThreads ? kSelectThreads : std::max(256, (p.N + kWave - 1) / kWave * kWave);
-  if (!exact) hipLaunchKernelGGL((select_kernel<false, float>), dim3(p.B), dim3(threads), lds, s, a);
-  else if (p.dtype == FICOCO_BF16) hipLaunchKernelGGL((select_kernel<true, bf16_t>), dim3(p.B), dim3(threads), lds, s, a);
-  else hipLaunchKernelGGL((select_kernel<true, float>), dim3(p.B), dim3(threads), lds, s, a);
+  const bool bf16 = p.dtype == FICOCO_BF16;
+  int side_kb = 0;
+  if (do_score && rows_with_filter(p, pl)) {
+    fill_row_args(p, pl, ws, a.side);
+    a.B = p.B;
+    a.side_chunks = (p.N + threads / kWave - 1) / (threads / kWave);
+    const int steps = (pl.Df / kVec + kWave - 1) / kWave;    // 16-byte vectors per lane and row
+    side_kb = steps <= 2 ? 2 : (steps <= 4 || !bf16) ? 4 : 8;
+  }
+  const dim3 grid(p.B + (side_kb ? p.B * a.side_chunks : 0)), block(threads);
+  auto go = [&](auto kern) {
+    if (lds > 32768) (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+    hipLaunchKernelGGL(kern, grid, block, lds, s, a);
+  };
+  if (exact) { if (bf16) go(select_kernel<true, bf16_t, 0>); else go(select_kernel<true, float, 0>); }
+  else if (side_kb == 0) go(select_kernel<false, float, 0>);
+  else if (bf16) {
+    if (side_kb == 2) go(select_kernel<false, bf16_t, 2>);
+    else if (side_kb == 4) go(select_kernel<false, bf16_t, 4>);
+    else go(select_kernel<false, bf16_t, 8>);
+  } else {
+    if (side_kb == 2) go(select_kernel<false, float, 2>); else go(select_kernel<false, float, 4>);
+  }
 }
 
 void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {

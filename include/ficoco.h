@@ -190,8 +190,13 @@ const char *ficoco_version(void);
  * inside a running pipeline.  NULL, NULL switches it off.
  *   kernel = FICOCO_PROBE_REDUCE : the attention-reduction kernel (bandwidth bound)
  *   kernel = FICOCO_PROBE_GRAM   : the bf16 matrix-core tile kernel of the cosine correlation
+ *   kernel = FICOCO_PROBE_GRAM_X16 : the same kernel launched FICOCO_PROBE_REPEAT times in a row
+ *            between the two events (every launch writes the same block, so results do not
+ *            change): elapsed / FICOCO_PROBE_REPEAT is the launch duration without the cost of
+ *            recording an event around a single short launch.  For ficoco_correlate loops only.
  */
-typedef enum { FICOCO_PROBE_REDUCE = 0, FICOCO_PROBE_GRAM = 1 } ficoco_probe_kernel;
+typedef enum { FICOCO_PROBE_REDUCE = 0, FICOCO_PROBE_GRAM = 1, FICOCO_PROBE_GRAM_X16 = 2 } ficoco_probe_kernel;
+#define FICOCO_PROBE_REPEAT 16
 int ficoco_set_probe(ficoco_ctx *ctx, int kernel, void *start_event, void *stop_event);
 
 /* Bytes of device workspace the calls below need for this problem (256-byte aligned

@@ -388,7 +388,7 @@ const char* ficoco_last_error(const ficoco_ctx* ctx) { return ctx ? ctx->err : "
 
 int ficoco_set_probe(ficoco_ctx* ctx, int kernel, void* start_event, void* stop_event) {
   if (!ctx || ((start_event == nullptr) != (stop_event == nullptr)) ||
-      (kernel != FICOCO_PROBE_REDUCE && kernel != FICOCO_PROBE_GRAM))
+      (kernel != FICOCO_PROBE_REDUCE && kernel != FICOCO_PROBE_GRAM && kernel != FICOCO_PROBE_GRAM_X16))
     return FICOCO_EINVAL;
   ctx->probe_kernel = kernel;
   ctx->probe_start = (hipEvent_t)start_event;
@@ -462,10 +462,10 @@ int ficoco_correlate(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t 
   if (rc != FICOCO_OK) return rc;
   if (!keep_idx || !overflow || (pl.n_disc > 0 && (!discard_idx || !edge_cnt || !edge_tgt || !edge_alpha)))
     return fail(ctx, FICOCO_EINVAL, "ficoco_correlate", "a pointer is NULL");
-  const bool pg = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_GRAM;
+  const bool pg = ctx->probe_start && (ctx->probe_kernel == FICOCO_PROBE_GRAM || ctx->probe_kernel == FICOCO_PROBE_GRAM_X16);
   launch_correlate(*p, pl, (char*)ws, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow,
                    false, pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr,
-                   (hipStream_t)stream);
+                   (hipStream_t)stream, pg && ctx->probe_kernel == FICOCO_PROBE_GRAM_X16 ? FICOCO_PROBE_REPEAT : 1);
   return finish(ctx, "ficoco_correlate");
 }
 

@@ -101,7 +101,7 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool fused,
-                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s);
+                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s, int gram_repeat = 1);
 void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_idx, const void* in,
                    int64_t sb, int64_t sn, int row_bytes, void* out, hipStream_t s);
 void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,

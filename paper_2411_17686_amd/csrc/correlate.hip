@@ -858,7 +858,7 @@ static void launch_cand_rows(int sel_m, dim3 grid, dim3 block, hipStream_t s, co
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool fused,
-                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s) {
+                      hipEvent_t gram_start, hipEvent_t gram_stop, hipStream_t s, int gram_repeat) {
   // fused: called from a fused step, whose filter stage cleared the overflow flags and whose
   // score stage formed the column maxima of the text profiles (text_stats_in_score)
   if (!fused)
@@ -917,12 +917,15 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
     const int tiles2 = p.B * ((pl.n_disc + kG2M - 1) / kG2M) * ((p.n_keep + kG2N - 1) / kG2N);
     const bool wide = pl.gram_splits == 1 && tiles2 >= 128;
     if (gram_start) (void)hipEventRecord(gram_start, s);
-    if (wide) {
-      const size_t lds = (size_t)2 * (kG2M + kG2N) * kG2Chunks * sizeof(uint4);
-      (void)hipFuncSetAttribute((const void*)gram_tile2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-      hipLaunchKernelGGL(gram_tile2_kernel, dim3(xcd_padded_total(tiles2)), dim3(kG2Threads), lds, s, g);
+    // gram_repeat > 1 (measurement only): the same launch again and again between the two events
+    for (int rep = 0; rep < gram_repeat; ++rep) {
+      if (wide) {
+        const size_t lds = (size_t)2 * (kG2M + kG2N) * kG2Chunks * sizeof(uint4);
+        (void)hipFuncSetAttribute((const void*)gram_tile2_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipLaunchKernelGGL(gram_tile2_kernel, dim3(xcd_padded_total(tiles2)), dim3(kG2Threads), lds, s, g);
+      }
+      else hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     }
-    else hipLaunchKernelGGL(gram_tile_kernel, dim3(xcd_padded_total(tiles)), dim3(256), 0, s, g);
     if (gram_stop) (void)hipEventRecord(gram_stop, s);
     if (L && need_colmax) hipLaunchKernelGGL(text_colmax_kernel, dim3((p.M + 63) / 64, p.B), dim3(256), 0, s, a);
     launch_cand_rows(pl.sel_m, grid, block, s, a);

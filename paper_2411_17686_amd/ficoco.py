@@ -18,7 +18,8 @@ VARIANT_V, VARIANT_L = 0, 1
 R_ATTN_RECV, R_VECTOR, R_SIM_MEAN = 0, 1, 2
 G_CLS_ATTN, G_TEXT_ATTN, G_VECTOR, G_EQ_TOKEN = 0, 1, 2, 3
 C_ATTN, C_COSINE = 0, 1
-PROBE_REDUCE, PROBE_GRAM = 0, 1
+PROBE_REDUCE, PROBE_GRAM, PROBE_GRAM_X16 = 0, 1, 2
+PROBE_REPEAT = 16
 K_ADAPTIVE, K_FIXED, K_CONVERGENT = 0, 1, 2
 COMPRESS_SELF, COMPRESS_AVERAGE = 0, 1
 

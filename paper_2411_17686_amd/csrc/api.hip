@@ -336,10 +336,11 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   const bool pr = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_REDUCE;
   const bool pg = ctx->probe_start && ctx->probe_kernel == FICOCO_PROBE_GRAM;
   if (pr) (void)hipEventRecord(ctx->probe_start, s);
-  if (pl.qk) launch_attn_qk(p, pl, w, s); else launch_attn_reduce(p, pl, w, s);
+  const bool tw = text_with_features(p, pl);
+  if (pl.qk) launch_attn_qk(p, pl, w, s); else launch_attn_reduce(p, pl, w, s, tw);
   if (pr) (void)hipEventRecord(ctx->probe_stop, s);
-  if (pl.need_features) launch_features(p, pl, w, s);
-  launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s);
+  if (pl.need_features) launch_features(p, pl, w, s, tw, tw);
+  launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s, tw);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true,
                    pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr, s);
   launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
@@ -436,10 +437,11 @@ int ficoco_score(ficoco_ctx* ctx, const ficoco_problem* p, void* ws, size_t ws_b
   const int rc = prepare(ctx, p, ws, ws_bytes, pl, "ficoco_score");
   if (rc != FICOCO_OK) return rc;
   if (!scores) return fail(ctx, FICOCO_EINVAL, "ficoco_score", "scores is NULL");
+  const bool tw = text_with_features(*p, pl);
   if (pl.qk) launch_attn_qk(*p, pl, (char*)ws, (hipStream_t)stream);
-  else launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream);
-  if (pl.need_features) launch_features(*p, pl, (char*)ws, (hipStream_t)stream);
-  launch_score(*p, pl, (char*)ws, scores, (hipStream_t)stream);
+  else launch_attn_reduce(*p, pl, (char*)ws, (hipStream_t)stream, tw);
+  if (pl.need_features) launch_features(*p, pl, (char*)ws, (hipStream_t)stream, tw, false);
+  launch_score(*p, pl, (char*)ws, scores, (hipStream_t)stream, tw);
   return finish(ctx, "ficoco_score");
 }
 

@@ -13,32 +13,13 @@
 // 16-byte loads; rows of a dense map with an odd length are only element aligned, the
 // hardware's unaligned dwordx4 access is relied on for those.
 #include "common.hpp"
+#include "text_rows.hpp"
 
 namespace ficoco {
 
-constexpr int kHeadBatch = 8;
 constexpr int kRowsAtOnce = 4;     // rows of one thread whose heads are added side by side ...
 constexpr int kHeadsAtOnce = 2;    // ... this many heads of each per batch of loads (more where the thread has fewer rows)
 
-struct AttnArgs {
-  const void* A;
-  int64_t sb, sh, sq;
-  int H;
-  int row0, nrows;  // rows [row0, row0+nrows) of the block are visited
-  int col0;         // column of visual key 0
-  int N;
-  int vis_r0, n_vis;  // rows of the visual queries (n_vis = 0: none)
-  int cls_r;          // row of the [CLS] query or -1
-  int M;              // text queries (text block only)
-  float* abar;
-  double* recv_part;
-  double* cls;
-  double* ttext;
-  int rows_per_wg, n_chunks, row_lanes, strip_groups, col_strips, B;
-  int shift;          // rows by which chunk 0 is shortened (visual row 0 starts a chunk)
-  int map_pitch;      // floats per row of abar
-  double invH;
-};
 
 // Three wavefronts per SIMD (170 registers): the four-row form keeps 32 double accumulators and 8
 // raw vectors per thread, and its grids hold about three wavefronts per SIMD anyway.
@@ -252,76 +233,9 @@ __global__ __launch_bounds__(kReduceThreads) __attribute__((amdgpu_waves_per_eu(
   }
 }
 
-// Text-query block of FiCoCo-L (task term of Eq. 3, profiles of Eq. 4): the head mean of
-// A_text[b][h][k][i], stored TRANSPOSED as the token's profile ttext[b][i][k].  A workgroup
-// owns 8 consecutive text rows x 256 key columns: a thread forms the head mean of one row and
-// 8 columns exactly as the kernel above does (heads added in order, in double), the tile is
-// turned in LDS, and each thread then writes the 8 rows of one column as one 64-byte piece.
-constexpr int kTextHeadBatch = 16;
-constexpr int kTextRows = 8;
-constexpr int kTextGroups = 256 / kTextRows;      // 8-column groups per workgroup
 template <typename T>
 __global__ __launch_bounds__(256) void text_reduce_kernel(AttnArgs a) {
-  __shared__ double tile[kTextGroups * kVec][kTextRows + 1];     // +1: rows of one column in different banks
-  const int chunk = blockIdx.x, strip = blockIdx.y;
-  const int64_t b = blockIdx.z;
-  const int tid = threadIdx.x;
-  const int cg = tid % kTextGroups, rl = tid / kTextGroups;
-  const int row = chunk * kTextRows + rl;
-  const int col0 = strip * kTextGroups * kVec;
-  const int col = col0 + cg * kVec;
-  const int ncol = max(min(kVec, a.N - col), 0);
-  if (row < a.M && ncol > 0) {
-    const T* base = (const T*)a.A + b * a.sb + (int64_t)row * a.sq + a.col0 + col;
-    double p[kVec];
-#pragma unroll
-    for (int k = 0; k < kVec; ++k) p[k] = 0.0;
-    if (ncol == kVec) {
-      int h0 = 0;
-      // the grid of this kernel is small (8 rows x 256 keys per workgroup), so each thread keeps
-      // more loads in flight than the map kernel does: kTextHeadBatch heads at a time
-      for (; h0 + kTextHeadBatch <= a.H; h0 += kTextHeadBatch) {
-        Raw8<T> raw[kTextHeadBatch];
-#pragma unroll
-        for (int u = 0; u < kTextHeadBatch; ++u) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
-        issue_fence();
-#pragma unroll
-        for (int u = 0; u < kTextHeadBatch; ++u) add_raw(raw[u], p);
-      }
-      for (; h0 + kHeadBatch <= a.H; h0 += kHeadBatch) {
-        Raw8<T> raw[kHeadBatch];
-#pragma unroll
-        for (int u = 0; u < kHeadBatch; ++u) load_raw(base + (int64_t)(h0 + u) * a.sh, raw[u]);
-#pragma unroll
-        for (int u = 0; u < kHeadBatch; ++u) add_raw(raw[u], p);
-      }
-      for (; h0 < a.H; ++h0) {
-        Raw8<T> raw;
-        load_raw(base + (int64_t)h0 * a.sh, raw);
-        add_raw(raw, p);
-      }
-    } else {
-      for (int h = 0; h < a.H; ++h)
-        for (int k = 0; k < ncol; ++k) p[k] += widen(base[(int64_t)h * a.sh + k]);
-    }
-#pragma unroll
-    for (int k = 0; k < kVec; ++k) tile[cg * kVec + k][rl] = p[k] * a.invH;
-  }
-  __syncthreads();
-  const int c = col0 + tid;                        // this thread's column
-  if (c >= a.N) return;
-  const int r0 = chunk * kTextRows;
-  const int nr = min(kTextRows, a.M - r0);
-  double* dst = a.ttext + ((int64_t)b * a.N + c) * a.M + r0;
-  if (nr == kTextRows && a.M % 2 == 0) {           // 16-byte aligned pieces
-#pragma unroll
-    for (int k = 0; k < kTextRows; k += 2) {
-      double2 v = make_double2(tile[tid][k], tile[tid][k + 1]);
-      *reinterpret_cast<double2*>(dst + k) = v;
-    }
-  } else {
-    for (int k = 0; k < nr; ++k) dst[k] = tile[tid][k];
-  }
+  text_reduce_block<T>(a, blockIdx.x, blockIdx.y, blockIdx.z);
 }
 
 static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hipStream_t s) {
@@ -336,7 +250,7 @@ static void launch_block(const AttnArgs& a, int B, int col_strips, bool bf16, hi
     hipLaunchKernelGGL(attn_reduce_kernel<float>, grid, block, lds, s, g);
 }
 
-void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool text_elsewhere) {
   const bool bf16 = p.dtype == FICOCO_BF16;
   const bool want_recv = p.red_src == FICOCO_R_ATTN_RECV;
   const bool want_cls = p.sem_src == FICOCO_G_CLS_ATTN;
@@ -362,22 +276,25 @@ void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipSt
     a.invH = 1.0 / (double)p.H;
     launch_block(a, p.B, pl.col_strips, bf16, s);
   }
-  if (p.A_text && p.variant == FICOCO_VARIANT_L) {
+  if (p.A_text && p.variant == FICOCO_VARIANT_L && !text_elsewhere) {
     AttnArgs a{};
-    a.A = p.A_text; a.sb = p.at_stride_b; a.sh = p.at_stride_h; a.sq = p.at_stride_q;
-    a.H = p.H;
-    a.row0 = 0; a.nrows = p.M;
-    a.col0 = p.vis_begin - p.at_k_begin;
-    a.N = p.N;
-    a.vis_r0 = 0; a.n_vis = 0; a.cls_r = -1;
-    a.M = p.M;
-    a.abar = nullptr; a.recv_part = nullptr; a.cls = nullptr;
-    a.ttext = (double*)(ws + pl.ttext);
-    a.invH = 1.0 / (double)p.H;
-    dim3 grid((p.M + kTextRows - 1) / kTextRows, (p.N + kTextGroups * kVec - 1) / (kTextGroups * kVec), p.B);
-    if (bf16) hipLaunchKernelGGL(text_reduce_kernel<bf16_t>, grid, dim3(256), 0, s, a);
-    else hipLaunchKernelGGL(text_reduce_kernel<float>, grid, dim3(256), 0, s, a);
+    fill_text_args(p, pl, ws, a);
+    if (bf16) hipLaunchKernelGGL(text_reduce_kernel<bf16_t>, text_grid(p), dim3(256), 0, s, a);
+    else hipLaunchKernelGGL(text_reduce_kernel<float>, text_grid(p), dim3(256), 0, s, a);
   }
+}
+
+void fill_text_args(const ficoco_problem& p, const Plan& pl, char* ws, AttnArgs& a) {
+  a.A = p.A_text; a.sb = p.at_stride_b; a.sh = p.at_stride_h; a.sq = p.at_stride_q;
+  a.H = p.H;
+  a.row0 = 0; a.nrows = p.M;
+  a.col0 = p.vis_begin - p.at_k_begin;
+  a.N = p.N;
+  a.vis_r0 = 0; a.n_vis = 0; a.cls_r = -1;
+  a.M = p.M;
+  a.abar = nullptr; a.recv_part = nullptr; a.cls = nullptr;
+  a.ttext = (double*)(ws + pl.ttext);
+  a.invH = 1.0 / (double)p.H;
 }
 
 }  // namespace ficoco

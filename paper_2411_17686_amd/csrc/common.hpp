@@ -76,11 +76,16 @@ int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
 // visual token, weight.  16 bytes, one load.
 
 // ---- launchers (all asynchronous on `s`) -----------------------------------------------
-void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+// text_elsewhere: the text-profile kernel is not launched here (text_with_features: it rides in the
+// feature stage's launch)
+void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool text_elsewhere = false);
 void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
 constexpr int kQkTile = 48;        // query rows per workgroup of the query/key form
 constexpr int kQkMaxKeys = 640;    // keys it holds in registers
-void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
+// with_text: the launch of the row-norm kernel also forms the text profiles and the launch of the
+// column-sum kernel their statistics (with_cmax: the column maxima too), see text_with_features
+void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool with_text = false,
+                     bool with_cmax = false);
 // The feature stage is norms and unit rows only (no score term reads the features; the cosine
 // correlation does): the score stage's launch of the filter kernel takes them along on workgroups
 // of its own, and launch_features does nothing.
@@ -92,12 +97,21 @@ inline bool rows_with_filter(const ficoco_problem& p, const Plan& pl) {
 inline bool text_stats_in_score(const ficoco_problem& p) {
   return p.variant == FICOCO_VARIANT_L && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 32;
 }
-void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s);
+// FiCoCo-L whose score reads both the features (column sums: four dependent launches) and the text
+// profiles (two dependent launches): the two chains do not depend on each other, so where score
+// and reduction are issued by the same call the text kernels ride in the launches of the feature
+// kernels instead of standing in line before and after them.
+inline bool text_with_features(const ficoco_problem& p, const Plan& pl) {
+  return text_stats_in_score(p) && p.A_text != nullptr && pl.need_features && !rows_with_filter(p, pl);
+}
+// text_stats_done: the text statistics were formed by the feature stage's launches
+void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s,
+                  bool text_stats_done = false);
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s);
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
                    bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
-                   hipStream_t s);
+                   hipStream_t s, bool text_stats_done = false);
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool fused,

@@ -5,6 +5,8 @@
 // two-level order (row chunks, then chunks) so results do not depend on scheduling.
 #include "common.hpp"
 #include "feature_rows.hpp"
+#include "text_rows.hpp"
+#include "text_stats.hpp"
 
 namespace ficoco {
 
@@ -16,6 +18,24 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
   row_norm_row<T, KB>(a, blockIdx.y, i, lane);
 }
 
+// The same rows with the text-profile kernel of FiCoCo-L in the same launch: the first
+// `text_blocks` workgroups (x fastest, then y, then image: tg = the text kernel's grid) form text
+// profiles, the others take four rows each.  Neither needs anything from the other; as two
+// launches the short text kernel stood in line before this one.
+template <typename T, int KB>
+__global__ __launch_bounds__(256) void rows_text_kernel(FeatArgs a, AttnArgs t, int text_blocks, int tgx, int tgy,
+                                                        int row_blocks) {
+  if ((int)blockIdx.x < text_blocks) {
+    const int q = blockIdx.x;
+    text_reduce_block<T>(t, q % tgx, (q / tgx) % tgy, q / (tgx * tgy));
+    return;
+  }
+  const int rb = (int)blockIdx.x - text_blocks;
+  const int i = (rb % row_blocks) * (blockDim.x / kWave) + threadIdx.x / kWave;
+  if (i >= a.N) return;      // whole wavefront leaves together
+  row_norm_row<T, KB>(a, rb / row_blocks, i, threadIdx.x % kWave);
+}
+
 // Partial column sums over a chunk of rows: slot 0 adds unit rows (row times the reciprocal of
 // its norm), slot 1 raw rows.  A workgroup covers 512 features: a lane owns 8 consecutive
 // ones, each of its four wavefronts takes a quarter of the chunk's rows (16-byte loads of up
@@ -23,12 +43,10 @@ __global__ __launch_bounds__(256) void row_norm_kernel(FeatArgs a) {
 constexpr int kColBatch = 8;
 constexpr int kColSpan = kWave * kVec;
 template <typename T>
-__global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
+__device__ __forceinline__ void col_sum_block(const FeatArgs& a, int chunk, int span, int64_t b) {
   __shared__ double part[3][2][kVec][kWave];
   const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
-  const int chunk = blockIdx.x;
-  const int d = blockIdx.y * kColSpan + lane * kVec;
-  const int64_t b = blockIdx.z;
+  const int d = span * kColSpan + lane * kVec;
   const int nd = max(min(kVec, a.Df - d), 0);
   const int c0 = chunk * a.f_rows_per_wg, c1 = min(c0 + a.f_rows_per_wg, a.N);
   const int quarter = (c1 - c0 + 3) / 4;
@@ -90,6 +108,23 @@ __global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) {
   const int64_t slot = (int64_t)a.B * a.f_chunks * a.Df;
   double* pu = a.colsum_part + (b * a.f_chunks + chunk) * a.Df + d;
   for (int k = 0; k < nd; ++k) { pu[k] = su[k]; pu[slot + k] = sr[k]; }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void col_sum_kernel(FeatArgs a) { col_sum_block<T>(a, blockIdx.x, blockIdx.y, blockIdx.z); }
+
+// The column sums with the statistics of the text profiles (FiCoCo-L) in the same launch: the first
+// `stat_blocks * B` workgroups take the statistics, the others the column sums (chunk fastest,
+// then feature span, then image).
+template <typename T>
+__global__ __launch_bounds__(256) void colsum_stats_kernel(FeatArgs a, TextStatsArgs t, int stat_blocks, int spans) {
+  const int n_stat = stat_blocks * a.B;
+  if ((int)blockIdx.x < n_stat) {
+    text_stats_block(t, (int)blockIdx.x % stat_blocks, (int)blockIdx.x / stat_blocks);
+    return;
+  }
+  const int q = (int)blockIdx.x - n_stat;
+  col_sum_block<T>(a, q % a.f_chunks, (q / a.f_chunks) % spans, q / (a.f_chunks * spans));
 }
 
 // Column means from the chunk partials (added in chunk order, 8 loads in flight).  Every
@@ -235,7 +270,7 @@ void fill_row_args(const ficoco_problem& p, const Plan& pl, char* ws, FeatArgs& 
   a.xhat = p.corr_src == FICOCO_C_COSINE ? (bf16_t*)(ws + pl.xhat) : nullptr;
 }
 
-void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
+void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool with_text, bool with_cmax) {
   if (rows_with_filter(p, pl)) return;      // norms and unit rows only: the filter kernel's launch takes them along
   FeatArgs a{};
   fill_row_args(p, pl, ws, a);
@@ -248,18 +283,38 @@ void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStrea
   const bool bf16 = p.dtype == FICOCO_BF16;
   dim3 rows((p.N + 3) / 4, p.B), block(256);
   const int steps = (pl.Df / kVec + kWave - 1) / kWave;    // 16-byte vectors per lane and row
-  if (bf16) {
-    if (steps <= 2) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 2>), rows, block, 0, s, a);
-    else if (steps <= 4) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 4>), rows, block, 0, s, a);
+  const int kb = steps <= 2 ? 2 : (steps <= 4 || !bf16) ? 4 : 8;
+  if (with_text) {
+    AttnArgs t{};
+    fill_text_args(p, pl, ws, t);
+    const dim3 tg = text_grid(p);
+    const int text_blocks = tg.x * tg.y * tg.z, row_blocks = rows.x;
+    const dim3 grid(text_blocks + row_blocks * p.B);
+    auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid, block, 0, s, a, t, text_blocks, (int)tg.x, (int)tg.y, row_blocks); };
+    if (bf16) { if (kb == 2) go(rows_text_kernel<bf16_t, 2>); else if (kb == 4) go(rows_text_kernel<bf16_t, 4>); else go(rows_text_kernel<bf16_t, 8>); }
+    else { if (kb == 2) go(rows_text_kernel<float, 2>); else go(rows_text_kernel<float, 4>); }
+  } else if (bf16) {
+    if (kb == 2) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 2>), rows, block, 0, s, a);
+    else if (kb == 4) hipLaunchKernelGGL((row_norm_kernel<bf16_t, 4>), rows, block, 0, s, a);
     else hipLaunchKernelGGL((row_norm_kernel<bf16_t, 8>), rows, block, 0, s, a);
   } else {
-    if (steps <= 2) hipLaunchKernelGGL((row_norm_kernel<float, 2>), rows, block, 0, s, a);
+    if (kb == 2) hipLaunchKernelGGL((row_norm_kernel<float, 2>), rows, block, 0, s, a);
     else hipLaunchKernelGGL((row_norm_kernel<float, 4>), rows, block, 0, s, a);
   }
   if (!a.want_sim && !a.want_eq) return;
-  dim3 cgrid(pl.f_chunks, (pl.Df + kColSpan - 1) / kColSpan, p.B);
-  if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);
-  else hipLaunchKernelGGL(col_sum_kernel<float>, cgrid, block, 0, s, a);
+  const int spans = (pl.Df + kColSpan - 1) / kColSpan;
+  if (with_text) {
+    TextStatsArgs t{};
+    fill_text_stats(p, pl, ws, t);
+    const int stat_blocks = text_stats_blocks(t, with_cmax);
+    const dim3 grid(stat_blocks * p.B + pl.f_chunks * spans * p.B);
+    if (bf16) hipLaunchKernelGGL(colsum_stats_kernel<bf16_t>, grid, block, 0, s, a, t, stat_blocks, spans);
+    else hipLaunchKernelGGL(colsum_stats_kernel<float>, grid, block, 0, s, a, t, stat_blocks, spans);
+  } else {
+    dim3 cgrid(pl.f_chunks, spans, p.B);
+    if (bf16) hipLaunchKernelGGL(col_sum_kernel<bf16_t>, cgrid, block, 0, s, a);
+    else hipLaunchKernelGGL(col_sum_kernel<float>, cgrid, block, 0, s, a);
+  }
   hipLaunchKernelGGL(col_mean_kernel, dim3((pl.Df + 255) / 256, p.B), block, 0, s, a);
   const dim3 trows((p.N + kFtRows - 1) / kFtRows, p.B);
   if (bf16) hipLaunchKernelGGL(feature_terms_kernel<bf16_t>, trows, block, 0, s, a);

@@ -13,6 +13,7 @@
 // (their result does not depend on the order of arrival).
 #include "common.hpp"
 #include "feature_rows.hpp"
+#include "text_stats.hpp"
 
 namespace ficoco {
 
@@ -641,55 +642,7 @@ __global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec,
   if (sem_vec) out_g[b * N + i] = vec_head_mean(sem_vec, dtype, b, H, N, i);
 }
 
-// From 32 text queries on: the task term of Eq. 3, the mean of a token's text profile, is formed
-// by one wavefront per token on the whole chip (lane sums over k = lane, lane + 64, ..., then a
-// fixed tree), so the per-image workgroup of select_kernel reads one value.  A thread of that
-// workgroup walking its token's profile touches a cache line per lane and load, all on one
-// compute unit (64 queries: 17 us for the select kernel against 9 + 4 us this way).
-// In the fused step the same launch also forms cmax[b][k], the maximum over the visual tokens of
-// profile entry k (the bound of Eq. 4's indirect term that the correlate stage needs): the
-// workgroups behind the first `mean_blocks` take 64 text queries of one image each, thread
-// (k, g) walking the tokens g, g + 4, ... with 16 independent loads per round, the four token
-// groups meeting in LDS.  Both are short chains of dependent loads on few workgroups; in one
-// launch they overlap instead of following each other.
-__global__ __launch_bounds__(256) void text_stats_kernel(const double* __restrict__ ttext, int N, int M,
-                                                         double* __restrict__ out_g, double* __restrict__ cmax,
-                                                         int mean_blocks) {
-  __shared__ double part[256];
-  const int64_t b = blockIdx.y;
-  if ((int)blockIdx.x < mean_blocks) {
-    const int lane = threadIdx.x % kWave;
-    const int i = blockIdx.x * (blockDim.x / kWave) + threadIdx.x / kWave;
-    if (i >= N) return;      // whole wavefront leaves together
-    const double* p = ttext + (b * N + i) * M;
-    double acc = 0.0;
-    for (int k = lane; k < M; k += kWave) acc += p[k];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off, kWave);
-    if (lane == 0) out_g[b * N + i] = acc / (double)M;
-    return;
-  }
-  const int tid = threadIdx.x;
-  const int k = ((int)blockIdx.x - mean_blocks) * 64 + tid % 64, g = tid / 64;
-  double mx = 0.0;
-  if (k < M) {
-    int i = g;
-    for (; i + 4 * 15 < N; i += 4 * 16) {              // 16 independent loads per round
-      double v[16];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) v[u] = ttext[(b * N + i + 4 * u) * M + k];
-#pragma unroll
-      for (int u = 0; u < 16; ++u) mx = v[u] > mx ? v[u] : mx;
-    }
-    for (; i < N; i += 4) { const double v = ttext[(b * N + i) * M + k]; mx = v > mx ? v : mx; }
-  }
-  part[tid] = mx;
-  __syncthreads();
-  if (g == 0 && k < M) {
-    for (int q = 1; q < 4; ++q) mx = part[q * 64 + tid] > mx ? part[q * 64 + tid] : mx;
-    cmax[b * M + k] = mx;
-  }
-}
+__global__ __launch_bounds__(256) void text_stats_kernel(TextStatsArgs a) { text_stats_block(a, blockIdx.x, blockIdx.y); }
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
   const size_t cells = penalty ? (size_t)p.grid_g * p.grid_h * p.grid_w : 0;
@@ -697,9 +650,17 @@ static size_t select_lds(const ficoco_problem& p, bool penalty) {
   return (size_t)p.N * sizeof(double) + (2 * kSelectThreads + 256 + 8 + (p.N + 31) / 32 + (cells > wide ? cells : wide)) * sizeof(int);
 }
 
+void fill_text_stats(const ficoco_problem& p, const Plan& pl, char* ws, TextStatsArgs& t) {
+  t.ttext = (const double*)(ws + pl.ttext);
+  t.N = p.N; t.M = p.M;
+  t.out_g = (double*)(ws + pl.fterm2);
+  t.cmax = (double*)(ws + pl.cmax);
+  t.mean_blocks = (p.N + 3) / 4;
+}
+
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
                    bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
-                   hipStream_t s) {
+                   hipStream_t s, bool text_stats_done) {
   SelectArgs a{};
   a.N = p.N; a.H = p.H; a.M = p.M; a.n_chunks = pl.n_chunks; a.dtype = p.dtype;
   a.red_src = p.red_src; a.sem_src = p.sem_src;
@@ -730,10 +691,12 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   if (do_score && p.sem_src == FICOCO_G_TEXT_ATTN && p.M >= 32) {
     // the equivalent-token buffer is free in FiCoCo-L; the column maxima ride along in the fused
     // step (text_stats_in_score), a staged correlate call forms them itself
-    const bool with_cmax = do_filter && text_stats_in_score(p);
-    const int mean_blocks = (p.N + 3) / 4;
-    hipLaunchKernelGGL(text_stats_kernel, dim3(mean_blocks + (with_cmax ? (p.M + 63) / 64 : 0), p.B), dim3(256), 0, s,
-                       a.ttext, p.N, p.M, (double*)(ws + pl.fterm2), (double*)(ws + pl.cmax), mean_blocks);
+    if (!text_stats_done) {
+      const bool with_cmax = do_filter && text_stats_in_score(p);
+      TextStatsArgs t{};
+      fill_text_stats(p, pl, ws, t);
+      hipLaunchKernelGGL(text_stats_kernel, dim3(text_stats_blocks(t, with_cmax), p.B), dim3(256), 0, s, t);
+    }
     a.sem_src = FICOCO_G_EQ_TOKEN;             // "read the precomputed term"
   }
   if (do_score && (p.red_src == FICOCO_R_SIM_MEAN || p.sem_src == FICOCO_G_EQ_TOKEN)) {
@@ -798,13 +761,13 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   }
 }
 
-void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s) {
-  launch_select(p, pl, ws, scores, true, false, nullptr, nullptr, nullptr, s);
+void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, hipStream_t s, bool text_stats_done) {
+  launch_select(p, pl, ws, scores, true, false, nullptr, nullptr, nullptr, s, text_stats_done);
 }
 
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s) {
-  launch_select(p, pl, ws, const_cast<double*>(scores), false, true, discard_idx, keep_idx, nullptr, s);
+  launch_select(p, pl, ws, const_cast<double*>(scores), false, true, discard_idx, keep_idx, nullptr, s, false);
 }
 
 }  // namespace ficoco

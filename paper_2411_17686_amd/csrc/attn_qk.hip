@@ -53,7 +53,8 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
   if (logical >= total) return;
   const int tile = logical % a.n_tiles;
   const int64_t b = logical / a.n_tiles;
-  const int lane = threadIdx.x % kWave, wv = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);   // the same in every lane: scalar, so tests on it are branches
   const int l16 = lane % 16, lg = lane / 16;
   const float NEG = -__builtin_huge_valf();
   const int key_base = wv * kQkKB * 16;             // first key of this wavefront
@@ -103,7 +104,9 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
     // last head the last one is loaded again)
     load_head(min(h + 1, a.H - 1));
     issue_fence();                  // the loads go out here, not where the next head first uses them
-    // keys past the block read as -inf (only the last blocks can hold any: a uniform test per block)
+    // keys past the block read as -inf (only the last wavefronts can hold any: a scalar test, so the
+    // others skip the selects altogether)
+    if (key_base + kQkKB * 16 > a.n) {
 #pragma unroll
     for (int kb = 0; kb < kQkKB; ++kb) {
       if (key_base + (kb + 1) * 16 > a.n) {
@@ -114,6 +117,7 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
             for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
           }
       }
+    }
     }
     // Softmax of every query's row with ONE exchange between the wavefronts: a wavefront takes the
     // exponentials relative to a reference at or above the maximum of ITS keys (the maximum in

@@ -63,38 +63,48 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   const int k_begin = split * a.st_per_split * kGK;
   const int k_len = max(min(a.Df - k_begin, a.st_per_split * kGK), 0);
   // loader: the stage is 128 rows x kGK/8 chunks of 8 elements per operand; thread -> kGChunks chunks each
-  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df + k_begin;
+  // Every load of the loader is unconditional: a row past the block reads token 0 and a chunk past
+  // the K range reads the row's first chunk (both valid addresses: N >= 1, Df >= 8), and what was
+  // read is cleared when it is put into LDS.  Under a per-lane condition the loads sit in
+  // branches, and the compiler then waits for ALL outstanding loads before it issues the next
+  // stage's -- which leaves one stage in flight instead of kGStages and the wait at the head of
+  // every stage.
+  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df;
   int lrow[kGChunks], lkc[kGChunks];
   const bf16_t* srcA[kGChunks];
   const bf16_t* srcB[kGChunks];
+  bool okA[kGChunks], okB[kGChunks];
 #pragma unroll
   for (int u = 0; u < kGChunks; ++u) {
     const int q = tid + 256 * u;
     lrow[u] = q / (kGK / 8);
     lkc[u] = (q % (kGK / 8)) * 8;
-    srcA[u] = rowA[lrow[u]] >= 0 ? Xb + (int64_t)rowA[lrow[u]] * a.Df + lkc[u] : nullptr;
-    srcB[u] = rowB[lrow[u]] >= 0 ? Xb + (int64_t)rowB[lrow[u]] * a.Df + lkc[u] : nullptr;
+    okA[u] = rowA[lrow[u]] >= 0;
+    okB[u] = rowB[lrow[u]] >= 0;
+    srcA[u] = Xb + (int64_t)max(rowA[lrow[u]], 0) * a.Df;
+    srcB[u] = Xb + (int64_t)max(rowB[lrow[u]], 0) * a.Df;
   }
   // Register ring of kGStages K-stages in flight per thread: a stage is fetched kGStages
   // iterations before it is stashed into LDS.
   uint4 ra[kGStages][kGChunks], rb[kGStages][kGChunks];
   const int n_st = (k_len + kGK - 1) / kGK;
+  auto in_range = [&](int st, int u) { return st < n_st && st * kGK + lkc[u] + 8 <= k_len; };   // Df is a multiple of 8 on this path
   auto fetch = [&](int slot, int st) {
-    const int k0 = st * kGK;
 #pragma unroll
     for (int u = 0; u < kGChunks; ++u) {
-      const bool in = st < n_st && k0 + lkc[u] + 8 <= k_len;   // Df is a multiple of 8 on this path
-      ra[slot][u] = make_uint4(0, 0, 0, 0);
-      rb[slot][u] = make_uint4(0, 0, 0, 0);
-      if (in && srcA[u]) __builtin_memcpy(&ra[slot][u], srcA[u] + k0, 16);
-      if (in && srcB[u]) __builtin_memcpy(&rb[slot][u], srcB[u] + k0, 16);
+      const int k = in_range(st, u) ? k_begin + st * kGK + lkc[u] : 0;
+      __builtin_memcpy(&ra[slot][u], srcA[u] + k, 16);
+      __builtin_memcpy(&rb[slot][u], srcB[u] + k, 16);
     }
   };
-  auto stash = [&](int slot, int buf) {
+  auto stash = [&](int slot, int buf, int st) {      // st: the stage that slot holds
 #pragma unroll
     for (int u = 0; u < kGChunks; ++u) {
-      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = ra[slot][u];
-      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = rb[slot][u];
+      const bool in = in_range(st, u);
+      // (a value on the other side of each choice: between two named objects the compiler picks
+      // an address and reads through it, which puts the ring into scratch memory)
+      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = in && okA[u] ? ra[slot][u] : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = in && okB[u] ? rb[slot][u] : make_uint4(0, 0, 0, 0);
     }
   };
 
@@ -110,7 +120,7 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   const int frow = lane % 32, fk = (lane / 32) * 8;   // fragment: row / column within the block, k offset
 #pragma unroll
   for (int sl = 0; sl < kGStages; ++sl) fetch(sl, sl);
-  stash(0, 0);
+  stash(0, 0, 0);
   __syncthreads();
   int cur = 0;
   for (int base = 0; base < n_st; base += kGStages) {
@@ -135,7 +145,7 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
               acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
         if (it + 1 < n_st) {
-          stash((sl + 1) % kGStages, cur ^ 1);  // the other buffer was last read before the previous barrier
+          stash((sl + 1) % kGStages, cur ^ 1, it + 1);  // the other buffer was last read before the previous barrier
           __syncthreads();
           cur ^= 1;
         }
@@ -206,7 +216,10 @@ __global__ __launch_bounds__(kG2Threads) void gram_tile2_kernel(GramArgs a) {
   constexpr int kSlotsA = kG2M * kG2Chunks / kG2Threads, kSlotsB = kG2N * kG2Chunks / kG2Threads;
   constexpr int kSlots = kSlotsA + kSlotsB;
   static_assert(kSlotsA * kG2Threads == kG2M * kG2Chunks && kSlotsB * kG2Threads == kG2N * kG2Chunks, "whole slots");
+  // (unconditional loads from addresses that are always valid, cleared on the way into LDS: see the
+  // loader of gram_tile_kernel)
   const bf16_t* src[kSlots];
+  bool row_ok[kSlots];
   int lds_at[kSlots], kc[kSlots];
 #pragma unroll
   for (int u = 0; u < kSlots; ++u) {
@@ -216,24 +229,22 @@ __global__ __launch_bounds__(kG2Threads) void gram_tile2_kernel(GramArgs a) {
     const int tok = aop ? rowA[row] : rowB[row];
     kc[u] = chunk * 8;
     lds_at[u] = g2_slot(row, chunk);
-    src[u] = tok >= 0 ? Xb + (int64_t)tok * a.Df + chunk * 8 : nullptr;
+    row_ok[u] = tok >= 0;
+    src[u] = Xb + (int64_t)max(tok, 0) * a.Df;
   }
   uint4 rg[kGStages][kSlots];
   const int n_st = (a.Df + kG2K - 1) / kG2K;
+  auto in_range = [&](int st, int u) { return st < n_st && st * kG2K + kc[u] + 8 <= a.Df; };   // Df is a multiple of 8 on this path
   auto fetch = [&](int slot, int st) {
-    const int k0 = st * kG2K;
 #pragma unroll
-    for (int u = 0; u < kSlots; ++u) {
-      const bool in = st < n_st && k0 + kc[u] + 8 <= a.Df;   // Df is a multiple of 8 on this path
-      rg[slot][u] = make_uint4(0, 0, 0, 0);
-      if (in && src[u]) __builtin_memcpy(&rg[slot][u], src[u] + k0, 16);
-    }
+    for (int u = 0; u < kSlots; ++u) __builtin_memcpy(&rg[slot][u], src[u] + (in_range(st, u) ? st * kG2K + kc[u] : 0), 16);
   };
-  auto stash = [&](int slot, int buf) {
+  auto stash = [&](int slot, int buf, int st) {      // st: the stage that slot holds
 #pragma unroll
     for (int u = 0; u < kSlots; ++u) {
-      if (u < kSlotsA) Abuf[buf * kG2M * kG2Chunks + lds_at[u]] = rg[slot][u];
-      else Bbuf[buf * kG2N * kG2Chunks + lds_at[u]] = rg[slot][u];
+      const uint4 v = row_ok[u] && in_range(st, u) ? rg[slot][u] : make_uint4(0, 0, 0, 0);
+      if (u < kSlotsA) Abuf[buf * kG2M * kG2Chunks + lds_at[u]] = v;
+      else Bbuf[buf * kG2N * kG2Chunks + lds_at[u]] = v;
     }
   };
 
@@ -249,7 +260,7 @@ __global__ __launch_bounds__(kG2Threads) void gram_tile2_kernel(GramArgs a) {
   const int frow = lane % 32, fch = lane / 32;     // fragment: row within the block, 16-byte chunk within a 16-feature step
 #pragma unroll
   for (int sl = 0; sl < kGStages; ++sl) fetch(sl, sl);
-  stash(0, 0);
+  stash(0, 0, 0);
   __syncthreads();
   int cur = 0;
   for (int base = 0; base < n_st; base += kGStages) {
@@ -278,7 +289,7 @@ __global__ __launch_bounds__(kG2Threads) void gram_tile2_kernel(GramArgs a) {
               acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
         if (it + 1 < n_st) {
-          stash((sl + 1) % kGStages, cur ^ 1);  // the other buffer was last read before the previous barrier
+          stash((sl + 1) % kGStages, cur ^ 1, it + 1);  // the other buffer was last read before the previous barrier
           __syncthreads();
           cur ^= 1;
         }

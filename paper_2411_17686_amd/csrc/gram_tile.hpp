@@ -63,48 +63,38 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   const int k_begin = split * a.st_per_split * kGK;
   const int k_len = max(min(a.Df - k_begin, a.st_per_split * kGK), 0);
   // loader: the stage is 128 rows x kGK/8 chunks of 8 elements per operand; thread -> kGChunks chunks each
-  // Every load of the loader is unconditional: a row past the block reads token 0 and a chunk past
-  // the K range reads the row's first chunk (both valid addresses: N >= 1, Df >= 8), and what was
-  // read is cleared when it is put into LDS.  Under a per-lane condition the loads sit in
-  // branches, and the compiler then waits for ALL outstanding loads before it issues the next
-  // stage's -- which leaves one stage in flight instead of kGStages and the wait at the head of
-  // every stage.
-  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df;
+  const bf16_t* Xb = a.xhat + b * a.N * (int64_t)a.Df + k_begin;
   int lrow[kGChunks], lkc[kGChunks];
   const bf16_t* srcA[kGChunks];
   const bf16_t* srcB[kGChunks];
-  bool okA[kGChunks], okB[kGChunks];
 #pragma unroll
   for (int u = 0; u < kGChunks; ++u) {
     const int q = tid + 256 * u;
     lrow[u] = q / (kGK / 8);
     lkc[u] = (q % (kGK / 8)) * 8;
-    okA[u] = rowA[lrow[u]] >= 0;
-    okB[u] = rowB[lrow[u]] >= 0;
-    srcA[u] = Xb + (int64_t)max(rowA[lrow[u]], 0) * a.Df;
-    srcB[u] = Xb + (int64_t)max(rowB[lrow[u]], 0) * a.Df;
+    srcA[u] = rowA[lrow[u]] >= 0 ? Xb + (int64_t)rowA[lrow[u]] * a.Df + lkc[u] : nullptr;
+    srcB[u] = rowB[lrow[u]] >= 0 ? Xb + (int64_t)rowB[lrow[u]] * a.Df + lkc[u] : nullptr;
   }
   // Register ring of kGStages K-stages in flight per thread: a stage is fetched kGStages
   // iterations before it is stashed into LDS.
   uint4 ra[kGStages][kGChunks], rb[kGStages][kGChunks];
   const int n_st = (k_len + kGK - 1) / kGK;
-  auto in_range = [&](int st, int u) { return st < n_st && st * kGK + lkc[u] + 8 <= k_len; };   // Df is a multiple of 8 on this path
   auto fetch = [&](int slot, int st) {
+    const int k0 = st * kGK;
 #pragma unroll
     for (int u = 0; u < kGChunks; ++u) {
-      const int k = in_range(st, u) ? k_begin + st * kGK + lkc[u] : 0;
-      __builtin_memcpy(&ra[slot][u], srcA[u] + k, 16);
-      __builtin_memcpy(&rb[slot][u], srcB[u] + k, 16);
+      const bool in = st < n_st && k0 + lkc[u] + 8 <= k_len;   // Df is a multiple of 8 on this path
+      ra[slot][u] = make_uint4(0, 0, 0, 0);
+      rb[slot][u] = make_uint4(0, 0, 0, 0);
+      if (in && srcA[u]) __builtin_memcpy(&ra[slot][u], srcA[u] + k0, 16);
+      if (in && srcB[u]) __builtin_memcpy(&rb[slot][u], srcB[u] + k0, 16);
     }
   };
-  auto stash = [&](int slot, int buf, int st) {      // st: the stage that slot holds
+  auto stash = [&](int slot, int buf) {
 #pragma unroll
     for (int u = 0; u < kGChunks; ++u) {
-      const bool in = in_range(st, u);
-      // (a value on the other side of each choice: between two named objects the compiler picks
-      // an address and reads through it, which puts the ring into scratch memory)
-      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = in && okA[u] ? ra[slot][u] : make_uint4(0, 0, 0, 0);
-      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = in && okB[u] ? rb[slot][u] : make_uint4(0, 0, 0, 0);
+      *reinterpret_cast<uint4*>(&As[buf][lrow[u] * kGStride + lkc[u]]) = ra[slot][u];
+      *reinterpret_cast<uint4*>(&Bs[buf][lrow[u] * kGStride + lkc[u]]) = rb[slot][u];
     }
   };
 
@@ -120,7 +110,7 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
   const int frow = lane % 32, fk = (lane / 32) * 8;   // fragment: row / column within the block, k offset
 #pragma unroll
   for (int sl = 0; sl < kGStages; ++sl) fetch(sl, sl);
-  stash(0, 0, 0);
+  stash(0, 0);
   __syncthreads();
   int cur = 0;
   for (int base = 0; base < n_st; base += kGStages) {
@@ -145,7 +135,7 @@ __global__ __launch_bounds__(256) void gram_tile_kernel(GramArgs a) {
               acc[mi][ni] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(fa[mi], fb[ni], acc[mi][ni], 0, 0, 0);
         }
         if (it + 1 < n_st) {
-          stash((sl + 1) % kGStages, cur ^ 1, it + 1);  // the other buffer was last read before the previous barrier
+          stash((sl + 1) % kGStages, cur ^ 1);  // the other buffer was last read before the previous barrier
           __syncthreads();
           cur ^= 1;
         }
@@ -216,8 +206,13 @@ __global__ __launch_bounds__(kG2Threads) void gram_tile2_kernel(GramArgs a) {
   constexpr int kSlotsA = kG2M * kG2Chunks / kG2Threads, kSlotsB = kG2N * kG2Chunks / kG2Threads;
   constexpr int kSlots = kSlotsA + kSlotsB;
   static_assert(kSlotsA * kG2Threads == kG2M * kG2Chunks && kSlotsB * kG2Threads == kG2N * kG2Chunks, "whole slots");
-  // (unconditional loads from addresses that are always valid, cleared on the way into LDS: see the
-  // loader of gram_tile_kernel)
+  // Every load of the loader is unconditional: a row past the block reads token 0 and a chunk past
+  // the K range reads the row's first chunk (both valid addresses: N >= 1, Df >= 8), and what was
+  // read is cleared when it is put into LDS.  Under a per-lane condition the loads sit in
+  // branches, and the compiler then waits for ALL outstanding loads before it issues the next
+  // stage's -- one stage in flight instead of two, and the wait at the head of every stage
+  // (measured here: 33-35 -> 30-33 us; the 128 x 128 kernel above, with four loads per stage, is
+  // no faster for it and keeps its conditional loads).
   const bf16_t* src[kSlots];
   bool row_ok[kSlots];
   int lds_at[kSlots], kc[kSlots];

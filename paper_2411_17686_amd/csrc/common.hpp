@@ -184,6 +184,35 @@ __device__ __forceinline__ void fma_raw(const Raw8<float>& r, double w, double (
 // which turns a batch of loads in flight back into one memory round trip after the other.
 __device__ __forceinline__ void issue_fence() { __builtin_amdgcn_sched_barrier(0); }
 
+// ---- reductions over the 64 lanes of a wavefront ----------------------------------------------------
+// Every lane must be active and every lane gets the result.  The first four steps pair lanes inside
+// a row of 16 with data-parallel-primitive moves (lane ^ 1, lane ^ 2, then the mirror images inside
+// 8 and inside 16 lanes, which reach the other half because the halves are uniform by then), the
+// four row results are read out by lane and combined as (r0 op r1) op (r2 op r3): a fixed tree,
+// and no trip through the LDS permute path (a butterfly of six of those costs several hundred
+// cycles in kernels that are chains of dependent steps).  `op` must be commutative.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, false); }
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float x) { return __int_as_float(dpp_move<CTRL>(__float_as_int(x))); }
+template <int CTRL>
+__device__ __forceinline__ double dpp_move(double x) {
+  return __hiloint2double(dpp_move<CTRL>(__double2hiint(x)), dpp_move<CTRL>(__double2loint(x)));
+}
+__device__ __forceinline__ int lane_value(int x, int l) { return __builtin_amdgcn_readlane(x, l); }
+__device__ __forceinline__ float lane_value(float x, int l) { return __int_as_float(lane_value(__float_as_int(x), l)); }
+__device__ __forceinline__ double lane_value(double x, int l) {
+  return __hiloint2double(lane_value(__double2hiint(x), l), lane_value(__double2loint(x), l));
+}
+template <typename T, typename F>
+__device__ __forceinline__ T wave_reduce(T v, F op) {
+  v = op(v, dpp_move<0xB1>(v));      // quad_perm [1,0,3,2]: lane ^ 1
+  v = op(v, dpp_move<0x4E>(v));      // quad_perm [2,3,0,1]: lane ^ 2
+  v = op(v, dpp_move<0x141>(v));     // mirror inside 8 lanes
+  v = op(v, dpp_move<0x140>(v));     // mirror inside 16 lanes
+  return op(op(lane_value(v, 0), lane_value(v, 16)), op(lane_value(v, 32), lane_value(v, 48)));
+}
+
 // all bits cleared (eight zeros) unless `keep`: selects, no branch
 __device__ __forceinline__ void keep_raw_if(Raw8<bf16_t>& r, bool keep) {
   r.a.x = keep ? r.a.x : 0u; r.a.y = keep ? r.a.y : 0u; r.a.z = keep ? r.a.z : 0u; r.a.w = keep ? r.a.w : 0u;

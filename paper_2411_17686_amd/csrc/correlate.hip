@@ -76,17 +76,13 @@ __device__ __forceinline__ double corr_value(const CorrArgs& a, int64_t b, int i
 }
 
 __device__ __forceinline__ double wave_max(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) {
-    const double o = __shfl_xor(v, off, kWave);
-    v = o > v ? o : v;
-  }
-  return v;
+  return wave_reduce(v, [](double x, double y) { return y > x ? y : x; });
+}
+__device__ __forceinline__ float wave_max(float v) {
+  return wave_reduce(v, [](float x, float y) { return y > x ? y : x; });
 }
 __device__ __forceinline__ int wave_sum(int v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+  return wave_reduce(v, [](int x, int y) { return x + y; });
 }
 
 __device__ __forceinline__ uint64_t order_key(double x) {   // monotone double -> uint64
@@ -266,9 +262,7 @@ __global__ __launch_bounds__(256) void corr_rows_kernel(CorrArgs a) {
 constexpr int kCandCap = 64;
 
 __device__ __forceinline__ double wave_sum_f64(double v) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+  return wave_reduce(v, [](double x, double y) { return x + y; });
 }
 
 // exact C[i][j], the whole wavefront working on one pair (all lanes return the value)
@@ -533,9 +527,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
   }
   float lambda = NEGF;
   for (int r = 0; r < a.sel_m; ++r) {
-    float mx = top[0];
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) { const float o = __shfl_xor(mx, off, kWave); mx = o > mx ? o : mx; }
+    const float mx = wave_max(top[0]);
     const unsigned long long who = __ballot(top[0] == mx);
     if (lane == __ffsll(who) - 1) {
 #pragma unroll
@@ -715,9 +707,7 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
     float cur = NEGF;
 #pragma unroll
     for (int k = 0; k < MC; ++k) cur = k == head ? top[k] : cur;
-    float mx = cur;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) { const float o = __shfl_xor(mx, off, kWave); mx = o > mx ? o : mx; }
+    const float mx = wave_max(cur);
     const unsigned long long who = __ballot(cur == mx);
     if (lane == __ffsll(who) - 1) ++head;
     if (r == 0 || mx < vf) n_gt = r;
@@ -754,9 +744,7 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
 #pragma unroll
       for (int k = 0; k < MC; ++k)
         if (open[k] && topj[k] < mine) { mine = topj[k]; mk = k; }
-      int mn = mine;
-#pragma unroll
-      for (int off = 32; off > 0; off >>= 1) mn = min(mn, __shfl_xor(mn, off, kWave));
+      const int mn = wave_reduce(mine, [](int x, int y) { return y < x ? y : x; });
       if (mn == 0x7fffffff) break;                               // uniform
       const bool owner = mine == mn;
       float vo = 0.0f;

@@ -212,6 +212,20 @@ __device__ __forceinline__ T wave_reduce(T v, F op) {
   v = op(v, dpp_move<0x140>(v));     // mirror inside 16 lanes
   return op(op(lane_value(v, 0), lane_value(v, 16)), op(lane_value(v, 32), lane_value(v, 48)));
 }
+// Inclusive prefix sum over the lanes of a wavefront (every lane active): four shifted adds inside
+// each row of 16 (a lane whose source would lie before its row adds zero), then the totals of
+// the rows before a lane's own, read out of lanes 15, 31 and 47.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move_or_zero(int x) { return __builtin_amdgcn_update_dpp(0, x, CTRL, 0xF, 0xF, true); }
+__device__ __forceinline__ int wave_scan_inclusive(int v) {
+  v += dpp_move_or_zero<0x111>(v);   // row_shr:1
+  v += dpp_move_or_zero<0x112>(v);   // row_shr:2
+  v += dpp_move_or_zero<0x114>(v);   // row_shr:4
+  v += dpp_move_or_zero<0x118>(v);   // row_shr:8
+  const int r0 = lane_value(v, 15), r1 = lane_value(v, 31), r2 = lane_value(v, 47);
+  const int row = (int)(threadIdx.x % kWave) / 16;
+  return v + (row >= 1 ? r0 : 0) + (row >= 2 ? r1 : 0) + (row >= 3 ? r2 : 0);
+}
 
 // all bits cleared (eight zeros) unless `keep`: selects, no branch
 __device__ __forceinline__ void keep_raw_if(Raw8<bf16_t>& r, bool keep) {
@@ -277,12 +291,7 @@ __host__ __device__ __forceinline__ int xcd_padded_total(int total) {
 // sum.  scratch: at least blockDim.x / 64 ints.
 __device__ __forceinline__ int block_scan_inclusive(int v, int* scratch, int* total) {
   const int tid = threadIdx.x, lane = tid % kWave, wv = tid / kWave, nw = blockDim.x / kWave;
-  int incl = v;
-#pragma unroll
-  for (int off = 1; off < kWave; off <<= 1) {
-    const int t = __shfl_up(incl, off, kWave);
-    if (lane >= off) incl += t;
-  }
+  const int incl = wave_scan_inclusive(v);
   __syncthreads();
   if (lane == kWave - 1) scratch[wv] = incl;
   __syncthreads();

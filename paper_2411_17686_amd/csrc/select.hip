@@ -143,8 +143,8 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
 #pragma unroll
       for (int c = 0; c < kBinCopies / 4; ++c)           // rotated by the bin so that neighbouring bins read different banks
         sum += hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
-      sum += __shfl_xor(sum, 1, kWave);
-      sum += __shfl_xor(sum, 2, kWave);
+      sum += dpp_move<0xB1>(sum);                          // lane ^ 1
+      sum += dpp_move<0x4E>(sum);                          // lane ^ 2
       if (part == 0) hist[bin] = sum;
     } else {
       if (tid < 256) hist[tid] = 0;
@@ -161,13 +161,8 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
 #pragma unroll
       for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
       const int lsum = h[0] + h[1] + h[2] + h[3];
-      int incl = lsum;                                   // sum over lanes >= this one
-#pragma unroll
-      for (int off = 1; off < kWave; off <<= 1) {
-        const int t = __shfl_down(incl, off, kWave);
-        if (tid + off < kWave) incl += t;
-      }
-      int above = incl - lsum;                           // tokens in bins above this lane's
+      const int upto = wave_scan_inclusive(lsum);        // lanes 0 .. this one; lane 63 holds the total
+      int above = lane_value(upto, kWave - 1) - upto;    // tokens in bins above this lane's
       if (above < need && need <= above + lsum) {        // exactly one lane
 #pragma unroll
         for (int k = 3; k >= 0; --k) {

@@ -213,7 +213,7 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
     while (hit) {
       const int l = __ffsll(hit) - 1;
       hit &= hit - 1;
-      const double cl = __shfl(c, l, kWave);
+      const double cl = lane_value(c, l);
       denom += cl;
       if (a.k_max <= kWave) {
         if (lane == cnt) { my_tgt = base + l; my_c = cl; }
@@ -567,7 +567,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     bool ok[kCandBatch];
 #pragma unroll
     for (int q = 0; q < kCandBatch; ++q) {
-      const int jq = __shfl(myj, min(c + q, n_cand - 1), kWave);
+      const int jq = lane_value(myj, min(c + q, n_cand - 1));
       ok[q] = (unsigned)jq < (unsigned)a.N;
       j[q] = ok[q] ? jq : i;                   // a valid row to read; the value is dropped
     }
@@ -604,7 +604,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
   while (hit) {                       // ascending target order
     const int l = __ffsll(hit) - 1;
     hit &= hit - 1;
-    denom += __shfl(myv, l, kWave);
+    denom += lane_value(myv, l);
   }
   const bool live = denom > 0.0;
   const int stored = cnt < a.k_max ? cnt : a.k_max;
@@ -753,7 +753,7 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
         if (owner && k == mk) { vo = top[k]; open[k] = false; }
       }
       const int l = __ffsll(__ballot(owner)) - 1;
-      const double cl = (double)__shfl(vo, l, kWave);
+      const double cl = (double)lane_value(vo, l);
       const bool is_eq = cl == tau;
       const bool take = cl > tau || (is_eq && ties_seen < tie_quota);
       ties_seen += is_eq ? 1 : 0;
@@ -783,8 +783,8 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
       while (hit) {
         const int l = __ffsll(hit) - 1;
         hit &= hit - 1;
-        const double cl = __shfl(c, l, kWave);
-        const int tl = __shfl(sv[u], l, kWave);
+        const double cl = lane_value(c, l);
+        const int tl = lane_value(sv[u], l);
         denom += cl;
         if (lane == cnt) { my_tgt = tl; my_c = cl; }
         ++cnt;

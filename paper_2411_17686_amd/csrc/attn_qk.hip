@@ -125,31 +125,62 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
     // exchanged, and its probabilities are its exponentials times 2^(own reference - largest
     // reference) / row sum.  scale_log2e > 0.
     const int par = h & 1;          // two sets of slots: the next head's writes do not wait for this head's reads
-    float mc[kQkQB];
+    // The three query blocks go through every stage side by side (maxima, their two exchanges
+    // between the lane groups, exponentials, sums, their exchanges, one write): taken one block
+    // after the other, each of the twelve lane exchanges of a head waits out its own trip
+    // through the permute path.
+    float mc[kQkQB], mw[kQkQB], lw[kQkQB];
     bool any_key[kQkQB];
 #pragma unroll
     for (int qb = 0; qb < kQkQB; ++qb) {
-      float mw = NEG;
+      mw[qb] = NEG;
 #pragma unroll
       for (int kb = 0; kb < kQkKB; ++kb)
 #pragma unroll
-        for (int v = 0; v < 4; ++v) mw = fmaxf(mw, S[kb][qb][v]);
-      mw = fmaxf(mw, __shfl_xor(mw, 16, kWave));
-      mw = fmaxf(mw, __shfl_xor(mw, 32, kWave));
-      any_key[qb] = mw > NEG;                       // a wavefront whose keys all lie past the block has none
-      mc[qb] = any_key[qb] ? ceilf(mw * a.scale_log2e) : 0.0f;      // a whole number: rescaling between wavefronts is exact
-      float lw = 0.0f;
+        for (int v = 0; v < 4; ++v) mw[qb] = fmaxf(mw[qb], S[kb][qb][v]);
+    }
+    {
+      float o[kQkQB];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(mw[qb], 16, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) mw[qb] = fmaxf(mw[qb], o[qb]);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(mw[qb], 32, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) mw[qb] = fmaxf(mw[qb], o[qb]);
+    }
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb) {
+      any_key[qb] = mw[qb] > NEG;                   // a wavefront whose keys all lie past the block has none
+      mc[qb] = any_key[qb] ? ceilf(mw[qb] * a.scale_log2e) : 0.0f;  // a whole number: rescaling between wavefronts is exact
+      lw[qb] = 0.0f;
 #pragma unroll
       for (int kb = 0; kb < kQkKB; ++kb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const float e = __builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -mc[qb]));
           S[kb][qb][v] = e;
-          lw += e;
+          lw[qb] += e;
         }
-      lw += __shfl_xor(lw, 16, kWave);
-      lw += __shfl_xor(lw, 32, kWave);
-      if (lg == 0) { xmax[par][wv][qb * 16 + l16] = any_key[qb] ? mc[qb] : NEG; xsum[par][wv][qb * 16 + l16] = lw; }
+    }
+    {
+      float o[kQkQB];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(lw[qb], 16, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) lw[qb] += o[qb];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(lw[qb], 32, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) lw[qb] += o[qb];
+    }
+    if (lg == 0) {
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        xmax[par][wv][qb * 16 + l16] = any_key[qb] ? mc[qb] : NEG;
+        xsum[par][wv][qb * 16 + l16] = lw[qb];
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -162,7 +193,10 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
 #pragma unroll
       for (int w = 0; w < kQkWaves; ++w)                                         // wavefronts in order; 2^(whole number) is exact
         l += xsum[par][w][qi] * __builtin_amdgcn_exp2f(fmaxf(xmax[par][w][qi] - m, -150.0f));
-      const float inv = any_key[qb] ? __builtin_amdgcn_exp2f(fmaxf(mc[qb] - m, -150.0f)) / l : 0.0f;
+      // the quotient is taken by every lane (l > 0: key 0 is valid) and dropped where the wavefront
+      // has no key: as the value of a choice it would sit in a branch of its own
+      const float q = __builtin_amdgcn_exp2f(fmaxf(mc[qb] - m, -150.0f)) / l;
+      const float inv = any_key[qb] ? q : 0.0f;
 #pragma unroll
       for (int kb = 0; kb < kQkKB; ++kb)
 #pragma unroll

@@ -862,18 +862,19 @@ __global__ __launch_bounds__(kExtraWaves * kWave) void extra_token_kernel(MergeA
 }
 
 
-template <typename T, bool MATCH, int SLICE, int WPU>
-static void launch_merge(const MergeArgs& m, int B, hipStream_t s) {
-  using Lds = MergeLds<MATCH, SLICE, WPU>;
+// Scanning mode (few discarded tokens): eight one-wavefront units per workgroup.
+template <typename T, int SLICE>
+static void launch_merge_scan(const MergeArgs& m, int B, hipStream_t s) {
+  using Lds = MergeLds<true, SLICE, 1>;
   constexpr int kSpan = kWave * kVec * SLICE;
   const int n_spans = (m.D + kSpan - 1) / kSpan;
   const size_t lds = Lds::bytes(m.n_disc);
-  const int units = (WPU > 1 ? m.n_keep : m.n_out) * n_spans;   // long-bucket pass: at most every preserved token
+  const int units = m.n_out * n_spans;
   dim3 grid((units + Lds::kUnits - 1) / Lds::kUnits, B), block(kMergeWaves * kWave);
   if (lds > 32768)
-    (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, MATCH, SLICE, WPU>,
+    (void)hipFuncSetAttribute((const void*)merge_rows_kernel<T, true, SLICE, 1>,
                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL((merge_rows_kernel<T, MATCH, SLICE, WPU>), grid, block, lds, s, m);
+  hipLaunchKernelGGL((merge_rows_kernel<T, true, SLICE, 1>), grid, block, lds, s, m);
 }
 
 template <typename T, int SLICE>
@@ -889,11 +890,6 @@ static void launch_merge_buckets(const MergeArgs& m, int B, hipStream_t s) {
     (void)hipFuncSetAttribute((const void*)merge_buckets_kernel<T, SLICE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
   hipLaunchKernelGGL((merge_buckets_kernel<T, SLICE>), dim3(hub_blocks + row_blocks, B), dim3(kMergeWaves * kWave), lds, s, m,
                      hub_blocks);
-}
-
-template <typename T, bool MATCH, int WPU>
-static void launch_merge_s(const MergeArgs& m, int B, int slice, hipStream_t s) {
-  if (slice == 1) launch_merge<T, MATCH, 1, WPU>(m, B, s); else launch_merge<T, MATCH, 2, WPU>(m, B, s);
 }
 
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
@@ -941,7 +937,8 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   const int slice = (int64_t)p.B * pl.n_out * ((p.D + 1023) / 1024) >= 4096 ? 2 : 1;
   const bool bf16 = p.dtype == FICOCO_BF16;
   if (match) {
-    if (bf16) launch_merge_s<bf16_t, true, 1>(m, p.B, slice, s); else launch_merge_s<float, true, 1>(m, p.B, slice, s);
+    if (bf16) { if (slice == 1) launch_merge_scan<bf16_t, 1>(m, p.B, s); else launch_merge_scan<bf16_t, 2>(m, p.B, s); }
+    else { if (slice == 1) launch_merge_scan<float, 1>(m, p.B, s); else launch_merge_scan<float, 2>(m, p.B, s); }
   } else {
     m.hub_list = (const int32_t*)(ws + pl.hub_list);
     m.hub_cnt = (const int32_t*)(ws + pl.hub_cnt);

@@ -234,6 +234,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.tgt_alpha = take(B * (size_t)pl.n_disc * p.k_max * sizeof(double));
   pl.hub_list = take(B * (size_t)p.n_keep * sizeof(int32_t));
   pl.hub_cnt = take(B * sizeof(int32_t));
+  pl.share_cnt = take(edges_inverted(pl) ? B * (size_t)invert_groups(pl) * p.n_keep * sizeof(int32_t) : 0);
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;
@@ -343,7 +344,7 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s, tw);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true,
                    pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr, s);
-  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s);
+  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s, true);
   return finish(ctx, fn);
 }
 

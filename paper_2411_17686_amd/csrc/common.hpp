@@ -52,6 +52,7 @@ struct Plan {
   size_t tgt_src;        // int32  [B][N^S*k_max] discarded token index per edge, by target
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t hub_list, hub_cnt;   // int32 [B][n_keep], [B]: preserved tokens with long buckets (inverted lists only)
+  size_t share_cnt;      // int32  [B][invert_groups][n_keep]  edges per target from each share of the discarded rows (fused step, inverted lists)
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
@@ -120,10 +121,25 @@ void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_
                    int64_t sb, int64_t sn, int row_bytes, void* out, hipStream_t s);
 void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, double* gap, hipStream_t s);
+// targets_counted: the edges per target and share of rows were counted while the correlate stage
+// wrote the lists (a fused step); otherwise the compress stage counts them from the lists it is given
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out,
-                     hipStream_t s);
+                     hipStream_t s, bool targets_counted = false);
+// Above kMatchMaxRows discarded tokens the compress stage first buckets the edges by target
+// (compress.hip).  The discarded rows are cut into invert_groups() shares of invert_share_rows()
+// consecutive rows, one workgroup of the bucketing kernel per share.  In a fused step the filter
+// stage clears a counter per (share, target) and the correlate stage adds one per edge it writes,
+// so the bucketing kernel starts from the counts instead of reading every list in every workgroup.
+constexpr int kMatchMaxRows = 1024;
+constexpr int kInvertRows = 512;
+inline bool edges_inverted(const Plan& pl) { return pl.n_disc > kMatchMaxRows; }
+inline int invert_groups(const Plan& pl) { return (pl.n_disc + kInvertRows - 1) / kInvertRows; }
+inline int invert_share_rows(const Plan& pl) {
+  const int g = invert_groups(pl);
+  return g > 0 ? (pl.n_disc + g - 1) / g : 1;
+}
 
 // ---- device helpers ----------------------------------------------------------------------
 typedef uint16_t bf16_t;

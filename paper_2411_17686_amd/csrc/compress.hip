@@ -29,18 +29,22 @@ struct InvertArgs {
   double* tgt_alpha;
   int32_t* hub_list;   // [B][n_keep]  preserved tokens with more than kHubMin sources (any order)
   int32_t* hub_cnt;    // [B]
+  const int32_t* share_cnt;   // [B][gridDim.x][n_keep] edges per (share of rows, target) counted by the correlate stage, or null
+  int share_rows;      // discarded rows per workgroup
 };
 
 constexpr int kHubMin = 32;        // buckets longer than this are merged by a whole workgroup
-constexpr int kInvertRows = 512;   // discarded rows one workgroup scatters
 
-// Buckets the edges of one image by target.  gridDim.x workgroups share an image: every one
-// of them counts ALL edges of the image into an LDS histogram (cheap, and it needs no
-// exchange between workgroups), noting separately how many come from rows before its own
-// share; the prefix sum of the histogram gives the bucket offsets, and offset + "before"
-// is where this workgroup's own rows start inside each bucket.  Then it scatters its rows.
-// No global atomics, nothing to clear beforehand, bucket regions per workgroup are fixed;
-// only the order inside a region depends on scheduling (the merge orders buckets itself).
+// Buckets the edges of one image by target.  gridDim.x workgroups share an image, each owning
+// share_rows consecutive discarded rows.  Every workgroup needs, per target, the number of edges
+// of the whole image and the number from rows before its own share: the prefix sum of the former
+// gives the bucket offsets, and offset + "before" is where this workgroup's own rows start inside
+// each bucket.  Then it scatters its rows.  The two numbers come from the counters the correlate
+// stage kept per (share, target) while it wrote the lists (share_cnt, a fused step), or else from
+// a pass of every workgroup over ALL lists of the image into an LDS histogram (it needs no
+// exchange between workgroups and nothing cleared beforehand).  Bucket regions per workgroup
+// are fixed either way; only the order inside a region depends on scheduling (the merge orders
+// buckets itself).
 template <int CH>   // consecutive list slots one thread loads at a time: 4 (rows of 4k slots, 16-byte aligned lists) or 1
 __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs a) {
   extern __shared__ int lds_i[];
@@ -50,11 +54,7 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
   const int64_t b = blockIdx.y;
   const int tid = threadIdx.x, nt = blockDim.x;
   const int n = a.n_keep;
-  const int share = (a.n_disc + (int)gridDim.x - 1) / (int)gridDim.x;
-  const int r_lo = min((int)blockIdx.x * share, a.n_disc), r_hi = min(r_lo + share, a.n_disc);
-  for (int j = tid; j <= n; j += nt) cnt[j] = 0;
-  for (int j = tid; j < n; j += nt) cursor[j] = 0;
-  __syncthreads();
+  const int r_lo = min((int)blockIdx.x * a.share_rows, a.n_disc), r_hi = min(r_lo + a.share_rows, a.n_disc);
   const int64_t rbase = b * a.n_disc;
   const int32_t* tgt = a.edge_tgt + rbase * a.k_max;      // the image's lists as one flat array of slots
   const double* alp = a.edge_alpha + rbase * a.k_max;
@@ -66,31 +66,57 @@ __global__ __launch_bounds__(kSelectThreads) void invert_edges_kernel(InvertArgs
       v[0] = tgt[f];
     }
   };
-  // Count pass over every slot of the image.  Consecutive threads take consecutive slots, so a
-  // wavefront's load covers whole cache lines (a thread per row would touch every line of the
-  // lists once per slot position); kInvertBatch loads per thread are in flight together.
-  constexpr int kInvertBatch = CH == 4 ? 8 : 16;     // loads of list slots one thread has in flight together
-  const int n_chunks = a.n_disc * a.k_max / CH;
-  for (int c0 = tid; c0 < n_chunks; c0 += nt * kInvertBatch) {
-    int v[kInvertBatch][CH], have[kInvertBatch], row[kInvertBatch];
+  if (a.share_cnt) {             // counted while the lists were written: add the shares up
+    const int32_t* sc = a.share_cnt + b * (int64_t)gridDim.x * n;
+    constexpr int kShareBatch = 8;      // counters one thread has in flight together
+    const int shares = gridDim.x, mine = blockIdx.x;
+    for (int j = tid; j < n; j += nt) {
+      int all = 0, before = 0;
+      for (int s0 = 0; s0 < shares; s0 += kShareBatch) {
+        int c[kShareBatch];
 #pragma unroll
-    for (int u = 0; u < kInvertBatch; ++u) {
-      const int f = min(c0 + u * nt, n_chunks - 1) * CH;   // clamped: always a valid address
-      row[u] = f / a.k_max;
-      have[u] = min(a.edge_cnt[rbase + row[u]], a.k_max) - (f - row[u] * a.k_max);   // list entries from slot f on
-      load_slots(f, v[u]);
+        for (int u = 0; u < kShareBatch; ++u) c[u] = sc[(int64_t)min(s0 + u, shares - 1) * n + j];   // clamped: always a valid address
+        issue_fence();
+#pragma unroll
+        for (int u = 0; u < kShareBatch; ++u) {
+          if (s0 + u < shares) all += c[u];
+          if (s0 + u < mine) before += c[u];
+        }
+      }
+      cnt[j] = all;
+      cursor[j] = before;
     }
-    issue_fence();
+    if (tid == 0) cnt[n] = 0;
+  } else {
+    // Count pass over every slot of the image.  Consecutive threads take consecutive slots, so a
+    // wavefront's load covers whole cache lines (a thread per row would touch every line of the
+    // lists once per slot position); kInvertBatch loads per thread are in flight together.
+    for (int j = tid; j <= n; j += nt) cnt[j] = 0;
+    for (int j = tid; j < n; j += nt) cursor[j] = 0;
+    __syncthreads();
+    constexpr int kInvertBatch = CH == 4 ? 8 : 16;     // loads of list slots one thread has in flight together
+    const int n_chunks = a.n_disc * a.k_max / CH;
+    for (int c0 = tid; c0 < n_chunks; c0 += nt * kInvertBatch) {
+      int v[kInvertBatch][CH], have[kInvertBatch], row[kInvertBatch];
 #pragma unroll
-    for (int u = 0; u < kInvertBatch; ++u) {
-      if (c0 + u * nt >= n_chunks) break;
-      const bool before = row[u] < r_lo;
+      for (int u = 0; u < kInvertBatch; ++u) {
+        const int f = min(c0 + u * nt, n_chunks - 1) * CH;   // clamped: always a valid address
+        row[u] = f / a.k_max;
+        have[u] = min(a.edge_cnt[rbase + row[u]], a.k_max) - (f - row[u] * a.k_max);   // list entries from slot f on
+        load_slots(f, v[u]);
+      }
+      issue_fence();
 #pragma unroll
-      for (int q = 0; q < CH; ++q) {
-        const int j = v[u][q];
-        if (q < have[u] && j >= 0 && j < n) {
-          atomicAdd(&cnt[j], 1);
-          if (before) atomicAdd(&cursor[j], 1);
+      for (int u = 0; u < kInvertBatch; ++u) {
+        if (c0 + u * nt >= n_chunks) break;
+        const bool before = row[u] < r_lo;
+#pragma unroll
+        for (int q = 0; q < CH; ++q) {
+          const int j = v[u][q];
+          if (q < have[u] && j >= 0 && j < n) {
+            atomicAdd(&cnt[j], 1);
+            if (before) atomicAdd(&cursor[j], 1);
+          }
         }
       }
     }
@@ -186,7 +212,7 @@ __device__ __forceinline__ void copy8(const T* src, T* dst) {
 }
 
 constexpr int kMergeWaves = 8;    // wavefronts (= output row spans) per workgroup
-constexpr int kMatchMaxRows = 1024;   // above this many discarded tokens the edge lists are inverted first
+// (kMatchMaxRows, common.hpp: above that many discarded tokens the edge lists are inverted first)
 static_assert(kMatchMaxRows % (kMergeWaves * kWave) == 0, "a workgroup stages the edge table in whole rounds");
 constexpr int kMatchCap = 64;     // scanning mode: sources of one target kept in LDS
 constexpr int kBucketCap = 256;   // inverted lists: bucket entries put in order in LDS
@@ -895,8 +921,8 @@ static void launch_merge_buckets(const MergeArgs& m, int B, hipStream_t s) {
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out,
-                     hipStream_t s) {
-  const bool match = pl.n_disc <= kMatchMaxRows;
+                     hipStream_t s, bool targets_counted) {
+  const bool match = !edges_inverted(pl);
   if (pl.n_disc > 0 && !match) {
     InvertArgs a{};
     a.n_keep = p.n_keep; a.n_disc = pl.n_disc; a.k_max = p.k_max;
@@ -913,8 +939,9 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
     auto kern = quads ? invert_edges_kernel<4> : invert_edges_kernel<1>;
     if (lds > 32768)
       (void)hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-    const int groups = (pl.n_disc + kInvertRows - 1) / kInvertRows;
-    hipLaunchKernelGGL(kern, dim3(groups, p.B), dim3(kSelectThreads), lds, s, a);
+    a.share_cnt = targets_counted ? (const int32_t*)(ws + pl.share_cnt) : nullptr;
+    a.share_rows = invert_share_rows(pl);
+    hipLaunchKernelGGL(kern, dim3(invert_groups(pl), p.B), dim3(kSelectThreads), lds, s, a);
   }
   MergeArgs m{};
   m.X = p.X; m.xsb = p.x_stride_b; m.xsn = p.x_stride_n; m.X_out = X_out;

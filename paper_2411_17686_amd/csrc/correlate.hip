@@ -42,7 +42,17 @@ struct CorrArgs {
   int fixed_k;           // > 0: ablation "fixed K" (sel_m = K, sel_g = 0): of the values equal to the threshold only
                          // the lowest positions are taken, K targets in all; -1: every value >= threshold
   double* gap;           // correlation-gap diagnostic output [B][n_disc] (its own kernel)
+  int32_t* share_cnt;    // [B][shares][n_keep] edges written per (share of discarded rows, target), cleared by the
+                         // filter stage of a fused step; null where the compress stage counts for itself
+  int shares, share_rows;
 };
+
+// One more edge from discarded row `row` to keep slot `tgt`: counted for the compress stage, which
+// buckets the edges by target (one workgroup per share of share_rows consecutive rows).
+__device__ __forceinline__ void count_edge(const CorrArgs& a, int64_t b, int row, int tgt) {
+  if (a.share_cnt && (unsigned)tgt < (unsigned)a.n_keep)
+    atomicAdd(&a.share_cnt[(b * a.shares + row / a.share_rows) * a.n_keep + tgt], 1);
+}
 
 __device__ __forceinline__ double dot_bf16(const bf16_t* __restrict__ x, const bf16_t* __restrict__ y, int D) {
   double acc = 0.0;
@@ -231,11 +241,13 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
       const double al = my_c / denom;
       a.edge_tgt[ebase + lane] = my_tgt;
       a.edge_alpha[ebase + lane] = al;
+      count_edge(a, b, row, my_tgt);
     }
   } else if (live && lane == 0) {
     for (int e = 0; e < stored; ++e) {
       const double al = a.edge_alpha[ebase + e] / denom;
       a.edge_alpha[ebase + e] = al;
+      count_edge(a, b, row, a.edge_tgt[ebase + e]);
     }
   }
   if (lane == 0) {
@@ -613,6 +625,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     const double al = myv / denom;
     a.edge_tgt[ebase + my_pos] = myjj;
     a.edge_alpha[ebase + my_pos] = al;
+    count_edge(a, b, row, myjj);
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -798,6 +811,7 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
     const double al = my_c / denom;
     a.edge_tgt[ebase + lane] = my_tgt;
     a.edge_alpha[ebase + lane] = al;
+    count_edge(a, b, row, my_tgt);
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -879,6 +893,11 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.fixed_k = pl.fixed_k;
   a.ct_splits = pl.gram_splits;
   a.delta = (float)(pl.Df + 4 * pl.gram_splits) * 2.384185791015625e-07f;   // (Df + 4 splits) * 2^-22
+  if (fused && edges_inverted(pl)) {
+    a.share_cnt = (int32_t*)(ws + pl.share_cnt);
+    a.shares = invert_groups(pl);
+    a.share_rows = invert_share_rows(pl);
+  }
   dim3 grid((pl.n_disc + 3) / 4, p.B), block(256);
   if (a.mode == kAttnV && !pl.dense_rows && p.k_max <= kWave) {
     const bool wide = p.N > 10 * kWave;     // longer rows: wider batches (fewer dependent trips to memory)

@@ -38,6 +38,8 @@ struct SelectArgs {
   int32_t* keep_idx;
   int32_t* slot_of;
   int32_t* overflow;        // zeroed here for the correlate stage (fused step only), may be null
+  int32_t* share_cnt;       // [B][share_n] edge counters of the correlate stage, zeroed here (fused step with inverted edge lists), or null
+  int share_n;
   // Exact re-evaluation of the cosine-derived terms for tokens whose decision is within the error
   // bound of the bulk evaluation (exact_r: the mean-cosine term, exact_g: the equivalent-token term)
   int exact_r, exact_g;
@@ -552,6 +554,8 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   }
   if (!a.do_filter) return;
   if (a.overflow && tid == 0) a.overflow[b] = 0;
+  if (a.share_cnt)
+    for (int j = tid; j < a.share_n; j += nt) a.share_cnt[(int64_t)b * a.share_n + j] = 0;
   if (!keys_ready) {
     __syncthreads();
     for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
@@ -726,6 +730,10 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.discard_idx = discard_idx; a.keep_idx = keep_idx;
   a.slot_of = (int32_t*)(ws + pl.slot_of);
   a.overflow = overflow;
+  if (overflow && edges_inverted(pl)) {      // a fused step: the correlate stage counts its edges per target
+    a.share_cnt = (int32_t*)(ws + pl.share_cnt);
+    a.share_n = invert_groups(pl) * p.n_keep;
+  }
   const size_t lds = select_lds(p, penalty);
   const bool exact = a.exact_r || a.exact_g;
   // Short sequences: no more wavefronts than tokens need (every barrier of the kernel waits for

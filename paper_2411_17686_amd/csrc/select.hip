@@ -95,15 +95,27 @@ __device__ __forceinline__ double combine_terms(double w, double R, double G) {
   return first - second;
 }
 
+// x / d for 0 <= x < 2^14 and 1 <= d, given rd = 1.0f / (float)d: the float product is within
+// 2^-9 of the quotient, so its integer part is off by at most one, which the remainder shows.
+// (Token, cell and window counts are at most 12288; an integer division costs five times as many
+// instructions, and the one workgroup of an image pays for every instruction of every token.)
+static_assert(kMaxSelectN <= (1 << 14), "div_small's range");
+__device__ __forceinline__ int div_small(int x, int d, float rd) {
+  int q = (int)((float)x * rd);
+  const int r = x - q * d;
+  if (r < 0) --q; else if (r >= d) ++q;
+  return q;
+}
+
 __device__ __forceinline__ uint64_t score_key(double s) {
   const uint64_t u = (uint64_t)__double_as_longlong(s + 0.0);   // -0 folded into +0
   return (u >> 63) ? ~u : (u | 0x8000000000000000ULL);
 }
 
 constexpr int kTokensPerThread = (kMaxSelectN + kSelectThreads - 1) / kSelectThreads;   // sequences longer than kSelectThreads run with kSelectThreads threads
-constexpr int kBinCopies = 32;      // counters per histogram bin in the many-keys form: one per LDS bank
-constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (it costs one more barrier per pass)
-static_assert(kSelectThreads == 4 * 256, "four threads fold the counters of one bin");
+constexpr int kBinCopies = 32;      // counters per histogram bin in the spread form: one per LDS bank
+constexpr int kSpreadMinN = 4096;   // tokens from which that form is used (below, clearing and folding 8192 counters costs more than the queueing: measured at 576 and 2304 tokens)
+constexpr int kRegsMinN = kSpreadMinN;   // tokens from which the keys of the selection live in registers (the workgroup then has kSelectThreads threads, and the spread counters exist)
 
 __device__ __forceinline__ double key_score(uint64_t k) {       // inverse of score_key
   const uint64_t u = (k >> 63) ? (k & 0x7fffffffffffffffULL) : ~k;
@@ -125,32 +137,40 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
   int need = n_disc;   // how many of the current candidates (keys matching the prefix) to take from the top
   uint64_t* small = (uint64_t*)hist;   // candidate keys once at most 64 are left (after the histogram is spent)
   const bool spread = N >= kSpreadMinN;   // uniform
+  // The counters are cleared once here and, in every pass, by the threads that have just read them
+  // (each barrier of the one workgroup costs a good part of a microsecond at sixteen wavefronts:
+  // a pass has two of them, three in the many-keys form).
+  if (spread) { for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0; }
+  else if (tid < 256) hist[tid] = 0;
+  __syncthreads();
   for (int pass = 0; pass < 8; ++pass) {
     const int shift = 56 - 8 * pass;
     const uint64_t hi_mask = pass == 0 ? 0ULL : (~0ULL << (shift + 8));
     if (spread) {
       // Many keys per thread: scores of one image share their leading digits, so in the first
-      // passes nearly all atomics would queue on one LDS address (one lane per cycle).  Every
-      // bin has 32 counters here, one per bank, lane l adding to counter l % 32 -- no two
-      // lanes of an instruction meet -- and four threads per bin fold them afterwards.
-      for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0;
-      __syncthreads();
+      // passes nearly all atomics would queue on one LDS address (one lane at a time).  Every
+      // bin has 32 counters here, one per bank, lane l adding to counter l % 32 -- only lanes
+      // l and l + 32 of an instruction meet -- and four threads per bin fold them afterwards.
       for (int i = tid; i < N; i += nt) {
         const uint64_t k = keys[i];
         if ((k & hi_mask) == kstar) atomicAdd(&hist_wide[(int)((k >> shift) & 255) * kBinCopies + tid % kBinCopies], 1);
       }
       __syncthreads();
-      const int bin = tid / 4, part = tid % 4;           // 1024 threads: four per bin
-      int sum = 0;
+      // four threads per bin (neighbouring lanes: the thread count is a multiple of 64)
+      for (int j = tid; j < 4 * 256; j += nt) {
+        const int bin = j / 4, part = j % 4;
+        int sum = 0;
 #pragma unroll
-      for (int c = 0; c < kBinCopies / 4; ++c)           // rotated by the bin so that neighbouring bins read different banks
-        sum += hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
-      sum += dpp_move<0xB1>(sum);                          // lane ^ 1
-      sum += dpp_move<0x4E>(sum);                          // lane ^ 2
-      if (part == 0) hist[bin] = sum;
+        for (int c = 0; c < kBinCopies / 4; ++c) {       // rotated by the bin so that neighbouring bins read different banks
+          int* ctr = &hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
+          sum += *ctr;
+          *ctr = 0;
+        }
+        sum += dpp_move<0xB1>(sum);                        // lane ^ 1
+        sum += dpp_move<0x4E>(sum);                        // lane ^ 2
+        if (part == 0) hist[bin] = sum;
+      }
     } else {
-      if (tid < 256) hist[tid] = 0;
-      __syncthreads();
       for (int i = tid; i < N; i += nt) {
         const uint64_t k = keys[i];
         if ((k & hi_mask) == kstar) atomicAdd(&hist[(int)((k >> shift) & 255)], 1);
@@ -162,6 +182,10 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
       int h[4];
 #pragma unroll
       for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
+      if (!spread) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) hist[4 * tid + k] = 0;
+      }
       const int lsum = h[0] + h[1] + h[2] + h[3];
       const int upto = wave_scan_inclusive(lsum);        // lanes 0 .. this one; lane 63 holds the total
       int above = lane_value(upto, kWave - 1) - upto;    // tokens in bins above this lane's
@@ -176,10 +200,10 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
       }
     }
     __syncthreads();
+    // (the next write of these three words lies behind the next pass's barriers)
     kstar |= (uint64_t)bcast[0] << shift;
     need = bcast[1];
     const int left = bcast[2];
-    __syncthreads();
     if (left <= kWave && shift > 0) {
       // Few candidates left: rank them directly in one wavefront instead of more passes.
       if (tid == 0) bcast[3] = 0;
@@ -189,6 +213,100 @@ __device__ __forceinline__ void radix_select_kstar(const uint64_t* keys, int N, 
         const uint64_t k = keys[i];
         if ((k & m2) == kstar) { const int slot = atomicAdd(&bcast[3], 1); if (slot < kWave) small[slot] = k; }
       }
+      __syncthreads();
+      if (tid < kWave) {
+        const uint64_t mine = tid < left ? small[tid] : 0ULL;
+        int greater = 0, equal = 0;
+        for (int l = 0; l < left; ++l) {
+          const uint64_t o = small[l];
+          greater += o > mine ? 1 : 0;
+          equal += o == mine ? 1 : 0;
+        }
+        if (tid < left && greater < need && need <= greater + equal) {   // all such lanes agree
+          small[kWave] = mine;
+          bcast[1] = need - greater;
+        }
+      }
+      __syncthreads();
+      kstar = small[kWave];
+      need = bcast[1];
+      __syncthreads();
+      break;
+    }
+  }
+  kstar_out = kstar;
+  need_out = need;
+}
+
+// The same selection for long sequences, with the keys in registers.  One workgroup serves an image,
+// so every instruction per token costs N / 64 cycles of the one compute unit (60 ns at 9216 tokens):
+// here a thread holds the keys of its own contiguous run of tokens (the run the ordered compaction
+// gives it anyway) and a bit per key that says whether the key still matches the digits chosen so
+// far, and a pass is a shift, a mask and an LDS add per live key -- no key is read from LDS again,
+// no 64-bit prefix is compared.  Histogram as in the many-keys form above (one counter per bank).
+// valid: bit u set where kreg[u] is a token.  Needs blockDim.x == kSelectThreads.
+template <int PER>
+__device__ __forceinline__ void radix_select_regs(const uint64_t (&kreg)[PER], uint32_t valid, int n_disc, int* hist,
+                                                  int* bcast, int* hist_wide, uint64_t& kstar_out, int& need_out) {
+  const int tid = threadIdx.x, nt = blockDim.x;
+  uint64_t kstar = 0;
+  int need = n_disc;
+  uint32_t alive = valid;
+  uint64_t* small = (uint64_t*)hist;
+  for (int j = tid; j < 256 * kBinCopies; j += nt) hist_wide[j] = 0;
+  __syncthreads();
+  for (int pass = 0; pass < 8; ++pass) {
+    const int shift = 56 - 8 * pass;
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      if ((alive >> u) & 1u) atomicAdd(&hist_wide[(int)((kreg[u] >> shift) & 255) * kBinCopies + tid % kBinCopies], 1);
+    __syncthreads();
+    {
+      const int bin = tid / 4, part = tid % 4;           // four threads per bin
+      int sum = 0;
+#pragma unroll
+      for (int c = 0; c < kBinCopies / 4; ++c) {         // read and cleared for the next pass
+        int* ctr = &hist_wide[bin * kBinCopies + (part * (kBinCopies / 4) + c + bin) % kBinCopies];
+        sum += *ctr;
+        *ctr = 0;
+      }
+      sum += dpp_move<0xB1>(sum);
+      sum += dpp_move<0x4E>(sum);
+      if (part == 0) hist[bin] = sum;
+    }
+    __syncthreads();
+    if (tid < kWave) {
+      int h[4];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) h[k] = hist[4 * tid + k];
+      const int lsum = h[0] + h[1] + h[2] + h[3];
+      const int upto = wave_scan_inclusive(lsum);
+      int above = lane_value(upto, kWave - 1) - upto;
+      if (above < need && need <= above + lsum) {        // exactly one lane
+#pragma unroll
+        for (int k = 3; k >= 0; --k) {
+          if (above < need && need <= above + h[k]) {
+            bcast[0] = 4 * tid + k; bcast[1] = need - above; bcast[2] = h[k];
+          }
+          above += h[k];
+        }
+      }
+    }
+    __syncthreads();
+    const int digit = bcast[0];
+    kstar |= (uint64_t)digit << shift;
+    need = bcast[1];
+    const int left = bcast[2];
+#pragma unroll
+    for (int u = 0; u < PER; ++u)
+      if ((int)((kreg[u] >> shift) & 255) != digit) alive &= ~(1u << u);
+    if (left <= kWave && shift > 0) {
+      // Few candidates left: rank them directly in one wavefront instead of more passes.
+      if (tid == 0) bcast[3] = 0;
+      __syncthreads();
+#pragma unroll
+      for (int u = 0; u < PER; ++u)
+        if ((alive >> u) & 1u) { const int slot = atomicAdd(&bcast[3], 1); if (slot < kWave) small[slot] = kreg[u]; }
       __syncthreads();
       if (tid < kWave) {
         const uint64_t mine = tid < left ? small[tid] : 0ULL;
@@ -466,24 +584,31 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       }
       if (a.window > 0) {
         const int cells = a.grid_g * a.grid_h * a.grid_w;
-        for (int c = tq; c < cells; c += nt) owner[c] = -1;
-        __syncthreads();
-        for (int i = tq; i < N; i += nt) {
-          const int c = a.pos ? a.pos[(int64_t)bq * N + i] : i;
-          if (c >= 0 && c < cells) owner[c] = i;
+        // Without position ids token i sits in cell i: no table of the cells' tokens is needed then.
+        const bool table = a.pos != nullptr;     // uniform
+        if (table) {
+          for (int c = tq; c < cells; c += nt) owner[c] = -1;
+          __syncthreads();
+          for (int i = tq; i < N; i += nt) {
+            const int c = a.pos[(int64_t)bq * N + i];
+            if (c >= 0 && c < cells) owner[c] = i;
+          }
         }
         __syncthreads();
+        auto token_in = [&](int cell) { return table ? owner[cell] : (cell < N ? cell : -1); };
         const int W = a.window;
         const int wr = (a.grid_h + W - 1) / W, wc = (a.grid_w + W - 1) / W;
         const int n_win = a.grid_g * wr * wc;
+        const float r_sub = 1.0f / (float)(wr * wc), r_wc = 1.0f / (float)wc;
         for (int w = tq; w < n_win; w += nt) {
-          const int sub = w / (wr * wc), rem = w % (wr * wc);
-          const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
+          const int sub = div_small(w, wr * wc, r_sub), rem = w - sub * (wr * wc);
+          const int wrow = div_small(rem, wc, r_wc);
+          const int r0 = wrow * W, c0 = (rem - wrow * wc) * W;
           int best = -1;
           double best_s = 0.0;
           for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
             for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
-              const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
+              const int t = token_in((sub * a.grid_h + r) * a.grid_w + c);
               if (t >= 0 && (best < 0 || s[t] > best_s)) { best = t; best_s = s[t]; }
             }
           if (exact_mode && best >= 0) {
@@ -494,7 +619,7 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
             bool any = false;
             for (int r = r0; r < min(r0 + W, a.grid_h); ++r)
               for (int c = c0; c < min(c0 + W, a.grid_w); ++c) {
-                const int t = owner[(sub * a.grid_h + r) * a.grid_w + c];
+                const int t = token_in((sub * a.grid_h + r) * a.grid_w + c);
                 if (t < 0 || t == best) continue;
                 const double d_t = is_exact(t) ? 0.0 : delta;
                 if (d_t + d_best > 0.0 && s[t] >= best_s - (d_t + d_best)) {
@@ -556,41 +681,61 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
   if (a.overflow && tid == 0) a.overflow[b] = 0;
   if (a.share_cnt)
     for (int j = tid; j < a.share_n; j += nt) a.share_cnt[(int64_t)b * a.share_n + j] = 0;
-  if (!keys_ready) {
-    __syncthreads();
-    for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
-    __syncthreads();
-    if (a.n_disc > 0) radix_select_kstar<EXACT>(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
-  }
-  // need = how many tokens with key == kstar are discarded (lowest indices first)
-
-  // ---- flags and ordered compaction -----------------------------------------------------------
+  // ---- K*, flags and ordered compaction --------------------------------------------------------
+  // Thread t owns the contiguous run [lo, hi) of tokens (at most kTokensPerThread of them).
   const int per = (N + nt - 1) / nt;
   const int lo = min(tid * per, N), hi = min(lo + per, N);
+  uint32_t eq_mask = 0, gt_mask = 0;    // bit u: the key of token lo + u is equal to / above K*
+  bool in_regs = false;                 // uniform: long sequence, keys not formed yet -> they live in registers
+  if constexpr (!EXACT) in_regs = !keys_ready && N >= kRegsMinN;
+  if (in_regs) {
+    if constexpr (!EXACT) {
+      __syncthreads();                  // the scores in LDS are final
+      uint64_t kreg[kTokensPerThread];
+#pragma unroll
+      for (int u = 0; u < kTokensPerThread; ++u) kreg[u] = lo + u < hi ? score_key(s[lo + u]) : 0ULL;
+      const uint32_t valid = (1u << (hi - lo)) - 1u;
+      if (a.n_disc > 0) {
+        radix_select_regs<kTokensPerThread>(kreg, valid, a.n_disc, hist, bcast, hist_wide, kstar, need);
+#pragma unroll
+        for (int u = 0; u < kTokensPerThread; ++u) {
+          eq_mask |= kreg[u] == kstar ? 1u << u : 0u;
+          gt_mask |= kreg[u] > kstar ? 1u << u : 0u;
+        }
+        eq_mask &= valid;
+        gt_mask &= valid;
+      }
+    }
+  } else {
+    if (!keys_ready) {
+      __syncthreads();
+      for (int i = tid; i < N; i += nt) keys[i] = score_key(s[i]);   // in place: same 8-byte slots
+      __syncthreads();
+      if (a.n_disc > 0) radix_select_kstar<EXACT>(keys, N, a.n_disc, hist, bcast, hist_wide, kstar, need);
+    }
+    for (int i = lo; i < hi; ++i) {
+      const uint64_t k = keys[i];
+      eq_mask |= (a.n_disc > 0 && k == kstar) ? 1u << (i - lo) : 0u;
+      gt_mask |= (a.n_disc > 0 && k > kstar) ? 1u << (i - lo) : 0u;
+    }
+  }
+  // need = how many tokens with key == K* are discarded (lowest indices first).
   // One scan carries both counts of this thread's tokens: keys above K* (upper half) and keys
   // equal to K* (lower half); neither total exceeds N <= 12288.  The discarded tokens before
   // `lo` are then the ones above K* plus the first `need` of the equal ones.
-  int n_eq = 0, n_gt = 0;
-  for (int i = lo; i < hi; ++i) {
-    const uint64_t k = keys[i];
-    n_eq += (a.n_disc > 0 && k == kstar) ? 1 : 0;
-    n_gt += (a.n_disc > 0 && k > kstar) ? 1 : 0;
-  }
+  const int n_eq = __popc(eq_mask), n_gt = __popc(gt_mask);
   int tot;
   const int packed = block_scan_inclusive((n_gt << 16) | n_eq, scan, &tot) - ((n_gt << 16) | n_eq);
   int eq_before = packed & 0xffff;
   const int gt_before = packed >> 16;
   int d_pos = gt_before + min(eq_before, need);                   // discarded tokens before `lo`
   int k_pos = lo - d_pos;                                         // preserved tokens before `lo`
-  uint32_t dis_mask = 0;  // per <= 12 tokens per thread (N <= kMaxSelectN)
-  for (int i = lo; i < hi; ++i) {
-    const uint64_t k = keys[i];
-    bool dis = false;
-    if (a.n_disc > 0) {
-      if (k > kstar) dis = true;
-      else if (k == kstar) { dis = eq_before < need; ++eq_before; }
+  uint32_t dis_mask = gt_mask;
+  for (int u = 0; u < hi - lo; ++u) {
+    if ((eq_mask >> u) & 1u) {
+      if (eq_before < need) dis_mask |= 1u << u;
+      ++eq_before;
     }
-    if (dis) dis_mask |= 1u << (i - lo);
   }
   const int n_keep = N - a.n_disc;
   for (int i = lo; i < hi; ++i) {

@@ -674,6 +674,14 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       if constexpr (EXACT) exact_terms_of<TF>(a, bq, ex_list, n_flag, pass == 0);
       keys_ready = false;
     }
+  } else if (N > nt) {           // several tokens per thread: all loads issued before the first use
+    double v[kTokensPerThread];
+#pragma unroll
+    for (int u = 0; u < kTokensPerThread; ++u) v[u] = a.scores[(int64_t)b * N + min(tid + u * nt, N - 1)];
+    issue_fence();
+#pragma unroll
+    for (int u = 0; u < kTokensPerThread; ++u)
+      if (tid + u * nt < N) s[tid + u * nt] = v[u];
   } else {
     for (int i = tid; i < N; i += nt) s[i] = a.scores[(int64_t)b * N + i];
   }
@@ -786,6 +794,85 @@ __global__ __launch_bounds__(256) void vector_terms_kernel(const void* recv_vec,
   if (sem_vec) out_g[b * N + i] = vec_head_mean(sem_vec, dtype, b, H, N, i);
 }
 
+// Both terms per-head vectors and the tokens in grid order (no position ids): nothing of the score
+// stage then needs a step across the image -- head means, Eq. 1 and the local penalty concern the
+// tokens of one window -- so a grid of workgroups forms the FINAL scores, one thread per penalty
+// window (same arithmetic and the same order inside a window as select_kernel), and the per-image
+// workgroup, where every instruction per token costs N / 64 cycles, only filters.  penalize == 0:
+// no penalty; the caller then passes windows of one cell.
+__global__ __launch_bounds__(256) void vector_scores_kernel(const void* recv_vec, const void* sem_vec, int dtype, int H,
+                                                            int N, double w, int grid_g, int grid_h, int grid_w, int W,
+                                                            int penalize, double coef, double* __restrict__ scores) {
+  const int win = blockIdx.x * blockDim.x + threadIdx.x;
+  const int64_t b = blockIdx.y;
+  const int wr = (grid_h + W - 1) / W, wc = (grid_w + W - 1) / W;
+  if (win >= grid_g * wr * wc) return;
+  const int sub = win / (wr * wc), rem = win % (wr * wc);
+  const int r0 = (rem / wc) * W, c0 = (rem % wc) * W;
+  int best = -1;
+  double best_s = 0.0;
+  for (int r = r0; r < min(r0 + W, grid_h); ++r)
+    for (int c = c0; c < min(c0 + W, grid_w); ++c) {
+      const int t = (sub * grid_h + r) * grid_w + c;       // token = cell
+      if (t >= N) continue;
+      const double R = vec_head_mean(recv_vec, dtype, b, H, N, t);
+      const double G = vec_head_mean(sem_vec, dtype, b, H, N, t);
+      const double st = combine_terms(w, R, G);
+      scores[b * N + t] = st;
+      if (best < 0 || st > best_s) { best = t; best_s = st; }
+    }
+  if (penalize && best >= 0) scores[b * N + best] = coef * best_s;
+}
+
+// The same with one thread per CELL (windows of at most 256 cells; a workgroup takes `wpb` whole
+// windows, thread k of a window its k-th cell in row-major order): the head means of a window's
+// tokens are then loaded side by side instead of one token after the other.  The window's first
+// thread picks the maximum, scanning the cells in the same order as above.
+__global__ __launch_bounds__(256) void vector_scores_cells_kernel(const void* recv_vec, const void* sem_vec, int dtype,
+                                                                  int H, int N, double w, int grid_g, int grid_h,
+                                                                  int grid_w, int W, int wpb, int penalize, double coef,
+                                                                  double* __restrict__ scores) {
+  __shared__ double sc[256];
+  __shared__ int tok[256];
+  __shared__ int best_of[256];
+  const int64_t b = blockIdx.y;
+  const int W2 = W * W;
+  const int lw = threadIdx.x / W2, k = threadIdx.x % W2;
+  const int wr = (grid_h + W - 1) / W, wc = (grid_w + W - 1) / W;
+  const int win = blockIdx.x * wpb + lw;
+  const bool active = lw < wpb && win < grid_g * wr * wc;
+  int t = -1;
+  if (active) {
+    const int sub = win / (wr * wc), rem = win % (wr * wc);
+    const int r = (rem / wc) * W + k / W, c = (rem % wc) * W + k % W;
+    if (r < grid_h && c < grid_w) {
+      const int cell = (sub * grid_h + r) * grid_w + c;
+      if (cell < N) t = cell;
+    }
+  }
+  double st = 0.0;
+  if (t >= 0) {
+    const double R = vec_head_mean(recv_vec, dtype, b, H, N, t);
+    const double G = vec_head_mean(sem_vec, dtype, b, H, N, t);
+    st = combine_terms(w, R, G);
+  }
+  sc[threadIdx.x] = st;
+  tok[threadIdx.x] = t;
+  __syncthreads();
+  if (active && k == 0) {
+    int best = -1;
+    double best_s = 0.0;
+    for (int j = 0; j < W2; ++j) {
+      const int tj = tok[lw * W2 + j];
+      const double sj = sc[lw * W2 + j];
+      if (tj >= 0 && (best < 0 || sj > best_s)) { best = tj; best_s = sj; }
+    }
+    best_of[lw] = best;
+  }
+  __syncthreads();
+  if (t >= 0) scores[b * N + t] = penalize && best_of[lw] == t ? coef * st : st;
+}
+
 __global__ __launch_bounds__(256) void text_stats_kernel(TextStatsArgs a) { text_stats_block(a, blockIdx.x, blockIdx.y); }
 
 static size_t select_lds(const ficoco_problem& p, bool penalty) {
@@ -823,7 +910,25 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.recv_vec = p.recv_vec; a.sem_vec = p.sem_vec;
   a.fterm_r = (const double*)(ws + pl.fterm);
   a.fterm_g = (const double*)(ws + pl.fterm2);
-  if (do_score && p.N > 2 * kSelectThreads && (p.red_src == FICOCO_R_VECTOR || p.sem_src == FICOCO_G_VECTOR)) {
+  const bool penalty = p.variant == FICOCO_VARIANT_V && p.window > 0;
+  bool scored = false;       // the final scores are in `scores` before the kernel starts
+  if (do_score && p.N > 2 * kSelectThreads && p.red_src == FICOCO_R_VECTOR && p.sem_src == FICOCO_G_VECTOR &&
+      !(penalty && p.pos)) {
+    const int g = penalty ? p.grid_g : 1, gh = penalty ? p.grid_h : 1, gw = penalty ? p.grid_w : p.N;
+    const int W = penalty ? p.window : 1;
+    const int n_win = g * ((gh + W - 1) / W) * ((gw + W - 1) / W);
+    if (W <= 16) {                 // a thread per cell, 256 / W^2 whole windows per workgroup
+      const int wpb = 256 / (W * W);
+      hipLaunchKernelGGL(vector_scores_cells_kernel, dim3((n_win + wpb - 1) / wpb, p.B), dim3(256), 0, s, p.recv_vec,
+                         p.sem_vec, (int)p.dtype, p.H, p.N, (double)p.w_score, g, gh, gw, W, wpb, penalty ? 1 : 0,
+                         (double)p.penalty_coef, scores);
+    } else {
+      hipLaunchKernelGGL(vector_scores_kernel, dim3((n_win + 255) / 256, p.B), dim3(256), 0, s, p.recv_vec, p.sem_vec,
+                         (int)p.dtype, p.H, p.N, (double)p.w_score, g, gh, gw, W, penalty ? 1 : 0,
+                         (double)p.penalty_coef, scores);
+    }
+    scored = true;
+  } else if (do_score && p.N > 2 * kSelectThreads && (p.red_src == FICOCO_R_VECTOR || p.sem_src == FICOCO_G_VECTOR)) {
     // the term buffers of the vector-sourced terms are free (the feature stage fills only the others)
     const bool vr = p.red_src == FICOCO_R_VECTOR, vg = p.sem_src == FICOCO_G_VECTOR;
     hipLaunchKernelGGL(vector_terms_kernel, dim3((p.N + 255) / 256, p.B), dim3(256), 0, s, vr ? p.recv_vec : nullptr,
@@ -865,7 +970,7 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
     a.ex_list = (int32_t*)(ws + pl.ex_list);
   }
   a.w = (double)p.w_score;
-  const bool penalty = p.variant == FICOCO_VARIANT_V && p.window > 0;
+  if (scored) a.do_score = 0;                    // the kernel reads the scores instead of forming them
   a.pos = p.pos;
   a.grid_g = p.grid_g; a.grid_h = p.grid_h; a.grid_w = p.grid_w;
   a.window = penalty ? p.window : 0;

@@ -53,6 +53,28 @@ def test_long_sequence_with_tied_scores(ctx, levels, window):
     assert out["X_out"].shape == (2, 700, 64)
 
 
+@pytest.mark.parametrize("window", [0, 1, 3, 17])
+@pytest.mark.parametrize("with_pos", [False, True])
+@pytest.mark.parametrize("staged", [False, True])
+def test_long_sequence_scored_from_vectors(ctx, window, with_pos, staged):
+    """More than 2048 tokens scored from per-head vectors alone: without position ids a grid of
+    workgroups forms the final scores, one thread per penalty window (47 is no multiple of the
+    window of 3: partial windows at two edges; window 1: every token is its window's maximum;
+    window 0: no penalty; window 17: more than 256 cells, one thread per window); with position ids (here: the shuffled cells of the same grid) the
+    per-image workgroup does, from head means formed beforehand."""
+    cfg = synth.ficoco_v_video(seed=75, B=2, frames=2, grid=47, D=64, H=3, centres=30, n_keep=900, dtype="f32")
+    cfg["window"] = window
+    pos = None
+    if with_pos:
+        g = torch.Generator().manual_seed(5)
+        pos = torch.stack([torch.randperm(cfg["N"], generator=g) for _ in range(cfg["B"])]).to(torch.int32)
+    kw = dict(red_src=fc.R_VECTOR, sem_src=fc.G_VECTOR, corr_src=fc.C_COSINE, staged=staged)
+    if pos is not None:
+        kw["pos"] = pos
+    out = _check(cfg, ctx, **kw)
+    assert out["X_out"].shape == (2, 900, 64)
+
+
 @pytest.mark.parametrize("grid,H,B", [(32, 5, 3), (32, 3, 2), (24, 7, 4), (40, 1, 1)])
 def test_reduction_chunk_shapes_and_odd_head_counts(ctx, grid, H, B):
     """The attention reduction adds the heads of up to four rows per thread side by side, a few

@@ -820,18 +820,30 @@ __global__ __launch_bounds__(kMergeWaves * kWave) void merge_rows_kernel(MergeAr
   if (WPU == 1) write_pos_out<SLICE>(a, blockIdx.x);
 }
 
-// Bucket mode, both passes in one launch: the first `hub_blocks` workgroups take one target with a
-// long bucket each (most of them find the list of such targets shorter than their index and
-// leave at once), the others eight units of the one-wavefront pass.  The long targets start
-// first, and no launch gap separates the passes.
+// Bucket mode, both passes in one launch (no launch gap separates them): the first `hub_blocks`
+// workgroups take the targets with long buckets, a whole workgroup per unit -- workgroup w takes
+// entries w, w + hub_blocks, ... of the list of such targets (times the spans of a row), as far
+// as the list goes -- the others eight units of the one-wavefront pass each.  How long the list
+// is only the device knows, so most of the first kind leave at once; but the chip starts only a
+// few hundred workgroups per microsecond, empty ones included: with one workgroup per POSSIBLE
+// long target ahead of the row workgroups (2304 at 1152 preserved tokens) the rows started 10 to
+// 16 us into the launch.  So there is one workgroup for every fourth possible entry (an image
+// with more long targets than that takes them in a second trip).  They still come first: the
+// long targets take longest, and with the rows ahead of them they wait for a place on the chip.
 template <typename T, int SLICE>
 __global__ __launch_bounds__(kMergeWaves * kWave) void merge_buckets_kernel(MergeArgs a, int hub_blocks) {
   extern __shared__ __attribute__((aligned(16))) char lds_m[];
-  if ((int)blockIdx.x < hub_blocks) {
-    (void)merge_unit<T, false, SLICE, kMergeWaves>(a, lds_m, blockIdx.x);
-  } else {
+  if ((int)blockIdx.x >= hub_blocks) {
     (void)merge_unit<T, false, SLICE, 1>(a, lds_m, blockIdx.x - hub_blocks);
     write_pos_out<SLICE>(a, blockIdx.x - hub_blocks);
+  } else {
+    constexpr int kSpan = kWave * kVec * SLICE;
+    const int n_spans = (a.D + kSpan - 1) / kSpan;
+    const int n_units = min(max(a.hub_cnt[blockIdx.y], 0), a.n_keep) * n_spans;     // uniform
+    for (int u = (int)blockIdx.x; u < n_units; u += hub_blocks) {
+      (void)merge_unit<T, false, SLICE, kMergeWaves>(a, lds_m, u);
+      __syncthreads();          // the partial sums in LDS are written again by the next entry
+    }
   }
 }
 
@@ -910,11 +922,12 @@ static void launch_merge_buckets(const MergeArgs& m, int B, hipStream_t s) {
   constexpr int kSpan = kWave * kVec * SLICE;
   const int n_spans = (m.D + kSpan - 1) / kSpan;
   const size_t lds = std::max(L1::bytes(m.n_disc), L8::bytes(m.n_disc));
-  const int hub_blocks = m.n_keep * n_spans;                       // at most every preserved token has a long bucket
+  const int hub_units = m.n_keep * n_spans;                        // at most every preserved token has a long bucket
+  const int hub_blocks = std::min(hub_units, std::max(64, (hub_units + 3) / 4));
   const int row_blocks = (m.n_out * n_spans + L1::kUnits - 1) / L1::kUnits;
   if (lds > 32768)
     (void)hipFuncSetAttribute((const void*)merge_buckets_kernel<T, SLICE>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-  hipLaunchKernelGGL((merge_buckets_kernel<T, SLICE>), dim3(hub_blocks + row_blocks, B), dim3(kMergeWaves * kWave), lds, s, m,
+  hipLaunchKernelGGL((merge_buckets_kernel<T, SLICE>), dim3(row_blocks + hub_blocks, B), dim3(kMergeWaves * kWave), lds, s, m,
                      hub_blocks);
 }
 

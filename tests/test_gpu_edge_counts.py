@@ -56,3 +56,22 @@ def test_decoder_step_with_bucketed_edges(ctx, corr, M, staged):
     for b in range(cfg["B"]):
         ref = P.oracle_l(cfg, b, fc.R_ATTN_RECV, corr)
         P.compare_image(out, b, ref, cfg["dtype"], cfg["vis_begin"], corr == fc.C_ATTN)
+
+
+@pytest.mark.parametrize("D", [64, 1544])
+def test_more_long_buckets_than_workgroups_for_them(ctx, D):
+    """2204 discarded tokens with three targets each among 100 preserved ones: nearly every target has
+    more than 32 sources, and the merge has one workgroup per four possible such targets (at least 64),
+    so some workgroups take a second target; 1544 features are two spans of a row."""
+    cfg = synth.ficoco_v_single(seed=93, B=2, grid=48, D=D, H=2, centres=5, dtype="bf16", n_keep=100)
+    kw = dict(corr_src=fc.C_ATTN, k_max=4, k_mode=fc.K_FIXED, fixed_k=3, window=2)
+    out, _ = P.run_v(cfg, cfg["A"], ctx=ctx, **kw)
+    okw = {k: v for k, v in kw.items() if k != "k_max"}
+    for b in range(cfg["B"]):
+        ref = P.oracle_v(cfg, cfg["A"], b, **okw)
+        sizes = {}
+        for j in ref["J"]:
+            for t in j:
+                sizes[int(t)] = sizes.get(int(t), 0) + 1
+        assert sum(1 for v in sizes.values() if v > 32) > 64
+        P.compare_image(out, b, ref, "bf16", cfg["vis_begin"], True)

@@ -235,6 +235,7 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.hub_list = take(B * (size_t)p.n_keep * sizeof(int32_t));
   pl.hub_cnt = take(B * sizeof(int32_t));
   pl.share_cnt = take(edges_inverted(pl) ? B * (size_t)invert_groups(pl) * p.n_keep * sizeof(int32_t) : 0);
+  pl.pair_tab = take(pair_records(p, pl) ? B * (size_t)pl.n_disc * sizeof(PairRec) : 0);
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;

@@ -53,6 +53,7 @@ struct Plan {
   size_t tgt_alpha;      // double [B][N^S*k_max]
   size_t hub_list, hub_cnt;   // int32 [B][n_keep], [B]: preserved tokens with long buckets (inverted lists only)
   size_t share_cnt;      // int32  [B][invert_groups][n_keep]  edges per target from each share of the discarded rows (fused step, inverted lists)
+  size_t pair_tab;       // PairRec [B][N^S]     first two edges of every discarded row (fused step, lists not inverted)
   size_t rowbuf;         // double [B][N^S][n_keep] (dense_rows only)
   size_t ct;             // float  [splits][B][N^S][n_keep]  approximate cosines (matrix-core path)
   size_t cmax;           // double [B][M]
@@ -121,8 +122,9 @@ void launch_gather(const ficoco_problem& p, const Plan& pl, const int32_t* keep_
                    int64_t sb, int64_t sn, int row_bytes, void* out, hipStream_t s);
 void launch_corr_gap(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, double* gap, hipStream_t s);
-// targets_counted: the edges per target and share of rows were counted while the correlate stage
-// wrote the lists (a fused step); otherwise the compress stage counts them from the lists it is given
+// targets_counted: the call follows the correlate stage of the same fused step, which counted the
+// edges per target and share of rows (inverted lists) or wrote the pair records (scanning merge)
+// while it wrote the lists; otherwise the compress stage works from the lists it is given alone
 void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                      const int32_t* keep_idx, const int32_t* edge_cnt, const int32_t* edge_tgt,
                      const double* edge_alpha, void* X_out, int32_t* pos_out,
@@ -132,8 +134,21 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
 // consecutive rows, one workgroup of the bucketing kernel per share.  In a fused step the filter
 // stage clears a counter per (share, target) and the correlate stage adds one per edge it writes,
 // so the bucketing kernel starts from the counts instead of reading every list in every workgroup.
+// Up to kMatchMaxRows discarded tokens every workgroup of the merge stages the image's edges in LDS:
+// count, source token and the first two (target, weight) pairs of each discarded row.  Gathered
+// from the lists (rows of k_max slots) that is two or three cache lines per four rows and several
+// strided loads per thread, in every workgroup; in a fused step the correlate stage therefore also
+// writes those fields as one 32-byte record per row, which the merge reads with whole-line loads.
+struct alignas(16) PairRec {
+  int32_t cnt, src, t0, t1;
+  double a0, a1;
+};
+static_assert(sizeof(PairRec) == 32, "two 16-byte loads per record");
 constexpr int kMatchMaxRows = 1024;
 constexpr int kInvertRows = 512;
+inline bool pair_records(const ficoco_problem& p, const Plan& pl) {     // (lists of at most 64 entries: one wavefront holds a row's edges)
+  return pl.n_disc > 0 && pl.n_disc <= kMatchMaxRows && p.k_max <= 64 && pl.fixed_k != 0;
+}
 inline bool edges_inverted(const Plan& pl) { return pl.n_disc > kMatchMaxRows; }
 inline int invert_groups(const Plan& pl) { return (pl.n_disc + kInvertRows - 1) / kInvertRows; }
 inline int invert_share_rows(const Plan& pl) {

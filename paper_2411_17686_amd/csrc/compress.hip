@@ -198,6 +198,7 @@ struct MergeArgs {
   int32_t* pos_out;
   const int32_t* hub_list;   // bucket mode: targets with more than kHubMin sources ...
   const int32_t* hub_cnt;    // ... and their number; null: no such split
+  const PairRec* pair_tab;   // [B][n_disc] the staged fields of every discarded row as one record (fused step), or null
   int average;      // ablation "average compression": every weight counts as one
   int extra_row;    // output row of the additional token of the convergent form (mean of the discarded tokens), or -1
 };
@@ -418,7 +419,18 @@ __device__ __forceinline__ int merge_unit(const MergeArgs& a, char* lds_m, int b
   constexpr int kStage = MATCH ? kMatchMaxRows / (kMergeWaves * kWave) : 1;   // edge-table rows per thread
   int st_cnt[kStage], st_src[kStage], st_t0[kStage], st_t1[kStage];
   double st_a0[kStage], st_a1[kStage];
-  if (MATCH && a.n_disc > 0) {
+  if (MATCH && a.n_disc > 0 && a.pair_tab) {       // uniform: one record per row, two whole-line loads
+#pragma unroll
+    for (int q = 0; q < kStage; ++q) {
+      const int row = min((int)threadIdx.x + q * kMergeWaves * kWave, a.n_disc - 1);   // clamped: a valid row
+      const PairRec* rec = a.pair_tab + (b * a.n_disc + row);
+      const int4 head = *reinterpret_cast<const int4*>(rec);
+      const double2 wts = *reinterpret_cast<const double2*>(&rec->a0);
+      st_cnt[q] = head.x; st_src[q] = head.y; st_t0[q] = head.z; st_t1[q] = head.w;
+      st_a0[q] = a.average ? 1.0 : wts.x;
+      st_a1[q] = a.average ? 1.0 : wts.y;
+    }
+  } else if (MATCH && a.n_disc > 0) {
     const int e1 = min(1, a.k_max - 1);
 #pragma unroll
     for (int q = 0; q < kStage; ++q) {
@@ -967,6 +979,7 @@ void launch_compress(const ficoco_problem& p, const Plan& pl, char* ws, const in
   m.edge_cnt = edge_cnt; m.edge_tgt = edge_tgt; m.edge_alpha = edge_alpha;
   m.pos = p.pos; m.pos_out = pos_out;
   m.average = p.compress_mode == FICOCO_COMPRESS_AVERAGE ? 1 : 0;
+  m.pair_tab = targets_counted && match && pair_records(p, pl) ? (const PairRec*)(ws + pl.pair_tab) : nullptr;
   m.extra_row = pl.extra_token ? p.vis_begin + p.n_keep : -1;
   // Narrow spans (one 8-element vector per lane) double the number of wavefronts: taken when the
   // wide ones would not fill the chip.  Bucket mode has two kinds of workgroups in its one launch:

@@ -45,7 +45,16 @@ struct CorrArgs {
   int32_t* share_cnt;    // [B][shares][n_keep] edges written per (share of discarded rows, target), cleared by the
                          // filter stage of a fused step; null where the compress stage counts for itself
   int shares, share_rows;
+  PairRec* pair_tab;     // [B][n_disc] first two edges of every row as one record (fused step, scanning merge), or null
 };
+
+// The record of discarded row `row` (source token i): written by one lane with two 16-byte stores.
+__device__ __forceinline__ void write_pair(const CorrArgs& a, int64_t b, int row, int cnt, int i, int t0, int t1,
+                                           double a0, double a1) {
+  PairRec r;
+  r.cnt = cnt; r.src = i; r.t0 = t0; r.t1 = t1; r.a0 = a0; r.a1 = a1;
+  a.pair_tab[b * a.n_disc + row] = r;
+}
 
 // One more edge from discarded row `row` to keep slot `tgt`: counted for the compress stage, which
 // buckets the edges by target (one workgroup per share of share_rows consecutive rows).
@@ -149,7 +158,10 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
   const int i = a.S[b * a.n_disc + row];
   const int32_t* T = a.T + b * n;
   if ((unsigned)i >= (unsigned)a.N) {  // index sets are device data: never index with a bad one
-    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    if (lane == 0) {
+      a.edge_cnt[b * a.n_disc + row] = 0;
+      if (a.pair_tab) write_pair(a, b, row, 0, 0, 0, 0, 0.0, 0.0);
+    }
     return;
   }
   const double* rowv = a.dense ? a.rowbuf + (b * a.n_disc + row) * n : nullptr;
@@ -249,6 +261,12 @@ __device__ void corr_row_exact(const CorrArgs& a, const int64_t b, const int row
       a.edge_alpha[ebase + e] = al;
       count_edge(a, b, row, a.edge_tgt[ebase + e]);
     }
+  }
+  if (a.pair_tab) {              // uniform (lists of at most 64 entries: lanes 0 and 1 hold the first two)
+    const double al = live && lane < stored ? my_c / denom : 0.0;
+    const int t0 = lane_value(my_tgt, 0), t1 = lane_value(my_tgt, 1);
+    const double a0 = lane_value(al, 0), a1 = lane_value(al, 1);
+    if (lane == 0) write_pair(a, b, row, live ? stored : 0, i, t0, t1, a0, a1);
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -431,7 +449,10 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
   const int i = a.S[b * a.n_disc + row];
   const int32_t* T = a.T + b * n;
   if ((unsigned)i >= (unsigned)a.N) {
-    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    if (lane == 0) {
+      a.edge_cnt[b * a.n_disc + row] = 0;
+      if (a.pair_tab) write_pair(a, b, row, 0, 0, 0, 0, 0.0, 0.0);
+    }
     return;
   }
   // approximate direct term of the row: the matrix-core cosines, or (FiCoCo-L with the
@@ -609,6 +630,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
   const bool is_eq = myjj >= 0 && myv == tau;
   const int eq_rank = __popcll(__ballot(is_eq) & ((1ULL << lane) - 1ULL));   // candidates are in ascending target order
   unsigned long long hit = __ballot(myjj >= 0 && (myv > tau || (is_eq && eq_rank < tie_quota)));
+  const unsigned long long hit_all = hit;
   const int cnt = __popcll(hit);
   const int my_pos = __popcll(hit & ((1ULL << lane) - 1ULL));
   const bool mine = (hit >> lane) & 1ULL;
@@ -626,6 +648,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(4))) void c
     a.edge_tgt[ebase + my_pos] = myjj;
     a.edge_alpha[ebase + my_pos] = al;
     count_edge(a, b, row, myjj);
+  }
+  if (a.pair_tab) {              // uniform; the lanes of the first two hits hold the first two edges
+    const double al = live && mine ? myv / denom : 0.0;
+    const unsigned long long rest = hit_all & (hit_all - 1);
+    const int l0 = hit_all ? __ffsll(hit_all) - 1 : 0, l1 = rest ? __ffsll(rest) - 1 : 0;
+    const int t0 = lane_value(myjj, l0), t1 = lane_value(myjj, l1);
+    const double a0 = lane_value(al, l0), a1 = lane_value(al, l1);
+    if (lane == 0) write_pair(a, b, row, live ? stored : 0, i, t0, t1, a0, a1);
   }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
@@ -654,7 +684,10 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
   if (row >= a.n_disc) return;                 // whole wavefront leaves together
   const int i = a.S[b * a.n_disc + row];
   if ((unsigned)i >= (unsigned)a.N) {          // index sets are device data
-    if (lane == 0) a.edge_cnt[b * a.n_disc + row] = 0;
+    if (lane == 0) {
+      a.edge_cnt[b * a.n_disc + row] = 0;
+      if (a.pair_tab) write_pair(a, b, row, 0, 0, 0, 0, 0.0, 0.0);
+    }
     return;
   }
   const float* mrow = a.abar + (b * a.N + i) * a.map_pitch;
@@ -813,6 +846,12 @@ __global__ __launch_bounds__(256) void corr_attn_rows_kernel(CorrArgs a) {
     a.edge_alpha[ebase + lane] = al;
     count_edge(a, b, row, my_tgt);
   }
+  if (a.pair_tab) {              // uniform
+    const double al = live && lane < stored ? my_c / denom : 0.0;
+    const int t0 = lane_value(my_tgt, 0), t1 = lane_value(my_tgt, 1);
+    const double a0 = lane_value(al, 0), a1 = lane_value(al, 1);
+    if (lane == 0) write_pair(a, b, row, live ? stored : 0, i, t0, t1, a0, a1);
+  }
   if (lane == 0) {
     a.edge_cnt[b * a.n_disc + row] = live ? stored : 0;
     if (live && cnt > a.k_max) a.overflow[b] = 1;
@@ -893,6 +932,7 @@ void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const i
   a.fixed_k = pl.fixed_k;
   a.ct_splits = pl.gram_splits;
   a.delta = (float)(pl.Df + 4 * pl.gram_splits) * 2.384185791015625e-07f;   // (Df + 4 splits) * 2^-22
+  if (fused && pair_records(p, pl)) a.pair_tab = (PairRec*)(ws + pl.pair_tab);
   if (fused && edges_inverted(pl)) {
     a.share_cnt = (int32_t*)(ws + pl.share_cnt);
     a.shares = invert_groups(pl);

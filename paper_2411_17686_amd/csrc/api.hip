@@ -342,10 +342,11 @@ static int run_step(ficoco_ctx* ctx, const ficoco_problem* p0, int variant, void
   if (pl.qk) launch_attn_qk(p, pl, w, s); else launch_attn_reduce(p, pl, w, s, tw);
   if (pr) (void)hipEventRecord(ctx->probe_stop, s);
   if (pl.need_features) launch_features(p, pl, w, s, tw, tw);
-  launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s, tw);
+  launch_select(p, pl, w, scores, true, true, discard_idx, keep_idx, overflow, s, tw, pos_out);
   launch_correlate(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, overflow, true,
                    pg ? ctx->probe_start : nullptr, pg ? ctx->probe_stop : nullptr, s);
-  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, pos_out, s, true);
+  // (the position ids of the preserved tokens were written by the filter, beside keep_idx)
+  launch_compress(p, pl, w, discard_idx, keep_idx, edge_cnt, edge_tgt, edge_alpha, X_out, nullptr, s, true);
   return finish(ctx, fn);
 }
 

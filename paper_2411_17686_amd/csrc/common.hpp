@@ -111,9 +111,11 @@ void launch_score(const ficoco_problem& p, const Plan& pl, char* ws, double* sco
                   bool text_stats_done = false);
 void launch_filter(const ficoco_problem& p, const Plan& pl, char* ws, const double* scores,
                    int32_t* discard_idx, int32_t* keep_idx, hipStream_t s);
+// pos_out: the filter also writes the position ids of the preserved tokens (a fused step: the
+// compress stage is then called without them), or null
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
                    bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
-                   hipStream_t s, bool text_stats_done = false);
+                   hipStream_t s, bool text_stats_done = false, int32_t* pos_out = nullptr);
 void launch_correlate(const ficoco_problem& p, const Plan& pl, char* ws, const int32_t* discard_idx,
                       const int32_t* keep_idx, int32_t* edge_cnt, int32_t* edge_tgt,
                       double* edge_alpha, int32_t* overflow, bool fused,

@@ -40,6 +40,7 @@ struct SelectArgs {
   int32_t* overflow;        // zeroed here for the correlate stage (fused step only), may be null
   int32_t* share_cnt;       // [B][share_n] edge counters of the correlate stage, zeroed here (fused step with inverted edge lists), or null
   int share_n;
+  int32_t* pos_out;         // [B][n_keep] position ids of the preserved tokens (fused step: written here, beside keep_idx), or null
   // Exact re-evaluation of the cosine-derived terms for tokens whose decision is within the error
   // bound of the bulk evaluation (exact_r: the mean-cosine term, exact_g: the equivalent-token term)
   int exact_r, exact_g;
@@ -752,7 +753,10 @@ __global__ __launch_bounds__(kSelectThreads) void select_kernel(SelectArgs a) {
       a.slot_of[(int64_t)b * N + i] = -1;
       ++d_pos;
     } else {
-      if (k_pos < n_keep) a.keep_idx[(int64_t)b * n_keep + k_pos] = i;
+      if (k_pos < n_keep) {
+        a.keep_idx[(int64_t)b * n_keep + k_pos] = i;
+        if (a.pos_out) a.pos_out[(int64_t)b * n_keep + k_pos] = a.pos ? a.pos[(int64_t)b * N + i] : i;
+      }
       a.slot_of[(int64_t)b * N + i] = k_pos;
       ++k_pos;
     }
@@ -891,7 +895,7 @@ void fill_text_stats(const ficoco_problem& p, const Plan& pl, char* ws, TextStat
 
 void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* scores, bool do_score,
                    bool do_filter, int32_t* discard_idx, int32_t* keep_idx, int32_t* overflow,
-                   hipStream_t s, bool text_stats_done) {
+                   hipStream_t s, bool text_stats_done, int32_t* pos_out) {
   SelectArgs a{};
   a.N = p.N; a.H = p.H; a.M = p.M; a.n_chunks = pl.n_chunks; a.dtype = p.dtype;
   a.red_src = p.red_src; a.sem_src = p.sem_src;
@@ -980,6 +984,7 @@ void launch_select(const ficoco_problem& p, const Plan& pl, char* ws, double* sc
   a.discard_idx = discard_idx; a.keep_idx = keep_idx;
   a.slot_of = (int32_t*)(ws + pl.slot_of);
   a.overflow = overflow;
+  a.pos_out = do_filter ? pos_out : nullptr;
   if (overflow && edges_inverted(pl)) {      // a fused step: the correlate stage counts its edges per target
     a.share_cnt = (int32_t*)(ws + pl.share_cnt);
     a.share_n = invert_groups(pl) * p.n_keep;

@@ -139,15 +139,18 @@ __global__ __launch_bounds__(256) void col_mean_kernel(FeatArgs a) {
   if (d < a.Df) {
     const double* p = a.colsum_part + b * a.f_chunks * (int64_t)a.Df + d;
     double su = 0.0, sr = 0.0;
-    int c = 0;
-    for (; c + 8 <= a.f_chunks; c += 8) {
+    for (int c = 0; c < a.f_chunks; c += 8) {     // past the last chunk the last one is loaded again and counted as zero
       double vu[8], vr[8];
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { vu[u] = p[(int64_t)(c + u) * a.Df]; vr[u] = p[slot + (int64_t)(c + u) * a.Df]; }
+      for (int u = 0; u < 8; ++u) {
+        const int64_t at = (int64_t)min(c + u, a.f_chunks - 1) * a.Df;
+        vu[u] = p[at];
+        vr[u] = p[slot + at];
+      }
+      issue_fence();
 #pragma unroll
-      for (int u = 0; u < 8; ++u) { su += vu[u]; sr += vr[u]; }
+      for (int u = 0; u < 8; ++u) { su += c + u < a.f_chunks ? vu[u] : 0.0; sr += c + u < a.f_chunks ? vr[u] : 0.0; }
     }
-    for (; c < a.f_chunks; ++c) { su += p[(int64_t)c * a.Df]; sr += p[slot + (int64_t)c * a.Df]; }
     const double mu = sr / (double)a.N;
     a.colmean[b * a.Df + d] = su / (double)a.N;
     a.colmean[(int64_t)a.B * a.Df + b * a.Df + d] = mu;

@@ -70,15 +70,14 @@ constexpr int kExactGroup = 8;    // tokens whose mean cosine is re-evaluated to
 template <typename T>
 __device__ __forceinline__ double vec_head_sum(const T* p, int H, int N) {
   double acc = 0.0;
-  int h = 0;
-  for (; h + 16 <= H; h += 16) {
+  for (int h = 0; h < H; h += 16) {       // past the last head the last one is loaded again and counted as zero
     T v[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(h + u) * N];
+    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)min(h + u, H - 1) * N];
+    issue_fence();
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc += widen(v[u]);
+    for (int u = 0; u < 16; ++u) acc += h + u < H ? widen(v[u]) : 0.0;
   }
-  for (; h < H; ++h) acc += widen(p[(int64_t)h * N]);
   return acc;
 }
 __device__ __forceinline__ double vec_head_mean(const void* v, int dtype, int64_t b, int H, int N, int i) {
@@ -772,16 +771,17 @@ __global__ __launch_bounds__(256) void combine_partials_kernel(const double* __r
   const int64_t b = blockIdx.y;
   if (i >= N) return;
   const double* p = part + b * n_chunks * (int64_t)N + i;
+  // 16 loads issued together; past the last chunk the last one is loaded again and counted as zero,
+  // so that the tail is one more trip to memory and not one per chunk
   double acc = 0.0;
-  int c = 0;
-  for (; c + 16 <= n_chunks; c += 16) {
+  for (int c = 0; c < n_chunks; c += 16) {
     double v[16];
 #pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)(c + u) * N];
+    for (int u = 0; u < 16; ++u) v[u] = p[(int64_t)min(c + u, n_chunks - 1) * N];
+    issue_fence();
 #pragma unroll
-    for (int u = 0; u < 16; ++u) acc += v[u];
+    for (int u = 0; u < 16; ++u) acc += c + u < n_chunks ? v[u] : 0.0;
   }
-  for (; c < n_chunks; ++c) acc += p[(int64_t)c * N];
   out[b * N + i] = acc;
 }
 

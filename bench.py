@@ -69,23 +69,23 @@ def make_workload(torch, fc, name, dev):
     g = torch.Generator(device=dev)
     bf, f32 = torch.bfloat16, torch.float32
     W = dict(name=name)
-    if name in ("1", "1c", "1q", "0", "2"):
+    if name in ("1", "1c", "1q", "0", "2", "2q"):
         B, grid_g, H, D = {"1": (16, 1, 16, 1024), "1c": (16, 1, 16, 1024), "1q": (16, 1, 16, 1024), "0": (1, 1, 16, 1024),
-                           "2": (4, 5, 16, 1024)}[name]
+                           "2": (4, 5, 16, 1024), "2q": (4, 5, 16, 1024)}[name]
         N = grid_g * 576
-        keep = {"1": 384, "1c": 384, "1q": 384, "0": 192, "2": 640}[name]
+        keep = {"1": 384, "1c": 384, "1q": 384, "0": 192, "2": 640, "2q": 640}[name]
         dt = f32 if name == "0" else bf
-        centres = {"1": 64, "1c": 64, "1q": 64, "0": 48, "2": 200}[name]
+        centres = {"1": 64, "1c": 64, "1q": 64, "0": 48, "2": 200, "2q": 200}[name]
         sigma = 1.5 if name in ("1", "1c", "1q") else 1.0
-        n_sets = {"1": 4, "1c": 4, "1q": 4, "0": 16, "2": 1}[name]
-        g.manual_seed({"1": 1, "1c": 1, "1q": 1, "0": 0, "2": 2}[name])
+        n_sets = {"1": 4, "1c": 4, "1q": 4, "0": 16, "2": 1, "2q": 4}[name]
+        g.manual_seed({"1": 1, "1c": 1, "1q": 1, "0": 0, "2": 2, "2q": 2}[name])
         d_head = 64
         sets = []
         for _ in range(n_sets):
             X = torch.empty(B, N + 1, D, device=dev)
             X[:, 0] = torch.randn(B, D, device=dev, generator=g)
             X[:, 1:] = _clustered(torch, g, dev, B, N, D, centres)
-            if name == "1q":
+            if name in ("1q", "2q"):
                 # queries and keys whose logits q.k / sqrt(d) are about N(0, sigma^2): the same family of maps
                 Q = (torch.randn(B, H, N + 1, d_head, device=dev, generator=g) * sigma ** 0.5).to(bf)
                 K = (torch.randn(B, H, N + 1, d_head, device=dev, generator=g) * sigma ** 0.5).to(bf)
@@ -97,18 +97,18 @@ def make_workload(torch, fc, name, dev):
         W.update(label="BASELINE config %s: FiCoCo-V fused step, B=%d, [CLS]+%d patches, D=%d, H=%d, %s, keep %d%s"
                  % (name[0] + (" step 1" if name[0] == "1" else ""), B, N, D, H, "bf16" if dt == bf else "f32", keep,
                     ", cosine correlation variant" if name == "1c" else
-                    ", maps formed from queries and keys (d_head 64) inside the step" if name == "1q" else ""),
+                    ", maps formed from queries and keys (d_head 64) inside the step" if name in ("1q", "2q") else ""),
                  B=B, N=N, D=D, H=H, keep=keep, dtype="bf16" if dt == bf else "f32", variant=fc.VARIANT_V, sets=sets,
                  kw=dict(vis_begin=1, N=N, n_keep=keep, cls_index=0, grid=(grid_g, 24, 24), window=2,
                          penalty_coef=2.0, w_score=0.35, eps=0.998, k_max=8,
                          corr_src=fc.C_COSINE if name == "1c" else fc.C_ATTN),
-                 dominant="gram" if name == "1c" else "qk" if name == "1q" else "reduce",
+                 dominant="gram" if name == "1c" else "qk" if name in ("1q", "2q") else "reduce",
                  qk_elements=B * H * (N + 1) * (N + 1), d_head=d_head,
                  qk_bytes=2 * B * H * (N + 1) * d_head * 2 + B * N * N * 4,
                  reduce_bytes=B * H * (N + 1) * (N + 1) * es + (0 if name == "1c" else B * N * N * 4),
                  gram_flops=2.0 * B * (N - keep) * keep * D,
                  step_bytes=B * H * (N + 1) * (N + 1) * es + B * N * N * 4 + B * (N + 1) * D * es
-                 + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name not in ("1c", "1q") else None)
+                 + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name not in ("1c", "1q", "2q") else None)
     elif name in ("3", "3p", "3b", "3bp"):
         B, n_sys, N, M, D, H, keep = 8, 35, 576, 64, 4096, 32, 144
         if name in ("3b", "3bp"):                # the 13B decoder shape with a long instruction
@@ -315,7 +315,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 1q (maps formed from queries and keys), 2, 3, 3p, 4; "
+    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 1q / 2q (configs 1 / 2 with the maps formed from queries and keys), 2, 3, 3p, 4; "
                                                   "3b / 3bp: the 13B decoder shape")
     ap.add_argument("--ablation", default="none",
                     choices=["none", "fixed0", "fixed1", "fixed2", "convergent", "average"],
@@ -467,12 +467,13 @@ def main():
         # 2 * d_head matrix-core flops; the vector operations are what the kernel waits for.
         algo = 7.0 * W["qk_elements"]
         achieved = algo / (alone_ms * 1e-3) / 1e12
-        roof = {"kernel": "attn_qk_kernel (softmax(QK^T) on bf16 MFMA 16x16x32, reduced on the fly)", "bound": "alu",
+        roof = {"kernel": "%s (softmax(QK^T) on bf16 MFMA 16x16x32, reduced on the fly)"
+                          % ("attn_qk_long_kernel" if W["N"] + 1 > 640 else "attn_qk_kernel"), "bound": "alu",
                 "achieved": achieved, "peak": 157.3, "unit": "TFLOP/s", "frac": achieved / 157.3, "traffic": None,
                 "algorithmic_flops": algo, "mfma_flops": 2.0 * W["d_head"] * W["qk_elements"],
                 "hbm_bytes_algorithmic": W["qk_bytes"],
-                "note": "the materialised-map path reads %d bytes of maps for the same outputs (bench.py --config 1)"
-                        % (W["qk_elements"] * 2)}
+                "note": "the materialised-map path reads %d bytes of maps for the same outputs (bench.py --config %s)"
+                        % (W["qk_elements"] * 2, W["name"][0])}
     elif W["dominant"] == "reduce":
         algo = W["reduce_bytes"]
         achieved = algo / (alone_ms * 1e-3) / 1e9

@@ -163,8 +163,8 @@ typedef struct {
    * unmasked, and reduces it on the fly -- the [B][H][n][n] maps are never stored.  Row r of Q
    * and of K is the token at sequence position qk_begin + r; the block must cover the visual
    * span and, for FICOCO_G_CLS_ATTN, cls_index.  bfloat16 only (qk_dtype = FICOCO_BF16, whatever
-   * `dtype` the tokens have), d_head in {32, 64, 128}, qk_n <= 640: FICOCO_EUNSUPPORTED
-   * otherwise.  Logits, exponentials and row sums are single precision (bf16 products are exact
+   * `dtype` the tokens have), d_head in {32, 64, 128}; with qk_n > 640 (the keys are then taken in blocks of 640, in two
+   * sweeps) at most 64 heads: FICOCO_EUNSUPPORTED otherwise.  Logits, exponentials and row sums are single precision (bf16 products are exact
    * in it), so scores and map entries agree with a double-precision evaluation to about 1e-6
    * relative, not to the last bit: a top-K or threshold decision whose margin is below that may
    * differ from one taken on double-precision values. */

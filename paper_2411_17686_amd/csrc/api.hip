@@ -80,9 +80,9 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
               "cls_index must be a row of Q / K outside the visual span");
     REQUIRE(p.qk_scale > 0.0f && p.qk_scale < 1e30f, "qk_scale must be positive and finite");
     if (p.qk_dtype != FICOCO_BF16 || !(p.d_head == 32 || p.d_head == 64 || p.d_head == 128) ||
-        p.qk_n > kQkMaxKeys || p.qk_stride_n % 8 != 0 || p.qk_stride_h % 8 != 0 || p.qk_stride_b % 8 != 0 ||
-        ((uintptr_t)p.Q & 15) || ((uintptr_t)p.K & 15)) {
-      *why = "queries / keys: bfloat16, 16-byte aligned rows, d_head in {32,64,128} and at most 640 rows are supported";
+        (p.qk_n > kQkMaxKeys && p.H > kQkLongMaxHeads) || p.qk_stride_n % 8 != 0 || p.qk_stride_h % 8 != 0 ||
+        p.qk_stride_b % 8 != 0 || ((uintptr_t)p.Q & 15) || ((uintptr_t)p.K & 15)) {
+      *why = "queries / keys: bfloat16, 16-byte aligned rows and d_head in {32,64,128} are supported (beyond 640 rows: at most 64 heads)";
       return FICOCO_EUNSUPPORTED;
     }
   } else if (need_A) {

@@ -230,6 +230,221 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
   }
 }
 
+// More keys than one workgroup holds in registers (kQkMaxKeys): the keys are taken in blocks of
+// kQkMaxKeys (each wavefront 80 of a block, as above), in two sweeps.  Sweep 1, head by head: the
+// row maximum and the row sum of every query over all key blocks, kept per wavefront as a running
+// (reference, sum) pair -- the reference a whole number in units of log2, so that rescaling the sum
+// when a later block raises it is exact -- and combined across the wavefronts once per head; the
+// results (reference, 1 / sum) of all heads wait in LDS.  Sweep 2, key block by key block: the
+// logits of every head are formed again, turned into probabilities with the stored pair and
+// accumulated over the heads in registers; the block's piece of the head-mean map, of the [CLS] row
+// and of the column partials is written as above.  The logits are computed twice; the maps still
+// never exist in memory.
+template <int KS>
+__global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a) {
+  extern __shared__ float norm[];                    // [H][kQkTile][2]: reference, 1 / row sum
+  __shared__ float xmax[kQkWaves][kQkTile];
+  __shared__ float xsum[kQkWaves][kQkTile];
+  const int total = a.n_tiles * a.B;
+  const int logical = xcd_logical_id(blockIdx.x, total);
+  if (logical >= total) return;
+  const int tile = logical % a.n_tiles;
+  const int64_t b = logical / a.n_tiles;
+  const int lane = threadIdx.x % kWave;
+  const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int l16 = lane % 16, lg = lane / 16;
+  const float NEG = -__builtin_huge_valf();
+  const int key_base = wv * kQkKB * 16;             // first key of this wavefront inside a key block
+  const int n_blocks = (a.n + kQkMaxKeys - 1) / kQkMaxKeys;
+
+  int64_t q_off[kQkQB];
+#pragma unroll
+  for (int qb = 0; qb < kQkQB; ++qb) q_off[qb] = (int64_t)min(tile * kQkTile + qb * 16 + l16, a.n - 1) * a.sn + lg * 8;
+
+  // Operands of head h and key block blk (rows clamped to valid ones), and the logits between this
+  // tile's queries and this wavefront's keys of the block (keys past the sequence read as -inf).
+  // The operands of the next (head, block) are loaded right after the matrix instructions of the
+  // current one, so that they arrive while its softmax is computed.
+  bf16x8_t kf[kQkKB][KS], qf[kQkQB][KS];
+  auto load_ops = [&](int h, int blk) {
+    const bf16_t* Qh = a.Q + b * a.sb + (int64_t)h * a.sh;
+    const bf16_t* Kh = a.K + b * a.sb + (int64_t)h * a.sh;
+    const int k0 = blk * kQkMaxKeys + key_base;
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb) {
+      const int64_t off = (int64_t)min(k0 + kb * 16 + l16, a.n - 1) * a.sn + lg * 8;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&kf[kb][ks], Kh + off + ks * 32, 16);
+    }
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb)
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&qf[qb][ks], Qh + q_off[qb] + ks * 32, 16);
+  };
+  auto logits = [&](int blk, f32x4_t (&S)[kQkKB][kQkQB], int h_next, int blk_next) {
+    const int k0 = blk * kQkMaxKeys + key_base;
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        S[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+          S[kb][qb] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kb][ks], qf[qb][ks], S[kb][qb], 0, 0, 0);
+      }
+    load_ops(h_next, blk_next);
+    issue_fence();                                   // the loads go out here, not where they are first used
+    if (k0 + kQkKB * 16 > a.n) {                     // scalar: only the last wavefronts of the last block
+#pragma unroll
+      for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v)
+          if (k0 + kb * 16 + lg * 4 + v >= a.n) {
+#pragma unroll
+            for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
+          }
+    }
+  };
+
+  // ---- sweep 1: (reference, 1 / sum) of every head and query ---------------------------------------
+  load_ops(0, 0);
+#pragma unroll 1
+  for (int h = 0; h < a.H; ++h) {
+    float mref[kQkQB], lsum[kQkQB];
+#pragma unroll
+    for (int qb = 0; qb < kQkQB; ++qb) { mref[qb] = NEG; lsum[qb] = 0.0f; }
+#pragma unroll 1
+    for (int blk = 0; blk < n_blocks; ++blk) {
+      f32x4_t S[kQkKB][kQkQB];
+      {
+        // next: the following block of this head, then block 0 of the next head; after the last of
+        // sweep 1 the first of sweep 2 (head 0, block 0)
+        const bool last_blk = blk + 1 == n_blocks;
+        logits(blk, S, last_blk ? (h + 1 < a.H ? h + 1 : 0) : h, last_blk ? 0 : blk + 1);
+      }
+      float mw[kQkQB];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        mw[qb] = NEG;
+#pragma unroll
+        for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) mw[qb] = fmaxf(mw[qb], S[kb][qb][v]);
+      }
+      {
+        float o[kQkQB];
+#pragma unroll
+        for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(mw[qb], 16, kWave);
+#pragma unroll
+        for (int qb = 0; qb < kQkQB; ++qb) mw[qb] = fmaxf(mw[qb], o[qb]);
+#pragma unroll
+        for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(mw[qb], 32, kWave);
+#pragma unroll
+        for (int qb = 0; qb < kQkQB; ++qb) mw[qb] = fmaxf(mw[qb], o[qb]);
+      }
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        // the block's maximum in units of log2, rounded up to a whole number; -inf: no key of it here
+        const float mc = mw[qb] > NEG ? ceilf(mw[qb] * a.scale_log2e) : NEG;
+        const float ref = fmaxf(mref[qb], mc);
+        const bool some = ref > NEG;                 // a key of this wavefront has been seen by now
+        lsum[qb] *= some && mref[qb] > NEG ? __builtin_amdgcn_exp2f(fmaxf(mref[qb] - ref, -150.0f)) : 0.0f;
+        mref[qb] = ref;
+        const float sub = some ? ref : 0.0f;
+#pragma unroll
+        for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v) lsum[qb] += __builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -sub));
+      }
+    }
+    {
+      float o[kQkQB];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(lsum[qb], 16, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) lsum[qb] += o[qb];
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) o[qb] = __shfl_xor(lsum[qb], 32, kWave);
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) lsum[qb] += o[qb];
+    }
+    if (lg == 0) {
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        xmax[wv][qb * 16 + l16] = mref[qb];
+        xsum[wv][qb * 16 + l16] = lsum[qb];
+      }
+    }
+    __syncthreads();
+    if ((int)threadIdx.x < kQkTile) {
+      const int qi = threadIdx.x;
+      float m = NEG;
+#pragma unroll
+      for (int w = 0; w < kQkWaves; ++w) m = fmaxf(m, xmax[w][qi]);               // finite: key 0 is valid
+      float l = 0.0f;
+#pragma unroll
+      for (int w = 0; w < kQkWaves; ++w)                                          // wavefronts in order
+        l += xmax[w][qi] > NEG ? xsum[w][qi] * __builtin_amdgcn_exp2f(fmaxf(xmax[w][qi] - m, -150.0f)) : 0.0f;
+      norm[(h * kQkTile + qi) * 2] = m;
+      norm[(h * kQkTile + qi) * 2 + 1] = 1.0f / l;
+    }
+    __syncthreads();              // the pairs are read back below; the exchange slots are written again by the next head
+  }
+
+  // ---- sweep 2: probabilities, head mean, outputs, key block by key block --------------------------
+  const float invH = 1.0f / (float)a.H;
+#pragma unroll 1
+  for (int blk = 0; blk < n_blocks; ++blk) {
+    f32x4_t P[kQkKB][kQkQB];
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) P[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 1
+    for (int h = 0; h < a.H; ++h) {
+      f32x4_t S[kQkKB][kQkQB];
+      {
+        // next: the following head of this block, then head 0 of the next block (past the end: the last again)
+        const bool last_h = h + 1 == a.H;
+        logits(blk, S, last_h ? 0 : h + 1, last_h ? min(blk + 1, n_blocks - 1) : blk);
+      }
+#pragma unroll
+      for (int qb = 0; qb < kQkQB; ++qb) {
+        const float m = norm[(h * kQkTile + qb * 16 + l16) * 2];
+        const float inv = norm[(h * kQkTile + qb * 16 + l16) * 2 + 1];
+#pragma unroll
+        for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+          for (int v = 0; v < 4; ++v)
+            P[kb][qb][v] = fmaf(__builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -m)), inv, P[kb][qb][v]);
+      }
+    }
+#pragma unroll
+    for (int kb = 0; kb < kQkKB; ++kb) {
+#pragma unroll
+      for (int v = 0; v < 4; ++v) {
+        const int key = blk * kQkMaxKeys + key_base + kb * 16 + lg * 4 + v;
+        const int ik = key - a.vis0;                                  // visual key index
+        const bool k_vis = key < a.n && ik >= 0 && ik < a.N;
+        float cs = 0.0f;                                              // received from this tile's visual queries
+#pragma unroll
+        for (int qb = 0; qb < kQkQB; ++qb) {
+          const int q = tile * kQkTile + qb * 16 + l16;
+          const int jq = q - a.vis0;                                  // visual query index
+          const bool q_vis = q < a.n && jq >= 0 && jq < a.N;
+          const float pm = P[kb][qb][v] * invH;                       // head-mean probability P[q][key]
+          if (a.abar && q_vis && k_vis) a.abar[(b * a.N + ik) * a.map_pitch + jq] = pm;
+          if (q == a.cls_r && k_vis) a.cls[b * a.N + ik] = (double)pm;
+          cs += q_vis ? pm : 0.0f;
+        }
+#pragma unroll
+        for (int off = 8; off > 0; off >>= 1) cs += __shfl_xor(cs, off, kWave);
+        if (l16 == 0 && k_vis) a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
+      }
+    }
+  }
+}
+
 void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s) {
   QkArgs a{};
   a.Q = (const bf16_t*)p.Q; a.K = (const bf16_t*)p.K;
@@ -244,6 +459,15 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
   a.cls = (double*)(ws + pl.cls);
   a.n_tiles = pl.n_chunks; a.B = p.B;
   const dim3 grid(xcd_padded_total(a.n_tiles * a.B)), block(kQkWaves * kWave);
+  if (p.qk_n > kQkMaxKeys) {          // keys in blocks, two sweeps
+    const size_t lds = (size_t)p.H * kQkTile * 2 * sizeof(float);
+    switch (p.d_head / 32) {
+      case 1: hipLaunchKernelGGL(attn_qk_long_kernel<1>, grid, block, lds, s, a); break;
+      case 2: hipLaunchKernelGGL(attn_qk_long_kernel<2>, grid, block, lds, s, a); break;
+      default: hipLaunchKernelGGL(attn_qk_long_kernel<4>, grid, block, lds, s, a); break;
+    }
+    return;
+  }
   switch (p.d_head / 32) {
     case 1: hipLaunchKernelGGL(attn_qk_kernel<1>, grid, block, 0, s, a); break;
     case 2: hipLaunchKernelGGL(attn_qk_kernel<2>, grid, block, 0, s, a); break;

@@ -83,7 +83,8 @@ int make_plan(const ficoco_problem& p, Plan& plan, const char** why);
 void launch_attn_reduce(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool text_elsewhere = false);
 void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s);
 constexpr int kQkTile = 48;        // query rows per workgroup of the query/key form
-constexpr int kQkMaxKeys = 640;    // keys it holds in registers
+constexpr int kQkMaxKeys = 640;    // keys it holds in registers (longer blocks: the keys in blocks of this size, two sweeps)
+constexpr int kQkLongMaxHeads = 64; // heads whose softmax normalisers that form keeps in LDS
 // with_text: the launch of the row-norm kernel also forms the text profiles and the launch of the
 // column-sum kernel their statistics (with_cmax: the column maxima too), see text_with_features
 void launch_features(const ficoco_problem& p, const Plan& pl, char* ws, hipStream_t s, bool with_text = false,

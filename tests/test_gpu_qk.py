@@ -109,6 +109,23 @@ def test_small_and_ragged_shapes(ctx, seed, grid, H, d, n_keep):
     assert full >= 1
 
 
+def test_long_sequence_at_full_width_from_queries_and_keys(ctx):
+    """2304 patches + [CLS], 16 heads of 64, D = 1024, 640 preserved (the size class of BASELINE
+    config 2): four key blocks, the last of 385 keys."""
+    full = _case(ctx, 42, 2, 48, 1024, 16, 64, "bf16", 640, 1.0)
+    say("2304-patch shape from Q, K: %d of 2 images with every decision identical" % full)
+
+
+@pytest.mark.parametrize("seed,grid,H,d,n_keep", [(1, 27, 3, 64, 300), (2, 36, 2, 32, 500), (3, 31, 5, 128, 700),
+                                                  (4, 40, 1, 64, 1000)])
+def test_sequences_longer_than_one_key_block(ctx, seed, grid, H, d, n_keep):
+    """More than 640 keys: the keys are taken in blocks of 640 in two sweeps (normalisers of every
+    head first, then the probabilities block by block).  730 keys: a second block of 90; 1297: a
+    third block of 17, most of whose wavefronts hold no key; 962 and 1601 with one to five heads."""
+    full = _case(ctx, 70 + seed, 2, grid, 72, H, d, ["f32", "bf16"][seed % 2], n_keep, 1.0)
+    assert full >= 1
+
+
 def test_unsupported_shapes_are_refused(ctx):
     cfg = synth.ficoco_v_single(seed=9, B=1, grid=4, D=8, H=1, centres=2, dtype="bf16", n_keep=8)
     Xd = cfg["X"].to("cuda")
@@ -119,3 +136,12 @@ def test_unsupported_shapes_are_refused(ctx):
         with pytest.raises(fc.FicocoError) as e:
             fc.workspace_bytes(p)
         assert e.value.code == fc.EUNSUPPORTED
+    # beyond 640 rows the normalisers of all heads are kept on chip: at most 64 heads
+    cfg = synth.ficoco_v_single(seed=9, B=1, grid=26, D=8, H=1, centres=2, dtype="bf16", n_keep=8)
+    Xd = cfg["X"].to("cuda")
+    Q = torch.zeros(1, 65, 677, 32, dtype=torch.bfloat16, device="cuda")
+    p = fc.make_problem(Xd, variant=fc.VARIANT_V, vis_begin=1, N=676, n_keep=8, cls_index=0, grid=(1, 26, 26), window=2,
+                        Q=Q, K=Q.clone())
+    with pytest.raises(fc.FicocoError) as e:
+        fc.workspace_bytes(p)
+    assert e.value.code == fc.EUNSUPPORTED

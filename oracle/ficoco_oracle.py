@@ -114,19 +114,24 @@ def round_to_dtype(x, dtype):
 
 
 # --------------------------------------------------------------------------- self-attention
-def attention_from_qk(Q, K, scale):
+def attention_from_qk(Q, K, scale, causal=False):
     """Sec. "Self-Attention": A = Softmax(Q K^T / sqrt(D)) per head, for a caller that hands over
     the projected queries and keys instead of the map.  Q [H, nq, d], K [H, nk, d] float64;
     `scale` (the 1/sqrt(D) of the equation) crosses the boundary as float32.  Returns [H, nq, nk]:
-    every row a softmax over all nk keys (no mask: the vision encoder attends everywhere).  The
-    logits are a float64 matrix product, the exponentials are taken relative to the row maximum
-    and the row is divided by its sum, keys added in order."""
+    every row a softmax over all nk keys (no mask: the vision encoder attends everywhere), or,
+    with causal=True (the decoder of FiCoCo-L; nq == nk, row r is sequence position r), over
+    keys 0 .. r only, the others exactly 0.  The logits are a float64 matrix product, the
+    exponentials are taken relative to the row maximum and the row is divided by its sum, keys
+    added in order."""
     Q = np.asarray(Q, dtype=F64)
     K = np.asarray(K, dtype=F64)
     sc = f32(scale)
     A = np.empty((Q.shape[0], Q.shape[1], K.shape[1]), dtype=F64)
+    later = np.triu(np.ones((Q.shape[1], K.shape[1]), dtype=bool), 1) if causal else None
     for h in range(Q.shape[0]):
         logits = (Q[h] @ K[h].T) * sc
+        if causal:
+            logits = np.where(later, -np.inf, logits)
         e = np.exp(logits - logits.max(axis=1, keepdims=True))
         den = np.zeros(e.shape[0], dtype=F64)
         for k in range(e.shape[1]):
@@ -566,6 +571,17 @@ def l_step(X, A_vv, A_tv, *, vis_begin, N, n_keep, beta=0.6, gamma=0.6, eps=0.99
         raise ValueError(corr_src)
     C_of = lambda S, T: correlation_l(direct(S, T), text_bridge(Pt, S, T), gamma)
     return _finish(X, vis_begin, s, n_keep, C_of, eps, None, k_mode, fixed_k, average)
+
+
+def l_step_qk(X, Q, K, scale, *, vis_begin, N, M, **kw):
+    """Algorithm 2 for a caller that supplies the decoder layer's projected queries and keys
+    (Q, K: [H, n_tot, d], causal attention) instead of the maps: the M text tokens follow the
+    visual span, A_tv is their attention on the visual keys and A_vv the visual block of the
+    same maps (reading R16)."""
+    A = attention_from_qk(Q, K, scale, causal=True)
+    vis = slice(vis_begin, vis_begin + N)
+    txt = slice(vis_begin + N, vis_begin + N + M)
+    return l_step(X, A[:, vis, vis], A[:, txt, vis], vis_begin=vis_begin, N=N, **kw)
 
 
 def gather_tokens(t, vis_begin, N, T):

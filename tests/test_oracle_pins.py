@@ -165,6 +165,37 @@ def test_step_from_qk_equals_step_from_the_map_it_defines():
     assert all(np.array_equal(x, y) for x, y in zip(a["J"], b["J"]))
 
 
+def test_causal_attention_from_qk():
+    """The decoder's causal maps: row r is the unmasked softmax over keys 0 .. r alone (computed
+    here row by row with a library log-sum-exp on the truncated key set), zero above the diagonal,
+    the first row is (1, 0, ...), identical keys give 1 / (r + 1); and a FiCoCo-L step fed Q, K
+    equals the step fed the visual and text blocks of the maps they define."""
+    from scipy.special import logsumexp
+    r = rng(72)
+    H, n, d = 2, 11, 4
+    Q, K = r.standard_normal((H, n, d)), r.standard_normal((H, n, d))
+    A = O.attention_from_qk(Q, K, 0.4, causal=True)
+    sc = float(np.float32(0.4))
+    for h in range(H):
+        for q in range(n):
+            L = (K[h, :q + 1] @ Q[h, q]) * sc
+            assert np.allclose(A[h, q, :q + 1], np.exp(L - logsumexp(L)), rtol=1e-13)
+            assert np.all(A[h, q, q + 1:] == 0.0)
+    assert np.all(A[:, 0, 0] == 1.0)
+    same = O.attention_from_qk(Q, np.tile(K[:, :1], (1, n, 1)), 0.4, causal=True)
+    for q in range(n):
+        assert np.allclose(same[:, q, :q + 1], 1.0 / (q + 1), rtol=0, atol=1e-15)
+    # the step: 2 system tokens, 6 visual, 3 text
+    n_sys, N, M, D = 2, 6, 3, 5
+    X = r.standard_normal((n, D))
+    kw = dict(n_keep=3, beta=0.6, gamma=0.6)
+    vis, txt = slice(n_sys, n_sys + N), slice(n_sys + N, n)
+    a = O.l_step(X, A[:, vis, vis], A[:, txt, vis], vis_begin=n_sys, N=N, **kw)
+    b = O.l_step_qk(X, Q, K, 0.4, vis_begin=n_sys, N=N, M=M, **kw)
+    assert np.array_equal(a["S"], b["S"]) and np.array_equal(a["X_out"], b["X_out"])
+    assert all(np.array_equal(x, y) for x, y in zip(a["J"], b["J"]))
+
+
 # ------------------------------------------------------------------ equivalent token / mean cosine
 def test_equivalent_token_closed_forms():
     """a^Eq = -cos(mu, F_i): identical tokens -> -1; F = {e1, e2} -> mu = (.5,.5), cos = 1/sqrt2."""

@@ -109,8 +109,10 @@ def make_workload(torch, fc, name, dev):
                  gram_flops=2.0 * B * (N - keep) * keep * D,
                  step_bytes=B * H * (N + 1) * (N + 1) * es + B * N * N * 4 + B * (N + 1) * D * es
                  + B * (keep + 1) * D * es + B * (N - keep) * keep * 4 if name not in ("1c", "1q", "2q") else None)
-    elif name in ("3", "3p", "3b", "3bp"):
+    elif name in ("3", "3p", "3b", "3bp", "3q", "3pq"):
         B, n_sys, N, M, D, H, keep = 8, 35, 576, 64, 4096, 32, 144
+        from_qk = name in ("3q", "3pq")
+        d_head = D // H
         if name in ("3b", "3bp"):                # the 13B decoder shape with a long instruction
             M, D, H = 512, 5120, 40
         n_tot = n_sys + N + M
@@ -121,23 +123,35 @@ def make_workload(torch, fc, name, dev):
         for _ in range(3):
             X = torch.randn(B, n_tot, D, device=dev, generator=g)
             X[:, n_sys:n_sys + N] = _clustered(torch, g, dev, B, N, D, 96)
+            if from_qk:
+                # the decoder layer's queries and keys (logits about N(0, 1)); the maps are causal
+                Q = torch.randn(B, H, n_tot, d_head, device=dev, generator=g).to(bf)
+                K = torch.randn(B, H, n_tot, d_head, device=dev, generator=g).to(bf)
+                sets.append(dict(X=X.to(bf).contiguous(), Q=Q, K=K))
+                continue
             A_tv = _softmax_map(torch, g, dev, B, H, M, n_tot, 1.0, bf, cols=(n_sys, n_sys + N))
             st = dict(X=X.to(bf).contiguous(), A_text=A_tv)
             if name in ("3p", "3bp"):
                 st["A"] = _softmax_map(torch, g, dev, B, H, N, n_sys + N, 1.0, bf, mask=mask, cols=(n_sys, n_sys + N))
             sets.append(st)
-        with_vv = name in ("3p", "3bp")
+        with_vv = name in ("3p", "3bp", "3pq")
+        q_rows = N + M if with_vv else M
         W.update(label="%s%s: FiCoCo-L fused step, B=8, 35 system + 576 visual + %d text tokens, "
                        "D=%d, H=%d, bf16, keep 144%s"
                        % ("BASELINE config 3" if M == 64 else "13B decoder shape", "'" if with_vv else "", M, D, H,
-                          " (with the causal visual->visual map)" if with_vv
-                          else " (no visual->visual map: mean-cosine + cosine correlation)"),
+                          (" (with the causal visual->visual map)" if with_vv
+                           else " (no visual->visual map: mean-cosine + cosine correlation)")
+                          + (", maps formed from the decoder layer's queries and keys (d_head %d) inside the step" % d_head
+                             if from_qk else "")),
                  B=B, N=N, D=D, H=H, keep=keep, dtype="bf16", variant=fc.VARIANT_L, sets=sets,
                  kw=dict(vis_begin=n_sys, N=N, n_keep=keep, a_q_begin=n_sys, a_k_begin=n_sys, at_k_begin=n_sys,
                          w_score=0.6, gamma=0.6, eps=0.998, k_max=8, window=0, sem_src=fc.G_TEXT_ATTN,
+                         **(dict(M=M) if from_qk else {}),
                          red_src=fc.R_ATTN_RECV if with_vv else fc.R_SIM_MEAN,
                          corr_src=fc.C_ATTN if with_vv else fc.C_COSINE),
-                 dominant="reduce" if with_vv else "gram",
+                 dominant="qk" if from_qk else "reduce" if with_vv else "gram",
+                 qk_elements=B * H * q_rows * n_tot, d_head=d_head, qk_long=True,
+                 qk_bytes=2 * B * H * n_tot * d_head * 2 + B * N * M * 8 + (B * N * N * 4 if with_vv else 0),
                  reduce_bytes=B * H * N * N * 2 + B * N * N * 4 + B * H * M * N * 2,
                  gram_flops=2.0 * B * (N - keep) * keep * D, step_bytes=None)
     elif name == "4":
@@ -315,7 +329,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=400)
     ap.add_argument("--warmup", type=int, default=40)
-    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 1q / 2q (configs 1 / 2 with the maps formed from queries and keys), 2, 3, 3p, 4; "
+    ap.add_argument("--config", default="1", help="0, 1 (default), 1c, 1q / 2q / 3q / 3pq (configs 1 / 2 / 3 / 3p with the maps formed from queries and keys), 2, 3, 3p, 4; "
                                                   "3b / 3bp: the 13B decoder shape")
     ap.add_argument("--ablation", default="none",
                     choices=["none", "fixed0", "fixed1", "fixed2", "convergent", "average"],
@@ -468,7 +482,7 @@ def main():
         algo = 7.0 * W["qk_elements"]
         achieved = algo / (alone_ms * 1e-3) / 1e12
         roof = {"kernel": "%s (softmax(QK^T) on bf16 MFMA 16x16x32, reduced on the fly)"
-                          % ("attn_qk_long_kernel" if W["N"] + 1 > 640 else "attn_qk_kernel"), "bound": "alu",
+                          % ("attn_qk_long_kernel" if W.get("qk_long") or W["N"] + 1 > 640 else "attn_qk_kernel"), "bound": "alu",
                 "achieved": achieved, "peak": 157.3, "unit": "TFLOP/s", "frac": achieved / 157.3, "traffic": None,
                 "algorithmic_flops": algo, "mfma_flops": 2.0 * W["d_head"] * W["qk_elements"],
                 "hbm_bytes_algorithmic": W["qk_bytes"],

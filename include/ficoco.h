@@ -158,13 +158,17 @@ typedef struct {
   int32_t compress_mode; /* ficoco_compress_mode                                           */
 
   /* Queries and keys instead of the map (Sec. "Self-Attention": A = Softmax(Q K^T / sqrt(D))).
-   * Used when A is NULL and an attention-derived term is selected (FiCoCo-V only): the step then
+   * FiCoCo-V: used when A is NULL and an attention-derived term is selected: the step then
    * forms softmax(qk_scale * Q_h K_h^T) of every head itself, row by row over all qk_n keys,
    * unmasked, and reduces it on the fly -- the [B][H][n][n] maps are never stored.  Row r of Q
    * and of K is the token at sequence position qk_begin + r; the block must cover the visual
-   * span and, for FICOCO_G_CLS_ATTN, cls_index.  bfloat16 only (qk_dtype = FICOCO_BF16, whatever
+   * span and, for FICOCO_G_CLS_ATTN, cls_index.
+   * FiCoCo-L: used when both A and A_text are NULL (M must be set): the maps are the decoder's,
+   * causal (row r attends rows 0 .. r of the block); the M text tokens are the positions
+   * vis_begin + N .. vis_begin + N + M - 1 and must lie inside the block; their rows give the
+   * text profiles of Eq. 3 / Eq. 4, the visual rows the visual-to-visual terms where selected.  bfloat16 only (qk_dtype = FICOCO_BF16, whatever
    * `dtype` the tokens have), d_head in {32, 64, 128}; with qk_n > 640 (the keys are then taken in blocks of 640, in two
-   * sweeps) at most 64 heads: FICOCO_EUNSUPPORTED otherwise.  Logits, exponentials and row sums are single precision (bf16 products are exact
+   * sweeps) and for FiCoCo-L at most 64 heads: FICOCO_EUNSUPPORTED otherwise.  Logits, exponentials and row sums are single precision (bf16 products are exact
    * in it), so scores and map entries agree with a double-precision evaluation to about 1e-6
    * relative, not to the last bit: a top-K or threshold decision whose margin is below that may
    * differ from one taken on double-precision values. */

@@ -67,22 +67,26 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   const bool L = p.variant == FICOCO_VARIANT_L;
   const bool need_A = p.red_src == FICOCO_R_ATTN_RECV || p.sem_src == FICOCO_G_CLS_ATTN ||
                       p.corr_src == FICOCO_C_ATTN;
-  const bool qk = need_A && p.A == nullptr && p.Q != nullptr && p.K != nullptr;
+  // queries and keys in place of the maps: FiCoCo-V with an attention-derived term and no A;
+  // FiCoCo-L with neither A nor A_text (the decoder's causal maps; the M text tokens follow the visual span)
+  const bool qk = p.A == nullptr && p.Q != nullptr && p.K != nullptr && (L ? p.A_text == nullptr : need_A);
   if (qk) {
-    REQUIRE(!L, "queries and keys in place of the map are taken by FiCoCo-V only");
     REQUIRE(p.H >= 1 && p.qk_n >= 1 && p.qk_stride_n >= p.d_head && p.qk_stride_h >= 0 && p.qk_stride_b >= 0,
             "bad Q / K shape or strides");
     REQUIRE(p.qk_begin >= 0 && p.qk_begin <= p.vis_begin && p.vis_begin + p.N <= p.qk_begin + p.qk_n,
             "Q / K do not cover the visual tokens");
+    if (L)
+      REQUIRE(p.M >= 1 && p.vis_begin + p.N + (int64_t)p.M <= p.qk_begin + (int64_t)p.qk_n,
+              "Q / K do not cover the M text tokens behind the visual span");
     if (p.sem_src == FICOCO_G_CLS_ATTN)
       REQUIRE(p.cls_index >= p.qk_begin && p.cls_index < p.qk_begin + p.qk_n &&
                   (p.cls_index < p.vis_begin || p.cls_index >= p.vis_begin + p.N),
               "cls_index must be a row of Q / K outside the visual span");
     REQUIRE(p.qk_scale > 0.0f && p.qk_scale < 1e30f, "qk_scale must be positive and finite");
     if (p.qk_dtype != FICOCO_BF16 || !(p.d_head == 32 || p.d_head == 64 || p.d_head == 128) ||
-        (p.qk_n > kQkMaxKeys && p.H > kQkLongMaxHeads) || p.qk_stride_n % 8 != 0 || p.qk_stride_h % 8 != 0 ||
+        ((L || p.qk_n > kQkMaxKeys) && p.H > kQkLongMaxHeads) || p.qk_stride_n % 8 != 0 || p.qk_stride_h % 8 != 0 ||
         p.qk_stride_b % 8 != 0 || ((uintptr_t)p.Q & 15) || ((uintptr_t)p.K & 15)) {
-      *why = "queries / keys: bfloat16, 16-byte aligned rows and d_head in {32,64,128} are supported (beyond 640 rows: at most 64 heads)";
+      *why = "queries / keys: bfloat16, 16-byte aligned rows and d_head in {32,64,128} are supported (beyond 640 rows and for FiCoCo-L: at most 64 heads)";
       return FICOCO_EUNSUPPORTED;
     }
   } else if (need_A) {
@@ -101,10 +105,11 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   }
   if (L) {
     REQUIRE(p.sem_src == FICOCO_G_TEXT_ATTN, "FiCoCo-L uses the text-attention term (Eq. 3)");
-    REQUIRE(p.A_text != nullptr && p.M >= 1 && p.H >= 1, "A_text / M missing for FiCoCo-L");
+    REQUIRE((qk || p.A_text != nullptr) && p.M >= 1 && p.H >= 1, "A_text / M missing for FiCoCo-L");
     REQUIRE(p.gamma >= 0.0f && p.gamma <= 1.0f, "gamma (Eq. 4) must be in [0, 1]");
-    REQUIRE(p.at_stride_q >= p.at_nk && p.at_k_begin <= p.vis_begin &&
-                p.vis_begin + p.N <= p.at_k_begin + p.at_nk, "A_text does not cover the visual keys");
+    if (!qk)
+      REQUIRE(p.at_stride_q >= p.at_nk && p.at_k_begin <= p.vis_begin &&
+                  p.vis_begin + p.N <= p.at_k_begin + p.at_nk, "A_text does not cover the visual keys");
   } else {
     REQUIRE(p.sem_src != FICOCO_G_TEXT_ATTN, "the text-attention term belongs to FiCoCo-L");
   }
@@ -166,7 +171,10 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   };
   pl.qk = qk;
   if (qk) {
-    pl.n_chunks = (p.qk_n + kQkTile - 1) / kQkTile;    // one column partial per tile of query rows
+    // one column partial per tile of query rows: all rows of the block, or (FiCoCo-L) the visual and
+    // text rows, or the text rows alone where no visual-to-visual term is needed
+    const int q_rows = !L ? p.qk_n : (p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN) ? p.N + p.M : p.M;
+    pl.n_chunks = (q_rows + kQkTile - 1) / kQkTile;
   } else if (need_A) {
     int lo = p.vis_begin - p.a_q_begin, hi = lo + p.N;  // visual query rows
     const bool vis_rows = p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN;

@@ -33,6 +33,11 @@ struct QkArgs {
   double* recv_part;    // [B][n_tiles][N]
   double* cls;          // [B][N]
   int n_tiles, B;
+  // the two-sweep kernel only:
+  int q_begin, q_count; // block rows whose queries are needed (the tiles cover these)
+  int causal;           // decoder: query r attends keys 0 .. r
+  int text0, M;         // FiCoCo-L: block row of the first text query, number of text queries
+  double* ttext;        // FiCoCo-L: [B][N][M] head-mean attention of the text queries on the visual keys, or null
 };
 
 // v_mfma_f32_16x16x32_bf16: operand A is 16 rows x 32 features (lane: row lane % 16, features
@@ -239,7 +244,10 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
 // logits of every head are formed again, turned into probabilities with the stored pair and
 // accumulated over the heads in registers; the block's piece of the head-mean map, of the [CLS] row
 // and of the column partials is written as above.  The logits are computed twice; the maps still
-// never exist in memory.
+// never exist in memory.  The same kernel serves the decoder of FiCoCo-L (causal = 1: a key behind
+// its query reads as -inf like a key past the sequence; the tiles cover the visual and the text
+// queries, or the text queries alone where no visual-to-visual term is needed; the rows of the text
+// queries leave as the text profiles of Eq. 3 / Eq. 4).
 template <int KS>
 __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a) {
   extern __shared__ float norm[];                    // [H][kQkTile][2]: reference, 1 / row sum
@@ -256,10 +264,19 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   const float NEG = -__builtin_huge_valf();
   const int key_base = wv * kQkKB * 16;             // first key of this wavefront inside a key block
   const int n_blocks = (a.n + kQkMaxKeys - 1) / kQkMaxKeys;
+  const int q_first = a.q_begin + tile * kQkTile;   // block row of this tile's first query
+  const int q_end = min(a.q_begin + a.q_count, a.n);
+  // decoder: key blocks that begin behind the tile's last query hold no key any of its queries
+  // attends -- they are not computed (their pieces of the outputs are written as zeros)
+  const int nb = a.causal ? min(n_blocks, min(q_first + kQkTile - 1, q_end - 1) / kQkMaxKeys + 1) : n_blocks;
 
+  int q_row[kQkQB];
   int64_t q_off[kQkQB];
 #pragma unroll
-  for (int qb = 0; qb < kQkQB; ++qb) q_off[qb] = (int64_t)min(tile * kQkTile + qb * 16 + l16, a.n - 1) * a.sn + lg * 8;
+  for (int qb = 0; qb < kQkQB; ++qb) {
+    q_row[qb] = q_first + qb * 16 + l16;
+    q_off[qb] = (int64_t)min(q_row[qb], a.n - 1) * a.sn + lg * 8;
+  }
 
   // Operands of head h and key block blk (rows clamped to valid ones), and the logits between this
   // tile's queries and this wavefront's keys of the block (keys past the sequence read as -inf).
@@ -304,6 +321,17 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
             for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
           }
     }
+    if (a.causal && k0 + kQkKB * 16 - 1 > q_first) {  // scalar: some key of this wavefront may lie behind some query
+#pragma unroll
+      for (int kb = 0; kb < kQkKB; ++kb)
+#pragma unroll
+        for (int v = 0; v < 4; ++v) {
+          const int key = k0 + kb * 16 + lg * 4 + v;
+#pragma unroll
+          for (int qb = 0; qb < kQkQB; ++qb)
+            if (key > q_row[qb]) S[kb][qb][v] = NEG;
+        }
+    }
   };
 
   // ---- sweep 1: (reference, 1 / sum) of every head and query ---------------------------------------
@@ -314,12 +342,12 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
 #pragma unroll
     for (int qb = 0; qb < kQkQB; ++qb) { mref[qb] = NEG; lsum[qb] = 0.0f; }
 #pragma unroll 1
-    for (int blk = 0; blk < n_blocks; ++blk) {
+    for (int blk = 0; blk < nb; ++blk) {
       f32x4_t S[kQkKB][kQkQB];
       {
         // next: the following block of this head, then block 0 of the next head; after the last of
         // sweep 1 the first of sweep 2 (head 0, block 0)
-        const bool last_blk = blk + 1 == n_blocks;
+        const bool last_blk = blk + 1 == nb;
         logits(blk, S, last_blk ? (h + 1 < a.H ? h + 1 : 0) : h, last_blk ? 0 : blk + 1);
       }
       float mw[kQkQB];
@@ -401,12 +429,12 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) P[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 1
-    for (int h = 0; h < a.H; ++h) {
+    for (int h = 0; h < (blk < nb ? a.H : 0); ++h) {
       f32x4_t S[kQkKB][kQkQB];
       {
         // next: the following head of this block, then head 0 of the next block (past the end: the last again)
         const bool last_h = h + 1 == a.H;
-        logits(blk, S, last_h ? 0 : h + 1, last_h ? min(blk + 1, n_blocks - 1) : blk);
+        logits(blk, S, last_h ? 0 : h + 1, last_h ? min(blk + 1, nb - 1) : blk);
       }
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) {
@@ -429,17 +457,19 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
         float cs = 0.0f;                                              // received from this tile's visual queries
 #pragma unroll
         for (int qb = 0; qb < kQkQB; ++qb) {
-          const int q = tile * kQkTile + qb * 16 + l16;
+          const int q = q_row[qb];
           const int jq = q - a.vis0;                                  // visual query index
-          const bool q_vis = q < a.n && jq >= 0 && jq < a.N;
+          const bool q_vis = q < q_end && jq >= 0 && jq < a.N;
           const float pm = P[kb][qb][v] * invH;                       // head-mean probability P[q][key]
           if (a.abar && q_vis && k_vis) a.abar[(b * a.N + ik) * a.map_pitch + jq] = pm;
           if (q == a.cls_r && k_vis) a.cls[b * a.N + ik] = (double)pm;
+          const int mq = q - a.text0;                                 // text query index
+          if (a.ttext && q < q_end && mq >= 0 && mq < a.M && k_vis) a.ttext[(b * a.N + ik) * a.M + mq] = (double)pm;
           cs += q_vis ? pm : 0.0f;
         }
 #pragma unroll
         for (int off = 8; off > 0; off >>= 1) cs += __shfl_xor(cs, off, kWave);
-        if (l16 == 0 && k_vis) a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
+        if (a.recv_part && l16 == 0 && k_vis) a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
       }
     }
   }
@@ -458,8 +488,20 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
   a.recv_part = (double*)(ws + pl.recv_part);
   a.cls = (double*)(ws + pl.cls);
   a.n_tiles = pl.n_chunks; a.B = p.B;
+  a.q_begin = 0; a.q_count = p.qk_n;
+  const bool L = p.variant == FICOCO_VARIANT_L;
+  if (L) {                            // decoder: causal; the text queries follow the visual span
+    const bool need_vv = p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN;
+    a.causal = 1;
+    a.text0 = a.vis0 + p.N;
+    a.M = p.M;
+    a.ttext = (double*)(ws + pl.ttext);
+    a.q_begin = need_vv ? a.vis0 : a.text0;
+    a.q_count = need_vv ? p.N + p.M : p.M;
+    if (!need_vv) a.recv_part = nullptr;
+  }
   const dim3 grid(xcd_padded_total(a.n_tiles * a.B)), block(kQkWaves * kWave);
-  if (p.qk_n > kQkMaxKeys) {          // keys in blocks, two sweeps
+  if (L || p.qk_n > kQkMaxKeys) {     // keys in blocks, two sweeps
     const size_t lds = (size_t)p.H * kQkTile * 2 * sizeof(float);
     switch (p.d_head / 32) {
       case 1: hipLaunchKernelGGL(attn_qk_long_kernel<1>, grid, block, lds, s, a); break;

@@ -162,7 +162,7 @@ def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_b
                  pos=None, grid=(1, 0, 0), window=0, penalty_coef=2.0, w_score=0.35, gamma=0.6,
                  eps=0.998, red_src=R_ATTN_RECV, sem_src=G_CLS_ATTN, corr_src=C_ATTN, k_max=8, H=None,
                  k_mode=K_ADAPTIVE, fixed_k=0, compress_mode=COMPRESS_SELF, Q=None, K=None, qk_begin=0,
-                 qk_scale=None):
+                 qk_scale=None, M=None):
     """Fill a `ficoco_problem` from torch tensors (shapes as in include/ficoco.h).  The
     returned Problem only holds raw pointers: keep the tensors alive while it is used."""
     p = Problem()
@@ -212,6 +212,8 @@ def make_problem(X, *, variant, vis_begin, N, n_keep, A=None, a_q_begin=0, a_k_b
         p.H = int(Q.shape[1])
         p.qk_begin, p.qk_n, p.d_head, p.qk_dtype = qk_begin, Q.shape[2], Q.shape[3], BF16
         p.qk_scale = float(Q.shape[3]) ** -0.5 if qk_scale is None else qk_scale
+    if M is not None and A_text is None:
+        p.M = M           # FiCoCo-L from queries and keys: the text tokens follow the visual span
     return p
 
 

@@ -244,6 +244,20 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.hub_cnt = take(B * sizeof(int32_t));
   pl.share_cnt = take(edges_inverted(pl) ? B * (size_t)invert_groups(pl) * p.n_keep * sizeof(int32_t) : 0);
   pl.pair_tab = take(pair_records(p, pl) ? B * (size_t)pl.n_disc * sizeof(PairRec) : 0);
+  pl.qk_groups = 1;
+  if (qk && (L || p.qk_n > kQkMaxKeys)) {
+    // Few query tiles (a decoder's 64 text queries are two): the heads are split over up to eight
+    // workgroups per tile until the chip has about one workgroup per compute unit.
+    const int64_t base = (int64_t)pl.n_chunks * p.B;
+    const int want = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(p.H, 8), 256 / std::max<int64_t>(base, 1)));
+    const int per = (p.H + want - 1) / want;
+    pl.qk_groups = (p.H + per - 1) / per;            // no group without heads
+  }
+  {
+    const size_t g = pl.qk_groups > 1 ? (size_t)pl.qk_groups : 0;
+    const size_t map = p.corr_src == FICOCO_C_ATTN ? B * N * (size_t)pl.map_pitch : 0;
+    pl.qk_part = take(g * (map + (L ? B * N * (size_t)p.M : 0) + B * (size_t)pl.n_chunks * N + B * N) * sizeof(float));
+  }
   pl.rowbuf = take(pl.dense_rows ? B * (size_t)pl.n_disc * p.n_keep * sizeof(double) : 0);
   pl.use_gram = p.corr_src == FICOCO_C_COSINE && !pl.dense_rows && pl.Df % 8 == 0 && p.k_max <= 64 &&
                 pl.n_disc > 0;

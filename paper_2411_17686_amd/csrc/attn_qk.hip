@@ -8,6 +8,8 @@
 // of the softmax, not memory, bounds the kernel.
 #include "common.hpp"
 
+#include <algorithm>
+
 namespace ficoco {
 
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
@@ -38,6 +40,14 @@ struct QkArgs {
   int causal;           // decoder: query r attends keys 0 .. r
   int text0, M;         // FiCoCo-L: block row of the first text query, number of text queries
   double* ttext;        // FiCoCo-L: [B][N][M] head-mean attention of the text queries on the visual keys, or null
+  // Few tiles: the heads are split over `groups` workgroups per tile (heads_per_group consecutive
+  // heads each), which leave head SUMS in single precision; a second kernel adds the groups in
+  // order and divides by H.  groups == 1: the outputs are written directly.
+  int groups, heads_per_group;
+  float* part_map;      // [groups][B][N][map_pitch]
+  float* part_text;     // [groups][B][N][M]
+  float* part_recv;     // [groups][B][n_tiles][N]
+  float* part_cls;      // [groups][B][N]
 };
 
 // v_mfma_f32_16x16x32_bf16: operand A is 16 rows x 32 features (lane: row lane % 16, features
@@ -248,27 +258,34 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
 // its query reads as -inf like a key past the sequence; the tiles cover the visual and the text
 // queries, or the text queries alone where no visual-to-visual term is needed; the rows of the text
 // queries leave as the text profiles of Eq. 3 / Eq. 4).
-template <int KS>
+template <int KS, int KBU>     // KBU: groups of 16 keys a wavefront holds of a key block (<= KBU)
 __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a) {
-  extern __shared__ float norm[];                    // [H][kQkTile][2]: reference, 1 / row sum
+  extern __shared__ float norm[];                    // [heads of this workgroup][kQkTile][2]: reference, 1 / row sum
   __shared__ float xmax[kQkWaves][kQkTile];
   __shared__ float xsum[kQkWaves][kQkTile];
-  const int total = a.n_tiles * a.B;
+  const int total = a.n_tiles * a.B * a.groups;
   const int logical = xcd_logical_id(blockIdx.x, total);
   if (logical >= total) return;
-  const int tile = logical % a.n_tiles;
-  const int64_t b = logical / a.n_tiles;
+  const int grp = logical % a.groups;               // the groups of a tile are neighbours: same operands
+  const int tile = (logical / a.groups) % a.n_tiles;
+  const int64_t b = logical / (a.groups * a.n_tiles);
+  const int h_lo = grp * a.heads_per_group, h_hi = min(h_lo + a.heads_per_group, a.H);
+  if (h_lo >= h_hi) return;                         // (the launcher leaves no group without heads)
   const int lane = threadIdx.x % kWave;
   const int wv = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int l16 = lane % 16, lg = lane / 16;
   const float NEG = -__builtin_huge_valf();
-  const int key_base = wv * kQkKB * 16;             // first key of this wavefront inside a key block
-  const int n_blocks = (a.n + kQkMaxKeys - 1) / kQkMaxKeys;
+  // A key block is KBU groups of 16 keys per wavefront: 640 keys with five groups, 384 with three
+  // (675 keys are two blocks of 384 instead of 640 + 35, with three fifths of the registers).
+  constexpr int kbu = KBU;
+  constexpr int blk_keys = kQkWaves * KBU * 16;
+  const int key_base = wv * KBU * 16;               // first key of this wavefront inside a key block
+  const int n_blocks = (a.n + blk_keys - 1) / blk_keys;
   const int q_first = a.q_begin + tile * kQkTile;   // block row of this tile's first query
   const int q_end = min(a.q_begin + a.q_count, a.n);
   // decoder: key blocks that begin behind the tile's last query hold no key any of its queries
   // attends -- they are not computed (their pieces of the outputs are written as zeros)
-  const int nb = a.causal ? min(n_blocks, min(q_first + kQkTile - 1, q_end - 1) / kQkMaxKeys + 1) : n_blocks;
+  const int nb = a.causal ? min(n_blocks, min(q_first + kQkTile - 1, q_end - 1) / blk_keys + 1) : n_blocks;
 
   int q_row[kQkQB];
   int64_t q_off[kQkQB];
@@ -282,13 +299,13 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   // tile's queries and this wavefront's keys of the block (keys past the sequence read as -inf).
   // The operands of the next (head, block) are loaded right after the matrix instructions of the
   // current one, so that they arrive while its softmax is computed.
-  bf16x8_t kf[kQkKB][KS], qf[kQkQB][KS];
+  bf16x8_t kf[KBU][KS], qf[kQkQB][KS];
   auto load_ops = [&](int h, int blk) {
     const bf16_t* Qh = a.Q + b * a.sb + (int64_t)h * a.sh;
     const bf16_t* Kh = a.K + b * a.sb + (int64_t)h * a.sh;
-    const int k0 = blk * kQkMaxKeys + key_base;
+    const int k0 = blk * blk_keys + key_base;
 #pragma unroll
-    for (int kb = 0; kb < kQkKB; ++kb) {
+    for (int kb = 0; kb < KBU; ++kb) {
       const int64_t off = (int64_t)min(k0 + kb * 16 + l16, a.n - 1) * a.sn + lg * 8;
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&kf[kb][ks], Kh + off + ks * 32, 16);
@@ -298,10 +315,10 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) __builtin_memcpy(&qf[qb][ks], Qh + q_off[qb] + ks * 32, 16);
   };
-  auto logits = [&](int blk, f32x4_t (&S)[kQkKB][kQkQB], int h_next, int blk_next) {
-    const int k0 = blk * kQkMaxKeys + key_base;
+  auto logits = [&](int blk, f32x4_t (&S)[KBU][kQkQB], int h_next, int blk_next) {
+    const int k0 = blk * blk_keys + key_base;
 #pragma unroll
-    for (int kb = 0; kb < kQkKB; ++kb)
+    for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) {
         S[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
@@ -311,9 +328,9 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
       }
     load_ops(h_next, blk_next);
     issue_fence();                                   // the loads go out here, not where they are first used
-    if (k0 + kQkKB * 16 > a.n) {                     // scalar: only the last wavefronts of the last block
+    if (k0 + kbu * 16 > a.n) {                       // scalar: only the last wavefronts of the last block
 #pragma unroll
-      for (int kb = 0; kb < kQkKB; ++kb)
+      for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
         for (int v = 0; v < 4; ++v)
           if (k0 + kb * 16 + lg * 4 + v >= a.n) {
@@ -321,9 +338,9 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
             for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
           }
     }
-    if (a.causal && k0 + kQkKB * 16 - 1 > q_first) {  // scalar: some key of this wavefront may lie behind some query
+    if (a.causal && k0 + kbu * 16 - 1 > q_first) {    // scalar: some key of this wavefront may lie behind some query
 #pragma unroll
-      for (int kb = 0; kb < kQkKB; ++kb)
+      for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
         for (int v = 0; v < 4; ++v) {
           const int key = k0 + kb * 16 + lg * 4 + v;
@@ -335,27 +352,27 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   };
 
   // ---- sweep 1: (reference, 1 / sum) of every head and query ---------------------------------------
-  load_ops(0, 0);
+  load_ops(h_lo, 0);
 #pragma unroll 1
-  for (int h = 0; h < a.H; ++h) {
+  for (int h = h_lo; h < h_hi; ++h) {
     float mref[kQkQB], lsum[kQkQB];
 #pragma unroll
     for (int qb = 0; qb < kQkQB; ++qb) { mref[qb] = NEG; lsum[qb] = 0.0f; }
 #pragma unroll 1
     for (int blk = 0; blk < nb; ++blk) {
-      f32x4_t S[kQkKB][kQkQB];
+      f32x4_t S[KBU][kQkQB];
       {
         // next: the following block of this head, then block 0 of the next head; after the last of
         // sweep 1 the first of sweep 2 (head 0, block 0)
         const bool last_blk = blk + 1 == nb;
-        logits(blk, S, last_blk ? (h + 1 < a.H ? h + 1 : 0) : h, last_blk ? 0 : blk + 1);
+        logits(blk, S, last_blk ? (h + 1 < h_hi ? h + 1 : h_lo) : h, last_blk ? 0 : blk + 1);
       }
       float mw[kQkQB];
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) {
         mw[qb] = NEG;
 #pragma unroll
-        for (int kb = 0; kb < kQkKB; ++kb)
+        for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
           for (int v = 0; v < 4; ++v) mw[qb] = fmaxf(mw[qb], S[kb][qb][v]);
       }
@@ -380,7 +397,7 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
         mref[qb] = ref;
         const float sub = some ? ref : 0.0f;
 #pragma unroll
-        for (int kb = 0; kb < kQkKB; ++kb)
+        for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
           for (int v = 0; v < 4; ++v) lsum[qb] += __builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -sub));
       }
@@ -413,8 +430,8 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
 #pragma unroll
       for (int w = 0; w < kQkWaves; ++w)                                          // wavefronts in order
         l += xmax[w][qi] > NEG ? xsum[w][qi] * __builtin_amdgcn_exp2f(fmaxf(xmax[w][qi] - m, -150.0f)) : 0.0f;
-      norm[(h * kQkTile + qi) * 2] = m;
-      norm[(h * kQkTile + qi) * 2 + 1] = 1.0f / l;
+      norm[((h - h_lo) * kQkTile + qi) * 2] = m;
+      norm[((h - h_lo) * kQkTile + qi) * 2 + 1] = 1.0f / l;
     }
     __syncthreads();              // the pairs are read back below; the exchange slots are written again by the next head
   }
@@ -423,35 +440,35 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   const float invH = 1.0f / (float)a.H;
 #pragma unroll 1
   for (int blk = 0; blk < n_blocks; ++blk) {
-    f32x4_t P[kQkKB][kQkQB];
+    f32x4_t P[KBU][kQkQB];
 #pragma unroll
-    for (int kb = 0; kb < kQkKB; ++kb)
+    for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) P[kb][qb] = f32x4_t{0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll 1
-    for (int h = 0; h < (blk < nb ? a.H : 0); ++h) {
-      f32x4_t S[kQkKB][kQkQB];
+    for (int h = h_lo; h < (blk < nb ? h_hi : h_lo); ++h) {
+      f32x4_t S[KBU][kQkQB];
       {
-        // next: the following head of this block, then head 0 of the next block (past the end: the last again)
-        const bool last_h = h + 1 == a.H;
-        logits(blk, S, last_h ? 0 : h + 1, last_h ? min(blk + 1, nb - 1) : blk);
+        // next: the following head of this block, then the first head of the next block (past the end: the last again)
+        const bool last_h = h + 1 == h_hi;
+        logits(blk, S, last_h ? h_lo : h + 1, last_h ? min(blk + 1, nb - 1) : blk);
       }
 #pragma unroll
       for (int qb = 0; qb < kQkQB; ++qb) {
-        const float m = norm[(h * kQkTile + qb * 16 + l16) * 2];
-        const float inv = norm[(h * kQkTile + qb * 16 + l16) * 2 + 1];
+        const float m = norm[((h - h_lo) * kQkTile + qb * 16 + l16) * 2];
+        const float inv = norm[((h - h_lo) * kQkTile + qb * 16 + l16) * 2 + 1];
 #pragma unroll
-        for (int kb = 0; kb < kQkKB; ++kb)
+        for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
           for (int v = 0; v < 4; ++v)
             P[kb][qb][v] = fmaf(__builtin_amdgcn_exp2f(fmaf(S[kb][qb][v], a.scale_log2e, -m)), inv, P[kb][qb][v]);
       }
     }
 #pragma unroll
-    for (int kb = 0; kb < kQkKB; ++kb) {
+    for (int kb = 0; kb < KBU; ++kb) {
 #pragma unroll
       for (int v = 0; v < 4; ++v) {
-        const int key = blk * kQkMaxKeys + key_base + kb * 16 + lg * 4 + v;
+        const int key = blk * blk_keys + key_base + kb * 16 + lg * 4 + v;
         const int ik = key - a.vis0;                                  // visual key index
         const bool k_vis = key < a.n && ik >= 0 && ik < a.N;
         float cs = 0.0f;                                              // received from this tile's visual queries
@@ -460,18 +477,57 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
           const int q = q_row[qb];
           const int jq = q - a.vis0;                                  // visual query index
           const bool q_vis = q < q_end && jq >= 0 && jq < a.N;
+          const int mq = q - a.text0;                                 // text query index
+          const bool q_txt = a.ttext && q < q_end && mq >= 0 && mq < a.M;
+          if (a.groups > 1) {            // uniform: head sums of this group, combined by qk_combine_kernel
+            const float ps = P[kb][qb][v];
+            const int64_t gb = (int64_t)grp * a.B + b;
+            if (a.abar && q_vis && k_vis) a.part_map[(gb * a.N + ik) * a.map_pitch + jq] = ps;
+            if (q == a.cls_r && k_vis) a.part_cls[gb * a.N + ik] = ps;
+            if (q_txt && k_vis) a.part_text[(gb * a.N + ik) * a.M + mq] = ps;
+            cs += q_vis ? ps : 0.0f;
+            continue;
+          }
           const float pm = P[kb][qb][v] * invH;                       // head-mean probability P[q][key]
           if (a.abar && q_vis && k_vis) a.abar[(b * a.N + ik) * a.map_pitch + jq] = pm;
           if (q == a.cls_r && k_vis) a.cls[b * a.N + ik] = (double)pm;
-          const int mq = q - a.text0;                                 // text query index
-          if (a.ttext && q < q_end && mq >= 0 && mq < a.M && k_vis) a.ttext[(b * a.N + ik) * a.M + mq] = (double)pm;
+          if (q_txt && k_vis) a.ttext[(b * a.N + ik) * a.M + mq] = (double)pm;
           cs += q_vis ? pm : 0.0f;
         }
 #pragma unroll
         for (int off = 8; off > 0; off >>= 1) cs += __shfl_xor(cs, off, kWave);
-        if (a.recv_part && l16 == 0 && k_vis) a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
+        if (a.recv_part && l16 == 0 && k_vis) {
+          if (a.groups > 1) a.part_recv[(((int64_t)grp * a.B + b) * a.n_tiles + tile) * a.N + ik] = cs;
+          else a.recv_part[(b * a.n_tiles + tile) * a.N + ik] = (double)cs;
+        }
       }
     }
+  }
+}
+
+// The groups' head sums added in group order and divided by H: one thread per output element
+// (blockIdx.y: 0 the map, 1 the text profiles, 2 the column partials, 3 the [CLS] row).
+__global__ __launch_bounds__(256) void qk_combine_kernel(QkArgs a) {
+  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const float invH = 1.0f / (float)a.H;
+  auto total = [&](const float* part, int64_t at, int64_t stride) {
+    float t = 0.0f;
+    for (int g = 0; g < a.groups; ++g) t += part[at + g * stride];
+    return t * invH;
+  };
+  if (blockIdx.y == 0) {
+    if (!a.abar || i >= (int64_t)a.B * a.N * a.N) return;
+    const int64_t at = (i / a.N) * a.map_pitch + i % a.N;           // [b][key][query < N]
+    a.abar[at] = total(a.part_map, at, (int64_t)a.B * a.N * a.map_pitch);
+  } else if (blockIdx.y == 1) {
+    if (!a.ttext || i >= (int64_t)a.B * a.N * a.M) return;
+    a.ttext[i] = (double)total(a.part_text, i, (int64_t)a.B * a.N * a.M);
+  } else if (blockIdx.y == 2) {
+    if (!a.recv_part || i >= (int64_t)a.B * a.n_tiles * a.N) return;
+    a.recv_part[i] = (double)total(a.part_recv, i, (int64_t)a.B * a.n_tiles * a.N);
+  } else {
+    if (a.cls_r < 0 || i >= (int64_t)a.B * a.N) return;
+    a.cls[i] = (double)total(a.part_cls, i, (int64_t)a.B * a.N);
   }
 }
 
@@ -502,11 +558,42 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
   }
   const dim3 grid(xcd_padded_total(a.n_tiles * a.B)), block(kQkWaves * kWave);
   if (L || p.qk_n > kQkMaxKeys) {     // keys in blocks, two sweeps
-    const size_t lds = (size_t)p.H * kQkTile * 2 * sizeof(float);
+    // key groups per wavefront that cut the keys evenly over as many blocks as blocks of 640 would take
+    const int blocks = (p.qk_n + kQkMaxKeys - 1) / kQkMaxKeys;
+    // (heads of 128 always take three: with five the kernel spills 41 registers)
+    const bool three = p.d_head == 128 || (p.qk_n + blocks * kQkWaves * 16 - 1) / (blocks * kQkWaves * 16) <= 3;
+    a.groups = pl.qk_groups;
+    a.heads_per_group = (p.H + a.groups - 1) / a.groups;
+    if (a.groups > 1) {
+      float* part = (float*)(ws + pl.qk_part);
+      a.part_map = part;
+      part += a.abar ? (size_t)a.groups * p.B * p.N * pl.map_pitch : 0;
+      a.part_text = part;
+      part += a.ttext ? (size_t)a.groups * p.B * p.N * p.M : 0;
+      a.part_recv = part;
+      part += (size_t)a.groups * p.B * a.n_tiles * p.N;
+      a.part_cls = part;
+    }
+    const dim3 grid2(xcd_padded_total(a.n_tiles * a.B * a.groups));
+    const size_t lds = (size_t)a.heads_per_group * kQkTile * 2 * sizeof(float);
     switch (p.d_head / 32) {
-      case 1: hipLaunchKernelGGL(attn_qk_long_kernel<1>, grid, block, lds, s, a); break;
-      case 2: hipLaunchKernelGGL(attn_qk_long_kernel<2>, grid, block, lds, s, a); break;
-      default: hipLaunchKernelGGL(attn_qk_long_kernel<4>, grid, block, lds, s, a); break;
+      case 1:
+        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<1, 3>), grid2, block, lds, s, a);
+        else hipLaunchKernelGGL((attn_qk_long_kernel<1, kQkKB>), grid2, block, lds, s, a);
+        break;
+      case 2:
+        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<2, 3>), grid2, block, lds, s, a);
+        else hipLaunchKernelGGL((attn_qk_long_kernel<2, kQkKB>), grid2, block, lds, s, a);
+        break;
+      default:
+        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<4, 3>), grid2, block, lds, s, a);
+        else hipLaunchKernelGGL((attn_qk_long_kernel<4, kQkKB>), grid2, block, lds, s, a);
+        break;
+    }
+    if (a.groups > 1) {
+      const int64_t most = std::max({(int64_t)(a.abar ? (int64_t)p.B * p.N * p.N : 0), (int64_t)p.B * p.N * std::max(p.M, 1),
+                                     (int64_t)p.B * a.n_tiles * p.N});
+      hipLaunchKernelGGL(qk_combine_kernel, dim3((unsigned)((most + 255) / 256), 4), dim3(256), 0, s, a);
     }
     return;
   }

@@ -66,6 +66,8 @@ struct Plan {
   int fixed_k;           // >= 0: targets per discarded token fixed by the caller (0: no edges), -1: adaptive
   bool extra_token;      // the additional token of the convergent form is written
   bool qk;               // the maps are formed from queries and keys on the fly (attn_qk.hip)
+  int qk_groups;         // two-sweep form: workgroups per query tile, each with a share of the heads (1: no split)
+  size_t qk_part;        // float: the groups' head sums of map, text profiles, column partials, [CLS] row (qk_groups > 1)
   bool use_gram;         // cosine correlation proposed by the MFMA tile kernel
   int gram_splits, gram_st_per_split;   // K ranges of that kernel and their length in 32-feature stages
   int f_chunks, f_rows_per_wg, Df;

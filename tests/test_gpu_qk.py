@@ -127,7 +127,7 @@ def test_sequences_longer_than_one_key_block(ctx, seed, grid, H, d, n_keep):
     assert full >= 1
 
 
-def _case_l(ctx, seed, B, n_sys, N, M, D, H, d, n_keep, red, corr, sigma=1.0):
+def _case_l(ctx, seed, B, n_sys, N, M, D, H, d, n_keep, red, corr, sigma=1.0, staged=False):
     """FiCoCo-L fed the decoder layer's queries and keys (causal maps; the text tokens follow the
     visual span) against the oracle's float64 evaluation, under the margin rule."""
     cfg = synth.ficoco_l_decoder(seed=seed, B=B, n_sys=n_sys, N=N, M=M, D=D, H=1, centres=8, n_keep=n_keep, with_vv=False)
@@ -138,7 +138,13 @@ def _case_l(ctx, seed, B, n_sys, N, M, D, H, d, n_keep, red, corr, sigma=1.0):
                         gamma=cfg["gamma"], eps=cfg["eps"], red_src=red, sem_src=fc.G_TEXT_ATTN, corr_src=corr,
                         window=0, Q=Qd, K=Kd, qk_begin=0, M=M)
     buf = fc.Buffers(p, "cuda", Xd.dtype)
-    fc.ficoco_l_step(ctx, p, buf)
+    if staged:
+        fc.ficoco_score(ctx, p, buf)
+        fc.ficoco_filter(ctx, p, buf)
+        fc.ficoco_correlate(ctx, p, buf)
+        fc.ficoco_compress(ctx, p, buf)
+    else:
+        fc.ficoco_l_step(ctx, p, buf)
     out = P.gpu_outputs(buf)
     del Xd, Qd, Kd
     full = 0
@@ -161,6 +167,12 @@ def test_decoder_step_from_queries_and_keys(ctx, shape, red, corr):
     n_sys, N, M, D, H, d, n_keep = shape
     full = _case_l(ctx, 80 + N % 50, 2, n_sys, N, M, D, H, d, n_keep, red, corr)
     assert full >= 1
+
+
+@pytest.mark.parametrize("red,corr", [(fc.R_ATTN_RECV, fc.C_ATTN), (fc.R_SIM_MEAN, fc.C_COSINE)])
+def test_decoder_stages_from_queries_and_keys(ctx, red, corr):
+    """The same through the staged entry points (score, filter, correlate, compress one call each)."""
+    assert _case_l(ctx, 91, 2, 4, 130, 33, 72, 6, 64, 60, red, corr, staged=True) >= 1
 
 
 def test_unsupported_shapes_are_refused(ctx):

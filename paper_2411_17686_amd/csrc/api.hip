@@ -246,10 +246,10 @@ int make_plan(const ficoco_problem& p, Plan& pl, const char** why) {
   pl.pair_tab = take(pair_records(p, pl) ? B * (size_t)pl.n_disc * sizeof(PairRec) : 0);
   pl.qk_groups = 1;
   if (qk && (L || p.qk_n > kQkMaxKeys)) {
-    // Few query tiles (a decoder's 64 text queries are two): the heads are split over up to eight
+    // Few query tiles (a decoder's 64 text queries are two): the heads are split over up to sixteen
     // workgroups per tile until the chip has about one workgroup per compute unit.
     const int64_t base = (int64_t)pl.n_chunks * p.B;
-    const int want = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(p.H, 8), 256 / std::max<int64_t>(base, 1)));
+    const int want = (int)std::max<int64_t>(1, std::min<int64_t>(std::min(p.H, 16), 256 / std::max<int64_t>(base, 1)));
     const int per = (p.H + want - 1) / want;
     pl.qk_groups = (p.H + per - 1) / per;            // no group without heads
   }

@@ -505,24 +505,28 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   }
 }
 
-// The groups' head sums added in group order and divided by H: one thread per output element
-// (blockIdx.y: 0 the map, 1 the text profiles, 2 the column partials, 3 the [CLS] row).
-__global__ __launch_bounds__(256) void qk_combine_kernel(QkArgs a) {
-  const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+// The groups' head sums added in group order and divided by H: one thread per output element.
+// The grid is the four outputs one after the other (map, text profiles, column partials, [CLS]
+// row), each with exactly the workgroups it needs (an empty workgroup still costs its start).
+struct QkCombineBlocks { int map, text, recv, cls; };
+__global__ __launch_bounds__(256) void qk_combine_kernel(QkArgs a, QkCombineBlocks nb) {
+  int blk = blockIdx.x, part = 0;
+  if (blk >= nb.map) { blk -= nb.map; part = 1; if (blk >= nb.text) { blk -= nb.text; part = 2; if (blk >= nb.recv) { blk -= nb.recv; part = 3; } } }
+  const int64_t i = (int64_t)blk * blockDim.x + threadIdx.x;
   const float invH = 1.0f / (float)a.H;
   auto total = [&](const float* part, int64_t at, int64_t stride) {
     float t = 0.0f;
     for (int g = 0; g < a.groups; ++g) t += part[at + g * stride];
     return t * invH;
   };
-  if (blockIdx.y == 0) {
+  if (part == 0) {
     if (!a.abar || i >= (int64_t)a.B * a.N * a.N) return;
     const int64_t at = (i / a.N) * a.map_pitch + i % a.N;           // [b][key][query < N]
     a.abar[at] = total(a.part_map, at, (int64_t)a.B * a.N * a.map_pitch);
-  } else if (blockIdx.y == 1) {
+  } else if (part == 1) {
     if (!a.ttext || i >= (int64_t)a.B * a.N * a.M) return;
     a.ttext[i] = (double)total(a.part_text, i, (int64_t)a.B * a.N * a.M);
-  } else if (blockIdx.y == 2) {
+  } else if (part == 2) {
     if (!a.recv_part || i >= (int64_t)a.B * a.n_tiles * a.N) return;
     a.recv_part[i] = (double)total(a.part_recv, i, (int64_t)a.B * a.n_tiles * a.N);
   } else {
@@ -591,9 +595,14 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
         break;
     }
     if (a.groups > 1) {
-      const int64_t most = std::max({(int64_t)(a.abar ? (int64_t)p.B * p.N * p.N : 0), (int64_t)p.B * p.N * std::max(p.M, 1),
-                                     (int64_t)p.B * a.n_tiles * p.N});
-      hipLaunchKernelGGL(qk_combine_kernel, dim3((unsigned)((most + 255) / 256), 4), dim3(256), 0, s, a);
+      auto blocks = [](int64_t n) { return (int)((n + 255) / 256); };
+      QkCombineBlocks nb;
+      nb.map = a.abar ? blocks((int64_t)p.B * p.N * p.N) : 0;
+      nb.text = a.ttext ? blocks((int64_t)p.B * p.N * p.M) : 0;
+      nb.recv = a.recv_part ? blocks((int64_t)p.B * a.n_tiles * p.N) : 0;
+      nb.cls = a.cls_r >= 0 ? blocks((int64_t)p.B * p.N) : 0;
+      const int all = nb.map + nb.text + nb.recv + nb.cls;
+      if (all > 0) hipLaunchKernelGGL(qk_combine_kernel, dim3(all), dim3(256), 0, s, a, nb);
     }
     return;
   }

@@ -37,7 +37,6 @@ struct QkArgs {
   int n_tiles, B;
   // the two-sweep kernel only:
   int q_begin, q_count; // block rows whose queries are needed (the tiles cover these)
-  int causal;           // decoder: query r attends keys 0 .. r
   int text0, M;         // FiCoCo-L: block row of the first text query, number of text queries
   double* ttext;        // FiCoCo-L: [B][N][M] head-mean attention of the text queries on the visual keys, or null
   // Few tiles: the heads are split over `groups` workgroups per tile (heads_per_group consecutive
@@ -254,11 +253,11 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_kernel(QkArgs a) {
 // logits of every head are formed again, turned into probabilities with the stored pair and
 // accumulated over the heads in registers; the block's piece of the head-mean map, of the [CLS] row
 // and of the column partials is written as above.  The logits are computed twice; the maps still
-// never exist in memory.  The same kernel serves the decoder of FiCoCo-L (causal = 1: a key behind
+// never exist in memory.  The same kernel serves the decoder of FiCoCo-L (DEC: a key behind
 // its query reads as -inf like a key past the sequence; the tiles cover the visual and the text
 // queries, or the text queries alone where no visual-to-visual term is needed; the rows of the text
 // queries leave as the text profiles of Eq. 3 / Eq. 4).
-template <int KS, int KBU>     // KBU: groups of 16 keys a wavefront holds of a key block (<= KBU)
+template <int KS, int KBU, bool DEC>     // KBU: groups of 16 keys a wavefront holds of a key block (<= kQkKB); DEC: the decoder's causal maps
 __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a) {
   extern __shared__ float norm[];                    // [heads of this workgroup][kQkTile][2]: reference, 1 / row sum
   __shared__ float xmax[kQkWaves][kQkTile];
@@ -285,7 +284,7 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
   const int q_end = min(a.q_begin + a.q_count, a.n);
   // decoder: key blocks that begin behind the tile's last query hold no key any of its queries
   // attends -- they are not computed (their pieces of the outputs are written as zeros)
-  const int nb = a.causal ? min(n_blocks, min(q_first + kQkTile - 1, q_end - 1) / blk_keys + 1) : n_blocks;
+  const int nb = DEC ? min(n_blocks, min(q_first + kQkTile - 1, q_end - 1) / blk_keys + 1) : n_blocks;
 
   int q_row[kQkQB];
   int64_t q_off[kQkQB];
@@ -338,7 +337,7 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
             for (int qb = 0; qb < kQkQB; ++qb) S[kb][qb][v] = NEG;
           }
     }
-    if (a.causal && k0 + kbu * 16 - 1 > q_first) {    // scalar: some key of this wavefront may lie behind some query
+    if (DEC && k0 + kbu * 16 - 1 > q_first) {         // scalar: some key of this wavefront may lie behind some query
 #pragma unroll
       for (int kb = 0; kb < KBU; ++kb)
 #pragma unroll
@@ -478,7 +477,7 @@ __global__ __launch_bounds__(kQkWaves * kWave) void attn_qk_long_kernel(QkArgs a
           const int jq = q - a.vis0;                                  // visual query index
           const bool q_vis = q < q_end && jq >= 0 && jq < a.N;
           const int mq = q - a.text0;                                 // text query index
-          const bool q_txt = a.ttext && q < q_end && mq >= 0 && mq < a.M;
+          const bool q_txt = DEC && a.ttext && q < q_end && mq >= 0 && mq < a.M;
           if (a.groups > 1) {            // uniform: head sums of this group, combined by qk_combine_kernel
             const float ps = P[kb][qb][v];
             const int64_t gb = (int64_t)grp * a.B + b;
@@ -552,7 +551,6 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
   const bool L = p.variant == FICOCO_VARIANT_L;
   if (L) {                            // decoder: causal; the text queries follow the visual span
     const bool need_vv = p.red_src == FICOCO_R_ATTN_RECV || p.corr_src == FICOCO_C_ATTN;
-    a.causal = 1;
     a.text0 = a.vis0 + p.N;
     a.M = p.M;
     a.ttext = (double*)(ws + pl.ttext);
@@ -580,19 +578,16 @@ void launch_attn_qk(const ficoco_problem& p, const Plan& pl, char* ws, hipStream
     }
     const dim3 grid2(xcd_padded_total(a.n_tiles * a.B * a.groups));
     const size_t lds = (size_t)a.heads_per_group * kQkTile * 2 * sizeof(float);
-    switch (p.d_head / 32) {
-      case 1:
-        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<1, 3>), grid2, block, lds, s, a);
-        else hipLaunchKernelGGL((attn_qk_long_kernel<1, kQkKB>), grid2, block, lds, s, a);
-        break;
-      case 2:
-        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<2, 3>), grid2, block, lds, s, a);
-        else hipLaunchKernelGGL((attn_qk_long_kernel<2, kQkKB>), grid2, block, lds, s, a);
-        break;
-      default:
-        if (three) hipLaunchKernelGGL((attn_qk_long_kernel<4, 3>), grid2, block, lds, s, a);
-        else hipLaunchKernelGGL((attn_qk_long_kernel<4, kQkKB>), grid2, block, lds, s, a);
-        break;
+    auto go = [&](auto kern) { hipLaunchKernelGGL(kern, grid2, block, lds, s, a); };
+    const int ks = p.d_head / 32;       // (heads of 128 always take three key groups)
+    if (L) {
+      if (ks == 1) { if (three) go(attn_qk_long_kernel<1, 3, true>); else go(attn_qk_long_kernel<1, kQkKB, true>); }
+      else if (ks == 2) { if (three) go(attn_qk_long_kernel<2, 3, true>); else go(attn_qk_long_kernel<2, kQkKB, true>); }
+      else go(attn_qk_long_kernel<4, 3, true>);
+    } else {
+      if (ks == 1) { if (three) go(attn_qk_long_kernel<1, 3, false>); else go(attn_qk_long_kernel<1, kQkKB, false>); }
+      else if (ks == 2) { if (three) go(attn_qk_long_kernel<2, 3, false>); else go(attn_qk_long_kernel<2, kQkKB, false>); }
+      else go(attn_qk_long_kernel<4, 3, false>);
     }
     if (a.groups > 1) {
       auto blocks = [](int64_t n) { return (int)((n + 255) / 256); };
